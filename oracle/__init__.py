@@ -1,0 +1,226 @@
+"""fp64 CPU oracle of the Double-P decode step (TEST INFRASTRUCTURE ONLY).
+
+``dp_oracle.c`` holds the arithmetic (plain C, IEEE double, scalar loops, one
+function per equation of the paper); this module is a ctypes wrapper that hands
+it numpy arrays.  Nothing under ``oracle/`` is imported by the HIP package; the
+only users are ``tests/``, ``__graft_entry__.smoke()`` and the ``cpu_baseline``
+leg of ``bench.py``.
+
+Stored bf16 tensors are passed as uint16 bit patterns and widened exactly
+inside the C code.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+import subprocess
+from dataclasses import dataclass
+from typing import List, Optional, Sequence, Tuple
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "dp_oracle.c")
+_LIB = os.path.join(_HERE, "libdp_oracle.so")
+
+P2_ABSOLUTE = 1
+
+
+def build(force: bool = False) -> str:
+    """Compile dp_oracle.c with gcc (-O2, OpenMP) into oracle/libdp_oracle.so."""
+    stale = (not os.path.exists(_LIB)) or os.path.getmtime(_LIB) < max(
+        os.path.getmtime(_SRC), os.path.getmtime(os.path.join(_HERE, "dp_oracle.h")))
+    if force or stale:
+        tmp = _LIB + f".tmp{os.getpid()}"
+        subprocess.check_call(["gcc", "-O2", "-std=c11", "-fPIC", "-shared", "-fopenmp", "-Wall", "-Wextra",
+                               "-o", tmp, _SRC, "-lm"])
+        os.replace(tmp, _LIB)
+    return _LIB
+
+
+class _Cache(C.Structure):
+    _fields_ = [("batch", C.c_int32), ("n_kv_heads", C.c_int32), ("n_q_heads", C.c_int32), ("head_dim", C.c_int32),
+                ("q", C.c_void_p), ("k_cache", C.c_void_p), ("v_cache", C.c_void_p),
+                ("seg_row_base", C.c_void_p), ("seg_cluster_ptr", C.c_void_p),
+                ("cluster_offsets", C.c_void_p), ("cluster_sizes", C.c_void_p),
+                ("k_centroids", C.c_void_p), ("v_centroids", C.c_void_p), ("sm_scale", C.c_double)]
+
+
+_lib = None
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        build()
+        L = C.CDLL(_LIB)
+        P, I, D, U = C.c_void_p, C.c_int32, C.c_double, C.c_uint32
+        CP = C.POINTER(_Cache)
+        L.dpo_num_clusters.restype = I
+        L.dpo_num_clusters.argtypes = [CP, I, I]
+        L.dpo_centroid_logits.restype = None
+        L.dpo_centroid_logits.argtypes = [CP, I, I, P]
+        L.dpo_cluster_distribution.restype = None
+        L.dpo_cluster_distribution.argtypes = [P, I, P]
+        L.dpo_sorted_order.restype = I
+        L.dpo_sorted_order.argtypes = [P, I, P]
+        L.dpo_double_top_p.restype = None
+        L.dpo_double_top_p.argtypes = [P, P, I, D, D, U, P, P, P, P]
+        L.dpo_mixed_attention.restype = None
+        L.dpo_mixed_attention.argtypes = [CP, I, I, P, I, P, I, P, P]
+        L.dpo_dense_attention.restype = None
+        L.dpo_dense_attention.argtypes = [CP, I, I, P, P]
+        L.dpo_exact_cluster_log_mass.restype = None
+        L.dpo_exact_cluster_log_mass.argtypes = [CP, I, I, P]
+        L.dpo_decode_step.restype = I
+        L.dpo_decode_step.argtypes = [CP, D, D, U, P, P, P, P, P, C.c_int64, I]
+        L.dpo_dense_step.restype = I
+        L.dpo_dense_step.argtypes = [CP, P, P, I]
+        _lib = L
+    return _lib
+
+
+def _ptr(a: np.ndarray) -> int:
+    return a.ctypes.data
+
+
+class Oracle:
+    """Binds one set of inputs (any object with the ClusteredCache fields)."""
+
+    def __init__(self, cache, sm_scale: float = 0.0):
+        self.lib = _load()
+        self.batch, self.n_kv_heads = int(cache.batch), int(cache.n_kv_heads)
+        self.n_q_heads, self.d = int(cache.n_q_heads), int(cache.head_dim)
+        # keep contiguous, correctly typed copies alive for the C side
+        self._a = dict(
+            q=np.ascontiguousarray(cache.q, dtype=np.uint16),
+            k_cache=np.ascontiguousarray(cache.k_cache, dtype=np.uint16),
+            v_cache=np.ascontiguousarray(cache.v_cache, dtype=np.uint16),
+            seg_row_base=np.ascontiguousarray(cache.seg_row_base, dtype=np.int64),
+            seg_cluster_ptr=np.ascontiguousarray(cache.seg_cluster_ptr, dtype=np.int32),
+            cluster_offsets=np.ascontiguousarray(cache.cluster_offsets, dtype=np.int32),
+            cluster_sizes=np.ascontiguousarray(cache.cluster_sizes, dtype=np.int32),
+            k_centroids=np.ascontiguousarray(cache.k_centroids, dtype=np.uint16),
+            v_centroids=np.ascontiguousarray(cache.v_centroids, dtype=np.uint16),
+        )
+        a = self._a
+        self.c = _Cache(self.batch, self.n_kv_heads, self.n_q_heads, self.d, _ptr(a["q"]), _ptr(a["k_cache"]),
+                        _ptr(a["v_cache"]), _ptr(a["seg_row_base"]), _ptr(a["seg_cluster_ptr"]),
+                        _ptr(a["cluster_offsets"]), _ptr(a["cluster_sizes"]), _ptr(a["k_centroids"]),
+                        _ptr(a["v_centroids"]), float(sm_scale))
+        self.cp = C.byref(self.c)
+
+    # ---- per-head stages -------------------------------------------------
+    def num_clusters(self, b: int, h: int) -> int:
+        return int(self.lib.dpo_num_clusters(self.cp, b, h))
+
+    def centroid_logits(self, b: int, h: int) -> np.ndarray:
+        out = np.empty(max(1, self.num_clusters(b, h)), dtype=np.float64)
+        self.lib.dpo_centroid_logits(self.cp, b, h, _ptr(out))
+        return out[: self.num_clusters(b, h)]
+
+    def cluster_distribution(self, logit: np.ndarray) -> np.ndarray:
+        logit = np.ascontiguousarray(logit, dtype=np.float64)
+        out = np.empty(max(1, logit.size), dtype=np.float64)
+        self.lib.dpo_cluster_distribution(_ptr(logit), logit.size, _ptr(out))
+        return out[: logit.size]
+
+    def sorted_order(self, logit: np.ndarray) -> np.ndarray:
+        logit = np.ascontiguousarray(logit, dtype=np.float64)
+        out = np.empty(max(1, logit.size), dtype=np.int32)
+        n = self.lib.dpo_sorted_order(_ptr(logit), logit.size, _ptr(out))
+        return out[:n]
+
+    def double_top_p(self, a_hat: np.ndarray, order: np.ndarray, p1: float, p2: float, flags: int = 0):
+        """-> (k1, k2, m1, cum)"""
+        a_hat = np.ascontiguousarray(a_hat, dtype=np.float64)
+        order = np.ascontiguousarray(order, dtype=np.int32)
+        cum = np.empty(max(1, order.size), dtype=np.float64)
+        k1, k2, m1 = C.c_int32(), C.c_int32(), C.c_double()
+        self.lib.dpo_double_top_p(_ptr(a_hat), _ptr(order), order.size, float(p1), float(p2), int(flags), _ptr(cum),
+                                  C.addressof(k1), C.addressof(k2), C.addressof(m1))
+        return k1.value, k2.value, m1.value, cum[: order.size]
+
+    def select(self, logit: np.ndarray, p1: float, p2: float, flags: int = 0) -> "Selection":
+        """Stage 2 from given logits (any float dtype; widened to double)."""
+        a_hat = self.cluster_distribution(logit)
+        order = self.sorted_order(logit)
+        k1, k2, m1, cum = self.double_top_p(a_hat, order, p1, p2, flags)
+        return Selection(order=order, k1=k1, k2=k2, m1=m1, cum=cum, a_hat=a_hat)
+
+    def mixed_attention(self, b: int, h: int, exact_ids: Sequence[int], approx_ids: Sequence[int]):
+        ex = np.ascontiguousarray(exact_ids, dtype=np.int32)
+        ap = np.ascontiguousarray(approx_ids, dtype=np.int32)
+        ex_p = np.concatenate([ex, np.zeros(1, np.int32)])  # non-null pointers for empty sets
+        ap_p = np.concatenate([ap, np.zeros(1, np.int32)])
+        out = np.empty(self.d, dtype=np.float64)
+        lse = C.c_double()
+        self.lib.dpo_mixed_attention(self.cp, b, h, _ptr(ex_p), ex.size, _ptr(ap_p), ap.size, _ptr(out),
+                                     C.addressof(lse))
+        return out, lse.value
+
+    def dense_attention(self, b: int, h: int):
+        out = np.empty(self.d, dtype=np.float64)
+        lse = C.c_double()
+        self.lib.dpo_dense_attention(self.cp, b, h, _ptr(out), C.addressof(lse))
+        return out, lse.value
+
+    def exact_cluster_log_mass(self, b: int, h: int) -> np.ndarray:
+        out = np.empty(max(1, self.num_clusters(b, h)), dtype=np.float64)
+        self.lib.dpo_exact_cluster_log_mass(self.cp, b, h, _ptr(out))
+        return out[: self.num_clusters(b, h)]
+
+    # ---- whole step ------------------------------------------------------
+    def decode_step(self, p1: float, p2: float, flags: int = 0, n_threads: int = 1, want_order: bool = True):
+        nh = self.batch * self.n_q_heads
+        out = np.empty((self.batch, self.n_q_heads, self.d), dtype=np.float64)
+        lse = np.empty(nh, dtype=np.float64)
+        k1 = np.empty(nh, dtype=np.int32)
+        k2 = np.empty(nh, dtype=np.int32)
+        stride = int(np.diff(self._a["seg_cluster_ptr"]).max()) if nh else 0
+        order = np.full((nh, max(1, stride)), -1, dtype=np.int32) if want_order else None
+        used = self.lib.dpo_decode_step(self.cp, float(p1), float(p2), int(flags), _ptr(out), _ptr(lse), _ptr(k1),
+                                        _ptr(k2), _ptr(order) if want_order else None, max(1, stride),
+                                        int(n_threads))
+        return StepResult(out=out, lse=lse.reshape(self.batch, self.n_q_heads),
+                          k1=k1.reshape(self.batch, self.n_q_heads), k2=k2.reshape(self.batch, self.n_q_heads),
+                          order=order, threads=int(used))
+
+    def dense_step(self, n_threads: int = 1):
+        nh = self.batch * self.n_q_heads
+        out = np.empty((self.batch, self.n_q_heads, self.d), dtype=np.float64)
+        lse = np.empty(nh, dtype=np.float64)
+        used = self.lib.dpo_dense_step(self.cp, _ptr(out), _ptr(lse), int(n_threads))
+        return out, lse.reshape(self.batch, self.n_q_heads), int(used)
+
+
+@dataclass
+class Selection:
+    order: np.ndarray   # non-empty clusters, score descending, index ascending among equals
+    k1: int             # order[:k1] retained by the first top-p
+    k2: int             # order[:k2] exact, order[k2:k1] approximated
+    m1: float           # mass of the retained set under A_hat
+    cum: np.ndarray     # cum[k] = mass of order[:k+1]
+    a_hat: np.ndarray   # Eq. 6 distribution, by cluster index
+
+    @property
+    def exact(self) -> np.ndarray:
+        return np.sort(self.order[: self.k2])
+
+    @property
+    def approx(self) -> np.ndarray:
+        return np.sort(self.order[self.k2: self.k1])
+
+    @property
+    def retained(self) -> np.ndarray:
+        return np.sort(self.order[: self.k1])
+
+
+@dataclass
+class StepResult:
+    out: np.ndarray
+    lse: np.ndarray
+    k1: np.ndarray
+    k2: np.ndarray
+    order: Optional[np.ndarray]
+    threads: int

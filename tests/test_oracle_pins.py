@@ -1,0 +1,413 @@
+"""Pins for the fp64 CPU oracle: each test ties it to something other than
+itself -- a hand-worked example, an independent library routine (scipy
+softmax / logsumexp), a closed form, brute force, or an invariant that follows
+from the paper's equations.  CPU only."""
+import itertools
+import json
+import math
+import os
+
+import numpy as np
+import pytest
+from scipy.special import logsumexp, softmax
+
+import oracle
+from workloads import ClusteredCache, bf16_bits_to_f32, f32_to_bf16_bits, make_cache, make_config
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+
+
+# --------------------------------------------------------------------------
+# helpers that build small caches by hand (inputs only)
+# --------------------------------------------------------------------------
+def cache_from_clusters(q_rows, clusters, d, n_kv_heads=1):
+    """clusters: list of (keys[s,d], values[s,d], k_centroid[d], v_centroid[d]); one KV head."""
+    ks, vs, kc, vc, sizes = [], [], [], [], []
+    for keys, vals, c_k, c_v in clusters:
+        keys = np.asarray(keys, dtype=np.float32).reshape(-1, d)
+        vals = np.asarray(vals, dtype=np.float32).reshape(-1, d)
+        ks.append(keys), vs.append(vals)
+        kc.append(np.asarray(c_k, dtype=np.float32)), vc.append(np.asarray(c_v, dtype=np.float32))
+        sizes.append(keys.shape[0])
+    sizes = np.asarray(sizes, dtype=np.int32)
+    offsets = np.concatenate([[0], np.cumsum(sizes)[:-1]]).astype(np.int32)
+    q = f32_to_bf16_bits(np.asarray(q_rows, dtype=np.float32).reshape(1, -1, d))
+    return ClusteredCache(
+        batch=1, n_kv_heads=1, n_q_heads=q.shape[1], head_dim=d, q=q,
+        k_cache=f32_to_bf16_bits(np.concatenate(ks) if ks else np.zeros((0, d), np.float32)),
+        v_cache=f32_to_bf16_bits(np.concatenate(vs) if vs else np.zeros((0, d), np.float32)),
+        seg_row_base=np.zeros(1, np.int64), seg_cluster_ptr=np.array([0, len(clusters)], np.int32),
+        cluster_offsets=offsets, cluster_sizes=sizes,
+        k_centroids=f32_to_bf16_bits(np.stack(kc)), v_centroids=f32_to_bf16_bits(np.stack(vc)))
+
+
+def scipy_dense(cache, b, h, rows=None, sm_scale=None):
+    """Independent dense softmax attention (Eq. 1) with scipy, over `rows` of the head's segment."""
+    d = cache.head_dim
+    seg = b * cache.n_kv_heads + h // cache.group
+    base = int(cache.seg_row_base[seg])
+    a, e = int(cache.seg_cluster_ptr[seg]), int(cache.seg_cluster_ptr[seg + 1])
+    if rows is None:
+        rows = np.concatenate([np.arange(o, o + s) for o, s in
+                               zip(cache.cluster_offsets[a:e], cache.cluster_sizes[a:e])] or [np.zeros(0, int)])
+    rows = base + np.asarray(rows, dtype=np.int64)
+    K = bf16_bits_to_f32(cache.k_cache[rows]).astype(np.float64)
+    V = bf16_bits_to_f32(cache.v_cache[rows]).astype(np.float64)
+    q = bf16_bits_to_f32(cache.q[b, h]).astype(np.float64)
+    x = (K @ q) * (sm_scale if sm_scale else 1.0 / math.sqrt(d))
+    return softmax(x) @ V, float(logsumexp(x))
+
+
+def rows_of(cache, seg, cluster_ids):
+    a = int(cache.seg_cluster_ptr[seg])
+    out = [np.arange(cache.cluster_offsets[a + c], cache.cluster_offsets[a + c] + cache.cluster_sizes[a + c])
+           for c in cluster_ids]
+    return np.concatenate(out) if out else np.zeros(0, dtype=np.int64)
+
+
+# --------------------------------------------------------------------------
+# hand-worked example (tests/golden/hand_worked_case.json)
+# --------------------------------------------------------------------------
+@pytest.fixture(scope="module")
+def hand():
+    with open(os.path.join(HERE, "golden", "hand_worked_case.json")) as f:
+        g = json.load(f)
+    cl = [(c["keys"], c["values"], c["k_centroid"], c["v_centroid"]) for c in g["clusters"]]
+    cache = cache_from_clusters([g["q"]], cl, d=2)
+    return g, cache, oracle.Oracle(cache, sm_scale=math.log(2.0))
+
+
+def test_hand_case_estimated_and_exact_masses(hand):
+    g, cache, o = hand
+    e = g["expected"]
+    logit = o.centroid_logits(0, 0)
+    np.testing.assert_allclose(np.exp(logit), e["Zhat"], rtol=1e-14)                      # Eq. 5
+    np.testing.assert_allclose(np.exp(o.exact_cluster_log_mass(0, 0)), e["Z_exact"], rtol=1e-14)   # Eq. 4
+    a_hat = o.cluster_distribution(logit)
+    np.testing.assert_allclose(a_hat, np.array(e["A_hat_num"]) / e["A_hat_den"], rtol=1e-14)        # Eq. 6
+    assert o.sorted_order(logit).tolist() == e["order"]
+
+
+def test_hand_case_selection_and_output(hand):
+    g, cache, o = hand
+    e = g["expected"]
+    logit = o.centroid_logits(0, 0)
+    s = o.select(logit, e["p1"], 0.5)
+    assert (s.k1, s.k2) == (e["k1"], e["p2_0.5"]["k2"])
+    assert s.m1 == pytest.approx(e["m1_num"] / e["m1_den"], rel=1e-14)
+    out, lse = o.mixed_attention(0, 0, s.exact, s.approx)
+    np.testing.assert_allclose(out, np.array(e["p2_0.5"]["out_num"]) / e["p2_0.5"]["out_den"], rtol=1e-14)
+    assert lse == pytest.approx(math.log(e["p2_0.5"]["Z_tilde"]), rel=1e-14)
+    # the two readings of the second top-p separate at p2 = 0.6
+    assert o.select(logit, e["p1"], 0.6).k2 == e["p2_0.6_renormalised"]["k2"]
+    sa = o.select(logit, e["p1"], 0.6, flags=oracle.P2_ABSOLUTE)
+    assert sa.k2 == e["p2_0.6_absolute"]["k2"]
+    # p2 = 0: everything retained is approximated
+    s0 = o.select(logit, e["p1"], 0.0)
+    assert s0.k2 == 0
+    out0, lse0 = o.mixed_attention(0, 0, s0.exact, s0.approx)
+    np.testing.assert_allclose(out0, [1.0, 1.0], rtol=1e-14)
+    assert lse0 == pytest.approx(math.log(e["p2_0"]["Z_tilde"]), rel=1e-14)
+
+
+def test_hand_case_whole_step_and_dense(hand):
+    g, cache, o = hand
+    e = g["expected"]
+    r = o.decode_step(e["p1"], 0.5)
+    np.testing.assert_allclose(r.out[0, 0], np.array(e["p2_0.5"]["out_num"]) / e["p2_0.5"]["out_den"], rtol=1e-14)
+    assert (int(r.k1[0, 0]), int(r.k2[0, 0])) == (e["k1"], e["p2_0.5"]["k2"])
+    assert r.order[0, :3].tolist() == e["order"]
+    dn, lse = o.dense_attention(0, 0)
+    np.testing.assert_allclose(dn, np.array(e["dense"]["out_num"]) / e["dense"]["out_den"], rtol=1e-14)
+    assert lse == pytest.approx(math.log(e["dense"]["Z"]), rel=1e-14)
+    # p1 = p2 = 1 is the dense result
+    r1 = o.decode_step(1.0, 1.0)
+    np.testing.assert_allclose(r1.out[0, 0], dn, rtol=1e-14)
+
+
+# --------------------------------------------------------------------------
+# Eq. 1 dense limit against scipy
+# --------------------------------------------------------------------------
+@pytest.mark.parametrize("seed", [0, 1])
+def test_dense_limit_equals_scipy_softmax_attention(seed):
+    c = make_cache(batch=2, n_kv_heads=2, n_q_heads=4, context=[384, 256], mean_cluster=16, q_scale=1.0, seed=seed)
+    o = oracle.Oracle(c)
+    r = o.decode_step(1.0, 1.0)
+    for b in range(c.batch):
+        for h in range(c.n_q_heads):
+            ref, ref_lse = scipy_dense(c, b, h)
+            np.testing.assert_allclose(r.out[b, h], ref, rtol=1e-11, atol=1e-13)
+            assert r.lse[b, h] == pytest.approx(ref_lse, rel=1e-12)
+            assert r.k1[b, h] == r.k2[b, h] == o.num_clusters(b, h)
+            dn, dl = o.dense_attention(b, h)
+            np.testing.assert_allclose(dn, ref, rtol=1e-11, atol=1e-13)
+            assert dl == pytest.approx(ref_lse, rel=1e-12)
+
+
+def test_centroid_logits_and_distribution_against_numpy_scipy():
+    c = make_cache(batch=1, n_kv_heads=2, n_q_heads=8, context=512, mean_cluster=8, size_hi=32, q_scale=0.5, seed=3)
+    o = oracle.Oracle(c)
+    for h in range(c.n_q_heads):
+        seg = h // c.group
+        a, e = c.seg_cluster_ptr[seg], c.seg_cluster_ptr[seg + 1]
+        KC = bf16_bits_to_f32(c.k_centroids[a:e]).astype(np.float64)
+        q = bf16_bits_to_f32(c.q[0, h]).astype(np.float64)
+        ref = KC @ q / math.sqrt(128) + np.log(c.cluster_sizes[a:e].astype(np.float64))
+        got = o.centroid_logits(0, h)
+        np.testing.assert_allclose(got, ref, rtol=1e-12, atol=1e-12)
+        np.testing.assert_allclose(o.cluster_distribution(got), softmax(ref), rtol=1e-11)
+
+
+# --------------------------------------------------------------------------
+# singleton clusters: centroids are the keys, the estimate is exact
+# --------------------------------------------------------------------------
+def singleton_cache(seed, n=96, scale=0.6):
+    c = make_cache(batch=1, n_kv_heads=1, n_q_heads=2, context=n, n_clusters=n, size_dist="ones", size_lo=1,
+                   size_hi=1, q_scale=scale, seed=seed)
+    assert (c.cluster_sizes == 1).all()
+    assert (c.k_centroids == c.k_cache).all() and (c.v_centroids == c.v_cache).all()
+    return c
+
+
+@pytest.mark.parametrize("p2", [0.0, 0.3, 0.9, 1.0])
+def test_singleton_clusters_p1_one_is_dense_for_any_p2(p2):
+    c = singleton_cache(5)
+    o = oracle.Oracle(c)
+    r = o.decode_step(1.0, p2)
+    for h in range(c.n_q_heads):
+        ref, ref_lse = scipy_dense(c, 0, h)
+        np.testing.assert_allclose(r.out[0, h], ref, rtol=1e-11, atol=1e-13)
+        assert r.lse[0, h] == pytest.approx(ref_lse, rel=1e-12)
+
+
+@pytest.mark.parametrize("p1,p2", [(0.5, 0.0), (0.8, 0.5), (0.95, 0.9)])
+def test_singleton_clusters_give_token_level_top_p(p1, p2):
+    c = singleton_cache(6)
+    o = oracle.Oracle(c)
+    r = o.decode_step(p1, p2)
+    for h in range(c.n_q_heads):
+        # token-level top-p computed independently: sort exact attention weights
+        K = bf16_bits_to_f32(c.k_cache).astype(np.float64)
+        q = bf16_bits_to_f32(c.q[0, h]).astype(np.float64)
+        A = softmax(K @ q / math.sqrt(128))
+        idx = np.argsort(-A, kind="stable")
+        k = int(np.searchsorted(np.cumsum(A[idx]), p1, side="left")) + 1
+        kept = np.sort(idx[:k])
+        assert r.k1[0, h] == k
+        assert np.array_equal(np.sort(r.order[h, :k]), kept)
+        ref, ref_lse = scipy_dense(c, 0, h, rows=kept)
+        np.testing.assert_allclose(r.out[0, h], ref, rtol=1e-11, atol=1e-13)   # independent of p2
+        assert r.lse[0, h] == pytest.approx(ref_lse, rel=1e-12)
+
+
+# --------------------------------------------------------------------------
+# zero-variance clusters: Zhat_i V_mean_i equals the exact contribution
+# --------------------------------------------------------------------------
+def zero_variance_cache(seed, n_clusters=24, d=128):
+    rng = np.random.default_rng(seed)
+    sizes = rng.choice([1, 2, 4, 8], size=n_clusters)
+    cl = []
+    for s in sizes:
+        centre = bf16_bits_to_f32(f32_to_bf16_bits(rng.standard_normal(d).astype(np.float32)))
+        keys = np.repeat(centre[None], s, axis=0)
+        # values on a 1/8 grid in [-1, 1] and power-of-two sizes: the mean is k/64, exact in bf16
+        vals = rng.integers(-8, 9, size=(s, d)).astype(np.float32) / 8.0
+        cl.append((keys, vals, centre, vals.mean(axis=0, dtype=np.float64)))
+    q = rng.standard_normal((2, d)).astype(np.float32) * 1.5
+    c = cache_from_clusters(q, cl, d)
+    # the stored (bf16) value means must be the exact means for the identity to be exact
+    for i, (_, vals, _, vm) in enumerate(cl):
+        assert np.array_equal(bf16_bits_to_f32(c.v_centroids[i]).astype(np.float64), vm), i
+    return c
+
+
+@pytest.mark.parametrize("p1", [1.0, 0.7])
+def test_zero_variance_clusters_output_independent_of_p2(p1):
+    c = zero_variance_cache(11)
+    o = oracle.Oracle(c)
+    base = o.decode_step(p1, 0.0)
+    for p2 in (0.25, 0.6, 0.9, 1.0):
+        r = o.decode_step(p1, p2)
+        assert (r.k1 == base.k1).all()
+        np.testing.assert_allclose(r.out, base.out, rtol=1e-11, atol=1e-13)
+        np.testing.assert_allclose(r.lse, base.lse, rtol=1e-12)
+    for h in range(c.n_q_heads):
+        kept = np.sort(base.order[h, : base.k1[0, h]])
+        ref, ref_lse = scipy_dense(c, 0, h, rows=rows_of(c, 0, kept))
+        np.testing.assert_allclose(base.out[0, h], ref, rtol=1e-11, atol=1e-13)
+        assert base.lse[0, h] == pytest.approx(ref_lse, rel=1e-12)
+
+
+# --------------------------------------------------------------------------
+# Jensen: Zhat_i <= Z_i when the centroid is the exact mean of the keys
+# --------------------------------------------------------------------------
+def symmetric_pairs_cache(seed, n_clusters=20, d=128):
+    """Every cluster is centre +/- delta pairs on a 1/8 grid: its mean key is exactly the centre."""
+    rng = np.random.default_rng(seed)
+    cl = []
+    for _ in range(n_clusters):
+        centre = rng.integers(-16, 17, size=d).astype(np.float32) / 8.0
+        npairs = int(rng.integers(1, 5))
+        delta = rng.integers(-8, 9, size=(npairs, d)).astype(np.float32) / 8.0
+        keys = np.concatenate([centre + delta, centre - delta])
+        vals = rng.integers(-8, 9, size=(2 * npairs, d)).astype(np.float32) / 8.0
+        vm = vals.mean(axis=0, dtype=np.float64).astype(np.float32)
+        cl.append((keys, vals, centre, vm))
+    q = rng.standard_normal((2, d)).astype(np.float32) * 0.5
+    return cache_from_clusters(q, cl, d)
+
+
+def test_jensen_bound_and_lse_monotone_in_p2():
+    c = symmetric_pairs_cache(21)
+    o = oracle.Oracle(c)
+    for h in range(c.n_q_heads):
+        log_zhat = o.centroid_logits(0, h)
+        log_z = o.exact_cluster_log_mass(0, h)
+        assert (log_zhat <= log_z + 1e-12).all()
+        assert (log_zhat < log_z - 1e-6).any()          # strict somewhere: the test is not vacuous
+    _, dense_lse, _ = o.dense_step()
+    prev = None
+    for p2 in (0.0, 0.2, 0.5, 0.8, 0.95, 1.0):
+        r = o.decode_step(0.9, p2)
+        assert (r.lse <= dense_lse + 1e-12).all()
+        if prev is not None:
+            assert (r.lse >= prev - 1e-12).all()
+        prev = r.lse
+    full = o.decode_step(1.0, 1.0)
+    np.testing.assert_allclose(full.lse, dense_lse, rtol=1e-12)
+
+
+# --------------------------------------------------------------------------
+# p2 = 0 closed form (Eq. 9 with no exact cluster)
+# --------------------------------------------------------------------------
+def test_p2_zero_closed_form():
+    c = make_cache(batch=1, n_kv_heads=1, n_q_heads=4, context=512, mean_cluster=8, size_hi=32, q_scale=0.4, seed=8)
+    o = oracle.Oracle(c)
+    r = o.decode_step(0.9, 0.0)
+    VC = bf16_bits_to_f32(c.v_centroids).astype(np.float64)
+    for h in range(4):
+        assert r.k2[0, h] == 0
+        a_hat = softmax(o.centroid_logits(0, h))
+        kept = r.order[h, : r.k1[0, h]]
+        m1 = a_hat[kept].sum()
+        np.testing.assert_allclose(r.out[0, h], (a_hat[kept][:, None] * VC[kept]).sum(0) / m1, rtol=1e-10, atol=1e-13)
+
+
+# --------------------------------------------------------------------------
+# top-p: mass >= p, minimality, prefix structure, brute force
+# --------------------------------------------------------------------------
+def test_mass_and_minimality_on_cfg0_and_flat_heads():
+    for c in (make_config(0), make_cache(batch=1, n_kv_heads=2, n_q_heads=8, context=2048, q_scale=0.3, seed=4)):
+        o = oracle.Oracle(c)
+        for p1, p2 in ((0.95, 0.9), (0.5, 0.5), (0.99, 0.1)):
+            for h in range(c.n_q_heads):
+                logit = o.centroid_logits(0, h)
+                s = o.select(logit, p1, p2)
+                a = softmax(logit)
+                mass1 = a[s.order[: s.k1]].sum()
+                assert mass1 >= p1 - 1e-15 and a[s.order[: s.k1 - 1]].sum() < p1
+                tau2 = p2 * mass1
+                assert a[s.order[: s.k2]].sum() >= tau2 - 1e-15
+                assert s.k2 == 0 or a[s.order[: s.k2 - 1]].sum() < tau2
+                assert 0 <= s.k2 <= s.k1 <= len(s.order)
+                # order is non-increasing in score, index ascending among equals
+                lo = logit[s.order]
+                assert (np.diff(lo) <= 0).all()
+                eq = np.diff(lo) == 0
+                assert (np.diff(s.order)[eq] > 0).all()
+                assert s.cum[s.k1 - 1] == pytest.approx(mass1, rel=1e-12)
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_top_p_against_brute_force_subsets(seed):
+    rng = np.random.default_rng(100 + seed)
+    n = int(rng.integers(3, 12))
+    logit = rng.standard_normal(n) * rng.uniform(0.3, 3.0)
+    a = softmax(logit)
+    o = oracle.Oracle(make_config(0, shrink=16))
+    for p in (0.3, 0.6, 0.9, 0.99):
+        s = o.select(logit, p, 1.0)
+        best_size, best_mass, best_set = None, -1.0, None
+        for r in range(1, n + 1):
+            for sub in itertools.combinations(range(n), r):
+                m = a[list(sub)].sum()
+                if m >= p and (best_size is None or r < best_size or (r == best_size and m > best_mass)):
+                    best_size, best_mass, best_set = r, m, sub
+            if best_size is not None:
+                break
+        assert s.k1 == best_size
+        assert set(s.order[: s.k1].tolist()) == set(best_set)
+
+
+def test_threshold_is_inclusive_and_ties_go_to_lower_index():
+    o = oracle.Oracle(make_config(0, shrink=16))
+    a_hat = np.array([0.25, 0.5, 0.25])
+    logit = np.log(a_hat)
+    order = o.sorted_order(logit)
+    assert order.tolist() == [1, 0, 2]                     # equal scores: lower index first
+    k1, k2, m1, cum = o.double_top_p(a_hat, order, 0.75, 1.0)
+    assert (k1, k2, m1) == (2, 2, 0.75)                    # reaching p exactly is enough (>=, not >)
+    k1, k2, m1, _ = o.double_top_p(a_hat, order, 0.75 + 1e-12, 0.5)
+    assert (k1, m1) == (3, 1.0) and k2 == 1                # 0.5 >= 0.5 * 1.0
+    k1, k2, _, _ = o.double_top_p(a_hat, order, 1.0, 1.0)
+    assert (k1, k2) == (3, 3)
+    # all-equal scores
+    eq = np.zeros(5)
+    assert o.sorted_order(eq).tolist() == [0, 1, 2, 3, 4]
+    s = o.select(eq, 0.5, 0.5)
+    assert (s.k1, s.k2) == (3, 2)                          # 0.6 >= 0.5 ; then 0.4 >= 0.3
+    # empty clusters are never ranked
+    lg = np.array([0.0, -np.inf, 1.0])
+    assert o.sorted_order(lg).tolist() == [2, 0]
+    assert o.cluster_distribution(lg)[1] == 0.0
+
+
+# --------------------------------------------------------------------------
+# convex hull, permutation and shift invariances
+# --------------------------------------------------------------------------
+def test_output_in_convex_hull_and_invariances():
+    c = make_cache(batch=1, n_kv_heads=1, n_q_heads=4, context=768, mean_cluster=12, size_hi=40, q_scale=0.5, seed=9)
+    o = oracle.Oracle(c)
+    r = o.decode_step(0.9, 0.6)
+    V = bf16_bits_to_f32(c.v_cache).astype(np.float64)
+    VC = bf16_bits_to_f32(c.v_centroids).astype(np.float64)
+    for h in range(4):
+        ex, ap = r.order[h, : r.k2[0, h]], r.order[h, r.k2[0, h]: r.k1[0, h]]
+        cand = np.concatenate([V[rows_of(c, 0, ex)], VC[ap]])
+        assert (r.out[0, h] <= cand.max(0) + 1e-12).all() and (r.out[0, h] >= cand.min(0) - 1e-12).all()
+
+    # permute the clusters (rows move with them): same output, sets map through the permutation
+    n = c.cluster_sizes.size
+    perm = np.random.default_rng(1).permutation(n)
+    new_rows = np.concatenate([np.arange(c.cluster_offsets[j], c.cluster_offsets[j] + c.cluster_sizes[j]) for j in perm])
+    sizes = c.cluster_sizes[perm]
+    offs = np.concatenate([[0], np.cumsum(sizes)[:-1]]).astype(np.int32)
+    c2 = ClusteredCache(batch=1, n_kv_heads=1, n_q_heads=4, head_dim=128, q=c.q, k_cache=c.k_cache[new_rows],
+                        v_cache=c.v_cache[new_rows], seg_row_base=c.seg_row_base, seg_cluster_ptr=c.seg_cluster_ptr,
+                        cluster_offsets=offs, cluster_sizes=sizes, k_centroids=c.k_centroids[perm],
+                        v_centroids=c.v_centroids[perm])
+    r2 = oracle.Oracle(c2).decode_step(0.9, 0.6)
+    np.testing.assert_allclose(r2.out, r.out, rtol=1e-10, atol=1e-13)
+    for h in range(4):
+        assert r2.k1[0, h] == r.k1[0, h] and r2.k2[0, h] == r.k2[0, h]
+        assert np.array_equal(perm[r2.order[h, : r.k1[0, h]]], r.order[h, : r.k1[0, h]])
+
+    # adding a constant to every logit (= scaling all sizes) changes neither A_hat nor the sets
+    lg = o.centroid_logits(0, 1)
+    s_a, s_b = o.select(lg, 0.9, 0.6), o.select(lg + math.log(3.0), 0.9, 0.6)
+    assert (s_a.k1, s_a.k2) == (s_b.k1, s_b.k2) and np.array_equal(s_a.order, s_b.order)
+    np.testing.assert_allclose(s_a.a_hat, s_b.a_hat, rtol=1e-12)
+
+
+def test_empty_segment_and_threads_agree():
+    c = make_cache(batch=2, n_kv_heads=2, n_q_heads=4, context=[256, 128], q_scale=1.0, seed=2)
+    # empty one cluster and a whole segment
+    c.cluster_sizes[3] = 0
+    a, e = c.seg_cluster_ptr[3], c.seg_cluster_ptr[4]
+    c.cluster_sizes[a:e] = 0
+    o = oracle.Oracle(c)
+    r1 = o.decode_step(0.9, 0.5, n_threads=1)
+    r4 = o.decode_step(0.9, 0.5, n_threads=4)
+    assert np.array_equal(r1.out, r4.out) and np.array_equal(r1.k1, r4.k1) and np.array_equal(r1.order, r4.order)
+    assert (r1.k1[1, 2:] == 0).all() and (r1.out[1, 2:] == 0).all() and np.isneginf(r1.lse[1, 2:]).all()
+    assert 3 not in r1.order[0, : r1.k1[0, 0]].tolist()
