@@ -1,0 +1,139 @@
+/*
+ * dp.h -- C ABI of the MI355X (gfx950) Double-P decode-attention library.
+ *
+ * One decode step, one layer, of hierarchical top-p sparse attention over a
+ * clustered KV cache (paper Sec. 4.2-4.4):
+ *   stage 1  size-weighted centroid scoring                 (Eq. 3, Eq. 5, Eq. 6)
+ *   stage 2  first top-p over clusters, second top-p that splits the retained
+ *            clusters into "exact" and "approximated"        (Eq. 7, Sec. 4.3)
+ *   stage 3  attention over the tokens of the exact clusters plus one
+ *            size-weighted centroid pseudo-token per approximated cluster,
+ *            with one shared normaliser                      (Eq. 8, Eq. 9)
+ *
+ * Conventions for every entry point
+ *   - Plain C linkage, no exceptions, no torch types.
+ *   - Every pointer inside dp_problem and every buffer argument is a DEVICE
+ *     pointer owned by the caller, unless the comment says "host".  dp_problem
+ *     itself is a host struct read during the call only.
+ *   - Calls enqueue work on `stream` (a hipStream_t passed as void*; NULL = the
+ *     default stream) and return without synchronising.  Nothing is allocated
+ *     or freed; the library keeps no state between calls.  Inputs are never
+ *     written.  Two calls that share a workspace must be ordered by the caller.
+ *   - Errors that can be detected on the host (null pointers, bad shapes, p out
+ *     of range, workspace too small, unsupported head_dim) are returned before
+ *     anything is launched.  Device data (offsets, sizes, ids) is NOT validated:
+ *     out-of-range values there are undefined behaviour.
+ *   - A "head" is a (sequence b, query head h) pair, index b*n_q_heads + h.  It
+ *     reads KV segment seg = b*n_kv_heads + h/(n_q_heads/n_kv_heads).
+ *   - Cluster ids in sel_ids are segment-local (0 .. Kc_seg-1).
+ */
+#ifndef DP_H
+#define DP_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  DP_OK = 0,
+  DP_ERR_INVALID_ARG = -1,         /* null pointer, non-positive shape, p outside its domain        */
+  DP_ERR_UNSUPPORTED = -2,         /* head_dim != 128, n_q_heads/n_kv_heads > 16, unknown dtype     */
+  DP_ERR_WORKSPACE_TOO_SMALL = -3, /* workspace_bytes < dp_workspace_bytes(problem)                 */
+  DP_ERR_HIP = -4                  /* a HIP runtime call failed (launch error)                      */
+} dp_status;
+
+typedef enum { DP_BF16 = 0, DP_F32 = 1 } dp_dtype;
+
+/* Second top-p reading.  Default: the exact set is the shortest prefix of the
+ * score order whose estimated mass reaches p2 * M1, M1 being the mass kept by
+ * the first top-p (a top-p over the retained set).  With this flag the
+ * threshold is min(p2, M1): p2 measured on the whole distribution. */
+#define DP_FLAG_P2_ABSOLUTE 1u
+
+typedef struct {
+  int32_t batch, n_kv_heads, n_q_heads, head_dim; /* n_q_heads % n_kv_heads == 0; head_dim == 128 */
+  const void *q;                  /* bf16 [batch, n_q_heads, head_dim]                                  */
+  const void *k_cache;            /* bf16 [total_rows, head_dim]; a cluster's rows are consecutive      */
+  const void *v_cache;            /* bf16 [total_rows, head_dim]; same row order as k_cache             */
+  const int64_t *seg_row_base;    /* [batch*n_kv_heads]    first cache row of each segment              */
+  const int32_t *seg_cluster_ptr; /* [batch*n_kv_heads+1]  CSR: clusters of seg are [ptr[seg],ptr[seg+1]) */
+  const int32_t *cluster_offsets; /* [total_clusters] first row of the cluster, relative to seg_row_base */
+  const int32_t *cluster_sizes;   /* [total_clusters] s_i >= 0; a cluster with s_i == 0 is never selected */
+  const void *k_centroids;        /* bf16 [total_clusters, head_dim]  C_i: mean key of the cluster      */
+  const void *v_centroids;        /* bf16 [total_clusters, head_dim]  mean value (Eq. 2), NOT the sum   */
+  int32_t total_clusters;         /* host-known: seg_cluster_ptr[batch*n_kv_heads]                      */
+  int32_t max_clusters_per_seg;   /* host-known upper bound on ptr[seg+1]-ptr[seg]                      */
+  int32_t max_rows_per_seg;       /* host-known upper bound on the rows (tokens) of one segment         */
+  float sm_scale;                 /* logit scale; 0 => 1/sqrt(head_dim)                                 */
+  uint32_t flags;                 /* DP_FLAG_*                                                          */
+} dp_problem;
+
+/* Host-only.  Bytes of device workspace that dp_sparse_decode and
+ * dp_decode_attention need for this problem (depends on the shape fields and
+ * the three host-known bounds only).  Returns 0 for an invalid problem. */
+size_t dp_workspace_bytes(const dp_problem *problem);
+
+/* Number of floats in the logits buffer: (n_q_heads/n_kv_heads) * total_clusters. */
+size_t dp_logits_count(const dp_problem *problem);
+
+/* Stage 1 (Eq. 3, 5, 6 before normalisation).  For head (b, h), j = h % G,
+ * G = n_q_heads/n_kv_heads, and cluster i of its segment:
+ *   logits[G*ptr[seg] + j*Kc_seg + i] = sm_scale * (q[b,h] . C_i) + ln(s_i)   (fp32; -inf if s_i == 0)
+ * i.e. one contiguous fp32 row of Kc_seg logits per head.  Each centroid row is
+ * read once and scored against the G query heads that share it. */
+dp_status dp_score_centroids(const dp_problem *problem, float *logits, void *stream);
+
+/* Stage 2 (Eq. 6 softmax, Eq. 7 first top-p, Sec. 4.3 second top-p).  Per head:
+ * clusters are ordered by logit descending, ties by lower cluster index; the
+ * retained set is the shortest prefix whose softmax mass reaches p1 (all
+ * non-empty clusters when p1 >= 1); the exact set is the shortest prefix that
+ * reaches the second threshold (see DP_FLAG_P2_ABSOLUTE; p2 >= 1 => every
+ * retained cluster, p2 == 0 => none).  Domain 0 < p1 <= 1, 0 <= p2 <= 1.
+ * Outputs (device):
+ *   sel_ids  int32 [batch*n_q_heads, max_clusters_per_seg]: per head the exact
+ *            ids in ascending order, then the approximated ids in ascending order;
+ *   n_exact, n_retained, n_exact_tokens  int32 [batch*n_q_heads]
+ *            (n_exact_tokens = sum of s_i over the exact set).
+ * Masses are accumulated in 2^-40 fixed point, so the result is independent of
+ * thread scheduling (bitwise reproducible). */
+dp_status dp_topp_select(const dp_problem *problem, const float *logits, float p1, float p2, int32_t *sel_ids,
+                         int32_t *n_exact, int32_t *n_retained, int32_t *n_exact_tokens, void *stream);
+
+/* Stage 3 (Eq. 8, Eq. 9) for caller-given sets in the dp_topp_select format
+ * (exact ids first, n_exact of them, then n_retained - n_exact approximated
+ * ids; ids unique, each cluster non-empty).  n_exact_tokens is recomputed, the
+ * argument may be NULL.
+ *   out  [batch, n_q_heads, head_dim] of out_dtype;  lse (nullable) fp32
+ *   [batch*n_q_heads] = ln of the shared normaliser Z~.  A head with an empty
+ *   retained set gets out = 0, lse = -inf.
+ * workspace: at least dp_workspace_bytes(problem) bytes, 256-byte aligned. */
+dp_status dp_sparse_decode(const dp_problem *problem, const int32_t *sel_ids, const int32_t *n_exact,
+                           const int32_t *n_retained, const int32_t *n_exact_tokens, void *out, dp_dtype out_dtype,
+                           float *lse, void *workspace, size_t workspace_bytes, void *stream);
+
+/* Stages 1-3 in one call (logits and id lists live in the workspace).  n_exact,
+ * n_retained, n_exact_tokens (int32 [batch*n_q_heads]) and lse are optional
+ * outputs (NULL to skip). */
+dp_status dp_decode_attention(const dp_problem *problem, float p1, float p2, void *out, dp_dtype out_dtype,
+                              float *lse, int32_t *n_exact, int32_t *n_retained, int32_t *n_exact_tokens,
+                              void *workspace, size_t workspace_bytes, void *stream);
+
+/* Where dp_decode_attention keeps its intermediate results inside the
+ * workspace (byte offsets; host-only, for inspection by tests and tools):
+ * logits as in dp_score_centroids, sel_ids as in dp_topp_select. */
+typedef struct {
+  size_t logits, sel_ids, row_start, chunk_entry, counts, partials, total;
+  int32_t splits;      /* partial results per head in stage 3          */
+  int32_t chunk_rows;  /* granularity (rows) of the stage-3 work split */
+} dp_workspace_layout;
+dp_status dp_get_workspace_layout(const dp_problem *problem, dp_workspace_layout *layout /* host */);
+
+const char *dp_status_string(dp_status status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DP_H */

@@ -1,0 +1,19 @@
+"""MI355X-native Double-P decode attention (hierarchical top-p sparse attention
+over a clustered KV cache): hand-written gfx950 kernels behind a C ABI
+(include/dp.h) and a thin ctypes binding with the same entry-point names."""
+from .binding import (  # noqa: F401
+    DP_BF16,
+    DP_F32,
+    DP_FLAG_P2_ABSOLUTE,
+    DPError,
+    DeviceCache,
+    Problem,
+    dp_decode_attention,
+    dp_score_centroids,
+    dp_sparse_decode,
+    dp_topp_select,
+    dp_workspace_bytes,
+    dp_workspace_layout,
+    library_path,
+    load_library,
+)

@@ -1,0 +1,215 @@
+"""ctypes binding of libdp_hip.so: argument marshalling only.
+
+Every function has the name and the meaning of the C entry point in
+include/dp.h.  torch is used for device memory and for the current stream;
+all arithmetic of the decode step happens inside the HIP kernels.  There is no
+CPU fallback: if the library is missing, loading raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from dataclasses import dataclass
+from typing import Optional
+
+import numpy as np
+import torch
+
+DP_BF16, DP_F32 = 0, 1
+DP_FLAG_P2_ABSOLUTE = 1
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_PKG, "libdp_hip.so")
+
+EXPORTS = ["dp_workspace_bytes", "dp_logits_count", "dp_get_workspace_layout", "dp_score_centroids",
+           "dp_topp_select", "dp_sparse_decode", "dp_decode_attention", "dp_status_string"]
+
+
+class DPError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {_status_string(status)} ({status})")
+
+
+class _Problem(C.Structure):
+    _fields_ = [("batch", C.c_int32), ("n_kv_heads", C.c_int32), ("n_q_heads", C.c_int32), ("head_dim", C.c_int32),
+                ("q", C.c_void_p), ("k_cache", C.c_void_p), ("v_cache", C.c_void_p),
+                ("seg_row_base", C.c_void_p), ("seg_cluster_ptr", C.c_void_p),
+                ("cluster_offsets", C.c_void_p), ("cluster_sizes", C.c_void_p),
+                ("k_centroids", C.c_void_p), ("v_centroids", C.c_void_p),
+                ("total_clusters", C.c_int32), ("max_clusters_per_seg", C.c_int32),
+                ("max_rows_per_seg", C.c_int32), ("sm_scale", C.c_float), ("flags", C.c_uint32)]
+
+
+class _Layout(C.Structure):
+    _fields_ = [("logits", C.c_size_t), ("sel_ids", C.c_size_t), ("row_start", C.c_size_t),
+                ("chunk_entry", C.c_size_t), ("counts", C.c_size_t), ("partials", C.c_size_t),
+                ("total", C.c_size_t), ("splits", C.c_int32), ("chunk_rows", C.c_int32)]
+
+
+_lib = None
+
+
+def library_path() -> str:
+    return _LIB_PATH
+
+
+def load_library():
+    """Load libdp_hip.so (built by paper_2602_05191_amd.build / __graft_entry__.build)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        raise ImportError(f"{_LIB_PATH} is missing: run `python -c 'import __graft_entry__ as g; g.build()'` "
+                          "(there is no CPU fallback)")
+    L = C.CDLL(_LIB_PATH)
+    PP, V, F, I = C.POINTER(_Problem), C.c_void_p, C.c_float, C.c_int
+    L.dp_workspace_bytes.restype = C.c_size_t
+    L.dp_workspace_bytes.argtypes = [PP]
+    L.dp_logits_count.restype = C.c_size_t
+    L.dp_logits_count.argtypes = [PP]
+    L.dp_get_workspace_layout.restype = I
+    L.dp_get_workspace_layout.argtypes = [PP, C.POINTER(_Layout)]
+    L.dp_score_centroids.restype = I
+    L.dp_score_centroids.argtypes = [PP, V, V]
+    L.dp_topp_select.restype = I
+    L.dp_topp_select.argtypes = [PP, V, F, F, V, V, V, V, V]
+    L.dp_sparse_decode.restype = I
+    L.dp_sparse_decode.argtypes = [PP, V, V, V, V, V, I, V, V, C.c_size_t, V]
+    L.dp_decode_attention.restype = I
+    L.dp_decode_attention.argtypes = [PP, F, F, V, I, V, V, V, V, V, C.c_size_t, V]
+    L.dp_status_string.restype = C.c_char_p
+    L.dp_status_string.argtypes = [I]
+    _lib = L
+    return L
+
+
+def _status_string(status: int) -> str:
+    return load_library().dp_status_string(int(status)).decode()
+
+
+def _check(status: int, where: str):
+    if status != 0:
+        raise DPError(status, where)
+
+
+def _ptr(t: Optional[torch.Tensor]) -> Optional[int]:
+    if t is None:
+        return None
+    return t.data_ptr() if t.numel() else None
+
+
+def _stream(stream) -> Optional[int]:
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    if isinstance(stream, int):
+        return stream or None
+    return stream.cuda_stream or None
+
+
+@dataclass
+class DeviceCache:
+    """Device-resident copies of one decode step's inputs (bf16 kept as raw int16 bits)."""
+    batch: int
+    n_kv_heads: int
+    n_q_heads: int
+    head_dim: int
+    q: torch.Tensor
+    k_cache: torch.Tensor
+    v_cache: torch.Tensor
+    seg_row_base: torch.Tensor
+    seg_cluster_ptr: torch.Tensor
+    cluster_offsets: torch.Tensor
+    cluster_sizes: torch.Tensor
+    k_centroids: torch.Tensor
+    v_centroids: torch.Tensor
+    total_clusters: int
+    max_clusters_per_seg: int
+    max_rows_per_seg: int
+
+    @staticmethod
+    def from_host(cache, device="cuda:0") -> "DeviceCache":
+        """Upload a workloads.ClusteredCache (numpy, bf16 as uint16 bits)."""
+        def up(a, dt):
+            return torch.from_numpy(np.ascontiguousarray(a).view(dt)).to(device)
+        return DeviceCache(
+            batch=cache.batch, n_kv_heads=cache.n_kv_heads, n_q_heads=cache.n_q_heads, head_dim=cache.head_dim,
+            q=up(cache.q, np.int16), k_cache=up(cache.k_cache, np.int16), v_cache=up(cache.v_cache, np.int16),
+            seg_row_base=up(cache.seg_row_base, np.int64), seg_cluster_ptr=up(cache.seg_cluster_ptr, np.int32),
+            cluster_offsets=up(cache.cluster_offsets, np.int32), cluster_sizes=up(cache.cluster_sizes, np.int32),
+            k_centroids=up(cache.k_centroids, np.int16), v_centroids=up(cache.v_centroids, np.int16),
+            total_clusters=int(cache.seg_cluster_ptr[-1]), max_clusters_per_seg=cache.max_clusters_per_seg,
+            max_rows_per_seg=cache.max_rows_per_seg)
+
+    def clone(self) -> "DeviceCache":
+        """A copy at distinct device addresses (used to rotate layers in the bench)."""
+        kw = {k: (v.clone() if isinstance(v, torch.Tensor) else v) for k, v in self.__dict__.items()}
+        return DeviceCache(**kw)
+
+
+class Problem:
+    """Host-side dp_problem that points at a DeviceCache's tensors."""
+
+    def __init__(self, dc: DeviceCache, sm_scale: float = 0.0, flags: int = 0):
+        self.dc = dc
+        self.nh = dc.batch * dc.n_q_heads
+        self.c = _Problem(dc.batch, dc.n_kv_heads, dc.n_q_heads, dc.head_dim, _ptr(dc.q), _ptr(dc.k_cache),
+                          _ptr(dc.v_cache), _ptr(dc.seg_row_base), _ptr(dc.seg_cluster_ptr),
+                          _ptr(dc.cluster_offsets), _ptr(dc.cluster_sizes), _ptr(dc.k_centroids),
+                          _ptr(dc.v_centroids), dc.total_clusters, dc.max_clusters_per_seg, dc.max_rows_per_seg,
+                          float(sm_scale), int(flags))
+
+    @property
+    def ref(self):
+        return C.byref(self.c)
+
+    @property
+    def device(self):
+        return self.dc.q.device
+
+
+def dp_workspace_bytes(problem: Problem) -> int:
+    return int(load_library().dp_workspace_bytes(problem.ref))
+
+
+def dp_workspace_layout(problem: Problem) -> dict:
+    lay = _Layout()
+    _check(load_library().dp_get_workspace_layout(problem.ref, C.byref(lay)), "dp_get_workspace_layout")
+    return {n: int(getattr(lay, n)) for n, _ in _Layout._fields_}
+
+
+def dp_score_centroids(problem: Problem, logits: torch.Tensor, stream=None) -> None:
+    L = load_library()
+    assert logits.dtype == torch.float32 and logits.is_contiguous() and logits.numel() >= L.dp_logits_count(problem.ref)
+    _check(L.dp_score_centroids(problem.ref, _ptr(logits), _stream(stream)), "dp_score_centroids")
+
+
+def dp_topp_select(problem: Problem, logits: torch.Tensor, p1: float, p2: float, sel_ids: torch.Tensor,
+                   n_exact: torch.Tensor, n_retained: torch.Tensor, n_exact_tokens: torch.Tensor, stream=None) -> None:
+    for t in (sel_ids, n_exact, n_retained, n_exact_tokens):
+        assert t.dtype == torch.int32 and t.is_contiguous()
+    assert sel_ids.numel() >= problem.nh * problem.dc.max_clusters_per_seg and n_exact.numel() >= problem.nh
+    _check(load_library().dp_topp_select(problem.ref, _ptr(logits), p1, p2, _ptr(sel_ids), _ptr(n_exact),
+                                         _ptr(n_retained), _ptr(n_exact_tokens), _stream(stream)), "dp_topp_select")
+
+
+def dp_sparse_decode(problem: Problem, sel_ids: torch.Tensor, n_exact: torch.Tensor, n_retained: torch.Tensor,
+                     out: torch.Tensor, lse: Optional[torch.Tensor], workspace: torch.Tensor, stream=None) -> None:
+    dt = {torch.float32: DP_F32, torch.bfloat16: DP_BF16}[out.dtype]
+    assert out.is_contiguous() and out.numel() == problem.nh * problem.dc.head_dim
+    _check(load_library().dp_sparse_decode(problem.ref, _ptr(sel_ids), _ptr(n_exact), _ptr(n_retained), None,
+                                           _ptr(out), dt, _ptr(lse), _ptr(workspace),
+                                           workspace.numel() * workspace.element_size(), _stream(stream)),
+           "dp_sparse_decode")
+
+
+def dp_decode_attention(problem: Problem, p1: float, p2: float, out: torch.Tensor, lse: Optional[torch.Tensor],
+                        workspace: torch.Tensor, n_exact: Optional[torch.Tensor] = None,
+                        n_retained: Optional[torch.Tensor] = None, n_exact_tokens: Optional[torch.Tensor] = None,
+                        stream=None) -> None:
+    dt = {torch.float32: DP_F32, torch.bfloat16: DP_BF16}[out.dtype]
+    assert out.is_contiguous() and out.numel() == problem.nh * problem.dc.head_dim
+    _check(load_library().dp_decode_attention(problem.ref, p1, p2, _ptr(out), dt, _ptr(lse), _ptr(n_exact),
+                                              _ptr(n_retained), _ptr(n_exact_tokens), _ptr(workspace),
+                                              workspace.numel() * workspace.element_size(), _stream(stream)),
+           "dp_decode_attention")

@@ -1,0 +1,241 @@
+// C ABI of the Double-P decode-attention library (see include/dp.h): argument
+// checks, workspace layout and kernel sequencing.  No allocation, no
+// synchronisation, no state.
+#include "dp.h"
+
+#include <math.h>
+
+#include "dp_kernels.hpp"
+
+namespace {
+
+inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+bool shape_ok(const dp_problem *p) {
+  return p && p->batch > 0 && p->n_kv_heads > 0 && p->n_q_heads > 0 && p->n_q_heads % p->n_kv_heads == 0 &&
+         p->total_clusters >= 0 && p->max_clusters_per_seg >= 0 && p->max_rows_per_seg >= 0 &&
+         p->max_clusters_per_seg <= p->total_clusters && !(p->sm_scale < 0.0f) && p->sm_scale == p->sm_scale;
+}
+
+dp_status supported(const dp_problem *p) {
+  if (p->head_dim != dp::kHeadDim) return DP_ERR_UNSUPPORTED;
+  if (p->n_q_heads / p->n_kv_heads > 16) return DP_ERR_UNSUPPORTED;  // one DPP-row lane per head of the group
+  if (p->max_clusters_per_seg > dp::kSelectMaxClusters) return DP_ERR_UNSUPPORTED;
+  return DP_OK;
+}
+
+bool pointers_ok(const dp_problem *p) {
+  return p->q && p->seg_row_base && p->seg_cluster_ptr &&
+         (p->total_clusters == 0 ||
+          (p->cluster_offsets && p->cluster_sizes && p->k_centroids && p->v_centroids && p->k_cache && p->v_cache));
+}
+
+dp::CacheView view_of(const dp_problem *p) {
+  dp::CacheView c;
+  c.batch = p->batch;
+  c.n_kv_heads = p->n_kv_heads;
+  c.n_q_heads = p->n_q_heads;
+  c.group = p->n_q_heads / p->n_kv_heads;
+  c.q = p->q;
+  c.k_cache = p->k_cache;
+  c.v_cache = p->v_cache;
+  c.k_centroids = p->k_centroids;
+  c.v_centroids = p->v_centroids;
+  c.seg_row_base = p->seg_row_base;
+  c.seg_cluster_ptr = p->seg_cluster_ptr;
+  c.cluster_offsets = p->cluster_offsets;
+  c.cluster_sizes = p->cluster_sizes;
+  c.max_clusters_per_seg = p->max_clusters_per_seg;
+  c.max_rows_per_seg = p->max_rows_per_seg;
+  c.sm_scale = p->sm_scale != 0.0f ? p->sm_scale : 1.0f / sqrtf((float)p->head_dim);
+  return c;
+}
+
+// stage-3 splits per head: aim at a few thousand workgroups in total
+int choose_splits(const dp_problem *p) {
+  const long nh = (long)p->batch * p->n_q_heads;
+  long s = (4096 + nh - 1) / nh;
+  const long by_rows = ((long)p->max_rows_per_seg + p->max_clusters_per_seg + dp::kChunkRows - 1) / dp::kChunkRows;
+  if (s > by_rows) s = by_rows;
+  if (s > 256) s = 256;
+  if (s < 1) s = 1;
+  return (int)s;
+}
+
+void layout_of(const dp_problem *p, dp_workspace_layout *L) {
+  const size_t nh = (size_t)p->batch * p->n_q_heads;
+  const size_t mk = (size_t)p->max_clusters_per_seg;
+  const size_t chunk_stride = ((size_t)p->max_rows_per_seg + mk) / dp::kChunkRows + 2;
+  const int splits = choose_splits(p);
+  size_t off = 0;
+  L->logits = off;
+  off = align_up(off + sizeof(float) * (size_t)(p->n_q_heads / p->n_kv_heads) * (size_t)p->total_clusters, 256);
+  L->sel_ids = off;
+  off = align_up(off + sizeof(int32_t) * nh * mk, 256);
+  size_t ent_src = off;  // plan.ent_src shares the layout slot directly after sel_ids
+  off = align_up(off + sizeof(int32_t) * nh * mk, 256);
+  L->row_start = off;
+  off = align_up(off + sizeof(int32_t) * nh * (mk + 1), 256);
+  L->chunk_entry = off;
+  off = align_up(off + sizeof(int32_t) * nh * chunk_stride, 256);
+  L->counts = off;  // n_exact, n_retained, n_exact_tokens, head_rows : 4 x [nh]
+  off = align_up(off + sizeof(int32_t) * 4 * nh, 256);
+  L->partials = off;
+  off = align_up(off + sizeof(float) * nh * (size_t)splits * (dp::kHeadDim + 2), 256);
+  L->total = off;
+  L->splits = splits;
+  L->chunk_rows = dp::kChunkRows;
+  (void)ent_src;
+}
+
+struct Workspace {
+  float *logits;
+  int32_t *sel_ids, *n_exact, *n_retained, *n_exact_tokens;
+  dp::Plan plan;
+  float *partials;
+  int splits;
+};
+
+Workspace carve(const dp_problem *p, void *ws) {
+  dp_workspace_layout L;
+  layout_of(p, &L);
+  char *b = static_cast<char *>(ws);
+  const size_t nh = (size_t)p->batch * p->n_q_heads;
+  const size_t mk = (size_t)p->max_clusters_per_seg;
+  Workspace w;
+  w.logits = reinterpret_cast<float *>(b + L.logits);
+  w.sel_ids = reinterpret_cast<int32_t *>(b + L.sel_ids);
+  w.plan.ent_src = reinterpret_cast<int32_t *>(b + align_up(L.sel_ids + sizeof(int32_t) * nh * mk, 256));
+  w.plan.row_start = reinterpret_cast<int32_t *>(b + L.row_start);
+  w.plan.chunk_entry = reinterpret_cast<int32_t *>(b + L.chunk_entry);
+  w.plan.chunk_stride = (int32_t)(((size_t)p->max_rows_per_seg + mk) / dp::kChunkRows + 2);
+  int32_t *counts = reinterpret_cast<int32_t *>(b + L.counts);
+  w.n_exact = counts;
+  w.n_retained = counts + nh;
+  w.n_exact_tokens = counts + 2 * nh;
+  w.plan.head_rows = counts + 3 * nh;
+  w.partials = reinterpret_cast<float *>(b + L.partials);
+  w.splits = L.splits;
+  return w;
+}
+
+dp_status check_common(const dp_problem *p) {
+  if (!shape_ok(p)) return DP_ERR_INVALID_ARG;
+  const dp_status s = supported(p);
+  if (s != DP_OK) return s;
+  if (!pointers_ok(p)) return DP_ERR_INVALID_ARG;
+  return DP_OK;
+}
+
+bool p_in_domain(float p1, float p2) { return p1 > 0.0f && p1 <= 1.0f && p2 >= 0.0f && p2 <= 1.0f; }
+
+}  // namespace
+
+extern "C" {
+
+size_t dp_workspace_bytes(const dp_problem *problem) {
+  if (!shape_ok(problem)) return 0;
+  dp_workspace_layout L;
+  layout_of(problem, &L);
+  return L.total;
+}
+
+size_t dp_logits_count(const dp_problem *problem) {
+  if (!shape_ok(problem)) return 0;
+  return (size_t)(problem->n_q_heads / problem->n_kv_heads) * (size_t)problem->total_clusters;
+}
+
+dp_status dp_get_workspace_layout(const dp_problem *problem, dp_workspace_layout *layout) {
+  if (!shape_ok(problem) || !layout) return DP_ERR_INVALID_ARG;
+  layout_of(problem, layout);
+  return DP_OK;
+}
+
+dp_status dp_score_centroids(const dp_problem *problem, float *logits, void *stream) {
+  dp_status st = check_common(problem);
+  if (st != DP_OK) return st;
+  if (!logits && problem->total_clusters > 0) return DP_ERR_INVALID_ARG;
+  if (problem->total_clusters == 0) return DP_OK;
+  return dp::launch_score(view_of(problem), logits, static_cast<hipStream_t>(stream)) == hipSuccess ? DP_OK
+                                                                                                   : DP_ERR_HIP;
+}
+
+dp_status dp_topp_select(const dp_problem *problem, const float *logits, float p1, float p2, int32_t *sel_ids,
+                         int32_t *n_exact, int32_t *n_retained, int32_t *n_exact_tokens, void *stream) {
+  dp_status st = check_common(problem);
+  if (st != DP_OK) return st;
+  if (!p_in_domain(p1, p2)) return DP_ERR_INVALID_ARG;
+  if (!n_exact || !n_retained || !n_exact_tokens) return DP_ERR_INVALID_ARG;
+  if (problem->max_clusters_per_seg > 0 && (!logits || !sel_ids)) return DP_ERR_INVALID_ARG;
+  dp::SelectOut out{sel_ids, n_exact, n_retained, n_exact_tokens};
+  dp::Plan none{nullptr, nullptr, nullptr, nullptr, 0};
+  return dp::launch_select(view_of(problem), logits, p1, p2, problem->flags, out, none,
+                           static_cast<hipStream_t>(stream)) == hipSuccess
+             ? DP_OK
+             : DP_ERR_HIP;
+}
+
+dp_status dp_sparse_decode(const dp_problem *problem, const int32_t *sel_ids, const int32_t *n_exact,
+                           const int32_t *n_retained, const int32_t *n_exact_tokens, void *out, dp_dtype out_dtype,
+                           float *lse, void *workspace, size_t workspace_bytes, void *stream) {
+  (void)n_exact_tokens;
+  dp_status st = check_common(problem);
+  if (st != DP_OK) return st;
+  if (out_dtype != DP_BF16 && out_dtype != DP_F32) return DP_ERR_UNSUPPORTED;
+  if (!n_exact || !n_retained || !out || !workspace) return DP_ERR_INVALID_ARG;
+  if (problem->max_clusters_per_seg > 0 && !sel_ids) return DP_ERR_INVALID_ARG;
+  if (workspace_bytes < dp_workspace_bytes(problem)) return DP_ERR_WORKSPACE_TOO_SMALL;
+  if (reinterpret_cast<uintptr_t>(workspace) % 256) return DP_ERR_INVALID_ARG;
+  const dp::CacheView c = view_of(problem);
+  const Workspace w = carve(problem, workspace);
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  if (dp::launch_plan(c, sel_ids, n_exact, n_retained, nullptr, w.plan, s) != hipSuccess) return DP_ERR_HIP;
+  if (dp::launch_decode(c, n_exact, n_retained, w.plan, w.partials, w.splits, out, out_dtype == DP_BF16, lse, s) !=
+      hipSuccess)
+    return DP_ERR_HIP;
+  return DP_OK;
+}
+
+dp_status dp_decode_attention(const dp_problem *problem, float p1, float p2, void *out, dp_dtype out_dtype,
+                              float *lse, int32_t *n_exact, int32_t *n_retained, int32_t *n_exact_tokens,
+                              void *workspace, size_t workspace_bytes, void *stream) {
+  dp_status st = check_common(problem);
+  if (st != DP_OK) return st;
+  if (!p_in_domain(p1, p2)) return DP_ERR_INVALID_ARG;
+  if (out_dtype != DP_BF16 && out_dtype != DP_F32) return DP_ERR_UNSUPPORTED;
+  if (!out || !workspace) return DP_ERR_INVALID_ARG;
+  if (workspace_bytes < dp_workspace_bytes(problem)) return DP_ERR_WORKSPACE_TOO_SMALL;
+  if (reinterpret_cast<uintptr_t>(workspace) % 256) return DP_ERR_INVALID_ARG;
+  const dp::CacheView c = view_of(problem);
+  const Workspace w = carve(problem, workspace);
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  if (dp::launch_score(c, w.logits, s) != hipSuccess) return DP_ERR_HIP;
+  dp::SelectOut so{w.sel_ids, w.n_exact, w.n_retained, w.n_exact_tokens};
+  if (dp::launch_select(c, w.logits, p1, p2, problem->flags, so, w.plan, s) != hipSuccess) return DP_ERR_HIP;
+  if (dp::launch_decode(c, w.n_exact, w.n_retained, w.plan, w.partials, w.splits, out, out_dtype == DP_BF16, lse,
+                        s) != hipSuccess)
+    return DP_ERR_HIP;
+  const size_t nh = (size_t)problem->batch * problem->n_q_heads;
+  // optional count outputs: device-to-device copies on the same stream
+  if (n_exact && hipMemcpyAsync(n_exact, w.n_exact, nh * 4, hipMemcpyDeviceToDevice, s) != hipSuccess)
+    return DP_ERR_HIP;
+  if (n_retained && hipMemcpyAsync(n_retained, w.n_retained, nh * 4, hipMemcpyDeviceToDevice, s) != hipSuccess)
+    return DP_ERR_HIP;
+  if (n_exact_tokens &&
+      hipMemcpyAsync(n_exact_tokens, w.n_exact_tokens, nh * 4, hipMemcpyDeviceToDevice, s) != hipSuccess)
+    return DP_ERR_HIP;
+  return DP_OK;
+}
+
+const char *dp_status_string(dp_status status) {
+  switch (status) {
+    case DP_OK: return "DP_OK";
+    case DP_ERR_INVALID_ARG: return "DP_ERR_INVALID_ARG: null pointer, bad shape or p outside its domain";
+    case DP_ERR_UNSUPPORTED: return "DP_ERR_UNSUPPORTED: head_dim != 128, GQA group > 16, too many clusters or bad dtype";
+    case DP_ERR_WORKSPACE_TOO_SMALL: return "DP_ERR_WORKSPACE_TOO_SMALL: see dp_workspace_bytes";
+    case DP_ERR_HIP: return "DP_ERR_HIP: a HIP runtime call failed";
+  }
+  return "unknown dp_status";
+}
+
+}  // extern "C"

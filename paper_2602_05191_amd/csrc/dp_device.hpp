@@ -1,0 +1,147 @@
+// Device-side helpers shared by the gfx950 kernels of the Double-P decode step.
+//
+// Data layout facts the kernels rely on:
+//   * head_dim = 128, bf16: one K / V / centroid row is 256 B = 16 lanes x 16 B,
+//     so a 16-lane DPP row owns one cache row and a wave64 covers 4 rows per
+//     global_load_dwordx4.  Lane t of the row holds dims [8t, 8t+8).
+//   * cross-lane sums inside a 16-lane row use DPP modifiers on v_add_f32
+//     (quad_perm, row_half_mirror, row_mirror): no LDS traffic.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "dp_kernels.hpp"
+
+namespace dp {
+
+constexpr int kRowBytes = kHeadDim * 2;
+
+// ---------------------------------------------------------------- DPP ----
+template <int CTRL>
+__device__ __forceinline__ float dpp_mov(float v) {
+  return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xf, 0xf, true));
+}
+
+// sum over the 16 lanes of a DPP row; every lane of the row gets the total
+__device__ __forceinline__ float row16_sum(float v) {
+  v += dpp_mov<0xB1>(v);   // quad_perm [1,0,3,2]
+  v += dpp_mov<0x4E>(v);   // quad_perm [2,3,0,1]
+  v += dpp_mov<0x141>(v);  // row_half_mirror
+  v += dpp_mov<0x140>(v);  // row_mirror
+  return v;
+}
+
+// ------------------------------------------------------------- bf16 ------
+__device__ __forceinline__ float bf16_lo(uint32_t u) { return __uint_as_float(u << 16); }
+__device__ __forceinline__ float bf16_hi(uint32_t u) { return __uint_as_float(u & 0xffff0000u); }
+
+__device__ __forceinline__ void unpack8(const uint4 &r, float (&f)[8]) {
+  f[0] = bf16_lo(r.x); f[1] = bf16_hi(r.x);
+  f[2] = bf16_lo(r.y); f[3] = bf16_hi(r.y);
+  f[4] = bf16_lo(r.z); f[5] = bf16_hi(r.z);
+  f[6] = bf16_lo(r.w); f[7] = bf16_hi(r.w);
+}
+
+// fp32 -> bf16 bits, round to nearest even (finite inputs)
+__device__ __forceinline__ uint32_t f32_to_bf16_rne(float f) {
+  uint32_t u = __float_as_uint(f);
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return u >> 16;
+}
+
+// 16-byte slice `lane16` of bf16 row `row` of a [rows,128] matrix
+__device__ __forceinline__ uint4 load_row_slice(const void *base, int64_t row, int lane16) {
+  const char *p = static_cast<const char *>(base) + row * kRowBytes + lane16 * 16;
+  return *reinterpret_cast<const uint4 *>(p);
+}
+
+// partial dot of the lane's 8 dims
+__device__ __forceinline__ float dot8(const float (&a)[8], const float (&b)[8]) {
+  float s = a[0] * b[0];
+#pragma unroll
+  for (int i = 1; i < 8; ++i) s = fmaf(a[i], b[i], s);
+  return s;
+}
+
+// ------------------------------------------- order-preserving float key --
+// a > b (as floats, -0 canonicalised to +0 by the caller)  <=>  key(a) > key(b)
+__device__ __forceinline__ uint32_t ordered_key(float f) {
+  uint32_t u = __float_as_uint(f);
+  return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+constexpr uint32_t kKeyLowestFinite = 0x00800000u;  // every finite float has a key >= this; key(-inf) is below
+
+// ------------------------------------------------- wave / block scans ----
+__device__ __forceinline__ int lane_id() { return threadIdx.x & 63; }
+__device__ __forceinline__ int wave_id() { return threadIdx.x >> 6; }
+
+template <typename T>
+__device__ __forceinline__ T wave_incl_scan(T v) {
+  const int lane = lane_id();
+#pragma unroll
+  for (int d = 1; d < 64; d <<= 1) {
+    T o = __shfl_up(v, d, 64);
+    if (lane >= d) v += o;
+  }
+  return v;
+}
+
+template <typename T>
+__device__ __forceinline__ T wave_sum(T v) {
+#pragma unroll
+  for (int d = 32; d >= 1; d >>= 1) v += __shfl_xor(v, d, 64);
+  return v;
+}
+
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+  for (int d = 32; d >= 1; d >>= 1) v = fmaxf(v, __shfl_xor(v, d, 64));
+  return v;
+}
+
+// Exclusive scan over the block (blockDim.x = 64*NW threads, thread order).
+// `total` receives the block sum.  scratch: NW + 1 elements of LDS.  Contains
+// two barriers; scratch may be reused after the call returns.
+template <typename T, int NW>
+__device__ __forceinline__ T block_excl_scan(T v, T *scratch, T &total) {
+  T incl = wave_incl_scan(v);
+  if (lane_id() == 63) scratch[wave_id()] = incl;
+  __syncthreads();
+  T base = 0, tot = 0;
+#pragma unroll
+  for (int w = 0; w < NW; ++w) {
+    T s = scratch[w];
+    if (w < wave_id()) base += s;
+    tot += s;
+  }
+  __syncthreads();
+  total = tot;
+  return base + incl - v;
+}
+
+template <typename T, int NW>
+__device__ __forceinline__ T block_sum(T v, T *scratch) {
+  v = wave_sum(v);
+  if (lane_id() == 0) scratch[wave_id()] = v;
+  __syncthreads();
+  T tot = 0;
+#pragma unroll
+  for (int w = 0; w < NW; ++w) tot += scratch[w];
+  __syncthreads();
+  return tot;
+}
+
+template <int NW>
+__device__ __forceinline__ float block_max(float v, float *scratch) {
+  v = wave_max(v);
+  if (lane_id() == 0) scratch[wave_id()] = v;
+  __syncthreads();
+  float m = scratch[0];
+#pragma unroll
+  for (int w = 1; w < NW; ++w) m = fmaxf(m, scratch[w]);
+  __syncthreads();
+  return m;
+}
+
+}  // namespace dp

@@ -1,0 +1,56 @@
+// Host-side launch interface between the C ABI (dp_api.hip) and the kernels.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace dp {
+
+constexpr int kHeadDim = 128;  // the only supported head dimension
+
+// rows of one stage-3 work chunk; split boundaries are multiples of it
+constexpr int kChunkRows = 64;
+
+struct CacheView {
+  int32_t batch, n_kv_heads, n_q_heads, group;  // group = n_q_heads / n_kv_heads
+  const void *q, *k_cache, *v_cache, *k_centroids, *v_centroids;
+  const int64_t *seg_row_base;
+  const int32_t *seg_cluster_ptr, *cluster_offsets, *cluster_sizes;
+  int32_t max_clusters_per_seg, max_rows_per_seg;
+  float sm_scale;
+};
+
+// Per-head stage-2 -> stage-3 plan, all int32, head-major:
+//   ent_src  [nh, max_k]      exact entry: first row of the cluster relative to the segment;
+//                             approximated entry: segment-local cluster id
+//   row_start[nh, max_k + 1]  exclusive prefix of rows over the entry list
+//                             (an exact cluster has s_i rows, an approximated one has 1)
+//   chunk_entry[nh, chunk_stride]  entry that holds row q*kChunkRows
+//   head_rows[nh]             total rows of the head
+struct Plan {
+  int32_t *ent_src, *row_start, *chunk_entry, *head_rows;
+  int32_t chunk_stride;
+};
+
+struct SelectOut {
+  int32_t *sel_ids;  // [nh, max_k]
+  int32_t *n_exact, *n_retained, *n_exact_tokens;  // [nh]
+};
+
+hipError_t launch_score(const CacheView &c, float *logits, hipStream_t s);
+
+// plan.ent_src == nullptr => no plan is written
+hipError_t launch_select(const CacheView &c, const float *logits, float p1, float p2, uint32_t flags,
+                         const SelectOut &out, const Plan &plan, hipStream_t s);
+
+// builds the plan from caller-given sets
+hipError_t launch_plan(const CacheView &c, const int32_t *sel_ids, const int32_t *n_exact,
+                       const int32_t *n_retained, int32_t *n_exact_tokens, const Plan &plan, hipStream_t s);
+
+hipError_t launch_decode(const CacheView &c, const int32_t *n_exact, const int32_t *n_retained, const Plan &plan,
+                         float *partials, int splits, void *out, int out_is_bf16, float *lse, hipStream_t s);
+
+// largest max_clusters_per_seg the selection kernel supports
+constexpr int kSelectMaxClusters = 65536;
+
+}  // namespace dp

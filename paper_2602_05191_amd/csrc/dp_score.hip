@@ -1,0 +1,117 @@
+// Stage 1: size-weighted centroid scoring (paper Sec. 4.2, Eq. 3 and Eq. 5):
+//   logit[h][i] = sm_scale * (q_h . C_i) + ln s_i
+// for every cluster i of a KV segment and every query head h of its GQA group.
+//
+// HBM-bound streaming kernel: the key-centroid matrix is read exactly once
+// (256 B per cluster) and each row is scored against all G query heads of the
+// group from registers.  A 16-lane DPP row owns one centroid row (16 B per
+// lane, global_load_dwordx4); the 16 partial dots are summed with DPP adds.
+// Algorithmic traffic per cluster: 256 B centroid + 4 B size read, 4*G B written.
+#include "dp_device.hpp"
+#include "dp_kernels.hpp"
+
+namespace dp {
+namespace {
+
+constexpr int kScoreThreads = 256;                   // 16 DPP rows
+constexpr int kScoreRowsPerGroup = 4;                // centroid rows in flight per 16-lane row
+constexpr int kScoreTile = (kScoreThreads / 16) * kScoreRowsPerGroup;  // 64 clusters per workgroup
+
+struct ScoreArgs {
+  const void *q, *k_centroids;
+  const int32_t *seg_cluster_ptr, *cluster_sizes;
+  float *logits;
+  int32_t n_kv_heads, n_q_heads, group;
+  int32_t head0, heads;  // this launch scores heads [head0, head0 + heads) of each group
+  float sm_scale;
+};
+
+template <int GH>
+__global__ __launch_bounds__(kScoreThreads) void score_kernel(ScoreArgs a) {
+  const int seg = blockIdx.y;
+  const int c0 = a.seg_cluster_ptr[seg];
+  const int kc = a.seg_cluster_ptr[seg + 1] - c0;
+  const int tile0 = blockIdx.x * kScoreTile;
+  if (tile0 >= kc) return;
+
+  const int lane16 = threadIdx.x & 15;
+  const int grp = threadIdx.x >> 4;
+  const int b = seg / a.n_kv_heads, g = seg % a.n_kv_heads;
+
+  // issue the centroid loads first: rows tile0 + grp + 16*k
+  uint4 raw[kScoreRowsPerGroup];
+  int size[kScoreRowsPerGroup];
+#pragma unroll
+  for (int k = 0; k < kScoreRowsPerGroup; ++k) {
+    const int i = tile0 + grp + 16 * k;
+    if (i < kc) {
+      raw[k] = load_row_slice(a.k_centroids, (int64_t)(c0 + i), lane16);
+      size[k] = a.cluster_sizes[c0 + i];
+    } else {
+      raw[k] = make_uint4(0, 0, 0, 0);
+      size[k] = 0;
+    }
+  }
+
+  // the group's query slices, fp32 in registers
+  float qf[GH][8];
+#pragma unroll
+  for (int j = 0; j < GH; ++j) {
+    const int h = g * a.group + a.head0 + j;
+    unpack8(load_row_slice(a.q, (int64_t)b * a.n_q_heads + h, lane16), qf[j]);
+  }
+
+  float *out = a.logits + (int64_t)a.group * c0 + (int64_t)a.head0 * kc;
+#pragma unroll
+  for (int k = 0; k < kScoreRowsPerGroup; ++k) {
+    const int i = tile0 + grp + 16 * k;
+    float cf[8];
+    unpack8(raw[k], cf);
+    float mine = 0.f;
+#pragma unroll
+    for (int j = 0; j < GH; ++j) {
+      float d = row16_sum(dot8(qf[j], cf));
+      if (lane16 == j) mine = d;
+    }
+    if (i < kc && lane16 < GH) {
+      const int s = size[k];
+      const float v = (s > 0) ? fmaf(mine, a.sm_scale, logf((float)s)) : -INFINITY;
+      out[(int64_t)lane16 * kc + i] = v;
+    }
+  }
+}
+
+}  // namespace
+
+hipError_t launch_score(const CacheView &c, float *logits, hipStream_t s) {
+  ScoreArgs a;
+  a.q = c.q;
+  a.k_centroids = c.k_centroids;
+  a.seg_cluster_ptr = c.seg_cluster_ptr;
+  a.cluster_sizes = c.cluster_sizes;
+  a.logits = logits;
+  a.n_kv_heads = c.n_kv_heads;
+  a.n_q_heads = c.n_q_heads;
+  a.group = c.group;
+  a.sm_scale = c.sm_scale;
+  const dim3 grid((c.max_clusters_per_seg + kScoreTile - 1) / kScoreTile, c.batch * c.n_kv_heads);
+  if (grid.x == 0 || grid.y == 0) return hipSuccess;
+  // heads of a group are scored 8/4/2/1 at a time (one pass when G is 1, 2, 4 or 8)
+  int h0 = 0;
+  while (h0 < c.group) {
+    const int left = c.group - h0;
+    const int gh = left >= 8 ? 8 : left >= 4 ? 4 : left >= 2 ? 2 : 1;
+    a.head0 = h0;
+    a.heads = gh;
+    switch (gh) {
+      case 8: hipLaunchKernelGGL(score_kernel<8>, grid, dim3(kScoreThreads), 0, s, a); break;
+      case 4: hipLaunchKernelGGL(score_kernel<4>, grid, dim3(kScoreThreads), 0, s, a); break;
+      case 2: hipLaunchKernelGGL(score_kernel<2>, grid, dim3(kScoreThreads), 0, s, a); break;
+      default: hipLaunchKernelGGL(score_kernel<1>, grid, dim3(kScoreThreads), 0, s, a); break;
+    }
+    h0 += gh;
+  }
+  return hipGetLastError();
+}
+
+}  // namespace dp

@@ -1,0 +1,291 @@
+"""GPU parity: the HIP path (through the C ABI binding) against the fp64 CPU
+oracle on the same seeded inputs.  Every test here needs a real MI355X."""
+import math
+
+import numpy as np
+import pytest
+
+import oracle
+from workloads import ClusteredCache, bf16_bits_to_f32, f32_to_bf16_bits, make_cache, make_config
+
+import harness as H
+
+pytestmark = pytest.mark.gpu
+
+
+# ---------------------------------------------------------------------------
+# cases: small enough for the oracle to finish in seconds, several tiles + ragged tails
+# ---------------------------------------------------------------------------
+def case_cfg0():
+    return make_config(0), 0.95, 0.9
+
+
+def case_flat_ragged():
+    # ragged batch, flat heads: hundreds of clusters retained, Kc (187 / 111) not a multiple of any tile
+    c = make_cache(batch=2, n_kv_heads=2, n_q_heads=8, context=[3000, 1777], mean_cluster=16, q_scale=0.35, seed=11)
+    return c, 0.95, 0.9
+
+
+def case_mixed_sharpness():
+    c = make_cache(batch=1, n_kv_heads=4, n_q_heads=16, context=8192, mean_cluster=16,
+                   q_scale=lambda rng, b, h: [0.2, 0.5, 1.0, 3.0][h % 4], seed=12)
+    return c, 0.95, 0.9
+
+
+def case_gqa8_pareto():
+    c = make_cache(batch=1, n_kv_heads=2, n_q_heads=16, context=16384, mean_cluster=16, size_dist="pareto",
+                   size_lo=1, size_hi=512, q_scale=lambda rng, b, h: 0.5 if h % 2 == 0 else 5.0, seed=13)
+    return c, 0.95, 0.9
+
+
+def case_gqa1():
+    return make_cache(batch=3, n_kv_heads=2, n_q_heads=2, context=[640, 1024, 333], mean_cluster=8, size_hi=32,
+                      q_scale=0.5, seed=14), 0.9, 0.7
+
+
+def case_gqa3_and_12():
+    return make_cache(batch=1, n_kv_heads=1, n_q_heads=3, context=2000, mean_cluster=10, size_hi=40, q_scale=0.6,
+                      seed=15), 0.98, 0.95
+
+
+def case_gqa12():
+    return make_cache(batch=1, n_kv_heads=1, n_q_heads=12, context=1500, mean_cluster=10, size_hi=40, q_scale=0.6,
+                      seed=16), 0.95, 0.8
+
+
+def case_many_clusters():
+    # 9000 clusters per segment: the selection kernel's 16-logits-per-thread variant
+    return make_cache(batch=1, n_kv_heads=1, n_q_heads=4, context=27000, mean_cluster=3, size_hi=8, q_scale=0.3,
+                      seed=17), 0.95, 0.9
+
+
+def case_single_cluster():
+    return make_cache(batch=1, n_kv_heads=1, n_q_heads=4, context=37, n_clusters=1, size_lo=1, size_hi=64,
+                      q_scale=1.0, seed=18), 0.95, 0.9
+
+
+def case_giant_cluster():
+    c = make_cache(batch=1, n_kv_heads=1, n_q_heads=4, context=1200, n_clusters=8, size_lo=1, size_hi=2000,
+                   size_dist="pareto", mean_cluster=150, q_scale=0.2, seed=19)
+    return c, 0.99, 0.9
+
+
+def case_empty_clusters_and_segment():
+    c = make_cache(batch=2, n_kv_heads=2, n_q_heads=4, context=[512, 256], mean_cluster=8, size_hi=32, q_scale=0.4,
+                   seed=20)
+    c.cluster_sizes[[1, 5, 17]] = 0
+    a, e = int(c.seg_cluster_ptr[3]), int(c.seg_cluster_ptr[4])
+    c.cluster_sizes[a:e] = 0          # a whole segment with nothing to attend to
+    return c, 0.95, 0.9
+
+
+CASES = {f.__name__[5:]: f for f in (case_cfg0, case_flat_ragged, case_mixed_sharpness, case_gqa8_pareto, case_gqa1,
+                                     case_gqa3_and_12, case_gqa12, case_many_clusters, case_single_cluster,
+                                     case_giant_cluster, case_empty_clusters_and_segment)}
+
+
+@pytest.fixture(scope="module", params=sorted(CASES))
+def case(request):
+    cache, p1, p2 = CASES[request.param]()
+    return request.param, cache, p1, p2, oracle.Oracle(cache)
+
+
+# ---------------------------------------------------------------------------
+# stage 1
+# ---------------------------------------------------------------------------
+def test_score_centroids_matches_oracle(case):
+    name, cache, p1, p2, orc = case
+    per_head, _ = H.gpu_logits(cache)
+    worst = 0.0
+    for b in range(cache.batch):
+        for h in range(cache.n_q_heads):
+            ref = orc.centroid_logits(b, h)
+            got = per_head[b * cache.n_q_heads + h].astype(np.float64)
+            assert got.shape == ref.shape
+            empty = np.isneginf(ref)
+            assert np.array_equal(np.isneginf(got), empty)
+            if (~empty).any():
+                # fp32 accumulation of exact bf16 products: a few ulp of the largest partial sum
+                tol = 4e-6 * max(1.0, np.abs(ref[~empty]).max()) + 2e-6
+                err = np.abs(got[~empty] - ref[~empty]).max()
+                worst = max(worst, err / tol)
+                assert err <= tol, (name, b, h, err, tol)
+    print(f"[{name}] logits worst err/tol = {worst:.3f}")
+
+
+# ---------------------------------------------------------------------------
+# stage 2 from the GPU's own fp32 logits: the decision is taken on identical numbers
+# ---------------------------------------------------------------------------
+@pytest.mark.parametrize("flags", [0, 1])
+def test_topp_select_matches_oracle_on_same_logits(case, flags):
+    name, cache, p1, p2, orc = case
+    per_head, flat = H.gpu_logits(cache)
+    for (q1, q2) in ((p1, p2), (0.5, 0.5), (1.0, 1.0), (0.9, 0.0), (1.0, 0.6)):
+        exact, approx, ntok = H.gpu_select(cache, flat, q1, q2, flags)
+        n_tol = 0
+        for i in range(cache.batch * cache.n_q_heads):
+            lg = per_head[i].astype(np.float64)
+            s = orc.select(lg, q1, q2, flags)
+            got_ret = np.sort(np.concatenate([exact[i], approx[i]]))
+            same = np.array_equal(got_ret, s.retained) and np.array_equal(exact[i], s.exact)
+            if not same:
+                ok1, _ = H.prefix_set_ok(got_ret.astype(np.int64), s.retained.astype(np.int64), s.a_hat, lg,
+                                         q1 if q1 < 1 else 2.0)
+                assert ok1 and q1 < 1.0, (name, i, q1, q2, got_ret[:10], s.retained[:10])
+                n_tol += 1
+        assert n_tol <= 1, (name, q1, q2, n_tol)
+
+
+# ---------------------------------------------------------------------------
+# stage 3 on the oracle's sets
+# ---------------------------------------------------------------------------
+def test_sparse_decode_matches_oracle_on_oracle_sets(case):
+    name, cache, p1, p2, orc = case
+    r = orc.decode_step(p1, p2)
+    nh = cache.batch * cache.n_q_heads
+    exact = [np.sort(r.order[i, : r.k2.flat[i]]) for i in range(nh)]
+    approx = [np.sort(r.order[i, r.k2.flat[i]: r.k1.flat[i]]) for i in range(nh)]
+    out, lse = H.gpu_sparse_decode(cache, exact, approx)
+    g = H.GpuStep(out=out, lse=lse, exact=exact, approx=approx, n_exact_tokens=np.zeros(nh))
+    worst, rel = H.check_outputs(cache, orc, g, tight=2e-4)
+    np.testing.assert_allclose(out, r.out, atol=H.OUT_MAX_ABS)
+    print(f"[{name}] sparse_decode max-abs {worst:.2e} rel-L2 {rel:.2e}")
+    # bf16 output = the fp32 output rounded to nearest even
+    out16, _ = H.gpu_sparse_decode(cache, exact, approx, out_bf16=True)
+    np.testing.assert_array_equal(f32_to_bf16_bits(out16), f32_to_bf16_bits(out))
+
+
+# ---------------------------------------------------------------------------
+# the one-call path
+# ---------------------------------------------------------------------------
+@pytest.mark.parametrize("pp", ["case", (0.5, 0.5), (1.0, 1.0), (0.9, 0.0), (0.99, 1.0)])
+def test_decode_attention_matches_oracle(case, pp):
+    name, cache, p1, p2, orc = case
+    if pp != "case":
+        p1, p2 = pp
+    g = H.gpu_decode_attention(cache, p1, p2)
+    tolerated = H.check_sets(cache, orc, g, p1, p2)
+    worst, rel = H.check_outputs(cache, orc, g, tight=2e-4)
+    nh = cache.batch * cache.n_q_heads
+    assert tolerated <= max(1, nh // 50), f"{tolerated} of {nh} heads differ from the oracle's sets"
+    if tolerated == 0:
+        r = orc.decode_step(p1, p2)
+        np.testing.assert_allclose(g.out, r.out, atol=H.OUT_MAX_ABS)
+    print(f"[{name} p=({p1},{p2})] sets exact on {nh - tolerated}/{nh} heads, out max-abs {worst:.2e} rel-L2 {rel:.2e}")
+
+
+def test_decode_attention_is_bitwise_reproducible(case):
+    name, cache, p1, p2, orc = case
+    a = H.gpu_decode_attention(cache, p1, p2)
+    b = H.gpu_decode_attention(cache, p1, p2)
+    assert np.array_equal(a.out.view(np.uint32), b.out.view(np.uint32))
+    assert np.array_equal(a.lse.view(np.uint32), b.lse.view(np.uint32))
+    for x, y in zip(a.exact + a.approx, b.exact + b.approx):
+        assert np.array_equal(x, y)
+
+
+def test_dense_limit_on_gpu():
+    c = make_cache(batch=1, n_kv_heads=2, n_q_heads=8, context=4096, mean_cluster=16, q_scale=0.5, seed=31)
+    orc = oracle.Oracle(c)
+    g = H.gpu_decode_attention(c, 1.0, 1.0)
+    dense, dense_lse, _ = orc.dense_step()
+    np.testing.assert_allclose(g.out, dense, atol=2e-4)
+    np.testing.assert_allclose(g.lse, dense_lse, atol=1e-3)
+    for i in range(8):
+        assert len(g.approx[i]) == 0 and len(g.exact[i]) == 256
+
+
+def test_hand_worked_case_on_gpu():
+    """The three-cluster example of tests/golden/hand_worked_case.json, zero-padded to head_dim 128."""
+    d = 128
+    def row(x):
+        r = np.zeros(d, np.float32)
+        r[: len(x)] = x
+        return r
+    keys = np.stack([row(k) for k in ([3, 0], [1, 0], [1, 0], [0, 0], [0, 0], [0, 0], [0, 0])])
+    vals = np.stack([row(v) for v in ([1, 0], [0, 1], [2, 2], [4, 0], [0, 4], [4, 4], [0, 0])])
+    kc = np.stack([row(k) for k in ([2, 0], [1, 0], [0, 0])])
+    vc = np.stack([row(v) for v in ([.5, .5], [2, 2], [2, 2])])
+    c = ClusteredCache(batch=1, n_kv_heads=1, n_q_heads=1, head_dim=d, q=f32_to_bf16_bits(row([1, 0]).reshape(1, 1, d)),
+                       k_cache=f32_to_bf16_bits(keys), v_cache=f32_to_bf16_bits(vals),
+                       seg_row_base=np.zeros(1, np.int64), seg_cluster_ptr=np.array([0, 3], np.int32),
+                       cluster_offsets=np.array([0, 2, 3], np.int32), cluster_sizes=np.array([2, 1, 4], np.int32),
+                       k_centroids=f32_to_bf16_bits(kc), v_centroids=f32_to_bf16_bits(vc))
+    g = H.gpu_decode_attention(c, 0.8, 0.5, sm_scale=math.log(2.0))
+    assert g.exact[0].tolist() == [0] and g.approx[0].tolist() == [2]
+    np.testing.assert_allclose(g.out[0, 0, :2], [8 / 7, 5 / 7], rtol=1e-6)
+    assert g.lse[0, 0] == pytest.approx(math.log(14.0), rel=1e-6)
+    ga = H.gpu_decode_attention(c, 0.8, 0.6, flags=1, sm_scale=math.log(2.0))
+    assert ga.exact[0].tolist() == [0, 2] and ga.approx[0].tolist() == []
+    g0 = H.gpu_decode_attention(c, 0.8, 0.0, sm_scale=math.log(2.0))
+    np.testing.assert_allclose(g0.out[0, 0, :2], [1.0, 1.0], rtol=1e-6)
+
+
+# ---------------------------------------------------------------------------
+# ties: equal scores are cut in cluster-index order
+# ---------------------------------------------------------------------------
+@pytest.mark.parametrize("n,p1,p2", [(2000, 0.5, 0.5), (2000, 0.3001, 1.0), (700, 0.9, 0.1), (5000, 0.77, 0.33)])
+def test_all_equal_scores_are_cut_by_index(n, p1, p2):
+    c = make_cache(batch=1, n_kv_heads=1, n_q_heads=2, context=n, n_clusters=n, size_dist="ones", size_lo=1,
+                   size_hi=1, q_scale=0.5, seed=40)
+    c.k_centroids[:] = c.k_centroids[0]          # every cluster gets the same score
+    orc = oracle.Oracle(c)
+    g = H.gpu_decode_attention(c, p1, p2)
+    for i in range(2):
+        s = orc.select(orc.centroid_logits(0, i), p1, p2)
+        k1 = len(g.exact[i]) + len(g.approx[i])
+        # all masses are equal: the cut may move by one element when p*n is within rounding of an integer
+        assert abs(k1 - s.k1) <= 1 and abs(len(g.exact[i]) - s.k2) <= 1, (k1, s.k1, len(g.exact[i]), s.k2)
+        assert np.array_equal(np.sort(np.concatenate([g.exact[i], g.approx[i]])), np.arange(k1))
+        assert np.array_equal(g.exact[i], np.arange(len(g.exact[i])))
+    H.check_outputs(c, orc, g, tight=2e-4)
+
+
+def test_partial_ties_at_the_threshold():
+    c = make_cache(batch=1, n_kv_heads=1, n_q_heads=4, context=1500, n_clusters=1500, size_dist="ones", size_lo=1,
+                   size_hi=1, q_scale=0.3, seed=41)
+    # blocks of identical centroids: many equal scores, some of them straddling the threshold
+    for start in range(0, 1500, 50):
+        c.k_centroids[start:start + 37] = c.k_centroids[start]
+    orc = oracle.Oracle(c)
+    for p1, p2 in ((0.5, 0.5), (0.9, 0.8), (0.97, 0.2)):
+        g = H.gpu_decode_attention(c, p1, p2)
+        assert H.check_sets(c, orc, g, p1, p2) <= 1
+        H.check_outputs(c, orc, g, tight=2e-4)
+
+
+# ---------------------------------------------------------------------------
+# error paths of the boundary (host-side checks; nothing is launched)
+# ---------------------------------------------------------------------------
+def test_boundary_rejects_bad_arguments():
+    import torch
+    import paper_2602_05191_amd as dp
+    c = make_config(0, shrink=4)
+    dc = dp.DeviceCache.from_host(c)
+    pr = dp.Problem(dc)
+    nh = c.batch * c.n_q_heads
+    ws = torch.empty(dp.dp_workspace_bytes(pr), dtype=torch.uint8, device="cuda:0")
+    out = torch.empty((1, 4, 128), dtype=torch.float32, device="cuda:0")
+    for p1, p2 in ((0.0, 0.5), (1.5, 0.5), (0.9, -0.1), (0.9, 1.1), (float("nan"), 0.5)):
+        with pytest.raises(dp.DPError) as e:
+            dp.dp_decode_attention(pr, p1, p2, out, None, ws)
+        assert e.value.status == -1
+    with pytest.raises(dp.DPError) as e:
+        dp.dp_decode_attention(pr, 0.9, 0.5, out, None, ws[:1024])
+    assert e.value.status == -3
+    bad = dp.Problem(dc)
+    bad.c.head_dim = 64
+    with pytest.raises(dp.DPError) as e:
+        dp.dp_decode_attention(bad, 0.9, 0.5, out, None, ws)
+    assert e.value.status == -2
+    bad = dp.Problem(dc)
+    bad.c.n_q_heads = 3
+    with pytest.raises(dp.DPError) as e:
+        dp.dp_decode_attention(bad, 0.9, 0.5, out, None, ws)
+    assert e.value.status == -1
+    bad = dp.Problem(dc)
+    bad.c.k_centroids = None
+    with pytest.raises(dp.DPError) as e:
+        dp.dp_score_centroids(bad, torch.empty(4 * 64, dtype=torch.float32, device="cuda:0"))
+    assert e.value.status == -1
+    torch.cuda.synchronize()
