@@ -1,0 +1,257 @@
+#!/usr/bin/env python3
+"""Benchmark of the Double-P decode step on one MI355X.
+
+A "step" is one call of dp_decode_attention: one layer's hierarchical top-p
+sparse attention for one decode token (centroid scoring, both top-p selections,
+sparse decode, split combine) over a synthetic clustered KV cache that is
+already resident in HBM.  Successive steps run on DIFFERENT replicas of the
+layer's buffers (distinct device addresses, like the layers of a model), enough
+of them that neither L2 nor the 256 MB Infinity Cache can hold what a step
+reads; all steps are enqueued back-to-back on one stream.
+
+Prints ONE JSON line:  metric/value = microseconds per decode step per layer,
+plus `roofline` (the kernel that moves the bytes, against the 8 TB/s HBM peak)
+and `cpu_baseline` (the fp64 CPU oracle timed on the host cores of this machine).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import math
+import os
+import statistics
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+CACHE_BYTES = 256e6 + 32e6          # Infinity Cache + 8 x 4 MB L2
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=3600)
+    ap.add_argument("--warmup", type=int, default=360)
+    ap.add_argument("--config", type=int, default=2, help="workload index 0..4 (default: 8B shape, 128k context)")
+    ap.add_argument("--replicas", type=int, default=0, help="layer replicas to rotate over (0 = auto)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-seconds", type=float, default=10.0, help="CPU time budget of the oracle baseline")
+    return ap.parse_args()
+
+
+def algorithmic_bytes(cache, sel, n_exact, n_retained):
+    """HBM bytes one step must move: key centroids + sizes once per KV segment, K+V rows of every
+    selected token and the two centroid rows of every approximated cluster (each counted once per KV
+    segment: the union over the query heads that share it), q in and o out."""
+    import numpy as np
+    d2 = 2 * cache.head_dim
+    G = cache.group
+    total_k = int(cache.seg_cluster_ptr[-1])
+    scan = total_k * (d2 + 4)
+    rows_union = rows_sum = 0
+    for b in range(cache.batch):
+        for g in range(cache.n_kv_heads):
+            seg = b * cache.n_kv_heads + g
+            c0 = int(cache.seg_cluster_ptr[seg])
+            ex_u, ap_u = set(), set()
+            for j in range(G):
+                i = b * cache.n_q_heads + g * G + j
+                ex = sel[i, : n_exact[i]]
+                ap = sel[i, n_exact[i]: n_retained[i]]
+                rows_sum += int(cache.cluster_sizes[c0 + ex].sum()) + len(ap)
+                ex_u.update(ex.tolist())
+                ap_u.update(ap.tolist())
+            ap_u -= ex_u
+            rows_union += int(cache.cluster_sizes[c0 + np.fromiter(ex_u, dtype=np.int64, count=len(ex_u))].sum()) \
+                + len(ap_u)
+    io = cache.batch * cache.n_q_heads * cache.head_dim * (2 + 4)
+    return dict(scan=scan, rows_union=rows_union, rows_sum=rows_sum, total=scan + rows_union * 2 * d2 + io,
+                total_per_head_sum=scan + rows_sum * 2 * d2 + io)
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (no collectives, no sharding); rerun with --gpus 1. "
+              "value is the one GPU's throughput.", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    import paper_2602_05191_amd as dp
+    from workloads import CONFIGS, make_config
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    dev = "cuda:0"
+    t0 = time.time()
+    cache = make_config(args.config)
+    t_gen = time.time() - t0
+    p1, p2 = cache.p1, cache.p2
+    nh = cache.batch * cache.n_q_heads
+    mk = cache.max_clusters_per_seg
+
+    base = dp.DeviceCache.from_host(cache, dev)
+    pr0 = dp.Problem(base)
+    ws_bytes = dp.dp_workspace_bytes(pr0)
+    ws = torch.zeros(ws_bytes, dtype=torch.uint8, device=dev)
+    out = torch.empty((cache.batch, cache.n_q_heads, cache.head_dim), dtype=torch.float32, device=dev)
+    lse = torch.empty(nh, dtype=torch.float32, device=dev)
+    ne = torch.empty(nh, dtype=torch.int32, device=dev)
+    nr, nt = torch.empty_like(ne), torch.empty_like(ne)
+
+    # one step to learn what the method touches on this input
+    dp.dp_decode_attention(pr0, p1, p2, out, lse, ws, ne, nr, nt)
+    torch.cuda.synchronize()
+    lay = dp.dp_workspace_layout(pr0)
+    sel = ws[lay["sel_ids"]: lay["sel_ids"] + 4 * nh * mk].cpu().numpy().view(np.int32).reshape(nh, mk)
+    ne_h, nr_h, nt_h = ne.cpu().numpy(), nr.cpu().numpy(), nt.cpu().numpy()
+    alg = algorithmic_bytes(cache, sel, ne_h, nr_h)
+
+    # replicas at distinct addresses: twice the on-chip cache capacity worth of touched bytes
+    L = args.replicas or int(min(64, max(2, math.ceil(2 * CACHE_BYTES / max(alg["total"], 1)))))
+    free, _ = torch.cuda.mem_get_info()
+    per_replica = sum(t.numel() * t.element_size() for t in base.__dict__.values() if isinstance(t, torch.Tensor))
+    L = int(max(1, min(L, (free * 0.8) // max(per_replica, 1))))
+    reps = [base] + [base.clone() for _ in range(L - 1)]
+    probs = [dp.Problem(r) for r in reps]
+    torch.cuda.synchronize()
+
+    def step(i):
+        dp.dp_decode_attention(probs[i % L], p1, p2, out, lse, ws, None, None, None)
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    w0 = time.perf_counter()
+    ev0.record()
+    for i in range(args.steps):
+        step(i)
+    ev1.record()
+    torch.cuda.synchronize()
+    w1 = time.perf_counter()
+    wall_us = (w1 - w0) * 1e6 / args.steps
+    event_us = ev0.elapsed_time(ev1) * 1e3 / args.steps
+
+    # same-layer repeat (everything cache-resident), labelled as such
+    torch.cuda.synchronize()
+    c0 = time.perf_counter()
+    for i in range(min(args.steps, 500)):
+        step(0)
+    torch.cuda.synchronize()
+    resident_us = (time.perf_counter() - c0) * 1e6 / min(args.steps, 500)
+
+    # ---- per-stage launch durations: each launch bracketed by its own pair of HIP events on the
+    # stream it is launched on (torch's current stream) -------------------------------------------
+    n_logits = cache.group * int(cache.seg_cluster_ptr[-1])
+    logits = torch.empty(n_logits, dtype=torch.float32, device=dev)
+    sel_d = torch.empty((nh, mk), dtype=torch.int32, device=dev)
+    n_stage = min(args.steps, 720)
+
+    def time_stage(fn):
+        pairs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n_stage)]
+        for i in range(min(50, n_stage)):
+            fn(i)
+        torch.cuda.synchronize()
+        for i, (a, b) in enumerate(pairs):
+            a.record()
+            fn(i)
+            b.record()
+        torch.cuda.synchronize()
+        ts = [a.elapsed_time(b) * 1e3 for a, b in pairs]
+        return statistics.mean(ts), statistics.median(ts)
+
+    score_us, score_med = time_stage(lambda i: dp.dp_score_centroids(probs[i % L], logits))
+    select_us, select_med = time_stage(lambda i: dp.dp_topp_select(probs[i % L], logits, p1, p2, sel_d, ne, nr, nt))
+    decode_us, decode_med = time_stage(lambda i: dp.dp_sparse_decode(probs[i % L], sel_d, ne, nr, out, lse, ws))
+
+    # the kernel that moves the bytes: centroid scoring reads every key centroid and size once and
+    # writes G logits per cluster
+    total_k = int(cache.seg_cluster_ptr[-1])
+    score_bytes = total_k * (2 * cache.head_dim + 4 + 4 * cache.group)
+    score_gbs = score_bytes / (score_us * 1e-6) / 1e9
+
+    value = wall_us
+    step_gbs = alg["total"] / (value * 1e-6) / 1e9
+    result = {
+        "metric": "us_per_decode_step_per_layer",
+        "value": round(value, 3),
+        "unit": "us",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(value / 1e3, 6),
+        "higher_is_better": False,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "bf16",
+        "data": "synthetic",
+        "config": {
+            "workload": f"{CONFIGS[args.config]}: batch {cache.batch}, {cache.n_kv_heads} KV heads, "
+                        f"{cache.n_q_heads} query heads, head_dim {cache.head_dim}, context "
+                        f"{cache.meta['context'] if cache.batch > 1 else cache.meta['context'][0]}, "
+                        f"{mk} clusters per KV head, bf16 K/V with fp32 accumulation, p1 {p1}, p2 {p2}",
+            "entry_point": "dp_decode_attention",
+            "layer_replicas": L,
+            "out_dtype": "f32",
+        },
+        "tokens_of_context_per_s": round(cache.context_tokens / (value * 1e-6), 1),
+        "step": {
+            "event_us": round(event_us, 3),
+            "cache_resident_us": round(resident_us, 3),
+            "algorithmic_bytes": alg["total"],
+            "algorithmic_bytes_per_head_sum": alg["total_per_head_sum"],
+            "achieved_GBs": round(step_gbs, 1),
+            "frac_of_hbm_peak": round(step_gbs / HBM_PEAK_GBS, 4),
+            "retained_clusters_mean": float(nr_h.mean()),
+            "exact_clusters_mean": float(ne_h.mean()),
+            "exact_tokens_mean": float(nt_h.mean()),
+        },
+        "stages_us": {
+            "dp_score_centroids": round(score_us, 3), "dp_topp_select": round(select_us, 3),
+            "dp_sparse_decode": round(decode_us, 3),
+            "median": {"score": round(score_med, 3), "select": round(select_med, 3), "decode": round(decode_med, 3)},
+        },
+        "roofline": {
+            "kernel": "score_kernel (dp_score_centroids)",
+            "bound": "hbm",
+            "achieved": round(score_gbs, 1),
+            "peak": HBM_PEAK_GBS,
+            "unit": "GB/s",
+            "frac": round(score_gbs / HBM_PEAK_GBS, 4),
+            "traffic": None,
+            "bytes_per_launch": score_bytes,
+            "avg_launch_us": round(score_us, 3),
+        },
+        "gen_seconds": round(t_gen, 1),
+    }
+
+    if not args.no_cpu_baseline:
+        import oracle
+        orc = oracle.Oracle(cache)
+        threads = os.cpu_count() or 1
+        times = []
+        t_end = time.time() + args.cpu_seconds
+        while (len(times) < 3 or time.time() < t_end) and len(times) < 200:
+            a = time.perf_counter()
+            r = orc.decode_step(p1, p2, n_threads=threads, want_order=False)
+            times.append(time.perf_counter() - a)
+        result["cpu_baseline"] = {
+            "value": round(statistics.median(times) * 1e6, 1),
+            "unit": "us",
+            "cores": int(r.threads),
+            "kind": "oracle",
+            "sample": f"the whole {CONFIGS[args.config]} step (all {nh} heads), fp64 C oracle, OpenMP over heads, "
+                      f"median of {len(times)} repetitions",
+        }
+        err = float(np.abs(out.cpu().numpy() - r.out).max())
+        result["step"]["max_abs_err_vs_oracle"] = err
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

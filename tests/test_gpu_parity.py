@@ -279,7 +279,7 @@ def test_boundary_rejects_bad_arguments():
         dp.dp_decode_attention(bad, 0.9, 0.5, out, None, ws)
     assert e.value.status == -2
     bad = dp.Problem(dc)
-    bad.c.n_q_heads = 3
+    bad.c.n_kv_heads = 3                 # 4 query heads do not divide into 3 KV heads
     with pytest.raises(dp.DPError) as e:
         dp.dp_decode_attention(bad, 0.9, 0.5, out, None, ws)
     assert e.value.status == -1
