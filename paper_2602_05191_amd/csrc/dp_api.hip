@@ -47,6 +47,11 @@ dp::CacheView view_of(const dp_problem *p) {
   c.cluster_sizes = p->cluster_sizes;
   c.max_clusters_per_seg = p->max_clusters_per_seg;
   c.max_rows_per_seg = p->max_rows_per_seg;
+  // every segment holds <= max clusters and they sum to total: equality means all are full
+  const int64_t n_seg = (int64_t)p->batch * p->n_kv_heads;
+  c.uniform_kc = (p->max_clusters_per_seg > 0 && n_seg * p->max_clusters_per_seg == p->total_clusters)
+                     ? p->max_clusters_per_seg
+                     : 0;
   c.sm_scale = p->sm_scale != 0.0f ? p->sm_scale : 1.0f / sqrtf((float)p->head_dim);
   return c;
 }
@@ -78,8 +83,8 @@ void layout_of(const dp_problem *p, dp_workspace_layout *L) {
   off = align_up(off + sizeof(int32_t) * nh * (mk + 1), 256);
   L->chunk_entry = off;
   off = align_up(off + sizeof(int32_t) * nh * chunk_stride, 256);
-  L->counts = off;  // n_exact, n_retained, n_exact_tokens, head_rows : 4 x [nh]
-  off = align_up(off + sizeof(int32_t) * 4 * nh, 256);
+  L->counts = off;  // n_exact, n_retained, n_exact_tokens, head_rows, done : 5 x [nh]
+  off = align_up(off + sizeof(int32_t) * 5 * nh, 256);
   L->partials = off;
   off = align_up(off + sizeof(float) * nh * (size_t)splits * (dp::kHeadDim + 2), 256);
   L->total = off;
@@ -114,6 +119,7 @@ Workspace carve(const dp_problem *p, void *ws) {
   w.n_retained = counts + nh;
   w.n_exact_tokens = counts + 2 * nh;
   w.plan.head_rows = counts + 3 * nh;
+  w.plan.done = counts + 4 * nh;
   w.partials = reinterpret_cast<float *>(b + L.partials);
   w.splits = L.splits;
   return w;
@@ -168,8 +174,9 @@ dp_status dp_topp_select(const dp_problem *problem, const float *logits, float p
   if (!n_exact || !n_retained || !n_exact_tokens) return DP_ERR_INVALID_ARG;
   if (problem->max_clusters_per_seg > 0 && (!logits || !sel_ids)) return DP_ERR_INVALID_ARG;
   dp::SelectOut out{sel_ids, n_exact, n_retained, n_exact_tokens};
-  dp::Plan none{nullptr, nullptr, nullptr, nullptr, 0};
-  return dp::launch_select(view_of(problem), logits, p1, p2, problem->flags, out, none,
+  dp::Plan none{nullptr, nullptr, nullptr, nullptr, nullptr, 0};
+  dp::AttnOut nowhere{nullptr, nullptr, 0};
+  return dp::launch_select(view_of(problem), logits, p1, p2, problem->flags, out, none, nowhere,
                            static_cast<hipStream_t>(stream)) == hipSuccess
              ? DP_OK
              : DP_ERR_HIP;
@@ -189,9 +196,9 @@ dp_status dp_sparse_decode(const dp_problem *problem, const int32_t *sel_ids, co
   const dp::CacheView c = view_of(problem);
   const Workspace w = carve(problem, workspace);
   hipStream_t s = static_cast<hipStream_t>(stream);
-  if (dp::launch_plan(c, sel_ids, n_exact, n_retained, nullptr, w.plan, s) != hipSuccess) return DP_ERR_HIP;
-  if (dp::launch_decode(c, n_exact, n_retained, w.plan, w.partials, w.splits, out, out_dtype == DP_BF16, lse, s) !=
-      hipSuccess)
+  const dp::AttnOut attn{out, lse, out_dtype == DP_BF16};
+  if (dp::launch_plan(c, sel_ids, n_exact, n_retained, nullptr, w.plan, attn, s) != hipSuccess) return DP_ERR_HIP;
+  if (dp::launch_decode(c, n_exact, n_retained, w.plan, w.partials, w.splits, attn, s) != hipSuccess)
     return DP_ERR_HIP;
   return DP_OK;
 }
@@ -211,9 +218,9 @@ dp_status dp_decode_attention(const dp_problem *problem, float p1, float p2, voi
   hipStream_t s = static_cast<hipStream_t>(stream);
   if (dp::launch_score(c, w.logits, s) != hipSuccess) return DP_ERR_HIP;
   dp::SelectOut so{w.sel_ids, w.n_exact, w.n_retained, w.n_exact_tokens};
-  if (dp::launch_select(c, w.logits, p1, p2, problem->flags, so, w.plan, s) != hipSuccess) return DP_ERR_HIP;
-  if (dp::launch_decode(c, w.n_exact, w.n_retained, w.plan, w.partials, w.splits, out, out_dtype == DP_BF16, lse,
-                        s) != hipSuccess)
+  const dp::AttnOut attn{out, lse, out_dtype == DP_BF16};
+  if (dp::launch_select(c, w.logits, p1, p2, problem->flags, so, w.plan, attn, s) != hipSuccess) return DP_ERR_HIP;
+  if (dp::launch_decode(c, w.n_exact, w.n_retained, w.plan, w.partials, w.splits, attn, s) != hipSuccess)
     return DP_ERR_HIP;
   const size_t nh = (size_t)problem->batch * problem->n_q_heads;
   // optional count outputs: device-to-device copies on the same stream

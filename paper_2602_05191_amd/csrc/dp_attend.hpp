@@ -1,0 +1,172 @@
+// Weighted online-softmax attention over a head's row list (paper Eq. 8, Eq. 9),
+// shared by the split decode kernel and by the selection kernel's inline path
+// for heads with few rows.
+//
+// Row list of a head: entries j = 0 .. n_rt-1; entry j < n_ex is an exact
+// cluster (its s rows are consecutive K/V cache rows, additive weight 0),
+// entry j >= n_ex is an approximated cluster (ONE pseudo-row: key centroid,
+// mean value, additive weight log2 s).  row_start[j] is the exclusive prefix
+// of rows.  A 16-lane DPP row ("group") owns one cache row per load: lane t
+// holds dims [8t, 8t+8) of K for the dot product and of V for the accumulation.
+// All exponents are base 2 (the query is pre-scaled by sm_scale * log2 e).
+#pragma once
+
+#include "dp_device.hpp"
+
+namespace dp {
+
+constexpr int kAttendBatch = 4;  // cache rows in flight per group
+
+struct RowState {
+  float m, l, acc[8];
+};
+
+__device__ __forceinline__ void row_state_init(RowState &s) {
+  s.m = -INFINITY;
+  s.l = 0.f;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) s.acc[i] = 0.f;
+}
+
+struct RowSources {
+  const void *k_cache, *v_cache, *k_centroids, *v_centroids;
+  const int32_t *seg_sizes;  // cluster_sizes + c0 of the head's segment
+  int64_t seg_row0;          // first cache row of the segment
+  int64_t c0;                // first centroid row of the segment
+};
+
+// Attend rows [ra, rb) of the list.  s_start[0 .. n_ent] and s_src[0 .. n_ent)
+// are the staged row_start / ent_src of entries ent0 .. ent0+n_ent-1, which
+// cover [ra, rb) (s_start[0] <= ra).  Every lane of the group runs the same
+// entry walk (uniform inside the group), so nothing is exchanged between lanes
+// except the DPP sum of the dot product.
+__device__ __forceinline__ void attend_rows(RowState &st, const float (&qf)[8], const RowSources &src,
+                                            const int *s_start, const int *s_src, int n_ent, int ent0, int n_ex,
+                                            int ra, int rb, int lane16) {
+  if (ra >= rb) return;
+  // entry that holds row ra: largest k in [0, n_ent) with s_start[k] <= ra
+  int k = 0;
+  {
+    int hi = n_ent;
+    while (hi - k > 1) {
+      const int mid = (k + hi) >> 1;
+      if (s_start[mid] <= ra) k = mid; else hi = mid;
+    }
+  }
+  int next_start = s_start[k + 1];
+  for (int r = ra; r < rb; r += kAttendBatch) {
+    uint4 kraw[kAttendBatch], vraw[kAttendBatch];
+    int ssz[kAttendBatch];
+    bool valid[kAttendBatch], approx[kAttendBatch];
+#pragma unroll
+    for (int u = 0; u < kAttendBatch; ++u) {
+      const int row = r + u;
+      valid[u] = row < rb;
+      approx[u] = false;
+      ssz[u] = 1;
+      if (valid[u]) {
+        if (row >= next_start) {  // every entry has at least one row: advance by one
+          ++k;
+          next_start = s_start[k + 1];
+        }
+        const int s = s_src[k];
+        if (ent0 + k < n_ex) {
+          const int64_t g = src.seg_row0 + s + (row - s_start[k]);
+          kraw[u] = load_row_slice(src.k_cache, g, lane16);
+          vraw[u] = load_row_slice(src.v_cache, g, lane16);
+        } else {
+          approx[u] = true;
+          ssz[u] = src.seg_sizes[s];
+          kraw[u] = load_row_slice(src.k_centroids, src.c0 + s, lane16);
+          vraw[u] = load_row_slice(src.v_centroids, src.c0 + s, lane16);
+        }
+      } else {
+        kraw[u] = make_uint4(0, 0, 0, 0);
+        vraw[u] = make_uint4(0, 0, 0, 0);
+      }
+    }
+    float x[kAttendBatch];
+    float m_new = st.m;
+#pragma unroll
+    for (int u = 0; u < kAttendBatch; ++u) {
+      float kf[8];
+      unpack8(kraw[u], kf);
+      const float d = row16_sum(dot8(qf, kf));
+      x[u] = valid[u] ? (approx[u] ? d + log2f((float)ssz[u]) : d) : -INFINITY;
+      m_new = fmaxf(m_new, x[u]);
+    }
+    // m_new is finite here: row r is valid
+    const float alpha = exp2f(st.m - m_new);  // st.m = -inf gives 0
+    st.l *= alpha;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) st.acc[i] *= alpha;
+#pragma unroll
+    for (int u = 0; u < kAttendBatch; ++u) {
+      const float p = exp2f(x[u] - m_new);
+      float vf[8];
+      unpack8(vraw[u], vf);
+      st.l += p;
+#pragma unroll
+      for (int i = 0; i < 8; ++i) st.acc[i] = fmaf(p, vf[i], st.acc[i]);
+    }
+    st.m = m_new;
+  }
+}
+
+// Merge the 4 groups of a wave (log-sum-exp merge); every group ends with the wave's state.
+__device__ __forceinline__ void wave_merge(RowState &st) {
+#pragma unroll
+  for (int d = 16; d <= 32; d <<= 1) {
+    const float om = __shfl_xor(st.m, d, 64);
+    const float M = fmaxf(st.m, om);
+    const float wa = (st.m == -INFINITY) ? 0.f : exp2f(st.m - M);
+    const float wb = (om == -INFINITY) ? 0.f : exp2f(om - M);
+    st.l = st.l * wa + __shfl_xor(st.l, d, 64) * wb;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) st.acc[i] = st.acc[i] * wa + __shfl_xor(st.acc[i], d, 64) * wb;
+    st.m = M;
+  }
+}
+
+// Merge the waves of a workgroup through LDS.  s_m / s_l: NW floats, s_acc: NW x 128 floats.
+// Returns, for threads tid < 128: M, L and the unnormalised output of dim tid.
+template <int NW>
+__device__ __forceinline__ void block_merge(RowState &st, float *s_m, float *s_l, float (*s_acc)[kHeadDim],
+                                            float &M, float &L, float &o) {
+  wave_merge(st);
+  const int lane = lane_id(), w = wave_id();
+  if (lane < 16) {
+    if (lane == 0) {
+      s_m[w] = st.m;
+      s_l[w] = st.l;
+    }
+#pragma unroll
+    for (int i = 0; i < 8; ++i) s_acc[w][lane * 8 + i] = st.acc[i];
+  }
+  __syncthreads();
+  M = -INFINITY;
+  L = 0.f;
+  o = 0.f;
+  if (threadIdx.x < kHeadDim) {
+#pragma unroll
+    for (int g = 0; g < NW; ++g) M = fmaxf(M, s_m[g]);
+#pragma unroll
+    for (int g = 0; g < NW; ++g) {
+      const float wg = (s_m[g] == -INFINITY) ? 0.f : exp2f(s_m[g] - M);
+      L += s_l[g] * wg;
+      o += s_acc[g][threadIdx.x] * wg;
+    }
+  }
+}
+
+__device__ __forceinline__ void store_out(void *out, int out_is_bf16, int64_t head, int t, float v) {
+  if (out_is_bf16)
+    static_cast<uint16_t *>(out)[head * kHeadDim + t] = (uint16_t)f32_to_bf16_rne(v);
+  else
+    static_cast<float *>(out)[head * kHeadDim + t] = v;
+}
+
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kLn2 = 0.6931471805599453f;
+
+}  // namespace dp

@@ -14,9 +14,10 @@
 // Inside a workgroup (256 threads) each 16-lane DPP row owns one cache row per
 // load (lane t holds dims [8t, 8t+8) of K for the dot and of V for the
 // accumulation), keeps its own online-softmax state in base-2 exponent form,
-// and the 16 states are merged through LDS.  Partials (m, l, acc[128]) go to
-// the workspace; a second small kernel merges the splits (log-sum-exp merge),
-// normalises and writes the output.
+// and the states are merged through LDS.  Partials (m, l, acc[128]) go to the
+// workspace; the split of a head that finishes last (an arrival counter, no
+// waiting) merges them (log-sum-exp merge), normalises and writes the output.
+#include "dp_attend.hpp"
 #include "dp_device.hpp"
 #include "dp_kernels.hpp"
 
@@ -24,12 +25,10 @@ namespace dp {
 namespace {
 
 constexpr int kDecThreads = 256;
+constexpr int kDecWaves = kDecThreads / 64;
 constexpr int kDecGroups = kDecThreads / 16;   // 16 DPP rows per workgroup
-constexpr int kDecBatch = 4;                   // cache rows in flight per DPP row
-constexpr int kDecBlockRows = 256;             // rows resolved per LDS staging round
+constexpr int kDecBlockRows = 512;             // rows resolved per LDS staging round
 constexpr int kPartialStride = kHeadDim + 2;   // m, l, acc[128]
-constexpr float kLog2e = 1.4426950408889634f;
-constexpr float kLn2 = 0.6931471805599453f;
 
 struct DecodeArgs {
   const void *q, *k_cache, *v_cache, *k_centroids, *v_centroids;
@@ -38,7 +37,9 @@ struct DecodeArgs {
   const int32_t *n_exact, *n_retained;
   Plan plan;
   float *partials;
-  int32_t n_kv_heads, n_q_heads, group, max_k, splits;
+  void *out;
+  float *lse;  // nullable
+  int32_t n_kv_heads, n_q_heads, group, max_k, splits, out_is_bf16;
   float scale_log2;  // sm_scale * log2(e)
 };
 
@@ -50,21 +51,22 @@ __device__ __forceinline__ int rows_per_split(int R, int S) {
 __global__ __launch_bounds__(kDecThreads) void decode_kernel(DecodeArgs a) {
   __shared__ int s_start[kDecBlockRows + 1];
   __shared__ int s_src[kDecBlockRows + 1];
-  __shared__ float s_m[kDecGroups], s_l[kDecGroups];
-  __shared__ float s_acc[kDecGroups][kHeadDim];
+  __shared__ float s_m[kDecWaves], s_l[kDecWaves];
+  __shared__ float s_acc[kDecWaves][kHeadDim];
+  __shared__ int s_last;
 
   const int head = blockIdx.y, split = blockIdx.x;
   const int R = a.plan.head_rows[head];
-  if (R <= 0) return;
+  if (R <= 0) return;  // 0: no rows (output already written); -1: attended by the selection kernel
   const int c = rows_per_split(R, a.splits);
   const int row_a = split * c;
   if (row_a >= R) return;
   const int row_b = min(R, row_a + c);
+  const int n_active = (R + c - 1) / c;
 
   const int b = head / a.n_q_heads, h = head % a.n_q_heads;
   const int seg = b * a.n_kv_heads + h / a.group;
   const int c0 = a.seg_cluster_ptr[seg];
-  const int64_t seg_row0 = a.seg_row_base[seg];
   const int n_ex = a.n_exact[head], n_rt = a.n_retained[head];
   const int32_t *ent_src = a.plan.ent_src + (int64_t)head * a.max_k;
   const int32_t *row_start = a.plan.row_start + (int64_t)head * (a.max_k + 1);
@@ -75,10 +77,17 @@ __global__ __launch_bounds__(kDecThreads) void decode_kernel(DecodeArgs a) {
 #pragma unroll
   for (int i = 0; i < 8; ++i) qf[i] *= a.scale_log2;
 
-  // online-softmax state of this DPP row, exponents in base 2
-  float m_run = -INFINITY, l_run = 0.f, acc[8];
-#pragma unroll
-  for (int i = 0; i < 8; ++i) acc[i] = 0.f;
+  RowSources src;
+  src.k_cache = a.k_cache;
+  src.v_cache = a.v_cache;
+  src.k_centroids = a.k_centroids;
+  src.v_centroids = a.v_centroids;
+  src.seg_sizes = a.cluster_sizes + c0;
+  src.seg_row0 = a.seg_row_base[seg];
+  src.c0 = c0;
+
+  RowState st;
+  row_state_init(st);
 
   int ent0 = a.plan.chunk_entry[(int64_t)head * a.plan.chunk_stride + row_a / kChunkRows];
 
@@ -92,78 +101,10 @@ __global__ __launch_bounds__(kDecThreads) void decode_kernel(DecodeArgs a) {
       s_src[k] = (k < n_ent) ? ent_src[ent0 + k] : 0;
     }
     __syncthreads();
-
-    for (int rb = r0 + grp * kDecBatch; rb < r1; rb += kDecGroups * kDecBatch) {
-      // resolve rows rb .. rb+3 : lanes 0..3 of the DPP row search, then broadcast
-      int64_t my_row = -1;   // row index in k_cache/v_cache, or in the centroid matrices
-      int my_kind = 0;       // 0 invalid, 1 token, 2 centroid pseudo-token
-      float my_bias = 0.f;
-      if (lane16 < kDecBatch) {
-        const int r = rb + lane16;
-        if (r < r1) {
-          int lo = 0, hi = n_ent;  // largest k in [0, n_ent) with s_start[k] <= r
-          while (hi - lo > 1) {
-            const int mid = (lo + hi) >> 1;
-            if (s_start[mid] <= r) lo = mid; else hi = mid;
-          }
-          const int j = ent0 + lo;
-          if (j < n_ex) {
-            my_kind = 1;
-            my_row = seg_row0 + s_src[lo] + (r - s_start[lo]);
-          } else {
-            my_kind = 2;
-            my_row = (int64_t)c0 + s_src[lo];
-            my_bias = log2f((float)a.cluster_sizes[c0 + s_src[lo]]);
-          }
-        }
-      }
-      uint4 kraw[kDecBatch], vraw[kDecBatch];
-      float bias[kDecBatch];
-      int kind[kDecBatch];
-#pragma unroll
-      for (int k = 0; k < kDecBatch; ++k) {
-        const int src_lane = (tid & ~15) + k;
-        kind[k] = __shfl(my_kind, src_lane, 64);
-        const int64_t row = __shfl(my_row, src_lane, 64);
-        bias[k] = __shfl(my_bias, src_lane, 64);
-        if (kind[k] == 1) {
-          kraw[k] = load_row_slice(a.k_cache, row, lane16);
-          vraw[k] = load_row_slice(a.v_cache, row, lane16);
-        } else if (kind[k] == 2) {
-          kraw[k] = load_row_slice(a.k_centroids, row, lane16);
-          vraw[k] = load_row_slice(a.v_centroids, row, lane16);
-        } else {
-          kraw[k] = make_uint4(0, 0, 0, 0);
-          vraw[k] = make_uint4(0, 0, 0, 0);
-        }
-      }
-      float x[kDecBatch];
-      float m_new = m_run;
-#pragma unroll
-      for (int k = 0; k < kDecBatch; ++k) {
-        float kf[8];
-        unpack8(kraw[k], kf);
-        const float d = row16_sum(dot8(qf, kf));
-        x[k] = kind[k] ? d + bias[k] : -INFINITY;
-        m_new = fmaxf(m_new, x[k]);
-      }
-      if (m_new != -INFINITY) {
-        const float alpha = exp2f(m_run - m_new);  // m_run = -inf gives 0
-        l_run *= alpha;
-#pragma unroll
-        for (int i = 0; i < 8; ++i) acc[i] *= alpha;
-#pragma unroll
-        for (int k = 0; k < kDecBatch; ++k) {
-          const float p = exp2f(x[k] - m_new);
-          float vf[8];
-          unpack8(vraw[k], vf);
-          l_run += p;
-#pragma unroll
-          for (int i = 0; i < 8; ++i) acc[i] = fmaf(p, vf[i], acc[i]);
-        }
-        m_run = m_new;
-      }
-    }
+    // each DPP-row group streams a contiguous run of the block's rows
+    const int per = kAttendBatch * ((r1 - r0 + kDecGroups * kAttendBatch - 1) / (kDecGroups * kAttendBatch));
+    const int ra = r0 + grp * per;
+    attend_rows(st, qf, src, s_start, s_src, n_ent, ent0, n_ex, ra, min(r1, ra + per), lane16);
     // first entry of the next block: the entry that holds row r1
     if (r1 < row_b) {
       int lo = 0, hi = n_ent + 1;  // s_start[n_ent] is staged as well
@@ -175,73 +116,55 @@ __global__ __launch_bounds__(kDecThreads) void decode_kernel(DecodeArgs a) {
     }
   }
 
-  // merge the 16 DPP-row states
-  if (lane16 == 0) {
-    s_m[grp] = m_run;
-    s_l[grp] = l_run;
+  float M, L, o;
+  block_merge<kDecWaves>(st, s_m, s_l, s_acc, M, L, o);
+
+  if (n_active == 1) {  // the only split of this head: finish here
+    if (tid < kHeadDim) {
+      store_out(a.out, a.out_is_bf16, head, tid, o / L);
+      if (a.lse && tid == 0) a.lse[head] = (M + log2f(L)) * kLn2;
+    }
+    return;
   }
-#pragma unroll
-  for (int i = 0; i < 8; ++i) s_acc[grp][lane16 * 8 + i] = acc[i];
-  __syncthreads();
+
+  float *P = a.partials + (int64_t)head * a.splits * kPartialStride;
   if (tid < kHeadDim) {
-    float M = s_m[0];
-#pragma unroll
-    for (int g2 = 1; g2 < kDecGroups; ++g2) M = fmaxf(M, s_m[g2]);
-    float L = 0.f, o = 0.f;
-#pragma unroll
-    for (int g2 = 0; g2 < kDecGroups; ++g2) {
-      const float w = (s_m[g2] == -INFINITY) ? 0.f : exp2f(s_m[g2] - M);
-      L += s_l[g2] * w;
-      o += s_acc[g2][tid] * w;
-    }
-    float *P = a.partials + ((int64_t)head * a.splits + split) * kPartialStride;
+    float *mine = P + (int64_t)split * kPartialStride;
     if (tid == 0) {
-      P[0] = M;
-      P[1] = L;
+      mine[0] = M;
+      mine[1] = L;
     }
-    P[2 + tid] = o;
+    mine[2 + tid] = o;
   }
-}
-
-struct CombineArgs {
-  const int32_t *head_rows;
-  const float *partials;
-  void *out;
-  float *lse;  // nullable
-  int32_t splits, out_is_bf16;
-};
-
-__global__ __launch_bounds__(kHeadDim) void combine_kernel(CombineArgs a) {
-  const int head = blockIdx.x, t = threadIdx.x;
-  const int R = a.head_rows[head];
-  float o = 0.f, lse = -INFINITY;
-  if (R > 0) {
-    const int c = rows_per_split(R, a.splits);
-    const int n = (R + c - 1) / c;
-    const float *P = a.partials + (int64_t)head * a.splits * kPartialStride;
-    float M = -INFINITY;
-    for (int s = 0; s < n; ++s) M = fmaxf(M, P[s * kPartialStride]);
-    float L = 0.f;
-    for (int s = 0; s < n; ++s) {
-      const float ms = P[s * kPartialStride];
-      const float w = (ms == -INFINITY) ? 0.f : exp2f(ms - M);
-      L += P[s * kPartialStride + 1] * w;
-      o += P[s * kPartialStride + 2 + t] * w;
+  // The split that arrives last merges all partials of the head (log-sum-exp merge).
+  __threadfence();
+  __syncthreads();
+  if (tid == 0) {
+    const int ticket = __hip_atomic_fetch_add(&a.plan.done[head], 1, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
+    s_last = (ticket == n_active - 1);
+  }
+  __syncthreads();
+  if (!s_last) return;
+  __threadfence();
+  if (tid < kHeadDim) {
+    float Mx = -INFINITY;
+    for (int s2 = 0; s2 < n_active; ++s2) Mx = fmaxf(Mx, __builtin_nontemporal_load(P + s2 * kPartialStride));
+    float Ls = 0.f, os = 0.f;
+    for (int s2 = 0; s2 < n_active; ++s2) {
+      const float ms = __builtin_nontemporal_load(P + s2 * kPartialStride);
+      const float w = exp2f(ms - Mx);
+      Ls += __builtin_nontemporal_load(P + s2 * kPartialStride + 1) * w;
+      os += __builtin_nontemporal_load(P + s2 * kPartialStride + 2 + tid) * w;
     }
-    o /= L;
-    lse = (M + log2f(L)) * kLn2;
+    store_out(a.out, a.out_is_bf16, head, tid, os / Ls);
+    if (a.lse && tid == 0) a.lse[head] = (Mx + log2f(Ls)) * kLn2;
   }
-  if (a.out_is_bf16)
-    static_cast<uint16_t *>(a.out)[(int64_t)head * kHeadDim + t] = (uint16_t)f32_to_bf16_rne(o);
-  else
-    static_cast<float *>(a.out)[(int64_t)head * kHeadDim + t] = o;
-  if (a.lse && t == 0) a.lse[head] = lse;
 }
 
 }  // namespace
 
 hipError_t launch_decode(const CacheView &c, const int32_t *n_exact, const int32_t *n_retained, const Plan &plan,
-                         float *partials, int splits, void *out, int out_is_bf16, float *lse, hipStream_t s) {
+                         float *partials, int splits, const AttnOut &attn, hipStream_t s) {
   const int nh = c.batch * c.n_q_heads;
   if (nh == 0) return hipSuccess;
   DecodeArgs a;
@@ -257,6 +180,9 @@ hipError_t launch_decode(const CacheView &c, const int32_t *n_exact, const int32
   a.n_retained = n_retained;
   a.plan = plan;
   a.partials = partials;
+  a.out = attn.out;
+  a.lse = attn.lse;
+  a.out_is_bf16 = attn.out_is_bf16;
   a.n_kv_heads = c.n_kv_heads;
   a.n_q_heads = c.n_q_heads;
   a.group = c.group;
@@ -264,14 +190,6 @@ hipError_t launch_decode(const CacheView &c, const int32_t *n_exact, const int32
   a.splits = splits;
   a.scale_log2 = c.sm_scale * kLog2e;
   hipLaunchKernelGGL(decode_kernel, dim3(splits, nh), dim3(kDecThreads), 0, s, a);
-  CombineArgs cb;
-  cb.head_rows = plan.head_rows;
-  cb.partials = partials;
-  cb.out = out;
-  cb.lse = lse;
-  cb.splits = splits;
-  cb.out_is_bf16 = out_is_bf16;
-  hipLaunchKernelGGL(combine_kernel, dim3(nh), dim3(kHeadDim), 0, s, cb);
   return hipGetLastError();
 }
 

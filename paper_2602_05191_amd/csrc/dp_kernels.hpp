@@ -17,6 +17,7 @@ struct CacheView {
   const int64_t *seg_row_base;
   const int32_t *seg_cluster_ptr, *cluster_offsets, *cluster_sizes;
   int32_t max_clusters_per_seg, max_rows_per_seg;
+  int32_t uniform_kc;  // > 0 when the host can tell that every segment has exactly this many clusters
   float sm_scale;
 };
 
@@ -26,10 +27,18 @@ struct CacheView {
 //   row_start[nh, max_k + 1]  exclusive prefix of rows over the entry list
 //                             (an exact cluster has s_i rows, an approximated one has 1)
 //   chunk_entry[nh, chunk_stride]  entry that holds row q*kChunkRows
-//   head_rows[nh]             total rows of the head
+//   head_rows[nh]             total rows of the head; -1: the head has already been attended
+//   done[nh]                  arrival counter of the head's decode workgroups (zeroed by the planner)
 struct Plan {
-  int32_t *ent_src, *row_start, *chunk_entry, *head_rows;
+  int32_t *ent_src, *row_start, *chunk_entry, *head_rows, *done;
   int32_t chunk_stride;
+};
+
+// where attention results go; out == nullptr: nowhere (selection only)
+struct AttnOut {
+  void *out;
+  float *lse;  // nullable
+  int32_t out_is_bf16;
 };
 
 struct SelectOut {
@@ -40,15 +49,17 @@ struct SelectOut {
 hipError_t launch_score(const CacheView &c, float *logits, hipStream_t s);
 
 // plan.ent_src == nullptr => no plan is written
+// With a plan and attn.out != nullptr, heads with few rows are attended inside the selection kernel.
 hipError_t launch_select(const CacheView &c, const float *logits, float p1, float p2, uint32_t flags,
-                         const SelectOut &out, const Plan &plan, hipStream_t s);
+                         const SelectOut &out, const Plan &plan, const AttnOut &attn, hipStream_t s);
 
 // builds the plan from caller-given sets
 hipError_t launch_plan(const CacheView &c, const int32_t *sel_ids, const int32_t *n_exact,
-                       const int32_t *n_retained, int32_t *n_exact_tokens, const Plan &plan, hipStream_t s);
+                       const int32_t *n_retained, int32_t *n_exact_tokens, const Plan &plan, const AttnOut &attn,
+                       hipStream_t s);
 
 hipError_t launch_decode(const CacheView &c, const int32_t *n_exact, const int32_t *n_retained, const Plan &plan,
-                         float *partials, int splits, void *out, int out_is_bf16, float *lse, hipStream_t s);
+                         float *partials, int splits, const AttnOut &attn, hipStream_t s);
 
 // largest max_clusters_per_seg the selection kernel supports
 constexpr int kSelectMaxClusters = 65536;

@@ -5,24 +5,27 @@
 // ascending), so it is fully described by its LAST element (key*, idx*):
 //   i is retained  <=>  key_i > key*  or  (key_i == key* and i <= idx*).
 // One workgroup of 1024 threads per head finds that element by threshold
-// search on cumulative mass:
-//   1. block max; weights w_i = exp(l_i - max) are converted to 2^-40 fixed
+// search on cumulative mass; each thread keeps E consecutive logits in
+// registers (E * 1024 >= clusters of the segment).
+//   1. block max.  Weights w_i = exp(l_i - max) are converted to 2^-40 fixed
 //      point (u64), so every sum below is an integer sum: associative, hence
-//      independent of atomics order and bitwise reproducible;
+//      independent of the order of the LDS atomics and bitwise reproducible.
+//      A logit more than 40 ln 2 below the max has mass 0 and is out of play.
 //   2. an LDS histogram of mass over 2048 bins that are linear in (max - l_i)
-//      (monotone in the logit), then a block scan locates the bin in which the
-//      cumulative mass crosses the target;
-//   3. inside that bin: if it holds few clusters, rank them exactly (pairwise
-//      comparison on (key, index)); otherwise split the bin's key range into
-//      2048 sub-ranges and repeat; a bin that holds one distinct key is a run
-//      of ties and is cut in cluster-index order.
-// The second threshold reuses the level-1 histogram.  Finally the two sets are
-// compacted in ascending cluster index with block scans, together with the
-// row-prefix plan that stage 3 uses to split work.
-//
-// Each thread keeps E consecutive logits in registers (E * 1024 >= clusters).
+//      (monotone in the logit); one block scan gives the total mass and, for
+//      both thresholds, the bin in which the cumulative mass crosses it.
+//   3. inside that bin: if it holds at most 512 clusters (the normal case: a
+//      handful), rank them exactly by pairwise comparison on (key, index);
+//      otherwise split the bin's key range into 2048 sub-ranges and repeat; a
+//      bin that holds one distinct key is a run of ties, cut in index order.
+//   4. the two sets are compacted in ascending cluster index with one block
+//      scan, together with the row-prefix plan that stage 3 splits work by.
+//   5. one-call path only: a head with at most 1024 rows is attended right
+//      here (64 DPP-row groups), which saves the latency of two more kernels
+//      for sharply peaked heads; heavier heads go to the split decode kernel.
 #include <limits.h>
 
+#include "dp_attend.hpp"
 #include "dp_device.hpp"
 #include "dp_kernels.hpp"
 
@@ -31,69 +34,80 @@ namespace {
 
 constexpr int kSelThreads = 1024;
 constexpr int kSelWaves = kSelThreads / 64;
-constexpr int kBins = 2048;            // = 2 bins per thread in the histogram scan
-constexpr float kBinRange = 27.0f;     // logits further than this below the max share the last bin
-constexpr int kMaxCand = 512;          // largest bin population that is ranked pairwise
-constexpr float kFxOne = 1099511627776.0f;  // 2^40
+constexpr int kBins = 2048;              // = 2 bins per thread in the histogram scan
+constexpr float kCut = 27.72f;           // just under 40 ln 2: beyond it the fixed-point mass is 0
+constexpr float kBinScale = (float)kBins / kCut;
+constexpr int kMaxCand = 512;            // largest bin population that is ranked pairwise
+constexpr int kInlineRows = 1024;        // heads with at most this many rows are attended in this kernel
 
 typedef unsigned long long u64;
+
+#ifdef DP_PHASE_CLOCKS  // development aid: per-phase timestamps of thread 0, never built into the library
+#define DP_MARK(i) do { if (a.dbg && threadIdx.x == 0) a.dbg[blockIdx.x * 16 + (i)] = wall_clock64(); } while (0)
+#else
+#define DP_MARK(i) do { } while (0)
+#endif
 
 struct SelectArgs {
   const float *logits;
   const int32_t *seg_cluster_ptr, *cluster_sizes, *cluster_offsets;
   int32_t n_kv_heads, n_q_heads, group, max_k;
+  int32_t uniform_kc;  // > 0: every segment has exactly this many clusters (no CSR lookup needed)
   float p1, p2;
   uint32_t p2_absolute;
   SelectOut out;
   Plan plan;
+  // inline attention (one-call path); out == nullptr disables it
+  const void *q, *k_cache, *v_cache, *k_centroids, *v_centroids;
+  const int64_t *seg_row_base;
+  void *attn_out;
+  float *lse;
+  int32_t out_is_bf16;
+  float scale_log2;
+#ifdef DP_PHASE_CLOCKS
+  unsigned long long *dbg;
+#endif
 };
 
-__device__ __forceinline__ u64 fx_mass(float l, float mx) {
-  if (l == -INFINITY) return 0;
-  return (u64)(expf(l - mx) * kFxOne);
+// floor(w * 2^40) for 0 <= w <= 1, exactly, with 32-bit conversions only
+__device__ __forceinline__ u64 fixed40(float w) {
+  const float t = w * 256.0f;
+  const uint32_t hi = (uint32_t)t;
+  const uint32_t lo = (uint32_t)((t - (float)hi) * 4294967296.0f);
+  return ((u64)hi << 32) | lo;
 }
 
-__device__ __forceinline__ int level1_bin(float l, float mx) {
-  const float t = (mx - l) * ((float)(kBins - 1) / kBinRange);
-  return t >= (float)(kBins - 1) ? kBins - 1 : (int)t;  // also catches +inf
+// d = max - logit >= 0 (+inf for an empty cluster)
+__device__ __forceinline__ u64 fx_mass(float d) {
+  return d < kCut ? fixed40(__builtin_amdgcn_exp2f(-d * kLog2e)) : 0;
 }
+__device__ __forceinline__ int level1_bin(float d) { return min(kBins - 1, (int)(d * kBinScale)); }
 
 struct Shared {
   u64 hist[kBins];
   u64 hist2[kBins];
-  u64 scr64[kSelWaves + 1];
-  float scrf[kSelWaves + 1];
-  int scri[kSelWaves + 1];
+  u64 scr64[kSelWaves];
+  float scrf[kSelWaves];
+  int scri[3 * kSelWaves];
   uint32_t red_lo[kSelWaves], red_hi[kSelWaves];
   int red_cnt[kSelWaves];
   uint32_t cand_key[kMaxCand];
   int cand_idx[kMaxCand];
   u64 cand_m[kMaxCand];
-  int ncand;
+  int ncand[2];
   int bin;
   u64 before;
   uint32_t res_key;
   int res_idx;
   u64 res_mass;
+  // inline attention
+  int l_start[kInlineRows + 1];
+  int l_src[kInlineRows];
+  float m_m[kSelWaves], m_l[kSelWaves];
+  float m_acc[kSelWaves][kHeadDim];
 };
 
-// locate the bin of `h` in which the running sum reaches tau; 2 bins per thread
-__device__ __forceinline__ void locate_bin(const u64 *h, u64 tau, Shared &sh) {
-  const int t = threadIdx.x;
-  const u64 h0 = h[2 * t], h1 = h[2 * t + 1];
-  u64 tot;
-  const u64 ex = block_excl_scan<u64, kSelWaves>(h0 + h1, sh.scr64, tot);
-  if (ex < tau && tau <= ex + h0) {
-    sh.bin = 2 * t;
-    sh.before = ex;
-  } else if (ex + h0 < tau && tau <= ex + h0 + h1) {
-    sh.bin = 2 * t + 1;
-    sh.before = ex + h0;
-  }
-  __syncthreads();
-}
-
-// count / min key / max key of the calling threads' members
+// count / min key / max key over the block
 __device__ __forceinline__ void reduce_members(int cnt, uint32_t lo, uint32_t hi, Shared &sh, int &cnt_o,
                                                uint32_t &lo_o, uint32_t &hi_o) {
 #pragma unroll
@@ -122,59 +136,68 @@ __device__ __forceinline__ void reduce_members(int cnt, uint32_t lo, uint32_t hi
   hi_o = h;
 }
 
-// Last element (key, index) of the shortest prefix of the order whose mass
-// reaches tau, and that prefix's mass.  Requires 1 <= tau <= total mass and a
-// level-1 histogram in sh.hist.  Block-uniform control flow throughout.
+// Rare path: the crossing bin holds more than kMaxCand clusters.  Narrow the key range
+// [klo, khi] (by up-to-2048-way splits of the key range, re-histogrammed in sh.hist2) until the members can
+// be ranked, or are a run of equal keys which is cut in index order.  On return either
+// cnt <= kMaxCand (members = keys in [klo, khi], not yet gathered) or the result is in sh.res_*.
 template <int E>
-__device__ __forceinline__ void find_prefix(const float (&l)[E], float mx, int base, u64 tau, Shared &sh,
-                                            uint32_t &key_o, int &idx_o, u64 &mass_o) {
+__device__ __forceinline__ bool refine_or_cut_ties(const float (&l)[E], float mx, int base, int bin1, u64 tau,
+                                                u64 &before, uint32_t &klo, uint32_t &khi, int &cnt, Shared &sh) {
   const int tid = threadIdx.x;
-  locate_bin(sh.hist, tau, sh);
-  const int bin1 = sh.bin;
-  u64 before = sh.before;
-
-  // members of the crossing bin: count and key range.  The bins are monotone
-  // in the logit, so from here on "member" means  klo <= key <= khi.
-  int cnt;
-  uint32_t klo, khi;
   {
     int c = 0;
     uint32_t lo = 0xffffffffu, hi = 0;
 #pragma unroll
-    for (int e = 0; e < E; ++e)
-      if (l[e] != -INFINITY && level1_bin(l[e], mx) == bin1) {
+    for (int e = 0; e < E; ++e) {
+      const float d = mx - l[e];
+      if (d < kCut && level1_bin(d) == bin1) {
         const uint32_t k = ordered_key(l[e]);
         ++c;
         lo = min(lo, k);
         hi = max(hi, k);
       }
+    }
     reduce_members(c, lo, hi, sh, cnt, klo, khi);
   }
-
-  // split the key range until the members can be ranked or are all ties
 #pragma unroll 1
   while (cnt > kMaxCand && klo != khi) {
     for (int i = tid; i < kBins; i += kSelThreads) sh.hist2[i] = 0;
     __syncthreads();
-    const u64 span = (u64)(khi - klo) + 1;
+    // 2048-way split of the key range by a shift: monotone in the key, no division
+    const int shift = max(0, 32 - __clz(khi - klo) - 11);
 #pragma unroll
     for (int e = 0; e < E; ++e) {
+      const float d = mx - l[e];
       const uint32_t k = ordered_key(l[e]);
-      if (l[e] != -INFINITY && k >= klo && k <= khi) {
-        const u64 m = fx_mass(l[e], mx);
-        if (m) atomicAdd(&sh.hist2[(int)(((u64)(khi - k) * kBins) / span)], m);
+      if (d < kCut && k >= klo && k <= khi) {
+        const u64 m = fx_mass(d);
+        if (m) atomicAdd(&sh.hist2[(khi - k) >> shift], m);
       }
     }
     __syncthreads();
-    locate_bin(sh.hist2, tau - before, sh);
+    {
+      const u64 h0 = sh.hist2[2 * tid], h1 = sh.hist2[2 * tid + 1];
+      u64 tot;
+      const u64 ex = block_excl_scan<u64, kSelWaves>(h0 + h1, sh.scr64, tot);
+      const u64 t2 = tau - before;
+      if (ex < t2 && t2 <= ex + h0) {
+        sh.bin = 2 * tid;
+        sh.before = ex;
+      } else if (ex + h0 < t2 && t2 <= ex + h0 + h1) {
+        sh.bin = 2 * tid + 1;
+        sh.before = ex + h0;
+      }
+      __syncthreads();
+    }
     const int bin2 = sh.bin;
     before += sh.before;
     int c = 0;
     uint32_t lo = 0xffffffffu, hi = 0;
 #pragma unroll
     for (int e = 0; e < E; ++e) {
+      const float d = mx - l[e];
       const uint32_t k = ordered_key(l[e]);
-      if (l[e] != -INFINITY && k >= klo && k <= khi && (int)(((u64)(khi - k) * kBins) / span) == bin2) {
+      if (d < kCut && k >= klo && k <= khi && (int)((khi - k) >> shift) == bin2) {
         ++c;
         lo = min(lo, k);
         hi = max(hi, k);
@@ -182,22 +205,115 @@ __device__ __forceinline__ void find_prefix(const float (&l)[E], float mx, int b
     }
     reduce_members(c, lo, hi, sh, cnt, klo, khi);
   }
+  if (cnt <= kMaxCand) return false;
 
-  if (cnt <= kMaxCand) {
-    // rank the members exactly on (key descending, index ascending)
-    if (tid == 0) sh.ncand = 0;
-    __syncthreads();
+  // one distinct key: a run of ties of equal mass, cut in cluster-index order
+  int c = 0;
+  u64 mm = 0;
+#pragma unroll
+  for (int e = 0; e < E; ++e)
+    if (mx - l[e] < kCut && ordered_key(l[e]) == klo) {
+      ++c;
+      mm = fx_mass(mx - l[e]);
+    }
+#pragma unroll
+  for (int d = 32; d >= 1; d >>= 1) {
+    const u64 o = __shfl_xor(mm, d, 64);
+    mm = o > mm ? o : mm;
+  }
+  if (lane_id() == 0) sh.scr64[wave_id()] = mm;
+  __syncthreads();
+  u64 m_tie = 0;
+#pragma unroll
+  for (int w = 0; w < kSelWaves; ++w) m_tie = sh.scr64[w] > m_tie ? sh.scr64[w] : m_tie;
+  __syncthreads();
+  const u64 need = (tau - before + m_tie - 1) / m_tie;  // ties taken, 1 <= need <= cnt
+  int tot;
+  const int ex = block_excl_scan<int, kSelWaves>(c, sh.scri, tot);
+  if ((u64)ex < need && need <= (u64)(ex + c)) {
+    int seen = ex;
+#pragma unroll
+    for (int e = 0; e < E; ++e)
+      if (mx - l[e] < kCut && ordered_key(l[e]) == klo) {
+        ++seen;
+        if ((u64)seen == need) {
+          sh.res_key = klo;
+          sh.res_idx = base + e;
+          sh.res_mass = before + need * m_tie;
+        }
+      }
+  }
+  __syncthreads();
+  return true;
+}
+
+// Last element (key, index) of the shortest prefix of the order whose mass reaches tau
+// (1 <= tau <= total mass) and that prefix's mass.  ex/h0/h1: this thread's exclusive
+// prefix and its two bins of the level-1 histogram.  `slot` picks the candidate counter.
+// cached_*: the bin whose members are currently gathered in sh.cand_* (reused when the
+// second threshold falls into the same bin).  Block-uniform control flow.
+template <int E>
+__device__ __forceinline__ void find_prefix(const float (&l)[E], float mx, int base, u64 tau, u64 ex, u64 h0, u64 h1,
+                                            int slot, Shared &sh, int &cached_bin, int &cached_cnt,
+                                            u64 &cached_before, uint32_t &key_o, int &idx_o, u64 &mass_o) {
+  const int tid = threadIdx.x;
+  if (ex < tau && tau <= ex + h0) {
+    sh.bin = 2 * tid;
+    sh.before = ex;
+  } else if (ex + h0 < tau && tau <= ex + h0 + h1) {
+    sh.bin = 2 * tid + 1;
+    sh.before = ex + h0;
+  }
+  __syncthreads();
+  const int bin1 = sh.bin;
+  u64 before = sh.before;
+  int cnt;
+  bool done = false;
+  if (bin1 == cached_bin) {
+    cnt = cached_cnt;
+    before = cached_before;
+  } else {
+    // gather the members of the crossing bin (bins are monotone in the logit)
 #pragma unroll
     for (int e = 0; e < E; ++e) {
-      const uint32_t k = ordered_key(l[e]);
-      if (l[e] != -INFINITY && k >= klo && k <= khi) {
-        const int slot = atomicAdd(&sh.ncand, 1);
-        sh.cand_key[slot] = k;
-        sh.cand_idx[slot] = base + e;
-        sh.cand_m[slot] = fx_mass(l[e], mx);
+      const float d = mx - l[e];
+      if (d < kCut && level1_bin(d) == bin1) {
+        const int s = atomicAdd(&sh.ncand[slot], 1);
+        if (s < kMaxCand) {
+          sh.cand_key[s] = ordered_key(l[e]);
+          sh.cand_idx[s] = base + e;
+          sh.cand_m[s] = fx_mass(d);
+        }
       }
     }
     __syncthreads();
+    cnt = sh.ncand[slot];
+    cached_bin = bin1;
+    cached_cnt = cnt;
+    cached_before = before;
+    if (cnt > kMaxCand) {
+      cached_bin = -1;  // the candidate arrays will not hold this bin
+      uint32_t klo, khi;
+      done = refine_or_cut_ties<E>(l, mx, base, bin1, tau, before, klo, khi, cnt, sh);
+      if (!done) {
+        if (tid == 0) sh.ncand[slot] = 0;
+        __syncthreads();
+#pragma unroll
+        for (int e = 0; e < E; ++e) {
+          const uint32_t k = ordered_key(l[e]);
+          if (mx - l[e] < kCut && k >= klo && k <= khi) {
+            const int s = atomicAdd(&sh.ncand[slot], 1);
+            sh.cand_key[s] = k;
+            sh.cand_idx[s] = base + e;
+            sh.cand_m[s] = fx_mass(mx - l[e]);
+          }
+        }
+        __syncthreads();
+      }
+    }
+  }
+  if (!done) {
+    // rank the members exactly on (key descending, index ascending)
     if (tid < cnt) {
       const uint32_t ki = sh.cand_key[tid];
       const int ii = sh.cand_idx[tid];
@@ -214,49 +330,10 @@ __device__ __forceinline__ void find_prefix(const float (&l)[E], float mx, int b
       }
     }
     __syncthreads();
-  } else {
-    // one distinct key: a run of ties of equal mass, cut in cluster-index order
-    int c = 0;
-    u64 mm = 0;
-#pragma unroll
-    for (int e = 0; e < E; ++e)
-      if (l[e] != -INFINITY && ordered_key(l[e]) == klo) {
-        ++c;
-        mm = fx_mass(l[e], mx);
-      }
-#pragma unroll
-    for (int d = 32; d >= 1; d >>= 1) {
-      const u64 o = __shfl_xor(mm, d, 64);
-      mm = o > mm ? o : mm;
-    }
-    if (lane_id() == 0) sh.scr64[wave_id()] = mm;
-    __syncthreads();
-    u64 m_tie = 0;
-#pragma unroll
-    for (int w = 0; w < kSelWaves; ++w) m_tie = sh.scr64[w] > m_tie ? sh.scr64[w] : m_tie;
-    __syncthreads();
-    const u64 need = (tau - before + m_tie - 1) / m_tie;  // ties taken, 1 <= need <= cnt
-    int tot;
-    const int ex = block_excl_scan<int, kSelWaves>(c, sh.scri, tot);
-    if ((u64)ex < need && need <= (u64)(ex + c)) {
-      int seen = ex;
-#pragma unroll
-      for (int e = 0; e < E; ++e)
-        if (l[e] != -INFINITY && ordered_key(l[e]) == klo) {
-          ++seen;
-          if ((u64)seen == need) {
-            sh.res_key = klo;
-            sh.res_idx = base + e;
-            sh.res_mass = before + need * m_tie;
-          }
-        }
-    }
-    __syncthreads();
   }
   key_o = sh.res_key;
   idx_o = sh.res_idx;
   mass_o = sh.res_mass;
-  __syncthreads();  // sh.res_* / sh.bin may be rewritten by the next search
 }
 
 template <int E>
@@ -265,18 +342,26 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(SelectArgs a) {
   const int head = blockIdx.x;
   const int b = head / a.n_q_heads, h = head % a.n_q_heads;
   const int seg = b * a.n_kv_heads + h / a.group;
-  const int c0 = a.seg_cluster_ptr[seg];
-  const int kc = a.seg_cluster_ptr[seg + 1] - c0;
+  int c0, kc;
+  if (a.uniform_kc > 0) {
+    c0 = seg * a.uniform_kc;
+    kc = a.uniform_kc;
+  } else {
+    c0 = a.seg_cluster_ptr[seg];
+    kc = a.seg_cluster_ptr[seg + 1] - c0;
+  }
   const float *lg = a.logits + (int64_t)a.group * c0 + (int64_t)(h % a.group) * kc;
   const int tid = threadIdx.x;
   const int base = tid * E;
 
   int32_t *sel = a.out.sel_ids + (int64_t)head * a.max_k;
   const bool plan = a.plan.ent_src != nullptr;
+  const bool can_inline = plan && a.attn_out != nullptr;
   int32_t *ent_src = plan ? a.plan.ent_src + (int64_t)head * a.max_k : nullptr;
   int32_t *row_start = plan ? a.plan.row_start + (int64_t)head * (a.max_k + 1) : nullptr;
   int32_t *chunk_entry = plan ? a.plan.chunk_entry + (int64_t)head * a.plan.chunk_stride : nullptr;
 
+  DP_MARK(0);
   // ---- load, max ---------------------------------------------------------
   float l[E];
   float tmax = -INFINITY;
@@ -284,12 +369,15 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(SelectArgs a) {
   for (int e = 0; e < E; ++e) {
     const int i = base + e;
     l[e] = (i < kc) ? lg[i] + 0.0f : -INFINITY;  // +0.0f: -0 becomes +0
-    tmax = fmaxf(tmax, l[e]);
   }
   for (int i = tid; i < kBins; i += kSelThreads) sh.hist[i] = 0;
-  const float mx = block_max<kSelWaves>(tmax, sh.scrf);  // barriers also publish the zeroed histogram
+  if (tid < 2) sh.ncand[tid] = 0;
+#pragma unroll
+  for (int e = 0; e < E; ++e) tmax = fmaxf(tmax, l[e]);
+  const float mx = block_max<kSelWaves>(tmax, sh.scrf);  // its barriers also publish the zeroed histogram
 
-  if (mx == -INFINITY) {  // no non-empty cluster
+  DP_MARK(1);
+  if (mx == -INFINITY) {  // no non-empty cluster: nothing selected, zero output
     if (tid == 0) {
       a.out.n_exact[head] = 0;
       a.out.n_retained[head] = 0;
@@ -297,27 +385,36 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(SelectArgs a) {
       if (plan) {
         row_start[0] = 0;
         a.plan.head_rows[head] = 0;
+        a.plan.done[head] = 0;
       }
+      if (can_inline && a.lse) a.lse[head] = -INFINITY;
     }
+    if (can_inline && tid < kHeadDim) store_out(a.attn_out, a.out_is_bf16, head, tid, 0.f);
     return;
   }
 
-  // ---- level-1 mass histogram and total mass -----------------------------
-  u64 wsum = 0;
+  // ---- level-1 mass histogram ---------------------------------------------
 #pragma unroll
   for (int e = 0; e < E; ++e) {
-    const u64 m = fx_mass(l[e], mx);
-    if (m) {
-      atomicAdd(&sh.hist[level1_bin(l[e], mx)], m);
-      wsum += m;
+    const float d = mx - l[e];
+    if (d < kCut) {
+      const u64 m = fx_mass(d);
+      if (m) atomicAdd(&sh.hist[level1_bin(d)], m);
     }
   }
-  const u64 W = block_sum<u64, kSelWaves>(wsum, sh.scr64);  // >= 2^40: the max element has weight 1
+  __syncthreads();
+  DP_MARK(2);
+  const u64 h0 = sh.hist[2 * tid], h1 = sh.hist[2 * tid + 1];
+  u64 W;  // total mass, >= 2^40: the max element has weight 1
+  const u64 ex = block_excl_scan<u64, kSelWaves>(h0 + h1, sh.scr64, W);
 
+  DP_MARK(3);
   // ---- the two thresholds -------------------------------------------------
   uint32_t key1, key2;
   int idx1, idx2;
   u64 mass1;
+  int cached_bin = -1, cached_cnt = 0;
+  u64 cached_before = 0;
   if (a.p1 >= 1.0f) {  // every non-empty cluster
     key1 = kKeyLowestFinite;
     idx1 = INT_MAX;
@@ -325,8 +422,9 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(SelectArgs a) {
   } else {
     u64 tau = (u64)ceil((double)a.p1 * (double)W);
     tau = tau < 1 ? 1 : (tau > W ? W : tau);
-    find_prefix<E>(l, mx, base, tau, sh, key1, idx1, mass1);
+    find_prefix<E>(l, mx, base, tau, ex, h0, h1, 0, sh, cached_bin, cached_cnt, cached_before, key1, idx1, mass1);
   }
+  DP_MARK(4);
   if (a.p2 >= 1.0f) {
     key2 = key1;
     idx2 = idx1;
@@ -337,56 +435,113 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(SelectArgs a) {
     u64 tau = a.p2_absolute ? (u64)ceil((double)a.p2 * (double)W) : (u64)ceil((double)a.p2 * (double)mass1);
     tau = tau < 1 ? 1 : (tau > mass1 ? mass1 : tau);
     u64 mass2;
-    find_prefix<E>(l, mx, base, tau, sh, key2, idx2, mass2);
+    __syncthreads();  // sh.bin / sh.res_* of the first search have been read by every thread
+    find_prefix<E>(l, mx, base, tau, ex, h0, h1, 1, sh, cached_bin, cached_cnt, cached_before, key2, idx2, mass2);
   }
 
+  DP_MARK(5);
   // ---- compaction in ascending cluster index ------------------------------
-  int ce = 0, ca = 0, te = 0;
+  // With p1 < 1 only clusters with non-zero mass can be selected; with p1 = 1 all non-empty ones are.
+  const bool all = a.p1 >= 1.0f;
+  u64 exa_mask = 0, ret_mask = 0;  // bit e: element e of this thread is exact / approximated
+  int sz[E], off[E];
 #pragma unroll
   for (int e = 0; e < E; ++e) {
-    if (l[e] == -INFINITY) continue;
+    sz[e] = 0;
+    off[e] = 0;
+    if (!(all ? l[e] != -INFINITY : mx - l[e] < kCut)) continue;
     const uint32_t k = ordered_key(l[e]);
     const int i = base + e;
-    const bool ret = k > key1 || (k == key1 && i <= idx1);
-    const bool exa = k > key2 || (k == key2 && i <= idx2);
-    if (exa) {
-      ++ce;
-      te += a.cluster_sizes[c0 + i];
-    } else if (ret) {
-      ++ca;
+    if (k > key2 || (k == key2 && i <= idx2)) {
+      exa_mask |= 1ull << e;
+      sz[e] = a.cluster_sizes[c0 + i];  // loads are issued here and consumed after the loop
+      if (plan) off[e] = a.cluster_offsets[c0 + i];
+    } else if (k > key1 || (k == key1 && i <= idx1)) {
+      ret_mask |= 1ull << e;
     }
   }
-  int n_ex, n_ap, n_tok;
-  int pe = block_excl_scan<int, kSelWaves>(ce, sh.scri, n_ex);
-  int pa = block_excl_scan<int, kSelWaves>(ca, sh.scri, n_ap);
-  int pt = block_excl_scan<int, kSelWaves>(te, sh.scri, n_tok);
+  const int ce = __popcll(exa_mask), ca = __popcll(ret_mask);
+  int te = 0;
 #pragma unroll
-  for (int e = 0; e < E; ++e) {
-    if (l[e] == -INFINITY) continue;
-    const uint32_t k = ordered_key(l[e]);
-    const int i = base + e;
-    const bool ret = k > key1 || (k == key1 && i <= idx1);
-    const bool exa = k > key2 || (k == key2 && i <= idx2);
-    if (exa) {
-      sel[pe] = i;
-      const int sz = a.cluster_sizes[c0 + i];
-      if (plan) {
-        ent_src[pe] = a.cluster_offsets[c0 + i];
-        row_start[pe] = pt;
-        for (int q = (pt + kChunkRows - 1) / kChunkRows; q * kChunkRows < pt + sz; ++q) chunk_entry[q] = pe;
+  for (int e = 0; e < E; ++e) te += sz[e];
+  DP_MARK(6);
+  int n_ex, n_ap, n_tok;
+  int pe, pa, pt;
+  {
+    // one scan for the three counters
+    int ie = ce, ia = ca, it = te;
+    const int lane = lane_id(), w = wave_id();
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+      const int oe = __shfl_up(ie, d, 64), oa = __shfl_up(ia, d, 64), ot = __shfl_up(it, d, 64);
+      if (lane >= d) {
+        ie += oe;
+        ia += oa;
+        it += ot;
       }
-      ++pe;
-      pt += sz;
-    } else if (ret) {
-      const int j = n_ex + pa;
-      sel[j] = i;
-      if (plan) {
-        const int row = n_tok + pa;
-        ent_src[j] = i;
-        row_start[j] = row;
-        if (row % kChunkRows == 0) chunk_entry[row / kChunkRows] = j;
+    }
+    if (lane == 63) {
+      sh.scri[w] = ie;
+      sh.scri[kSelWaves + w] = ia;
+      sh.scri[2 * kSelWaves + w] = it;
+    }
+    __syncthreads();
+    int be = 0, ba = 0, bt = 0;
+    n_ex = n_ap = n_tok = 0;
+#pragma unroll
+    for (int v = 0; v < kSelWaves; ++v) {
+      const int se = sh.scri[v], sa = sh.scri[kSelWaves + v], st = sh.scri[2 * kSelWaves + v];
+      if (v < w) {
+        be += se;
+        ba += sa;
+        bt += st;
       }
-      ++pa;
+      n_ex += se;
+      n_ap += sa;
+      n_tok += st;
+    }
+    pe = be + ie - ce;
+    pa = ba + ia - ca;
+    pt = bt + it - te;
+  }
+  DP_MARK(7);
+  const int R = n_tok + n_ap;
+  const bool inline_attn = can_inline && R <= kInlineRows;
+
+  if (ce + ca > 0) {
+#pragma unroll
+    for (int e = 0; e < E; ++e) {
+      const int i = base + e;
+      if ((exa_mask >> e) & 1) {
+        sel[pe] = i;
+        if (plan) {
+          if (inline_attn) {
+            sh.l_start[pe] = pt;
+            sh.l_src[pe] = off[e];
+          } else {
+            ent_src[pe] = off[e];
+            row_start[pe] = pt;
+            for (int q = (pt + kChunkRows - 1) / kChunkRows; q * kChunkRows < pt + sz[e]; ++q) chunk_entry[q] = pe;
+          }
+        }
+        ++pe;
+        pt += sz[e];
+      } else if ((ret_mask >> e) & 1) {
+        const int j = n_ex + pa;
+        sel[j] = i;
+        if (plan) {
+          const int row = n_tok + pa;
+          if (inline_attn) {
+            sh.l_start[j] = row;
+            sh.l_src[j] = i;
+          } else {
+            ent_src[j] = i;
+            row_start[j] = row;
+            if (row % kChunkRows == 0) chunk_entry[row / kChunkRows] = j;
+          }
+        }
+        ++pa;
+      }
     }
   }
   if (tid == 0) {
@@ -394,8 +549,48 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(SelectArgs a) {
     a.out.n_retained[head] = n_ex + n_ap;
     a.out.n_exact_tokens[head] = n_tok;
     if (plan) {
-      row_start[n_ex + n_ap] = n_tok + n_ap;
-      a.plan.head_rows[head] = n_tok + n_ap;
+      if (inline_attn) {
+        sh.l_start[n_ex + n_ap] = R;
+        a.plan.head_rows[head] = -1;  // attended here: nothing left for the decode kernel
+      } else {
+        row_start[n_ex + n_ap] = R;
+        a.plan.head_rows[head] = R;
+      }
+      a.plan.done[head] = 0;
+    }
+  }
+  DP_MARK(8);
+  if (!inline_attn) return;
+
+  // ---- inline attention for a head with few rows ---------------------------
+  __syncthreads();
+  {
+    const int lane16 = tid & 15, grp = tid >> 4;
+    float qf[8];
+    unpack8(load_row_slice(a.q, (int64_t)head, lane16), qf);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) qf[i] *= a.scale_log2;
+    RowSources src;
+    src.k_cache = a.k_cache;
+    src.v_cache = a.v_cache;
+    src.k_centroids = a.k_centroids;
+    src.v_centroids = a.v_centroids;
+    src.seg_sizes = a.cluster_sizes + c0;
+    src.seg_row0 = a.seg_row_base[seg];
+    src.c0 = c0;
+    RowState st;
+    row_state_init(st);
+    constexpr int kGroups = kSelThreads / 16;
+    const int per = kAttendBatch * ((R + kGroups * kAttendBatch - 1) / (kGroups * kAttendBatch));
+    const int ra = grp * per, rb = min(R, ra + per);
+    attend_rows(st, qf, src, sh.l_start, sh.l_src, n_ex + n_ap, 0, n_ex, ra, rb, lane16);
+    DP_MARK(9);
+    float M, L, o;
+    block_merge<kSelWaves>(st, sh.m_m, sh.m_l, sh.m_acc, M, L, o);
+    DP_MARK(10);
+    if (tid < kHeadDim) {
+      store_out(a.attn_out, a.out_is_bf16, head, tid, o / L);
+      if (a.lse && tid == 0) a.lse[head] = (M + log2f(L)) * kLn2;
     }
   }
 }
@@ -409,6 +604,9 @@ struct PlanArgs {
   int32_t *n_exact_tokens;  // nullable
   int32_t n_kv_heads, n_q_heads, group, max_k;
   Plan plan;
+  void *attn_out;  // a head without rows gets out = 0, lse = -inf here
+  float *lse;
+  int32_t out_is_bf16;
 };
 
 __global__ __launch_bounds__(kPlanThreads) void plan_kernel(PlanArgs a) {
@@ -448,17 +646,31 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(PlanArgs a) {
     row_start[j] = row;
     if (row % kChunkRows == 0) chunk_entry[row / kChunkRows] = j;
   }
+  const int R = n_tok + (n_rt - n_ex);
   if (tid == 0) {
-    row_start[n_rt] = n_tok + (n_rt - n_ex);
-    a.plan.head_rows[head] = n_tok + (n_rt - n_ex);
+    row_start[n_rt] = R;
+    a.plan.head_rows[head] = R;
+    a.plan.done[head] = 0;
     if (a.n_exact_tokens) a.n_exact_tokens[head] = n_tok;
+    if (R == 0 && a.lse) a.lse[head] = -INFINITY;
   }
+  if (R == 0 && tid < kHeadDim) store_out(a.attn_out, a.out_is_bf16, head, tid, 0.f);
+}
+
+template <int E>
+void launch_select_e(const SelectArgs &a, dim3 grid, hipStream_t s) {
+  hipLaunchKernelGGL(select_kernel<E>, grid, dim3(kSelThreads), 0, s, a);
 }
 
 }  // namespace
 
+#ifdef DP_PHASE_CLOCKS
+unsigned long long *g_phase_clock_buffer = nullptr;
+extern "C" void dp_debug_set_phase_clock_buffer(void *p) { g_phase_clock_buffer = (unsigned long long *)p; }
+#endif
+
 hipError_t launch_select(const CacheView &c, const float *logits, float p1, float p2, uint32_t flags,
-                         const SelectOut &out, const Plan &plan, hipStream_t s) {
+                         const SelectOut &out, const Plan &plan, const AttnOut &attn, hipStream_t s) {
   SelectArgs a;
   a.logits = logits;
   a.seg_cluster_ptr = c.seg_cluster_ptr;
@@ -468,26 +680,41 @@ hipError_t launch_select(const CacheView &c, const float *logits, float p1, floa
   a.n_q_heads = c.n_q_heads;
   a.group = c.group;
   a.max_k = c.max_clusters_per_seg;
+  a.uniform_kc = c.uniform_kc;
   a.p1 = p1;
   a.p2 = p2;
   a.p2_absolute = flags & 1u;
   a.out = out;
   a.plan = plan;
-  const dim3 grid(c.batch * c.n_q_heads), block(kSelThreads);
+  a.q = c.q;
+  a.k_cache = c.k_cache;
+  a.v_cache = c.v_cache;
+  a.k_centroids = c.k_centroids;
+  a.v_centroids = c.v_centroids;
+  a.seg_row_base = c.seg_row_base;
+  a.attn_out = attn.out;
+  a.lse = attn.lse;
+  a.out_is_bf16 = attn.out_is_bf16;
+  a.scale_log2 = c.sm_scale * kLog2e;
+#ifdef DP_PHASE_CLOCKS
+  a.dbg = g_phase_clock_buffer;
+#endif
+  const dim3 grid(c.batch * c.n_q_heads);
   if (grid.x == 0) return hipSuccess;
   const int k = c.max_clusters_per_seg;
-  if (k <= 2 * kSelThreads) hipLaunchKernelGGL(select_kernel<2>, grid, block, 0, s, a);
-  else if (k <= 4 * kSelThreads) hipLaunchKernelGGL(select_kernel<4>, grid, block, 0, s, a);
-  else if (k <= 8 * kSelThreads) hipLaunchKernelGGL(select_kernel<8>, grid, block, 0, s, a);
-  else if (k <= 16 * kSelThreads) hipLaunchKernelGGL(select_kernel<16>, grid, block, 0, s, a);
-  else if (k <= 32 * kSelThreads) hipLaunchKernelGGL(select_kernel<32>, grid, block, 0, s, a);
-  else if (k <= 64 * kSelThreads) hipLaunchKernelGGL(select_kernel<64>, grid, block, 0, s, a);
+  if (k <= 2 * kSelThreads) launch_select_e<2>(a, grid, s);
+  else if (k <= 4 * kSelThreads) launch_select_e<4>(a, grid, s);
+  else if (k <= 8 * kSelThreads) launch_select_e<8>(a, grid, s);
+  else if (k <= 16 * kSelThreads) launch_select_e<16>(a, grid, s);
+  else if (k <= 32 * kSelThreads) launch_select_e<32>(a, grid, s);
+  else if (k <= 64 * kSelThreads) launch_select_e<64>(a, grid, s);
   else return hipErrorInvalidValue;
   return hipGetLastError();
 }
 
 hipError_t launch_plan(const CacheView &c, const int32_t *sel_ids, const int32_t *n_exact,
-                       const int32_t *n_retained, int32_t *n_exact_tokens, const Plan &plan, hipStream_t s) {
+                       const int32_t *n_retained, int32_t *n_exact_tokens, const Plan &plan, const AttnOut &attn,
+                       hipStream_t s) {
   PlanArgs a;
   a.seg_cluster_ptr = c.seg_cluster_ptr;
   a.cluster_sizes = c.cluster_sizes;
@@ -501,6 +728,9 @@ hipError_t launch_plan(const CacheView &c, const int32_t *sel_ids, const int32_t
   a.group = c.group;
   a.max_k = c.max_clusters_per_seg;
   a.plan = plan;
+  a.attn_out = attn.out;
+  a.lse = attn.lse;
+  a.out_is_bf16 = attn.out_is_bf16;
   const dim3 grid(c.batch * c.n_q_heads);
   if (grid.x == 0) return hipSuccess;
   hipLaunchKernelGGL(plan_kernel, grid, dim3(kPlanThreads), 0, s, a);
