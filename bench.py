@@ -145,25 +145,28 @@ def main():
     torch.cuda.synchronize()
     resident_us = (time.perf_counter() - c0) * 1e6 / min(args.steps, 500)
 
-    # ---- per-stage launch durations: each launch bracketed by its own pair of HIP events on the
-    # stream it is launched on (torch's current stream) -------------------------------------------
+    # ---- per-stage launch durations, HIP events on the launch stream (torch's current stream) ----
     n_logits = cache.group * int(cache.seg_cluster_ptr[-1])
     logits = torch.empty(n_logits, dtype=torch.float32, device=dev)
     sel_d = torch.empty((nh, mk), dtype=torch.int32, device=dev)
     n_stage = min(args.steps, 720)
 
     def time_stage(fn):
-        pairs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n_stage)]
+        """Average duration of one launch in a back-to-back stream of n_stage launches (rotating
+        replicas), from one pair of HIP events on the launch stream; median over 5 such runs."""
         for i in range(min(50, n_stage)):
             fn(i)
         torch.cuda.synchronize()
-        for i, (a, b) in enumerate(pairs):
+        runs = []
+        for _ in range(5):
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
             a.record()
-            fn(i)
+            for i in range(n_stage):
+                fn(i)
             b.record()
-        torch.cuda.synchronize()
-        ts = [a.elapsed_time(b) * 1e3 for a, b in pairs]
-        return statistics.mean(ts), statistics.median(ts)
+            torch.cuda.synchronize()
+            runs.append(a.elapsed_time(b) * 1e3 / n_stage)
+        return statistics.mean(runs), statistics.median(runs)
 
     score_us, score_med = time_stage(lambda i: dp.dp_score_centroids(probs[i % L], logits))
     select_us, select_med = time_stage(lambda i: dp.dp_topp_select(probs[i % L], logits, p1, p2, sel_d, ne, nr, nt))

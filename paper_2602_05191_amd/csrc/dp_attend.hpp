@@ -8,7 +8,7 @@
 // mean value, additive weight log2 s).  row_start[j] is the exclusive prefix
 // of rows.  A 16-lane DPP row ("group") owns one cache row per load: lane t
 // holds dims [8t, 8t+8) of K for the dot product and of V for the accumulation.
-// All exponents are base 2 (the query is pre-scaled by sm_scale * log2 e).
+// All exponents are base 2 (logits are scaled by sm_scale * log2 e).
 #pragma once
 
 #include "dp_device.hpp"
@@ -40,7 +40,7 @@ struct RowSources {
 // cover [ra, rb) (s_start[0] <= ra).  Every lane of the group runs the same
 // entry walk (uniform inside the group), so nothing is exchanged between lanes
 // except the DPP sum of the dot product.
-__device__ __forceinline__ void attend_rows(RowState &st, const float (&qf)[8], const RowSources &src,
+__device__ __forceinline__ void attend_rows(RowState &st, const uint4 &qv, float scale_log2, const RowSources &src,
                                             const int *s_start, const int *s_src, int n_ent, int ent0, int n_ex,
                                             int ra, int rb, int lane16) {
   if (ra >= rb) return;
@@ -89,9 +89,7 @@ __device__ __forceinline__ void attend_rows(RowState &st, const float (&qf)[8], 
     float m_new = st.m;
 #pragma unroll
     for (int u = 0; u < kAttendBatch; ++u) {
-      float kf[8];
-      unpack8(kraw[u], kf);
-      const float d = row16_sum(dot8(qf, kf));
+      const float d = row16_sum(dot8_bf16(qv, kraw[u])) * scale_log2;
       x[u] = valid[u] ? (approx[u] ? d + log2f((float)ssz[u]) : d) : -INFINITY;
       m_new = fmaxf(m_new, x[u]);
     }
@@ -128,30 +126,31 @@ __device__ __forceinline__ void wave_merge(RowState &st) {
   }
 }
 
-// Merge the waves of a workgroup through LDS.  s_m / s_l: NW floats, s_acc: NW x 128 floats.
-// Returns, for threads tid < 128: M, L and the unnormalised output of dim tid.
+// Merge the first n_waves waves of a workgroup through LDS (the others hold no rows).
+// s_m / s_l: NW floats, s_acc: NW x 128 floats.  Returns, for threads tid < 128: M, L and the
+// unnormalised output of dim tid.  n_waves is block-uniform, 1 <= n_waves <= NW.
 template <int NW>
 __device__ __forceinline__ void block_merge(RowState &st, float *s_m, float *s_l, float (*s_acc)[kHeadDim],
-                                            float &M, float &L, float &o) {
-  wave_merge(st);
+                                            int n_waves, float &M, float &L, float &o) {
   const int lane = lane_id(), w = wave_id();
-  if (lane < 16) {
-    if (lane == 0) {
-      s_m[w] = st.m;
-      s_l[w] = st.l;
-    }
+  if (w < n_waves) {
+    wave_merge(st);
+    if (lane < 16) {
+      if (lane == 0) {
+        s_m[w] = st.m;
+        s_l[w] = st.l;
+      }
 #pragma unroll
-    for (int i = 0; i < 8; ++i) s_acc[w][lane * 8 + i] = st.acc[i];
+      for (int i = 0; i < 8; ++i) s_acc[w][lane * 8 + i] = st.acc[i];
+    }
   }
   __syncthreads();
   M = -INFINITY;
   L = 0.f;
   o = 0.f;
   if (threadIdx.x < kHeadDim) {
-#pragma unroll
-    for (int g = 0; g < NW; ++g) M = fmaxf(M, s_m[g]);
-#pragma unroll
-    for (int g = 0; g < NW; ++g) {
+    for (int g = 0; g < n_waves; ++g) M = fmaxf(M, s_m[g]);
+    for (int g = 0; g < n_waves; ++g) {
       const float wg = (s_m[g] == -INFINITY) ? 0.f : exp2f(s_m[g] - M);
       L += s_l[g] * wg;
       o += s_acc[g][threadIdx.x] * wg;

@@ -72,10 +72,7 @@ __global__ __launch_bounds__(kDecThreads) void decode_kernel(DecodeArgs a) {
   const int32_t *row_start = a.plan.row_start + (int64_t)head * (a.max_k + 1);
   const int tid = threadIdx.x, lane16 = tid & 15, grp = tid >> 4;
 
-  float qf[8];
-  unpack8(load_row_slice(a.q, (int64_t)head, lane16), qf);
-#pragma unroll
-  for (int i = 0; i < 8; ++i) qf[i] *= a.scale_log2;
+  const uint4 qv = load_row_slice(a.q, (int64_t)head, lane16);
 
   RowSources src;
   src.k_cache = a.k_cache;
@@ -104,7 +101,7 @@ __global__ __launch_bounds__(kDecThreads) void decode_kernel(DecodeArgs a) {
     // each DPP-row group streams a contiguous run of the block's rows
     const int per = kAttendBatch * ((r1 - r0 + kDecGroups * kAttendBatch - 1) / (kDecGroups * kAttendBatch));
     const int ra = r0 + grp * per;
-    attend_rows(st, qf, src, s_start, s_src, n_ent, ent0, n_ex, ra, min(r1, ra + per), lane16);
+    attend_rows(st, qv, a.scale_log2, src, s_start, s_src, n_ent, ent0, n_ex, ra, min(r1, ra + per), lane16);
     // first entry of the next block: the entry that holds row r1
     if (r1 < row_b) {
       int lo = 0, hi = n_ent + 1;  // s_start[n_ent] is staged as well
@@ -117,7 +114,7 @@ __global__ __launch_bounds__(kDecThreads) void decode_kernel(DecodeArgs a) {
   }
 
   float M, L, o;
-  block_merge<kDecWaves>(st, s_m, s_l, s_acc, M, L, o);
+  block_merge<kDecWaves>(st, s_m, s_l, s_acc, kDecWaves, M, L, o);
 
   if (n_active == 1) {  // the only split of this head: finish here
     if (tid < kHeadDim) {

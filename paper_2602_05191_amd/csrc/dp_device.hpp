@@ -56,6 +56,17 @@ __device__ __forceinline__ uint4 load_row_slice(const void *base, int64_t row, i
   return *reinterpret_cast<const uint4 *>(p);
 }
 
+// bf16 x bf16 dot product of the lane's 8 dims, accumulated in fp32 by v_dot2c_f32_bf16
+// (two multiply-adds per instruction, operands stay packed: no unpacking)
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ float dot8_bf16(const uint4 &a, const uint4 &b) {
+  float s = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, a.x), __builtin_bit_cast(bf16x2_t, b.x), 0.f, false);
+  s = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, a.y), __builtin_bit_cast(bf16x2_t, b.y), s, false);
+  s = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, a.z), __builtin_bit_cast(bf16x2_t, b.z), s, false);
+  s = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, a.w), __builtin_bit_cast(bf16x2_t, b.w), s, false);
+  return s;
+}
+
 // partial dot of the lane's 8 dims
 __device__ __forceinline__ float dot8(const float (&a)[8], const float (&b)[8]) {
   float s = a[0] * b[0];
@@ -87,16 +98,44 @@ __device__ __forceinline__ T wave_incl_scan(T v) {
   return v;
 }
 
-template <typename T>
-__device__ __forceinline__ T wave_sum(T v) {
-#pragma unroll
-  for (int d = 32; d >= 1; d >>= 1) v += __shfl_xor(v, d, 64);
+// Wave reductions: 4 DPP steps inside each 16-lane row, then 2 cross-row exchanges.
+template <int CTRL>
+__device__ __forceinline__ uint32_t dpp_mov_u32(uint32_t v) {
+  return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, CTRL, 0xf, 0xf, true);
+}
+template <int CTRL>
+__device__ __forceinline__ unsigned long long dpp_mov_u64(unsigned long long v) {
+  const uint32_t lo = dpp_mov_u32<CTRL>((uint32_t)v), hi = dpp_mov_u32<CTRL>((uint32_t)(v >> 32));
+  return ((unsigned long long)hi << 32) | lo;
+}
+
+__device__ __forceinline__ unsigned long long wave_sum(unsigned long long v) {
+  v += dpp_mov_u64<0xB1>(v);
+  v += dpp_mov_u64<0x4E>(v);
+  v += dpp_mov_u64<0x141>(v);
+  v += dpp_mov_u64<0x140>(v);
+  v += __shfl_xor(v, 16, 64);
+  v += __shfl_xor(v, 32, 64);
+  return v;
+}
+
+__device__ __forceinline__ int wave_sum(int v) {
+  v += (int)dpp_mov_u32<0xB1>((uint32_t)v);
+  v += (int)dpp_mov_u32<0x4E>((uint32_t)v);
+  v += (int)dpp_mov_u32<0x141>((uint32_t)v);
+  v += (int)dpp_mov_u32<0x140>((uint32_t)v);
+  v += __shfl_xor(v, 16, 64);
+  v += __shfl_xor(v, 32, 64);
   return v;
 }
 
 __device__ __forceinline__ float wave_max(float v) {
-#pragma unroll
-  for (int d = 32; d >= 1; d >>= 1) v = fmaxf(v, __shfl_xor(v, d, 64));
+  v = fmaxf(v, dpp_mov<0xB1>(v));
+  v = fmaxf(v, dpp_mov<0x4E>(v));
+  v = fmaxf(v, dpp_mov<0x141>(v));
+  v = fmaxf(v, dpp_mov<0x140>(v));
+  v = fmaxf(v, __shfl_xor(v, 16, 64));
+  v = fmaxf(v, __shfl_xor(v, 32, 64));
   return v;
 }
 

@@ -5,7 +5,8 @@
 // HBM-bound streaming kernel: the key-centroid matrix is read exactly once
 // (256 B per cluster) and each row is scored against all G query heads of the
 // group from registers.  A 16-lane DPP row owns one centroid row (16 B per
-// lane, global_load_dwordx4); the 16 partial dots are summed with DPP adds.
+// lane, global_load_dwordx4); each lane's 8 products are accumulated by the
+// packed bf16 dot instruction and the 16 partial dots are summed with DPP adds.
 // Algorithmic traffic per cluster: 256 B centroid + 4 B size read, 4*G B written.
 #include "dp_device.hpp"
 #include "dp_kernels.hpp"
@@ -14,23 +15,33 @@ namespace dp {
 namespace {
 
 constexpr int kScoreThreads = 256;                   // 16 DPP rows
-constexpr int kScoreRowsPerGroup = 4;                // centroid rows in flight per 16-lane row
-constexpr int kScoreTile = (kScoreThreads / 16) * kScoreRowsPerGroup;  // 64 clusters per workgroup
+#ifndef DP_SCORE_RB
+#define DP_SCORE_RB 4
+#endif
+constexpr int kScoreRowsPerGroup = DP_SCORE_RB;      // centroid rows in flight per 16-lane row
+constexpr int kScoreTile = (kScoreThreads / 16) * kScoreRowsPerGroup;  // clusters per workgroup
 
 struct ScoreArgs {
   const void *q, *k_centroids;
   const int32_t *seg_cluster_ptr, *cluster_sizes;
   float *logits;
   int32_t n_kv_heads, n_q_heads, group;
-  int32_t head0, heads;  // this launch scores heads [head0, head0 + heads) of each group
+  int32_t head0;       // this launch scores heads [head0, head0 + GH) of each group
+  int32_t uniform_kc;  // > 0: every segment has exactly this many clusters
   float sm_scale;
 };
 
 template <int GH>
 __global__ __launch_bounds__(kScoreThreads) void score_kernel(ScoreArgs a) {
   const int seg = blockIdx.y;
-  const int c0 = a.seg_cluster_ptr[seg];
-  const int kc = a.seg_cluster_ptr[seg + 1] - c0;
+  int c0, kc;
+  if (a.uniform_kc > 0) {  // no CSR lookup in front of the centroid loads
+    c0 = seg * a.uniform_kc;
+    kc = a.uniform_kc;
+  } else {
+    c0 = a.seg_cluster_ptr[seg];
+    kc = a.seg_cluster_ptr[seg + 1] - c0;
+  }
   const int tile0 = blockIdx.x * kScoreTile;
   if (tile0 >= kc) return;
 
@@ -38,12 +49,13 @@ __global__ __launch_bounds__(kScoreThreads) void score_kernel(ScoreArgs a) {
   const int grp = threadIdx.x >> 4;
   const int b = seg / a.n_kv_heads, g = seg % a.n_kv_heads;
 
-  // issue the centroid loads first: rows tile0 + grp + 16*k
+  // issue the centroid loads first: this group owns rows tile0 + grp*RB .. +RB-1
+  const int i0 = tile0 + grp * kScoreRowsPerGroup;
   uint4 raw[kScoreRowsPerGroup];
   int size[kScoreRowsPerGroup];
 #pragma unroll
   for (int k = 0; k < kScoreRowsPerGroup; ++k) {
-    const int i = tile0 + grp + 16 * k;
+    const int i = i0 + k;
     if (i < kc) {
       raw[k] = load_row_slice(a.k_centroids, (int64_t)(c0 + i), lane16);
       size[k] = a.cluster_sizes[c0 + i];
@@ -53,30 +65,39 @@ __global__ __launch_bounds__(kScoreThreads) void score_kernel(ScoreArgs a) {
     }
   }
 
-  // the group's query slices, fp32 in registers
-  float qf[GH][8];
+  // the group's query slices stay packed bf16
+  uint4 qv[GH];
 #pragma unroll
-  for (int j = 0; j < GH; ++j) {
-    const int h = g * a.group + a.head0 + j;
-    unpack8(load_row_slice(a.q, (int64_t)b * a.n_q_heads + h, lane16), qf[j]);
-  }
+  for (int j = 0; j < GH; ++j)
+    qv[j] = load_row_slice(a.q, (int64_t)b * a.n_q_heads + g * a.group + a.head0 + j, lane16);
 
-  float *out = a.logits + (int64_t)a.group * c0 + (int64_t)a.head0 * kc;
+  // lane j of the group ends up with head j's logits of the group's RB consecutive clusters
+  float mine[kScoreRowsPerGroup];
 #pragma unroll
   for (int k = 0; k < kScoreRowsPerGroup; ++k) {
-    const int i = tile0 + grp + 16 * k;
-    float cf[8];
-    unpack8(raw[k], cf);
-    float mine = 0.f;
+    mine[k] = 0.f;
 #pragma unroll
     for (int j = 0; j < GH; ++j) {
-      float d = row16_sum(dot8(qf[j], cf));
-      if (lane16 == j) mine = d;
+      const float d = row16_sum(dot8_bf16(qv[j], raw[k]));
+      if (lane16 == j) mine[k] = d;
     }
-    if (i < kc && lane16 < GH) {
-      const int s = size[k];
-      const float v = (s > 0) ? fmaf(mine, a.sm_scale, logf((float)s)) : -INFINITY;
-      out[(int64_t)lane16 * kc + i] = v;
+  }
+  if (lane16 < GH && i0 < kc) {
+    float *out = a.logits + (int64_t)a.group * c0 + (int64_t)(a.head0 + lane16) * kc + i0;
+    float v[kScoreRowsPerGroup];
+#pragma unroll
+    for (int k = 0; k < kScoreRowsPerGroup; ++k) {
+      // ln s from the hardware log2 (1 ulp), exact for s = 1
+      v[k] = (size[k] > 0) ? fmaf(mine[k], a.sm_scale, __builtin_amdgcn_logf((float)size[k]) * 0.6931471805599453f)
+                           : -INFINITY;
+    }
+    if (kScoreRowsPerGroup == 4 && i0 + 3 < kc && (reinterpret_cast<uintptr_t>(out) & 15) == 0) {
+      *reinterpret_cast<float4 *>(out) = make_float4(v[0], v[1 % kScoreRowsPerGroup], v[2 % kScoreRowsPerGroup],
+                                                     v[3 % kScoreRowsPerGroup]);
+    } else {
+#pragma unroll
+      for (int k = 0; k < kScoreRowsPerGroup; ++k)
+        if (i0 + k < kc) out[k] = v[k];
     }
   }
 }
@@ -94,6 +115,7 @@ hipError_t launch_score(const CacheView &c, float *logits, hipStream_t s) {
   a.n_q_heads = c.n_q_heads;
   a.group = c.group;
   a.sm_scale = c.sm_scale;
+  a.uniform_kc = c.uniform_kc;
   const dim3 grid((c.max_clusters_per_seg + kScoreTile - 1) / kScoreTile, c.batch * c.n_kv_heads);
   if (grid.x == 0 || grid.y == 0) return hipSuccess;
   // heads of a group are scored 8/4/2/1 at a time (one pass when G is 1, 2, 4 or 8)
@@ -102,7 +124,6 @@ hipError_t launch_score(const CacheView &c, float *logits, hipStream_t s) {
     const int left = c.group - h0;
     const int gh = left >= 8 ? 8 : left >= 4 ? 4 : left >= 2 ? 2 : 1;
     a.head0 = h0;
-    a.heads = gh;
     switch (gh) {
       case 8: hipLaunchKernelGGL(score_kernel<8>, grid, dim3(kScoreThreads), 0, s, a); break;
       case 4: hipLaunchKernelGGL(score_kernel<4>, grid, dim3(kScoreThreads), 0, s, a); break;

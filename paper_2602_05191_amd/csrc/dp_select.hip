@@ -20,6 +20,10 @@
 //      bin that holds one distinct key is a run of ties, cut in index order.
 //   4. the two sets are compacted in ascending cluster index with one block
 //      scan, together with the row-prefix plan that stage 3 splits work by.
+//   Fast path (tried first): when at most 64 clusters lie within 6 of the max
+//      logit and their mass already reaches the first threshold (a peaked head),
+//      the retained set is inside that top set; one wave ranks it pairwise and
+//      emits both lists, and steps 2-4 are skipped.  Same masses, same result.
 //   5. one-call path only: a head with at most 1024 rows is attended right
 //      here (64 DPP-row groups), which saves the latency of two more kernels
 //      for sharply peaked heads; heavier heads go to the split decode kernel.
@@ -39,6 +43,8 @@ constexpr float kCut = 27.72f;           // just under 40 ln 2: beyond it the fi
 constexpr float kBinScale = (float)kBins / kCut;
 constexpr int kMaxCand = 512;            // largest bin population that is ranked pairwise
 constexpr int kInlineRows = 1024;        // heads with at most this many rows are attended in this kernel
+constexpr float kTopCut = 6.0f;          // "top set": clusters whose logit is within this of the max
+constexpr int kTopMax = 64;              // largest top set handled by the one-wave fast path
 
 typedef unsigned long long u64;
 
@@ -100,6 +106,11 @@ struct Shared {
   uint32_t res_key;
   int res_idx;
   u64 res_mass;
+  // fast path: the top set
+  uint32_t top_key[kTopMax];
+  int top_idx[kTopMax], top_sz[kTopMax], top_off[kTopMax];
+  u64 top_m[kTopMax];
+  int ntop, fast_ok, f_nex, f_nap, f_ntok;
   // inline attention
   int l_start[kInlineRows + 1];
   int l_src[kInlineRows];
@@ -336,6 +347,40 @@ __device__ __forceinline__ void find_prefix(const float (&l)[E], float mx, int b
   mass_o = sh.res_mass;
 }
 
+// Where the selected ids and the stage-3 plan of one head go: the caller-visible id list,
+// and either the LDS lists of the inline attention or the global plan arrays.
+struct Emit {
+  int32_t *sel, *ent_src, *row_start, *chunk_entry;
+  int *l_start, *l_src;
+  bool plan, to_lds;
+  int n_ex, n_tok;
+  __device__ __forceinline__ void exact(int pe, int pt, int sz, int off, int id) const {
+    sel[pe] = id;
+    if (!plan) return;
+    if (to_lds) {
+      l_start[pe] = pt;
+      l_src[pe] = off;
+    } else {
+      ent_src[pe] = off;
+      row_start[pe] = pt;
+      for (int q = (pt + kChunkRows - 1) / kChunkRows; q * kChunkRows < pt + sz; ++q) chunk_entry[q] = pe;
+    }
+  }
+  __device__ __forceinline__ void approx(int pa, int id) const {
+    const int j = n_ex + pa, row = n_tok + pa;
+    sel[j] = id;
+    if (!plan) return;
+    if (to_lds) {
+      l_start[j] = row;
+      l_src[j] = id;
+    } else {
+      ent_src[j] = id;
+      row_start[j] = row;
+      if (row % kChunkRows == 0) chunk_entry[row / kChunkRows] = j;
+    }
+  }
+};
+
 template <int E>
 __global__ __launch_bounds__(kSelThreads) void select_kernel(SelectArgs a) {
   __shared__ Shared sh;
@@ -354,27 +399,80 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(SelectArgs a) {
   const int tid = threadIdx.x;
   const int base = tid * E;
 
-  int32_t *sel = a.out.sel_ids + (int64_t)head * a.max_k;
   const bool plan = a.plan.ent_src != nullptr;
   const bool can_inline = plan && a.attn_out != nullptr;
-  int32_t *ent_src = plan ? a.plan.ent_src + (int64_t)head * a.max_k : nullptr;
-  int32_t *row_start = plan ? a.plan.row_start + (int64_t)head * (a.max_k + 1) : nullptr;
-  int32_t *chunk_entry = plan ? a.plan.chunk_entry + (int64_t)head * a.plan.chunk_stride : nullptr;
+  Emit emit;
+  emit.sel = a.out.sel_ids + (int64_t)head * a.max_k;
+  emit.ent_src = plan ? a.plan.ent_src + (int64_t)head * a.max_k : nullptr;
+  emit.row_start = plan ? a.plan.row_start + (int64_t)head * (a.max_k + 1) : nullptr;
+  emit.chunk_entry = plan ? a.plan.chunk_entry + (int64_t)head * a.plan.chunk_stride : nullptr;
+  emit.l_start = sh.l_start;
+  emit.l_src = sh.l_src;
+  emit.plan = plan;
 
   DP_MARK(0);
   // ---- load, max ---------------------------------------------------------
   float l[E];
-  float tmax = -INFINITY;
+  if (E >= 4 && (reinterpret_cast<uintptr_t>(lg) & 15) == 0) {
 #pragma unroll
-  for (int e = 0; e < E; ++e) {
-    const int i = base + e;
-    l[e] = (i < kc) ? lg[i] + 0.0f : -INFINITY;  // +0.0f: -0 becomes +0
+    for (int e = 0; e < E; e += 4) {  // E >= 4 here; 16-byte loads
+      const int i = base + e;
+      if (i + 3 < kc) {
+        const float4 v = *reinterpret_cast<const float4 *>(lg + i);
+        l[e] = v.x;
+        l[e + 1 < E ? e + 1 : e] = v.y;
+        l[e + 2 < E ? e + 2 : e] = v.z;
+        l[e + 3 < E ? e + 3 : e] = v.w;
+      } else {
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+          if (e + u < E) l[e + u] = (i + u < kc) ? lg[i + u] : -INFINITY;
+      }
+    }
+  } else {
+#pragma unroll
+    for (int e = 0; e < E; ++e) l[e] = (base + e < kc) ? lg[base + e] : -INFINITY;
+  }
+  const int64_t seg_row0 = can_inline ? a.seg_row_base[seg] : 0;  // needed last; its latency hides here
+  // With few logits per thread, sizes and offsets are fetched up front next to the logits, so that no
+  // dependent load sits between the selection and the first K/V row.
+#ifdef DP_NO_PRELOAD
+  constexpr bool kPre = false;
+#else
+  constexpr bool kPre = E <= 8;
+#endif
+  constexpr int EP = kPre ? E : 1;
+  int psz[EP], poff[EP];
+  if (kPre) {
+    const int32_t *sp = a.cluster_sizes + c0 + base, *op = a.cluster_offsets + c0 + base;
+    if (E >= 4 && ((reinterpret_cast<uintptr_t>(sp) | reinterpret_cast<uintptr_t>(op)) & 15) == 0 && base + E <= kc) {
+#pragma unroll
+      for (int e = 0; e < EP; e += 4) {
+        const int4 v = *reinterpret_cast<const int4 *>(sp + e);
+        psz[e] = v.x; psz[e + 1 < EP ? e + 1 : e] = v.y; psz[e + 2 < EP ? e + 2 : e] = v.z; psz[e + 3 < EP ? e + 3 : e] = v.w;
+        if (plan) {
+          const int4 u = *reinterpret_cast<const int4 *>(op + e);
+          poff[e] = u.x; poff[e + 1 < EP ? e + 1 : e] = u.y; poff[e + 2 < EP ? e + 2 : e] = u.z; poff[e + 3 < EP ? e + 3 : e] = u.w;
+        }
+      }
+    } else {
+#pragma unroll
+      for (int e = 0; e < EP; ++e) {
+        psz[e] = (base + e < kc) ? sp[e] : 0;
+        poff[e] = (plan && base + e < kc) ? op[e] : 0;
+      }
+    }
   }
   for (int i = tid; i < kBins; i += kSelThreads) sh.hist[i] = 0;
   if (tid < 2) sh.ncand[tid] = 0;
+  if (tid == 2) sh.ntop = 0;
+  float tmax = -INFINITY;
 #pragma unroll
-  for (int e = 0; e < E; ++e) tmax = fmaxf(tmax, l[e]);
-  const float mx = block_max<kSelWaves>(tmax, sh.scrf);  // its barriers also publish the zeroed histogram
+  for (int e = 0; e < E; ++e) {
+    l[e] += 0.0f;  // -0 becomes +0
+    tmax = fmaxf(tmax, l[e]);
+  }
+  const float mx = block_max<kSelWaves>(tmax, sh.scrf);  // its barriers also publish the zeroed LDS
 
   DP_MARK(1);
   if (mx == -INFINITY) {  // no non-empty cluster: nothing selected, zero output
@@ -383,7 +481,7 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(SelectArgs a) {
       a.out.n_retained[head] = 0;
       a.out.n_exact_tokens[head] = 0;
       if (plan) {
-        row_start[0] = 0;
+        emit.row_start[0] = 0;
         a.plan.head_rows[head] = 0;
         a.plan.done[head] = 0;
       }
@@ -393,157 +491,260 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(SelectArgs a) {
     return;
   }
 
-  // ---- level-1 mass histogram ---------------------------------------------
+  // ---- total mass; how many clusters are close to the top ------------------
+  u64 wsum = 0;
+  int ctop = 0;
 #pragma unroll
   for (int e = 0; e < E; ++e) {
     const float d = mx - l[e];
     if (d < kCut) {
-      const u64 m = fx_mass(d);
-      if (m) atomicAdd(&sh.hist[level1_bin(d)], m);
+      wsum += fx_mass(d);
+      ctop += d < kTopCut;
     }
   }
-  __syncthreads();
-  DP_MARK(2);
-  const u64 h0 = sh.hist[2 * tid], h1 = sh.hist[2 * tid + 1];
-  u64 W;  // total mass, >= 2^40: the max element has weight 1
-  const u64 ex = block_excl_scan<u64, kSelWaves>(h0 + h1, sh.scr64, W);
-
-  DP_MARK(3);
-  // ---- the two thresholds -------------------------------------------------
-  uint32_t key1, key2;
-  int idx1, idx2;
-  u64 mass1;
-  int cached_bin = -1, cached_cnt = 0;
-  u64 cached_before = 0;
-  if (a.p1 >= 1.0f) {  // every non-empty cluster
-    key1 = kKeyLowestFinite;
-    idx1 = INT_MAX;
-    mass1 = W;
-  } else {
-    u64 tau = (u64)ceil((double)a.p1 * (double)W);
-    tau = tau < 1 ? 1 : (tau > W ? W : tau);
-    find_prefix<E>(l, mx, base, tau, ex, h0, h1, 0, sh, cached_bin, cached_cnt, cached_before, key1, idx1, mass1);
-  }
-  DP_MARK(4);
-  if (a.p2 >= 1.0f) {
-    key2 = key1;
-    idx2 = idx1;
-  } else if (a.p2 <= 0.0f) {  // nothing is exact
-    key2 = 0xffffffffu;
-    idx2 = -1;
-  } else {
-    u64 tau = a.p2_absolute ? (u64)ceil((double)a.p2 * (double)W) : (u64)ceil((double)a.p2 * (double)mass1);
-    tau = tau < 1 ? 1 : (tau > mass1 ? mass1 : tau);
-    u64 mass2;
-    __syncthreads();  // sh.bin / sh.res_* of the first search have been read by every thread
-    find_prefix<E>(l, mx, base, tau, ex, h0, h1, 1, sh, cached_bin, cached_cnt, cached_before, key2, idx2, mass2);
-  }
-
-  DP_MARK(5);
-  // ---- compaction in ascending cluster index ------------------------------
-  // With p1 < 1 only clusters with non-zero mass can be selected; with p1 = 1 all non-empty ones are.
-  const bool all = a.p1 >= 1.0f;
-  u64 exa_mask = 0, ret_mask = 0;  // bit e: element e of this thread is exact / approximated
-  int sz[E], off[E];
-#pragma unroll
-  for (int e = 0; e < E; ++e) {
-    sz[e] = 0;
-    off[e] = 0;
-    if (!(all ? l[e] != -INFINITY : mx - l[e] < kCut)) continue;
-    const uint32_t k = ordered_key(l[e]);
-    const int i = base + e;
-    if (k > key2 || (k == key2 && i <= idx2)) {
-      exa_mask |= 1ull << e;
-      sz[e] = a.cluster_sizes[c0 + i];  // loads are issued here and consumed after the loop
-      if (plan) off[e] = a.cluster_offsets[c0 + i];
-    } else if (k > key1 || (k == key1 && i <= idx1)) {
-      ret_mask |= 1ull << e;
-    }
-  }
-  const int ce = __popcll(exa_mask), ca = __popcll(ret_mask);
-  int te = 0;
-#pragma unroll
-  for (int e = 0; e < E; ++e) te += sz[e];
-  DP_MARK(6);
-  int n_ex, n_ap, n_tok;
-  int pe, pa, pt;
+  int ntop;
+  u64 W;  // >= 2^40: the max element has weight 1
   {
-    // one scan for the three counters
-    int ie = ce, ia = ca, it = te;
-    const int lane = lane_id(), w = wave_id();
-#pragma unroll
-    for (int d = 1; d < 64; d <<= 1) {
-      const int oe = __shfl_up(ie, d, 64), oa = __shfl_up(ia, d, 64), ot = __shfl_up(it, d, 64);
-      if (lane >= d) {
-        ie += oe;
-        ia += oa;
-        it += ot;
-      }
-    }
-    if (lane == 63) {
-      sh.scri[w] = ie;
-      sh.scri[kSelWaves + w] = ia;
-      sh.scri[2 * kSelWaves + w] = it;
+    wsum = wave_sum(wsum);
+    ctop = wave_sum(ctop);
+    if (lane_id() == 0) {
+      sh.scr64[wave_id()] = wsum;
+      sh.scri[wave_id()] = ctop;
     }
     __syncthreads();
-    int be = 0, ba = 0, bt = 0;
-    n_ex = n_ap = n_tok = 0;
+    W = 0;
+    ntop = 0;
 #pragma unroll
-    for (int v = 0; v < kSelWaves; ++v) {
-      const int se = sh.scri[v], sa = sh.scri[kSelWaves + v], st = sh.scri[2 * kSelWaves + v];
-      if (v < w) {
-        be += se;
-        ba += sa;
-        bt += st;
-      }
-      n_ex += se;
-      n_ap += sa;
-      n_tok += st;
+    for (int w = 0; w < kSelWaves; ++w) {
+      W += sh.scr64[w];
+      ntop += sh.scri[w];
     }
-    pe = be + ie - ce;
-    pa = ba + ia - ca;
-    pt = bt + it - te;
   }
-  DP_MARK(7);
-  const int R = n_tok + n_ap;
-  const bool inline_attn = can_inline && R <= kInlineRows;
+  DP_MARK(2);
 
-  if (ce + ca > 0) {
+  int n_ex, n_ap, n_tok;
+  bool fast = a.p1 < 1.0f && ntop <= kTopMax;
+  if (fast) {
+    // ---- fast path: the retained set lies inside the top set (the usual case for a peaked
+    // head).  Gather the top set with its sizes / offsets, then one wave ranks it pairwise. ----
 #pragma unroll
     for (int e = 0; e < E; ++e) {
+      const float d = mx - l[e];
+      if (d < kTopCut) {
+        const int s = atomicAdd(&sh.ntop, 1);
+        const int i = base + e;
+        sh.top_key[s] = ordered_key(l[e]);
+        sh.top_idx[s] = i;
+        sh.top_m[s] = fx_mass(d);
+        sh.top_sz[s] = kPre ? psz[kPre ? e : 0] : a.cluster_sizes[c0 + i];
+        sh.top_off[s] = !plan ? 0 : kPre ? poff[kPre ? e : 0] : a.cluster_offsets[c0 + i];
+      }
+    }
+    __syncthreads();
+    if (wave_id() == 0) {
+      const int i = lane_id();
+      const bool act = i < ntop;
+      const uint32_t key_i = act ? sh.top_key[i] : 0u;
+      const int idx_i = act ? sh.top_idx[i] : INT_MAX;
+      const u64 m_i = act ? sh.top_m[i] : 0;
+      const int sz_i = act ? sh.top_sz[i] : 0;
+      u64 ahead = 0;  // mass of the clusters that precede cluster i in the order
+      for (int j = 0; j < ntop; ++j) {
+        const uint32_t kj = sh.top_key[j];
+        if (kj > key_i || (kj == key_i && sh.top_idx[j] < idx_i)) ahead += sh.top_m[j];
+      }
+      const u64 top_mass = wave_sum(m_i);
+      u64 tau1 = (u64)ceil((double)a.p1 * (double)W);
+      tau1 = tau1 < 1 ? 1 : (tau1 > W ? W : tau1);
+      const bool ok = top_mass >= tau1;  // otherwise the prefix reaches below the top set
+      if (ok) {
+        const bool ret = act && ahead < tau1;
+        u64 m1 = ret ? ahead + m_i : 0;  // mass of the retained prefix = the largest inclusive prefix
+#pragma unroll
+        for (int d = 32; d >= 1; d >>= 1) {
+          const u64 o = __shfl_xor(m1, d, 64);
+          m1 = o > m1 ? o : m1;
+        }
+        bool exa;
+        if (a.p2 >= 1.0f) {
+          exa = ret;
+        } else if (a.p2 <= 0.0f) {
+          exa = false;
+        } else {
+          u64 tau2 = a.p2_absolute ? (u64)ceil((double)a.p2 * (double)W) : (u64)ceil((double)a.p2 * (double)m1);
+          tau2 = tau2 < 1 ? 1 : (tau2 > m1 ? m1 : tau2);
+          exa = act && ahead < tau2;
+        }
+        const bool apx = ret && !exa;
+        const u64 exa_mask = __ballot(exa), apx_mask = __ballot(apx);
+        n_ex = __popcll(exa_mask);
+        n_ap = __popcll(apx_mask);
+        n_tok = wave_sum(exa ? sz_i : 0);
+        // position of cluster i in its list = selected clusters with a smaller index
+        int pe = 0, pa = 0, pt = 0;
+        for (int j = 0; j < ntop; ++j) {
+          const bool before = sh.top_idx[j] < idx_i;
+          if ((exa_mask >> j) & 1) {
+            pe += before;
+            pt += before ? sh.top_sz[j] : 0;
+          } else if ((apx_mask >> j) & 1) {
+            pa += before;
+          }
+        }
+        const int R = n_tok + n_ap;
+        emit.to_lds = can_inline && R <= kInlineRows;
+        emit.n_ex = n_ex;
+        emit.n_tok = n_tok;
+        if (exa) emit.exact(pe, pt, sz_i, sh.top_off[i], idx_i);
+        if (apx) emit.approx(pa, idx_i);
+        if (i == 0) {
+          sh.f_nex = n_ex;
+          sh.f_nap = n_ap;
+          sh.f_ntok = n_tok;
+        }
+      }
+      if (i == 0) sh.fast_ok = ok;
+    }
+    __syncthreads();
+    fast = sh.fast_ok;
+    n_ex = sh.f_nex;
+    n_ap = sh.f_nap;
+    n_tok = sh.f_ntok;
+  }
+  DP_MARK(3);
+
+  if (!fast) {
+    // ---- general path: level-1 mass histogram, scan, threshold search ---------
+#pragma unroll
+    for (int e = 0; e < E; ++e) {
+      const float d = mx - l[e];
+      if (d < kCut) {
+        const u64 m = fx_mass(d);
+        if (m) atomicAdd(&sh.hist[level1_bin(d)], m);
+      }
+    }
+    __syncthreads();
+    const u64 h0 = sh.hist[2 * tid], h1 = sh.hist[2 * tid + 1];
+    u64 Wh;  // equals W: the same masses, summed in another order
+    const u64 ex = block_excl_scan<u64, kSelWaves>(h0 + h1, sh.scr64, Wh);
+
+    uint32_t key1, key2;
+    int idx1, idx2;
+    u64 mass1;
+    int cached_bin = -1, cached_cnt = 0;
+    u64 cached_before = 0;
+    if (a.p1 >= 1.0f) {  // every non-empty cluster
+      key1 = kKeyLowestFinite;
+      idx1 = INT_MAX;
+      mass1 = W;
+    } else {
+      u64 tau = (u64)ceil((double)a.p1 * (double)W);
+      tau = tau < 1 ? 1 : (tau > W ? W : tau);
+      find_prefix<E>(l, mx, base, tau, ex, h0, h1, 0, sh, cached_bin, cached_cnt, cached_before, key1, idx1, mass1);
+    }
+    if (a.p2 >= 1.0f) {
+      key2 = key1;
+      idx2 = idx1;
+    } else if (a.p2 <= 0.0f) {  // nothing is exact
+      key2 = 0xffffffffu;
+      idx2 = -1;
+    } else {
+      u64 tau = a.p2_absolute ? (u64)ceil((double)a.p2 * (double)W) : (u64)ceil((double)a.p2 * (double)mass1);
+      tau = tau < 1 ? 1 : (tau > mass1 ? mass1 : tau);
+      u64 mass2;
+      __syncthreads();  // sh.bin / sh.res_* of the first search have been read by every thread
+      find_prefix<E>(l, mx, base, tau, ex, h0, h1, 1, sh, cached_bin, cached_cnt, cached_before, key2, idx2, mass2);
+    }
+
+    // ---- compaction in ascending cluster index ------------------------------
+    // With p1 < 1 only clusters with non-zero mass can be selected; with p1 = 1 all non-empty ones are.
+    const bool all = a.p1 >= 1.0f;
+    u64 exa_mask = 0, ret_mask = 0;  // bit e: element e of this thread is exact / approximated
+    int sz[E], off[E];
+#pragma unroll
+    for (int e = 0; e < E; ++e) {
+      const uint32_t k = ordered_key(l[e]);
       const int i = base + e;
-      if ((exa_mask >> e) & 1) {
-        sel[pe] = i;
-        if (plan) {
-          if (inline_attn) {
-            sh.l_start[pe] = pt;
-            sh.l_src[pe] = off[e];
-          } else {
-            ent_src[pe] = off[e];
-            row_start[pe] = pt;
-            for (int q = (pt + kChunkRows - 1) / kChunkRows; q * kChunkRows < pt + sz[e]; ++q) chunk_entry[q] = pe;
-          }
+      const bool in_play = all ? l[e] != -INFINITY : mx - l[e] < kCut;
+      const bool exa = in_play && (k > key2 || (k == key2 && i <= idx2));
+      const bool apx = in_play && !exa && (k > key1 || (k == key1 && i <= idx1));
+      exa_mask |= (u64)exa << e;
+      ret_mask |= (u64)apx << e;
+      if (kPre) {
+        sz[e] = exa ? psz[kPre ? e : 0] : 0;
+        off[e] = exa ? poff[kPre ? e : 0] : 0;
+      } else {
+        sz[e] = 0;
+        off[e] = 0;
+        if (exa) {  // loads are issued here and consumed after the loop
+          sz[e] = a.cluster_sizes[c0 + i];
+          if (plan) off[e] = a.cluster_offsets[c0 + i];
         }
-        ++pe;
-        pt += sz[e];
-      } else if ((ret_mask >> e) & 1) {
-        const int j = n_ex + pa;
-        sel[j] = i;
-        if (plan) {
-          const int row = n_tok + pa;
-          if (inline_attn) {
-            sh.l_start[j] = row;
-            sh.l_src[j] = i;
-          } else {
-            ent_src[j] = i;
-            row_start[j] = row;
-            if (row % kChunkRows == 0) chunk_entry[row / kChunkRows] = j;
-          }
+      }
+    }
+    const int ce = __popcll(exa_mask), ca = __popcll(ret_mask);
+    int te = 0;
+#pragma unroll
+    for (int e = 0; e < E; ++e) te += sz[e];
+    int pe, pa, pt;
+    {
+      // one scan for the three counters
+      int ie = ce, ia = ca, it = te;
+      const int lane = lane_id(), w = wave_id();
+#pragma unroll
+      for (int d = 1; d < 64; d <<= 1) {
+        const int oe = __shfl_up(ie, d, 64), oa = __shfl_up(ia, d, 64), ot = __shfl_up(it, d, 64);
+        if (lane >= d) {
+          ie += oe;
+          ia += oa;
+          it += ot;
         }
-        ++pa;
+      }
+      if (lane == 63) {
+        sh.scri[w] = ie;
+        sh.scri[kSelWaves + w] = ia;
+        sh.scri[2 * kSelWaves + w] = it;
+      }
+      __syncthreads();
+      int be = 0, ba = 0, bt = 0;
+      n_ex = n_ap = n_tok = 0;
+#pragma unroll
+      for (int v = 0; v < kSelWaves; ++v) {
+        const int se = sh.scri[v], sa = sh.scri[kSelWaves + v], st = sh.scri[2 * kSelWaves + v];
+        if (v < w) {
+          be += se;
+          ba += sa;
+          bt += st;
+        }
+        n_ex += se;
+        n_ap += sa;
+        n_tok += st;
+      }
+      pe = be + ie - ce;
+      pa = ba + ia - ca;
+      pt = bt + it - te;
+    }
+    emit.to_lds = can_inline && n_tok + n_ap <= kInlineRows;
+    emit.n_ex = n_ex;
+    emit.n_tok = n_tok;
+    if (ce + ca > 0) {
+#pragma unroll
+      for (int e = 0; e < E; ++e) {
+        if ((exa_mask >> e) & 1) {
+          emit.exact(pe, pt, sz[e], off[e], base + e);
+          ++pe;
+          pt += sz[e];
+        } else if ((ret_mask >> e) & 1) {
+          emit.approx(pa, base + e);
+          ++pa;
+        }
       }
     }
   }
+  DP_MARK(4);
+
+  const int R = n_tok + n_ap;
+  const bool inline_attn = can_inline && R <= kInlineRows;
   if (tid == 0) {
     a.out.n_exact[head] = n_ex;
     a.out.n_retained[head] = n_ex + n_ap;
@@ -553,45 +754,43 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(SelectArgs a) {
         sh.l_start[n_ex + n_ap] = R;
         a.plan.head_rows[head] = -1;  // attended here: nothing left for the decode kernel
       } else {
-        row_start[n_ex + n_ap] = R;
+        emit.row_start[n_ex + n_ap] = R;
         a.plan.head_rows[head] = R;
       }
       a.plan.done[head] = 0;
     }
   }
-  DP_MARK(8);
   if (!inline_attn) return;
 
   // ---- inline attention for a head with few rows ---------------------------
   __syncthreads();
+  DP_MARK(5);
   {
     const int lane16 = tid & 15, grp = tid >> 4;
-    float qf[8];
-    unpack8(load_row_slice(a.q, (int64_t)head, lane16), qf);
-#pragma unroll
-    for (int i = 0; i < 8; ++i) qf[i] *= a.scale_log2;
+    const uint4 qv = load_row_slice(a.q, (int64_t)head, lane16);
     RowSources src;
     src.k_cache = a.k_cache;
     src.v_cache = a.v_cache;
     src.k_centroids = a.k_centroids;
     src.v_centroids = a.v_centroids;
     src.seg_sizes = a.cluster_sizes + c0;
-    src.seg_row0 = a.seg_row_base[seg];
+    src.seg_row0 = seg_row0;
     src.c0 = c0;
     RowState st;
     row_state_init(st);
     constexpr int kGroups = kSelThreads / 16;
     const int per = kAttendBatch * ((R + kGroups * kAttendBatch - 1) / (kGroups * kAttendBatch));
     const int ra = grp * per, rb = min(R, ra + per);
-    attend_rows(st, qf, src, sh.l_start, sh.l_src, n_ex + n_ap, 0, n_ex, ra, rb, lane16);
-    DP_MARK(9);
+    attend_rows(st, qv, a.scale_log2, src, sh.l_start, sh.l_src, n_ex + n_ap, 0, n_ex, ra, rb, lane16);
+    DP_MARK(6);
     float M, L, o;
-    block_merge<kSelWaves>(st, sh.m_m, sh.m_l, sh.m_acc, M, L, o);
-    DP_MARK(10);
+    const int groups_used = (R + per - 1) / per;
+    block_merge<kSelWaves>(st, sh.m_m, sh.m_l, sh.m_acc, (groups_used + 3) / 4, M, L, o);
     if (tid < kHeadDim) {
       store_out(a.attn_out, a.out_is_bf16, head, tid, o / L);
       if (a.lse && tid == 0) a.lse[head] = (M + log2f(L)) * kLn2;
     }
+    DP_MARK(7);
   }
 }
 
