@@ -21,6 +21,8 @@ consumers (the fp64 CPU oracle, the HIP library) want the raw stored bits.
 """
 from __future__ import annotations
 
+import os
+from concurrent.futures import ThreadPoolExecutor
 from dataclasses import dataclass, field
 from typing import Dict, List, Optional, Sequence
 
@@ -222,34 +224,49 @@ def make_cache(*, batch: int, n_kv_heads: int, n_q_heads: int, context: Sequence
     q = np.empty((batch, n_q_heads, d), dtype=np.uint16)
     scales = np.empty((batch, n_q_heads), dtype=np.float64)
 
+    # every segment has its own random stream, so segments can be drawn by a thread pool
+    # (numpy releases the GIL while it draws) without changing a single value
+    row_of, cl_of = [], []
     row, cl = 0, 0
     for b in range(batch):
         for g in range(n_kv_heads):
-            seg = b * n_kv_heads + g
-            rng = np.random.default_rng(np.random.SeedSequence([seed, tag, b, g]))
-            s = make_segment(rng, ctx[b], ncl[b], size_dist, float(mean_cluster), size_lo, size_hi, d,
-                             key_spread=key_spread)
-            n, k = ctx[b], ncl[b]
-            seg_row_base[seg] = row
-            seg_cluster_ptr[seg] = cl
-            k_cache[row:row + n] = s["k"]
-            v_cache[row:row + n] = s["v"]
-            kc[cl:cl + k] = s["kc"]
-            vc[cl:cl + k] = s["vc"]
-            offsets[cl:cl + k] = s["offsets"]
-            sizes[cl:cl + k] = s["sizes"]
-            for j in range(G):
-                h = g * G + j
-                if callable(q_scale):
-                    sc = float(q_scale(rng, b, h))
-                elif np.isscalar(q_scale):
-                    sc = float(q_scale)
-                else:
-                    sc = float(q_scale[h])
-                scales[b, h] = sc
-                q[b, h] = draw_query(rng, s["centres"], sc)
-            row += n
-            cl += k
+            row_of.append(row)
+            cl_of.append(cl)
+            row += ctx[b]
+            cl += ncl[b]
+
+    def draw(seg):
+        b, g = divmod(seg, n_kv_heads)
+        rng = np.random.default_rng(np.random.SeedSequence([seed, tag, b, g]))
+        s = make_segment(rng, ctx[b], ncl[b], size_dist, float(mean_cluster), size_lo, size_hi, d,
+                         key_spread=key_spread)
+        n, k, r0, c0 = ctx[b], ncl[b], row_of[seg], cl_of[seg]
+        seg_row_base[seg] = r0
+        seg_cluster_ptr[seg] = c0
+        k_cache[r0:r0 + n] = s["k"]
+        v_cache[r0:r0 + n] = s["v"]
+        kc[c0:c0 + k] = s["kc"]
+        vc[c0:c0 + k] = s["vc"]
+        offsets[c0:c0 + k] = s["offsets"]
+        sizes[c0:c0 + k] = s["sizes"]
+        for j in range(G):
+            h = g * G + j
+            if callable(q_scale):
+                sc = float(q_scale(rng, b, h))
+            elif np.isscalar(q_scale):
+                sc = float(q_scale)
+            else:
+                sc = float(q_scale[h])
+            scales[b, h] = sc
+            q[b, h] = draw_query(rng, s["centres"], sc)
+
+    workers = min(n_seg, max(1, min(16, os.cpu_count() or 1)))
+    if workers > 1 and tot_rows >= (1 << 18):
+        with ThreadPoolExecutor(max_workers=workers) as pool:
+            list(pool.map(draw, range(n_seg)))
+    else:
+        for seg in range(n_seg):
+            draw(seg)
     seg_cluster_ptr[n_seg] = cl
     return ClusteredCache(batch=batch, n_kv_heads=n_kv_heads, n_q_heads=n_q_heads, head_dim=d, q=q,
                           k_cache=k_cache, v_cache=v_cache, seg_row_base=seg_row_base,
