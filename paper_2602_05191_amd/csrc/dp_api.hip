@@ -56,10 +56,14 @@ dp::CacheView view_of(const dp_problem *p) {
   return c;
 }
 
-// stage-3 splits per head: aim at a few thousand workgroups in total
+// stage-3 splits per head: aim at several thousand workgroups in total, many more than the 256 CUs can
+// hold at once, so that the last round of workgroups is short against the whole
+#ifndef DP_SPLIT_TARGET
+#define DP_SPLIT_TARGET 8192
+#endif
 int choose_splits(const dp_problem *p) {
   const long nh = (long)p->batch * p->n_q_heads;
-  long s = (4096 + nh - 1) / nh;
+  long s = (DP_SPLIT_TARGET + nh - 1) / nh;
   const long by_rows = ((long)p->max_rows_per_seg + p->max_clusters_per_seg + dp::kChunkRows - 1) / dp::kChunkRows;
   if (s > by_rows) s = by_rows;
   if (s > 256) s = 256;

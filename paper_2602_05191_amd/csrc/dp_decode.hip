@@ -124,34 +124,38 @@ __global__ __launch_bounds__(kDecThreads) void decode_kernel(DecodeArgs a) {
     return;
   }
 
+  // Partials are exchanged through device-coherent (agent-scope) stores and loads, which go
+  // straight to memory: no L2 write-back or invalidate of the whole cache is needed around the
+  // arrival counter, only "my stores have completed" before the ticket is taken.
   float *P = a.partials + (int64_t)head * a.splits * kPartialStride;
   if (tid < kHeadDim) {
     float *mine = P + (int64_t)split * kPartialStride;
     if (tid == 0) {
-      mine[0] = M;
-      mine[1] = L;
+      __hip_atomic_store(mine + 0, M, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      __hip_atomic_store(mine + 1, L, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
-    mine[2 + tid] = o;
+    __hip_atomic_store(mine + 2 + tid, o, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   }
-  // The split that arrives last merges all partials of the head (log-sum-exp merge).
-  __threadfence();
+  __builtin_amdgcn_s_waitcnt(0);  // all of this thread's memory operations have completed
   __syncthreads();
+  // The split that arrives last merges all partials of the head (log-sum-exp merge).
   if (tid == 0) {
-    const int ticket = __hip_atomic_fetch_add(&a.plan.done[head], 1, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
+    const int ticket = __hip_atomic_fetch_add(&a.plan.done[head], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     s_last = (ticket == n_active - 1);
   }
   __syncthreads();
   if (!s_last) return;
-  __threadfence();
   if (tid < kHeadDim) {
     float Mx = -INFINITY;
-    for (int s2 = 0; s2 < n_active; ++s2) Mx = fmaxf(Mx, __builtin_nontemporal_load(P + s2 * kPartialStride));
+    for (int s2 = 0; s2 < n_active; ++s2)
+      Mx = fmaxf(Mx, __hip_atomic_load(P + s2 * kPartialStride, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
     float Ls = 0.f, os = 0.f;
     for (int s2 = 0; s2 < n_active; ++s2) {
-      const float ms = __builtin_nontemporal_load(P + s2 * kPartialStride);
+      const float *Q = P + s2 * kPartialStride;
+      const float ms = __hip_atomic_load(Q, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
       const float w = exp2f(ms - Mx);
-      Ls += __builtin_nontemporal_load(P + s2 * kPartialStride + 1) * w;
-      os += __builtin_nontemporal_load(P + s2 * kPartialStride + 2 + tid) * w;
+      Ls += __hip_atomic_load(Q + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) * w;
+      os += __hip_atomic_load(Q + 2 + tid, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) * w;
     }
     store_out(a.out, a.out_is_bf16, head, tid, os / Ls);
     if (a.lse && tid == 0) a.lse[head] = (Mx + log2f(Ls)) * kLn2;
