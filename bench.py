@@ -73,6 +73,19 @@ def algorithmic_bytes(cache, sel, n_exact, n_retained):
                 total_per_head_sum=scan + rows_sum * 2 * d2 + io)
 
 
+def measured_traffic(config):
+    """HBM bytes per launch of the scoring kernel from the committed rocprofv3 counter summary
+    (FETCH_SIZE and WRITE_SIZE, scaled by what a plain copy of known size reads); None if there is none."""
+    path = os.path.join(ROOT, "profiles", f"score_kernel_cfg{config}.txt")
+    try:
+        for line in open(path):
+            if line.startswith("traffic_bytes_per_launch"):
+                return int(float(line.split("=")[1].split()[0]))
+    except OSError:
+        pass
+    return None
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -168,7 +181,31 @@ def main():
             runs.append(a.elapsed_time(b) * 1e3 / n_stage)
         return statistics.mean(runs), statistics.median(runs)
 
-    score_us, score_med = time_stage(lambda i: dp.dp_score_centroids(probs[i % L], logits))
+    score_gap_us, _ = time_stage(lambda i: dp.dp_score_centroids(probs[i % L], logits))
+
+    # The scoring kernel's own duration: every launch carries a pair of HIP events that the runtime stamps
+    # with the kernel's begin and end (dp_score_centroids_timed), launched back-to-back on the same stream.
+    import ctypes
+    hip = ctypes.CDLL("libamdhip64.so")
+    pairs = []
+    for _ in range(n_stage):
+        e0, e1 = ctypes.c_void_p(), ctypes.c_void_p()
+        assert hip.hipEventCreate(ctypes.byref(e0)) == 0 and hip.hipEventCreate(ctypes.byref(e1)) == 0
+        pairs.append((e0, e1))
+    for i in range(50):
+        dp.dp_score_centroids(probs[i % L], logits)
+    torch.cuda.synchronize()
+    for i, (e0, e1) in enumerate(pairs):
+        dp.dp_score_centroids_timed(probs[i % L], logits, e0, e1)
+    torch.cuda.synchronize()
+    durs = []
+    for e0, e1 in pairs:
+        ms = ctypes.c_float()
+        assert hip.hipEventElapsedTime(ctypes.byref(ms), e0, e1) == 0
+        durs.append(ms.value * 1e3)
+        hip.hipEventDestroy(e0)
+        hip.hipEventDestroy(e1)
+    score_us, score_med = statistics.mean(durs), statistics.median(durs)
     select_us, select_med = time_stage(lambda i: dp.dp_topp_select(probs[i % L], logits, p1, p2, sel_d, ne, nr, nt))
     decode_us, decode_med = time_stage(lambda i: dp.dp_sparse_decode(probs[i % L], sel_d, ne, nr, out, lse, ws))
 
@@ -226,9 +263,11 @@ def main():
             "peak": HBM_PEAK_GBS,
             "unit": "GB/s",
             "frac": round(score_gbs / HBM_PEAK_GBS, 4),
-            "traffic": None,
+            "traffic": measured_traffic(args.config),
             "bytes_per_launch": score_bytes,
             "avg_launch_us": round(score_us, 3),
+            "median_launch_us": round(score_med, 3),
+            "back_to_back_interval_us": round(score_gap_us, 3),
         },
         "gen_seconds": round(t_gen, 1),
     }

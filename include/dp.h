@@ -86,6 +86,13 @@ size_t dp_logits_count(const dp_problem *problem);
  * read once and scored against the G query heads that share it. */
 dp_status dp_score_centroids(const dp_problem *problem, float *logits, void *stream);
 
+/* dp_score_centroids for measurement: start_event / stop_event (hipEvent_t passed as void*, created by the
+ * caller with timing enabled, either may be NULL) receive the begin and end timestamps of the scoring kernel
+ * itself (not of the gap before it), so hipEventElapsedTime(start, stop) after the stream has drained is the
+ * kernel's duration.  Same result and errors as dp_score_centroids. */
+dp_status dp_score_centroids_timed(const dp_problem *problem, float *logits, void *stream, void *start_event,
+                                   void *stop_event);
+
 /* Stage 2 (Eq. 6 softmax, Eq. 7 first top-p, Sec. 4.3 second top-p).  Per head:
  * clusters are ordered by logit descending, ties by lower cluster index; the
  * retained set is the shortest prefix whose softmax mass reaches p1 (all

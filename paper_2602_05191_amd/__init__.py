@@ -10,6 +10,7 @@ from .binding import (  # noqa: F401
     Problem,
     dp_decode_attention,
     dp_score_centroids,
+    dp_score_centroids_timed,
     dp_sparse_decode,
     dp_topp_select,
     dp_workspace_bytes,

@@ -22,6 +22,7 @@ _PKG = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_PKG, "libdp_hip.so")
 
 EXPORTS = ["dp_workspace_bytes", "dp_logits_count", "dp_get_workspace_layout", "dp_score_centroids",
+           "dp_score_centroids_timed",
            "dp_topp_select", "dp_sparse_decode", "dp_decode_attention", "dp_status_string"]
 
 
@@ -72,6 +73,8 @@ def load_library():
     L.dp_get_workspace_layout.argtypes = [PP, C.POINTER(_Layout)]
     L.dp_score_centroids.restype = I
     L.dp_score_centroids.argtypes = [PP, V, V]
+    L.dp_score_centroids_timed.restype = I
+    L.dp_score_centroids_timed.argtypes = [PP, V, V, V, V]
     L.dp_topp_select.restype = I
     L.dp_topp_select.argtypes = [PP, V, F, F, V, V, V, V, V]
     L.dp_sparse_decode.restype = I
@@ -182,6 +185,13 @@ def dp_score_centroids(problem: Problem, logits: torch.Tensor, stream=None) -> N
     L = load_library()
     assert logits.dtype == torch.float32 and logits.is_contiguous() and logits.numel() >= L.dp_logits_count(problem.ref)
     _check(L.dp_score_centroids(problem.ref, _ptr(logits), _stream(stream)), "dp_score_centroids")
+
+
+def dp_score_centroids_timed(problem: Problem, logits: torch.Tensor, start_event: int, stop_event: int,
+                             stream=None) -> None:
+    """start_event / stop_event: raw hipEvent_t handles (ints) that receive the kernel's own timestamps."""
+    _check(load_library().dp_score_centroids_timed(problem.ref, _ptr(logits), _stream(stream), start_event,
+                                                   stop_event), "dp_score_centroids_timed")
 
 
 def dp_topp_select(problem: Problem, logits: torch.Tensor, p1: float, p2: float, sel_ids: torch.Tensor,

@@ -170,6 +170,18 @@ dp_status dp_score_centroids(const dp_problem *problem, float *logits, void *str
                                                                                                    : DP_ERR_HIP;
 }
 
+dp_status dp_score_centroids_timed(const dp_problem *problem, float *logits, void *stream, void *start_event,
+                                   void *stop_event) {
+  dp_status st = check_common(problem);
+  if (st != DP_OK) return st;
+  if (!logits && problem->total_clusters > 0) return DP_ERR_INVALID_ARG;
+  if (problem->total_clusters == 0) return DP_OK;
+  return dp::launch_score(view_of(problem), logits, static_cast<hipStream_t>(stream),
+                          static_cast<hipEvent_t>(start_event), static_cast<hipEvent_t>(stop_event)) == hipSuccess
+             ? DP_OK
+             : DP_ERR_HIP;
+}
+
 dp_status dp_topp_select(const dp_problem *problem, const float *logits, float p1, float p2, int32_t *sel_ids,
                          int32_t *n_exact, int32_t *n_retained, int32_t *n_exact_tokens, void *stream) {
   dp_status st = check_common(problem);

@@ -46,7 +46,9 @@ struct SelectOut {
   int32_t *n_exact, *n_retained, *n_exact_tokens;  // [nh]
 };
 
-hipError_t launch_score(const CacheView &c, float *logits, hipStream_t s);
+// start / stop (nullable): HIP events that receive the kernel's own begin and end timestamps
+hipError_t launch_score(const CacheView &c, float *logits, hipStream_t s, hipEvent_t start = nullptr,
+                        hipEvent_t stop = nullptr);
 
 // plan.ent_src == nullptr => no plan is written
 // With a plan and attn.out != nullptr, heads with few rows are attended inside the selection kernel.

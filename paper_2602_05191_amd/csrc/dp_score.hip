@@ -8,6 +8,8 @@
 // lane, global_load_dwordx4); each lane's 8 products are accumulated by the
 // packed bf16 dot instruction and the 16 partial dots are summed with DPP adds.
 // Algorithmic traffic per cluster: 256 B centroid + 4 B size read, 4*G B written.
+#include <hip/hip_ext.h>
+
 #include "dp_device.hpp"
 #include "dp_kernels.hpp"
 
@@ -104,7 +106,15 @@ __global__ __launch_bounds__(kScoreThreads) void score_kernel(ScoreArgs a) {
 
 }  // namespace
 
-hipError_t launch_score(const CacheView &c, float *logits, hipStream_t s) {
+template <int GH>
+void launch_one(const ScoreArgs &a, dim3 grid, hipStream_t s, hipEvent_t start, hipEvent_t stop) {
+  if (start || stop)
+    hipExtLaunchKernelGGL(score_kernel<GH>, grid, dim3(kScoreThreads), 0, s, start, stop, 0, a);
+  else
+    hipLaunchKernelGGL(score_kernel<GH>, grid, dim3(kScoreThreads), 0, s, a);
+}
+
+hipError_t launch_score(const CacheView &c, float *logits, hipStream_t s, hipEvent_t start, hipEvent_t stop) {
   ScoreArgs a;
   a.q = c.q;
   a.k_centroids = c.k_centroids;
@@ -124,11 +134,13 @@ hipError_t launch_score(const CacheView &c, float *logits, hipStream_t s) {
     const int left = c.group - h0;
     const int gh = left >= 8 ? 8 : left >= 4 ? 4 : left >= 2 ? 2 : 1;
     a.head0 = h0;
+    // with several passes the events bracket the first pass's begin and the last pass's end
+    hipEvent_t ev0 = (h0 == 0) ? start : nullptr, ev1 = (h0 + gh >= c.group) ? stop : nullptr;
     switch (gh) {
-      case 8: hipLaunchKernelGGL(score_kernel<8>, grid, dim3(kScoreThreads), 0, s, a); break;
-      case 4: hipLaunchKernelGGL(score_kernel<4>, grid, dim3(kScoreThreads), 0, s, a); break;
-      case 2: hipLaunchKernelGGL(score_kernel<2>, grid, dim3(kScoreThreads), 0, s, a); break;
-      default: hipLaunchKernelGGL(score_kernel<1>, grid, dim3(kScoreThreads), 0, s, a); break;
+      case 8: launch_one<8>(a, grid, s, ev0, ev1); break;
+      case 4: launch_one<4>(a, grid, s, ev0, ev1); break;
+      case 2: launch_one<2>(a, grid, s, ev0, ev1); break;
+      default: launch_one<1>(a, grid, s, ev0, ev1); break;
     }
     h0 += gh;
   }

@@ -289,3 +289,28 @@ def test_boundary_rejects_bad_arguments():
         dp.dp_score_centroids(bad, torch.empty(4 * 64, dtype=torch.float32, device="cuda:0"))
     assert e.value.status == -1
     torch.cuda.synchronize()
+
+
+def test_score_centroids_timed_stamps_the_kernel():
+    """The measurement entry point gives the same logits and a plausible kernel duration."""
+    import ctypes
+    import torch
+    import paper_2602_05191_amd as dp
+    c = make_config(1, shrink=4)
+    dc = dp.DeviceCache.from_host(c)
+    pr = dp.Problem(dc)
+    n = c.group * int(c.seg_cluster_ptr[-1])
+    a = torch.zeros(n, dtype=torch.float32, device="cuda:0")
+    b = torch.zeros(n, dtype=torch.float32, device="cuda:0")
+    hip = ctypes.CDLL("libamdhip64.so")
+    e0, e1 = ctypes.c_void_p(), ctypes.c_void_p()
+    assert hip.hipEventCreate(ctypes.byref(e0)) == 0 and hip.hipEventCreate(ctypes.byref(e1)) == 0
+    dp.dp_score_centroids(pr, a)
+    dp.dp_score_centroids_timed(pr, b, e0, e1)
+    torch.cuda.synchronize()
+    ms = ctypes.c_float()
+    assert hip.hipEventElapsedTime(ctypes.byref(ms), e0, e1) == 0
+    assert 0.0 < ms.value < 5.0
+    assert torch.equal(a, b)
+    hip.hipEventDestroy(e0)
+    hip.hipEventDestroy(e1)
