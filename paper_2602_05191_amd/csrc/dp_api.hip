@@ -59,7 +59,7 @@ dp::CacheView view_of(const dp_problem *p) {
 // stage-3 splits per head: aim at several thousand workgroups in total, many more than the 256 CUs can
 // hold at once, so that the last round of workgroups is short against the whole
 #ifndef DP_SPLIT_TARGET
-#define DP_SPLIT_TARGET 8192
+#define DP_SPLIT_TARGET 16384
 #endif
 int choose_splits(const dp_problem *p) {
   const long nh = (long)p->batch * p->n_q_heads;
@@ -67,6 +67,8 @@ int choose_splits(const dp_problem *p) {
   const long by_rows = ((long)p->max_rows_per_seg + p->max_clusters_per_seg + dp::kChunkRows - 1) / dp::kChunkRows;
   if (s > by_rows) s = by_rows;
   if (s > 256) s = 256;
+  if (s < 8) s = 8;
+  if (s > by_rows && by_rows >= 1) s = by_rows;
   if (s < 1) s = 1;
   return (int)s;
 }
@@ -87,8 +89,8 @@ void layout_of(const dp_problem *p, dp_workspace_layout *L) {
   off = align_up(off + sizeof(int32_t) * nh * (mk + 1), 256);
   L->chunk_entry = off;
   off = align_up(off + sizeof(int32_t) * nh * chunk_stride, 256);
-  L->counts = off;  // n_exact, n_retained, n_exact_tokens, head_rows, done : 5 x [nh]
-  off = align_up(off + sizeof(int32_t) * 5 * nh, 256);
+  L->counts = off;  // n_exact, n_retained, n_exact_tokens, head_rows, done : 5 x [nh], then the queue counters
+  off = align_up(off + sizeof(int32_t) * (5 * nh + (nh + dp::kMaxQueueHeads - 1) / dp::kMaxQueueHeads), 256);
   L->partials = off;
   off = align_up(off + sizeof(float) * nh * (size_t)splits * (dp::kHeadDim + 2), 256);
   L->total = off;
@@ -124,6 +126,7 @@ Workspace carve(const dp_problem *p, void *ws) {
   w.n_exact_tokens = counts + 2 * nh;
   w.plan.head_rows = counts + 3 * nh;
   w.plan.done = counts + 4 * nh;
+  w.plan.queue_next = counts + 5 * nh;
   w.partials = reinterpret_cast<float *>(b + L.partials);
   w.splits = L.splits;
   return w;
@@ -190,7 +193,7 @@ dp_status dp_topp_select(const dp_problem *problem, const float *logits, float p
   if (!n_exact || !n_retained || !n_exact_tokens) return DP_ERR_INVALID_ARG;
   if (problem->max_clusters_per_seg > 0 && (!logits || !sel_ids)) return DP_ERR_INVALID_ARG;
   dp::SelectOut out{sel_ids, n_exact, n_retained, n_exact_tokens};
-  dp::Plan none{nullptr, nullptr, nullptr, nullptr, nullptr, 0};
+  dp::Plan none{nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, 0};
   dp::AttnOut nowhere{nullptr, nullptr, 0};
   return dp::launch_select(view_of(problem), logits, p1, p2, problem->flags, out, none, nowhere,
                            static_cast<hipStream_t>(stream)) == hipSuccess

@@ -38,14 +38,14 @@ struct RowSources {
   int64_t c0;                // first centroid row of the segment
 };
 
-// Attend rows [ra, rb) of the list.  s_start[0 .. n_ent] and s_src[0 .. n_ent)
+// Attend rows ra, ra+1, .., ra+B-1, then ra+stride .. (B = kAttendBatch rows per step), below rb.  s_start[0 .. n_ent] and s_src[0 .. n_ent)
 // are the staged row_start / ent_src of entries ent0 .. ent0+n_ent-1, which
 // cover [ra, rb) (s_start[0] <= ra).  Every lane of the group runs the same
 // entry walk (uniform inside the group), so nothing is exchanged between lanes
 // except the DPP sum of the dot product.
 __device__ __forceinline__ void attend_rows(RowState &st, const uint4 &qv, float scale_log2, const RowSources &src,
                                             const int *s_start, const int *s_src, int n_ent, int ent0, int n_ex,
-                                            int ra, int rb, int lane16) {
+                                            int ra, int rb, int stride, int lane16) {
   if (ra >= rb) return;
   // entry that holds row ra: largest k in [0, n_ent) with s_start[k] <= ra
   int k = 0;
@@ -57,7 +57,7 @@ __device__ __forceinline__ void attend_rows(RowState &st, const uint4 &qv, float
     }
   }
   int next_start = s_start[k + 1];
-  for (int r = ra; r < rb; r += kAttendBatch) {
+  for (int r = ra; r < rb; r += stride) {
     uint4 kraw[kAttendBatch], vraw[kAttendBatch];
     int ssz[kAttendBatch];
     bool valid[kAttendBatch], approx[kAttendBatch];
@@ -68,13 +68,17 @@ __device__ __forceinline__ void attend_rows(RowState &st, const uint4 &qv, float
       approx[u] = false;
       ssz[u] = 1;
       if (valid[u]) {
-        if (row >= next_start) {  // every entry has at least one row: advance by one
+        while (row >= next_start) {  // walk forward to the entry that holds this row
           ++k;
           next_start = s_start[k + 1];
         }
         const int s = s_src[k];
         if (ent0 + k < n_ex) {
+#ifdef DP_LAB_RANDOM_ROWS  // development aid: 32-row chunks at pseudo-random places of the segment
+          const int64_t g = src.seg_row0 + (int64_t)((((uint32_t)(row >> 5) + (uint32_t)src.c0 * 977u) * 2654435761u) >> 20) * 32 + (row & 31);
+#else
           const int64_t g = src.seg_row0 + s + (row - s_start[k]);
+#endif
           kraw[u] = load_row_slice(src.k_cache, g, lane16);
           vraw[u] = load_row_slice(src.v_cache, g, lane16);
         } else {
@@ -88,6 +92,16 @@ __device__ __forceinline__ void attend_rows(RowState &st, const uint4 &qv, float
         vraw[u] = make_uint4(0, 0, 0, 0);
       }
     }
+#ifdef DP_LAB_NOCOMPUTE  // development aid: loads only
+    {
+      uint32_t acc = 0;
+#pragma unroll
+      for (int u = 0; u < kAttendBatch; ++u) acc += (kraw[u].x ^ kraw[u].y) + (kraw[u].z ^ kraw[u].w) + (vraw[u].x ^ vraw[u].y) + (vraw[u].z ^ vraw[u].w) + ssz[u];
+      st.l += __uint_as_float(acc & 0x3fffff);
+      st.m = 0.f;
+      continue;
+    }
+#endif
     float x[kAttendBatch];
     float m_new = st.m;
 #pragma unroll

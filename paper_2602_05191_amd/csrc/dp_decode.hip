@@ -8,14 +8,19 @@
 // PLACE from the cluster-contiguous cache: no gather buffer is materialised, so
 // the traffic is the 512 B per row the method itself needs.
 //
-// Work split: head x split.  A head with R rows uses ceil(R / c) splits of
-// c = 64 * ceil(R / (64 * S)) rows; split boundaries are multiples of 64 rows
-// so the first list entry of a split comes from the plan's chunk table in O(1).
+// Work split: a head with R rows is cut into ceil(R / c) items of
+// c = 64 * max(4, ceil(R / (64 * S))) rows (S = partial slots per head); item
+// boundaries are multiples of 64 rows, so the first list entry of an item comes
+// from the plan's chunk table in O(1).  Heads differ by orders of magnitude in
+// rows and the host knows none of the counts, so the grid is a fixed number of
+// workgroups that pull items from a device-side queue: every workgroup builds
+// the same prefix of items per head in LDS from head_rows[], then claims item
+// numbers with an atomic counter until they run out (nobody waits for anybody).
 // Inside a workgroup (256 threads) each 16-lane DPP row owns one cache row per
 // load (lane t holds dims [8t, 8t+8) of K for the dot and of V for the
 // accumulation), keeps its own online-softmax state in base-2 exponent form,
 // and the states are merged through LDS.  Partials (m, l, acc[128]) go to the
-// workspace; the split of a head that finishes last (an arrival counter, no
+// workspace; the item of a head that finishes last (an arrival counter, no
 // waiting) merges them (log-sum-exp merge), normalises and writes the output.
 #include "dp_attend.hpp"
 #include "dp_device.hpp"
@@ -29,6 +34,18 @@ constexpr int kDecWaves = kDecThreads / 64;
 constexpr int kDecGroups = kDecThreads / 16;   // 16 DPP rows per workgroup
 constexpr int kDecBlockRows = 512;             // rows resolved per LDS staging round
 constexpr int kPartialStride = kHeadDim + 2;   // m, l, acc[128]
+#ifndef DP_MIN_ITEM_CHUNKS
+#define DP_MIN_ITEM_CHUNKS 8
+#endif
+constexpr int kMinItemChunks = DP_MIN_ITEM_CHUNKS;  // an item has at least this many 64-row chunks (unless the head has fewer)
+
+#ifdef DP_PHASE_CLOCKS  // development aid, never built into the library
+#define DD_MARK(i) do { if (a.dbg && threadIdx.x == 0 && blockIdx.x < 2048) a.dbg[blockIdx.x * 16 + (i)] = wall_clock64(); } while (0)
+#define DD_COUNT() do { if (a.dbg && threadIdx.x == 0 && blockIdx.x < 2048) a.dbg[blockIdx.x * 16 + 8] += 1; } while (0)
+#else
+#define DD_MARK(i) do { } while (0)
+#define DD_COUNT() do { } while (0)
+#endif
 
 struct DecodeArgs {
   const void *q, *k_cache, *v_cache, *k_centroids, *v_centroids;
@@ -40,27 +57,26 @@ struct DecodeArgs {
   void *out;
   float *lse;  // nullable
   int32_t n_kv_heads, n_q_heads, group, max_k, splits, out_is_bf16;
-  float scale_log2;  // sm_scale * log2(e)
+  int32_t head0, n_heads;  // this launch serves heads [head0, head0 + n_heads), n_heads <= kMaxQueueHeads
+  int32_t *queue_next;     // the launch's item counter (zeroed by the planner)
+  float scale_log2;        // sm_scale * log2(e)
+#ifdef DP_PHASE_CLOCKS
+  unsigned long long *dbg;
+#endif
 };
 
-// rows per split of a head with R rows (multiple of kChunkRows)
-__device__ __forceinline__ int rows_per_split(int R, int S) {
-  return kChunkRows * ((R + kChunkRows * S - 1) / (kChunkRows * S));
+// rows per item of a head with R rows (multiple of kChunkRows)
+__device__ __forceinline__ int rows_per_item(int R, int S) {
+  return kChunkRows * max(kMinItemChunks, (R + kChunkRows * S - 1) / (kChunkRows * S));
 }
 
-__global__ __launch_bounds__(kDecThreads) void decode_kernel(DecodeArgs a) {
-  __shared__ int s_start[kDecBlockRows + 1];
-  __shared__ int s_src[kDecBlockRows + 1];
-  __shared__ float s_m[kDecWaves], s_l[kDecWaves];
-  __shared__ float s_acc[kDecWaves][kHeadDim];
-  __shared__ int s_last;
-
-  const int head = blockIdx.y, split = blockIdx.x;
-  const int R = a.plan.head_rows[head];
-  if (R <= 0) return;  // 0: no rows (output already written); -1: attended by the selection kernel
-  const int c = rows_per_split(R, a.splits);
+// One (head, split) item: attend its rows, publish the partial, and merge the head if this item arrives last.
+__device__ __forceinline__ void decode_item(const DecodeArgs &a, int head, int split, int R, int *s_start, int *s_src,
+                                            float *s_m, float *s_l, float (*s_acc)[kHeadDim], int *s_last, int tid,
+                                            int lane16, int grp) {
+  DD_MARK(1);
+  const int c = rows_per_item(R, a.splits);
   const int row_a = split * c;
-  if (row_a >= R) return;
   const int row_b = min(R, row_a + c);
   const int n_active = (R + c - 1) / c;
 
@@ -70,7 +86,6 @@ __global__ __launch_bounds__(kDecThreads) void decode_kernel(DecodeArgs a) {
   const int n_ex = a.n_exact[head], n_rt = a.n_retained[head];
   const int32_t *ent_src = a.plan.ent_src + (int64_t)head * a.max_k;
   const int32_t *row_start = a.plan.row_start + (int64_t)head * (a.max_k + 1);
-  const int tid = threadIdx.x, lane16 = tid & 15, grp = tid >> 4;
 
   const uint4 qv = load_row_slice(a.q, (int64_t)head, lane16);
 
@@ -86,8 +101,29 @@ __global__ __launch_bounds__(kDecThreads) void decode_kernel(DecodeArgs a) {
   RowState st;
   row_state_init(st);
 
+#ifdef DP_LAB_PURE  // development aid: lab-style loop, pseudo-random 32-row chunks, loads only
+  {
+    uint32_t accx = 0;
+    for (int r = row_a + grp * 32; r < row_b; r += 512) {
+      const int64_t g0 = src.seg_row0 + (int64_t)((((uint32_t)(r >> 5) + (uint32_t)head * 977u) * 2654435761u) >> 20) * 32;
+      for (int rr = 0; rr < 32; rr += 4) {
+        uint4 ka[4], va[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+          ka[u] = load_row_slice(a.k_cache, g0 + rr + u, lane16);
+          va[u] = load_row_slice(a.v_cache, g0 + rr + u, lane16);
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) accx += (ka[u].x ^ ka[u].y) + (ka[u].z ^ ka[u].w) + (va[u].x ^ va[u].y) + (va[u].z ^ va[u].w);
+      }
+    }
+    st.m = 0.f;
+    st.l = 1.f + __uint_as_float(accx & 0x3fffff);
+  }
+#else
   int ent0 = a.plan.chunk_entry[(int64_t)head * a.plan.chunk_stride + row_a / kChunkRows];
 
+  DD_MARK(2);
   for (int r0 = row_a; r0 < row_b; r0 += kDecBlockRows) {
     const int r1 = min(row_b, r0 + kDecBlockRows);
     // stage the list entries that cover rows [r0, r1): every entry has >= 1 row
@@ -98,10 +134,18 @@ __global__ __launch_bounds__(kDecThreads) void decode_kernel(DecodeArgs a) {
       s_src[k] = (k < n_ent) ? ent_src[ent0 + k] : 0;
     }
     __syncthreads();
+    DD_MARK(3);
+#ifdef DP_DECODE_CONTIGUOUS
     // each DPP-row group streams a contiguous run of the block's rows
     const int per = kAttendBatch * ((r1 - r0 + kDecGroups * kAttendBatch - 1) / (kDecGroups * kAttendBatch));
     const int ra = r0 + grp * per;
-    attend_rows(st, qv, a.scale_log2, src, s_start, s_src, n_ent, ent0, n_ex, ra, min(r1, ra + per), lane16);
+    attend_rows(st, qv, a.scale_log2, src, s_start, s_src, n_ent, ent0, n_ex, ra, min(r1, ra + per), kAttendBatch,
+                lane16);
+#else
+    // the 16 DPP-row groups take consecutive 4-row pieces: one step of the workgroup reads 64 consecutive rows
+    attend_rows(st, qv, a.scale_log2, src, s_start, s_src, n_ent, ent0, n_ex, r0 + grp * kAttendBatch, r1,
+                kDecGroups * kAttendBatch, lane16);
+#endif
     // first entry of the next block: the entry that holds row r1
     if (r1 < row_b) {
       int lo = 0, hi = n_ent + 1;  // s_start[n_ent] is staged as well
@@ -113,8 +157,11 @@ __global__ __launch_bounds__(kDecThreads) void decode_kernel(DecodeArgs a) {
     }
   }
 
+#endif
+  DD_MARK(4);
   float M, L, o;
   block_merge<kDecWaves>(st, s_m, s_l, s_acc, kDecWaves, M, L, o);
+  DD_MARK(5);
 
   if (n_active == 1) {  // the only split of this head: finish here
     if (tid < kHeadDim) {
@@ -141,28 +188,108 @@ __global__ __launch_bounds__(kDecThreads) void decode_kernel(DecodeArgs a) {
   // The split that arrives last merges all partials of the head (log-sum-exp merge).
   if (tid == 0) {
     const int ticket = __hip_atomic_fetch_add(&a.plan.done[head], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    s_last = (ticket == n_active - 1);
+    (*s_last) = (ticket == n_active - 1);
   }
   __syncthreads();
-  if (!s_last) return;
+  DD_MARK(6);
+  if (!(*s_last)) return;
   if (tid < kHeadDim) {
-    float Mx = -INFINITY;
-    for (int s2 = 0; s2 < n_active; ++s2)
-      Mx = fmaxf(Mx, __hip_atomic_load(P + s2 * kPartialStride, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
-    float Ls = 0.f, os = 0.f;
-    for (int s2 = 0; s2 < n_active; ++s2) {
-      const float *Q = P + s2 * kPartialStride;
-      const float ms = __hip_atomic_load(Q, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      const float w = exp2f(ms - Mx);
-      Ls += __hip_atomic_load(Q + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) * w;
-      os += __hip_atomic_load(Q + 2 + tid, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) * w;
+    // running log-sum-exp merge; the coherent loads of 8 partials are issued together
+    float Mx = -INFINITY, Ls = 0.f, os = 0.f;
+    for (int s0 = 0; s0 < n_active; s0 += 8) {
+      float ms[8], ll[8], oo[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        const float *Q = P + min(s0 + u, n_active - 1) * kPartialStride;
+        ms[u] = __hip_atomic_load(Q, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        ll[u] = __hip_atomic_load(Q + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        oo[u] = __hip_atomic_load(Q + 2 + tid, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      }
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        if (s0 + u < n_active) {  // every partial has a finite m: an item has at least one row
+          const float Mn = fmaxf(Mx, ms[u]);
+          const float sc = exp2f(Mx - Mn), w = exp2f(ms[u] - Mn);
+          Ls = Ls * sc + ll[u] * w;
+          os = os * sc + oo[u] * w;
+          Mx = Mn;
+        }
+      }
     }
     store_out(a.out, a.out_is_bf16, head, tid, os / Ls);
     if (a.lse && tid == 0) a.lse[head] = (Mx + log2f(Ls)) * kLn2;
   }
 }
 
+__global__ __launch_bounds__(kDecThreads) void decode_kernel(DecodeArgs a) {
+  __shared__ int s_start[kDecBlockRows + 1];
+  __shared__ int s_src[kDecBlockRows + 1];
+  __shared__ float s_m[kDecWaves], s_l[kDecWaves];
+  __shared__ float s_acc[kDecWaves][kHeadDim];
+  __shared__ int s_last, s_item;
+  __shared__ int s_first[kMaxQueueHeads + 1];  // first item number of each head of this launch
+  __shared__ int s_scan[kDecWaves + 1];
+  __shared__ int s_rows[kMaxQueueHeads];
+  const int tid = threadIdx.x, lane16 = tid & 15, grp = tid >> 4;
+
+  DD_MARK(0);
+  // ---- the queue: items per head from head_rows[], exclusive prefix in LDS ----
+  constexpr int kPer = kMaxQueueHeads / kDecThreads;  // consecutive heads per thread
+  int cnt[kPer], mine = 0;
+#pragma unroll
+  for (int u = 0; u < kPer; ++u) {
+    const int hh = tid * kPer + u;
+    int n = 0, R = 0;
+    if (hh < a.n_heads) {
+      R = a.plan.head_rows[a.head0 + hh];  // <= 0: nothing to do (empty, or attended already)
+      if (R > 0) {
+        const int c = rows_per_item(R, a.splits);
+        n = (R + c - 1) / c;
+      }
+    }
+    s_rows[hh] = R;
+    cnt[u] = n;
+    mine += n;
+  }
+  int total;
+  int run = block_excl_scan<int, kDecWaves>(mine, s_scan, total);
+#pragma unroll
+  for (int u = 0; u < kPer; ++u) {
+    s_first[tid * kPer + u] = run;
+    run += cnt[u];
+  }
+  if (tid == kDecThreads - 1) s_first[kMaxQueueHeads] = total;
+  __syncthreads();
+  if (total == 0) return;
+
+#pragma unroll 1
+  // the first item of a workgroup is its block index; further items are claimed from the counter
+  for (int item = blockIdx.x; item < total;) {
+    // head that owns the item: the largest hh with s_first[hh] <= item (heads without items repeat the
+    // next head's value, so the largest such hh is the one with s_first[hh + 1] > item)
+    int lo = 0, hi = kMaxQueueHeads;
+    while (hi - lo > 1) {
+      const int mid = (lo + hi) >> 1;
+      if (s_first[mid] <= item) lo = mid; else hi = mid;
+    }
+    const int head = a.head0 + lo, split = item - s_first[lo];
+    decode_item(a, head, split, s_rows[lo], s_start, s_src, s_m, s_l, s_acc, &s_last, tid, lane16, grp);
+    if (tid == 0)
+      s_item = gridDim.x + __hip_atomic_fetch_add(a.queue_next, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __syncthreads();  // also: LDS is reused by the next item
+    item = s_item;
+    __syncthreads();
+    DD_MARK(7);
+    DD_COUNT();
+  }
+}
+
 }  // namespace
+
+#ifdef DP_PHASE_CLOCKS
+unsigned long long *g_decode_clock_buffer = nullptr;
+extern "C" void dp_debug_set_decode_clock_buffer(void *p) { g_decode_clock_buffer = (unsigned long long *)p; }
+#endif
 
 hipError_t launch_decode(const CacheView &c, const int32_t *n_exact, const int32_t *n_retained, const Plan &plan,
                          float *partials, int splits, const AttnOut &attn, hipStream_t s) {
@@ -190,7 +317,18 @@ hipError_t launch_decode(const CacheView &c, const int32_t *n_exact, const int32
   a.max_k = c.max_clusters_per_seg;
   a.splits = splits;
   a.scale_log2 = c.sm_scale * kLog2e;
-  hipLaunchKernelGGL(decode_kernel, dim3(splits, nh), dim3(kDecThreads), 0, s, a);
+#ifdef DP_PHASE_CLOCKS
+  a.dbg = g_decode_clock_buffer;
+#endif
+  // one launch per slab of kMaxQueueHeads heads, each with its own item counter
+  for (int h0 = 0, slab = 0; h0 < nh; h0 += kMaxQueueHeads, ++slab) {
+    a.head0 = h0;
+    a.n_heads = nh - h0 < kMaxQueueHeads ? nh - h0 : kMaxQueueHeads;
+    a.queue_next = plan.queue_next + slab;
+    const long max_items = (long)a.n_heads * splits;
+    const int grid = (int)(max_items < kDecodeGrid ? max_items : kDecodeGrid);
+    hipLaunchKernelGGL(decode_kernel, dim3(grid), dim3(kDecThreads), 0, s, a);
+  }
   return hipGetLastError();
 }
 

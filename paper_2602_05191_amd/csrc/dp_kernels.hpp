@@ -8,8 +8,14 @@ namespace dp {
 
 constexpr int kHeadDim = 128;  // the only supported head dimension
 
-// rows of one stage-3 work chunk; split boundaries are multiples of it
+// rows of one stage-3 work chunk; item boundaries are multiples of it
 constexpr int kChunkRows = 64;
+// stage 3 pulls (head, split) items from a device-side queue: heads served per launch, workgroups per launch
+constexpr int kMaxQueueHeads = 1024;
+#ifndef DP_DECODE_GRID
+#define DP_DECODE_GRID 1280
+#endif
+constexpr int kDecodeGrid = DP_DECODE_GRID;
 
 struct CacheView {
   int32_t batch, n_kv_heads, n_q_heads, group;  // group = n_q_heads / n_kv_heads
@@ -31,6 +37,7 @@ struct CacheView {
 //   done[nh]                  arrival counter of the head's decode workgroups (zeroed by the planner)
 struct Plan {
   int32_t *ent_src, *row_start, *chunk_entry, *head_rows, *done;
+  int32_t *queue_next;  // one item counter per slab of kMaxQueueHeads heads (zeroed by the planner)
   int32_t chunk_stride;
 };
 

@@ -410,6 +410,8 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(SelectArgs a) {
   emit.l_src = sh.l_src;
   emit.plan = plan;
 
+  if (plan && tid == 0 && head % kMaxQueueHeads == 0) a.plan.queue_next[head / kMaxQueueHeads] = 0;
+
   DP_MARK(0);
   // ---- load, max ---------------------------------------------------------
   float l[E];
@@ -781,7 +783,7 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(SelectArgs a) {
     constexpr int kGroups = kSelThreads / 16;
     const int per = kAttendBatch * ((R + kGroups * kAttendBatch - 1) / (kGroups * kAttendBatch));
     const int ra = grp * per, rb = min(R, ra + per);
-    attend_rows(st, qv, a.scale_log2, src, sh.l_start, sh.l_src, n_ex + n_ap, 0, n_ex, ra, rb, lane16);
+    attend_rows(st, qv, a.scale_log2, src, sh.l_start, sh.l_src, n_ex + n_ap, 0, n_ex, ra, rb, kAttendBatch, lane16);
     DP_MARK(6);
     float M, L, o;
     const int groups_used = (R + per - 1) / per;
@@ -820,6 +822,7 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(PlanArgs a) {
   int32_t *row_start = a.plan.row_start + (int64_t)head * (a.max_k + 1);
   int32_t *chunk_entry = a.plan.chunk_entry + (int64_t)head * a.plan.chunk_stride;
   const int tid = threadIdx.x;
+  if (tid == 0 && head % kMaxQueueHeads == 0) a.plan.queue_next[head / kMaxQueueHeads] = 0;
 
   int carry = 0;
   for (int j0 = 0; j0 < n_ex; j0 += kPlanThreads) {
