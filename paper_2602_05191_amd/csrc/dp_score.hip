@@ -56,16 +56,12 @@ __global__ __launch_bounds__(kScoreThreads) void score_kernel(ScoreArgs a) {
   uint4 raw[kScoreRowsPerGroup];
   int size[kScoreRowsPerGroup];
 #pragma unroll
-  for (int k = 0; k < kScoreRowsPerGroup; ++k) {
-    const int i = i0 + k;
-    if (i < kc) {
-      raw[k] = load_row_slice(a.k_centroids, (int64_t)(c0 + i), lane16);
-      size[k] = a.cluster_sizes[c0 + i];
-    } else {
-      raw[k] = make_uint4(0, 0, 0, 0);
-      size[k] = 0;
-    }
-  }
+  for (int k = 0; k < kScoreRowsPerGroup; ++k)
+    raw[k] = (i0 + k < kc) ? load_row_slice(a.k_centroids, (int64_t)(c0 + i0 + k), lane16) : make_uint4(0, 0, 0, 0);
+  // sizes: one dword per row, the same address for the 16 lanes of the group (a broadcast load; wider
+  // or masked loads of the four sizes measured slower)
+#pragma unroll
+  for (int k = 0; k < kScoreRowsPerGroup; ++k) size[k] = (i0 + k < kc) ? a.cluster_sizes[c0 + i0 + k] : 0;
 
   // the group's query slices stay packed bf16
   uint4 qv[GH];
