@@ -74,6 +74,10 @@ def _load():
         L.dpo_exact_cluster_log_mass.argtypes = [CP, I, I, P]
         L.dpo_decode_step.restype = I
         L.dpo_decode_step.argtypes = [CP, D, D, U, P, P, P, P, P, C.c_int64, I]
+        L.dpo_fixed_budget.restype = None
+        L.dpo_fixed_budget.argtypes = [I, I, I, P, P]
+        L.dpo_budget_step.restype = I
+        L.dpo_budget_step.argtypes = [CP, I, I, P, P, P, P, P, C.c_int64, I]
         L.dpo_dense_step.restype = I
         L.dpo_dense_step.argtypes = [CP, P, P, I]
         _lib = L
@@ -148,6 +152,16 @@ class Oracle:
         k1, k2, m1, cum = self.double_top_p(a_hat, order, p1, p2, flags)
         return Selection(order=order, k1=k1, k2=k2, m1=m1, cum=cum, a_hat=a_hat)
 
+    def fixed_budget(self, logit: np.ndarray, k_retained: int, k_exact: int) -> "Selection":
+        """Fixed-budget selection from given logits (Sec. 5.1, cluster-based baseline)."""
+        a_hat = self.cluster_distribution(logit)
+        order = self.sorted_order(logit)
+        k1, k2 = C.c_int32(), C.c_int32()
+        self.lib.dpo_fixed_budget(order.size, int(k_retained), int(k_exact), C.addressof(k1), C.addressof(k2))
+        cum = np.cumsum(a_hat[order]) if order.size else np.zeros(0)
+        m1 = float(cum[k1.value - 1]) if k1.value > 0 else 0.0
+        return Selection(order=order, k1=k1.value, k2=k2.value, m1=m1, cum=cum, a_hat=a_hat)
+
     def mixed_attention(self, b: int, h: int, exact_ids: Sequence[int], approx_ids: Sequence[int]):
         ex = np.ascontiguousarray(exact_ids, dtype=np.int32)
         ap = np.ascontiguousarray(approx_ids, dtype=np.int32)
@@ -180,6 +194,21 @@ class Oracle:
         stride = int(np.diff(self._a["seg_cluster_ptr"]).max()) if nh else 0
         order = np.full((nh, max(1, stride)), -1, dtype=np.int32) if want_order else None
         used = self.lib.dpo_decode_step(self.cp, float(p1), float(p2), int(flags), _ptr(out), _ptr(lse), _ptr(k1),
+                                        _ptr(k2), _ptr(order) if want_order else None, max(1, stride),
+                                        int(n_threads))
+        return StepResult(out=out, lse=lse.reshape(self.batch, self.n_q_heads),
+                          k1=k1.reshape(self.batch, self.n_q_heads), k2=k2.reshape(self.batch, self.n_q_heads),
+                          order=order, threads=int(used))
+
+    def budget_step(self, k_retained: int, k_exact: int, n_threads: int = 1, want_order: bool = True):
+        nh = self.batch * self.n_q_heads
+        out = np.empty((self.batch, self.n_q_heads, self.d), dtype=np.float64)
+        lse = np.empty(nh, dtype=np.float64)
+        k1 = np.empty(nh, dtype=np.int32)
+        k2 = np.empty(nh, dtype=np.int32)
+        stride = int(np.diff(self._a["seg_cluster_ptr"]).max()) if nh else 0
+        order = np.full((nh, max(1, stride)), -1, dtype=np.int32) if want_order else None
+        used = self.lib.dpo_budget_step(self.cp, int(k_retained), int(k_exact), _ptr(out), _ptr(lse), _ptr(k1),
                                         _ptr(k2), _ptr(order) if want_order else None, max(1, stride),
                                         int(n_threads))
         return StepResult(out=out, lse=lse.reshape(self.batch, self.n_q_heads),

@@ -283,6 +283,52 @@ int32_t dpo_decode_step(const dpo_cache *c, double p1, double p2, uint32_t flags
   return used;
 }
 
+/* ---- fixed budget instead of the two top-p thresholds (Sec. 5.1, cluster-based baseline) ---- */
+void dpo_fixed_budget(int32_t n_nonempty, int32_t k_retained, int32_t k_exact, int32_t *k1_out, int32_t *k2_out) {
+  int32_t k1 = k_retained < 0 ? 0 : k_retained;
+  if (k1 > n_nonempty) k1 = n_nonempty;
+  int32_t k2 = k_exact < 0 ? 0 : k_exact;
+  if (k2 > k1) k2 = k1;
+  *k1_out = k1;
+  *k2_out = k2;
+}
+
+static void budget_head(const dpo_cache *c, int32_t b, int32_t h, int32_t k_retained, int32_t k_exact, double *out,
+                        double *lse, int32_t *k1, int32_t *k2, int32_t *order_out) {
+  int32_t n = dpo_num_clusters(c, b, h);
+  size_t m = (size_t)(n > 0 ? n : 1);
+  double *logit = (double *)malloc(sizeof(double) * m);
+  int32_t *order = (int32_t *)malloc(sizeof(int32_t) * m);
+  dpo_centroid_logits(c, b, h, logit);
+  int32_t nn = dpo_sorted_order(logit, n, order);
+  dpo_fixed_budget(nn, k_retained, k_exact, k1, k2);
+  dpo_mixed_attention(c, b, h, order, *k2, order + *k2, *k1 - *k2, out, lse);
+  if (order_out) memcpy(order_out, order, sizeof(int32_t) * (size_t)nn);
+  free(logit);
+  free(order);
+}
+
+int32_t dpo_budget_step(const dpo_cache *c, int32_t k_retained, int32_t k_exact, double *out, double *lse,
+                        int32_t *k1, int32_t *k2, int32_t *order, int64_t order_stride, int32_t n_threads) {
+  const int32_t nh = c->batch * c->n_q_heads, d = c->head_dim;
+  int32_t used = 1;
+#ifdef _OPENMP
+  if (n_threads > 1) {
+    used = n_threads < nh ? n_threads : (nh > 0 ? nh : 1);
+#pragma omp parallel for schedule(dynamic, 1) num_threads(used)
+    for (int32_t i = 0; i < nh; ++i)
+      budget_head(c, i / c->n_q_heads, i % c->n_q_heads, k_retained, k_exact, out + (int64_t)i * d, lse + i, k1 + i,
+                  k2 + i, order ? order + i * order_stride : 0);
+    return used;
+  }
+#endif
+  (void)n_threads;
+  for (int32_t i = 0; i < nh; ++i)
+    budget_head(c, i / c->n_q_heads, i % c->n_q_heads, k_retained, k_exact, out + (int64_t)i * d, lse + i, k1 + i,
+                k2 + i, order ? order + i * order_stride : 0);
+  return used;
+}
+
 int32_t dpo_dense_step(const dpo_cache *c, double *out, double *lse, int32_t n_threads) {
   const int32_t nh = c->batch * c->n_q_heads, d = c->head_dim;
   int32_t used = 1;

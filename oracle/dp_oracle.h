@@ -86,6 +86,17 @@ void dpo_exact_cluster_log_mass(const dpo_cache *c, int32_t b, int32_t h, double
 int32_t dpo_decode_step(const dpo_cache *c, double p1, double p2, uint32_t flags, double *out, double *lse,
                         int32_t *k1, int32_t *k2, int32_t *order, int64_t order_stride, int32_t n_threads);
 
+/* Fixed budget in place of the two thresholds (the fixed top-k cluster retrieval of
+ * the cluster-based baseline, Sec. 5.1): of the n_nonempty clusters of the order
+ * the first k1 = min(max(k_retained, 0), n_nonempty) are retained and the first
+ * k2 = min(max(k_exact, 0), k1) of them are exact. */
+void dpo_fixed_budget(int32_t n_nonempty, int32_t k_retained, int32_t k_exact, int32_t *k1, int32_t *k2);
+
+/* The decode step with dpo_fixed_budget in place of dpo_double_top_p; same
+ * outputs and threading as dpo_decode_step. */
+int32_t dpo_budget_step(const dpo_cache *c, int32_t k_retained, int32_t k_exact, double *out, double *lse,
+                        int32_t *k1, int32_t *k2, int32_t *order, int64_t order_stride, int32_t n_threads);
+
 /* Eq. 1 for every (b, h), same threading. */
 int32_t dpo_dense_step(const dpo_cache *c, double *out, double *lse, int32_t n_threads);
 

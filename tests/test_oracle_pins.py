@@ -411,3 +411,81 @@ def test_empty_segment_and_threads_agree():
     assert np.array_equal(r1.out, r4.out) and np.array_equal(r1.k1, r4.k1) and np.array_equal(r1.order, r4.order)
     assert (r1.k1[1, 2:] == 0).all() and (r1.out[1, 2:] == 0).all() and np.isneginf(r1.lse[1, 2:]).all()
     assert 3 not in r1.order[0, : r1.k1[0, 0]].tolist()
+
+
+# --------------------------------------------------------------------------
+# fixed budget in place of the two thresholds (Sec. 5.1, the cluster-based baseline)
+# --------------------------------------------------------------------------
+def test_fixed_budget_is_the_numpy_top_k_with_index_ties():
+    rng = np.random.default_rng(77)
+    o = oracle.Oracle(make_config(0, shrink=16))
+    for trial in range(20):
+        n = int(rng.integers(1, 40))
+        # few distinct values: many ties; some empty clusters (-inf)
+        logit = rng.integers(-3, 3, size=n).astype(np.float64) * 0.5
+        logit[rng.random(n) < 0.2] = -np.inf
+        nonempty = np.flatnonzero(np.isfinite(logit))
+        ref = nonempty[np.lexsort((nonempty, -logit[nonempty]))]  # score descending, then index ascending
+        for kr, ke in ((0, 0), (1, 0), (1, 1), (3, 2), (5, 9), (n, 1), (n + 7, n + 7), (-2, 4)):
+            s = o.fixed_budget(logit, kr, ke)
+            k1 = min(max(kr, 0), len(ref))
+            k2 = min(max(ke, 0), k1)
+            assert (s.k1, s.k2) == (k1, k2)
+            assert s.order[: s.k1].tolist() == ref[:k1].tolist()
+            assert set(s.exact.tolist()) == set(ref[:k2].tolist())
+            assert set(s.approx.tolist()) == set(ref[k2:k1].tolist())
+
+
+def test_fixed_budget_with_the_top_p_counts_reproduces_the_top_p_step():
+    """Cross-consistency: the budget step run with the counts the two thresholds chose is the same step."""
+    c = make_cache(batch=1, n_kv_heads=2, n_q_heads=4, context=1536, mean_cluster=8, size_hi=32, q_scale=0.35, seed=21)
+    o = oracle.Oracle(c)
+    r = o.decode_step(0.9, 0.6)
+    for h in range(4):
+        logit = o.centroid_logits(0, h)
+        s = o.fixed_budget(logit, int(r.k1[0, h]), int(r.k2[0, h]))
+        t = o.select(logit, 0.9, 0.6)
+        assert s.exact.tolist() == t.exact.tolist() and s.approx.tolist() == t.approx.tolist()
+        out, lse = o.mixed_attention(0, h, s.exact, s.approx)
+        np.testing.assert_allclose(out, r.out[0, h], rtol=1e-12, atol=1e-14)
+        assert lse == pytest.approx(r.lse[0, h], rel=1e-12)
+
+
+def test_budget_step_limits_and_threads():
+    c = make_cache(batch=2, n_kv_heads=2, n_q_heads=4, context=[700, 300], mean_cluster=8, size_hi=32, q_scale=0.5,
+                   seed=22)
+    o = oracle.Oracle(c)
+    kmax = int(np.diff(c.seg_cluster_ptr).max())
+    # everything retained and exact: dense attention (Eq. 1), checked with scipy
+    r = o.budget_step(kmax, kmax)
+    for b in range(2):
+        for h in range(4):
+            ref, ref_lse = scipy_dense(c, b, h)
+            np.testing.assert_allclose(r.out[b, h], ref, rtol=1e-9, atol=1e-12)
+            assert r.lse[b, h] == pytest.approx(ref_lse, rel=1e-12)
+    # one exact cluster, nothing else: attention over that cluster's tokens alone
+    r = o.budget_step(1, 1)
+    for b in range(2):
+        for h in range(4):
+            seg = b * c.n_kv_heads + h // c.group
+            top = int(r.order[b * 4 + h, 0])
+            ref, _ = scipy_dense(c, b, h, rows=rows_of(c, seg, [top]))
+            np.testing.assert_allclose(r.out[b, h], ref, rtol=1e-9, atol=1e-12)
+    # nothing exact: size-weighted average of the value centroids of the top clusters
+    r = o.budget_step(5, 0)
+    VC = bf16_bits_to_f32(c.v_centroids).astype(np.float64)
+    for b in range(2):
+        for h in range(4):
+            seg = b * c.n_kv_heads + h // c.group
+            a0 = int(c.seg_cluster_ptr[seg])
+            logit = o.centroid_logits(b, h)
+            kept = r.order[b * 4 + h, : r.k1[b, h]]
+            w = softmax(logit[kept])
+            np.testing.assert_allclose(r.out[b, h], (w[:, None] * VC[a0 + kept]).sum(0), rtol=1e-10, atol=1e-13)
+    # nothing retained: zero output, lse = -inf
+    r = o.budget_step(0, 0)
+    assert (r.out == 0).all() and np.isneginf(r.lse).all()
+    # threads agree
+    a = o.budget_step(6, 2, n_threads=1)
+    t = o.budget_step(6, 2, n_threads=4)
+    assert (a.out == t.out).all() and (a.k1 == t.k1).all() and (a.k2 == t.k2).all()
