@@ -128,6 +128,22 @@ dp_status dp_decode_attention(const dp_problem *problem, float p1, float p2, voi
                               float *lse, int32_t *n_exact, int32_t *n_retained, int32_t *n_exact_tokens,
                               void *workspace, size_t workspace_bytes, void *stream);
 
+/* Stage 2 with a fixed budget in place of the two thresholds: the fixed top-k
+ * cluster retrieval of the cluster-based baseline the paper compares with
+ * (Sec. 5.1 "Baselines").  Same order as dp_topp_select (logit descending,
+ * ties by lower cluster index, empty clusters never selected): the first
+ * min(k_retained, non-empty clusters) clusters are retained and the first
+ * min(k_exact, that) of them are exact.  k_retained == 0 selects nothing.
+ * Outputs as dp_topp_select.  DP_ERR_INVALID_ARG for a negative budget. */
+dp_status dp_topk_select(const dp_problem *problem, const float *logits, int32_t k_retained, int32_t k_exact,
+                         int32_t *sel_ids, int32_t *n_exact, int32_t *n_retained, int32_t *n_exact_tokens,
+                         void *stream);
+
+/* dp_decode_attention with the selection rule of dp_topk_select. */
+dp_status dp_budget_decode_attention(const dp_problem *problem, int32_t k_retained, int32_t k_exact, void *out,
+                                     dp_dtype out_dtype, float *lse, int32_t *n_exact, int32_t *n_retained,
+                                     int32_t *n_exact_tokens, void *workspace, size_t workspace_bytes, void *stream);
+
 /* Where dp_decode_attention keeps its intermediate results inside the
  * workspace (byte offsets; host-only, for inspection by tests and tools):
  * logits as in dp_score_centroids, sel_ids as in dp_topp_select. */

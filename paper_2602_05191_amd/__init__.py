@@ -8,10 +8,12 @@ from .binding import (  # noqa: F401
     DPError,
     DeviceCache,
     Problem,
+    dp_budget_decode_attention,
     dp_decode_attention,
     dp_score_centroids,
     dp_score_centroids_timed,
     dp_sparse_decode,
+    dp_topk_select,
     dp_topp_select,
     dp_workspace_bytes,
     dp_workspace_layout,

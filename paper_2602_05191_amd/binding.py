@@ -23,7 +23,8 @@ _LIB_PATH = os.path.join(_PKG, "libdp_hip.so")
 
 EXPORTS = ["dp_workspace_bytes", "dp_logits_count", "dp_get_workspace_layout", "dp_score_centroids",
            "dp_score_centroids_timed",
-           "dp_topp_select", "dp_sparse_decode", "dp_decode_attention", "dp_status_string"]
+           "dp_topp_select", "dp_topk_select", "dp_sparse_decode", "dp_decode_attention",
+           "dp_budget_decode_attention", "dp_status_string"]
 
 
 class DPError(RuntimeError):
@@ -81,6 +82,10 @@ def load_library():
     L.dp_sparse_decode.argtypes = [PP, V, V, V, V, V, I, V, V, C.c_size_t, V]
     L.dp_decode_attention.restype = I
     L.dp_decode_attention.argtypes = [PP, F, F, V, I, V, V, V, V, V, C.c_size_t, V]
+    L.dp_topk_select.restype = I
+    L.dp_topk_select.argtypes = [PP, V, I, I, V, V, V, V, V]
+    L.dp_budget_decode_attention.restype = I
+    L.dp_budget_decode_attention.argtypes = [PP, I, I, V, I, V, V, V, V, V, C.c_size_t, V]
     L.dp_status_string.restype = C.c_char_p
     L.dp_status_string.argtypes = [I]
     _lib = L
@@ -203,6 +208,15 @@ def dp_topp_select(problem: Problem, logits: torch.Tensor, p1: float, p2: float,
                                          _ptr(n_retained), _ptr(n_exact_tokens), _stream(stream)), "dp_topp_select")
 
 
+def dp_topk_select(problem: Problem, logits: torch.Tensor, k_retained: int, k_exact: int, sel_ids: torch.Tensor,
+                   n_exact: torch.Tensor, n_retained: torch.Tensor, n_exact_tokens: torch.Tensor, stream=None) -> None:
+    for t in (sel_ids, n_exact, n_retained, n_exact_tokens):
+        assert t.dtype == torch.int32 and t.is_contiguous()
+    assert sel_ids.numel() >= problem.nh * problem.dc.max_clusters_per_seg and n_exact.numel() >= problem.nh
+    _check(load_library().dp_topk_select(problem.ref, _ptr(logits), k_retained, k_exact, _ptr(sel_ids), _ptr(n_exact),
+                                         _ptr(n_retained), _ptr(n_exact_tokens), _stream(stream)), "dp_topk_select")
+
+
 def dp_sparse_decode(problem: Problem, sel_ids: torch.Tensor, n_exact: torch.Tensor, n_retained: torch.Tensor,
                      out: torch.Tensor, lse: Optional[torch.Tensor], workspace: torch.Tensor, stream=None) -> None:
     dt = {torch.float32: DP_F32, torch.bfloat16: DP_BF16}[out.dtype]
@@ -223,3 +237,16 @@ def dp_decode_attention(problem: Problem, p1: float, p2: float, out: torch.Tenso
                                               _ptr(n_retained), _ptr(n_exact_tokens), _ptr(workspace),
                                               workspace.numel() * workspace.element_size(), _stream(stream)),
            "dp_decode_attention")
+
+
+def dp_budget_decode_attention(problem: Problem, k_retained: int, k_exact: int, out: torch.Tensor,
+                               lse: Optional[torch.Tensor], workspace: torch.Tensor,
+                               n_exact: Optional[torch.Tensor] = None, n_retained: Optional[torch.Tensor] = None,
+                               n_exact_tokens: Optional[torch.Tensor] = None, stream=None) -> None:
+    dt = {torch.float32: DP_F32, torch.bfloat16: DP_BF16}[out.dtype]
+    assert out.is_contiguous() and out.numel() == problem.nh * problem.dc.head_dim
+    _check(load_library().dp_budget_decode_attention(problem.ref, k_retained, k_exact, _ptr(out), dt, _ptr(lse),
+                                                     _ptr(n_exact), _ptr(n_retained), _ptr(n_exact_tokens),
+                                                     _ptr(workspace), workspace.numel() * workspace.element_size(),
+                                                     _stream(stream)),
+           "dp_budget_decode_attention")

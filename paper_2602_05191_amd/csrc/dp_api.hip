@@ -142,6 +142,55 @@ dp_status check_common(const dp_problem *p) {
 
 bool p_in_domain(float p1, float p2) { return p1 > 0.0f && p1 <= 1.0f && p2 >= 0.0f && p2 <= 1.0f; }
 
+dp::SelectRule top_p_rule(const dp_problem *p, float p1, float p2) {
+  return dp::SelectRule{p1, p2, p->flags & DP_FLAG_P2_ABSOLUTE, 0, 0, 0};
+}
+dp::SelectRule budget_rule(int32_t k_retained, int32_t k_exact) {
+  return dp::SelectRule{1.0f, 1.0f, 0u, 1, k_retained, k_exact};
+}
+
+dp_status select_only(const dp_problem *problem, const float *logits, const dp::SelectRule &rule, int32_t *sel_ids,
+                      int32_t *n_exact, int32_t *n_retained, int32_t *n_exact_tokens, void *stream) {
+  if (!n_exact || !n_retained || !n_exact_tokens) return DP_ERR_INVALID_ARG;
+  if (problem->max_clusters_per_seg > 0 && (!logits || !sel_ids)) return DP_ERR_INVALID_ARG;
+  dp::SelectOut out{sel_ids, n_exact, n_retained, n_exact_tokens};
+  dp::Plan none{nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, 0};
+  dp::AttnOut nowhere{nullptr, nullptr, 0};
+  return dp::launch_select(view_of(problem), logits, rule, out, none, nowhere, static_cast<hipStream_t>(stream)) ==
+                 hipSuccess
+             ? DP_OK
+             : DP_ERR_HIP;
+}
+
+// score -> select (+ attention of light heads) -> split decode, on one stream
+dp_status whole_step(const dp_problem *problem, const dp::SelectRule &rule, void *out, dp_dtype out_dtype, float *lse,
+                     int32_t *n_exact, int32_t *n_retained, int32_t *n_exact_tokens, void *workspace,
+                     size_t workspace_bytes, void *stream) {
+  if (out_dtype != DP_BF16 && out_dtype != DP_F32) return DP_ERR_UNSUPPORTED;
+  if (!out || !workspace) return DP_ERR_INVALID_ARG;
+  if (workspace_bytes < dp_workspace_bytes(problem)) return DP_ERR_WORKSPACE_TOO_SMALL;
+  if (reinterpret_cast<uintptr_t>(workspace) % 256) return DP_ERR_INVALID_ARG;
+  const dp::CacheView c = view_of(problem);
+  const Workspace w = carve(problem, workspace);
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  if (dp::launch_score(c, w.logits, s) != hipSuccess) return DP_ERR_HIP;
+  dp::SelectOut so{w.sel_ids, w.n_exact, w.n_retained, w.n_exact_tokens};
+  const dp::AttnOut attn{out, lse, out_dtype == DP_BF16};
+  if (dp::launch_select(c, w.logits, rule, so, w.plan, attn, s) != hipSuccess) return DP_ERR_HIP;
+  if (dp::launch_decode(c, w.n_exact, w.n_retained, w.plan, w.partials, w.splits, attn, s) != hipSuccess)
+    return DP_ERR_HIP;
+  const size_t nh = (size_t)problem->batch * problem->n_q_heads;
+  // optional count outputs: device-to-device copies on the same stream
+  if (n_exact && hipMemcpyAsync(n_exact, w.n_exact, nh * 4, hipMemcpyDeviceToDevice, s) != hipSuccess)
+    return DP_ERR_HIP;
+  if (n_retained && hipMemcpyAsync(n_retained, w.n_retained, nh * 4, hipMemcpyDeviceToDevice, s) != hipSuccess)
+    return DP_ERR_HIP;
+  if (n_exact_tokens &&
+      hipMemcpyAsync(n_exact_tokens, w.n_exact_tokens, nh * 4, hipMemcpyDeviceToDevice, s) != hipSuccess)
+    return DP_ERR_HIP;
+  return DP_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -190,15 +239,18 @@ dp_status dp_topp_select(const dp_problem *problem, const float *logits, float p
   dp_status st = check_common(problem);
   if (st != DP_OK) return st;
   if (!p_in_domain(p1, p2)) return DP_ERR_INVALID_ARG;
-  if (!n_exact || !n_retained || !n_exact_tokens) return DP_ERR_INVALID_ARG;
-  if (problem->max_clusters_per_seg > 0 && (!logits || !sel_ids)) return DP_ERR_INVALID_ARG;
-  dp::SelectOut out{sel_ids, n_exact, n_retained, n_exact_tokens};
-  dp::Plan none{nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, 0};
-  dp::AttnOut nowhere{nullptr, nullptr, 0};
-  return dp::launch_select(view_of(problem), logits, p1, p2, problem->flags, out, none, nowhere,
-                           static_cast<hipStream_t>(stream)) == hipSuccess
-             ? DP_OK
-             : DP_ERR_HIP;
+  return select_only(problem, logits, top_p_rule(problem, p1, p2), sel_ids, n_exact, n_retained, n_exact_tokens,
+                     stream);
+}
+
+dp_status dp_topk_select(const dp_problem *problem, const float *logits, int32_t k_retained, int32_t k_exact,
+                         int32_t *sel_ids, int32_t *n_exact, int32_t *n_retained, int32_t *n_exact_tokens,
+                         void *stream) {
+  dp_status st = check_common(problem);
+  if (st != DP_OK) return st;
+  if (k_retained < 0 || k_exact < 0) return DP_ERR_INVALID_ARG;
+  return select_only(problem, logits, budget_rule(k_retained, k_exact), sel_ids, n_exact, n_retained, n_exact_tokens,
+                     stream);
 }
 
 dp_status dp_sparse_decode(const dp_problem *problem, const int32_t *sel_ids, const int32_t *n_exact,
@@ -228,35 +280,24 @@ dp_status dp_decode_attention(const dp_problem *problem, float p1, float p2, voi
   dp_status st = check_common(problem);
   if (st != DP_OK) return st;
   if (!p_in_domain(p1, p2)) return DP_ERR_INVALID_ARG;
-  if (out_dtype != DP_BF16 && out_dtype != DP_F32) return DP_ERR_UNSUPPORTED;
-  if (!out || !workspace) return DP_ERR_INVALID_ARG;
-  if (workspace_bytes < dp_workspace_bytes(problem)) return DP_ERR_WORKSPACE_TOO_SMALL;
-  if (reinterpret_cast<uintptr_t>(workspace) % 256) return DP_ERR_INVALID_ARG;
-  const dp::CacheView c = view_of(problem);
-  const Workspace w = carve(problem, workspace);
-  hipStream_t s = static_cast<hipStream_t>(stream);
-  if (dp::launch_score(c, w.logits, s) != hipSuccess) return DP_ERR_HIP;
-  dp::SelectOut so{w.sel_ids, w.n_exact, w.n_retained, w.n_exact_tokens};
-  const dp::AttnOut attn{out, lse, out_dtype == DP_BF16};
-  if (dp::launch_select(c, w.logits, p1, p2, problem->flags, so, w.plan, attn, s) != hipSuccess) return DP_ERR_HIP;
-  if (dp::launch_decode(c, w.n_exact, w.n_retained, w.plan, w.partials, w.splits, attn, s) != hipSuccess)
-    return DP_ERR_HIP;
-  const size_t nh = (size_t)problem->batch * problem->n_q_heads;
-  // optional count outputs: device-to-device copies on the same stream
-  if (n_exact && hipMemcpyAsync(n_exact, w.n_exact, nh * 4, hipMemcpyDeviceToDevice, s) != hipSuccess)
-    return DP_ERR_HIP;
-  if (n_retained && hipMemcpyAsync(n_retained, w.n_retained, nh * 4, hipMemcpyDeviceToDevice, s) != hipSuccess)
-    return DP_ERR_HIP;
-  if (n_exact_tokens &&
-      hipMemcpyAsync(n_exact_tokens, w.n_exact_tokens, nh * 4, hipMemcpyDeviceToDevice, s) != hipSuccess)
-    return DP_ERR_HIP;
-  return DP_OK;
+  return whole_step(problem, top_p_rule(problem, p1, p2), out, out_dtype, lse, n_exact, n_retained, n_exact_tokens,
+                    workspace, workspace_bytes, stream);
+}
+
+dp_status dp_budget_decode_attention(const dp_problem *problem, int32_t k_retained, int32_t k_exact, void *out,
+                                     dp_dtype out_dtype, float *lse, int32_t *n_exact, int32_t *n_retained,
+                                     int32_t *n_exact_tokens, void *workspace, size_t workspace_bytes, void *stream) {
+  dp_status st = check_common(problem);
+  if (st != DP_OK) return st;
+  if (k_retained < 0 || k_exact < 0) return DP_ERR_INVALID_ARG;
+  return whole_step(problem, budget_rule(k_retained, k_exact), out, out_dtype, lse, n_exact, n_retained,
+                    n_exact_tokens, workspace, workspace_bytes, stream);
 }
 
 const char *dp_status_string(dp_status status) {
   switch (status) {
     case DP_OK: return "DP_OK";
-    case DP_ERR_INVALID_ARG: return "DP_ERR_INVALID_ARG: null pointer, bad shape or p outside its domain";
+    case DP_ERR_INVALID_ARG: return "DP_ERR_INVALID_ARG: null pointer, bad shape, p outside its domain or a negative budget";
     case DP_ERR_UNSUPPORTED: return "DP_ERR_UNSUPPORTED: head_dim != 128, GQA group > 16, too many clusters or bad dtype";
     case DP_ERR_WORKSPACE_TOO_SMALL: return "DP_ERR_WORKSPACE_TOO_SMALL: see dp_workspace_bytes";
     case DP_ERR_HIP: return "DP_ERR_HIP: a HIP runtime call failed";

@@ -57,10 +57,19 @@ struct SelectOut {
 hipError_t launch_score(const CacheView &c, float *logits, hipStream_t s, hipEvent_t start = nullptr,
                         hipEvent_t stop = nullptr);
 
+// How stage 2 cuts the order (logit descending, index ascending):
+//   by_count == 0: the two top-p thresholds p1, p2 (p2_absolute: p2 is a mass of the whole distribution)
+//   by_count != 0: fixed budget, the first k_retained clusters are retained and the first k_exact of them exact
+struct SelectRule {
+  float p1, p2;
+  uint32_t p2_absolute;
+  int32_t by_count, k_retained, k_exact;
+};
+
 // plan.ent_src == nullptr => no plan is written
 // With a plan and attn.out != nullptr, heads with few rows are attended inside the selection kernel.
-hipError_t launch_select(const CacheView &c, const float *logits, float p1, float p2, uint32_t flags,
-                         const SelectOut &out, const Plan &plan, const AttnOut &attn, hipStream_t s);
+hipError_t launch_select(const CacheView &c, const float *logits, const SelectRule &rule, const SelectOut &out,
+                         const Plan &plan, const AttnOut &attn, hipStream_t s);
 
 // builds the plan from caller-given sets
 hipError_t launch_plan(const CacheView &c, const int32_t *sel_ids, const int32_t *n_exact,

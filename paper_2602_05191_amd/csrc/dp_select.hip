@@ -61,6 +61,7 @@ struct SelectArgs {
   int32_t uniform_kc;  // > 0: every segment has exactly this many clusters (no CSR lookup needed)
   float p1, p2;
   uint32_t p2_absolute;
+  int32_t k_retained, k_exact;  // fixed-budget rule (the kernel's kCount variant): counts instead of p1, p2
   SelectOut out;
   Plan plan;
   // inline attention (one-call path); out == nullptr disables it
@@ -87,7 +88,16 @@ __device__ __forceinline__ u64 fixed40(float w) {
 __device__ __forceinline__ u64 fx_mass(float d) {
   return d < kCut ? fixed40(__builtin_amdgcn_exp2f(-d * kLog2e)) : 0;
 }
-__device__ __forceinline__ int level1_bin(float d) { return min(kBins - 1, (int)(d * kBinScale)); }
+__device__ __forceinline__ int level1_bin(float d) { return (int)fminf(d * kBinScale, (float)(kBins - 1)); }
+
+// The same threshold search serves two rules.  Top-p (kCount = false): a cluster weighs its
+// fixed-point softmax mass and is in play while that mass is non-zero.  Fixed budget (kCount =
+// true): every non-empty cluster weighs 1, so "the shortest prefix whose weight reaches k" is
+// the top-k of the order, and bins beyond kCut all fall into the last level-1 bin.
+template <bool kCount>
+__device__ __forceinline__ bool in_play(float d) { return kCount ? d < INFINITY : d < kCut; }
+template <bool kCount>
+__device__ __forceinline__ u64 mass_of(float d) { return kCount ? (u64)(d < INFINITY) : fx_mass(d); }
 
 struct Shared {
   u64 hist[kBins];
@@ -151,7 +161,7 @@ __device__ __forceinline__ void reduce_members(int cnt, uint32_t lo, uint32_t hi
 // [klo, khi] (by up-to-2048-way splits of the key range, re-histogrammed in sh.hist2) until the members can
 // be ranked, or are a run of equal keys which is cut in index order.  On return either
 // cnt <= kMaxCand (members = keys in [klo, khi], not yet gathered) or the result is in sh.res_*.
-template <int E>
+template <int E, bool kCount>
 __device__ __forceinline__ bool refine_or_cut_ties(const float (&l)[E], float mx, int base, int bin1, u64 tau,
                                                 u64 &before, uint32_t &klo, uint32_t &khi, int &cnt, Shared &sh) {
   const int tid = threadIdx.x;
@@ -161,7 +171,7 @@ __device__ __forceinline__ bool refine_or_cut_ties(const float (&l)[E], float mx
 #pragma unroll
     for (int e = 0; e < E; ++e) {
       const float d = mx - l[e];
-      if (d < kCut && level1_bin(d) == bin1) {
+      if (in_play<kCount>(d) && level1_bin(d) == bin1) {
         const uint32_t k = ordered_key(l[e]);
         ++c;
         lo = min(lo, k);
@@ -180,8 +190,8 @@ __device__ __forceinline__ bool refine_or_cut_ties(const float (&l)[E], float mx
     for (int e = 0; e < E; ++e) {
       const float d = mx - l[e];
       const uint32_t k = ordered_key(l[e]);
-      if (d < kCut && k >= klo && k <= khi) {
-        const u64 m = fx_mass(d);
+      if (in_play<kCount>(d) && k >= klo && k <= khi) {
+        const u64 m = mass_of<kCount>(d);
         if (m) atomicAdd(&sh.hist2[(khi - k) >> shift], m);
       }
     }
@@ -208,7 +218,7 @@ __device__ __forceinline__ bool refine_or_cut_ties(const float (&l)[E], float mx
     for (int e = 0; e < E; ++e) {
       const float d = mx - l[e];
       const uint32_t k = ordered_key(l[e]);
-      if (d < kCut && k >= klo && k <= khi && (int)((khi - k) >> shift) == bin2) {
+      if (in_play<kCount>(d) && k >= klo && k <= khi && (int)((khi - k) >> shift) == bin2) {
         ++c;
         lo = min(lo, k);
         hi = max(hi, k);
@@ -223,9 +233,9 @@ __device__ __forceinline__ bool refine_or_cut_ties(const float (&l)[E], float mx
   u64 mm = 0;
 #pragma unroll
   for (int e = 0; e < E; ++e)
-    if (mx - l[e] < kCut && ordered_key(l[e]) == klo) {
+    if (in_play<kCount>(mx - l[e]) && ordered_key(l[e]) == klo) {
       ++c;
-      mm = fx_mass(mx - l[e]);
+      mm = mass_of<kCount>(mx - l[e]);
     }
 #pragma unroll
   for (int d = 32; d >= 1; d >>= 1) {
@@ -245,7 +255,7 @@ __device__ __forceinline__ bool refine_or_cut_ties(const float (&l)[E], float mx
     int seen = ex;
 #pragma unroll
     for (int e = 0; e < E; ++e)
-      if (mx - l[e] < kCut && ordered_key(l[e]) == klo) {
+      if (in_play<kCount>(mx - l[e]) && ordered_key(l[e]) == klo) {
         ++seen;
         if ((u64)seen == need) {
           sh.res_key = klo;
@@ -263,7 +273,7 @@ __device__ __forceinline__ bool refine_or_cut_ties(const float (&l)[E], float mx
 // prefix and its two bins of the level-1 histogram.  `slot` picks the candidate counter.
 // cached_*: the bin whose members are currently gathered in sh.cand_* (reused when the
 // second threshold falls into the same bin).  Block-uniform control flow.
-template <int E>
+template <int E, bool kCount>
 __device__ __forceinline__ void find_prefix(const float (&l)[E], float mx, int base, u64 tau, u64 ex, u64 h0, u64 h1,
                                             int slot, Shared &sh, int &cached_bin, int &cached_cnt,
                                             u64 &cached_before, uint32_t &key_o, int &idx_o, u64 &mass_o) {
@@ -288,12 +298,12 @@ __device__ __forceinline__ void find_prefix(const float (&l)[E], float mx, int b
 #pragma unroll
     for (int e = 0; e < E; ++e) {
       const float d = mx - l[e];
-      if (d < kCut && level1_bin(d) == bin1) {
+      if (in_play<kCount>(d) && level1_bin(d) == bin1) {
         const int s = atomicAdd(&sh.ncand[slot], 1);
         if (s < kMaxCand) {
           sh.cand_key[s] = ordered_key(l[e]);
           sh.cand_idx[s] = base + e;
-          sh.cand_m[s] = fx_mass(d);
+          sh.cand_m[s] = mass_of<kCount>(d);
         }
       }
     }
@@ -305,18 +315,18 @@ __device__ __forceinline__ void find_prefix(const float (&l)[E], float mx, int b
     if (cnt > kMaxCand) {
       cached_bin = -1;  // the candidate arrays will not hold this bin
       uint32_t klo, khi;
-      done = refine_or_cut_ties<E>(l, mx, base, bin1, tau, before, klo, khi, cnt, sh);
+      done = refine_or_cut_ties<E, kCount>(l, mx, base, bin1, tau, before, klo, khi, cnt, sh);
       if (!done) {
         if (tid == 0) sh.ncand[slot] = 0;
         __syncthreads();
 #pragma unroll
         for (int e = 0; e < E; ++e) {
           const uint32_t k = ordered_key(l[e]);
-          if (mx - l[e] < kCut && k >= klo && k <= khi) {
+          if (in_play<kCount>(mx - l[e]) && k >= klo && k <= khi) {
             const int s = atomicAdd(&sh.ncand[slot], 1);
             sh.cand_key[s] = k;
             sh.cand_idx[s] = base + e;
-            sh.cand_m[s] = fx_mass(mx - l[e]);
+            sh.cand_m[s] = mass_of<kCount>(mx - l[e]);
           }
         }
         __syncthreads();
@@ -381,7 +391,36 @@ struct Emit {
   }
 };
 
-template <int E>
+// The two thresholds of a head in units of the rule's weights.
+//   first : all == true, or tau1 in [1, W]
+//   second: kind 0 = nothing exact, 1 = every retained cluster, 2 = tau2 in [1, m1]
+template <bool kCount>
+__device__ __forceinline__ bool retain_all(const SelectArgs &a, u64 W) {
+  return kCount ? (u64)a.k_retained >= W : a.p1 >= 1.0f;
+}
+template <bool kCount>
+__device__ __forceinline__ u64 first_tau(const SelectArgs &a, u64 W) {
+  if (kCount) return (u64)a.k_retained < W ? (u64)a.k_retained : W;  // k_retained >= 1 here
+  const u64 t = (u64)ceil((double)a.p1 * (double)W);
+  return t < 1 ? 1 : (t > W ? W : t);
+}
+// m1: weight of the retained prefix
+template <bool kCount>
+__device__ __forceinline__ int second_tau(const SelectArgs &a, u64 W, u64 m1, u64 &tau2) {
+  if (kCount) {
+    if (a.k_exact <= 0) return 0;
+    if ((u64)a.k_exact >= m1) return 1;
+    tau2 = (u64)a.k_exact;
+    return 2;
+  }
+  if (a.p2 >= 1.0f) return 1;
+  if (a.p2 <= 0.0f) return 0;
+  const u64 t = a.p2_absolute ? (u64)ceil((double)a.p2 * (double)W) : (u64)ceil((double)a.p2 * (double)m1);
+  tau2 = t < 1 ? 1 : (t > m1 ? m1 : t);
+  return 2;
+}
+
+template <int E, bool kCount>
 __global__ __launch_bounds__(kSelThreads) void select_kernel(SelectArgs a) {
   __shared__ Shared sh;
   const int head = blockIdx.x;
@@ -477,7 +516,7 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(SelectArgs a) {
   const float mx = block_max<kSelWaves>(tmax, sh.scrf);  // its barriers also publish the zeroed LDS
 
   DP_MARK(1);
-  if (mx == -INFINITY) {  // no non-empty cluster: nothing selected, zero output
+  if (mx == -INFINITY || (kCount && a.k_retained <= 0)) {  // no non-empty cluster, or a budget of 0: nothing selected, zero output
     if (tid == 0) {
       a.out.n_exact[head] = 0;
       a.out.n_retained[head] = 0;
@@ -499,13 +538,13 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(SelectArgs a) {
 #pragma unroll
   for (int e = 0; e < E; ++e) {
     const float d = mx - l[e];
-    if (d < kCut) {
-      wsum += fx_mass(d);
+    if (in_play<kCount>(d)) {
+      wsum += mass_of<kCount>(d);
       ctop += d < kTopCut;
     }
   }
   int ntop;
-  u64 W;  // >= 2^40: the max element has weight 1
+  u64 W;  // total weight; top-p: >= 2^40 (the max element has weight 1); fixed budget: the non-empty clusters
   {
     wsum = wave_sum(wsum);
     ctop = wave_sum(ctop);
@@ -525,7 +564,8 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(SelectArgs a) {
   DP_MARK(2);
 
   int n_ex, n_ap, n_tok;
-  bool fast = a.p1 < 1.0f && ntop <= kTopMax;
+  const bool all = retain_all<kCount>(a, W);  // every non-empty cluster is retained
+  bool fast = !all && ntop <= kTopMax;
   if (fast) {
     // ---- fast path: the retained set lies inside the top set (the usual case for a peaked
     // head).  Gather the top set with its sizes / offsets, then one wave ranks it pairwise. ----
@@ -537,7 +577,7 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(SelectArgs a) {
         const int i = base + e;
         sh.top_key[s] = ordered_key(l[e]);
         sh.top_idx[s] = i;
-        sh.top_m[s] = fx_mass(d);
+        sh.top_m[s] = mass_of<kCount>(d);
         sh.top_sz[s] = kPre ? psz[kPre ? e : 0] : a.cluster_sizes[c0 + i];
         sh.top_off[s] = !plan ? 0 : kPre ? poff[kPre ? e : 0] : a.cluster_offsets[c0 + i];
       }
@@ -556,8 +596,7 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(SelectArgs a) {
         if (kj > key_i || (kj == key_i && sh.top_idx[j] < idx_i)) ahead += sh.top_m[j];
       }
       const u64 top_mass = wave_sum(m_i);
-      u64 tau1 = (u64)ceil((double)a.p1 * (double)W);
-      tau1 = tau1 < 1 ? 1 : (tau1 > W ? W : tau1);
+      const u64 tau1 = first_tau<kCount>(a, W);
       const bool ok = top_mass >= tau1;  // otherwise the prefix reaches below the top set
       if (ok) {
         const bool ret = act && ahead < tau1;
@@ -567,16 +606,9 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(SelectArgs a) {
           const u64 o = __shfl_xor(m1, d, 64);
           m1 = o > m1 ? o : m1;
         }
-        bool exa;
-        if (a.p2 >= 1.0f) {
-          exa = ret;
-        } else if (a.p2 <= 0.0f) {
-          exa = false;
-        } else {
-          u64 tau2 = a.p2_absolute ? (u64)ceil((double)a.p2 * (double)W) : (u64)ceil((double)a.p2 * (double)m1);
-          tau2 = tau2 < 1 ? 1 : (tau2 > m1 ? m1 : tau2);
-          exa = act && ahead < tau2;
-        }
+        u64 tau2 = 0;
+        const int kind = second_tau<kCount>(a, W, m1, tau2);
+        const bool exa = kind == 1 ? ret : (kind == 2 && act && ahead < tau2);
         const bool apx = ret && !exa;
         const u64 exa_mask = __ballot(exa), apx_mask = __ballot(apx);
         n_ex = __popcll(exa_mask);
@@ -620,10 +652,8 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(SelectArgs a) {
 #pragma unroll
     for (int e = 0; e < E; ++e) {
       const float d = mx - l[e];
-      if (d < kCut) {
-        const u64 m = fx_mass(d);
-        if (m) atomicAdd(&sh.hist[level1_bin(d)], m);
-      }
+      const u64 m = mass_of<kCount>(d);
+      if (m) atomicAdd(&sh.hist[level1_bin(d)], m);
     }
     __syncthreads();
     const u64 h0 = sh.hist[2 * tid], h1 = sh.hist[2 * tid + 1];
@@ -635,41 +665,40 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(SelectArgs a) {
     u64 mass1;
     int cached_bin = -1, cached_cnt = 0;
     u64 cached_before = 0;
-    if (a.p1 >= 1.0f) {  // every non-empty cluster
+    if (all) {  // every non-empty cluster
       key1 = kKeyLowestFinite;
       idx1 = INT_MAX;
       mass1 = W;
     } else {
-      u64 tau = (u64)ceil((double)a.p1 * (double)W);
-      tau = tau < 1 ? 1 : (tau > W ? W : tau);
-      find_prefix<E>(l, mx, base, tau, ex, h0, h1, 0, sh, cached_bin, cached_cnt, cached_before, key1, idx1, mass1);
+      find_prefix<E, kCount>(l, mx, base, first_tau<kCount>(a, W), ex, h0, h1, 0, sh, cached_bin, cached_cnt,
+                             cached_before, key1, idx1, mass1);
     }
-    if (a.p2 >= 1.0f) {
+    u64 tau2 = 0;
+    const int kind = second_tau<kCount>(a, W, mass1, tau2);
+    if (kind == 1) {
       key2 = key1;
       idx2 = idx1;
-    } else if (a.p2 <= 0.0f) {  // nothing is exact
+    } else if (kind == 0) {  // nothing is exact
       key2 = 0xffffffffu;
       idx2 = -1;
     } else {
-      u64 tau = a.p2_absolute ? (u64)ceil((double)a.p2 * (double)W) : (u64)ceil((double)a.p2 * (double)mass1);
-      tau = tau < 1 ? 1 : (tau > mass1 ? mass1 : tau);
       u64 mass2;
       __syncthreads();  // sh.bin / sh.res_* of the first search have been read by every thread
-      find_prefix<E>(l, mx, base, tau, ex, h0, h1, 1, sh, cached_bin, cached_cnt, cached_before, key2, idx2, mass2);
+      find_prefix<E, kCount>(l, mx, base, tau2, ex, h0, h1, 1, sh, cached_bin, cached_cnt, cached_before, key2, idx2,
+                             mass2);
     }
 
     // ---- compaction in ascending cluster index ------------------------------
-    // With p1 < 1 only clusters with non-zero mass can be selected; with p1 = 1 all non-empty ones are.
-    const bool all = a.p1 >= 1.0f;
+    // Only clusters in play (non-zero weight) can be selected, unless all non-empty ones are.
     u64 exa_mask = 0, ret_mask = 0;  // bit e: element e of this thread is exact / approximated
     int sz[E], off[E];
 #pragma unroll
     for (int e = 0; e < E; ++e) {
       const uint32_t k = ordered_key(l[e]);
       const int i = base + e;
-      const bool in_play = all ? l[e] != -INFINITY : mx - l[e] < kCut;
-      const bool exa = in_play && (k > key2 || (k == key2 && i <= idx2));
-      const bool apx = in_play && !exa && (k > key1 || (k == key1 && i <= idx1));
+      const bool live = all ? l[e] != -INFINITY : in_play<kCount>(mx - l[e]);
+      const bool exa = live && (k > key2 || (k == key2 && i <= idx2));
+      const bool apx = live && !exa && (k > key1 || (k == key1 && i <= idx1));
       exa_mask |= (u64)exa << e;
       ret_mask |= (u64)apx << e;
       if (kPre) {
@@ -860,8 +889,11 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(PlanArgs a) {
 }
 
 template <int E>
-void launch_select_e(const SelectArgs &a, dim3 grid, hipStream_t s) {
-  hipLaunchKernelGGL(select_kernel<E>, grid, dim3(kSelThreads), 0, s, a);
+void launch_select_e(const SelectArgs &a, bool by_count, dim3 grid, hipStream_t s) {
+  if (by_count)
+    hipLaunchKernelGGL((select_kernel<E, true>), grid, dim3(kSelThreads), 0, s, a);
+  else
+    hipLaunchKernelGGL((select_kernel<E, false>), grid, dim3(kSelThreads), 0, s, a);
 }
 
 }  // namespace
@@ -871,8 +903,8 @@ unsigned long long *g_phase_clock_buffer = nullptr;
 extern "C" void dp_debug_set_phase_clock_buffer(void *p) { g_phase_clock_buffer = (unsigned long long *)p; }
 #endif
 
-hipError_t launch_select(const CacheView &c, const float *logits, float p1, float p2, uint32_t flags,
-                         const SelectOut &out, const Plan &plan, const AttnOut &attn, hipStream_t s) {
+hipError_t launch_select(const CacheView &c, const float *logits, const SelectRule &rule, const SelectOut &out,
+                         const Plan &plan, const AttnOut &attn, hipStream_t s) {
   SelectArgs a;
   a.logits = logits;
   a.seg_cluster_ptr = c.seg_cluster_ptr;
@@ -883,9 +915,12 @@ hipError_t launch_select(const CacheView &c, const float *logits, float p1, floa
   a.group = c.group;
   a.max_k = c.max_clusters_per_seg;
   a.uniform_kc = c.uniform_kc;
-  a.p1 = p1;
-  a.p2 = p2;
-  a.p2_absolute = flags & 1u;
+  a.p1 = rule.p1;
+  a.p2 = rule.p2;
+  a.p2_absolute = rule.p2_absolute;
+  a.k_retained = rule.k_retained;
+  a.k_exact = rule.k_exact;
+  const bool bc = rule.by_count != 0;
   a.out = out;
   a.plan = plan;
   a.q = c.q;
@@ -904,12 +939,12 @@ hipError_t launch_select(const CacheView &c, const float *logits, float p1, floa
   const dim3 grid(c.batch * c.n_q_heads);
   if (grid.x == 0) return hipSuccess;
   const int k = c.max_clusters_per_seg;
-  if (k <= 2 * kSelThreads) launch_select_e<2>(a, grid, s);
-  else if (k <= 4 * kSelThreads) launch_select_e<4>(a, grid, s);
-  else if (k <= 8 * kSelThreads) launch_select_e<8>(a, grid, s);
-  else if (k <= 16 * kSelThreads) launch_select_e<16>(a, grid, s);
-  else if (k <= 32 * kSelThreads) launch_select_e<32>(a, grid, s);
-  else if (k <= 64 * kSelThreads) launch_select_e<64>(a, grid, s);
+  if (k <= 2 * kSelThreads) launch_select_e<2>(a, bc, grid, s);
+  else if (k <= 4 * kSelThreads) launch_select_e<4>(a, bc, grid, s);
+  else if (k <= 8 * kSelThreads) launch_select_e<8>(a, bc, grid, s);
+  else if (k <= 16 * kSelThreads) launch_select_e<16>(a, bc, grid, s);
+  else if (k <= 32 * kSelThreads) launch_select_e<32>(a, bc, grid, s);
+  else if (k <= 64 * kSelThreads) launch_select_e<64>(a, bc, grid, s);
   else return hipErrorInvalidValue;
   return hipGetLastError();
 }

@@ -55,7 +55,8 @@ def gpu_logits(cache: ClusteredCache, sm_scale: float = 0.0):
     return out, lg
 
 
-def gpu_select(cache: ClusteredCache, flat_logits: np.ndarray, p1: float, p2: float, flags: int = 0):
+def gpu_select(cache: ClusteredCache, flat_logits: np.ndarray, p1: float, p2: float, flags: int = 0, budget=None):
+    """budget = (k_retained, k_exact): dp_topk_select instead of dp_topp_select (p1, p2 unused)."""
     import torch
     import paper_2602_05191_amd as dp
     dc = dp.DeviceCache.from_host(cache)
@@ -65,7 +66,10 @@ def gpu_select(cache: ClusteredCache, flat_logits: np.ndarray, p1: float, p2: fl
     sel = torch.full((nh, mk), -7, dtype=torch.int32, device="cuda:0")
     ne = torch.full((nh,), -7, dtype=torch.int32, device="cuda:0")
     nr, nt = ne.clone(), ne.clone()
-    dp.dp_topp_select(pr, lg, p1, p2, sel, ne, nr, nt)
+    if budget is None:
+        dp.dp_topp_select(pr, lg, p1, p2, sel, ne, nr, nt)
+    else:
+        dp.dp_topk_select(pr, lg, int(budget[0]), int(budget[1]), sel, ne, nr, nt)
     torch.cuda.synchronize()
     sel, ne, nr, nt = sel.cpu().numpy(), ne.cpu().numpy(), nr.cpu().numpy(), nt.cpu().numpy()
     exact = [sel[i, :ne[i]].copy() for i in range(nh)]
@@ -98,7 +102,8 @@ def gpu_sparse_decode(cache: ClusteredCache, exact: List[np.ndarray], approx: Li
 
 
 def gpu_decode_attention(cache: ClusteredCache, p1: float, p2: float, flags: int = 0, sm_scale: float = 0.0,
-                         want_logits: bool = False, dc=None) -> GpuStep:
+                         want_logits: bool = False, dc=None, budget=None) -> GpuStep:
+    """budget = (k_retained, k_exact): dp_budget_decode_attention instead of dp_decode_attention."""
     import torch
     import paper_2602_05191_amd as dp
     if dc is None:
@@ -111,7 +116,10 @@ def gpu_decode_attention(cache: ClusteredCache, p1: float, p2: float, flags: int
     lse = torch.full((nh,), float("nan"), dtype=torch.float32, device="cuda:0")
     ne = torch.full((nh,), -7, dtype=torch.int32, device="cuda:0")
     nr, nt = ne.clone(), ne.clone()
-    dp.dp_decode_attention(pr, p1, p2, out, lse, ws, ne, nr, nt)
+    if budget is None:
+        dp.dp_decode_attention(pr, p1, p2, out, lse, ws, ne, nr, nt)
+    else:
+        dp.dp_budget_decode_attention(pr, int(budget[0]), int(budget[1]), out, lse, ws, ne, nr, nt)
     torch.cuda.synchronize()
     lay = dp.dp_workspace_layout(pr)
     wsh = ws.cpu().numpy()

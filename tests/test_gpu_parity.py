@@ -255,6 +255,68 @@ def test_partial_ties_at_the_threshold():
 
 
 # ---------------------------------------------------------------------------
+# fixed budget in place of the two thresholds (dp_topk_select, dp_budget_decode_attention)
+# ---------------------------------------------------------------------------
+BUDGETS = [(1, 1), (1, 0), (7, 3), (64, 16), (65, 65), (300, 40), (10 ** 6, 5), (10 ** 6, 10 ** 6), (0, 0), (5, 9)]
+
+
+def test_topk_select_is_the_oracle_top_k_of_the_same_logits(case):
+    """Integer work on identical inputs: the sets must be identical."""
+    name, cache, p1, p2, orc = case
+    per_head, flat = H.gpu_logits(cache)
+    for kr, ke in BUDGETS:
+        exact, approx, ntok = H.gpu_select(cache, flat, 0, 0, budget=(kr, ke))
+        for b in range(cache.batch):
+            for h in range(cache.n_q_heads):
+                i = b * cache.n_q_heads + h
+                s = orc.fixed_budget(per_head[i].astype(np.float64), kr, ke)
+                assert np.array_equal(exact[i], s.exact) and np.array_equal(approx[i], s.approx), (name, kr, ke, i)
+                seg = b * cache.n_kv_heads + h // cache.group
+                c0 = int(cache.seg_cluster_ptr[seg])
+                assert int(ntok[i]) == int(cache.cluster_sizes[c0 + s.exact].sum())
+
+
+@pytest.mark.parametrize("budget", [(1, 1), (7, 3), (64, 16), (300, 40), (10 ** 6, 10 ** 6), (0, 0)])
+def test_budget_decode_attention_matches_oracle(case, budget):
+    name, cache, p1, p2, orc = case
+    g = H.gpu_decode_attention(cache, 0, 0, want_logits=True, budget=budget)
+    nh = cache.batch * cache.n_q_heads
+    for i in range(nh):
+        # the sets are the top-k of the logits the GPU itself computed (checked against the oracle's in stage 1)
+        s = orc.fixed_budget(g.logits[i].astype(np.float64), *budget)
+        assert np.array_equal(g.exact[i], s.exact) and np.array_equal(g.approx[i], s.approx), (name, budget, i)
+    # against the oracle's own step: same counts; sets equal except where fp32 and fp64 logits order a near-tie differently
+    r = orc.budget_step(*budget, n_threads=4)
+    differing = 0
+    for i in range(nh):
+        b, h = divmod(i, cache.n_q_heads)
+        assert len(g.exact[i]) == r.k2[b, h] and len(g.exact[i]) + len(g.approx[i]) == r.k1[b, h]
+        same = (np.array_equal(g.exact[i], np.sort(r.order[i, : r.k2[b, h]])) and
+                np.array_equal(g.approx[i], np.sort(r.order[i, r.k2[b, h]: r.k1[b, h]])))
+        if not same:
+            lg = orc.centroid_logits(b, h)
+            for got, want in ((g.exact[i], r.order[i, : r.k2[b, h]]),
+                              (np.concatenate([g.exact[i], g.approx[i]]), r.order[i, : r.k1[b, h]])):
+                swapped = np.setxor1d(got, want)
+                assert swapped.size == 0 or np.ptp(lg[swapped]) <= H.LOGIT_TIE_TOL, (name, budget, i, swapped)
+            differing += 1
+    assert differing <= max(1, nh // 8), (name, budget, differing)
+    H.check_outputs(cache, orc, g, tight=2e-4)
+
+
+def test_budget_ties_are_cut_by_index():
+    c = make_cache(batch=1, n_kv_heads=1, n_q_heads=2, context=3000, n_clusters=3000, size_dist="ones", size_lo=1,
+                   size_hi=1, q_scale=0.5, seed=42)
+    c.k_centroids[:] = c.k_centroids[0]          # every cluster gets the same score
+    orc = oracle.Oracle(c)
+    for kr, ke in ((1, 1), (700, 699), (2999, 1), (3000, 3000), (1025, 513)):
+        g = H.gpu_decode_attention(c, 0, 0, budget=(kr, ke))
+        for i in range(2):
+            assert np.array_equal(g.exact[i], np.arange(ke)) and np.array_equal(g.approx[i], np.arange(ke, kr))
+        H.check_outputs(c, orc, g, tight=2e-4)
+
+
+# ---------------------------------------------------------------------------
 # error paths of the boundary (host-side checks; nothing is launched)
 # ---------------------------------------------------------------------------
 def test_boundary_rejects_bad_arguments():
@@ -273,6 +335,10 @@ def test_boundary_rejects_bad_arguments():
     with pytest.raises(dp.DPError) as e:
         dp.dp_decode_attention(pr, 0.9, 0.5, out, None, ws[:1024])
     assert e.value.status == -3
+    for kr, ke in ((-1, 0), (3, -2)):
+        with pytest.raises(dp.DPError) as e:
+            dp.dp_budget_decode_attention(pr, kr, ke, out, None, ws)
+        assert e.value.status == -1
     bad = dp.Problem(dc)
     bad.c.head_dim = 64
     with pytest.raises(dp.DPError) as e:
