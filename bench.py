@@ -73,6 +73,10 @@ def algorithmic_bytes(cache, sel, n_exact, n_retained):
                 total_per_head_sum=scan + rows_sum * 2 * d2 + io)
 
 
+def total_clusters_nonzero(cache):
+    return int(cache.seg_cluster_ptr[-1]) > 0 and (cache.seg_cluster_ptr[1:] > cache.seg_cluster_ptr[:-1]).all()
+
+
 def measured_traffic(config):
     """HBM bytes per launch of the scoring kernel from the committed rocprofv3 counter summary
     (FETCH_SIZE and WRITE_SIZE, scaled by what a plain copy of known size reads); None if there is none."""
@@ -209,6 +213,31 @@ def main():
     select_us, select_med = time_stage(lambda i: dp.dp_topp_select(probs[i % L], logits, p1, p2, sel_d, ne, nr, nt))
     decode_us, decode_med = time_stage(lambda i: dp.dp_sparse_decode(probs[i % L], sel_d, ne, nr, out, lse, ws))
 
+    # ---- same-box baselines in the shape of the paper's efficiency comparison (Sec. 5.3): full attention
+    # over every token, and a fixed top-k cluster budget (1.8 % of the clusters exact, 25 % retained) ----
+    seg_rows_h = np.add.reduceat(cache.cluster_sizes.astype(np.int64), cache.seg_cluster_ptr[:-1].astype(np.int64)) \
+        if total_clusters_nonzero(cache) else np.zeros(cache.batch * cache.n_kv_heads, np.int64)
+    seg_rows = torch.from_numpy(seg_rows_h.astype(np.int32)).to(dev)
+    k_ret, k_ex = max(1, mk // 4), max(1, round(mk * 0.018))
+
+    def wall_time(fn, n):
+        for i in range(min(n, 20)):
+            fn(i)
+        torch.cuda.synchronize()
+        a = time.perf_counter()
+        for i in range(n):
+            fn(i)
+        torch.cuda.synchronize()
+        return (time.perf_counter() - a) * 1e6 / n
+
+    n_base = max(10, min(args.steps, 200))
+    dense_us = wall_time(lambda i: dp.dp_dense_decode(probs[i % L], seg_rows, out, lse, ws), n_base)
+    budget_us = wall_time(lambda i: dp.dp_budget_decode_attention(probs[i % L], k_ret, k_ex, out, lse, ws), n_base)
+    dense_bytes = int(seg_rows_h.sum()) * 4 * cache.head_dim + nh * cache.head_dim * 6
+    # leave the top-p step's result in out / lse for the check against the oracle below
+    dp.dp_decode_attention(pr0, p1, p2, out, lse, ws, None, None, None)
+    torch.cuda.synchronize()
+
     # the kernel that moves the bytes: centroid scoring reads every key centroid and size once and
     # writes G logits per cluster
     total_k = int(cache.seg_cluster_ptr[-1])
@@ -268,6 +297,16 @@ def main():
             "avg_launch_us": round(score_us, 3),
             "median_launch_us": round(score_med, 3),
             "back_to_back_interval_us": round(score_gap_us, 3),
+        },
+        "baselines_same_box": {
+            "dense_us": round(dense_us, 3),
+            "dense_entry_point": "dp_dense_decode (Eq. 1 over every token, K/V read once per KV head)",
+            "dense_bytes": dense_bytes,
+            "dense_GBs": round(dense_bytes / (dense_us * 1e-6) / 1e9, 1),
+            "speedup_over_dense": round(dense_us / value, 2),
+            "fixed_budget_us": round(budget_us, 3),
+            "fixed_budget": {"k_retained": k_ret, "k_exact": k_ex, "entry_point": "dp_budget_decode_attention"},
+            "speedup_over_fixed_budget": round(budget_us / value, 2),
         },
         "gen_seconds": round(t_gen, 1),
     }

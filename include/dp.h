@@ -144,6 +144,18 @@ dp_status dp_budget_decode_attention(const dp_problem *problem, int32_t k_retain
                                      dp_dtype out_dtype, float *lse, int32_t *n_exact, int32_t *n_retained,
                                      int32_t *n_exact_tokens, void *workspace, size_t workspace_bytes, void *stream);
 
+/* Dense attention (Sec. 2.1, Eq. 1) over every token of each head's KV segment:
+ * the full-attention baseline of the paper's efficiency comparison (Sec. 5.3).
+ * The tokens of segment seg are the cache rows [seg_row_base[seg],
+ * seg_row_base[seg] + seg_rows[seg]); seg_rows is a DEVICE array, int32
+ * [batch*n_kv_heads], each entry <= max_rows_per_seg (larger values are
+ * clamped to it).  The cluster arrays of the problem are not read and may be
+ * NULL.  K/V rows are read once per KV head and scored against all query heads
+ * of the GQA group (any group size).  out, lse, workspace as dp_sparse_decode;
+ * a segment without rows gives out = 0, lse = -inf. */
+dp_status dp_dense_decode(const dp_problem *problem, const int32_t *seg_rows, void *out, dp_dtype out_dtype,
+                          float *lse, void *workspace, size_t workspace_bytes, void *stream);
+
 /* Where dp_decode_attention keeps its intermediate results inside the
  * workspace (byte offsets; host-only, for inspection by tests and tools):
  * logits as in dp_score_centroids, sel_ids as in dp_topp_select. */

@@ -10,6 +10,7 @@ from .binding import (  # noqa: F401
     Problem,
     dp_budget_decode_attention,
     dp_decode_attention,
+    dp_dense_decode,
     dp_score_centroids,
     dp_score_centroids_timed,
     dp_sparse_decode,

@@ -24,7 +24,7 @@ _LIB_PATH = os.path.join(_PKG, "libdp_hip.so")
 EXPORTS = ["dp_workspace_bytes", "dp_logits_count", "dp_get_workspace_layout", "dp_score_centroids",
            "dp_score_centroids_timed",
            "dp_topp_select", "dp_topk_select", "dp_sparse_decode", "dp_decode_attention",
-           "dp_budget_decode_attention", "dp_status_string"]
+           "dp_budget_decode_attention", "dp_dense_decode", "dp_status_string"]
 
 
 class DPError(RuntimeError):
@@ -86,6 +86,8 @@ def load_library():
     L.dp_topk_select.argtypes = [PP, V, I, I, V, V, V, V, V]
     L.dp_budget_decode_attention.restype = I
     L.dp_budget_decode_attention.argtypes = [PP, I, I, V, I, V, V, V, V, V, C.c_size_t, V]
+    L.dp_dense_decode.restype = I
+    L.dp_dense_decode.argtypes = [PP, V, V, I, V, V, C.c_size_t, V]
     L.dp_status_string.restype = C.c_char_p
     L.dp_status_string.argtypes = [I]
     _lib = L
@@ -250,3 +252,14 @@ def dp_budget_decode_attention(problem: Problem, k_retained: int, k_exact: int, 
                                                      _ptr(workspace), workspace.numel() * workspace.element_size(),
                                                      _stream(stream)),
            "dp_budget_decode_attention")
+
+
+def dp_dense_decode(problem: Problem, seg_rows: torch.Tensor, out: torch.Tensor, lse: Optional[torch.Tensor],
+                    workspace: torch.Tensor, stream=None) -> None:
+    dt = {torch.float32: DP_F32, torch.bfloat16: DP_BF16}[out.dtype]
+    assert out.is_contiguous() and out.numel() == problem.nh * problem.dc.head_dim
+    assert seg_rows.dtype == torch.int32 and seg_rows.is_contiguous()
+    assert seg_rows.numel() == problem.c.batch * problem.c.n_kv_heads
+    _check(load_library().dp_dense_decode(problem.ref, _ptr(seg_rows), _ptr(out), dt, _ptr(lse), _ptr(workspace),
+                                          workspace.numel() * workspace.element_size(), _stream(stream)),
+           "dp_dense_decode")

@@ -66,7 +66,7 @@ int choose_splits(const dp_problem *p) {
   long s = (DP_SPLIT_TARGET + nh - 1) / nh;
   const long by_rows = ((long)p->max_rows_per_seg + p->max_clusters_per_seg + dp::kChunkRows - 1) / dp::kChunkRows;
   if (s > by_rows) s = by_rows;
-  if (s > 256) s = 256;
+  if (s > dp::kMaxSplits) s = dp::kMaxSplits;
   if (s < 8) s = 8;
   if (s > by_rows && by_rows >= 1) s = by_rows;
   if (s < 1) s = 1;
@@ -292,6 +292,23 @@ dp_status dp_budget_decode_attention(const dp_problem *problem, int32_t k_retain
   if (k_retained < 0 || k_exact < 0) return DP_ERR_INVALID_ARG;
   return whole_step(problem, budget_rule(k_retained, k_exact), out, out_dtype, lse, n_exact, n_retained,
                     n_exact_tokens, workspace, workspace_bytes, stream);
+}
+
+dp_status dp_dense_decode(const dp_problem *problem, const int32_t *seg_rows, void *out, dp_dtype out_dtype,
+                          float *lse, void *workspace, size_t workspace_bytes, void *stream) {
+  if (!shape_ok(problem)) return DP_ERR_INVALID_ARG;
+  if (problem->head_dim != dp::kHeadDim) return DP_ERR_UNSUPPORTED;
+  if (out_dtype != DP_BF16 && out_dtype != DP_F32) return DP_ERR_UNSUPPORTED;
+  if (!problem->q || !problem->seg_row_base || !seg_rows || !out || !workspace) return DP_ERR_INVALID_ARG;
+  if (problem->max_rows_per_seg > 0 && (!problem->k_cache || !problem->v_cache)) return DP_ERR_INVALID_ARG;
+  if (workspace_bytes < dp_workspace_bytes(problem)) return DP_ERR_WORKSPACE_TOO_SMALL;
+  if (reinterpret_cast<uintptr_t>(workspace) % 256) return DP_ERR_INVALID_ARG;
+  const dp::CacheView c = view_of(problem);
+  const Workspace w = carve(problem, workspace);
+  const dp::AttnOut attn{out, lse, out_dtype == DP_BF16};
+  return dp::launch_dense(c, seg_rows, w.partials, w.splits, attn, static_cast<hipStream_t>(stream)) == hipSuccess
+             ? DP_OK
+             : DP_ERR_HIP;
 }
 
 const char *dp_status_string(dp_status status) {

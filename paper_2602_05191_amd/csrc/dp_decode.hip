@@ -9,9 +9,11 @@
 // the traffic is the 512 B per row the method itself needs.
 //
 // Work split: a head with R rows is cut into ceil(R / c) items of
-// c = 64 * max(4, ceil(R / (64 * S))) rows (S = partial slots per head); item
-// boundaries are multiples of 64 rows, so the first list entry of an item comes
-// from the plan's chunk table in O(1).  Heads differ by orders of magnitude in
+// c = 64 * max(g, ceil(R / (64 * S))) rows (S = partial slots per head; g = 1..8
+// grows with the launch's total rows: a light launch spreads over the whole chip
+// in 64-row items, a heavy one amortises its merges); item boundaries are
+// multiples of 64 rows, so the first list entry of an item comes from the
+// plan's chunk table in O(1).  Heads differ by orders of magnitude in
 // rows and the host knows none of the counts, so the grid is a fixed number of
 // workgroups that pull items from a device-side queue: every workgroup builds
 // the same prefix of items per head in LDS from head_rows[], then claims item
@@ -37,7 +39,7 @@ constexpr int kPartialStride = kHeadDim + 2;   // m, l, acc[128]
 #ifndef DP_MIN_ITEM_CHUNKS
 #define DP_MIN_ITEM_CHUNKS 8
 #endif
-constexpr int kMinItemChunks = DP_MIN_ITEM_CHUNKS;  // an item has at least this many 64-row chunks (unless the head has fewer)
+constexpr int kMinItemChunks = DP_MIN_ITEM_CHUNKS;  // items of a heavy launch have at least this many 64-row chunks
 
 #ifdef DP_PHASE_CLOCKS  // development aid, never built into the library
 #define DD_MARK(i) do { if (a.dbg && threadIdx.x == 0 && blockIdx.x < 2048) a.dbg[blockIdx.x * 16 + (i)] = wall_clock64(); } while (0)
@@ -65,17 +67,17 @@ struct DecodeArgs {
 #endif
 };
 
-// rows per item of a head with R rows (multiple of kChunkRows)
-__device__ __forceinline__ int rows_per_item(int R, int S) {
-  return kChunkRows * max(kMinItemChunks, (R + kChunkRows * S - 1) / (kChunkRows * S));
+// rows per item of a head with R rows (multiple of kChunkRows); g: least chunks per item of this launch
+__device__ __forceinline__ int rows_per_item(int R, int S, int g) {
+  return kChunkRows * max(g, (R + kChunkRows * S - 1) / (kChunkRows * S));
 }
 
 // One (head, split) item: attend its rows, publish the partial, and merge the head if this item arrives last.
-__device__ __forceinline__ void decode_item(const DecodeArgs &a, int head, int split, int R, int *s_start, int *s_src,
+__device__ __forceinline__ void decode_item(const DecodeArgs &a, int head, int split, int R, int g, int *s_start, int *s_src,
                                             float *s_m, float *s_l, float (*s_acc)[kHeadDim], int *s_last, int tid,
                                             int lane16, int grp) {
   DD_MARK(1);
-  const int c = rows_per_item(R, a.splits);
+  const int c = rows_per_item(R, a.splits, g);
   const int row_a = split * c;
   const int row_b = min(R, row_a + c);
   const int n_active = (R + c - 1) / c;
@@ -235,19 +237,25 @@ __global__ __launch_bounds__(kDecThreads) void decode_kernel(DecodeArgs a) {
   DD_MARK(0);
   // ---- the queue: items per head from head_rows[], exclusive prefix in LDS ----
   constexpr int kPer = kMaxQueueHeads / kDecThreads;  // consecutive heads per thread
-  int cnt[kPer], mine = 0;
+  int rows[kPer], chunks = 0;
 #pragma unroll
   for (int u = 0; u < kPer; ++u) {
     const int hh = tid * kPer + u;
-    int n = 0, R = 0;
-    if (hh < a.n_heads) {
-      R = a.plan.head_rows[a.head0 + hh];  // <= 0: nothing to do (empty, or attended already)
-      if (R > 0) {
-        const int c = rows_per_item(R, a.splits);
-        n = (R + c - 1) / c;
-      }
+    rows[u] = hh < a.n_heads ? a.plan.head_rows[a.head0 + hh] : 0;  // <= 0: nothing to do (empty, or attended already)
+    s_rows[hh] = rows[u];
+    if (rows[u] > 0) chunks += min(1 << 20, (rows[u] + kChunkRows - 1) / kChunkRows);  // capped: the sum stays in range
+  }
+  // least chunks per item: about one item for every second workgroup of the grid, between 1 and kMinItemChunks
+  const int all_chunks = block_sum<int, kDecWaves>(chunks, s_scan);
+  const int g = min(kMinItemChunks, max(1, (all_chunks + kDecodeGrid / 2 - 1) / (kDecodeGrid / 2)));
+  int cnt[kPer], mine = 0;
+#pragma unroll
+  for (int u = 0; u < kPer; ++u) {
+    int n = 0;
+    if (rows[u] > 0) {
+      const int c = rows_per_item(rows[u], a.splits, g);
+      n = (rows[u] + c - 1) / c;
     }
-    s_rows[hh] = R;
     cnt[u] = n;
     mine += n;
   }
@@ -273,7 +281,8 @@ __global__ __launch_bounds__(kDecThreads) void decode_kernel(DecodeArgs a) {
       if (s_first[mid] <= item) lo = mid; else hi = mid;
     }
     const int head = a.head0 + lo, split = item - s_first[lo];
-    decode_item(a, head, split, s_rows[lo], s_start, s_src, s_m, s_l, s_acc, &s_last, tid, lane16, grp);
+    decode_item(a, head, split, s_rows[lo], g, s_start, s_src, s_m, s_l, s_acc, &s_last, tid, lane16, grp);
+    if (total <= (int)gridDim.x) break;  // every item had its workgroup: nothing to claim
     if (tid == 0)
       s_item = gridDim.x + __hip_atomic_fetch_add(a.queue_next, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     __syncthreads();  // also: LDS is reused by the next item

@@ -12,6 +12,7 @@ constexpr int kHeadDim = 128;  // the only supported head dimension
 constexpr int kChunkRows = 64;
 // stage 3 pulls (head, split) items from a device-side queue: heads served per launch, workgroups per launch
 constexpr int kMaxQueueHeads = 1024;
+constexpr int kMaxSplits = 256;  // most partial slots per head
 #ifndef DP_DECODE_GRID
 #define DP_DECODE_GRID 1280
 #endif
@@ -78,6 +79,11 @@ hipError_t launch_plan(const CacheView &c, const int32_t *sel_ids, const int32_t
 
 hipError_t launch_decode(const CacheView &c, const int32_t *n_exact, const int32_t *n_retained, const Plan &plan,
                          float *partials, int splits, const AttnOut &attn, hipStream_t s);
+
+// Dense attention over rows [seg_row_base[seg], + seg_rows[seg]) of every segment for all its query heads.
+// partials: room for nh * max_splits * (kHeadDim + 2) floats.
+hipError_t launch_dense(const CacheView &c, const int32_t *seg_rows, float *partials, int max_splits,
+                        const AttnOut &attn, hipStream_t s);
 
 // largest max_clusters_per_seg the selection kernel supports
 constexpr int kSelectMaxClusters = 65536;

@@ -88,12 +88,14 @@ __device__ __forceinline__ u64 fixed40(float w) {
 __device__ __forceinline__ u64 fx_mass(float d) {
   return d < kCut ? fixed40(__builtin_amdgcn_exp2f(-d * kLog2e)) : 0;
 }
-__device__ __forceinline__ int level1_bin(float d) { return (int)fminf(d * kBinScale, (float)(kBins - 1)); }
+// level-1 bin of a cluster at distance d below the max logit; bs = bins per unit of d
+__device__ __forceinline__ int level1_bin(float d, float bs) { return (int)fminf(d * bs, (float)(kBins - 1)); }
 
 // The same threshold search serves two rules.  Top-p (kCount = false): a cluster weighs its
 // fixed-point softmax mass and is in play while that mass is non-zero.  Fixed budget (kCount =
 // true): every non-empty cluster weighs 1, so "the shortest prefix whose weight reaches k" is
-// the top-k of the order, and bins beyond kCut all fall into the last level-1 bin.
+// the top-k of the order; its level-1 bins are spread over the head's own range of logits
+// (max - min), because clusters far below the max still count.
 template <bool kCount>
 __device__ __forceinline__ bool in_play(float d) { return kCount ? d < INFINITY : d < kCut; }
 template <bool kCount>
@@ -162,7 +164,7 @@ __device__ __forceinline__ void reduce_members(int cnt, uint32_t lo, uint32_t hi
 // be ranked, or are a run of equal keys which is cut in index order.  On return either
 // cnt <= kMaxCand (members = keys in [klo, khi], not yet gathered) or the result is in sh.res_*.
 template <int E, bool kCount>
-__device__ __forceinline__ bool refine_or_cut_ties(const float (&l)[E], float mx, int base, int bin1, u64 tau,
+__device__ __forceinline__ bool refine_or_cut_ties(const float (&l)[E], float mx, float bs, int base, int bin1, u64 tau,
                                                 u64 &before, uint32_t &klo, uint32_t &khi, int &cnt, Shared &sh) {
   const int tid = threadIdx.x;
   {
@@ -171,7 +173,7 @@ __device__ __forceinline__ bool refine_or_cut_ties(const float (&l)[E], float mx
 #pragma unroll
     for (int e = 0; e < E; ++e) {
       const float d = mx - l[e];
-      if (in_play<kCount>(d) && level1_bin(d) == bin1) {
+      if (in_play<kCount>(d) && level1_bin(d, bs) == bin1) {
         const uint32_t k = ordered_key(l[e]);
         ++c;
         lo = min(lo, k);
@@ -274,7 +276,7 @@ __device__ __forceinline__ bool refine_or_cut_ties(const float (&l)[E], float mx
 // cached_*: the bin whose members are currently gathered in sh.cand_* (reused when the
 // second threshold falls into the same bin).  Block-uniform control flow.
 template <int E, bool kCount>
-__device__ __forceinline__ void find_prefix(const float (&l)[E], float mx, int base, u64 tau, u64 ex, u64 h0, u64 h1,
+__device__ __forceinline__ void find_prefix(const float (&l)[E], float mx, float bs, int base, u64 tau, u64 ex, u64 h0, u64 h1,
                                             int slot, Shared &sh, int &cached_bin, int &cached_cnt,
                                             u64 &cached_before, uint32_t &key_o, int &idx_o, u64 &mass_o) {
   const int tid = threadIdx.x;
@@ -298,7 +300,7 @@ __device__ __forceinline__ void find_prefix(const float (&l)[E], float mx, int b
 #pragma unroll
     for (int e = 0; e < E; ++e) {
       const float d = mx - l[e];
-      if (in_play<kCount>(d) && level1_bin(d) == bin1) {
+      if (in_play<kCount>(d) && level1_bin(d, bs) == bin1) {
         const int s = atomicAdd(&sh.ncand[slot], 1);
         if (s < kMaxCand) {
           sh.cand_key[s] = ordered_key(l[e]);
@@ -315,7 +317,7 @@ __device__ __forceinline__ void find_prefix(const float (&l)[E], float mx, int b
     if (cnt > kMaxCand) {
       cached_bin = -1;  // the candidate arrays will not hold this bin
       uint32_t klo, khi;
-      done = refine_or_cut_ties<E, kCount>(l, mx, base, bin1, tau, before, klo, khi, cnt, sh);
+      done = refine_or_cut_ties<E, kCount>(l, mx, bs, base, bin1, tau, before, klo, khi, cnt, sh);
       if (!done) {
         if (tid == 0) sh.ncand[slot] = 0;
         __syncthreads();
@@ -532,6 +534,17 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(SelectArgs a) {
     return;
   }
 
+  // level-1 bins: top-p spreads them over the kCut below the max that carries mass; a fixed budget
+  // spreads them over the head's whole range of finite logits
+  float bs = kBinScale;
+  if (kCount) {
+    float tmin = INFINITY;
+#pragma unroll
+    for (int e = 0; e < E; ++e) tmin = fminf(tmin, l[e] == -INFINITY ? INFINITY : l[e]);
+    const float mn = -block_max<kSelWaves>(-tmin, sh.scrf);
+    bs = mx > mn ? ((float)kBins - 0.5f) / (mx - mn) : 0.f;
+  }
+
   // ---- total mass; how many clusters are close to the top ------------------
   u64 wsum = 0;
   int ctop = 0;
@@ -653,7 +666,7 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(SelectArgs a) {
     for (int e = 0; e < E; ++e) {
       const float d = mx - l[e];
       const u64 m = mass_of<kCount>(d);
-      if (m) atomicAdd(&sh.hist[level1_bin(d)], m);
+      if (m) atomicAdd(&sh.hist[level1_bin(d, bs)], m);
     }
     __syncthreads();
     const u64 h0 = sh.hist[2 * tid], h1 = sh.hist[2 * tid + 1];
@@ -670,7 +683,7 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(SelectArgs a) {
       idx1 = INT_MAX;
       mass1 = W;
     } else {
-      find_prefix<E, kCount>(l, mx, base, first_tau<kCount>(a, W), ex, h0, h1, 0, sh, cached_bin, cached_cnt,
+      find_prefix<E, kCount>(l, mx, bs, base, first_tau<kCount>(a, W), ex, h0, h1, 0, sh, cached_bin, cached_cnt,
                              cached_before, key1, idx1, mass1);
     }
     u64 tau2 = 0;
@@ -684,7 +697,7 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(SelectArgs a) {
     } else {
       u64 mass2;
       __syncthreads();  // sh.bin / sh.res_* of the first search have been read by every thread
-      find_prefix<E, kCount>(l, mx, base, tau2, ex, h0, h1, 1, sh, cached_bin, cached_cnt, cached_before, key2, idx2,
+      find_prefix<E, kCount>(l, mx, bs, base, tau2, ex, h0, h1, 1, sh, cached_bin, cached_cnt, cached_before, key2, idx2,
                              mass2);
     }
 

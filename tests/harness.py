@@ -139,6 +139,36 @@ def gpu_decode_attention(cache: ClusteredCache, p1: float, p2: float, flags: int
                    approx=[sel[i, ne[i]:nr[i]].copy() for i in range(nh)], n_exact_tokens=nt, logits=logits)
 
 
+def segment_rows(cache: ClusteredCache) -> np.ndarray:
+    """Rows of each KV segment, or None when the clusters of some segment do not tile [0, rows)
+    without gaps (then the segment's tokens are not one contiguous row range)."""
+    n_seg = cache.batch * cache.n_kv_heads
+    rows = np.zeros(n_seg, dtype=np.int32)
+    for seg in range(n_seg):
+        a, e = int(cache.seg_cluster_ptr[seg]), int(cache.seg_cluster_ptr[seg + 1])
+        off, sz = cache.cluster_offsets[a:e].astype(np.int64), cache.cluster_sizes[a:e].astype(np.int64)
+        order = np.argsort(off, kind="stable")
+        if e > a and not (off[order][0] == 0 and (off[order][1:] == np.cumsum(sz[order])[:-1]).all()):
+            return None
+        rows[seg] = int(sz.sum())
+    return rows
+
+
+def gpu_dense_decode(cache: ClusteredCache, seg_rows: np.ndarray, sm_scale: float = 0.0, out_bf16: bool = False):
+    import torch
+    import paper_2602_05191_amd as dp
+    dc = dp.DeviceCache.from_host(cache)
+    pr = dp.Problem(dc, sm_scale=sm_scale)
+    nh = cache.batch * cache.n_q_heads
+    ws = torch.empty(max(dp.dp_workspace_bytes(pr), 256), dtype=torch.uint8, device="cuda:0")
+    out = torch.full((cache.batch, cache.n_q_heads, cache.head_dim), float("nan"),
+                     dtype=torch.bfloat16 if out_bf16 else torch.float32, device="cuda:0")
+    lse = torch.full((nh,), float("nan"), dtype=torch.float32, device="cuda:0")
+    dp.dp_dense_decode(pr, torch.from_numpy(np.ascontiguousarray(seg_rows, dtype=np.int32)).cuda(), out, lse, ws)
+    torch.cuda.synchronize()
+    return out.float().cpu().numpy(), lse.cpu().numpy().reshape(cache.batch, cache.n_q_heads)
+
+
 # ---------------------------------------------------------------------------
 # comparison rules
 # ---------------------------------------------------------------------------

@@ -73,3 +73,16 @@ def test_full_size_cfg2_fixed_budget():
         assert np.array_equal(g.exact[i], s.exact) and np.array_equal(g.approx[i], s.approx), i
     worst, rel = H.check_outputs(cache, orc, g, tight=2e-4)
     print(f"[cfg2 budget {budget}] max-abs {worst:.2e} rel-L2 {rel:.2e}")
+
+
+@pytest.mark.parametrize("idx", [2, 3])
+def test_full_size_dense_baseline(idx):
+    """Full attention over 128k tokens per KV head; the oracle checks every head."""
+    cache = make_config(idx)
+    orc = oracle.Oracle(cache)
+    out, lse = H.gpu_dense_decode(cache, H.segment_rows(cache))
+    print(f"[cfg{idx} dense] gpu done", flush=True)
+    ref, ref_lse, _ = orc.dense_step(n_threads=8)
+    worst = float(np.abs(out - ref).max())
+    assert worst <= 2e-4 and np.abs(lse - ref_lse).max() <= 1e-3, worst
+    print(f"[cfg{idx} dense] max-abs {worst:.2e}")

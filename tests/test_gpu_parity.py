@@ -317,6 +317,47 @@ def test_budget_ties_are_cut_by_index():
 
 
 # ---------------------------------------------------------------------------
+# dense baseline (Eq. 1): dp_dense_decode
+# ---------------------------------------------------------------------------
+def check_dense(cache, orc, out, lse, tight=2e-4):
+    ref, ref_lse, _ = orc.dense_step(n_threads=4)
+    d = out.astype(np.float64) - ref
+    worst = float(np.abs(d).max()) if d.size else 0.0
+    den = float((ref * ref).sum())
+    rel = (float((d * d).sum()) / den) ** 0.5 if den > 0 else 0.0
+    assert worst <= min(H.OUT_MAX_ABS, tight) and rel <= H.OUT_REL_L2, (worst, rel)
+    fin = np.isfinite(ref_lse)
+    assert (np.abs(lse[fin] - ref_lse[fin]) <= 1e-3 + 1e-5 * np.abs(ref_lse[fin])).all()
+    assert np.isneginf(lse[~fin]).all() and (out[~fin] == 0).all()
+    return worst, rel
+
+
+def test_dense_decode_matches_oracle(case):
+    name, cache, p1, p2, orc = case
+    rows = H.segment_rows(cache)
+    if rows is None:
+        pytest.skip("clusters with emptied sizes leave gaps: the segment is not a contiguous row range")
+    out, lse = H.gpu_dense_decode(cache, rows)
+    check_dense(cache, orc, out, lse)
+
+
+def test_dense_decode_bf16_output_and_scale():
+    c = make_cache(batch=2, n_kv_heads=2, n_q_heads=8, context=[5000, 129], mean_cluster=16, q_scale=0.6, seed=51)
+    orc = oracle.Oracle(c, sm_scale=0.05)
+    out, lse = H.gpu_dense_decode(c, H.segment_rows(c), sm_scale=0.05, out_bf16=True)
+    ref, ref_lse, _ = orc.dense_step(n_threads=4)
+    assert np.abs(out - ref).max() <= 2e-4 + np.abs(ref).max() * 2.0 ** -8   # one bf16 rounding of the result
+    assert np.abs(lse - ref_lse).max() <= 1e-3
+
+
+def test_dense_decode_equals_the_sparse_path_with_everything_exact():
+    c = make_cache(batch=1, n_kv_heads=2, n_q_heads=8, context=6000, mean_cluster=16, q_scale=0.5, seed=52)
+    out, lse = H.gpu_dense_decode(c, H.segment_rows(c))
+    g = H.gpu_decode_attention(c, 1.0, 1.0)
+    assert np.abs(out - g.out).max() <= 1e-5 and np.abs(lse - g.lse).max() <= 1e-4
+
+
+# ---------------------------------------------------------------------------
 # error paths of the boundary (host-side checks; nothing is launched)
 # ---------------------------------------------------------------------------
 def test_boundary_rejects_bad_arguments():
