@@ -54,6 +54,10 @@ typedef unsigned long long u64;
 #define DP_MARK(i) do { } while (0)
 #endif
 
+#ifdef DP_PHASE_CLOCKS
+__device__ unsigned long long *g_dbg_ptr = nullptr;
+#endif
+
 struct SelectArgs {
   const float *logits;
   const int32_t *seg_cluster_ptr, *cluster_sizes, *cluster_offsets;
@@ -104,7 +108,7 @@ __device__ __forceinline__ u64 mass_of(float d) { return kCount ? (u64)(d < INFI
 struct Shared {
   u64 hist[kBins];
   u64 hist2[kBins];
-  u64 scr64[kSelWaves];
+  u64 scr64[kSelWaves], scr64b[kSelWaves];
   float scrf[kSelWaves];
   int scri[3 * kSelWaves];
   uint32_t red_lo[kSelWaves], red_hi[kSelWaves];
@@ -122,7 +126,7 @@ struct Shared {
   uint32_t top_key[kTopMax];
   int top_idx[kTopMax], top_sz[kTopMax], top_off[kTopMax];
   u64 top_m[kTopMax];
-  int ntop, fast_ok, f_nex, f_nap, f_ntok;
+  int ntop, f_nex, f_nap, f_ntok;
   // inline attention
   int l_start[kInlineRows + 1];
   int l_src[kInlineRows];
@@ -162,19 +166,31 @@ __device__ __forceinline__ void reduce_members(int cnt, uint32_t lo, uint32_t hi
 // Rare path: the crossing bin holds more than kMaxCand clusters.  Narrow the key range
 // [klo, khi] (by up-to-2048-way splits of the key range, re-histogrammed in sh.hist2) until the members can
 // be ranked, or are a run of equal keys which is cut in index order.  On return either
-// cnt <= kMaxCand (members = keys in [klo, khi], not yet gathered) or the result is in sh.res_*.
+// cnt <= kMaxCand (members = keys in [klo, khi], not yet gathered) or done and the result is in sh.res_*.
+// The logits are read again from memory in rolled loops, so that this path adds nothing to the register
+// pressure of the common one (it costs a few global round trips per pass instead).
+struct Refined {
+  u64 before;
+  uint32_t klo, khi;
+  int cnt;
+  bool done;
+};
 template <int E, bool kCount>
-__device__ __forceinline__ bool refine_or_cut_ties(const float (&l)[E], float mx, float bs, int base, int bin1, u64 tau,
-                                                u64 &before, uint32_t &klo, uint32_t &khi, int &cnt, Shared &sh) {
+__device__ __forceinline__ Refined refine_or_cut_ties(const float *lg, int kc, float mx, float bs, int base, int bin1,
+                                                      u64 tau, u64 before, Shared *shp) {
+  Shared &sh = *shp;
   const int tid = threadIdx.x;
+  auto logit = [&](int e) { return (base + e < kc) ? lg[base + e] + 0.0f : -INFINITY; };
+  uint32_t klo, khi;
+  int cnt;
   {
     int c = 0;
     uint32_t lo = 0xffffffffu, hi = 0;
-#pragma unroll
+#pragma unroll 1
     for (int e = 0; e < E; ++e) {
-      const float d = mx - l[e];
+      const float le = logit(e), d = mx - le;
       if (in_play<kCount>(d) && level1_bin(d, bs) == bin1) {
-        const uint32_t k = ordered_key(l[e]);
+        const uint32_t k = ordered_key(le);
         ++c;
         lo = min(lo, k);
         hi = max(hi, k);
@@ -188,10 +204,10 @@ __device__ __forceinline__ bool refine_or_cut_ties(const float (&l)[E], float mx
     __syncthreads();
     // 2048-way split of the key range by a shift: monotone in the key, no division
     const int shift = max(0, 32 - __clz(khi - klo) - 11);
-#pragma unroll
+#pragma unroll 1
     for (int e = 0; e < E; ++e) {
-      const float d = mx - l[e];
-      const uint32_t k = ordered_key(l[e]);
+      const float le = logit(e), d = mx - le;
+      const uint32_t k = ordered_key(le);
       if (in_play<kCount>(d) && k >= klo && k <= khi) {
         const u64 m = mass_of<kCount>(d);
         if (m) atomicAdd(&sh.hist2[(khi - k) >> shift], m);
@@ -216,10 +232,10 @@ __device__ __forceinline__ bool refine_or_cut_ties(const float (&l)[E], float mx
     before += sh.before;
     int c = 0;
     uint32_t lo = 0xffffffffu, hi = 0;
-#pragma unroll
+#pragma unroll 1
     for (int e = 0; e < E; ++e) {
-      const float d = mx - l[e];
-      const uint32_t k = ordered_key(l[e]);
+      const float le = logit(e), d = mx - le;
+      const uint32_t k = ordered_key(le);
       if (in_play<kCount>(d) && k >= klo && k <= khi && (int)((khi - k) >> shift) == bin2) {
         ++c;
         lo = min(lo, k);
@@ -228,17 +244,19 @@ __device__ __forceinline__ bool refine_or_cut_ties(const float (&l)[E], float mx
     }
     reduce_members(c, lo, hi, sh, cnt, klo, khi);
   }
-  if (cnt <= kMaxCand) return false;
+  if (cnt <= kMaxCand) return Refined{before, klo, khi, cnt, false};
 
   // one distinct key: a run of ties of equal mass, cut in cluster-index order
   int c = 0;
   u64 mm = 0;
-#pragma unroll
-  for (int e = 0; e < E; ++e)
-    if (in_play<kCount>(mx - l[e]) && ordered_key(l[e]) == klo) {
+#pragma unroll 1
+  for (int e = 0; e < E; ++e) {
+    const float le = logit(e);
+    if (in_play<kCount>(mx - le) && ordered_key(le) == klo) {
       ++c;
-      mm = mass_of<kCount>(mx - l[e]);
+      mm = mass_of<kCount>(mx - le);
     }
+  }
 #pragma unroll
   for (int d = 32; d >= 1; d >>= 1) {
     const u64 o = __shfl_xor(mm, d, 64);
@@ -255,9 +273,10 @@ __device__ __forceinline__ bool refine_or_cut_ties(const float (&l)[E], float mx
   const int ex = block_excl_scan<int, kSelWaves>(c, sh.scri, tot);
   if ((u64)ex < need && need <= (u64)(ex + c)) {
     int seen = ex;
-#pragma unroll
-    for (int e = 0; e < E; ++e)
-      if (in_play<kCount>(mx - l[e]) && ordered_key(l[e]) == klo) {
+#pragma unroll 1
+    for (int e = 0; e < E; ++e) {
+      const float le = logit(e);
+      if (in_play<kCount>(mx - le) && ordered_key(le) == klo) {
         ++seen;
         if ((u64)seen == need) {
           sh.res_key = klo;
@@ -265,9 +284,10 @@ __device__ __forceinline__ bool refine_or_cut_ties(const float (&l)[E], float mx
           sh.res_mass = before + need * m_tie;
         }
       }
+    }
   }
   __syncthreads();
-  return true;
+  return Refined{before, klo, khi, cnt, true};
 }
 
 // Last element (key, index) of the shortest prefix of the order whose mass reaches tau
@@ -276,7 +296,7 @@ __device__ __forceinline__ bool refine_or_cut_ties(const float (&l)[E], float mx
 // cached_*: the bin whose members are currently gathered in sh.cand_* (reused when the
 // second threshold falls into the same bin).  Block-uniform control flow.
 template <int E, bool kCount>
-__device__ __forceinline__ void find_prefix(const float (&l)[E], float mx, float bs, int base, u64 tau, u64 ex, u64 h0, u64 h1,
+__device__ __forceinline__ void find_prefix(const float (&l)[E], const float *lg, int kc, float mx, float bs, int base, u64 tau, u64 ex, u64 h0, u64 h1,
                                             int slot, Shared &sh, int &cached_bin, int &cached_cnt,
                                             u64 &cached_before, uint32_t &key_o, int &idx_o, u64 &mass_o) {
   const int tid = threadIdx.x;
@@ -311,13 +331,19 @@ __device__ __forceinline__ void find_prefix(const float (&l)[E], float mx, float
     }
     __syncthreads();
     cnt = sh.ncand[slot];
+#ifdef DP_PHASE_CLOCKS
+    if (threadIdx.x == 0 && g_dbg_ptr) g_dbg_ptr[blockIdx.x * 16 + 13 + slot] = cnt;
+#endif
     cached_bin = bin1;
     cached_cnt = cnt;
     cached_before = before;
     if (cnt > kMaxCand) {
       cached_bin = -1;  // the candidate arrays will not hold this bin
-      uint32_t klo, khi;
-      done = refine_or_cut_ties<E, kCount>(l, mx, bs, base, bin1, tau, before, klo, khi, cnt, sh);
+      const Refined rf = refine_or_cut_ties<E, kCount>(lg, kc, mx, bs, base, bin1, tau, before, &sh);
+      const uint32_t klo = rf.klo, khi = rf.khi;
+      before = rf.before;
+      cnt = rf.cnt;
+      done = rf.done;
       if (!done) {
         if (tid == 0) sh.ncand[slot] = 0;
         __syncthreads();
@@ -453,6 +479,10 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(SelectArgs a) {
 
   if (plan && tid == 0 && head % kMaxQueueHeads == 0) a.plan.queue_next[head / kMaxQueueHeads] = 0;
 
+#ifdef DP_PHASE_CLOCKS
+  if (threadIdx.x == 0) g_dbg_ptr = a.dbg;
+  __syncthreads();
+#endif
   DP_MARK(0);
   // ---- load, max ---------------------------------------------------------
   float l[E];
@@ -546,31 +576,39 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(SelectArgs a) {
   }
 
   // ---- total mass; how many clusters are close to the top ------------------
-  u64 wsum = 0;
+  u64 wsum = 0, wtop = 0;
   int ctop = 0;
 #pragma unroll
   for (int e = 0; e < E; ++e) {
     const float d = mx - l[e];
     if (in_play<kCount>(d)) {
-      wsum += mass_of<kCount>(d);
-      ctop += d < kTopCut;
+      const u64 m = mass_of<kCount>(d);
+      wsum += m;
+      if (d < kTopCut) {
+        ++ctop;
+        wtop += m;
+      }
     }
   }
   int ntop;
-  u64 W;  // total weight; top-p: >= 2^40 (the max element has weight 1); fixed budget: the non-empty clusters
+  u64 W, Wtop;  // total weight (top-p: >= 2^40, the max element has weight 1; fixed budget: the non-empty clusters), weight of the top set
   {
     wsum = wave_sum(wsum);
+    wtop = wave_sum(wtop);
     ctop = wave_sum(ctop);
     if (lane_id() == 0) {
       sh.scr64[wave_id()] = wsum;
+      sh.scr64b[wave_id()] = wtop;
       sh.scri[wave_id()] = ctop;
     }
     __syncthreads();
     W = 0;
+    Wtop = 0;
     ntop = 0;
 #pragma unroll
     for (int w = 0; w < kSelWaves; ++w) {
       W += sh.scr64[w];
+      Wtop += sh.scr64b[w];
       ntop += sh.scri[w];
     }
   }
@@ -578,10 +616,11 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(SelectArgs a) {
 
   int n_ex, n_ap, n_tok;
   const bool all = retain_all<kCount>(a, W);  // every non-empty cluster is retained
-  bool fast = !all && ntop <= kTopMax;
+  // fast path: the top set is small and already holds the first threshold's weight (integer sums: exact), so
+  // the retained set lies inside it (the usual case for a peaked head)
+  const bool fast = !all && ntop <= kTopMax && Wtop >= first_tau<kCount>(a, W);
   if (fast) {
-    // ---- fast path: the retained set lies inside the top set (the usual case for a peaked
-    // head).  Gather the top set with its sizes / offsets, then one wave ranks it pairwise. ----
+    // ---- gather the top set with its sizes / offsets, then one wave ranks it pairwise ----
 #pragma unroll
     for (int e = 0; e < E; ++e) {
       const float d = mx - l[e];
@@ -608,10 +647,8 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(SelectArgs a) {
         const uint32_t kj = sh.top_key[j];
         if (kj > key_i || (kj == key_i && sh.top_idx[j] < idx_i)) ahead += sh.top_m[j];
       }
-      const u64 top_mass = wave_sum(m_i);
       const u64 tau1 = first_tau<kCount>(a, W);
-      const bool ok = top_mass >= tau1;  // otherwise the prefix reaches below the top set
-      if (ok) {
+      {
         const bool ret = act && ahead < tau1;
         u64 m1 = ret ? ahead + m_i : 0;  // mass of the retained prefix = the largest inclusive prefix
 #pragma unroll
@@ -650,10 +687,8 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(SelectArgs a) {
           sh.f_ntok = n_tok;
         }
       }
-      if (i == 0) sh.fast_ok = ok;
     }
     __syncthreads();
-    fast = sh.fast_ok;
     n_ex = sh.f_nex;
     n_ap = sh.f_nap;
     n_tok = sh.f_ntok;
@@ -669,9 +704,11 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(SelectArgs a) {
       if (m) atomicAdd(&sh.hist[level1_bin(d, bs)], m);
     }
     __syncthreads();
+    DP_MARK(8);
     const u64 h0 = sh.hist[2 * tid], h1 = sh.hist[2 * tid + 1];
     u64 Wh;  // equals W: the same masses, summed in another order
     const u64 ex = block_excl_scan<u64, kSelWaves>(h0 + h1, sh.scr64, Wh);
+    DP_MARK(9);
 
     uint32_t key1, key2;
     int idx1, idx2;
@@ -683,9 +720,10 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(SelectArgs a) {
       idx1 = INT_MAX;
       mass1 = W;
     } else {
-      find_prefix<E, kCount>(l, mx, bs, base, first_tau<kCount>(a, W), ex, h0, h1, 0, sh, cached_bin, cached_cnt,
+      find_prefix<E, kCount>(l, lg, kc, mx, bs, base, first_tau<kCount>(a, W), ex, h0, h1, 0, sh, cached_bin, cached_cnt,
                              cached_before, key1, idx1, mass1);
     }
+    DP_MARK(10);
     u64 tau2 = 0;
     const int kind = second_tau<kCount>(a, W, mass1, tau2);
     if (kind == 1) {
@@ -697,14 +735,15 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(SelectArgs a) {
     } else {
       u64 mass2;
       __syncthreads();  // sh.bin / sh.res_* of the first search have been read by every thread
-      find_prefix<E, kCount>(l, mx, bs, base, tau2, ex, h0, h1, 1, sh, cached_bin, cached_cnt, cached_before, key2, idx2,
+      find_prefix<E, kCount>(l, lg, kc, mx, bs, base, tau2, ex, h0, h1, 1, sh, cached_bin, cached_cnt, cached_before, key2, idx2,
                              mass2);
     }
 
+    DP_MARK(11);
     // ---- compaction in ascending cluster index ------------------------------
     // Only clusters in play (non-zero weight) can be selected, unless all non-empty ones are.
     u64 exa_mask = 0, ret_mask = 0;  // bit e: element e of this thread is exact / approximated
-    int sz[E], off[E];
+    int te = 0;                      // tokens of this thread's exact clusters
 #pragma unroll
     for (int e = 0; e < E; ++e) {
       const uint32_t k = ordered_key(l[e]);
@@ -714,22 +753,10 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(SelectArgs a) {
       const bool apx = live && !exa && (k > key1 || (k == key1 && i <= idx1));
       exa_mask |= (u64)exa << e;
       ret_mask |= (u64)apx << e;
-      if (kPre) {
-        sz[e] = exa ? psz[kPre ? e : 0] : 0;
-        off[e] = exa ? poff[kPre ? e : 0] : 0;
-      } else {
-        sz[e] = 0;
-        off[e] = 0;
-        if (exa) {  // loads are issued here and consumed after the loop
-          sz[e] = a.cluster_sizes[c0 + i];
-          if (plan) off[e] = a.cluster_offsets[c0 + i];
-        }
-      }
+      // sizes: preloaded, or fetched here for the sum and again (cached) when the entry is written
+      if (exa) te += kPre ? psz[kPre ? e : 0] : a.cluster_sizes[c0 + i];
     }
     const int ce = __popcll(exa_mask), ca = __popcll(ret_mask);
-    int te = 0;
-#pragma unroll
-    for (int e = 0; e < E; ++e) te += sz[e];
     int pe, pa, pt;
     {
       // one scan for the three counters
@@ -768,6 +795,7 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(SelectArgs a) {
       pa = ba + ia - ca;
       pt = bt + it - te;
     }
+    DP_MARK(12);
     emit.to_lds = can_inline && n_tok + n_ap <= kInlineRows;
     emit.n_ex = n_ex;
     emit.n_tok = n_tok;
@@ -775,9 +803,11 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(SelectArgs a) {
 #pragma unroll
       for (int e = 0; e < E; ++e) {
         if ((exa_mask >> e) & 1) {
-          emit.exact(pe, pt, sz[e], off[e], base + e);
+          const int sz = kPre ? psz[kPre ? e : 0] : a.cluster_sizes[c0 + base + e];
+          const int off = !plan ? 0 : kPre ? poff[kPre ? e : 0] : a.cluster_offsets[c0 + base + e];
+          emit.exact(pe, pt, sz, off, base + e);
           ++pe;
-          pt += sz[e];
+          pt += sz;
         } else if ((ret_mask >> e) & 1) {
           emit.approx(pa, base + e);
           ++pa;
