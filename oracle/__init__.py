@@ -14,7 +14,7 @@ from __future__ import annotations
 import ctypes as C
 import os
 import subprocess
-from dataclasses import dataclass
+from dataclasses import dataclass, field
 from typing import List, Optional, Sequence, Tuple
 
 import numpy as np
@@ -43,7 +43,8 @@ class _Cache(C.Structure):
                 ("q", C.c_void_p), ("k_cache", C.c_void_p), ("v_cache", C.c_void_p),
                 ("seg_row_base", C.c_void_p), ("seg_cluster_ptr", C.c_void_p),
                 ("cluster_offsets", C.c_void_p), ("cluster_sizes", C.c_void_p),
-                ("k_centroids", C.c_void_p), ("v_centroids", C.c_void_p), ("sm_scale", C.c_double)]
+                ("k_centroids", C.c_void_p), ("v_centroids", C.c_void_p), ("sm_scale", C.c_double),
+                ("cluster_flags", C.c_void_p)]
 
 
 _lib = None
@@ -60,6 +61,10 @@ def _load():
         L.dpo_num_clusters.argtypes = [CP, I, I]
         L.dpo_centroid_logits.restype = None
         L.dpo_centroid_logits.argtypes = [CP, I, I, P]
+        L.dpo_candidate_logits.restype = None
+        L.dpo_candidate_logits.argtypes = [CP, I, I, P]
+        L.dpo_pinned_clusters.restype = I
+        L.dpo_pinned_clusters.argtypes = [CP, I, I, P]
         L.dpo_cluster_distribution.restype = None
         L.dpo_cluster_distribution.argtypes = [P, I, P]
         L.dpo_sorted_order.restype = I
@@ -107,11 +112,15 @@ class Oracle:
             k_centroids=np.ascontiguousarray(cache.k_centroids, dtype=np.uint16),
             v_centroids=np.ascontiguousarray(cache.v_centroids, dtype=np.uint16),
         )
+        flags = getattr(cache, "cluster_flags", None)
+        if flags is not None:
+            self._a["cluster_flags"] = np.ascontiguousarray(flags, dtype=np.uint8)
         a = self._a
         self.c = _Cache(self.batch, self.n_kv_heads, self.n_q_heads, self.d, _ptr(a["q"]), _ptr(a["k_cache"]),
                         _ptr(a["v_cache"]), _ptr(a["seg_row_base"]), _ptr(a["seg_cluster_ptr"]),
                         _ptr(a["cluster_offsets"]), _ptr(a["cluster_sizes"]), _ptr(a["k_centroids"]),
-                        _ptr(a["v_centroids"]), float(sm_scale))
+                        _ptr(a["v_centroids"]), float(sm_scale),
+                        _ptr(a["cluster_flags"]) if flags is not None else None)
         self.cp = C.byref(self.c)
 
     # ---- per-head stages -------------------------------------------------
@@ -122,6 +131,17 @@ class Oracle:
         out = np.empty(max(1, self.num_clusters(b, h)), dtype=np.float64)
         self.lib.dpo_centroid_logits(self.cp, b, h, _ptr(out))
         return out[: self.num_clusters(b, h)]
+
+    def candidate_logits(self, b: int, h: int) -> np.ndarray:
+        """centroid_logits with the pinned clusters at -inf: what the selection runs on."""
+        out = np.empty(max(1, self.num_clusters(b, h)), dtype=np.float64)
+        self.lib.dpo_candidate_logits(self.cp, b, h, _ptr(out))
+        return out[: self.num_clusters(b, h)]
+
+    def pinned_clusters(self, b: int, h: int) -> np.ndarray:
+        out = np.empty(max(1, self.num_clusters(b, h)), dtype=np.int32)
+        n = self.lib.dpo_pinned_clusters(self.cp, b, h, _ptr(out))
+        return out[:n].copy()
 
     def cluster_distribution(self, logit: np.ndarray) -> np.ndarray:
         logit = np.ascontiguousarray(logit, dtype=np.float64)
@@ -145,22 +165,34 @@ class Oracle:
                                   C.addressof(k1), C.addressof(k2), C.addressof(m1))
         return k1.value, k2.value, m1.value, cum[: order.size]
 
-    def select(self, logit: np.ndarray, p1: float, p2: float, flags: int = 0) -> "Selection":
-        """Stage 2 from given logits (any float dtype; widened to double)."""
+    @staticmethod
+    def _candidates(logit: np.ndarray, pinned) -> np.ndarray:
+        logit = np.array(logit, dtype=np.float64)
+        if pinned is not None and len(pinned):
+            logit[np.asarray(pinned, dtype=np.int64)] = -np.inf
+        return logit
+
+    def select(self, logit: np.ndarray, p1: float, p2: float, flags: int = 0, pinned=None) -> "Selection":
+        """Stage 2 from given logits (any float dtype; widened to double).  pinned: ids of the non-empty
+        pinned clusters of the head (pinned_clusters): out of the distribution, always exact."""
+        logit = self._candidates(logit, pinned)
         a_hat = self.cluster_distribution(logit)
         order = self.sorted_order(logit)
         k1, k2, m1, cum = self.double_top_p(a_hat, order, p1, p2, flags)
-        return Selection(order=order, k1=k1, k2=k2, m1=m1, cum=cum, a_hat=a_hat)
+        return Selection(order=order, k1=k1, k2=k2, m1=m1, cum=cum, a_hat=a_hat,
+                         pinned=np.asarray(pinned if pinned is not None else [], dtype=np.int32))
 
-    def fixed_budget(self, logit: np.ndarray, k_retained: int, k_exact: int) -> "Selection":
+    def fixed_budget(self, logit: np.ndarray, k_retained: int, k_exact: int, pinned=None) -> "Selection":
         """Fixed-budget selection from given logits (Sec. 5.1, cluster-based baseline)."""
+        logit = self._candidates(logit, pinned)
         a_hat = self.cluster_distribution(logit)
         order = self.sorted_order(logit)
         k1, k2 = C.c_int32(), C.c_int32()
         self.lib.dpo_fixed_budget(order.size, int(k_retained), int(k_exact), C.addressof(k1), C.addressof(k2))
         cum = np.cumsum(a_hat[order]) if order.size else np.zeros(0)
         m1 = float(cum[k1.value - 1]) if k1.value > 0 else 0.0
-        return Selection(order=order, k1=k1.value, k2=k2.value, m1=m1, cum=cum, a_hat=a_hat)
+        return Selection(order=order, k1=k1.value, k2=k2.value, m1=m1, cum=cum, a_hat=a_hat,
+                         pinned=np.asarray(pinned if pinned is not None else [], dtype=np.int32))
 
     def mixed_attention(self, b: int, h: int, exact_ids: Sequence[int], approx_ids: Sequence[int]):
         ex = np.ascontiguousarray(exact_ids, dtype=np.int32)
@@ -231,10 +263,11 @@ class Selection:
     m1: float           # mass of the retained set under A_hat
     cum: np.ndarray     # cum[k] = mass of order[:k+1]
     a_hat: np.ndarray   # Eq. 6 distribution, by cluster index
+    pinned: np.ndarray = field(default_factory=lambda: np.zeros(0, np.int32))  # always exact, outside the order
 
     @property
     def exact(self) -> np.ndarray:
-        return np.sort(self.order[: self.k2])
+        return np.sort(np.concatenate([self.pinned, self.order[: self.k2]]).astype(np.int32))
 
     @property
     def approx(self) -> np.ndarray:
@@ -242,7 +275,7 @@ class Selection:
 
     @property
     def retained(self) -> np.ndarray:
-        return np.sort(self.order[: self.k1])
+        return np.sort(np.concatenate([self.pinned, self.order[: self.k1]]).astype(np.int32))
 
 
 @dataclass

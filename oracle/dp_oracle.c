@@ -240,6 +240,36 @@ void dpo_exact_cluster_log_mass(const dpo_cache *c, int32_t b, int32_t h, double
   }
 }
 
+/* ---- pinned clusters (Sec. 5.1: sink and window tokens stay dense, the selection sees the rest) ---- */
+static int is_pinned(const dpo_cache *c, int32_t cluster) {
+  return c->cluster_flags && (c->cluster_flags[cluster] & DPO_CLUSTER_PINNED);
+}
+
+void dpo_candidate_logits(const dpo_cache *c, int32_t b, int32_t h, double *logit) {
+  const int32_t seg = seg_of(c, b, h);
+  const int32_t c0 = c->seg_cluster_ptr[seg], n = c->seg_cluster_ptr[seg + 1] - c0;
+  dpo_centroid_logits(c, b, h, logit);
+  for (int32_t i = 0; i < n; ++i)
+    if (is_pinned(c, c0 + i)) logit[i] = -INFINITY;
+}
+
+int32_t dpo_pinned_clusters(const dpo_cache *c, int32_t b, int32_t h, int32_t *ids) {
+  const int32_t seg = seg_of(c, b, h);
+  const int32_t c0 = c->seg_cluster_ptr[seg], n = c->seg_cluster_ptr[seg + 1] - c0;
+  int32_t m = 0;
+  for (int32_t i = 0; i < n; ++i)
+    if (is_pinned(c, c0 + i) && c->cluster_sizes[c0 + i] > 0) ids[m++] = i;
+  return m;
+}
+
+/* exact set of a head = the pinned clusters, then the first k2 clusters of the order */
+static int32_t exact_with_pinned(const dpo_cache *c, int32_t b, int32_t h, const int32_t *order, int32_t k2,
+                                 int32_t *exact) {
+  int32_t m = dpo_pinned_clusters(c, b, h, exact);
+  for (int32_t r = 0; r < k2; ++r) exact[m++] = order[r];
+  return m;
+}
+
 /* ---- one head of the decode step: the stages chained in the paper's order ---- */
 static void decode_head(const dpo_cache *c, int32_t b, int32_t h, double p1, double p2, uint32_t flags, double *out,
                         double *lse, int32_t *k1, int32_t *k2, int32_t *order_out) {
@@ -250,12 +280,15 @@ static void decode_head(const dpo_cache *c, int32_t b, int32_t h, double p1, dou
   double *cum = (double *)malloc(sizeof(double) * m);
   int32_t *order = (int32_t *)malloc(sizeof(int32_t) * m);
   double m1;
-  dpo_centroid_logits(c, b, h, logit);
+  int32_t *exact = (int32_t *)malloc(sizeof(int32_t) * m);
+  dpo_candidate_logits(c, b, h, logit);
   dpo_cluster_distribution(logit, n, a_hat);
   int32_t nn = dpo_sorted_order(logit, n, order);
   dpo_double_top_p(a_hat, order, nn, p1, p2, flags, cum, k1, k2, &m1);
-  dpo_mixed_attention(c, b, h, order, *k2, order + *k2, *k1 - *k2, out, lse);
+  int32_t ne = exact_with_pinned(c, b, h, order, *k2, exact);
+  dpo_mixed_attention(c, b, h, exact, ne, order + *k2, *k1 - *k2, out, lse);
   if (order_out) memcpy(order_out, order, sizeof(int32_t) * (size_t)nn);
+  free(exact);
   free(logit);
   free(a_hat);
   free(cum);
@@ -299,11 +332,14 @@ static void budget_head(const dpo_cache *c, int32_t b, int32_t h, int32_t k_reta
   size_t m = (size_t)(n > 0 ? n : 1);
   double *logit = (double *)malloc(sizeof(double) * m);
   int32_t *order = (int32_t *)malloc(sizeof(int32_t) * m);
-  dpo_centroid_logits(c, b, h, logit);
+  int32_t *exact = (int32_t *)malloc(sizeof(int32_t) * m);
+  dpo_candidate_logits(c, b, h, logit);
   int32_t nn = dpo_sorted_order(logit, n, order);
   dpo_fixed_budget(nn, k_retained, k_exact, k1, k2);
-  dpo_mixed_attention(c, b, h, order, *k2, order + *k2, *k1 - *k2, out, lse);
+  int32_t ne = exact_with_pinned(c, b, h, order, *k2, exact);
+  dpo_mixed_attention(c, b, h, exact, ne, order + *k2, *k1 - *k2, out, lse);
   if (order_out) memcpy(order_out, order, sizeof(int32_t) * (size_t)nn);
+  free(exact);
   free(logit);
   free(order);
 }

@@ -42,7 +42,14 @@ typedef struct {
   const uint16_t *k_centroids;    /* bf16 [total_clusters, head_dim]  C_i                    */
   const uint16_t *v_centroids;    /* bf16 [total_clusters, head_dim]  mean value of cluster  */
   double sm_scale;                /* 0 => 1/sqrt(head_dim)                                   */
+  const uint8_t *cluster_flags;   /* [total_clusters] DPO_CLUSTER_* bits; NULL = none set     */
 } dpo_cache;
+
+/* A pinned cluster holds tokens that every method keeps dense (the sink and
+ * sliding-window tokens of Sec. 5.1): it takes no part in the cluster
+ * distribution (Eq. 6, Eq. 7 and the second top-p run over the other, "middle"
+ * clusters only) and its tokens are always in the exact token set of Eq. 8/9. */
+#define DPO_CLUSTER_PINNED 1u
 
 /* Second top-p reading: default = threshold p2 * (mass retained by the first
  * top-p); with this flag = min(p2, that mass), i.e. p2 on the full distribution. */
@@ -53,6 +60,14 @@ int32_t dpo_num_clusters(const dpo_cache *c, int32_t b, int32_t h);
 
 /* Eq. 3 + Eq. 5: logit[i] = q.C_i/sqrt(d) + ln s_i  (= log Zhat_i); -inf if s_i == 0. */
 void dpo_centroid_logits(const dpo_cache *c, int32_t b, int32_t h, double *logit);
+
+/* dpo_centroid_logits with the pinned clusters set to -inf: the logits of the
+ * candidates of the cluster distribution. */
+void dpo_candidate_logits(const dpo_cache *c, int32_t b, int32_t h, double *logit);
+
+/* Pinned, non-empty clusters of the head's segment in ascending order; returns
+ * their number. ids: room for dpo_num_clusters entries. */
+int32_t dpo_pinned_clusters(const dpo_cache *c, int32_t b, int32_t h, int32_t *ids);
 
 /* Eq. 6: A_hat = softmax(logit) over the n clusters (empty clusters get 0). */
 void dpo_cluster_distribution(const double *logit, int32_t n, double *a_hat);
@@ -78,7 +93,8 @@ void dpo_dense_attention(const dpo_cache *c, int32_t b, int32_t h, double *out, 
 /* Eq. 4: log_z[i] = ln sum_j exp(x_ij) per cluster (-inf if empty). */
 void dpo_exact_cluster_log_mass(const dpo_cache *c, int32_t b, int32_t h, double *log_z);
 
-/* The whole decode step for every (b, h): stages in the order above.
+/* The whole decode step for every (b, h): stages in the order above, on the
+ * candidate logits; the exact set is order[0..k2) plus the pinned clusters.
  * out [batch*n_q_heads*d], lse/k1/k2 [batch*n_q_heads]; order (nullable)
  * [batch*n_q_heads, order_stride] receives each head's sorted order.
  * n_threads <= 1 runs serially, else OpenMP over (b, h). Returns the number of

@@ -489,3 +489,101 @@ def test_budget_step_limits_and_threads():
     a = o.budget_step(6, 2, n_threads=1)
     t = o.budget_step(6, 2, n_threads=4)
     assert (a.out == t.out).all() and (a.k1 == t.k1).all() and (a.k2 == t.k2).all()
+
+
+# --------------------------------------------------------------------------
+# pinned clusters (sink / window tokens of Sec. 5.1): out of the distribution, always exact
+# --------------------------------------------------------------------------
+def without_clusters(c, drop):
+    """The same cache with the clusters `drop` (per-segment lists of local ids) removed from the cluster arrays
+    (their K/V rows stay where they are, unreferenced)."""
+    keep_all, ptr = [], [0]
+    for seg in range(c.n_seg):
+        a, e = int(c.seg_cluster_ptr[seg]), int(c.seg_cluster_ptr[seg + 1])
+        keep = [a + i for i in range(e - a) if i not in set(drop[seg])]
+        keep_all += keep
+        ptr.append(len(keep_all))
+    k = np.asarray(keep_all, dtype=np.int64)
+    return ClusteredCache(batch=c.batch, n_kv_heads=c.n_kv_heads, n_q_heads=c.n_q_heads, head_dim=c.head_dim, q=c.q,
+                          k_cache=c.k_cache, v_cache=c.v_cache, seg_row_base=c.seg_row_base,
+                          seg_cluster_ptr=np.asarray(ptr, np.int32), cluster_offsets=c.cluster_offsets[k],
+                          cluster_sizes=c.cluster_sizes[k], k_centroids=c.k_centroids[k], v_centroids=c.v_centroids[k])
+
+
+def lse_merge(parts):
+    """[(out, lse)] of attention over disjoint token sets -> (out, lse) over their union (Eq. 1 identity)."""
+    lses = np.array([l for _, l in parts])
+    tot = logsumexp(lses)
+    w = np.exp(lses - tot)
+    return sum(wi * o for wi, (o, _) in zip(w, parts)), float(tot)
+
+
+def test_pinned_step_equals_middle_step_merged_with_dense_over_the_pinned_tokens():
+    """Independent route: delete the pinned clusters from the cache, run the (already pinned) step on the rest,
+    run scipy dense attention over the pinned tokens, and merge the two by their normalisers."""
+    from workloads import pin_sink_and_window
+    c = make_cache(batch=2, n_kv_heads=2, n_q_heads=8, context=[1500, 700], mean_cluster=8, size_hi=32, q_scale=0.5,
+                   seed=31)
+    pin_sink_and_window(c, first=1, last=3)
+    c.cluster_sizes[int(c.seg_cluster_ptr[1]) - 1] = 0      # an EMPTY pinned cluster is ignored
+    drop = []
+    for seg in range(c.n_seg):
+        a, e = int(c.seg_cluster_ptr[seg]), int(c.seg_cluster_ptr[seg + 1])
+        drop.append([i for i in range(e - a) if c.cluster_flags[a + i] & 1])
+    middle = oracle.Oracle(without_clusters(c, drop))
+    o = oracle.Oracle(c)
+    for p1, p2, fl in ((0.9, 0.6, 0), (0.95, 0.0, 0), (1.0, 1.0, 0), (0.8, 0.7, oracle.P2_ABSOLUTE)):
+        r = o.decode_step(p1, p2, fl)
+        m = middle.decode_step(p1, p2, fl)
+        for b in range(c.batch):
+            for h in range(c.n_q_heads):
+                seg = b * c.n_kv_heads + h // c.group
+                live = [i for i in drop[seg] if c.cluster_sizes[int(c.seg_cluster_ptr[seg]) + i] > 0]
+                assert o.pinned_clusters(b, h).tolist() == live
+                pin_out, pin_lse = scipy_dense(c, b, h, rows=rows_of(c, seg, live))
+                want, want_lse = lse_merge([(m.out[b, h], m.lse[b, h]), (pin_out, pin_lse)])
+                np.testing.assert_allclose(r.out[b, h], want, rtol=1e-9, atol=1e-12)
+                assert r.lse[b, h] == pytest.approx(want_lse, rel=1e-12)
+                assert (r.k1[b, h], r.k2[b, h]) == (m.k1[b, h], m.k2[b, h])
+    # the same identity for the fixed budget
+    r, m = o.budget_step(9, 3), middle.budget_step(9, 3)
+    for b in range(c.batch):
+        for h in range(c.n_q_heads):
+            seg = b * c.n_kv_heads + h // c.group
+            live = [i for i in drop[seg] if c.cluster_sizes[int(c.seg_cluster_ptr[seg]) + i] > 0]
+            pin_out, pin_lse = scipy_dense(c, b, h, rows=rows_of(c, seg, live))
+            want, want_lse = lse_merge([(m.out[b, h], m.lse[b, h]), (pin_out, pin_lse)])
+            np.testing.assert_allclose(r.out[b, h], want, rtol=1e-9, atol=1e-12)
+
+
+def test_pinned_special_cases():
+    from workloads import pin_sink_and_window
+    c = make_cache(batch=1, n_kv_heads=1, n_q_heads=4, context=600, mean_cluster=8, size_hi=32, q_scale=0.6, seed=32)
+    n = int(c.seg_cluster_ptr[1])
+    base = oracle.Oracle(c).decode_step(0.9, 0.5)
+    # no flag set: the flags array changes nothing
+    c.cluster_flags = np.zeros(n, np.uint8)
+    r = oracle.Oracle(c).decode_step(0.9, 0.5)
+    assert (r.out == base.out).all() and (r.k1 == base.k1).all() and (r.k2 == base.k2).all()
+    # every cluster pinned: dense attention whatever p is; nothing is left for the distribution
+    c.cluster_flags = np.ones(n, np.uint8)
+    o = oracle.Oracle(c)
+    r = o.decode_step(0.5, 0.0)
+    for h in range(4):
+        ref, ref_lse = scipy_dense(c, 0, h)
+        np.testing.assert_allclose(r.out[0, h], ref, rtol=1e-9, atol=1e-12)
+        assert r.k1[0, h] == 0 and r.k2[0, h] == 0 and np.isneginf(o.candidate_logits(0, h)).all()
+    # candidate logits: -inf exactly at the pinned clusters, Eq. 3 + 5 elsewhere
+    pin_sink_and_window(c, first=2, last=1)
+    o = oracle.Oracle(c)
+    full, cand = o.centroid_logits(0, 1), o.candidate_logits(0, 1)
+    pinned = np.flatnonzero(c.cluster_flags & 1)
+    assert pinned.tolist() == [0, 1, n - 1] and np.isneginf(cand[pinned]).all()
+    rest = np.setdiff1d(np.arange(n), pinned)
+    assert (cand[rest] == full[rest]).all()
+    # selection helper: pinned ids are exact and never counted in k1 / k2
+    s = o.select(full, 0.9, 0.5, pinned=o.pinned_clusters(0, 1))
+    assert set(pinned.tolist()) <= set(s.exact.tolist()) and not set(pinned.tolist()) & set(s.order.tolist())
+    assert len(s.exact) == s.k2 + len(pinned) and len(s.retained) == s.k1 + len(pinned)
+    a = softmax(cand)
+    assert a[s.order[: s.k1]].sum() >= 0.9 - 1e-15 and a[s.order[: s.k1 - 1]].sum() < 0.9

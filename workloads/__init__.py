@@ -12,4 +12,6 @@ from .synth import (  # noqa: F401
     make_cache,
     f32_to_bf16_bits,
     bf16_bits_to_f32,
+    pin_sink_and_window,
+    CLUSTER_PINNED,
 )

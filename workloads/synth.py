@@ -31,6 +31,9 @@ import numpy as np
 HEAD_DIM = 128
 
 
+CLUSTER_PINNED = 1
+
+
 # --------------------------------------------------------------------------
 # bf16 storage format helpers (format conversion only)
 # --------------------------------------------------------------------------
@@ -70,6 +73,7 @@ class ClusteredCache:
     p2: float = 0.9
     name: str = ""
     meta: Dict[str, object] = field(default_factory=dict)
+    cluster_flags: Optional[np.ndarray] = None  # uint8 [total_clusters]; bit 0: pinned (sink / window tokens)
 
     @property
     def n_seg(self) -> int:
@@ -310,3 +314,17 @@ def make_config(idx: int, *, seed: Optional[int] = None, shrink: int = 1) -> Clu
                           q_scale=lambda rng, b, h: 0.5 if h % 2 == 0 else 5.0,
                           p1=0.95, p2=0.9, seed=seed, tag=4, name=CONFIGS[4])
     raise ValueError(f"no config {idx}")
+
+
+def pin_sink_and_window(cache: ClusteredCache, first: int = 1, last: int = 4) -> ClusteredCache:
+    """Flag the first ``first`` and the last ``last`` clusters of every segment as pinned, in place:
+    the stand-in for a cache that keeps its attention-sink tokens and its most recent tokens in
+    clusters of their own (4 + 64 tokens in the paper's runs; here whatever sizes those clusters
+    drew, about 16 tokens each).  Returns the cache."""
+    flags = np.zeros(int(cache.seg_cluster_ptr[-1]), dtype=np.uint8)
+    for seg in range(cache.n_seg):
+        a, e = int(cache.seg_cluster_ptr[seg]), int(cache.seg_cluster_ptr[seg + 1])
+        flags[a:min(e, a + first)] |= CLUSTER_PINNED
+        flags[max(a, e - last):e] |= CLUSTER_PINNED
+    cache.cluster_flags = flags
+    return cache
