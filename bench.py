@@ -238,6 +238,19 @@ def main():
     dp.dp_decode_attention(pr0, p1, p2, out, lse, ws, None, None, None)
     torch.cuda.synchronize()
 
+    # ---- the step with the sink and window clusters pinned (what the paper's runs do at every layer, Sec. 5.1):
+    # first cluster and last four clusters of every KV head always exact and outside the distribution ----
+    from workloads import pin_sink_and_window
+    pinned_flags = torch.from_numpy(pin_sink_and_window(cache, first=1, last=4).cluster_flags).to(dev)
+    cache.cluster_flags = None
+    pinned_probs = []
+    for r in reps:
+        pc = dp.DeviceCache(**{**r.__dict__, "cluster_flags": pinned_flags})
+        pinned_probs.append(dp.Problem(pc))
+    pinned_us = wall_time(lambda i: dp.dp_decode_attention(pinned_probs[i % L], p1, p2, out, lse, ws), n_base)
+    dp.dp_decode_attention(pr0, p1, p2, out, lse, ws, None, None, None)
+    torch.cuda.synchronize()
+
     # the kernel that moves the bytes: centroid scoring reads every key centroid and size once and
     # writes G logits per cluster
     total_k = int(cache.seg_cluster_ptr[-1])
@@ -308,6 +321,7 @@ def main():
             "fixed_budget": {"k_retained": k_ret, "k_exact": k_ex, "entry_point": "dp_budget_decode_attention"},
             "speedup_over_fixed_budget": round(budget_us / value, 2),
         },
+        "with_sink_and_window_pinned_us": round(pinned_us, 3),
         "gen_seconds": round(t_gen, 1),
     }
 

@@ -69,7 +69,19 @@ typedef struct {
   int32_t max_rows_per_seg;       /* host-known upper bound on the rows (tokens) of one segment         */
   float sm_scale;                 /* logit scale; 0 => 1/sqrt(head_dim)                                 */
   uint32_t flags;                 /* DP_FLAG_*                                                          */
+  const uint8_t *cluster_flags;   /* [total_clusters] DP_CLUSTER_* bits per cluster, or NULL (none set) */
 } dp_problem;
+
+/* A pinned cluster holds tokens that are always attended exactly: the sink and
+ * sliding-window tokens that the paper's runs keep dense at every layer while
+ * the sparse selection sees only the remaining tokens (Sec. 5.1).  Stage 2
+ * (dp_topp_select, dp_topk_select and the one-call entry points) ignores the
+ * logit of a pinned cluster: it takes no part in the softmax over clusters,
+ * the thresholds or a budget, and it is always a member of the exact list
+ * (counted in n_exact, n_retained, n_exact_tokens) unless it is empty.
+ * dp_score_centroids still writes its Eq. 3 / Eq. 5 logit; dp_sparse_decode
+ * and dp_dense_decode do not read the flags. */
+#define DP_CLUSTER_PINNED 1u
 
 /* Host-only.  Bytes of device workspace that dp_sparse_decode and
  * dp_decode_attention need for this problem (depends on the shape fields and

@@ -3,6 +3,7 @@ over a clustered KV cache): hand-written gfx950 kernels behind a C ABI
 (include/dp.h) and a thin ctypes binding with the same entry-point names."""
 from .binding import (  # noqa: F401
     DP_BF16,
+    DP_CLUSTER_PINNED,
     DP_F32,
     DP_FLAG_P2_ABSOLUTE,
     DPError,

@@ -17,6 +17,7 @@ import torch
 
 DP_BF16, DP_F32 = 0, 1
 DP_FLAG_P2_ABSOLUTE = 1
+DP_CLUSTER_PINNED = 1
 
 _PKG = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_PKG, "libdp_hip.so")
@@ -40,7 +41,8 @@ class _Problem(C.Structure):
                 ("cluster_offsets", C.c_void_p), ("cluster_sizes", C.c_void_p),
                 ("k_centroids", C.c_void_p), ("v_centroids", C.c_void_p),
                 ("total_clusters", C.c_int32), ("max_clusters_per_seg", C.c_int32),
-                ("max_rows_per_seg", C.c_int32), ("sm_scale", C.c_float), ("flags", C.c_uint32)]
+                ("max_rows_per_seg", C.c_int32), ("sm_scale", C.c_float), ("flags", C.c_uint32),
+                ("cluster_flags", C.c_void_p)]
 
 
 class _Layout(C.Structure):
@@ -136,6 +138,7 @@ class DeviceCache:
     total_clusters: int
     max_clusters_per_seg: int
     max_rows_per_seg: int
+    cluster_flags: Optional[torch.Tensor] = None  # uint8 [total_clusters], DP_CLUSTER_* bits
 
     @staticmethod
     def from_host(cache, device="cuda:0") -> "DeviceCache":
@@ -149,7 +152,9 @@ class DeviceCache:
             cluster_offsets=up(cache.cluster_offsets, np.int32), cluster_sizes=up(cache.cluster_sizes, np.int32),
             k_centroids=up(cache.k_centroids, np.int16), v_centroids=up(cache.v_centroids, np.int16),
             total_clusters=int(cache.seg_cluster_ptr[-1]), max_clusters_per_seg=cache.max_clusters_per_seg,
-            max_rows_per_seg=cache.max_rows_per_seg)
+            max_rows_per_seg=cache.max_rows_per_seg,
+            cluster_flags=(up(cache.cluster_flags, np.uint8)
+                           if getattr(cache, "cluster_flags", None) is not None else None))
 
     def clone(self) -> "DeviceCache":
         """A copy at distinct device addresses (used to rotate layers in the bench)."""
@@ -167,7 +172,7 @@ class Problem:
                           _ptr(dc.v_cache), _ptr(dc.seg_row_base), _ptr(dc.seg_cluster_ptr),
                           _ptr(dc.cluster_offsets), _ptr(dc.cluster_sizes), _ptr(dc.k_centroids),
                           _ptr(dc.v_centroids), dc.total_clusters, dc.max_clusters_per_seg, dc.max_rows_per_seg,
-                          float(sm_scale), int(flags))
+                          float(sm_scale), int(flags), _ptr(dc.cluster_flags))
 
     @property
     def ref(self):

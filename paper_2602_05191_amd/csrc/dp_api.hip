@@ -45,6 +45,7 @@ dp::CacheView view_of(const dp_problem *p) {
   c.seg_cluster_ptr = p->seg_cluster_ptr;
   c.cluster_offsets = p->cluster_offsets;
   c.cluster_sizes = p->cluster_sizes;
+  c.cluster_flags = p->cluster_flags;
   c.max_clusters_per_seg = p->max_clusters_per_seg;
   c.max_rows_per_seg = p->max_rows_per_seg;
   // every segment holds <= max clusters and they sum to total: equality means all are full

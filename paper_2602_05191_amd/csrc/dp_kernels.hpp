@@ -23,6 +23,7 @@ struct CacheView {
   const void *q, *k_cache, *v_cache, *k_centroids, *v_centroids;
   const int64_t *seg_row_base;
   const int32_t *seg_cluster_ptr, *cluster_offsets, *cluster_sizes;
+  const uint8_t *cluster_flags;  // nullable
   int32_t max_clusters_per_seg, max_rows_per_seg;
   int32_t uniform_kc;  // > 0 when the host can tell that every segment has exactly this many clusters
   float sm_scale;

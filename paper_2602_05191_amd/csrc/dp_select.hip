@@ -61,6 +61,7 @@ __device__ unsigned long long *g_dbg_ptr = nullptr;
 struct SelectArgs {
   const float *logits;
   const int32_t *seg_cluster_ptr, *cluster_sizes, *cluster_offsets;
+  const uint8_t *cluster_flags;  // nullable; bit 0: pinned cluster (out of the distribution, always exact)
   int32_t n_kv_heads, n_q_heads, group, max_k;
   int32_t uniform_kc;  // > 0: every segment has exactly this many clusters (no CSR lookup needed)
   float p1, p2;
@@ -536,6 +537,36 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(SelectArgs a) {
       }
     }
   }
+  // Pinned clusters (the caller's sink / window tokens): their logits leave the distribution here and
+  // they join the exact list further down.  bit e of pinmask: element e is a pinned, non-empty cluster.
+  u64 pinmask = 0;
+  const bool has_flags = a.cluster_flags != nullptr;
+  if (has_flags) {
+    const uint8_t *fp = a.cluster_flags + c0 + base;
+    constexpr int kVec = E < 8 ? E : 8;  // flag bytes per load when the thread's run of flags is aligned
+    if ((reinterpret_cast<uintptr_t>(fp) & (kVec - 1)) == 0 && base + E <= kc) {
+#pragma unroll
+      for (int e = 0; e < E; e += kVec) {
+        u64 w;
+        if (kVec == 8) w = *reinterpret_cast<const u64 *>(fp + e);
+        else if (kVec == 4) w = *reinterpret_cast<const uint32_t *>(fp + e);
+        else w = *reinterpret_cast<const uint16_t *>(fp + e);
+#pragma unroll
+        for (int u = 0; u < kVec; ++u) pinmask |= ((w >> (8 * u)) & 1ull) << (e + u);
+      }
+    } else {
+#pragma unroll
+      for (int e = 0; e < E; ++e)
+        if (base + e < kc && (fp[e] & 1u)) pinmask |= 1ull << e;
+    }
+#pragma unroll
+    for (int e = 0; e < E; ++e)
+      if ((pinmask >> e) & 1) {
+        const int sz = kPre ? psz[kPre ? e : 0] : a.cluster_sizes[c0 + base + e];
+        if (sz <= 0) pinmask &= ~(1ull << e);
+        l[e] = -INFINITY;
+      }
+  }
   for (int i = tid; i < kBins; i += kSelThreads) sh.hist[i] = 0;
   if (tid < 2) sh.ncand[tid] = 0;
   if (tid == 2) sh.ntop = 0;
@@ -545,10 +576,13 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(SelectArgs a) {
     l[e] += 0.0f;  // -0 becomes +0
     tmax = fmaxf(tmax, l[e]);
   }
-  const float mx = block_max<kSelWaves>(tmax, sh.scrf);  // its barriers also publish the zeroed LDS
+  const float mx_raw = block_max<kSelWaves>(tmax, sh.scrf);  // its barriers also publish the zeroed LDS
 
   DP_MARK(1);
-  if (mx == -INFINITY || (kCount && a.k_retained <= 0)) {  // no non-empty cluster, or a budget of 0: nothing selected, zero output
+  // no candidate cluster, or a budget of 0: the distribution selects nothing
+  const bool nothing = mx_raw == -INFINITY || (kCount && a.k_retained <= 0);
+  const float mx = mx_raw == -INFINITY ? 0.f : mx_raw;
+  if (nothing && !has_flags) {  // and nothing can be pinned: zero output
     if (tid == 0) {
       a.out.n_exact[head] = 0;
       a.out.n_retained[head] = 0;
@@ -590,6 +624,7 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(SelectArgs a) {
       }
     }
   }
+  ctop += __popcll(pinmask);  // pinned clusters ride along in the top set
   int ntop;
   u64 W, Wtop;  // total weight (top-p: >= 2^40, the max element has weight 1; fixed budget: the non-empty clusters), weight of the top set
   {
@@ -615,16 +650,16 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(SelectArgs a) {
   DP_MARK(2);
 
   int n_ex, n_ap, n_tok;
-  const bool all = retain_all<kCount>(a, W);  // every non-empty cluster is retained
+  const bool all = !nothing && retain_all<kCount>(a, W);  // every non-empty candidate is retained
   // fast path: the top set is small and already holds the first threshold's weight (integer sums: exact), so
   // the retained set lies inside it (the usual case for a peaked head)
-  const bool fast = !all && ntop <= kTopMax && Wtop >= first_tau<kCount>(a, W);
+  const bool fast = !nothing && !all && ntop <= kTopMax && Wtop >= first_tau<kCount>(a, W);
   if (fast) {
     // ---- gather the top set with its sizes / offsets, then one wave ranks it pairwise ----
 #pragma unroll
     for (int e = 0; e < E; ++e) {
       const float d = mx - l[e];
-      if (d < kTopCut) {
+      if (d < kTopCut || ((pinmask >> e) & 1)) {
         const int s = atomicAdd(&sh.ntop, 1);
         const int i = base + e;
         sh.top_key[s] = ordered_key(l[e]);
@@ -642,15 +677,21 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(SelectArgs a) {
       const int idx_i = act ? sh.top_idx[i] : INT_MAX;
       const u64 m_i = act ? sh.top_m[i] : 0;
       const int sz_i = act ? sh.top_sz[i] : 0;
+      const bool pin_i = act && m_i == 0;  // a candidate of the top set has weight > 0, a pinned cluster 0
+      // lane j holds entry j: the loops below fetch it with readlane (j is uniform), not from LDS
+      const uint32_t mlo_i = (uint32_t)m_i, mhi_i = (uint32_t)(m_i >> 32);
       u64 ahead = 0;  // mass of the clusters that precede cluster i in the order
       for (int j = 0; j < ntop; ++j) {
-        const uint32_t kj = sh.top_key[j];
-        if (kj > key_i || (kj == key_i && sh.top_idx[j] < idx_i)) ahead += sh.top_m[j];
+        const uint32_t kj = __builtin_amdgcn_readlane(key_i, j);
+        const int ij = __builtin_amdgcn_readlane(idx_i, j);
+        const u64 mj = ((u64)(uint32_t)__builtin_amdgcn_readlane(mhi_i, j) << 32) |
+                       (uint32_t)__builtin_amdgcn_readlane(mlo_i, j);
+        if (kj > key_i || (kj == key_i && ij < idx_i)) ahead += mj;
       }
       const u64 tau1 = first_tau<kCount>(a, W);
       {
-        const bool ret = act && ahead < tau1;
-        u64 m1 = ret ? ahead + m_i : 0;  // mass of the retained prefix = the largest inclusive prefix
+        const bool ret = pin_i || (act && ahead < tau1);
+        u64 m1 = (ret && !pin_i) ? ahead + m_i : 0;  // mass of the retained prefix = the largest inclusive prefix
 #pragma unroll
         for (int d = 32; d >= 1; d >>= 1) {
           const u64 o = __shfl_xor(m1, d, 64);
@@ -658,7 +699,7 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(SelectArgs a) {
         }
         u64 tau2 = 0;
         const int kind = second_tau<kCount>(a, W, m1, tau2);
-        const bool exa = kind == 1 ? ret : (kind == 2 && act && ahead < tau2);
+        const bool exa = pin_i || (kind == 1 ? ret : (kind == 2 && act && ahead < tau2));
         const bool apx = ret && !exa;
         const u64 exa_mask = __ballot(exa), apx_mask = __ballot(apx);
         n_ex = __popcll(exa_mask);
@@ -667,10 +708,10 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(SelectArgs a) {
         // position of cluster i in its list = selected clusters with a smaller index
         int pe = 0, pa = 0, pt = 0;
         for (int j = 0; j < ntop; ++j) {
-          const bool before = sh.top_idx[j] < idx_i;
+          const bool before = __builtin_amdgcn_readlane(idx_i, j) < idx_i;
           if ((exa_mask >> j) & 1) {
             pe += before;
-            pt += before ? sh.top_sz[j] : 0;
+            pt += before ? __builtin_amdgcn_readlane(sz_i, j) : 0;
           } else if ((apx_mask >> j) & 1) {
             pa += before;
           }
@@ -696,49 +737,53 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(SelectArgs a) {
   DP_MARK(3);
 
   if (!fast) {
-    // ---- general path: level-1 mass histogram, scan, threshold search ---------
+    // the prefix ends: the last retained and the last exact cluster of the order as (key, index); the
+    // initial values select nothing
+    uint32_t key1 = 0xffffffffu, key2 = 0xffffffffu;
+    int idx1 = -1, idx2 = -1;
+    if (!nothing) {
+      // ---- general path: level-1 mass histogram, scan, threshold search ---------
 #pragma unroll
-    for (int e = 0; e < E; ++e) {
-      const float d = mx - l[e];
-      const u64 m = mass_of<kCount>(d);
-      if (m) atomicAdd(&sh.hist[level1_bin(d, bs)], m);
-    }
-    __syncthreads();
-    DP_MARK(8);
-    const u64 h0 = sh.hist[2 * tid], h1 = sh.hist[2 * tid + 1];
-    u64 Wh;  // equals W: the same masses, summed in another order
-    const u64 ex = block_excl_scan<u64, kSelWaves>(h0 + h1, sh.scr64, Wh);
-    DP_MARK(9);
+      for (int e = 0; e < E; ++e) {
+        const float d = mx - l[e];
+        const u64 m = mass_of<kCount>(d);
+        if (m) atomicAdd(&sh.hist[level1_bin(d, bs)], m);
+      }
+      __syncthreads();
+      DP_MARK(8);
+      const u64 h0 = sh.hist[2 * tid], h1 = sh.hist[2 * tid + 1];
+      u64 Wh;  // equals W: the same masses, summed in another order
+      const u64 ex = block_excl_scan<u64, kSelWaves>(h0 + h1, sh.scr64, Wh);
+      DP_MARK(9);
 
-    uint32_t key1, key2;
-    int idx1, idx2;
-    u64 mass1;
-    int cached_bin = -1, cached_cnt = 0;
-    u64 cached_before = 0;
-    if (all) {  // every non-empty cluster
-      key1 = kKeyLowestFinite;
-      idx1 = INT_MAX;
-      mass1 = W;
-    } else {
-      find_prefix<E, kCount>(l, lg, kc, mx, bs, base, first_tau<kCount>(a, W), ex, h0, h1, 0, sh, cached_bin, cached_cnt,
-                             cached_before, key1, idx1, mass1);
-    }
-    DP_MARK(10);
-    u64 tau2 = 0;
-    const int kind = second_tau<kCount>(a, W, mass1, tau2);
-    if (kind == 1) {
-      key2 = key1;
-      idx2 = idx1;
-    } else if (kind == 0) {  // nothing is exact
-      key2 = 0xffffffffu;
-      idx2 = -1;
-    } else {
-      u64 mass2;
-      __syncthreads();  // sh.bin / sh.res_* of the first search have been read by every thread
-      find_prefix<E, kCount>(l, lg, kc, mx, bs, base, tau2, ex, h0, h1, 1, sh, cached_bin, cached_cnt, cached_before, key2, idx2,
-                             mass2);
-    }
+      u64 mass1;
+      int cached_bin = -1, cached_cnt = 0;
+      u64 cached_before = 0;
+      if (all) {  // every non-empty cluster
+        key1 = kKeyLowestFinite;
+        idx1 = INT_MAX;
+        mass1 = W;
+      } else {
+        find_prefix<E, kCount>(l, lg, kc, mx, bs, base, first_tau<kCount>(a, W), ex, h0, h1, 0, sh, cached_bin, cached_cnt,
+                               cached_before, key1, idx1, mass1);
+      }
+      DP_MARK(10);
+      u64 tau2 = 0;
+      const int kind = second_tau<kCount>(a, W, mass1, tau2);
+      if (kind == 1) {
+        key2 = key1;
+        idx2 = idx1;
+      } else if (kind == 0) {  // nothing is exact
+        key2 = 0xffffffffu;
+        idx2 = -1;
+      } else {
+        u64 mass2;
+        __syncthreads();  // sh.bin / sh.res_* of the first search have been read by every thread
+        find_prefix<E, kCount>(l, lg, kc, mx, bs, base, tau2, ex, h0, h1, 1, sh, cached_bin, cached_cnt, cached_before, key2, idx2,
+                               mass2);
+      }
 
+    }
     DP_MARK(11);
     // ---- compaction in ascending cluster index ------------------------------
     // Only clusters in play (non-zero weight) can be selected, unless all non-empty ones are.
@@ -749,7 +794,7 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(SelectArgs a) {
       const uint32_t k = ordered_key(l[e]);
       const int i = base + e;
       const bool live = all ? l[e] != -INFINITY : in_play<kCount>(mx - l[e]);
-      const bool exa = live && (k > key2 || (k == key2 && i <= idx2));
+      const bool exa = ((pinmask >> e) & 1) || (live && (k > key2 || (k == key2 && i <= idx2)));
       const bool apx = live && !exa && (k > key1 || (k == key1 && i <= idx1));
       exa_mask |= (u64)exa << e;
       ret_mask |= (u64)apx << e;
@@ -835,6 +880,11 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(SelectArgs a) {
     }
   }
   if (!inline_attn) return;
+  if (R == 0) {  // nothing to attend to: zero output
+    if (tid < kHeadDim) store_out(a.attn_out, a.out_is_bf16, head, tid, 0.f);
+    if (tid == 0 && a.lse) a.lse[head] = -INFINITY;
+    return;
+  }
 
   // ---- inline attention for a head with few rows ---------------------------
   __syncthreads();
@@ -953,6 +1003,7 @@ hipError_t launch_select(const CacheView &c, const float *logits, const SelectRu
   a.seg_cluster_ptr = c.seg_cluster_ptr;
   a.cluster_sizes = c.cluster_sizes;
   a.cluster_offsets = c.cluster_offsets;
+  a.cluster_flags = c.cluster_flags;
   a.n_kv_heads = c.n_kv_heads;
   a.n_q_heads = c.n_q_heads;
   a.group = c.group;

@@ -198,14 +198,22 @@ def check_sets(cache: ClusteredCache, orc: "oracle.Oracle", g: GpuStep, p1: floa
     for b in range(cache.batch):
         for h in range(cache.n_q_heads):
             i = b * cache.n_q_heads + h
-            logit = orc.centroid_logits(b, h)
-            s = orc.select(logit, p1, p2, flags)
-            got_ret = np.sort(np.concatenate([g.exact[i], g.approx[i]])).astype(np.int64)
-            got_ex = np.asarray(g.exact[i], dtype=np.int64)
+            pins = orc.pinned_clusters(b, h)
+            logit = orc.candidate_logits(b, h)
+            full = orc.select(logit, p1, p2, flags, pinned=pins)
             assert (np.diff(g.exact[i]) > 0).all() and (np.diff(g.approx[i]) > 0).all(), f"head {i}: ids not ascending"
             assert len(np.intersect1d(g.exact[i], g.approx[i])) == 0
+            # pinned clusters: all of them exact; the rest is judged as a selection among the candidates
+            assert np.isin(pins, g.exact[i]).all() and not np.isin(pins, g.approx[i]).any(), f"head {i}: pinned"
+            s = orc.select(logit, p1, p2, flags)   # pinned logits are -inf here: the candidates alone
+            assert np.array_equal(full.exact, np.sort(np.concatenate([pins, s.exact])))
+            got_ex = np.setdiff1d(g.exact[i], pins).astype(np.int64)
+            got_ret = np.sort(np.concatenate([got_ex, g.approx[i]])).astype(np.int64)
             if s.order.size == 0:
                 assert got_ret.size == 0
+                seg = b * cache.n_kv_heads + h // cache.group
+                c0 = int(cache.seg_cluster_ptr[seg])
+                assert int(g.n_exact_tokens[i]) == int(cache.cluster_sizes[c0 + pins].sum())
                 continue
             tau1 = p1 if p1 < 1.0 else s.a_hat.sum()
             if p1 >= 1.0:
@@ -230,7 +238,7 @@ def check_sets(cache: ClusteredCache, orc: "oracle.Oracle", g: GpuStep, p1: floa
             tolerated += int(not (same1 and same2))
             seg = b * cache.n_kv_heads + h // cache.group
             c0 = int(cache.seg_cluster_ptr[seg])
-            assert int(g.n_exact_tokens[i]) == int(cache.cluster_sizes[c0 + got_ex].sum())
+            assert int(g.n_exact_tokens[i]) == int(cache.cluster_sizes[c0 + np.asarray(g.exact[i], np.int64)].sum())
     return tolerated
 
 

@@ -86,3 +86,18 @@ def test_full_size_dense_baseline(idx):
     worst = float(np.abs(out - ref).max())
     assert worst <= 2e-4 and np.abs(lse - ref_lse).max() <= 1e-3, worst
     print(f"[cfg{idx} dense] max-abs {worst:.2e}")
+
+
+def test_full_size_cfg2_with_sink_and_window_pinned():
+    """cfg 2 with the first cluster and the last four clusters of every KV head pinned (the stand-in for
+    the 4 sink + 64 recent tokens that the paper's runs keep dense)."""
+    from workloads import pin_sink_and_window
+    cache = pin_sink_and_window(make_config(2), first=1, last=4)
+    orc = oracle.Oracle(cache)
+    g = H.gpu_decode_attention(cache, cache.p1, cache.p2)
+    assert H.check_sets(cache, orc, g, cache.p1, cache.p2) <= 1
+    worst, rel = H.check_outputs(cache, orc, g, tight=2e-4)
+    r = orc.decode_step(cache.p1, cache.p2, n_threads=8)
+    np.testing.assert_allclose(g.out, r.out, atol=H.OUT_MAX_ABS)
+    assert min(len(e) for e in g.exact) >= 5
+    print(f"[cfg2 pinned] max-abs {worst:.2e} rel-L2 {rel:.2e}")

@@ -79,9 +79,34 @@ def case_empty_clusters_and_segment():
     return c, 0.95, 0.9
 
 
+def case_pinned_peaked():
+    # sink + window clusters pinned on sharply peaked heads: the one-wave fast path carries the pinned clusters
+    from workloads import pin_sink_and_window
+    return pin_sink_and_window(make_config(0), first=1, last=4), 0.95, 0.9
+
+
+def case_pinned_flat_ragged():
+    # the same on flat heads (general path), ragged batch, one pinned cluster emptied, one segment pinned entirely
+    from workloads import pin_sink_and_window
+    c = make_cache(batch=2, n_kv_heads=2, n_q_heads=8, context=[3000, 1777], mean_cluster=16, q_scale=0.35, seed=21)
+    pin_sink_and_window(c, first=2, last=5)
+    c.cluster_sizes[int(c.seg_cluster_ptr[1]) - 2] = 0
+    c.cluster_flags[int(c.seg_cluster_ptr[3]): int(c.seg_cluster_ptr[4])] = 1
+    return c, 0.95, 0.9
+
+
+def case_pinned_many_clusters():
+    # 9000 clusters per segment (16 logits per thread) with scattered pinned clusters
+    c = make_cache(batch=1, n_kv_heads=1, n_q_heads=4, context=27000, mean_cluster=3, size_hi=8, q_scale=0.3,
+                   seed=22)
+    c.cluster_flags = (np.random.default_rng(5).random(int(c.seg_cluster_ptr[-1])) < 0.01).astype(np.uint8)
+    return c, 0.95, 0.9
+
+
 CASES = {f.__name__[5:]: f for f in (case_cfg0, case_flat_ragged, case_mixed_sharpness, case_gqa8_pareto, case_gqa1,
                                      case_gqa3_and_12, case_gqa12, case_many_clusters, case_single_cluster,
-                                     case_giant_cluster, case_empty_clusters_and_segment)}
+                                     case_giant_cluster, case_empty_clusters_and_segment, case_pinned_peaked,
+                                     case_pinned_flat_ragged, case_pinned_many_clusters)}
 
 
 @pytest.fixture(scope="module", params=sorted(CASES))
@@ -125,12 +150,15 @@ def test_topp_select_matches_oracle_on_same_logits(case, flags):
         n_tol = 0
         for i in range(cache.batch * cache.n_q_heads):
             lg = per_head[i].astype(np.float64)
-            s = orc.select(lg, q1, q2, flags)
+            pins = orc.pinned_clusters(*divmod(i, cache.n_q_heads))
+            s = orc.select(lg, q1, q2, flags, pinned=pins)
             got_ret = np.sort(np.concatenate([exact[i], approx[i]]))
             same = np.array_equal(got_ret, s.retained) and np.array_equal(exact[i], s.exact)
             if not same:
-                ok1, _ = H.prefix_set_ok(got_ret.astype(np.int64), s.retained.astype(np.int64), s.a_hat, lg,
-                                         q1 if q1 < 1 else 2.0)
+                assert np.isin(pins, exact[i]).all()
+                lg[pins] = -np.inf
+                ok1, _ = H.prefix_set_ok(np.setdiff1d(got_ret, pins).astype(np.int64),
+                                         np.sort(s.order[: s.k1]).astype(np.int64), s.a_hat, lg, q1 if q1 < 1 else 2.0)
                 assert ok1 and q1 < 1.0, (name, i, q1, q2, got_ret[:10], s.retained[:10])
                 n_tol += 1
         assert n_tol <= 1, (name, q1, q2, n_tol)
@@ -143,7 +171,8 @@ def test_sparse_decode_matches_oracle_on_oracle_sets(case):
     name, cache, p1, p2, orc = case
     r = orc.decode_step(p1, p2)
     nh = cache.batch * cache.n_q_heads
-    exact = [np.sort(r.order[i, : r.k2.flat[i]]) for i in range(nh)]
+    exact = [np.sort(np.concatenate([orc.pinned_clusters(*divmod(i, cache.n_q_heads)), r.order[i, : r.k2.flat[i]]]))
+             for i in range(nh)]
     approx = [np.sort(r.order[i, r.k2.flat[i]: r.k1.flat[i]]) for i in range(nh)]
     out, lse = H.gpu_sparse_decode(cache, exact, approx)
     g = H.GpuStep(out=out, lse=lse, exact=exact, approx=approx, n_exact_tokens=np.zeros(nh))
@@ -269,7 +298,7 @@ def test_topk_select_is_the_oracle_top_k_of_the_same_logits(case):
         for b in range(cache.batch):
             for h in range(cache.n_q_heads):
                 i = b * cache.n_q_heads + h
-                s = orc.fixed_budget(per_head[i].astype(np.float64), kr, ke)
+                s = orc.fixed_budget(per_head[i].astype(np.float64), kr, ke, pinned=orc.pinned_clusters(b, h))
                 assert np.array_equal(exact[i], s.exact) and np.array_equal(approx[i], s.approx), (name, kr, ke, i)
                 seg = b * cache.n_kv_heads + h // cache.group
                 c0 = int(cache.seg_cluster_ptr[seg])
@@ -283,20 +312,24 @@ def test_budget_decode_attention_matches_oracle(case, budget):
     nh = cache.batch * cache.n_q_heads
     for i in range(nh):
         # the sets are the top-k of the logits the GPU itself computed (checked against the oracle's in stage 1)
-        s = orc.fixed_budget(g.logits[i].astype(np.float64), *budget)
+        s = orc.fixed_budget(g.logits[i].astype(np.float64), *budget,
+                             pinned=orc.pinned_clusters(*divmod(i, cache.n_q_heads)))
         assert np.array_equal(g.exact[i], s.exact) and np.array_equal(g.approx[i], s.approx), (name, budget, i)
     # against the oracle's own step: same counts; sets equal except where fp32 and fp64 logits order a near-tie differently
     r = orc.budget_step(*budget, n_threads=4)
     differing = 0
     for i in range(nh):
         b, h = divmod(i, cache.n_q_heads)
-        assert len(g.exact[i]) == r.k2[b, h] and len(g.exact[i]) + len(g.approx[i]) == r.k1[b, h]
-        same = (np.array_equal(g.exact[i], np.sort(r.order[i, : r.k2[b, h]])) and
+        pins = orc.pinned_clusters(b, h)
+        assert np.isin(pins, g.exact[i]).all()
+        got_ex = np.setdiff1d(g.exact[i], pins)
+        assert len(got_ex) == r.k2[b, h] and len(got_ex) + len(g.approx[i]) == r.k1[b, h]
+        same = (np.array_equal(got_ex, np.sort(r.order[i, : r.k2[b, h]])) and
                 np.array_equal(g.approx[i], np.sort(r.order[i, r.k2[b, h]: r.k1[b, h]])))
         if not same:
             lg = orc.centroid_logits(b, h)
-            for got, want in ((g.exact[i], r.order[i, : r.k2[b, h]]),
-                              (np.concatenate([g.exact[i], g.approx[i]]), r.order[i, : r.k1[b, h]])):
+            for got, want in ((got_ex, r.order[i, : r.k2[b, h]]),
+                              (np.concatenate([got_ex, g.approx[i]]), r.order[i, : r.k1[b, h]])):
                 swapped = np.setxor1d(got, want)
                 assert swapped.size == 0 or np.ptp(lg[swapped]) <= H.LOGIT_TIE_TOL, (name, budget, i, swapped)
             differing += 1
