@@ -83,6 +83,8 @@ def _load():
         L.dpo_fixed_budget.argtypes = [I, I, I, P, P]
         L.dpo_budget_step.restype = I
         L.dpo_budget_step.argtypes = [CP, I, I, P, P, P, P, P, C.c_int64, I]
+        L.dpo_build_cluster_cache.restype = None
+        L.dpo_build_cluster_cache.argtypes = [I, I] + [P] * 14
         L.dpo_dense_step.restype = I
         L.dpo_dense_step.argtypes = [CP, P, P, I]
         _lib = L
@@ -286,3 +288,27 @@ class StepResult:
     k2: np.ndarray
     order: Optional[np.ndarray]
     threads: int
+
+
+def build_cluster_cache(tokens) -> dict:
+    """Prefill side (Sec. 4.1, Eq. 2) for a workloads.TokenOrderInput: the cluster-contiguous cache and
+    the cluster metadata, as numpy arrays keyed like the ClusteredCache fields (+ v_sums, token_row)."""
+    lib = _load()
+    t = tokens
+    d = int(t.head_dim)
+    n_rows, n_cl = int(t.k_tokens.shape[0]), int(t.seg_cluster_ptr[-1])
+    a = dict(k=np.ascontiguousarray(t.k_tokens, np.uint16), v=np.ascontiguousarray(t.v_tokens, np.uint16),
+             asg=np.ascontiguousarray(t.assignment, np.int32), base=np.ascontiguousarray(t.seg_row_base, np.int64),
+             rows=np.ascontiguousarray(t.seg_rows, np.int32), ptr=np.ascontiguousarray(t.seg_cluster_ptr, np.int32))
+    out = dict(k_cache=np.zeros((n_rows, d), np.uint16), v_cache=np.zeros((n_rows, d), np.uint16),
+               cluster_offsets=np.zeros(max(n_cl, 1), np.int32), cluster_sizes=np.zeros(max(n_cl, 1), np.int32),
+               k_centroids=np.zeros((max(n_cl, 1), d), np.uint16), v_centroids=np.zeros((max(n_cl, 1), d), np.uint16),
+               v_sums=np.zeros((max(n_cl, 1), d), np.float64), token_row=np.zeros(max(n_rows, 1), np.int32))
+    lib.dpo_build_cluster_cache(len(a["rows"]), d, _ptr(a["k"]), _ptr(a["v"]), _ptr(a["asg"]), _ptr(a["base"]),
+                                _ptr(a["rows"]), _ptr(a["ptr"]), _ptr(out["k_cache"]), _ptr(out["v_cache"]),
+                                _ptr(out["cluster_offsets"]), _ptr(out["cluster_sizes"]), _ptr(out["k_centroids"]),
+                                _ptr(out["v_centroids"]), _ptr(out["v_sums"]), _ptr(out["token_row"]))
+    for k in ("cluster_offsets", "cluster_sizes", "k_centroids", "v_centroids", "v_sums"):
+        out[k] = out[k][:n_cl]
+    out["token_row"] = out["token_row"][:n_rows]
+    return out

@@ -382,3 +382,69 @@ int32_t dpo_dense_step(const dpo_cache *c, double *out, double *lse, int32_t n_t
     dpo_dense_attention(c, i / c->n_q_heads, i % c->n_q_heads, out + (int64_t)i * d, lse + i);
   return used;
 }
+
+/* ---- prefill side (Sec. 4.1): cluster-contiguous cache and cluster metadata from token-order K/V ---- */
+
+/* double -> bf16 bits, one rounding to 8 significant bits, ties to even (finite, normal values) */
+static uint16_t double_to_bf16(double x) {
+  if (x == 0.0) return (uint16_t)(signbit(x) ? 0x8000u : 0u);
+  int e;
+  double m = frexp(x, &e);                  /* x = m * 2^e, 0.5 <= |m| < 1 */
+  double r = nearbyint(ldexp(m, 8));        /* default rounding mode: ties to even */
+  float f = (float)ldexp(r, e - 8);         /* exactly representable */
+  uint32_t u;
+  memcpy(&u, &f, sizeof u);
+  return (uint16_t)(u >> 16);
+}
+
+void dpo_build_cluster_cache(int32_t n_seg, int32_t d, const uint16_t *k_tokens, const uint16_t *v_tokens,
+                             const int32_t *assignment, const int64_t *seg_row_base, const int32_t *seg_rows,
+                             const int32_t *seg_cluster_ptr, uint16_t *k_cache, uint16_t *v_cache,
+                             int32_t *cluster_offsets, int32_t *cluster_sizes, uint16_t *k_centroids,
+                             uint16_t *v_centroids, double *v_sums, int32_t *token_row) {
+  for (int32_t seg = 0; seg < n_seg; ++seg) {
+    const int64_t r0 = seg_row_base[seg];
+    const int32_t n = seg_rows[seg], c0 = seg_cluster_ptr[seg], kc = seg_cluster_ptr[seg + 1] - c0;
+    /* s_i = |T_i| */
+    for (int32_t i = 0; i < kc; ++i) cluster_sizes[c0 + i] = 0;
+    for (int32_t t = 0; t < n; ++t) {
+      int32_t a = assignment[r0 + t];
+      if (a >= 0 && a < kc) cluster_sizes[c0 + a] += 1;
+    }
+    /* clusters are laid out one after the other, in index order */
+    int32_t run = 0;
+    for (int32_t i = 0; i < kc; ++i) {
+      cluster_offsets[c0 + i] = run;
+      run += cluster_sizes[c0 + i];
+    }
+    /* tokens of a cluster keep their token order */
+    int32_t *cursor = (int32_t *)malloc(sizeof(int32_t) * (size_t)(kc > 0 ? kc : 1));
+    for (int32_t i = 0; i < kc; ++i) cursor[i] = cluster_offsets[c0 + i];
+    for (int32_t t = 0; t < n; ++t) {
+      int32_t a = assignment[r0 + t];
+      int32_t row = -1;
+      if (a >= 0 && a < kc) {
+        row = cursor[a]++;
+        memcpy(k_cache + (r0 + row) * d, k_tokens + (r0 + t) * d, sizeof(uint16_t) * (size_t)d);
+        memcpy(v_cache + (r0 + row) * d, v_tokens + (r0 + t) * d, sizeof(uint16_t) * (size_t)d);
+      }
+      if (token_row) token_row[r0 + t] = row;
+    }
+    free(cursor);
+    /* C_i = mean key, Eq. 2: V^Sigma_i = sum of values, V-bar_i = V^Sigma_i / s_i */
+    for (int32_t i = 0; i < kc; ++i) {
+      const int32_t s = cluster_sizes[c0 + i];
+      for (int32_t j = 0; j < d; ++j) {
+        double ks = 0.0, vs = 0.0;
+        for (int32_t r = 0; r < s; ++r) {
+          const int64_t row = r0 + cluster_offsets[c0 + i] + r;
+          ks += bf16_to_double(k_cache[row * d + j]);
+          vs += bf16_to_double(v_cache[row * d + j]);
+        }
+        k_centroids[(int64_t)(c0 + i) * d + j] = s > 0 ? double_to_bf16(ks / s) : 0;
+        v_centroids[(int64_t)(c0 + i) * d + j] = s > 0 ? double_to_bf16(vs / s) : 0;
+        if (v_sums) v_sums[(int64_t)(c0 + i) * d + j] = vs;
+      }
+    }
+  }
+}

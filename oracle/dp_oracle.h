@@ -116,6 +116,22 @@ int32_t dpo_budget_step(const dpo_cache *c, int32_t k_retained, int32_t k_exact,
 /* Eq. 1 for every (b, h), same threading. */
 int32_t dpo_dense_step(const dpo_cache *c, double *out, double *lse, int32_t n_threads);
 
+/* Prefill side (Sec. 4.1, Eq. 2): from K / V in token order and each token's
+ * cluster id, the cluster-contiguous cache and the per-cluster metadata that the
+ * decode step reads.  Segment seg owns rows [seg_row_base[seg], + seg_rows[seg])
+ * of the token arrays and of the output cache, and clusters [ptr[seg], ptr[seg+1]).
+ * Clusters are laid out in index order, the tokens of a cluster in token order.
+ *   cluster_sizes s_i, cluster_offsets (exclusive prefix of the sizes),
+ *   k_centroids C_i = mean key, v_centroids = V^Sigma_i / s_i, both rounded once
+ *   to bf16 (ties to even; zero rows for an empty cluster), v_sums (nullable)
+ *   V^Sigma_i in double, token_row (nullable) the segment-relative cache row of each token.
+ * A token whose id is outside [0, clusters of the segment) is left out (token_row -1). */
+void dpo_build_cluster_cache(int32_t n_seg, int32_t d, const uint16_t *k_tokens, const uint16_t *v_tokens,
+                             const int32_t *assignment, const int64_t *seg_row_base, const int32_t *seg_rows,
+                             const int32_t *seg_cluster_ptr, uint16_t *k_cache, uint16_t *v_cache,
+                             int32_t *cluster_offsets, int32_t *cluster_sizes, uint16_t *k_centroids,
+                             uint16_t *v_centroids, double *v_sums, int32_t *token_row);
+
 #ifdef __cplusplus
 }
 #endif

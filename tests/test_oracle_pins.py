@@ -587,3 +587,83 @@ def test_pinned_special_cases():
     assert len(s.exact) == s.k2 + len(pinned) and len(s.retained) == s.k1 + len(pinned)
     a = softmax(cand)
     assert a[s.order[: s.k1]].sum() >= 0.9 - 1e-15 and a[s.order[: s.k1 - 1]].sum() < 0.9
+
+
+# --------------------------------------------------------------------------
+# prefill side: cluster-contiguous cache and metadata (Sec. 4.1, Eq. 2)
+# --------------------------------------------------------------------------
+def test_build_cluster_cache_layout_against_numpy_stable_sort():
+    from workloads import token_order_input
+    c = make_cache(batch=2, n_kv_heads=2, n_q_heads=4, context=[900, 333], mean_cluster=8, size_hi=32, q_scale=1.0,
+                   seed=41)
+    t = token_order_input(c, seed=3)
+    t.assignment[5] = -1                       # two tokens without a valid cluster are left out
+    t.assignment[int(t.seg_row_base[2]) + 7] = 10 ** 6
+    m = oracle.build_cluster_cache(t)
+    for seg in range(t.n_seg):
+        r0, n = int(t.seg_row_base[seg]), int(t.seg_rows[seg])
+        a, e = int(t.seg_cluster_ptr[seg]), int(t.seg_cluster_ptr[seg + 1])
+        asg = t.assignment[r0:r0 + n]
+        valid = (asg >= 0) & (asg < e - a)
+        sizes = np.bincount(asg[valid], minlength=e - a)
+        assert np.array_equal(m["cluster_sizes"][a:e], sizes)
+        assert np.array_equal(m["cluster_offsets"][a:e], np.concatenate([[0], np.cumsum(sizes)[:-1]]))
+        order = np.flatnonzero(valid)[np.argsort(asg[valid], kind="stable")]   # cluster by cluster, token order kept
+        assert np.array_equal(m["k_cache"][r0:r0 + len(order)], t.k_tokens[r0 + order])
+        assert np.array_equal(m["v_cache"][r0:r0 + len(order)], t.v_tokens[r0 + order])
+        row = m["token_row"][r0:r0 + n]
+        assert (row[~valid] == -1).all() and np.array_equal(row[order], np.arange(len(order)))
+
+
+def test_build_cluster_cache_means_are_exact_means_rounded_once():
+    from fractions import Fraction
+    from workloads import token_order_input
+    c = make_cache(batch=1, n_kv_heads=1, n_q_heads=1, context=120, mean_cluster=6, size_hi=20, q_scale=1.0, seed=42)
+    m = oracle.build_cluster_cache(token_order_input(c, seed=1))
+    K, V = bf16_bits_to_f32(m["k_cache"]), bf16_bits_to_f32(m["v_cache"])
+
+    def rne_bf16(fr):
+        """Exact rational -> nearest bf16 (8 significant bits), ties to even, as a float."""
+        if fr == 0:
+            return 0.0
+        sign, fr = (-1 if fr < 0 else 1), abs(fr)
+        e = 0
+        while fr >= 256:
+            fr /= 2
+            e += 1
+        while fr < 128:
+            fr *= 2
+            e -= 1
+        q, rem = divmod(fr.numerator, fr.denominator)
+        twice = 2 * rem
+        if twice > fr.denominator or (twice == fr.denominator and q % 2 == 1):
+            q += 1
+        return sign * float(Fraction(q) * Fraction(2) ** e)
+
+    for i in range(len(m["cluster_sizes"])):
+        s, off = int(m["cluster_sizes"][i]), int(m["cluster_offsets"][i])
+        for j in (0, 17, 127):
+            ks = sum(Fraction(float(x)) for x in K[off:off + s, j])
+            vs = sum(Fraction(float(x)) for x in V[off:off + s, j])
+            assert float(bf16_bits_to_f32(m["k_centroids"][i, j:j + 1])[0]) == rne_bf16(ks / s)
+            assert float(bf16_bits_to_f32(m["v_centroids"][i, j:j + 1])[0]) == rne_bf16(vs / s)
+            assert m["v_sums"][i, j] == pytest.approx(float(vs), rel=1e-14, abs=1e-300)
+
+
+def test_decode_on_the_rebuilt_cache_equals_decode_on_the_original():
+    """The method does not depend on the order of tokens inside a cluster: rebuilding the cache from a
+    shuffled token order must give the same decode step (same sets, same output up to summation order)."""
+    from workloads import token_order_input
+    c = make_cache(batch=1, n_kv_heads=2, n_q_heads=4, context=2000, mean_cluster=10, size_hi=40, q_scale=0.5, seed=43)
+    m = oracle.build_cluster_cache(token_order_input(c, seed=9))
+    assert np.array_equal(m["cluster_sizes"], c.cluster_sizes) and np.array_equal(m["cluster_offsets"], c.cluster_offsets)
+    # the generator's centroids are fp64 means of the same rows in another order: equal up to one bf16 ulp, rarely
+    dk = np.abs(bf16_bits_to_f32(m["k_centroids"]).astype(np.float64) - bf16_bits_to_f32(c.k_centroids))
+    assert (dk > 0).mean() < 1e-3 and (dk <= np.abs(bf16_bits_to_f32(c.k_centroids)) * 2.0 ** -7).all()
+    rebuilt = ClusteredCache(batch=c.batch, n_kv_heads=c.n_kv_heads, n_q_heads=c.n_q_heads, head_dim=c.head_dim, q=c.q,
+                             k_cache=m["k_cache"], v_cache=m["v_cache"], seg_row_base=c.seg_row_base,
+                             seg_cluster_ptr=c.seg_cluster_ptr, cluster_offsets=m["cluster_offsets"],
+                             cluster_sizes=m["cluster_sizes"], k_centroids=c.k_centroids, v_centroids=c.v_centroids)
+    a, b = oracle.Oracle(c).decode_step(0.95, 0.7), oracle.Oracle(rebuilt).decode_step(0.95, 0.7)
+    assert (a.k1 == b.k1).all() and (a.k2 == b.k2).all() and (a.order == b.order).all()
+    np.testing.assert_allclose(a.out, b.out, rtol=1e-11, atol=1e-13)

@@ -13,5 +13,7 @@ from .synth import (  # noqa: F401
     f32_to_bf16_bits,
     bf16_bits_to_f32,
     pin_sink_and_window,
+    TokenOrderInput,
+    token_order_input,
     CLUSTER_PINNED,
 )

@@ -328,3 +328,43 @@ def pin_sink_and_window(cache: ClusteredCache, first: int = 1, last: int = 4) ->
         flags[max(a, e - last):e] |= CLUSTER_PINNED
     cache.cluster_flags = flags
     return cache
+
+
+@dataclass
+class TokenOrderInput:
+    """What the prefill stage hands to the metadata build: K / V in token order and a cluster id per token."""
+    n_seg: int
+    head_dim: int
+    k_tokens: np.ndarray         # uint16 [total_rows, d]
+    v_tokens: np.ndarray         # uint16 [total_rows, d]
+    assignment: np.ndarray       # int32  [total_rows]  segment-local cluster id of each token
+    seg_row_base: np.ndarray     # int64  [n_seg]
+    seg_rows: np.ndarray         # int32  [n_seg]
+    seg_cluster_ptr: np.ndarray  # int32  [n_seg+1]
+
+
+def token_order_input(cache: ClusteredCache, seed: int = 0) -> TokenOrderInput:
+    """Undo the cluster-contiguous layout of a generated cache: the rows of every segment are put into a
+    seeded random "token order" and each token remembers the cluster it came from.  (The clusters of the
+    cache must tile their segment without gaps.)"""
+    k_tok, v_tok = np.empty_like(cache.k_cache), np.empty_like(cache.v_cache)
+    asg = np.empty(cache.k_cache.shape[0], dtype=np.int32)
+    rows = np.zeros(cache.n_seg, dtype=np.int32)
+    for seg in range(cache.n_seg):
+        a, e = int(cache.seg_cluster_ptr[seg]), int(cache.seg_cluster_ptr[seg + 1])
+        n, r0 = int(cache.cluster_sizes[a:e].sum()), int(cache.seg_row_base[seg])
+        cluster_of_row = np.repeat(np.arange(e - a, dtype=np.int32), cache.cluster_sizes[a:e])
+        row_of = np.empty(n, dtype=np.int64)   # rows listed cluster by cluster, at their actual offsets
+        pos = 0
+        for i in range(a, e):
+            s = int(cache.cluster_sizes[i])
+            row_of[pos:pos + s] = int(cache.cluster_offsets[i]) + np.arange(s)
+            pos += s
+        perm = np.random.default_rng(np.random.SeedSequence([seed, 77, seg])).permutation(n)
+        k_tok[r0:r0 + n] = cache.k_cache[r0 + row_of[perm]]
+        v_tok[r0:r0 + n] = cache.v_cache[r0 + row_of[perm]]
+        asg[r0:r0 + n] = cluster_of_row[perm]
+        rows[seg] = n
+    return TokenOrderInput(n_seg=cache.n_seg, head_dim=cache.head_dim, k_tokens=k_tok, v_tokens=v_tok,
+                           assignment=asg, seg_row_base=cache.seg_row_base.copy(), seg_rows=rows,
+                           seg_cluster_ptr=cache.seg_cluster_ptr.copy())
