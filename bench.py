@@ -251,6 +251,22 @@ def main():
     dp.dp_decode_attention(pr0, p1, p2, out, lse, ws, None, None, None)
     torch.cuda.synchronize()
 
+    # ---- the prefill-side build of this workload's cache (Sec. 4.1, Eq. 2): token-order K / V + cluster ids ->
+    # cluster-contiguous rows, sizes, offsets, centroids.  One call per layer, not part of the decode step. ----
+    from workloads import token_order_input
+    tok = token_order_input(cache, seed=1)
+    up = lambda a, dt: torch.from_numpy(np.ascontiguousarray(a).view(dt)).to(dev)
+    pf = dp.Prefill(up(tok.k_tokens, np.int16), up(tok.v_tokens, np.int16), up(tok.assignment, np.int32),
+                    base.seg_row_base, up(tok.seg_rows, np.int32), base.seg_cluster_ptr, base.total_clusters, mk,
+                    int(tok.seg_rows.max()))
+    bws = torch.empty(max(dp.dp_build_workspace_bytes(pf), 256), dtype=torch.uint8, device=dev)
+    b_k, b_v = torch.empty_like(base.k_cache), torch.empty_like(base.v_cache)
+    b_off, b_sz = torch.empty_like(base.cluster_offsets), torch.empty_like(base.cluster_sizes)
+    b_kc, b_vc = torch.empty_like(base.k_centroids), torch.empty_like(base.v_centroids)
+    build_us = wall_time(lambda i: dp.dp_build_cluster_cache(pf, b_k, b_v, b_off, b_sz, b_kc, b_vc, bws), 20)
+    build_bytes = int(tok.k_tokens.shape[0]) * (3 * 512 + 4)   # K+V rows read, written, read again for the means; ids
+    del tok, pf, bws, b_k, b_v, b_off, b_sz, b_kc, b_vc
+
     # the kernel that moves the bytes: centroid scoring reads every key centroid and size once and
     # writes G logits per cluster
     total_k = int(cache.seg_cluster_ptr[-1])
@@ -322,6 +338,8 @@ def main():
             "speedup_over_fixed_budget": round(budget_us / value, 2),
         },
         "with_sink_and_window_pinned_us": round(pinned_us, 3),
+        "prefill_build": {"entry_point": "dp_build_cluster_cache", "us": round(build_us, 1),
+                          "bytes": build_bytes, "GBs": round(build_bytes / (build_us * 1e-6) / 1e9, 1)},
         "gen_seconds": round(t_gen, 1),
     }
 

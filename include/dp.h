@@ -168,6 +168,52 @@ dp_status dp_budget_decode_attention(const dp_problem *problem, int32_t k_retain
 dp_status dp_dense_decode(const dp_problem *problem, const int32_t *seg_rows, void *out, dp_dtype out_dtype,
                           float *lse, void *workspace, size_t workspace_bytes, void *stream);
 
+/* ---- prefill side: the cluster-contiguous cache and its metadata (Sec. 4.1, Eq. 2) ---- */
+
+/* K / V of the context in token order with one cluster id per token (the result
+ * of the clustering step, which is not part of this library).  Segment seg owns
+ * rows [seg_row_base[seg], seg_row_base[seg] + seg_rows[seg]) of k_tokens,
+ * v_tokens, assignment AND of the output cache, and clusters
+ * [seg_cluster_ptr[seg], seg_cluster_ptr[seg+1]).  All pointers are device
+ * pointers; the three bounds are host-known. */
+typedef struct {
+  int32_t n_seg;                  /* batch * n_kv_heads                                                  */
+  int32_t head_dim;               /* 128                                                                 */
+  const void *k_tokens;           /* bf16 [total_rows, head_dim], token order                            */
+  const void *v_tokens;           /* bf16 [total_rows, head_dim]                                         */
+  const int32_t *assignment;      /* [total_rows] segment-local cluster id of each token                 */
+  const int64_t *seg_row_base;    /* [n_seg]                                                             */
+  const int32_t *seg_rows;        /* [n_seg] tokens of each segment (clamped to max_rows_per_seg)        */
+  const int32_t *seg_cluster_ptr; /* [n_seg+1]                                                           */
+  int32_t total_clusters;         /* seg_cluster_ptr[n_seg]                                              */
+  int32_t max_clusters_per_seg;   /* upper bound on ptr[seg+1]-ptr[seg]                                  */
+  int32_t max_rows_per_seg;       /* upper bound on seg_rows[seg]                                        */
+} dp_prefill;
+
+/* Host-only.  Device workspace dp_build_cluster_cache needs (per segment and
+ * 1024-token block one int32 per cluster, plus 2 bytes per token); 0 for an
+ * invalid description. */
+size_t dp_build_workspace_bytes(const dp_prefill *in);
+
+/* Builds what the decode entry points read (the dp_problem fields of the same
+ * names): clusters laid out in index order, the tokens of a cluster in token
+ * order (a stable counting sort by cluster id):
+ *   k_cache, v_cache   bf16 [total_rows, head_dim]   the rows, cluster-contiguous
+ *   cluster_sizes      int32 [total_clusters]        s_i = |T_i|
+ *   cluster_offsets    int32 [total_clusters]        exclusive prefix of the sizes per segment
+ *   k_centroids        bf16 [total_clusters, d]      C_i: mean key of the cluster
+ *   v_centroids        bf16 [total_clusters, d]      V-bar_i = V^Sigma_i / s_i (Eq. 2)
+ *   v_sums (nullable)  fp32 [total_clusters, d]      V^Sigma_i (Eq. 2)
+ *   token_row (nullable) int32 [total_rows]          segment-relative cache row of each token, -1 if left out
+ * Means are fp64 sums in row order divided by s_i and rounded ONCE to bf16 (ties
+ * to even); an empty cluster gets zero rows.  A token whose id is outside
+ * [0, clusters of its segment) is left out of the cache.  Bitwise reproducible.
+ * The outputs must not alias the inputs.  workspace: dp_build_workspace_bytes,
+ * 256-byte aligned. */
+dp_status dp_build_cluster_cache(const dp_prefill *in, void *k_cache, void *v_cache, int32_t *cluster_offsets,
+                                 int32_t *cluster_sizes, void *k_centroids, void *v_centroids, float *v_sums,
+                                 int32_t *token_row, void *workspace, size_t workspace_bytes, void *stream);
+
 /* Where dp_decode_attention keeps its intermediate results inside the
  * workspace (byte offsets; host-only, for inspection by tests and tools):
  * logits as in dp_score_centroids, sel_ids as in dp_topp_select. */

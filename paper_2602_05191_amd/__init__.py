@@ -8,8 +8,11 @@ from .binding import (  # noqa: F401
     DP_FLAG_P2_ABSOLUTE,
     DPError,
     DeviceCache,
+    Prefill,
     Problem,
     dp_budget_decode_attention,
+    dp_build_cluster_cache,
+    dp_build_workspace_bytes,
     dp_decode_attention,
     dp_dense_decode,
     dp_score_centroids,

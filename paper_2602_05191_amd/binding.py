@@ -25,7 +25,8 @@ _LIB_PATH = os.path.join(_PKG, "libdp_hip.so")
 EXPORTS = ["dp_workspace_bytes", "dp_logits_count", "dp_get_workspace_layout", "dp_score_centroids",
            "dp_score_centroids_timed",
            "dp_topp_select", "dp_topk_select", "dp_sparse_decode", "dp_decode_attention",
-           "dp_budget_decode_attention", "dp_dense_decode", "dp_status_string"]
+           "dp_budget_decode_attention", "dp_dense_decode", "dp_build_workspace_bytes", "dp_build_cluster_cache",
+           "dp_status_string"]
 
 
 class DPError(RuntimeError):
@@ -43,6 +44,13 @@ class _Problem(C.Structure):
                 ("total_clusters", C.c_int32), ("max_clusters_per_seg", C.c_int32),
                 ("max_rows_per_seg", C.c_int32), ("sm_scale", C.c_float), ("flags", C.c_uint32),
                 ("cluster_flags", C.c_void_p)]
+
+
+class _Prefill(C.Structure):
+    _fields_ = [("n_seg", C.c_int32), ("head_dim", C.c_int32), ("k_tokens", C.c_void_p), ("v_tokens", C.c_void_p),
+                ("assignment", C.c_void_p), ("seg_row_base", C.c_void_p), ("seg_rows", C.c_void_p),
+                ("seg_cluster_ptr", C.c_void_p), ("total_clusters", C.c_int32),
+                ("max_clusters_per_seg", C.c_int32), ("max_rows_per_seg", C.c_int32)]
 
 
 class _Layout(C.Structure):
@@ -90,6 +98,10 @@ def load_library():
     L.dp_budget_decode_attention.argtypes = [PP, I, I, V, I, V, V, V, V, V, C.c_size_t, V]
     L.dp_dense_decode.restype = I
     L.dp_dense_decode.argtypes = [PP, V, V, I, V, V, C.c_size_t, V]
+    L.dp_build_workspace_bytes.restype = C.c_size_t
+    L.dp_build_workspace_bytes.argtypes = [C.POINTER(_Prefill)]
+    L.dp_build_cluster_cache.restype = I
+    L.dp_build_cluster_cache.argtypes = [C.POINTER(_Prefill), V, V, V, V, V, V, V, V, V, C.c_size_t, V]
     L.dp_status_string.restype = C.c_char_p
     L.dp_status_string.argtypes = [I]
     _lib = L
@@ -268,3 +280,46 @@ def dp_dense_decode(problem: Problem, seg_rows: torch.Tensor, out: torch.Tensor,
     _check(load_library().dp_dense_decode(problem.ref, _ptr(seg_rows), _ptr(out), dt, _ptr(lse), _ptr(workspace),
                                           workspace.numel() * workspace.element_size(), _stream(stream)),
            "dp_dense_decode")
+
+
+class Prefill:
+    """Host-side dp_prefill over device tensors (bf16 as int16 bits)."""
+
+    def __init__(self, k_tokens: torch.Tensor, v_tokens: torch.Tensor, assignment: torch.Tensor,
+                 seg_row_base: torch.Tensor, seg_rows: torch.Tensor, seg_cluster_ptr: torch.Tensor,
+                 total_clusters: int, max_clusters_per_seg: int, max_rows_per_seg: int, head_dim: int = 128):
+        self.tensors = (k_tokens, v_tokens, assignment, seg_row_base, seg_rows, seg_cluster_ptr)
+        assert assignment.dtype == torch.int32 and seg_rows.dtype == torch.int32
+        assert seg_row_base.dtype == torch.int64 and seg_cluster_ptr.dtype == torch.int32
+        self.n_seg = int(seg_rows.numel())
+        self.total_rows, self.total_clusters = int(k_tokens.shape[0]), int(total_clusters)
+        self.c = _Prefill(self.n_seg, head_dim, _ptr(k_tokens), _ptr(v_tokens), _ptr(assignment), _ptr(seg_row_base),
+                          _ptr(seg_rows), _ptr(seg_cluster_ptr), int(total_clusters), int(max_clusters_per_seg),
+                          int(max_rows_per_seg))
+
+    @property
+    def ref(self):
+        return C.byref(self.c)
+
+
+def dp_build_workspace_bytes(prefill: Prefill) -> int:
+    return int(load_library().dp_build_workspace_bytes(prefill.ref))
+
+
+def dp_build_cluster_cache(prefill: Prefill, k_cache: torch.Tensor, v_cache: torch.Tensor,
+                           cluster_offsets: torch.Tensor, cluster_sizes: torch.Tensor, k_centroids: torch.Tensor,
+                           v_centroids: torch.Tensor, workspace: torch.Tensor, v_sums: Optional[torch.Tensor] = None,
+                           token_row: Optional[torch.Tensor] = None, stream=None) -> None:
+    for t in (cluster_offsets, cluster_sizes):
+        assert t.dtype == torch.int32 and t.is_contiguous() and t.numel() >= prefill.total_clusters
+    for t in (k_cache, v_cache):
+        assert t.is_contiguous() and t.element_size() == 2 and t.numel() >= prefill.total_rows * prefill.c.head_dim
+    for t in (k_centroids, v_centroids):
+        assert t.is_contiguous() and t.element_size() == 2 and t.numel() >= prefill.total_clusters * prefill.c.head_dim
+    assert v_sums is None or (v_sums.dtype == torch.float32 and v_sums.is_contiguous())
+    assert token_row is None or (token_row.dtype == torch.int32 and token_row.numel() >= prefill.total_rows)
+    _check(load_library().dp_build_cluster_cache(prefill.ref, _ptr(k_cache), _ptr(v_cache), _ptr(cluster_offsets),
+                                                 _ptr(cluster_sizes), _ptr(k_centroids), _ptr(v_centroids),
+                                                 _ptr(v_sums), _ptr(token_row), _ptr(workspace),
+                                                 workspace.numel() * workspace.element_size(), _stream(stream)),
+           "dp_build_cluster_cache")

@@ -312,6 +312,54 @@ dp_status dp_dense_decode(const dp_problem *problem, const int32_t *seg_rows, vo
              : DP_ERR_HIP;
 }
 
+static bool prefill_ok(const dp_prefill *in) {
+  return in && in->n_seg >= 0 && in->total_clusters >= 0 && in->max_clusters_per_seg >= 0 &&
+         in->max_rows_per_seg >= 0 && in->max_clusters_per_seg <= in->total_clusters;
+}
+
+size_t dp_build_workspace_bytes(const dp_prefill *in) {
+  if (!prefill_ok(in)) return 0;
+  size_t hist, rank;
+  int nb;
+  dp::build_workspace_layout(in->n_seg, in->max_rows_per_seg, in->max_clusters_per_seg, &hist, &rank, &nb);
+  return hist + rank;
+}
+
+dp_status dp_build_cluster_cache(const dp_prefill *in, void *k_cache, void *v_cache, int32_t *cluster_offsets,
+                                 int32_t *cluster_sizes, void *k_centroids, void *v_centroids, float *v_sums,
+                                 int32_t *token_row, void *workspace, size_t workspace_bytes, void *stream) {
+  if (!prefill_ok(in)) return DP_ERR_INVALID_ARG;
+  if (in->head_dim != dp::kHeadDim) return DP_ERR_UNSUPPORTED;
+  if (in->n_seg == 0) return DP_OK;
+  if (!in->seg_row_base || !in->seg_rows || !in->seg_cluster_ptr) return DP_ERR_INVALID_ARG;
+  if (in->max_rows_per_seg > 0 && (!in->k_tokens || !in->v_tokens || !in->assignment || !k_cache || !v_cache))
+    return DP_ERR_INVALID_ARG;
+  if (in->total_clusters > 0 && (!cluster_offsets || !cluster_sizes || !k_centroids || !v_centroids))
+    return DP_ERR_INVALID_ARG;
+  const size_t need = dp_build_workspace_bytes(in);
+  if (workspace_bytes < need) return DP_ERR_WORKSPACE_TOO_SMALL;
+  if (need > 0 && (!workspace || reinterpret_cast<uintptr_t>(workspace) % 256)) return DP_ERR_INVALID_ARG;
+  dp::BuildProblem p;
+  p.n_seg = in->n_seg;
+  p.k_tokens = in->k_tokens;
+  p.v_tokens = in->v_tokens;
+  p.assignment = in->assignment;
+  p.seg_row_base = in->seg_row_base;
+  p.seg_rows = in->seg_rows;
+  p.seg_cluster_ptr = in->seg_cluster_ptr;
+  p.max_kc = in->max_clusters_per_seg;
+  p.max_rows = in->max_rows_per_seg;
+  p.k_cache = k_cache;
+  p.v_cache = v_cache;
+  p.k_centroids = k_centroids;
+  p.v_centroids = v_centroids;
+  p.cluster_offsets = cluster_offsets;
+  p.cluster_sizes = cluster_sizes;
+  p.token_row = token_row;
+  p.v_sums = v_sums;
+  return dp::launch_build(p, workspace, static_cast<hipStream_t>(stream)) == hipSuccess ? DP_OK : DP_ERR_HIP;
+}
+
 const char *dp_status_string(dp_status status) {
   switch (status) {
     case DP_OK: return "DP_OK";

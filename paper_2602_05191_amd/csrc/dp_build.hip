@@ -1,0 +1,269 @@
+// Prefill side of the clustered cache (paper Sec. 4.1, Eq. 2): from K / V in
+// token order and one cluster id per token, build what the decode step reads:
+// the cluster-contiguous K / V rows, per-cluster sizes and offsets, the key
+// centroids C_i (mean key) and the value aggregates V^Sigma_i and V-bar_i.
+//
+// A stable counting sort by cluster id, then a segmented mean.  HBM-bound: the
+// K / V rows are read once and written once by the scatter and read once more
+// (mostly from cache) by the mean.  Everything is deterministic: counts are
+// integers, a token's place inside its cluster is its token order, and the
+// means are fp64 sums taken in row order and rounded once to bf16.
+//
+//   rank     per 1024-token block: a token's rank among the EARLIER tokens of
+//            its block with the same id (pairwise compare against ids staged in
+//            LDS) and, by integer atomic max, the block's count per cluster
+//   scan     per cluster: exclusive prefix of those counts over the blocks
+//            (in place) and the cluster's size
+//   offsets  per segment: exclusive prefix of the sizes
+//   scatter  row of a token = offset of its cluster + count of its cluster in
+//            earlier blocks + rank; a 16-lane DPP row moves one 256 B row
+//   means    one 16-lane row per cluster walks the cluster's rows in order
+#include "dp_device.hpp"
+#include "dp_kernels.hpp"
+
+namespace dp {
+namespace {
+
+constexpr int kBuildBlock = 1024;  // tokens per block = threads per workgroup of rank / scatter
+
+struct BuildArgs {
+  const void *k_tokens, *v_tokens;
+  const int32_t *assignment;
+  const int64_t *seg_row_base;
+  const int32_t *seg_rows, *seg_cluster_ptr;
+  void *k_cache, *v_cache, *k_centroids, *v_centroids;
+  int32_t *cluster_offsets, *cluster_sizes, *token_row;  // token_row nullable
+  float *v_sums;                                         // nullable
+  int32_t *hist;                                         // [n_seg, n_blocks, max_kc]
+  uint16_t *rank;                                        // [n_seg, n_blocks * kBuildBlock]
+  int32_t n_blocks, max_kc, max_rows;
+};
+
+__global__ void build_zero_kernel(int32_t *p, size_t n) {
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) p[i] = 0;
+}
+
+__global__ __launch_bounds__(kBuildBlock) void build_rank_kernel(BuildArgs a) {
+  __shared__ int s_id[kBuildBlock];
+  const int seg = blockIdx.y, blk = blockIdx.x, tid = threadIdx.x;
+  const int n = min(a.seg_rows[seg], a.max_rows);
+  if (blk * kBuildBlock >= n) return;
+  const int c0 = a.seg_cluster_ptr[seg], kc = min(a.seg_cluster_ptr[seg + 1] - c0, a.max_kc);
+  const int t = blk * kBuildBlock + tid;
+  int c = -1;
+  if (t < n) {
+    c = a.assignment[a.seg_row_base[seg] + t];
+    if ((unsigned)c >= (unsigned)kc) c = -1;  // a token without a valid cluster is left out
+  }
+  s_id[tid] = c;
+  __syncthreads();
+  if (c < 0) return;
+  // earlier tokens of the block with the same id; the bound is uniform in the wave
+  int earlier = 0;
+  const int bound = (tid | 63) + 1;
+  for (int j = 0; j < bound; j += 4) {
+    const int4 v = *reinterpret_cast<const int4 *>(&s_id[j]);
+    earlier += (v.x == c && j < tid) + (v.y == c && j + 1 < tid) + (v.z == c && j + 2 < tid) + (v.w == c && j + 3 < tid);
+  }
+  a.rank[((size_t)seg * a.n_blocks + blk) * kBuildBlock + tid] = (uint16_t)earlier;
+  // the block's count of cluster c = the largest rank + 1 (an integer maximum: order-independent)
+  atomicMax(&a.hist[((size_t)seg * a.n_blocks + blk) * a.max_kc + c], earlier + 1);
+}
+
+__global__ __launch_bounds__(256) void build_scan_kernel(BuildArgs a) {
+  const int seg = blockIdx.y;
+  const int c0 = a.seg_cluster_ptr[seg], kc = min(a.seg_cluster_ptr[seg + 1] - c0, a.max_kc);
+  const int c = blockIdx.x * 256 + threadIdx.x;
+  if (c >= kc) return;
+  const int n = min(a.seg_rows[seg], a.max_rows);
+  const int blocks = (n + kBuildBlock - 1) / kBuildBlock;
+  int32_t *h = a.hist + (size_t)seg * a.n_blocks * a.max_kc + c;
+  int run = 0;
+  for (int b = 0; b < blocks; ++b) {
+    const int v = h[(size_t)b * a.max_kc];
+    h[(size_t)b * a.max_kc] = run;
+    run += v;
+  }
+  a.cluster_sizes[c0 + c] = run;
+}
+
+__global__ __launch_bounds__(1024) void build_offsets_kernel(BuildArgs a) {
+  __shared__ int scr[1024 / 64 + 1];
+  const int seg = blockIdx.x, tid = threadIdx.x;
+  const int c0 = a.seg_cluster_ptr[seg], kc = a.seg_cluster_ptr[seg + 1] - c0;
+  int carry = 0;
+  for (int i0 = 0; i0 < kc; i0 += 1024) {
+    const int i = i0 + tid;
+    // clusters beyond the host's bound received no size: they are reported empty
+    const int s = (i < kc && i < a.max_kc) ? a.cluster_sizes[c0 + i] : 0;
+    int tot;
+    const int ex = block_excl_scan<int, 1024 / 64>(s, scr, tot);
+    if (i < kc) {
+      a.cluster_offsets[c0 + i] = carry + ex;
+      if (i >= a.max_kc) a.cluster_sizes[c0 + i] = 0;
+    }
+    carry += tot;
+  }
+}
+
+__global__ __launch_bounds__(kBuildBlock) void build_scatter_kernel(BuildArgs a) {
+  __shared__ int s_dest[kBuildBlock];
+  const int seg = blockIdx.y, blk = blockIdx.x, tid = threadIdx.x;
+  const int n = min(a.seg_rows[seg], a.max_rows);
+  if (blk * kBuildBlock >= n) return;
+  const int c0 = a.seg_cluster_ptr[seg], kc = min(a.seg_cluster_ptr[seg + 1] - c0, a.max_kc);
+  const int64_t r0 = a.seg_row_base[seg];
+  const int t = blk * kBuildBlock + tid;
+  int dest = -1;
+  if (t < n) {
+    const int c = a.assignment[r0 + t];
+    if ((unsigned)c < (unsigned)kc)
+      dest = a.cluster_offsets[c0 + c] + a.hist[((size_t)seg * a.n_blocks + blk) * a.max_kc + c] +
+             a.rank[((size_t)seg * a.n_blocks + blk) * kBuildBlock + tid];
+    if (a.token_row) a.token_row[r0 + t] = dest;
+  }
+  s_dest[tid] = dest;
+  __syncthreads();
+  // every 16-lane row moves one 256 B K row and one V row per step, 4 steps in flight
+  const int lane16 = tid & 15, grp = tid >> 4;
+  constexpr int kGroups = kBuildBlock / 16;
+  for (int i0 = grp; i0 < kBuildBlock; i0 += 4 * kGroups) {
+    uint4 kr[4], vr[4];
+    int d[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int i = i0 + u * kGroups;
+      d[u] = s_dest[i];
+      if (d[u] >= 0) {
+        kr[u] = load_row_slice(a.k_tokens, r0 + blk * kBuildBlock + i, lane16);
+        vr[u] = load_row_slice(a.v_tokens, r0 + blk * kBuildBlock + i, lane16);
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      if (d[u] >= 0) {
+        *reinterpret_cast<uint4 *>(static_cast<char *>(a.k_cache) + (r0 + d[u]) * kRowBytes + lane16 * 16) = kr[u];
+        *reinterpret_cast<uint4 *>(static_cast<char *>(a.v_cache) + (r0 + d[u]) * kRowBytes + lane16 * 16) = vr[u];
+      }
+    }
+  }
+}
+
+// double -> bf16 bits with ONE rounding to 8 significant bits, ties to even.  Values whose magnitude
+// is below the bf16 normal range go through float (two roundings, irrelevant at 1e-38).
+__device__ __forceinline__ uint32_t f64_to_bf16_rne(double x) {
+  const unsigned long long u = (unsigned long long)__double_as_longlong(x);
+  const int e = (int)((u >> 52) & 0x7ff) - 1023 + 127;  // bf16 / float exponent field
+  if (e <= 0 || e >= 255) return f32_to_bf16_rne((float)x);
+  const unsigned long long man = u & 0xfffffffffffffull;
+  unsigned long long top = man >> 45;                   // 7 explicit mantissa bits
+  const unsigned long long rest = man & ((1ull << 45) - 1), half = 1ull << 44;
+  uint32_t bits = ((uint32_t)(u >> 63) << 15) | ((uint32_t)e << 7) | (uint32_t)top;
+  if (rest > half || (rest == half && (top & 1))) bits += 1;  // a carry runs into the exponent, as it should
+  return bits;
+}
+
+__global__ __launch_bounds__(256) void build_means_kernel(BuildArgs a) {
+  const int seg = blockIdx.y;
+  const int c0 = a.seg_cluster_ptr[seg], kc = a.seg_cluster_ptr[seg + 1] - c0;
+  const int lane16 = threadIdx.x & 15, grp = threadIdx.x >> 4;
+  const int ci = blockIdx.x * 16 + grp;
+  if (ci >= kc) return;
+  const int s = a.cluster_sizes[c0 + ci];
+  const int64_t row0 = a.seg_row_base[seg] + a.cluster_offsets[c0 + ci];
+  double ks[8], vs[8];
+#pragma unroll
+  for (int i = 0; i < 8; ++i) ks[i] = vs[i] = 0.0;
+  for (int r = 0; r < s; r += 4) {
+    uint4 kr[4], vr[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      if (r + u < s) {
+        kr[u] = load_row_slice(a.k_cache, row0 + r + u, lane16);
+        vr[u] = load_row_slice(a.v_cache, row0 + r + u, lane16);
+      } else {
+        kr[u] = make_uint4(0, 0, 0, 0);
+        vr[u] = make_uint4(0, 0, 0, 0);
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {  // rows beyond the cluster add +0.0: the sums are unchanged
+      float kf[8], vf[8];
+      unpack8(kr[u], kf);
+      unpack8(vr[u], vf);
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        ks[i] += (double)kf[i];
+        vs[i] += (double)vf[i];
+      }
+    }
+  }
+  uint32_t kb[8], vb[8];
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    kb[i] = s > 0 ? f64_to_bf16_rne(ks[i] / (double)s) : 0u;
+    vb[i] = s > 0 ? f64_to_bf16_rne(vs[i] / (double)s) : 0u;
+  }
+  const size_t off = (size_t)(c0 + ci) * kRowBytes + lane16 * 16;
+  *reinterpret_cast<uint4 *>(static_cast<char *>(a.k_centroids) + off) =
+      make_uint4(kb[0] | (kb[1] << 16), kb[2] | (kb[3] << 16), kb[4] | (kb[5] << 16), kb[6] | (kb[7] << 16));
+  *reinterpret_cast<uint4 *>(static_cast<char *>(a.v_centroids) + off) =
+      make_uint4(vb[0] | (vb[1] << 16), vb[2] | (vb[3] << 16), vb[4] | (vb[5] << 16), vb[6] | (vb[7] << 16));
+  if (a.v_sums) {
+    float *o = a.v_sums + (size_t)(c0 + ci) * kHeadDim + lane16 * 8;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) o[i] = (float)vs[i];
+  }
+}
+
+}  // namespace
+
+void build_workspace_layout(int n_seg, int max_rows, int max_kc, size_t *hist_bytes, size_t *rank_bytes, int *n_blocks) {
+  const int nb = (max_rows + kBuildBlock - 1) / kBuildBlock;
+  *n_blocks = nb;
+  *hist_bytes = ((size_t)n_seg * nb * max_kc * sizeof(int32_t) + 255) / 256 * 256;
+  *rank_bytes = ((size_t)n_seg * nb * kBuildBlock * sizeof(uint16_t) + 255) / 256 * 256;
+}
+
+hipError_t launch_build(const BuildProblem &p, void *workspace, hipStream_t s) {
+  if (p.n_seg == 0) return hipSuccess;
+  size_t hist_bytes, rank_bytes;
+  int n_blocks;
+  build_workspace_layout(p.n_seg, p.max_rows, p.max_kc, &hist_bytes, &rank_bytes, &n_blocks);
+  BuildArgs a;
+  a.k_tokens = p.k_tokens;
+  a.v_tokens = p.v_tokens;
+  a.assignment = p.assignment;
+  a.seg_row_base = p.seg_row_base;
+  a.seg_rows = p.seg_rows;
+  a.seg_cluster_ptr = p.seg_cluster_ptr;
+  a.k_cache = p.k_cache;
+  a.v_cache = p.v_cache;
+  a.k_centroids = p.k_centroids;
+  a.v_centroids = p.v_centroids;
+  a.cluster_offsets = p.cluster_offsets;
+  a.cluster_sizes = p.cluster_sizes;
+  a.token_row = p.token_row;
+  a.v_sums = p.v_sums;
+  a.hist = static_cast<int32_t *>(workspace);
+  a.rank = reinterpret_cast<uint16_t *>(static_cast<char *>(workspace) + hist_bytes);
+  a.n_blocks = n_blocks;
+  a.max_kc = p.max_kc;
+  a.max_rows = p.max_rows;
+  const size_t hist_n = (size_t)p.n_seg * n_blocks * p.max_kc;
+  if (hist_n > 0) {
+    const size_t want = (hist_n + 255) / 256;
+    hipLaunchKernelGGL(build_zero_kernel, dim3((unsigned)(want < 4096 ? want : 4096)), dim3(256), 0, s, a.hist, hist_n);
+  }
+  if (n_blocks > 0 && p.max_kc > 0)
+    hipLaunchKernelGGL(build_rank_kernel, dim3(n_blocks, p.n_seg), dim3(kBuildBlock), 0, s, a);
+  if (p.max_kc > 0)
+    hipLaunchKernelGGL(build_scan_kernel, dim3((p.max_kc + 255) / 256, p.n_seg), dim3(256), 0, s, a);
+  hipLaunchKernelGGL(build_offsets_kernel, dim3(p.n_seg), dim3(1024), 0, s, a);
+  if (n_blocks > 0 && p.max_kc > 0)
+    hipLaunchKernelGGL(build_scatter_kernel, dim3(n_blocks, p.n_seg), dim3(kBuildBlock), 0, s, a);
+  if (p.max_kc > 0) hipLaunchKernelGGL(build_means_kernel, dim3((p.max_kc + 15) / 16, p.n_seg), dim3(256), 0, s, a);
+  return hipGetLastError();
+}
+
+}  // namespace dp

@@ -86,6 +86,21 @@ hipError_t launch_decode(const CacheView &c, const int32_t *n_exact, const int32
 hipError_t launch_dense(const CacheView &c, const int32_t *seg_rows, float *partials, int max_splits,
                         const AttnOut &attn, hipStream_t s);
 
+// Prefill side: token-order K / V + cluster ids -> cluster-contiguous cache and cluster metadata.
+struct BuildProblem {
+  int32_t n_seg;
+  const void *k_tokens, *v_tokens;
+  const int32_t *assignment;
+  const int64_t *seg_row_base;
+  const int32_t *seg_rows, *seg_cluster_ptr;
+  int32_t max_kc, max_rows;
+  void *k_cache, *v_cache, *k_centroids, *v_centroids;
+  int32_t *cluster_offsets, *cluster_sizes, *token_row;  // token_row nullable
+  float *v_sums;                                         // nullable
+};
+void build_workspace_layout(int n_seg, int max_rows, int max_kc, size_t *hist_bytes, size_t *rank_bytes, int *n_blocks);
+hipError_t launch_build(const BuildProblem &p, void *workspace, hipStream_t s);
+
 // largest max_clusters_per_seg the selection kernel supports
 constexpr int kSelectMaxClusters = 65536;
 
