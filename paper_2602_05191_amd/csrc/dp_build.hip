@@ -79,10 +79,15 @@ __global__ __launch_bounds__(256) void build_scan_kernel(BuildArgs a) {
   const int blocks = (n + kBuildBlock - 1) / kBuildBlock;
   int32_t *h = a.hist + (size_t)seg * a.n_blocks * a.max_kc + c;
   int run = 0;
-  for (int b = 0; b < blocks; ++b) {
-    const int v = h[(size_t)b * a.max_kc];
-    h[(size_t)b * a.max_kc] = run;
-    run += v;
+  for (int b0 = 0; b0 < blocks; b0 += 8) {  // 8 independent loads in flight, then the running prefix
+    int v[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) v[u] = (b0 + u < blocks) ? h[(size_t)(b0 + u) * a.max_kc] : 0;
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      if (b0 + u < blocks) h[(size_t)(b0 + u) * a.max_kc] = run;
+      run += v[u];
+    }
   }
   a.cluster_sizes[c0 + c] = run;
 }
@@ -174,10 +179,11 @@ __global__ __launch_bounds__(256) void build_means_kernel(BuildArgs a) {
   double ks[8], vs[8];
 #pragma unroll
   for (int i = 0; i < 8; ++i) ks[i] = vs[i] = 0.0;
-  for (int r = 0; r < s; r += 4) {
-    uint4 kr[4], vr[4];
+  constexpr int kB = 4;  // rows in flight per 16-lane row
+  for (int r = 0; r < s; r += kB) {
+    uint4 kr[kB], vr[kB];
 #pragma unroll
-    for (int u = 0; u < 4; ++u) {
+    for (int u = 0; u < kB; ++u) {
       if (r + u < s) {
         kr[u] = load_row_slice(a.k_cache, row0 + r + u, lane16);
         vr[u] = load_row_slice(a.v_cache, row0 + r + u, lane16);
@@ -187,7 +193,7 @@ __global__ __launch_bounds__(256) void build_means_kernel(BuildArgs a) {
       }
     }
 #pragma unroll
-    for (int u = 0; u < 4; ++u) {  // rows beyond the cluster add +0.0: the sums are unchanged
+    for (int u = 0; u < kB; ++u) {  // rows beyond the cluster add +0.0: the sums are unchanged
       float kf[8], vf[8];
       unpack8(kr[u], kf);
       unpack8(vr[u], vf);
