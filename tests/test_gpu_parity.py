@@ -350,6 +350,38 @@ def test_budget_ties_are_cut_by_index():
 
 
 # ---------------------------------------------------------------------------
+# the largest cluster counts: 32 and 64 logits per thread, and one over the limit
+# ---------------------------------------------------------------------------
+@pytest.mark.parametrize("n_clusters", [20000, 65536])
+def test_very_many_clusters(n_clusters):
+    c = make_cache(batch=1, n_kv_heads=1, n_q_heads=2, context=2 * n_clusters, n_clusters=n_clusters, size_lo=1,
+                   size_hi=6, mean_cluster=2, q_scale=lambda rng, b, h: [0.3, 2.0][h], seed=70)
+    orc = oracle.Oracle(c)
+    for p1, p2 in ((0.95, 0.9), (0.6, 0.3)):
+        g = H.gpu_decode_attention(c, p1, p2)
+        assert H.check_sets(c, orc, g, p1, p2) <= 1
+        H.check_outputs(c, orc, g, tight=2e-4)
+    g = H.gpu_decode_attention(c, 0, 0, want_logits=True, budget=(3000, 700))
+    for i in range(2):
+        s = orc.fixed_budget(g.logits[i].astype(np.float64), 3000, 700)
+        assert np.array_equal(g.exact[i], s.exact) and np.array_equal(g.approx[i], s.approx)
+    H.check_outputs(c, orc, g, tight=2e-4)
+
+
+def test_more_clusters_than_supported_is_refused():
+    import torch
+    import paper_2602_05191_amd as dp
+    c = make_cache(batch=1, n_kv_heads=1, n_q_heads=1, context=70000, n_clusters=65537, size_lo=1, size_hi=3,
+                   mean_cluster=1, q_scale=1.0, seed=71)
+    pr = dp.Problem(dp.DeviceCache.from_host(c))
+    ws = torch.empty(max(dp.dp_workspace_bytes(pr), 256), dtype=torch.uint8, device="cuda:0")
+    out = torch.empty((1, 1, 128), dtype=torch.float32, device="cuda:0")
+    with pytest.raises(dp.DPError) as e:
+        dp.dp_decode_attention(pr, 0.9, 0.5, out, None, ws)
+    assert e.value.status == -2
+
+
+# ---------------------------------------------------------------------------
 # dense baseline (Eq. 1): dp_dense_decode
 # ---------------------------------------------------------------------------
 def check_dense(cache, orc, out, lse, tight=2e-4):
