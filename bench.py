@@ -77,10 +77,10 @@ def total_clusters_nonzero(cache):
     return int(cache.seg_cluster_ptr[-1]) > 0 and (cache.seg_cluster_ptr[1:] > cache.seg_cluster_ptr[:-1]).all()
 
 
-def measured_traffic(config):
-    """HBM bytes per launch of the scoring kernel from the committed rocprofv3 counter summary
+def measured_traffic(kernel, config):
+    """HBM bytes per launch of `kernel` from the committed rocprofv3 counter summary
     (FETCH_SIZE and WRITE_SIZE, scaled by what a plain copy of known size reads); None if there is none."""
-    path = os.path.join(ROOT, "profiles", f"score_kernel_cfg{config}.txt")
+    path = os.path.join(ROOT, "profiles", f"{kernel}_cfg{config}.txt")
     try:
         for line in open(path):
             if line.startswith("traffic_bytes_per_launch"):
@@ -210,6 +210,38 @@ def main():
         hip.hipEventDestroy(e0)
         hip.hipEventDestroy(e1)
     score_us, score_med = statistics.mean(durs), statistics.median(durs)
+
+    # The three kernels inside the one-call path: dp_decode_attention_timed stamps each kernel's begin and end.
+    n_in = min(n_stage, 360)
+    sets = []
+    for _ in range(n_in):
+        ev = [ctypes.c_void_p() for _ in range(6)]
+        for e in ev:
+            assert hip.hipEventCreate(ctypes.byref(e)) == 0
+        sets.append(ev)
+    for i in range(min(50, n_in)):
+        step(i)
+    torch.cuda.synchronize()
+    for i, ev in enumerate(sets):
+        dp.dp_decode_attention_timed(probs[i % L], p1, p2, out, lse, ws, ev)
+    torch.cuda.synchronize()
+
+    def elapsed(a, b):
+        ms = ctypes.c_float()
+        assert hip.hipEventElapsedTime(ctypes.byref(ms), a, b) == 0
+        return ms.value * 1e3
+
+    in_step = {k: [] for k in ("score", "select", "decode", "gap_score_select", "gap_select_decode")}
+    for ev in sets:
+        in_step["score"].append(elapsed(ev[0], ev[1]))
+        in_step["select"].append(elapsed(ev[2], ev[3]))
+        in_step["decode"].append(elapsed(ev[4], ev[5]))
+        in_step["gap_score_select"].append(elapsed(ev[1], ev[2]))
+        in_step["gap_select_decode"].append(elapsed(ev[3], ev[4]))
+        for e in ev:
+            hip.hipEventDestroy(e)
+    in_step_avg = {k: statistics.mean(v) for k, v in in_step.items()}
+    in_step_med = {k: statistics.median(v) for k, v in in_step.items()}
     select_us, select_med = time_stage(lambda i: dp.dp_topp_select(probs[i % L], logits, p1, p2, sel_d, ne, nr, nt))
     decode_us, decode_med = time_stage(lambda i: dp.dp_sparse_decode(probs[i % L], sel_d, ne, nr, out, lse, ws))
 
@@ -273,6 +305,18 @@ def main():
     score_bytes = total_k * (2 * cache.head_dim + 4 + 4 * cache.group)
     score_gbs = score_bytes / (score_us * 1e-6) / 1e9
 
+    # the dominant kernel = the one that moves most of the step's algorithmic bytes: the centroid scan for
+    # peaked heads, the row gather of the decode kernel when heads are flat
+    decode_bytes = alg["rows_union"] * 4 * cache.head_dim
+    if decode_bytes > score_bytes:
+        roof = dict(kernel="decode_kernel (steps a5-a6 of dp_decode_attention)", name="decode_kernel",
+                    bytes=decode_bytes, avg=in_step_avg["decode"], med=in_step_med["decode"],
+                    how="kernel-stamped HIP events inside dp_decode_attention")
+    else:
+        roof = dict(kernel="score_kernel (dp_score_centroids)", name="score_kernel", bytes=score_bytes,
+                    avg=score_us, med=score_med, how="kernel-stamped HIP events, back-to-back launches")
+    roof_gbs = roof["bytes"] / (roof["avg"] * 1e-6) / 1e9
+
     value = wall_us
     step_gbs = alg["total"] / (value * 1e-6) / 1e9
     result = {
@@ -314,18 +358,25 @@ def main():
             "dp_sparse_decode": round(decode_us, 3),
             "median": {"score": round(score_med, 3), "select": round(select_med, 3), "decode": round(decode_med, 3)},
         },
+        "kernels_in_step_us": {
+            "avg": {k: round(v, 3) for k, v in in_step_avg.items()},
+            "median": {k: round(v, 3) for k, v in in_step_med.items()},
+            "how": "dp_decode_attention_timed: HIP events stamped with each kernel's own begin and end",
+        },
         "roofline": {
-            "kernel": "score_kernel (dp_score_centroids)",
+            "kernel": roof["kernel"],
             "bound": "hbm",
-            "achieved": round(score_gbs, 1),
+            "achieved": round(roof_gbs, 1),
             "peak": HBM_PEAK_GBS,
             "unit": "GB/s",
-            "frac": round(score_gbs / HBM_PEAK_GBS, 4),
-            "traffic": measured_traffic(args.config),
-            "bytes_per_launch": score_bytes,
-            "avg_launch_us": round(score_us, 3),
-            "median_launch_us": round(score_med, 3),
-            "back_to_back_interval_us": round(score_gap_us, 3),
+            "frac": round(roof_gbs / HBM_PEAK_GBS, 4),
+            "traffic": measured_traffic(roof["name"], args.config),
+            "bytes_per_launch": roof["bytes"],
+            "avg_launch_us": round(roof["avg"], 3),
+            "median_launch_us": round(roof["med"], 3),
+            "measured_with": roof["how"],
+            "score_kernel": {"bytes_per_launch": score_bytes, "avg_launch_us": round(score_us, 3),
+                             "GBs": round(score_gbs, 1), "back_to_back_interval_us": round(score_gap_us, 3)},
         },
         "baselines_same_box": {
             "dense_us": round(dense_us, 3),

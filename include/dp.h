@@ -140,6 +140,18 @@ dp_status dp_decode_attention(const dp_problem *problem, float p1, float p2, voi
                               float *lse, int32_t *n_exact, int32_t *n_retained, int32_t *n_exact_tokens,
                               void *workspace, size_t workspace_bytes, void *stream);
 
+/* dp_decode_attention for measurement: events is a HOST array of 6 hipEvent_t
+ * (passed as void*, created by the caller with timing enabled, any may be
+ * NULL): {score begin, score end, select begin, select end, decode begin,
+ * decode end}.  Each pair receives the begin and end timestamps of that kernel
+ * itself, so after the stream has drained hipEventElapsedTime of a pair is the
+ * kernel's duration inside the one-call path and the time between pairs is the
+ * gap between the kernels.  Same result and errors as dp_decode_attention
+ * (without the optional count outputs). */
+dp_status dp_decode_attention_timed(const dp_problem *problem, float p1, float p2, void *out, dp_dtype out_dtype,
+                                    float *lse, void *workspace, size_t workspace_bytes, void *stream,
+                                    void *const *events);
+
 /* Stage 2 with a fixed budget in place of the two thresholds: the fixed top-k
  * cluster retrieval of the cluster-based baseline the paper compares with
  * (Sec. 5.1 "Baselines").  Same order as dp_topp_select (logit descending,

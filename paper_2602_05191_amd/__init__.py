@@ -14,6 +14,7 @@ from .binding import (  # noqa: F401
     dp_build_cluster_cache,
     dp_build_workspace_bytes,
     dp_decode_attention,
+    dp_decode_attention_timed,
     dp_dense_decode,
     dp_score_centroids,
     dp_score_centroids_timed,

@@ -25,7 +25,7 @@ _LIB_PATH = os.path.join(_PKG, "libdp_hip.so")
 EXPORTS = ["dp_workspace_bytes", "dp_logits_count", "dp_get_workspace_layout", "dp_score_centroids",
            "dp_score_centroids_timed",
            "dp_topp_select", "dp_topk_select", "dp_sparse_decode", "dp_decode_attention",
-           "dp_budget_decode_attention", "dp_dense_decode", "dp_build_workspace_bytes", "dp_build_cluster_cache",
+           "dp_decode_attention_timed", "dp_budget_decode_attention", "dp_dense_decode", "dp_build_workspace_bytes", "dp_build_cluster_cache",
            "dp_status_string"]
 
 
@@ -92,6 +92,8 @@ def load_library():
     L.dp_sparse_decode.argtypes = [PP, V, V, V, V, V, I, V, V, C.c_size_t, V]
     L.dp_decode_attention.restype = I
     L.dp_decode_attention.argtypes = [PP, F, F, V, I, V, V, V, V, V, C.c_size_t, V]
+    L.dp_decode_attention_timed.restype = I
+    L.dp_decode_attention_timed.argtypes = [PP, F, F, V, I, V, V, C.c_size_t, V, C.POINTER(C.c_void_p)]
     L.dp_topk_select.restype = I
     L.dp_topk_select.argtypes = [PP, V, I, I, V, V, V, V, V]
     L.dp_budget_decode_attention.restype = I
@@ -323,3 +325,16 @@ def dp_build_cluster_cache(prefill: Prefill, k_cache: torch.Tensor, v_cache: tor
                                                  _ptr(v_sums), _ptr(token_row), _ptr(workspace),
                                                  workspace.numel() * workspace.element_size(), _stream(stream)),
            "dp_build_cluster_cache")
+
+
+def dp_decode_attention_timed(problem: Problem, p1: float, p2: float, out: torch.Tensor, lse: Optional[torch.Tensor],
+                              workspace: torch.Tensor, events, stream=None) -> None:
+    """events: 6 raw hipEvent_t handles (ints or ctypes.c_void_p; None to skip one):
+    score begin / end, select begin / end, decode begin / end."""
+    dt = {torch.float32: DP_F32, torch.bfloat16: DP_BF16}[out.dtype]
+    assert len(events) == 6
+    arr = (C.c_void_p * 6)(*[e.value if isinstance(e, C.c_void_p) else e for e in events])
+    _check(load_library().dp_decode_attention_timed(problem.ref, p1, p2, _ptr(out), dt, _ptr(lse), _ptr(workspace),
+                                                    workspace.numel() * workspace.element_size(), _stream(stream),
+                                                    arr),
+           "dp_decode_attention_timed")

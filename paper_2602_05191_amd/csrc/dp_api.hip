@@ -166,7 +166,10 @@ dp_status select_only(const dp_problem *problem, const float *logits, const dp::
 // score -> select (+ attention of light heads) -> split decode, on one stream
 dp_status whole_step(const dp_problem *problem, const dp::SelectRule &rule, void *out, dp_dtype out_dtype, float *lse,
                      int32_t *n_exact, int32_t *n_retained, int32_t *n_exact_tokens, void *workspace,
-                     size_t workspace_bytes, void *stream) {
+                     size_t workspace_bytes, void *stream, void *const *events = nullptr) {
+  hipEvent_t ev[6] = {nullptr, nullptr, nullptr, nullptr, nullptr, nullptr};
+  if (events)
+    for (int i = 0; i < 6; ++i) ev[i] = static_cast<hipEvent_t>(events[i]);
   if (out_dtype != DP_BF16 && out_dtype != DP_F32) return DP_ERR_UNSUPPORTED;
   if (!out || !workspace) return DP_ERR_INVALID_ARG;
   if (workspace_bytes < dp_workspace_bytes(problem)) return DP_ERR_WORKSPACE_TOO_SMALL;
@@ -174,11 +177,12 @@ dp_status whole_step(const dp_problem *problem, const dp::SelectRule &rule, void
   const dp::CacheView c = view_of(problem);
   const Workspace w = carve(problem, workspace);
   hipStream_t s = static_cast<hipStream_t>(stream);
-  if (dp::launch_score(c, w.logits, s) != hipSuccess) return DP_ERR_HIP;
+  if (dp::launch_score(c, w.logits, s, ev[0], ev[1]) != hipSuccess) return DP_ERR_HIP;
   dp::SelectOut so{w.sel_ids, w.n_exact, w.n_retained, w.n_exact_tokens};
   const dp::AttnOut attn{out, lse, out_dtype == DP_BF16};
-  if (dp::launch_select(c, w.logits, rule, so, w.plan, attn, s) != hipSuccess) return DP_ERR_HIP;
-  if (dp::launch_decode(c, w.n_exact, w.n_retained, w.plan, w.partials, w.splits, attn, s) != hipSuccess)
+  if (dp::launch_select(c, w.logits, rule, so, w.plan, attn, s, ev[2], ev[3]) != hipSuccess) return DP_ERR_HIP;
+  if (dp::launch_decode(c, w.n_exact, w.n_retained, w.plan, w.partials, w.splits, attn, s, ev[4], ev[5]) !=
+      hipSuccess)
     return DP_ERR_HIP;
   const size_t nh = (size_t)problem->batch * problem->n_q_heads;
   // optional count outputs: device-to-device copies on the same stream
@@ -283,6 +287,16 @@ dp_status dp_decode_attention(const dp_problem *problem, float p1, float p2, voi
   if (!p_in_domain(p1, p2)) return DP_ERR_INVALID_ARG;
   return whole_step(problem, top_p_rule(problem, p1, p2), out, out_dtype, lse, n_exact, n_retained, n_exact_tokens,
                     workspace, workspace_bytes, stream);
+}
+
+dp_status dp_decode_attention_timed(const dp_problem *problem, float p1, float p2, void *out, dp_dtype out_dtype,
+                                    float *lse, void *workspace, size_t workspace_bytes, void *stream,
+                                    void *const *events) {
+  dp_status st = check_common(problem);
+  if (st != DP_OK) return st;
+  if (!p_in_domain(p1, p2) || !events) return DP_ERR_INVALID_ARG;
+  return whole_step(problem, top_p_rule(problem, p1, p2), out, out_dtype, lse, nullptr, nullptr, nullptr, workspace,
+                    workspace_bytes, stream, events);
 }
 
 dp_status dp_budget_decode_attention(const dp_problem *problem, int32_t k_retained, int32_t k_exact, void *out,

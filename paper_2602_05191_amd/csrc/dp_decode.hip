@@ -24,6 +24,8 @@
 // and the states are merged through LDS.  Partials (m, l, acc[128]) go to the
 // workspace; the item of a head that finishes last (an arrival counter, no
 // waiting) merges them (log-sum-exp merge), normalises and writes the output.
+#include <hip/hip_ext.h>
+
 #include "dp_attend.hpp"
 #include "dp_device.hpp"
 #include "dp_kernels.hpp"
@@ -301,7 +303,8 @@ extern "C" void dp_debug_set_decode_clock_buffer(void *p) { g_decode_clock_buffe
 #endif
 
 hipError_t launch_decode(const CacheView &c, const int32_t *n_exact, const int32_t *n_retained, const Plan &plan,
-                         float *partials, int splits, const AttnOut &attn, hipStream_t s) {
+                         float *partials, int splits, const AttnOut &attn, hipStream_t s, hipEvent_t start,
+                         hipEvent_t stop) {
   const int nh = c.batch * c.n_q_heads;
   if (nh == 0) return hipSuccess;
   DecodeArgs a;
@@ -336,7 +339,12 @@ hipError_t launch_decode(const CacheView &c, const int32_t *n_exact, const int32
     a.queue_next = plan.queue_next + slab;
     const long max_items = (long)a.n_heads * splits;
     const int grid = (int)(max_items < kDecodeGrid ? max_items : kDecodeGrid);
-    hipLaunchKernelGGL(decode_kernel, dim3(grid), dim3(kDecThreads), 0, s, a);
+    // measurement: the events bracket the first slab's begin and the last slab's end
+    hipEvent_t ev0 = (h0 == 0) ? start : nullptr, ev1 = (h0 + kMaxQueueHeads >= nh) ? stop : nullptr;
+    if (ev0 || ev1)
+      hipExtLaunchKernelGGL(decode_kernel, dim3(grid), dim3(kDecThreads), 0, s, ev0, ev1, 0, a);
+    else
+      hipLaunchKernelGGL(decode_kernel, dim3(grid), dim3(kDecThreads), 0, s, a);
   }
   return hipGetLastError();
 }

@@ -71,7 +71,8 @@ struct SelectRule {
 // plan.ent_src == nullptr => no plan is written
 // With a plan and attn.out != nullptr, heads with few rows are attended inside the selection kernel.
 hipError_t launch_select(const CacheView &c, const float *logits, const SelectRule &rule, const SelectOut &out,
-                         const Plan &plan, const AttnOut &attn, hipStream_t s);
+                         const Plan &plan, const AttnOut &attn, hipStream_t s, hipEvent_t start = nullptr,
+                         hipEvent_t stop = nullptr);
 
 // builds the plan from caller-given sets
 hipError_t launch_plan(const CacheView &c, const int32_t *sel_ids, const int32_t *n_exact,
@@ -79,7 +80,8 @@ hipError_t launch_plan(const CacheView &c, const int32_t *sel_ids, const int32_t
                        hipStream_t s);
 
 hipError_t launch_decode(const CacheView &c, const int32_t *n_exact, const int32_t *n_retained, const Plan &plan,
-                         float *partials, int splits, const AttnOut &attn, hipStream_t s);
+                         float *partials, int splits, const AttnOut &attn, hipStream_t s, hipEvent_t start = nullptr,
+                         hipEvent_t stop = nullptr);
 
 // Dense attention over rows [seg_row_base[seg], + seg_rows[seg]) of every segment for all its query heads.
 // partials: room for nh * max_splits * (kHeadDim + 2) floats.

@@ -27,6 +27,7 @@
 //   5. one-call path only: a head with at most 1024 rows is attended right
 //      here (64 DPP-row groups), which saves the latency of two more kernels
 //      for sharply peaked heads; heavier heads go to the split decode kernel.
+#include <hip/hip_ext.h>
 #include <limits.h>
 
 #include "dp_attend.hpp"
@@ -982,11 +983,17 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(PlanArgs a) {
 }
 
 template <int E>
-void launch_select_e(const SelectArgs &a, bool by_count, dim3 grid, hipStream_t s) {
-  if (by_count)
+void launch_select_e(const SelectArgs &a, bool by_count, dim3 grid, hipStream_t s, hipEvent_t start, hipEvent_t stop) {
+  if (start || stop) {  // measurement: the runtime stamps the kernel's own begin and end
+    if (by_count)
+      hipExtLaunchKernelGGL((select_kernel<E, true>), grid, dim3(kSelThreads), 0, s, start, stop, 0, a);
+    else
+      hipExtLaunchKernelGGL((select_kernel<E, false>), grid, dim3(kSelThreads), 0, s, start, stop, 0, a);
+  } else if (by_count) {
     hipLaunchKernelGGL((select_kernel<E, true>), grid, dim3(kSelThreads), 0, s, a);
-  else
+  } else {
     hipLaunchKernelGGL((select_kernel<E, false>), grid, dim3(kSelThreads), 0, s, a);
+  }
 }
 
 }  // namespace
@@ -997,7 +1004,7 @@ extern "C" void dp_debug_set_phase_clock_buffer(void *p) { g_phase_clock_buffer 
 #endif
 
 hipError_t launch_select(const CacheView &c, const float *logits, const SelectRule &rule, const SelectOut &out,
-                         const Plan &plan, const AttnOut &attn, hipStream_t s) {
+                         const Plan &plan, const AttnOut &attn, hipStream_t s, hipEvent_t start, hipEvent_t stop) {
   SelectArgs a;
   a.logits = logits;
   a.seg_cluster_ptr = c.seg_cluster_ptr;
@@ -1033,12 +1040,12 @@ hipError_t launch_select(const CacheView &c, const float *logits, const SelectRu
   const dim3 grid(c.batch * c.n_q_heads);
   if (grid.x == 0) return hipSuccess;
   const int k = c.max_clusters_per_seg;
-  if (k <= 2 * kSelThreads) launch_select_e<2>(a, bc, grid, s);
-  else if (k <= 4 * kSelThreads) launch_select_e<4>(a, bc, grid, s);
-  else if (k <= 8 * kSelThreads) launch_select_e<8>(a, bc, grid, s);
-  else if (k <= 16 * kSelThreads) launch_select_e<16>(a, bc, grid, s);
-  else if (k <= 32 * kSelThreads) launch_select_e<32>(a, bc, grid, s);
-  else if (k <= 64 * kSelThreads) launch_select_e<64>(a, bc, grid, s);
+  if (k <= 2 * kSelThreads) launch_select_e<2>(a, bc, grid, s, start, stop);
+  else if (k <= 4 * kSelThreads) launch_select_e<4>(a, bc, grid, s, start, stop);
+  else if (k <= 8 * kSelThreads) launch_select_e<8>(a, bc, grid, s, start, stop);
+  else if (k <= 16 * kSelThreads) launch_select_e<16>(a, bc, grid, s, start, stop);
+  else if (k <= 32 * kSelThreads) launch_select_e<32>(a, bc, grid, s, start, stop);
+  else if (k <= 64 * kSelThreads) launch_select_e<64>(a, bc, grid, s, start, stop);
   else return hipErrorInvalidValue;
   return hipGetLastError();
 }

@@ -486,3 +486,37 @@ def test_score_centroids_timed_stamps_the_kernel():
     assert torch.equal(a, b)
     hip.hipEventDestroy(e0)
     hip.hipEventDestroy(e1)
+
+
+def test_decode_attention_timed_stamps_the_three_kernels():
+    """The measurement variant of the one-call path: same output bits, and per-kernel durations that
+    are positive, ordered and shorter than the whole."""
+    import ctypes
+    import torch
+    import paper_2602_05191_amd as dp
+    c = make_cache(batch=1, n_kv_heads=2, n_q_heads=8, context=20000, mean_cluster=16, q_scale=0.4, seed=81)
+    dc = dp.DeviceCache.from_host(c)
+    pr = dp.Problem(dc)
+    ws = torch.zeros(dp.dp_workspace_bytes(pr), dtype=torch.uint8, device="cuda:0")
+    a = torch.zeros((1, 8, 128), dtype=torch.float32, device="cuda:0")
+    b = torch.zeros_like(a)
+    hip = ctypes.CDLL("libamdhip64.so")
+    ev = [ctypes.c_void_p() for _ in range(6)]
+    for e in ev:
+        assert hip.hipEventCreate(ctypes.byref(e)) == 0
+    dp.dp_decode_attention(pr, 0.95, 0.9, a, None, ws)
+    dp.dp_decode_attention_timed(pr, 0.95, 0.9, b, None, ws, ev)
+    torch.cuda.synchronize()
+    assert torch.equal(a, b)
+
+    def us(x, y):
+        ms = ctypes.c_float()
+        assert hip.hipEventElapsedTime(ctypes.byref(ms), x, y) == 0
+        return ms.value * 1e3
+
+    durations = [us(ev[0], ev[1]), us(ev[2], ev[3]), us(ev[4], ev[5])]
+    assert all(0.0 < d < 5000.0 for d in durations), durations
+    assert us(ev[1], ev[2]) >= 0.0 and us(ev[3], ev[4]) >= 0.0          # the kernels run one after the other
+    assert us(ev[0], ev[5]) >= sum(durations) - 1.0
+    for e in ev:
+        hip.hipEventDestroy(e)
