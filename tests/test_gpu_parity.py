@@ -520,3 +520,64 @@ def test_decode_attention_timed_stamps_the_three_kernels():
     assert us(ev[0], ev[5]) >= sum(durations) - 1.0
     for e in ev:
         hip.hipEventDestroy(e)
+
+
+# ---------------------------------------------------------------------------
+# the entry points hold no state: two streams at once, and HIP graph capture
+# ---------------------------------------------------------------------------
+def test_two_streams_with_own_workspaces_do_not_interfere():
+    import torch
+    import paper_2602_05191_amd as dp
+    ca = make_cache(batch=1, n_kv_heads=2, n_q_heads=8, context=30000, mean_cluster=16, q_scale=0.4, seed=91)
+    cb = make_cache(batch=2, n_kv_heads=2, n_q_heads=4, context=[9000, 4000], mean_cluster=16, q_scale=2.0, seed=92)
+    runs = []
+    for c in (ca, cb):
+        pr = dp.Problem(dp.DeviceCache.from_host(c))
+        ws = torch.zeros(dp.dp_workspace_bytes(pr), dtype=torch.uint8, device="cuda:0")
+        ref = torch.zeros((c.batch, c.n_q_heads, 128), dtype=torch.float32, device="cuda:0")
+        dp.dp_decode_attention(pr, 0.95, 0.9, ref, None, ws)
+        runs.append((pr, ws, ref, torch.zeros_like(ref), torch.cuda.Stream()))
+    torch.cuda.synchronize()
+    for _ in range(20):
+        for pr, ws, ref, out, st in runs:
+            with torch.cuda.stream(st):
+                dp.dp_decode_attention(pr, 0.95, 0.9, out, None, ws)
+    torch.cuda.synchronize()
+    for pr, ws, ref, out, st in runs:
+        assert torch.equal(out, ref)
+
+
+def test_one_call_path_replays_from_a_hip_graph():
+    """Capture dp_decode_attention into a graph and replay it with other queries; every replay must equal
+    the eager result on the same inputs (eager work and synchronisations in between)."""
+    import torch
+    import paper_2602_05191_amd as dp
+    c = make_cache(batch=1, n_kv_heads=2, n_q_heads=8, context=24000, mean_cluster=16,
+                   q_scale=lambda rng, b, h: 0.4 if h % 2 else 3.0, seed=93)
+    dc = dp.DeviceCache.from_host(c)
+    pr = dp.Problem(dc)
+    ws = torch.zeros(dp.dp_workspace_bytes(pr), dtype=torch.uint8, device="cuda:0")
+    out = torch.zeros((1, 8, 128), dtype=torch.float32, device="cuda:0")
+    lse = torch.zeros(8, dtype=torch.float32, device="cuda:0")
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        dp.dp_decode_attention(pr, 0.95, 0.9, out, lse, ws)          # warm up outside the capture
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g, stream=side):
+        dp.dp_decode_attention(pr, 0.95, 0.9, out, lse, ws)
+    rng = np.random.default_rng(3)
+    q0 = dc.q.clone()
+    for rep in range(4):
+        if rep:                                                      # a new query at the same address
+            perm = torch.from_numpy(rng.permutation(8)).cuda()
+            dc.q.copy_(q0[:, perm])
+        g.replay()
+        torch.cuda.synchronize()
+        got, got_lse = out.clone(), lse.clone()
+        eager, eager_lse = torch.zeros_like(out), torch.zeros_like(lse)
+        dp.dp_decode_attention(pr, 0.95, 0.9, eager, eager_lse, ws)
+        torch.cuda.synchronize()
+        assert torch.equal(got, eager) and torch.equal(got_lse, eager_lse), rep
