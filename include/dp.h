@@ -152,6 +152,16 @@ dp_status dp_decode_attention_timed(const dp_problem *problem, float p1, float p
                                     float *lse, void *workspace, size_t workspace_bytes, void *stream,
                                     void *const *events);
 
+/* A/B variant of dp_topp_select in the structure the paper describes for its own
+ * top-p kernel (Sec. 4.4): the cluster scores of a head are sorted first and the
+ * two cuts are taken by a prefix sum along the sorted order.  Same masses, same
+ * order, same tie-break, hence the same outputs as dp_topp_select; it exists to
+ * time the two designs against each other and nothing in the library calls it.
+ * DP_ERR_UNSUPPORTED for more than 8192 clusters per segment or with
+ * cluster_flags set. */
+dp_status dp_topp_select_sorted(const dp_problem *problem, const float *logits, float p1, float p2, int32_t *sel_ids,
+                                int32_t *n_exact, int32_t *n_retained, int32_t *n_exact_tokens, void *stream);
+
 /* Stage 2 with a fixed budget in place of the two thresholds: the fixed top-k
  * cluster retrieval of the cluster-based baseline the paper compares with
  * (Sec. 5.1 "Baselines").  Same order as dp_topp_select (logit descending,

@@ -21,6 +21,7 @@ from .binding import (  # noqa: F401
     dp_sparse_decode,
     dp_topk_select,
     dp_topp_select,
+    dp_topp_select_sorted,
     dp_workspace_bytes,
     dp_workspace_layout,
     library_path,

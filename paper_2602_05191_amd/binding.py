@@ -24,7 +24,7 @@ _LIB_PATH = os.path.join(_PKG, "libdp_hip.so")
 
 EXPORTS = ["dp_workspace_bytes", "dp_logits_count", "dp_get_workspace_layout", "dp_score_centroids",
            "dp_score_centroids_timed",
-           "dp_topp_select", "dp_topk_select", "dp_sparse_decode", "dp_decode_attention",
+           "dp_topp_select", "dp_topp_select_sorted", "dp_topk_select", "dp_sparse_decode", "dp_decode_attention",
            "dp_decode_attention_timed", "dp_budget_decode_attention", "dp_dense_decode", "dp_build_workspace_bytes", "dp_build_cluster_cache",
            "dp_status_string"]
 
@@ -94,6 +94,8 @@ def load_library():
     L.dp_decode_attention.argtypes = [PP, F, F, V, I, V, V, V, V, V, C.c_size_t, V]
     L.dp_decode_attention_timed.restype = I
     L.dp_decode_attention_timed.argtypes = [PP, F, F, V, I, V, V, C.c_size_t, V, C.POINTER(C.c_void_p)]
+    L.dp_topp_select_sorted.restype = I
+    L.dp_topp_select_sorted.argtypes = [PP, V, F, F, V, V, V, V, V]
     L.dp_topk_select.restype = I
     L.dp_topk_select.argtypes = [PP, V, I, I, V, V, V, V, V]
     L.dp_budget_decode_attention.restype = I
@@ -338,3 +340,15 @@ def dp_decode_attention_timed(problem: Problem, p1: float, p2: float, out: torch
                                                     workspace.numel() * workspace.element_size(), _stream(stream),
                                                     arr),
            "dp_decode_attention_timed")
+
+
+def dp_topp_select_sorted(problem: Problem, logits: torch.Tensor, p1: float, p2: float, sel_ids: torch.Tensor,
+                          n_exact: torch.Tensor, n_retained: torch.Tensor, n_exact_tokens: torch.Tensor,
+                          stream=None) -> None:
+    """A/B variant of dp_topp_select (sort first, then prefix sums); same outputs."""
+    for t in (sel_ids, n_exact, n_retained, n_exact_tokens):
+        assert t.dtype == torch.int32 and t.is_contiguous()
+    assert sel_ids.numel() >= problem.nh * problem.dc.max_clusters_per_seg and n_exact.numel() >= problem.nh
+    _check(load_library().dp_topp_select_sorted(problem.ref, _ptr(logits), p1, p2, _ptr(sel_ids), _ptr(n_exact),
+                                                _ptr(n_retained), _ptr(n_exact_tokens), _stream(stream)),
+           "dp_topp_select_sorted")

@@ -248,6 +248,21 @@ dp_status dp_topp_select(const dp_problem *problem, const float *logits, float p
                      stream);
 }
 
+dp_status dp_topp_select_sorted(const dp_problem *problem, const float *logits, float p1, float p2, int32_t *sel_ids,
+                                int32_t *n_exact, int32_t *n_retained, int32_t *n_exact_tokens, void *stream) {
+  dp_status st = check_common(problem);
+  if (st != DP_OK) return st;
+  if (!p_in_domain(p1, p2)) return DP_ERR_INVALID_ARG;
+  if (problem->max_clusters_per_seg > dp::kSortedSelectMaxClusters || problem->cluster_flags) return DP_ERR_UNSUPPORTED;
+  if (!n_exact || !n_retained || !n_exact_tokens) return DP_ERR_INVALID_ARG;
+  if (problem->max_clusters_per_seg > 0 && (!logits || !sel_ids)) return DP_ERR_INVALID_ARG;
+  dp::SelectOut out{sel_ids, n_exact, n_retained, n_exact_tokens};
+  return dp::launch_select_sorted(view_of(problem), logits, top_p_rule(problem, p1, p2), out,
+                                  static_cast<hipStream_t>(stream)) == hipSuccess
+             ? DP_OK
+             : DP_ERR_HIP;
+}
+
 dp_status dp_topk_select(const dp_problem *problem, const float *logits, int32_t k_retained, int32_t k_exact,
                          int32_t *sel_ids, int32_t *n_exact, int32_t *n_retained, int32_t *n_exact_tokens,
                          void *stream) {

@@ -83,6 +83,13 @@ hipError_t launch_decode(const CacheView &c, const int32_t *n_exact, const int32
                          float *partials, int splits, const AttnOut &attn, hipStream_t s, hipEvent_t start = nullptr,
                          hipEvent_t stop = nullptr);
 
+// A/B variants in the structure of the paper's own kernels (dp_variants.hip)
+constexpr int kSortedSelectMaxClusters = 8192;
+hipError_t launch_select_sorted(const CacheView &c, const float *logits, const SelectRule &rule, const SelectOut &out,
+                                hipStream_t s);
+hipError_t launch_gather_rows(const CacheView &c, const int32_t *n_exact, const Plan &plan, void *k_buf, void *v_buf,
+                              int rows_cap, int32_t *overflow, hipStream_t s);
+
 // Dense attention over rows [seg_row_base[seg], + seg_rows[seg]) of every segment for all its query heads.
 // partials: room for nh * max_splits * (kHeadDim + 2) floats.
 hipError_t launch_dense(const CacheView &c, const int32_t *seg_rows, float *partials, int max_splits,

@@ -33,6 +33,7 @@
 #include "dp_attend.hpp"
 #include "dp_device.hpp"
 #include "dp_kernels.hpp"
+#include "dp_mass.hpp"
 
 namespace dp {
 namespace {
@@ -40,14 +41,11 @@ namespace {
 constexpr int kSelThreads = 1024;
 constexpr int kSelWaves = kSelThreads / 64;
 constexpr int kBins = 2048;              // = 2 bins per thread in the histogram scan
-constexpr float kCut = 27.72f;           // just under 40 ln 2: beyond it the fixed-point mass is 0
 constexpr float kBinScale = (float)kBins / kCut;
 constexpr int kMaxCand = 512;            // largest bin population that is ranked pairwise
 constexpr int kInlineRows = 1024;        // heads with at most this many rows are attended in this kernel
 constexpr float kTopCut = 6.0f;          // "top set": clusters whose logit is within this of the max
 constexpr int kTopMax = 64;              // largest top set handled by the one-wave fast path
-
-typedef unsigned long long u64;
 
 #ifdef DP_PHASE_CLOCKS  // development aid: per-phase timestamps of thread 0, never built into the library
 #define DP_MARK(i) do { if (a.dbg && threadIdx.x == 0) a.dbg[blockIdx.x * 16 + (i)] = wall_clock64(); } while (0)
@@ -82,18 +80,6 @@ struct SelectArgs {
 #endif
 };
 
-// floor(w * 2^40) for 0 <= w <= 1, exactly, with 32-bit conversions only
-__device__ __forceinline__ u64 fixed40(float w) {
-  const float t = w * 256.0f;
-  const uint32_t hi = (uint32_t)t;
-  const uint32_t lo = (uint32_t)((t - (float)hi) * 4294967296.0f);
-  return ((u64)hi << 32) | lo;
-}
-
-// d = max - logit >= 0 (+inf for an empty cluster)
-__device__ __forceinline__ u64 fx_mass(float d) {
-  return d < kCut ? fixed40(__builtin_amdgcn_exp2f(-d * kLog2e)) : 0;
-}
 // level-1 bin of a cluster at distance d below the max logit; bs = bins per unit of d
 __device__ __forceinline__ int level1_bin(float d, float bs) { return (int)fminf(d * bs, (float)(kBins - 1)); }
 
@@ -431,8 +417,7 @@ __device__ __forceinline__ bool retain_all(const SelectArgs &a, u64 W) {
 template <bool kCount>
 __device__ __forceinline__ u64 first_tau(const SelectArgs &a, u64 W) {
   if (kCount) return (u64)a.k_retained < W ? (u64)a.k_retained : W;  // k_retained >= 1 here
-  const u64 t = (u64)ceil((double)a.p1 * (double)W);
-  return t < 1 ? 1 : (t > W ? W : t);
+  return top_p_first_tau(a.p1, W);
 }
 // m1: weight of the retained prefix
 template <bool kCount>
@@ -443,11 +428,7 @@ __device__ __forceinline__ int second_tau(const SelectArgs &a, u64 W, u64 m1, u6
     tau2 = (u64)a.k_exact;
     return 2;
   }
-  if (a.p2 >= 1.0f) return 1;
-  if (a.p2 <= 0.0f) return 0;
-  const u64 t = a.p2_absolute ? (u64)ceil((double)a.p2 * (double)W) : (u64)ceil((double)a.p2 * (double)m1);
-  tau2 = t < 1 ? 1 : (t > m1 ? m1 : t);
-  return 2;
+  return top_p_second_tau(a.p2, a.p2_absolute != 0, W, m1, tau2);
 }
 
 template <int E, bool kCount>

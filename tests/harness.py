@@ -56,7 +56,8 @@ def gpu_logits(cache: ClusteredCache, sm_scale: float = 0.0):
 
 
 def gpu_select(cache: ClusteredCache, flat_logits: np.ndarray, p1: float, p2: float, flags: int = 0, budget=None):
-    """budget = (k_retained, k_exact): dp_topk_select instead of dp_topp_select (p1, p2 unused)."""
+    """budget = (k_retained, k_exact): dp_topk_select instead of dp_topp_select (p1, p2 unused);
+    budget = "sorted": the sort-based A/B variant dp_topp_select_sorted."""
     import torch
     import paper_2602_05191_amd as dp
     dc = dp.DeviceCache.from_host(cache)
@@ -66,7 +67,9 @@ def gpu_select(cache: ClusteredCache, flat_logits: np.ndarray, p1: float, p2: fl
     sel = torch.full((nh, mk), -7, dtype=torch.int32, device="cuda:0")
     ne = torch.full((nh,), -7, dtype=torch.int32, device="cuda:0")
     nr, nt = ne.clone(), ne.clone()
-    if budget is None:
+    if budget == "sorted":
+        dp.dp_topp_select_sorted(pr, lg, p1, p2, sel, ne, nr, nt)
+    elif budget is None:
         dp.dp_topp_select(pr, lg, p1, p2, sel, ne, nr, nt)
     else:
         dp.dp_topk_select(pr, lg, int(budget[0]), int(budget[1]), sel, ne, nr, nt)

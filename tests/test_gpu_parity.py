@@ -581,3 +581,39 @@ def test_one_call_path_replays_from_a_hip_graph():
         dp.dp_decode_attention(pr, 0.95, 0.9, eager, eager_lse, ws)
         torch.cuda.synchronize()
         assert torch.equal(got, eager) and torch.equal(got_lse, eager_lse), rep
+
+
+# ---------------------------------------------------------------------------
+# A/B variant in the paper's own kernel structure: sort first, then prefix sums (Sec. 4.4)
+# ---------------------------------------------------------------------------
+@pytest.mark.parametrize("flags", [0, 1])
+def test_sorted_select_variant_gives_the_same_sets(case, flags):
+    """Same masses, same order, same tie-break: identical outputs to dp_topp_select, and to the oracle
+    under the same rule as dp_topp_select."""
+    import paper_2602_05191_amd as dp
+    name, cache, p1, p2, orc = case
+    if cache.max_clusters_per_seg > 8192 or cache.cluster_flags is not None:
+        with pytest.raises(dp.DPError) as e:
+            H.gpu_select(cache, H.gpu_logits(cache)[1], p1, p2, flags, budget="sorted")
+        assert e.value.status == -2
+        return
+    per_head, flat = H.gpu_logits(cache)
+    for (q1, q2) in ((p1, p2), (0.5, 0.5), (1.0, 1.0), (0.9, 0.0), (1.0, 0.6), (0.999, 0.999)):
+        ex_a, ap_a, nt_a = H.gpu_select(cache, flat, q1, q2, flags)
+        ex_b, ap_b, nt_b = H.gpu_select(cache, flat, q1, q2, flags, budget="sorted")
+        for i in range(cache.batch * cache.n_q_heads):
+            assert np.array_equal(ex_a[i], ex_b[i]) and np.array_equal(ap_a[i], ap_b[i]), (name, q1, q2, i)
+        assert np.array_equal(nt_a, nt_b)
+
+
+def test_sorted_select_variant_on_ties():
+    c = make_cache(batch=1, n_kv_heads=1, n_q_heads=2, context=3000, n_clusters=3000, size_dist="ones", size_lo=1,
+                   size_hi=1, q_scale=0.5, seed=43)
+    for start in range(0, 3000, 60):
+        c.k_centroids[start:start + 41] = c.k_centroids[start]     # runs of equal scores
+    _, flat = H.gpu_logits(c)
+    for q1, q2 in ((0.5, 0.5), (0.9, 0.8), (0.97, 0.2)):
+        ex_a, ap_a, _ = H.gpu_select(c, flat, q1, q2)
+        ex_b, ap_b, _ = H.gpu_select(c, flat, q1, q2, budget="sorted")
+        for i in range(2):
+            assert np.array_equal(ex_a[i], ex_b[i]) and np.array_equal(ap_a[i], ap_b[i])
