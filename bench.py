@@ -283,6 +283,25 @@ def main():
     dp.dp_decode_attention(pr0, p1, p2, out, lse, ws, None, None, None)
     torch.cuda.synchronize()
 
+    # ---- A/B against the kernel structure the paper describes for its own implementation (Sec. 4.4): top-p on
+    # sorted scores, and gathering the selected rows into a contiguous buffer before attending.  Same results
+    # (tested bit-identical); staged entry points, back-to-back launches over the rotating replicas. ----
+    ab = {"dp_topp_select_us": round(select_us, 3), "dp_sparse_decode_us": round(decode_us, 3)}
+    if mk <= 8192:
+        dp.dp_score_centroids(pr0, logits)
+        ab["dp_topp_select_sorted_us"] = round(time_stage(
+            lambda i: dp.dp_topp_select_sorted(probs[i % L], logits, p1, p2, sel_d, ne, nr, nt))[0], 3)
+    dp.dp_topp_select(pr0, logits, p1, p2, sel_d, ne, nr, nt)
+    torch.cuda.synchronize()
+    cap = int(nt.max().item()) + 1
+    if nh * cap * cache.head_dim * 4 <= 2 ** 34:
+        kb = torch.empty((nh, cap, cache.head_dim), dtype=torch.int16, device=dev)
+        vb = torch.empty_like(kb)
+        ab["dp_sparse_decode_gathered_us"] = round(time_stage(
+            lambda i: dp.dp_sparse_decode_gathered(probs[i % L], sel_d, ne, nr, out, lse, kb, vb, cap, ws))[0], 3)
+        ab["gather_buffer_rows_per_head"] = cap
+        del kb, vb
+
     # ---- the prefill-side build of this workload's cache (Sec. 4.1, Eq. 2): token-order K / V + cluster ids ->
     # cluster-contiguous rows, sizes, offsets, centroids.  One call per layer, not part of the decode step. ----
     from workloads import token_order_input
@@ -388,6 +407,7 @@ def main():
             "fixed_budget": {"k_retained": k_ret, "k_exact": k_ex, "entry_point": "dp_budget_decode_attention"},
             "speedup_over_fixed_budget": round(budget_us / value, 2),
         },
+        "ab_paper_kernel_structure_us": ab,
         "with_sink_and_window_pinned_us": round(pinned_us, 3),
         "prefill_build": {"entry_point": "dp_build_cluster_cache", "us": round(build_us, 1),
                           "bytes": build_bytes, "GBs": round(build_bytes / (build_us * 1e-6) / 1e9, 1)},

@@ -133,6 +133,19 @@ dp_status dp_sparse_decode(const dp_problem *problem, const int32_t *sel_ids, co
                            const int32_t *n_retained, const int32_t *n_exact_tokens, void *out, dp_dtype out_dtype,
                            float *lse, void *workspace, size_t workspace_bytes, void *stream);
 
+/* A/B variant of dp_sparse_decode in the structure the paper describes for its
+ * own kernels (Sec. 4.4): the K / V rows of every head's exact clusters are first
+ * copied into a contiguous per-head buffer (k_buf, v_buf: bf16
+ * [batch*n_q_heads, rows_cap, head_dim], device), and the weighted flash-decode
+ * then reads that buffer instead of the cache (centroid rows are still read in
+ * place; a head with more than rows_cap exact rows is not copied and is read in
+ * place).  Same arithmetic in the same order, hence the same output bits as
+ * dp_sparse_decode; it exists to time the two designs against each other. */
+dp_status dp_sparse_decode_gathered(const dp_problem *problem, const int32_t *sel_ids, const int32_t *n_exact,
+                                    const int32_t *n_retained, void *out, dp_dtype out_dtype, float *lse,
+                                    void *k_buf, void *v_buf, int32_t rows_cap, void *workspace,
+                                    size_t workspace_bytes, void *stream);
+
 /* Stages 1-3 in one call (logits and id lists live in the workspace).  n_exact,
  * n_retained, n_exact_tokens (int32 [batch*n_q_heads]) and lse are optional
  * outputs (NULL to skip). */

@@ -24,7 +24,7 @@ _LIB_PATH = os.path.join(_PKG, "libdp_hip.so")
 
 EXPORTS = ["dp_workspace_bytes", "dp_logits_count", "dp_get_workspace_layout", "dp_score_centroids",
            "dp_score_centroids_timed",
-           "dp_topp_select", "dp_topp_select_sorted", "dp_topk_select", "dp_sparse_decode", "dp_decode_attention",
+           "dp_topp_select", "dp_topp_select_sorted", "dp_topk_select", "dp_sparse_decode", "dp_sparse_decode_gathered", "dp_decode_attention",
            "dp_decode_attention_timed", "dp_budget_decode_attention", "dp_dense_decode", "dp_build_workspace_bytes", "dp_build_cluster_cache",
            "dp_status_string"]
 
@@ -96,6 +96,8 @@ def load_library():
     L.dp_decode_attention_timed.argtypes = [PP, F, F, V, I, V, V, C.c_size_t, V, C.POINTER(C.c_void_p)]
     L.dp_topp_select_sorted.restype = I
     L.dp_topp_select_sorted.argtypes = [PP, V, F, F, V, V, V, V, V]
+    L.dp_sparse_decode_gathered.restype = I
+    L.dp_sparse_decode_gathered.argtypes = [PP, V, V, V, V, I, V, V, V, I, V, C.c_size_t, V]
     L.dp_topk_select.restype = I
     L.dp_topk_select.argtypes = [PP, V, I, I, V, V, V, V, V]
     L.dp_budget_decode_attention.restype = I
@@ -352,3 +354,18 @@ def dp_topp_select_sorted(problem: Problem, logits: torch.Tensor, p1: float, p2:
     _check(load_library().dp_topp_select_sorted(problem.ref, _ptr(logits), p1, p2, _ptr(sel_ids), _ptr(n_exact),
                                                 _ptr(n_retained), _ptr(n_exact_tokens), _stream(stream)),
            "dp_topp_select_sorted")
+
+
+def dp_sparse_decode_gathered(problem: Problem, sel_ids: torch.Tensor, n_exact: torch.Tensor, n_retained: torch.Tensor,
+                              out: torch.Tensor, lse: Optional[torch.Tensor], k_buf: torch.Tensor, v_buf: torch.Tensor,
+                              rows_cap: int, workspace: torch.Tensor, stream=None) -> None:
+    """A/B variant of dp_sparse_decode (gather into contiguous buffers, then attend); same outputs."""
+    dt = {torch.float32: DP_F32, torch.bfloat16: DP_BF16}[out.dtype]
+    assert out.is_contiguous() and out.numel() == problem.nh * problem.dc.head_dim
+    for t in (k_buf, v_buf):
+        assert t.is_contiguous() and t.element_size() == 2 and t.numel() >= problem.nh * rows_cap * problem.dc.head_dim
+    _check(load_library().dp_sparse_decode_gathered(problem.ref, _ptr(sel_ids), _ptr(n_exact), _ptr(n_retained),
+                                                    _ptr(out), dt, _ptr(lse), _ptr(k_buf), _ptr(v_buf), int(rows_cap),
+                                                    _ptr(workspace), workspace.numel() * workspace.element_size(),
+                                                    _stream(stream)),
+           "dp_sparse_decode_gathered")

@@ -294,6 +294,29 @@ dp_status dp_sparse_decode(const dp_problem *problem, const int32_t *sel_ids, co
   return DP_OK;
 }
 
+dp_status dp_sparse_decode_gathered(const dp_problem *problem, const int32_t *sel_ids, const int32_t *n_exact,
+                                    const int32_t *n_retained, void *out, dp_dtype out_dtype, float *lse,
+                                    void *k_buf, void *v_buf, int32_t rows_cap, void *workspace,
+                                    size_t workspace_bytes, void *stream) {
+  dp_status st = check_common(problem);
+  if (st != DP_OK) return st;
+  if (out_dtype != DP_BF16 && out_dtype != DP_F32) return DP_ERR_UNSUPPORTED;
+  if (!n_exact || !n_retained || !out || !workspace || !k_buf || !v_buf || rows_cap <= 0) return DP_ERR_INVALID_ARG;
+  if (problem->max_clusters_per_seg > 0 && !sel_ids) return DP_ERR_INVALID_ARG;
+  if (workspace_bytes < dp_workspace_bytes(problem)) return DP_ERR_WORKSPACE_TOO_SMALL;
+  if (reinterpret_cast<uintptr_t>(workspace) % 256) return DP_ERR_INVALID_ARG;
+  const dp::CacheView c = view_of(problem);
+  const Workspace w = carve(problem, workspace);
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  const dp::AttnOut attn{out, lse, out_dtype == DP_BF16};
+  if (dp::launch_plan(c, sel_ids, n_exact, n_retained, nullptr, w.plan, attn, s) != hipSuccess) return DP_ERR_HIP;
+  if (dp::launch_gather_rows(c, n_exact, w.plan, k_buf, v_buf, rows_cap, s) != hipSuccess) return DP_ERR_HIP;
+  if (dp::launch_decode(c, n_exact, n_retained, w.plan, w.partials, w.splits, attn, s, nullptr, nullptr, k_buf, v_buf,
+                        rows_cap) != hipSuccess)
+    return DP_ERR_HIP;
+  return DP_OK;
+}
+
 dp_status dp_decode_attention(const dp_problem *problem, float p1, float p2, void *out, dp_dtype out_dtype,
                               float *lse, int32_t *n_exact, int32_t *n_retained, int32_t *n_exact_tokens,
                               void *workspace, size_t workspace_bytes, void *stream) {

@@ -36,6 +36,9 @@ struct RowSources {
   const int32_t *seg_sizes;  // cluster_sizes + c0 of the head's segment
   int64_t seg_row0;          // first cache row of the segment
   int64_t c0;                // first centroid row of the segment
+  // A/B variant only (kGathered): the head's exact rows copied to a contiguous buffer, list row r at gather_row0 + r
+  const void *k_gather, *v_gather;
+  int64_t gather_row0;
 };
 
 // Attend rows ra, ra+1, .., ra+B-1, then ra+stride .. (B = kAttendBatch rows per step), below rb.  s_start[0 .. n_ent] and s_src[0 .. n_ent)
@@ -43,6 +46,7 @@ struct RowSources {
 // cover [ra, rb) (s_start[0] <= ra).  Every lane of the group runs the same
 // entry walk (uniform inside the group), so nothing is exchanged between lanes
 // except the DPP sum of the dot product.
+template <bool kGathered = false>
 __device__ __forceinline__ void attend_rows(RowState &st, const uint4 &qv, float scale_log2, const RowSources &src,
                                             const int *s_start, const int *s_src, int n_ent, int ent0, int n_ex,
                                             int ra, int rb, int stride, int lane16) {
@@ -79,8 +83,13 @@ __device__ __forceinline__ void attend_rows(RowState &st, const uint4 &qv, float
 #else
           const int64_t g = src.seg_row0 + s + (row - s_start[k]);
 #endif
-          kraw[u] = load_row_slice(src.k_cache, g, lane16);
-          vraw[u] = load_row_slice(src.v_cache, g, lane16);
+          if (kGathered) {
+            kraw[u] = load_row_slice(src.k_gather, src.gather_row0 + row, lane16);
+            vraw[u] = load_row_slice(src.v_gather, src.gather_row0 + row, lane16);
+          } else {
+            kraw[u] = load_row_slice(src.k_cache, g, lane16);
+            vraw[u] = load_row_slice(src.v_cache, g, lane16);
+          }
         } else {
           approx[u] = true;
           ssz[u] = src.seg_sizes[s];

@@ -63,6 +63,9 @@ struct DecodeArgs {
   int32_t n_kv_heads, n_q_heads, group, max_k, splits, out_is_bf16;
   int32_t head0, n_heads;  // this launch serves heads [head0, head0 + n_heads), n_heads <= kMaxQueueHeads
   int32_t *queue_next;     // the launch's item counter (zeroed by the planner)
+  // A/B variant (decode_kernel<true>): per-head buffers that hold the gathered exact rows of heads with at most rows_cap of them
+  const void *k_gather, *v_gather;
+  int32_t rows_cap;
   float scale_log2;        // sm_scale * log2(e)
 #ifdef DP_PHASE_CLOCKS
   unsigned long long *dbg;
@@ -75,6 +78,7 @@ __device__ __forceinline__ int rows_per_item(int R, int S, int g) {
 }
 
 // One (head, split) item: attend its rows, publish the partial, and merge the head if this item arrives last.
+template <bool kGathered>
 __device__ __forceinline__ void decode_item(const DecodeArgs &a, int head, int split, int R, int g, int *s_start, int *s_src,
                                             float *s_m, float *s_l, float (*s_acc)[kHeadDim], int *s_last, int tid,
                                             int lane16, int grp) {
@@ -101,6 +105,15 @@ __device__ __forceinline__ void decode_item(const DecodeArgs &a, int head, int s
   src.seg_sizes = a.cluster_sizes + c0;
   src.seg_row0 = a.seg_row_base[seg];
   src.c0 = c0;
+  src.k_gather = src.v_gather = nullptr;
+  src.gather_row0 = 0;
+  // a head whose exact rows did not fit the buffer was not gathered: it is read in place
+  const bool use_gather = kGathered && n_ex > 0 && row_start[n_ex] <= a.rows_cap;
+  if (use_gather) {
+    src.k_gather = a.k_gather;
+    src.v_gather = a.v_gather;
+    src.gather_row0 = (int64_t)head * a.rows_cap;
+  }
 
   RowState st;
   row_state_init(st);
@@ -144,11 +157,15 @@ __device__ __forceinline__ void decode_item(const DecodeArgs &a, int head, int s
     const int per = kAttendBatch * ((r1 - r0 + kDecGroups * kAttendBatch - 1) / (kDecGroups * kAttendBatch));
     const int ra = r0 + grp * per;
     attend_rows(st, qv, a.scale_log2, src, s_start, s_src, n_ent, ent0, n_ex, ra, min(r1, ra + per), kAttendBatch,
-                lane16);
+                lane16);  // (the contiguous development variant always reads in place)
 #else
     // the 16 DPP-row groups take consecutive 4-row pieces: one step of the workgroup reads 64 consecutive rows
-    attend_rows(st, qv, a.scale_log2, src, s_start, s_src, n_ent, ent0, n_ex, r0 + grp * kAttendBatch, r1,
-                kDecGroups * kAttendBatch, lane16);
+    if (use_gather)
+      attend_rows<true>(st, qv, a.scale_log2, src, s_start, s_src, n_ent, ent0, n_ex, r0 + grp * kAttendBatch, r1,
+                        kDecGroups * kAttendBatch, lane16);
+    else
+      attend_rows<false>(st, qv, a.scale_log2, src, s_start, s_src, n_ent, ent0, n_ex, r0 + grp * kAttendBatch, r1,
+                         kDecGroups * kAttendBatch, lane16);
 #endif
     // first entry of the next block: the entry that holds row r1
     if (r1 < row_b) {
@@ -225,6 +242,7 @@ __device__ __forceinline__ void decode_item(const DecodeArgs &a, int head, int s
   }
 }
 
+template <bool kGathered>
 __global__ __launch_bounds__(kDecThreads) void decode_kernel(DecodeArgs a) {
   __shared__ int s_start[kDecBlockRows + 1];
   __shared__ int s_src[kDecBlockRows + 1];
@@ -283,7 +301,7 @@ __global__ __launch_bounds__(kDecThreads) void decode_kernel(DecodeArgs a) {
       if (s_first[mid] <= item) lo = mid; else hi = mid;
     }
     const int head = a.head0 + lo, split = item - s_first[lo];
-    decode_item(a, head, split, s_rows[lo], g, s_start, s_src, s_m, s_l, s_acc, &s_last, tid, lane16, grp);
+    decode_item<kGathered>(a, head, split, s_rows[lo], g, s_start, s_src, s_m, s_l, s_acc, &s_last, tid, lane16, grp);
     if (total <= (int)gridDim.x) break;  // every item had its workgroup: nothing to claim
     if (tid == 0)
       s_item = gridDim.x + __hip_atomic_fetch_add(a.queue_next, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -304,7 +322,7 @@ extern "C" void dp_debug_set_decode_clock_buffer(void *p) { g_decode_clock_buffe
 
 hipError_t launch_decode(const CacheView &c, const int32_t *n_exact, const int32_t *n_retained, const Plan &plan,
                          float *partials, int splits, const AttnOut &attn, hipStream_t s, hipEvent_t start,
-                         hipEvent_t stop) {
+                         hipEvent_t stop, const void *k_gather, const void *v_gather, int rows_cap) {
   const int nh = c.batch * c.n_q_heads;
   if (nh == 0) return hipSuccess;
   DecodeArgs a;
@@ -329,6 +347,9 @@ hipError_t launch_decode(const CacheView &c, const int32_t *n_exact, const int32
   a.max_k = c.max_clusters_per_seg;
   a.splits = splits;
   a.scale_log2 = c.sm_scale * kLog2e;
+  a.k_gather = k_gather;
+  a.v_gather = v_gather;
+  a.rows_cap = rows_cap;
 #ifdef DP_PHASE_CLOCKS
   a.dbg = g_decode_clock_buffer;
 #endif
@@ -341,10 +362,12 @@ hipError_t launch_decode(const CacheView &c, const int32_t *n_exact, const int32
     const int grid = (int)(max_items < kDecodeGrid ? max_items : kDecodeGrid);
     // measurement: the events bracket the first slab's begin and the last slab's end
     hipEvent_t ev0 = (h0 == 0) ? start : nullptr, ev1 = (h0 + kMaxQueueHeads >= nh) ? stop : nullptr;
-    if (ev0 || ev1)
-      hipExtLaunchKernelGGL(decode_kernel, dim3(grid), dim3(kDecThreads), 0, s, ev0, ev1, 0, a);
+    if (k_gather)
+      hipLaunchKernelGGL(decode_kernel<true>, dim3(grid), dim3(kDecThreads), 0, s, a);
+    else if (ev0 || ev1)
+      hipExtLaunchKernelGGL(decode_kernel<false>, dim3(grid), dim3(kDecThreads), 0, s, ev0, ev1, 0, a);
     else
-      hipLaunchKernelGGL(decode_kernel, dim3(grid), dim3(kDecThreads), 0, s, a);
+      hipLaunchKernelGGL(decode_kernel<false>, dim3(grid), dim3(kDecThreads), 0, s, a);
   }
   return hipGetLastError();
 }

@@ -81,14 +81,15 @@ hipError_t launch_plan(const CacheView &c, const int32_t *sel_ids, const int32_t
 
 hipError_t launch_decode(const CacheView &c, const int32_t *n_exact, const int32_t *n_retained, const Plan &plan,
                          float *partials, int splits, const AttnOut &attn, hipStream_t s, hipEvent_t start = nullptr,
-                         hipEvent_t stop = nullptr);
+                         hipEvent_t stop = nullptr, const void *k_gather = nullptr, const void *v_gather = nullptr,
+                         int rows_cap = 0);
 
 // A/B variants in the structure of the paper's own kernels (dp_variants.hip)
 constexpr int kSortedSelectMaxClusters = 8192;
 hipError_t launch_select_sorted(const CacheView &c, const float *logits, const SelectRule &rule, const SelectOut &out,
                                 hipStream_t s);
 hipError_t launch_gather_rows(const CacheView &c, const int32_t *n_exact, const Plan &plan, void *k_buf, void *v_buf,
-                              int rows_cap, int32_t *overflow, hipStream_t s);
+                              int rows_cap, hipStream_t s);
 
 // Dense attention over rows [seg_row_base[seg], + seg_rows[seg]) of every segment for all its query heads.
 // partials: room for nh * max_splits * (kHeadDim + 2) floats.

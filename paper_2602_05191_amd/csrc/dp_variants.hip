@@ -185,7 +185,6 @@ struct GatherArgs {
   Plan plan;
   void *k_buf, *v_buf;  // [nh, rows_cap, 128] bf16
   int32_t n_kv_heads, n_q_heads, group, max_k, rows_cap;
-  int32_t *overflow;    // set to 1 when a head has more exact rows than the buffer holds
 };
 
 __global__ __launch_bounds__(256) void gather_rows_kernel(GatherArgs a) {
@@ -196,10 +195,7 @@ __global__ __launch_bounds__(256) void gather_rows_kernel(GatherArgs a) {
   const int32_t *ent_src = a.plan.ent_src + (int64_t)head * a.max_k;
   const int32_t *row_start = a.plan.row_start + (int64_t)head * (a.max_k + 1);
   const int rows = n_ex > 0 ? row_start[n_ex] : 0;  // exact rows come first in the list
-  if (rows > a.rows_cap) {
-    if (threadIdx.x == 0 && blockIdx.x == 0) *a.overflow = 1;
-    return;
-  }
+  if (rows > a.rows_cap) return;  // does not fit: the decode kernel reads this head in place
   const int r0 = blockIdx.x * kChunkRows;
   if (r0 >= rows) return;
   const int lane16 = threadIdx.x & 15, grp = threadIdx.x >> 4;
@@ -243,7 +239,7 @@ hipError_t launch_select_sorted(const CacheView &c, const float *logits, const S
 }
 
 hipError_t launch_gather_rows(const CacheView &c, const int32_t *n_exact, const Plan &plan, void *k_buf, void *v_buf,
-                              int rows_cap, int32_t *overflow, hipStream_t s) {
+                              int rows_cap, hipStream_t s) {
   const int nh = c.batch * c.n_q_heads;
   if (nh == 0 || rows_cap <= 0) return hipSuccess;
   GatherArgs a;
@@ -259,7 +255,6 @@ hipError_t launch_gather_rows(const CacheView &c, const int32_t *n_exact, const 
   a.group = c.group;
   a.max_k = c.max_clusters_per_seg;
   a.rows_cap = rows_cap;
-  a.overflow = overflow;
   hipLaunchKernelGGL(gather_rows_kernel, dim3((rows_cap + kChunkRows - 1) / kChunkRows, nh), dim3(256), 0, s, a);
   return hipGetLastError();
 }

@@ -617,3 +617,40 @@ def test_sorted_select_variant_on_ties():
         ex_b, ap_b, _ = H.gpu_select(c, flat, q1, q2, budget="sorted")
         for i in range(2):
             assert np.array_equal(ex_a[i], ex_b[i]) and np.array_equal(ap_a[i], ap_b[i])
+
+
+@pytest.mark.parametrize("rows_cap", [64, 700, 100000])
+def test_gathered_decode_variant_gives_the_same_bits(case, rows_cap):
+    """Copying the exact rows into a contiguous per-head buffer first changes where the rows are read from,
+    not what is computed: the output must equal dp_sparse_decode's bit for bit (heads that do not fit the
+    buffer are read in place)."""
+    import torch
+    import paper_2602_05191_amd as dp
+    name, cache, p1, p2, orc = case
+    r = orc.decode_step(p1, p2)
+    nh, mk = cache.batch * cache.n_q_heads, max(cache.max_clusters_per_seg, 1)
+    sel = np.full((nh, mk), -1, dtype=np.int32)
+    ne, nr = np.zeros(nh, np.int32), np.zeros(nh, np.int32)
+    most = 0
+    for i in range(nh):
+        b, h = divmod(i, cache.n_q_heads)
+        ex = np.sort(np.concatenate([orc.pinned_clusters(b, h), r.order[i, : r.k2.flat[i]]]))
+        ap = np.sort(r.order[i, r.k2.flat[i]: r.k1.flat[i]])
+        ne[i], nr[i] = len(ex), len(ex) + len(ap)
+        sel[i, :ne[i]], sel[i, ne[i]:nr[i]] = ex, ap
+        c0 = int(cache.seg_cluster_ptr[b * cache.n_kv_heads + h // cache.group])
+        most = max(most, int(cache.cluster_sizes[c0 + ex].sum()))
+    cap = min(rows_cap, max(most, 1) + 5)
+    dc = dp.DeviceCache.from_host(cache)
+    pr = dp.Problem(dc)
+    ws = torch.zeros(max(dp.dp_workspace_bytes(pr), 256), dtype=torch.uint8, device="cuda:0")
+    sel_d, ne_d, nr_d = torch.from_numpy(sel).cuda(), torch.from_numpy(ne).cuda(), torch.from_numpy(nr).cuda()
+    a = torch.full((cache.batch, cache.n_q_heads, 128), float("nan"), dtype=torch.float32, device="cuda:0")
+    b_ = a.clone()
+    la, lb = torch.zeros(nh, dtype=torch.float32, device="cuda:0"), torch.zeros(nh, dtype=torch.float32, device="cuda:0")
+    kb = torch.zeros((nh, cap, 128), dtype=torch.int16, device="cuda:0")
+    vb = torch.zeros_like(kb)
+    dp.dp_sparse_decode(pr, sel_d, ne_d, nr_d, a, la, ws)
+    dp.dp_sparse_decode_gathered(pr, sel_d, ne_d, nr_d, b_, lb, kb, vb, cap, ws)
+    torch.cuda.synchronize()
+    assert torch.equal(a, b_) and torch.equal(la, lb), (name, rows_cap)
