@@ -78,11 +78,7 @@ __device__ __forceinline__ void attend_rows(RowState &st, const uint4 &qv, float
         }
         const int s = s_src[k];
         if (ent0 + k < n_ex) {
-#ifdef DP_LAB_RANDOM_ROWS  // development aid: 32-row chunks at pseudo-random places of the segment
-          const int64_t g = src.seg_row0 + (int64_t)((((uint32_t)(row >> 5) + (uint32_t)src.c0 * 977u) * 2654435761u) >> 20) * 32 + (row & 31);
-#else
           const int64_t g = src.seg_row0 + s + (row - s_start[k]);
-#endif
           if (kGathered) {
             kraw[u] = load_row_slice(src.k_gather, src.gather_row0 + row, lane16);
             vraw[u] = load_row_slice(src.v_gather, src.gather_row0 + row, lane16);
@@ -101,16 +97,6 @@ __device__ __forceinline__ void attend_rows(RowState &st, const uint4 &qv, float
         vraw[u] = make_uint4(0, 0, 0, 0);
       }
     }
-#ifdef DP_LAB_NOCOMPUTE  // development aid: loads only
-    {
-      uint32_t acc = 0;
-#pragma unroll
-      for (int u = 0; u < kAttendBatch; ++u) acc += (kraw[u].x ^ kraw[u].y) + (kraw[u].z ^ kraw[u].w) + (vraw[u].x ^ vraw[u].y) + (vraw[u].z ^ vraw[u].w) + ssz[u];
-      st.l += __uint_as_float(acc & 0x3fffff);
-      st.m = 0.f;
-      continue;
-    }
-#endif
     float x[kAttendBatch];
     float m_new = st.m;
 #pragma unroll

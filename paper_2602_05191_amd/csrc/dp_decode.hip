@@ -45,10 +45,8 @@ constexpr int kMinItemChunks = DP_MIN_ITEM_CHUNKS;  // items of a heavy launch h
 
 #ifdef DP_PHASE_CLOCKS  // development aid, never built into the library
 #define DD_MARK(i) do { if (a.dbg && threadIdx.x == 0 && blockIdx.x < 2048) a.dbg[blockIdx.x * 16 + (i)] = wall_clock64(); } while (0)
-#define DD_COUNT() do { if (a.dbg && threadIdx.x == 0 && blockIdx.x < 2048) a.dbg[blockIdx.x * 16 + 8] += 1; } while (0)
 #else
 #define DD_MARK(i) do { } while (0)
-#define DD_COUNT() do { } while (0)
 #endif
 
 struct DecodeArgs {
@@ -118,26 +116,6 @@ __device__ __forceinline__ void decode_item(const DecodeArgs &a, int head, int s
   RowState st;
   row_state_init(st);
 
-#ifdef DP_LAB_PURE  // development aid: lab-style loop, pseudo-random 32-row chunks, loads only
-  {
-    uint32_t accx = 0;
-    for (int r = row_a + grp * 32; r < row_b; r += 512) {
-      const int64_t g0 = src.seg_row0 + (int64_t)((((uint32_t)(r >> 5) + (uint32_t)head * 977u) * 2654435761u) >> 20) * 32;
-      for (int rr = 0; rr < 32; rr += 4) {
-        uint4 ka[4], va[4];
-#pragma unroll
-        for (int u = 0; u < 4; ++u) {
-          ka[u] = load_row_slice(a.k_cache, g0 + rr + u, lane16);
-          va[u] = load_row_slice(a.v_cache, g0 + rr + u, lane16);
-        }
-#pragma unroll
-        for (int u = 0; u < 4; ++u) accx += (ka[u].x ^ ka[u].y) + (ka[u].z ^ ka[u].w) + (va[u].x ^ va[u].y) + (va[u].z ^ va[u].w);
-      }
-    }
-    st.m = 0.f;
-    st.l = 1.f + __uint_as_float(accx & 0x3fffff);
-  }
-#else
   int ent0 = a.plan.chunk_entry[(int64_t)head * a.plan.chunk_stride + row_a / kChunkRows];
 
   DD_MARK(2);
@@ -152,13 +130,6 @@ __device__ __forceinline__ void decode_item(const DecodeArgs &a, int head, int s
     }
     __syncthreads();
     DD_MARK(3);
-#ifdef DP_DECODE_CONTIGUOUS
-    // each DPP-row group streams a contiguous run of the block's rows
-    const int per = kAttendBatch * ((r1 - r0 + kDecGroups * kAttendBatch - 1) / (kDecGroups * kAttendBatch));
-    const int ra = r0 + grp * per;
-    attend_rows(st, qv, a.scale_log2, src, s_start, s_src, n_ent, ent0, n_ex, ra, min(r1, ra + per), kAttendBatch,
-                lane16);  // (the contiguous development variant always reads in place)
-#else
     // the 16 DPP-row groups take consecutive 4-row pieces: one step of the workgroup reads 64 consecutive rows
     if (use_gather)
       attend_rows<true>(st, qv, a.scale_log2, src, s_start, s_src, n_ent, ent0, n_ex, r0 + grp * kAttendBatch, r1,
@@ -166,7 +137,6 @@ __device__ __forceinline__ void decode_item(const DecodeArgs &a, int head, int s
     else
       attend_rows<false>(st, qv, a.scale_log2, src, s_start, s_src, n_ent, ent0, n_ex, r0 + grp * kAttendBatch, r1,
                          kDecGroups * kAttendBatch, lane16);
-#endif
     // first entry of the next block: the entry that holds row r1
     if (r1 < row_b) {
       int lo = 0, hi = n_ent + 1;  // s_start[n_ent] is staged as well
@@ -178,7 +148,6 @@ __device__ __forceinline__ void decode_item(const DecodeArgs &a, int head, int s
     }
   }
 
-#endif
   DD_MARK(4);
   float M, L, o;
   block_merge<kDecWaves>(st, s_m, s_l, s_acc, kDecWaves, M, L, o);
@@ -309,7 +278,6 @@ __global__ __launch_bounds__(kDecThreads) void decode_kernel(DecodeArgs a) {
     item = s_item;
     __syncthreads();
     DD_MARK(7);
-    DD_COUNT();
   }
 }
 

@@ -492,11 +492,7 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(SelectArgs a) {
   const int64_t seg_row0 = can_inline ? a.seg_row_base[seg] : 0;  // needed last; its latency hides here
   // With few logits per thread, sizes and offsets are fetched up front next to the logits, so that no
   // dependent load sits between the selection and the first K/V row.
-#ifdef DP_NO_PRELOAD
-  constexpr bool kPre = false;
-#else
   constexpr bool kPre = E <= 8;
-#endif
   constexpr int EP = kPre ? E : 1;
   int psz[EP], poff[EP];
   if (kPre) {
