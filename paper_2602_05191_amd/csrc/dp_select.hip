@@ -38,8 +38,8 @@
 namespace dp {
 namespace {
 
-constexpr int kSelThreads = 1024;
-constexpr int kSelWaves = kSelThreads / 64;
+constexpr int kSelThreads = 1024;             // largest workgroup; a launch with more heads than CUs uses 512
+constexpr int kSelWaves = kSelThreads / 64;   // LDS scratch is sized for the largest workgroup
 constexpr int kBins = 2048;              // = 2 bins per thread in the histogram scan
 constexpr float kBinScale = (float)kBins / kCut;
 constexpr int kMaxCand = 512;            // largest bin population that is ranked pairwise
@@ -123,6 +123,7 @@ struct Shared {
 };
 
 // count / min key / max key over the block
+template <int T>
 __device__ __forceinline__ void reduce_members(int cnt, uint32_t lo, uint32_t hi, Shared &sh, int &cnt_o,
                                                uint32_t &lo_o, uint32_t &hi_o) {
 #pragma unroll
@@ -140,7 +141,7 @@ __device__ __forceinline__ void reduce_members(int cnt, uint32_t lo, uint32_t hi
   int c = 0;
   uint32_t l = 0xffffffffu, h = 0;
 #pragma unroll
-  for (int w = 0; w < kSelWaves; ++w) {
+  for (int w = 0; w < (T / 64); ++w) {
     c += sh.red_cnt[w];
     l = min(l, sh.red_lo[w]);
     h = max(h, sh.red_hi[w]);
@@ -163,7 +164,7 @@ struct Refined {
   int cnt;
   bool done;
 };
-template <int E, bool kCount>
+template <int E, bool kCount, int T>
 __device__ __forceinline__ Refined refine_or_cut_ties(const float *lg, int kc, float mx, float bs, int base, int bin1,
                                                       u64 tau, u64 before, Shared *shp) {
   Shared &sh = *shp;
@@ -184,11 +185,11 @@ __device__ __forceinline__ Refined refine_or_cut_ties(const float *lg, int kc, f
         hi = max(hi, k);
       }
     }
-    reduce_members(c, lo, hi, sh, cnt, klo, khi);
+    reduce_members<T>(c, lo, hi, sh, cnt, klo, khi);
   }
 #pragma unroll 1
   while (cnt > kMaxCand && klo != khi) {
-    for (int i = tid; i < kBins; i += kSelThreads) sh.hist2[i] = 0;
+    for (int i = tid; i < kBins; i += T) sh.hist2[i] = 0;
     __syncthreads();
     // 2048-way split of the key range by a shift: monotone in the key, no division
     const int shift = max(0, 32 - __clz(khi - klo) - 11);
@@ -203,16 +204,23 @@ __device__ __forceinline__ Refined refine_or_cut_ties(const float *lg, int kc, f
     }
     __syncthreads();
     {
-      const u64 h0 = sh.hist2[2 * tid], h1 = sh.hist2[2 * tid + 1];
+      constexpr int B = kBins / T;  // consecutive bins per thread
+      u64 hb[B], sum = 0;
+#pragma unroll
+      for (int q = 0; q < B; ++q) {
+        hb[q] = sh.hist2[B * tid + q];
+        sum += hb[q];
+      }
       u64 tot;
-      const u64 ex = block_excl_scan<u64, kSelWaves>(h0 + h1, sh.scr64, tot);
+      u64 run = block_excl_scan<u64, (T / 64)>(sum, sh.scr64, tot);
       const u64 t2 = tau - before;
-      if (ex < t2 && t2 <= ex + h0) {
-        sh.bin = 2 * tid;
-        sh.before = ex;
-      } else if (ex + h0 < t2 && t2 <= ex + h0 + h1) {
-        sh.bin = 2 * tid + 1;
-        sh.before = ex + h0;
+#pragma unroll
+      for (int q = 0; q < B; ++q) {
+        if (run < t2 && t2 <= run + hb[q]) {
+          sh.bin = B * tid + q;
+          sh.before = run;
+        }
+        run += hb[q];
       }
       __syncthreads();
     }
@@ -230,7 +238,7 @@ __device__ __forceinline__ Refined refine_or_cut_ties(const float *lg, int kc, f
         hi = max(hi, k);
       }
     }
-    reduce_members(c, lo, hi, sh, cnt, klo, khi);
+    reduce_members<T>(c, lo, hi, sh, cnt, klo, khi);
   }
   if (cnt <= kMaxCand) return Refined{before, klo, khi, cnt, false};
 
@@ -254,11 +262,11 @@ __device__ __forceinline__ Refined refine_or_cut_ties(const float *lg, int kc, f
   __syncthreads();
   u64 m_tie = 0;
 #pragma unroll
-  for (int w = 0; w < kSelWaves; ++w) m_tie = sh.scr64[w] > m_tie ? sh.scr64[w] : m_tie;
+  for (int w = 0; w < (T / 64); ++w) m_tie = sh.scr64[w] > m_tie ? sh.scr64[w] : m_tie;
   __syncthreads();
   const u64 need = (tau - before + m_tie - 1) / m_tie;  // ties taken, 1 <= need <= cnt
   int tot;
-  const int ex = block_excl_scan<int, kSelWaves>(c, sh.scri, tot);
+  const int ex = block_excl_scan<int, (T / 64)>(c, sh.scri, tot);
   if ((u64)ex < need && need <= (u64)(ex + c)) {
     int seen = ex;
 #pragma unroll 1
@@ -279,21 +287,25 @@ __device__ __forceinline__ Refined refine_or_cut_ties(const float *lg, int kc, f
 }
 
 // Last element (key, index) of the shortest prefix of the order whose mass reaches tau
-// (1 <= tau <= total mass) and that prefix's mass.  ex/h0/h1: this thread's exclusive
-// prefix and its two bins of the level-1 histogram.  `slot` picks the candidate counter.
+// (1 <= tau <= total mass) and that prefix's mass.  ex/hb: this thread's exclusive
+// prefix and its consecutive bins of the level-1 histogram.  `slot` picks the candidate counter.
 // cached_*: the bin whose members are currently gathered in sh.cand_* (reused when the
 // second threshold falls into the same bin).  Block-uniform control flow.
-template <int E, bool kCount>
-__device__ __forceinline__ void find_prefix(const float (&l)[E], const float *lg, int kc, float mx, float bs, int base, u64 tau, u64 ex, u64 h0, u64 h1,
-                                            int slot, Shared &sh, int &cached_bin, int &cached_cnt,
+template <int E, bool kCount, int T>
+__device__ __forceinline__ void find_prefix(const float (&l)[E], const float *lg, int kc, float mx, float bs, int base, u64 tau, u64 ex,
+                                            const u64 (&hb)[kBins / T], int slot, Shared &sh, int &cached_bin, int &cached_cnt,
                                             u64 &cached_before, uint32_t &key_o, int &idx_o, u64 &mass_o) {
   const int tid = threadIdx.x;
-  if (ex < tau && tau <= ex + h0) {
-    sh.bin = 2 * tid;
-    sh.before = ex;
-  } else if (ex + h0 < tau && tau <= ex + h0 + h1) {
-    sh.bin = 2 * tid + 1;
-    sh.before = ex + h0;
+  {
+    u64 run = ex;
+#pragma unroll
+    for (int q = 0; q < kBins / T; ++q) {
+      if (run < tau && tau <= run + hb[q]) {
+        sh.bin = (kBins / T) * tid + q;
+        sh.before = run;
+      }
+      run += hb[q];
+    }
   }
   __syncthreads();
   const int bin1 = sh.bin;
@@ -327,7 +339,7 @@ __device__ __forceinline__ void find_prefix(const float (&l)[E], const float *lg
     cached_before = before;
     if (cnt > kMaxCand) {
       cached_bin = -1;  // the candidate arrays will not hold this bin
-      const Refined rf = refine_or_cut_ties<E, kCount>(lg, kc, mx, bs, base, bin1, tau, before, &sh);
+      const Refined rf = refine_or_cut_ties<E, kCount, T>(lg, kc, mx, bs, base, bin1, tau, before, &sh);
       const uint32_t klo = rf.klo, khi = rf.khi;
       before = rf.before;
       cnt = rf.cnt;
@@ -431,8 +443,8 @@ __device__ __forceinline__ int second_tau(const SelectArgs &a, u64 W, u64 m1, u6
   return top_p_second_tau(a.p2, a.p2_absolute != 0, W, m1, tau2);
 }
 
-template <int E, bool kCount>
-__global__ __launch_bounds__(kSelThreads) void select_kernel(SelectArgs a) {
+template <int E, bool kCount, int T>
+__global__ __launch_bounds__(T) void select_kernel(SelectArgs a) {
   __shared__ Shared sh;
   const int head = blockIdx.x;
   const int b = head / a.n_q_heads, h = head % a.n_q_heads;
@@ -545,7 +557,7 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(SelectArgs a) {
         l[e] = -INFINITY;
       }
   }
-  for (int i = tid; i < kBins; i += kSelThreads) sh.hist[i] = 0;
+  for (int i = tid; i < kBins; i += T) sh.hist[i] = 0;
   if (tid < 2) sh.ncand[tid] = 0;
   if (tid == 2) sh.ntop = 0;
   float tmax = -INFINITY;
@@ -554,7 +566,7 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(SelectArgs a) {
     l[e] += 0.0f;  // -0 becomes +0
     tmax = fmaxf(tmax, l[e]);
   }
-  const float mx_raw = block_max<kSelWaves>(tmax, sh.scrf);  // its barriers also publish the zeroed LDS
+  const float mx_raw = block_max<(T / 64)>(tmax, sh.scrf);  // its barriers also publish the zeroed LDS
 
   DP_MARK(1);
   // no candidate cluster, or a budget of 0: the distribution selects nothing
@@ -583,7 +595,7 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(SelectArgs a) {
     float tmin = INFINITY;
 #pragma unroll
     for (int e = 0; e < E; ++e) tmin = fminf(tmin, l[e] == -INFINITY ? INFINITY : l[e]);
-    const float mn = -block_max<kSelWaves>(-tmin, sh.scrf);
+    const float mn = -block_max<(T / 64)>(-tmin, sh.scrf);
     bs = mx > mn ? ((float)kBins - 0.5f) / (mx - mn) : 0.f;
   }
 
@@ -619,7 +631,7 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(SelectArgs a) {
     Wtop = 0;
     ntop = 0;
 #pragma unroll
-    for (int w = 0; w < kSelWaves; ++w) {
+    for (int w = 0; w < (T / 64); ++w) {
       W += sh.scr64[w];
       Wtop += sh.scr64b[w];
       ntop += sh.scri[w];
@@ -729,9 +741,15 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(SelectArgs a) {
       }
       __syncthreads();
       DP_MARK(8);
-      const u64 h0 = sh.hist[2 * tid], h1 = sh.hist[2 * tid + 1];
+      constexpr int B = kBins / T;  // consecutive bins per thread
+      u64 hb[B], hsum = 0;
+#pragma unroll
+      for (int q = 0; q < B; ++q) {
+        hb[q] = sh.hist[B * tid + q];
+        hsum += hb[q];
+      }
       u64 Wh;  // equals W: the same masses, summed in another order
-      const u64 ex = block_excl_scan<u64, kSelWaves>(h0 + h1, sh.scr64, Wh);
+      const u64 ex = block_excl_scan<u64, (T / 64)>(hsum, sh.scr64, Wh);
       DP_MARK(9);
 
       u64 mass1;
@@ -742,7 +760,7 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(SelectArgs a) {
         idx1 = INT_MAX;
         mass1 = W;
       } else {
-        find_prefix<E, kCount>(l, lg, kc, mx, bs, base, first_tau<kCount>(a, W), ex, h0, h1, 0, sh, cached_bin, cached_cnt,
+        find_prefix<E, kCount, T>(l, lg, kc, mx, bs, base, first_tau<kCount>(a, W), ex, hb, 0, sh, cached_bin, cached_cnt,
                                cached_before, key1, idx1, mass1);
       }
       DP_MARK(10);
@@ -757,7 +775,7 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(SelectArgs a) {
       } else {
         u64 mass2;
         __syncthreads();  // sh.bin / sh.res_* of the first search have been read by every thread
-        find_prefix<E, kCount>(l, lg, kc, mx, bs, base, tau2, ex, h0, h1, 1, sh, cached_bin, cached_cnt, cached_before, key2, idx2,
+        find_prefix<E, kCount, T>(l, lg, kc, mx, bs, base, tau2, ex, hb, 1, sh, cached_bin, cached_cnt, cached_before, key2, idx2,
                                mass2);
       }
 
@@ -796,15 +814,15 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(SelectArgs a) {
       }
       if (lane == 63) {
         sh.scri[w] = ie;
-        sh.scri[kSelWaves + w] = ia;
-        sh.scri[2 * kSelWaves + w] = it;
+        sh.scri[(T / 64) + w] = ia;
+        sh.scri[2 * (T / 64) + w] = it;
       }
       __syncthreads();
       int be = 0, ba = 0, bt = 0;
       n_ex = n_ap = n_tok = 0;
 #pragma unroll
-      for (int v = 0; v < kSelWaves; ++v) {
-        const int se = sh.scri[v], sa = sh.scri[kSelWaves + v], st = sh.scri[2 * kSelWaves + v];
+      for (int v = 0; v < (T / 64); ++v) {
+        const int se = sh.scri[v], sa = sh.scri[(T / 64) + v], st = sh.scri[2 * (T / 64) + v];
         if (v < w) {
           be += se;
           ba += sa;
@@ -880,14 +898,14 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(SelectArgs a) {
     src.c0 = c0;
     RowState st;
     row_state_init(st);
-    constexpr int kGroups = kSelThreads / 16;
+    constexpr int kGroups = T / 16;
     const int per = kAttendBatch * ((R + kGroups * kAttendBatch - 1) / (kGroups * kAttendBatch));
     const int ra = grp * per, rb = min(R, ra + per);
     attend_rows(st, qv, a.scale_log2, src, sh.l_start, sh.l_src, n_ex + n_ap, 0, n_ex, ra, rb, kAttendBatch, lane16);
     DP_MARK(6);
     float M, L, o;
     const int groups_used = (R + per - 1) / per;
-    block_merge<kSelWaves>(st, sh.m_m, sh.m_l, sh.m_acc, (groups_used + 3) / 4, M, L, o);
+    block_merge<(T / 64)>(st, sh.m_m, sh.m_l, sh.m_acc, (groups_used + 3) / 4, M, L, o);
     if (tid < kHeadDim) {
       store_out(a.attn_out, a.out_is_bf16, head, tid, o / L);
       if (a.lse && tid == 0) a.lse[head] = (M + log2f(L)) * kLn2;
@@ -959,17 +977,17 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(PlanArgs a) {
   if (R == 0 && tid < kHeadDim) store_out(a.attn_out, a.out_is_bf16, head, tid, 0.f);
 }
 
-template <int E>
+template <int E, int T>
 void launch_select_e(const SelectArgs &a, bool by_count, dim3 grid, hipStream_t s, hipEvent_t start, hipEvent_t stop) {
   if (start || stop) {  // measurement: the runtime stamps the kernel's own begin and end
     if (by_count)
-      hipExtLaunchKernelGGL((select_kernel<E, true>), grid, dim3(kSelThreads), 0, s, start, stop, 0, a);
+      hipExtLaunchKernelGGL((select_kernel<E, true, T>), grid, dim3(T), 0, s, start, stop, 0, a);
     else
-      hipExtLaunchKernelGGL((select_kernel<E, false>), grid, dim3(kSelThreads), 0, s, start, stop, 0, a);
+      hipExtLaunchKernelGGL((select_kernel<E, false, T>), grid, dim3(T), 0, s, start, stop, 0, a);
   } else if (by_count) {
-    hipLaunchKernelGGL((select_kernel<E, true>), grid, dim3(kSelThreads), 0, s, a);
+    hipLaunchKernelGGL((select_kernel<E, true, T>), grid, dim3(T), 0, s, a);
   } else {
-    hipLaunchKernelGGL((select_kernel<E, false>), grid, dim3(kSelThreads), 0, s, a);
+    hipLaunchKernelGGL((select_kernel<E, false, T>), grid, dim3(T), 0, s, a);
   }
 }
 
@@ -1017,12 +1035,19 @@ hipError_t launch_select(const CacheView &c, const float *logits, const SelectRu
   const dim3 grid(c.batch * c.n_q_heads);
   if (grid.x == 0) return hipSuccess;
   const int k = c.max_clusters_per_seg;
-  if (k <= 2 * kSelThreads) launch_select_e<2>(a, bc, grid, s, start, stop);
-  else if (k <= 4 * kSelThreads) launch_select_e<4>(a, bc, grid, s, start, stop);
-  else if (k <= 8 * kSelThreads) launch_select_e<8>(a, bc, grid, s, start, stop);
-  else if (k <= 16 * kSelThreads) launch_select_e<16>(a, bc, grid, s, start, stop);
-  else if (k <= 32 * kSelThreads) launch_select_e<32>(a, bc, grid, s, start, stop);
-  else if (k <= 64 * kSelThreads) launch_select_e<64>(a, bc, grid, s, start, stop);
+  // A 1024-thread workgroup fills a CU's wave slots by itself (its registers allow one per CU).  With more heads
+  // than CUs the heads would run in rounds, so they get 512-thread workgroups instead: two per CU at once.
+  constexpr int kHalf = kSelThreads / 2;
+  if (grid.x > 256 && k <= 8 * kHalf) {  // (16 logits per thread would need too many registers for two per CU)
+    if (k <= 2 * kHalf) launch_select_e<2, kHalf>(a, bc, grid, s, start, stop);
+    else if (k <= 4 * kHalf) launch_select_e<4, kHalf>(a, bc, grid, s, start, stop);
+    else launch_select_e<8, kHalf>(a, bc, grid, s, start, stop);
+  } else if (k <= 2 * kSelThreads) launch_select_e<2, kSelThreads>(a, bc, grid, s, start, stop);
+  else if (k <= 4 * kSelThreads) launch_select_e<4, kSelThreads>(a, bc, grid, s, start, stop);
+  else if (k <= 8 * kSelThreads) launch_select_e<8, kSelThreads>(a, bc, grid, s, start, stop);
+  else if (k <= 16 * kSelThreads) launch_select_e<16, kSelThreads>(a, bc, grid, s, start, stop);
+  else if (k <= 32 * kSelThreads) launch_select_e<32, kSelThreads>(a, bc, grid, s, start, stop);
+  else if (k <= 64 * kSelThreads) launch_select_e<64, kSelThreads>(a, bc, grid, s, start, stop);
   else return hipErrorInvalidValue;
   return hipGetLastError();
 }

@@ -103,10 +103,19 @@ def case_pinned_many_clusters():
     return c, 0.95, 0.9
 
 
+def case_many_heads():
+    # more heads (320) than CUs: the selection kernel runs two 512-thread workgroups per CU; flat and peaked
+    # heads, ragged batch, 3300 / 1500 / 600 clusters per segment, sink and window pinned
+    from workloads import pin_sink_and_window
+    c = make_cache(batch=10, n_kv_heads=8, n_q_heads=32, context=[26400, 12000, 4800, 900, 26400, 700, 5000, 64, 3000, 9999],
+                   mean_cluster=8, size_hi=32, q_scale=lambda rng, b, h: [0.3, 3.0, 0.6, 1.5][h % 4], seed=23)
+    return pin_sink_and_window(c, first=1, last=2), 0.95, 0.9
+
+
 CASES = {f.__name__[5:]: f for f in (case_cfg0, case_flat_ragged, case_mixed_sharpness, case_gqa8_pareto, case_gqa1,
                                      case_gqa3_and_12, case_gqa12, case_many_clusters, case_single_cluster,
                                      case_giant_cluster, case_empty_clusters_and_segment, case_pinned_peaked,
-                                     case_pinned_flat_ragged, case_pinned_many_clusters)}
+                                     case_pinned_flat_ragged, case_pinned_many_clusters, case_many_heads)}
 
 
 @pytest.fixture(scope="module", params=sorted(CASES))
