@@ -90,8 +90,8 @@ void layout_of(const dp_problem *p, dp_workspace_layout *L) {
   off = align_up(off + sizeof(int32_t) * nh * (mk + 1), 256);
   L->chunk_entry = off;
   off = align_up(off + sizeof(int32_t) * nh * chunk_stride, 256);
-  L->counts = off;  // n_exact, n_retained, n_exact_tokens, head_rows, done : 5 x [nh], then the queue counters
-  off = align_up(off + sizeof(int32_t) * (5 * nh + (nh + dp::kMaxQueueHeads - 1) / dp::kMaxQueueHeads), 256);
+  L->counts = off;  // n_exact, n_retained, n_exact_tokens, head_rows, done : 5 x [nh], then the queue and pending counters
+  off = align_up(off + sizeof(int32_t) * (5 * nh + 2 * ((nh + dp::kMaxQueueHeads - 1) / dp::kMaxQueueHeads)), 256);
   L->partials = off;
   off = align_up(off + sizeof(float) * nh * (size_t)splits * (dp::kHeadDim + 2), 256);
   L->total = off;
@@ -128,6 +128,7 @@ Workspace carve(const dp_problem *p, void *ws) {
   w.plan.head_rows = counts + 3 * nh;
   w.plan.done = counts + 4 * nh;
   w.plan.queue_next = counts + 5 * nh;
+  w.plan.pending = nullptr;  // the one-call path turns it on (its scoring kernel clears the counters)
   w.partials = reinterpret_cast<float *>(b + L.partials);
   w.splits = L.splits;
   return w;
@@ -155,7 +156,7 @@ dp_status select_only(const dp_problem *problem, const float *logits, const dp::
   if (!n_exact || !n_retained || !n_exact_tokens) return DP_ERR_INVALID_ARG;
   if (problem->max_clusters_per_seg > 0 && (!logits || !sel_ids)) return DP_ERR_INVALID_ARG;
   dp::SelectOut out{sel_ids, n_exact, n_retained, n_exact_tokens};
-  dp::Plan none{nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, 0};
+  dp::Plan none{nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, 0};
   dp::AttnOut nowhere{nullptr, nullptr, 0};
   return dp::launch_select(view_of(problem), logits, rule, out, none, nowhere, static_cast<hipStream_t>(stream)) ==
                  hipSuccess
@@ -175,9 +176,11 @@ dp_status whole_step(const dp_problem *problem, const dp::SelectRule &rule, void
   if (workspace_bytes < dp_workspace_bytes(problem)) return DP_ERR_WORKSPACE_TOO_SMALL;
   if (reinterpret_cast<uintptr_t>(workspace) % 256) return DP_ERR_INVALID_ARG;
   const dp::CacheView c = view_of(problem);
-  const Workspace w = carve(problem, workspace);
+  Workspace w = carve(problem, workspace);
   hipStream_t s = static_cast<hipStream_t>(stream);
-  if (dp::launch_score(c, w.logits, s, ev[0], ev[1]) != hipSuccess) return DP_ERR_HIP;
+  const int n_slabs = (int)(((size_t)problem->batch * problem->n_q_heads + dp::kMaxQueueHeads - 1) / dp::kMaxQueueHeads);
+  if (problem->max_clusters_per_seg > 0 && n_slabs <= 256) w.plan.pending = w.plan.queue_next + n_slabs;
+  if (dp::launch_score(c, w.logits, s, ev[0], ev[1], w.plan.pending, n_slabs) != hipSuccess) return DP_ERR_HIP;
   dp::SelectOut so{w.sel_ids, w.n_exact, w.n_retained, w.n_exact_tokens};
   const dp::AttnOut attn{out, lse, out_dtype == DP_BF16};
   if (dp::launch_select(c, w.logits, rule, so, w.plan, attn, s, ev[2], ev[3]) != hipSuccess) return DP_ERR_HIP;

@@ -61,6 +61,7 @@ struct DecodeArgs {
   int32_t n_kv_heads, n_q_heads, group, max_k, splits, out_is_bf16;
   int32_t head0, n_heads;  // this launch serves heads [head0, head0 + n_heads), n_heads <= kMaxQueueHeads
   int32_t *queue_next;     // the launch's item counter (zeroed by the planner)
+  const int32_t *pending;  // nullable: heads of this launch that have work; 0 = return at once
   // A/B variant (decode_kernel<true>): per-head buffers that hold the gathered exact rows of heads with at most rows_cap of them
   const void *k_gather, *v_gather;
   int32_t rows_cap;
@@ -224,6 +225,7 @@ __global__ __launch_bounds__(kDecThreads) void decode_kernel(DecodeArgs a) {
   const int tid = threadIdx.x, lane16 = tid & 15, grp = tid >> 4;
 
   DD_MARK(0);
+  if (a.pending && *a.pending == 0) return;  // every head was finished by the selection kernel
   // ---- the queue: items per head from head_rows[], exclusive prefix in LDS ----
   constexpr int kPer = kMaxQueueHeads / kDecThreads;  // consecutive heads per thread
   int rows[kPer], chunks = 0;
@@ -326,6 +328,7 @@ hipError_t launch_decode(const CacheView &c, const int32_t *n_exact, const int32
     a.head0 = h0;
     a.n_heads = nh - h0 < kMaxQueueHeads ? nh - h0 : kMaxQueueHeads;
     a.queue_next = plan.queue_next + slab;
+    a.pending = plan.pending ? plan.pending + slab : nullptr;
     const long max_items = (long)a.n_heads * splits;
     const int grid = (int)(max_items < kDecodeGrid ? max_items : kDecodeGrid);
     // measurement: the events bracket the first slab's begin and the last slab's end

@@ -40,6 +40,9 @@ struct CacheView {
 struct Plan {
   int32_t *ent_src, *row_start, *chunk_entry, *head_rows, *done;
   int32_t *queue_next;  // one item counter per slab of kMaxQueueHeads heads (zeroed by the planner)
+  // nullable: per slab, how many heads the selection kernel left for the decode kernel.  Zeroed by the scoring
+  // kernel of the same step; a decode launch that reads 0 returns at once.
+  int32_t *pending;
   int32_t chunk_stride;
 };
 
@@ -56,8 +59,9 @@ struct SelectOut {
 };
 
 // start / stop (nullable): HIP events that receive the kernel's own begin and end timestamps
+// zero_words (nullable): n_zero int32 that the kernel clears (the step's pending counters)
 hipError_t launch_score(const CacheView &c, float *logits, hipStream_t s, hipEvent_t start = nullptr,
-                        hipEvent_t stop = nullptr);
+                        hipEvent_t stop = nullptr, int32_t *zero_words = nullptr, int n_zero = 0);
 
 // How stage 2 cuts the order (logit descending, index ascending):
 //   by_count == 0: the two top-p thresholds p1, p2 (p2_absolute: p2 is a mass of the whole distribution)

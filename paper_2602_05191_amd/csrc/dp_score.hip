@@ -31,11 +31,14 @@ struct ScoreArgs {
   int32_t head0;       // this launch scores heads [head0, head0 + GH) of each group
   int32_t uniform_kc;  // > 0: every segment has exactly this many clusters
   float sm_scale;
+  int32_t *zero_words;  // nullable: n_zero words cleared by the first workgroup (counters of the step's later kernels)
+  int32_t n_zero;
 };
 
 template <int GH>
 __global__ __launch_bounds__(kScoreThreads) void score_kernel(ScoreArgs a) {
   const int seg = blockIdx.y;
+  if (a.zero_words && blockIdx.x == 0 && blockIdx.y == 0 && (int)threadIdx.x < a.n_zero) a.zero_words[threadIdx.x] = 0;
   int c0, kc;
   if (a.uniform_kc > 0) {  // no CSR lookup in front of the centroid loads
     c0 = seg * a.uniform_kc;
@@ -110,7 +113,8 @@ void launch_one(const ScoreArgs &a, dim3 grid, hipStream_t s, hipEvent_t start, 
     hipLaunchKernelGGL(score_kernel<GH>, grid, dim3(kScoreThreads), 0, s, a);
 }
 
-hipError_t launch_score(const CacheView &c, float *logits, hipStream_t s, hipEvent_t start, hipEvent_t stop) {
+hipError_t launch_score(const CacheView &c, float *logits, hipStream_t s, hipEvent_t start, hipEvent_t stop,
+                        int32_t *zero_words, int n_zero) {
   ScoreArgs a;
   a.q = c.q;
   a.k_centroids = c.k_centroids;
@@ -122,6 +126,8 @@ hipError_t launch_score(const CacheView &c, float *logits, hipStream_t s, hipEve
   a.group = c.group;
   a.sm_scale = c.sm_scale;
   a.uniform_kc = c.uniform_kc;
+  a.zero_words = n_zero <= kScoreThreads ? zero_words : nullptr;
+  a.n_zero = n_zero;
   const dim3 grid((c.max_clusters_per_seg + kScoreTile - 1) / kScoreTile, c.batch * c.n_kv_heads);
   if (grid.x == 0 || grid.y == 0) return hipSuccess;
   // heads of a group are scored 8/4/2/1 at a time (one pass when G is 1, 2, 4 or 8)
@@ -130,6 +136,7 @@ hipError_t launch_score(const CacheView &c, float *logits, hipStream_t s, hipEve
     const int left = c.group - h0;
     const int gh = left >= 8 ? 8 : left >= 4 ? 4 : left >= 2 ? 2 : 1;
     a.head0 = h0;
+    if (h0 > 0) a.zero_words = nullptr;  // cleared once, by the first pass
     // with several passes the events bracket the first pass's begin and the last pass's end
     hipEvent_t ev0 = (h0 == 0) ? start : nullptr, ev1 = (h0 + gh >= c.group) ? stop : nullptr;
     switch (gh) {

@@ -871,6 +871,7 @@ __global__ __launch_bounds__(T) void select_kernel(SelectArgs a) {
       } else {
         emit.row_start[n_ex + n_ap] = R;
         a.plan.head_rows[head] = R;
+        if (a.plan.pending && R > 0) atomicAdd(&a.plan.pending[head / kMaxQueueHeads], 1);
       }
       a.plan.done[head] = 0;
     }
