@@ -38,12 +38,14 @@
 namespace dp {
 namespace {
 
-constexpr int kSelThreads = 1024;             // largest workgroup; a launch with more heads than CUs uses 512
-constexpr int kSelWaves = kSelThreads / 64;   // LDS scratch is sized for the largest workgroup
-constexpr int kBins = 2048;              // = 2 bins per thread in the histogram scan
-constexpr float kBinScale = (float)kBins / kCut;
+constexpr int kSelThreads = 1024;             // largest workgroup; launches with more heads than CUs use 512 or 256
+constexpr int kSelWaves = kSelThreads / 64;   // the small LDS scratch arrays are sized for the largest workgroup
+// level-1 histogram bins, by workgroup size T (2 or 4 consecutive bins per thread in the scan)
+constexpr int bins_of(int T) { return T >= 512 ? 2048 : 1024; }
+constexpr int log2_bins_of(int T) { return T >= 512 ? 11 : 10; }
+// heads with at most this many rows are attended inside the selection kernel (T / 16 DPP rows, 16 rows each)
+constexpr int inline_rows_of(int T) { return T; }
 constexpr int kMaxCand = 512;            // largest bin population that is ranked pairwise
-constexpr int kInlineRows = 1024;        // heads with at most this many rows are attended in this kernel
 constexpr float kTopCut = 6.0f;          // "top set": clusters whose logit is within this of the max
 constexpr int kTopMax = 64;              // largest top set handled by the one-wave fast path
 
@@ -81,7 +83,7 @@ struct SelectArgs {
 };
 
 // level-1 bin of a cluster at distance d below the max logit; bs = bins per unit of d
-__device__ __forceinline__ int level1_bin(float d, float bs) { return (int)fminf(d * bs, (float)(kBins - 1)); }
+__device__ __forceinline__ int level1_bin(float d, float bs, int bins) { return (int)fminf(d * bs, (float)(bins - 1)); }
 
 // The same threshold search serves two rules.  Top-p (kCount = false): a cluster weighs its
 // fixed-point softmax mass and is in play while that mass is non-zero.  Fixed budget (kCount =
@@ -93,9 +95,9 @@ __device__ __forceinline__ bool in_play(float d) { return kCount ? d < INFINITY 
 template <bool kCount>
 __device__ __forceinline__ u64 mass_of(float d) { return kCount ? (u64)(d < INFINITY) : fx_mass(d); }
 
+template <int T>
 struct Shared {
-  u64 hist[kBins];
-  u64 hist2[kBins];
+  u64 hist[bins_of(T)];
   u64 scr64[kSelWaves], scr64b[kSelWaves];
   float scrf[kSelWaves];
   int scri[3 * kSelWaves];
@@ -115,16 +117,22 @@ struct Shared {
   int top_idx[kTopMax], top_sz[kTopMax], top_off[kTopMax];
   u64 top_m[kTopMax];
   int ntop, f_nex, f_nap, f_ntok;
-  // inline attention
-  int l_start[kInlineRows + 1];
-  int l_src[kInlineRows];
-  float m_m[kSelWaves], m_l[kSelWaves];
-  float m_acc[kSelWaves][kHeadDim];
+  // The refinement histogram of the (rare) crowded-bin search and the lists / merge buffers of the inline
+  // attention never live at the same time: the lists are written once the search is over.
+  union {
+    u64 hist2[bins_of(T)];
+    struct {
+      int l_start[inline_rows_of(T) + 1];
+      int l_src[inline_rows_of(T)];
+      float m_m[kSelWaves], m_l[kSelWaves];
+      float m_acc[T / 64][kHeadDim];
+    } at;
+  };
 };
 
 // count / min key / max key over the block
 template <int T>
-__device__ __forceinline__ void reduce_members(int cnt, uint32_t lo, uint32_t hi, Shared &sh, int &cnt_o,
+__device__ __forceinline__ void reduce_members(int cnt, uint32_t lo, uint32_t hi, Shared<T> &sh, int &cnt_o,
                                                uint32_t &lo_o, uint32_t &hi_o) {
 #pragma unroll
   for (int d = 32; d >= 1; d >>= 1) {
@@ -166,8 +174,9 @@ struct Refined {
 };
 template <int E, bool kCount, int T>
 __device__ __forceinline__ Refined refine_or_cut_ties(const float *lg, int kc, float mx, float bs, int base, int bin1,
-                                                      u64 tau, u64 before, Shared *shp) {
-  Shared &sh = *shp;
+                                                      u64 tau, u64 before, Shared<T> *shp) {
+  Shared<T> &sh = *shp;
+  constexpr int kBins = bins_of(T);
   const int tid = threadIdx.x;
   auto logit = [&](int e) { return (base + e < kc) ? lg[base + e] + 0.0f : -INFINITY; };
   uint32_t klo, khi;
@@ -178,7 +187,7 @@ __device__ __forceinline__ Refined refine_or_cut_ties(const float *lg, int kc, f
 #pragma unroll 1
     for (int e = 0; e < E; ++e) {
       const float le = logit(e), d = mx - le;
-      if (in_play<kCount>(d) && level1_bin(d, bs) == bin1) {
+      if (in_play<kCount>(d) && level1_bin(d, bs, kBins) == bin1) {
         const uint32_t k = ordered_key(le);
         ++c;
         lo = min(lo, k);
@@ -191,8 +200,8 @@ __device__ __forceinline__ Refined refine_or_cut_ties(const float *lg, int kc, f
   while (cnt > kMaxCand && klo != khi) {
     for (int i = tid; i < kBins; i += T) sh.hist2[i] = 0;
     __syncthreads();
-    // 2048-way split of the key range by a shift: monotone in the key, no division
-    const int shift = max(0, 32 - __clz(khi - klo) - 11);
+    // kBins-way split of the key range by a shift: monotone in the key, no division
+    const int shift = max(0, 32 - __clz(khi - klo) - log2_bins_of(T));
 #pragma unroll 1
     for (int e = 0; e < E; ++e) {
       const float le = logit(e), d = mx - le;
@@ -293,9 +302,10 @@ __device__ __forceinline__ Refined refine_or_cut_ties(const float *lg, int kc, f
 // second threshold falls into the same bin).  Block-uniform control flow.
 template <int E, bool kCount, int T>
 __device__ __forceinline__ void find_prefix(const float (&l)[E], const float *lg, int kc, float mx, float bs, int base, u64 tau, u64 ex,
-                                            const u64 (&hb)[kBins / T], int slot, Shared &sh, int &cached_bin, int &cached_cnt,
+                                            const u64 (&hb)[bins_of(T) / T], int slot, Shared<T> &sh, int &cached_bin, int &cached_cnt,
                                             u64 &cached_before, uint32_t &key_o, int &idx_o, u64 &mass_o) {
   const int tid = threadIdx.x;
+  constexpr int kBins = bins_of(T);
   {
     u64 run = ex;
 #pragma unroll
@@ -320,7 +330,7 @@ __device__ __forceinline__ void find_prefix(const float (&l)[E], const float *lg
 #pragma unroll
     for (int e = 0; e < E; ++e) {
       const float d = mx - l[e];
-      if (in_play<kCount>(d) && level1_bin(d, bs) == bin1) {
+      if (in_play<kCount>(d) && level1_bin(d, bs, kBins) == bin1) {
         const int s = atomicAdd(&sh.ncand[slot], 1);
         if (s < kMaxCand) {
           sh.cand_key[s] = ordered_key(l[e]);
@@ -445,7 +455,9 @@ __device__ __forceinline__ int second_tau(const SelectArgs &a, u64 W, u64 m1, u6
 
 template <int E, bool kCount, int T>
 __global__ __launch_bounds__(T) void select_kernel(SelectArgs a) {
-  __shared__ Shared sh;
+  __shared__ Shared<T> sh;
+  constexpr int kBins = bins_of(T);
+  constexpr int kInlineRows = inline_rows_of(T);
   const int head = blockIdx.x;
   const int b = head / a.n_q_heads, h = head % a.n_q_heads;
   const int seg = b * a.n_kv_heads + h / a.group;
@@ -468,8 +480,8 @@ __global__ __launch_bounds__(T) void select_kernel(SelectArgs a) {
   emit.ent_src = plan ? a.plan.ent_src + (int64_t)head * a.max_k : nullptr;
   emit.row_start = plan ? a.plan.row_start + (int64_t)head * (a.max_k + 1) : nullptr;
   emit.chunk_entry = plan ? a.plan.chunk_entry + (int64_t)head * a.plan.chunk_stride : nullptr;
-  emit.l_start = sh.l_start;
-  emit.l_src = sh.l_src;
+  emit.l_start = sh.at.l_start;
+  emit.l_src = sh.at.l_src;
   emit.plan = plan;
 
   if (plan && tid == 0 && head % kMaxQueueHeads == 0) a.plan.queue_next[head / kMaxQueueHeads] = 0;
@@ -590,7 +602,7 @@ __global__ __launch_bounds__(T) void select_kernel(SelectArgs a) {
 
   // level-1 bins: top-p spreads them over the kCut below the max that carries mass; a fixed budget
   // spreads them over the head's whole range of finite logits
-  float bs = kBinScale;
+  float bs = (float)kBins / kCut;
   if (kCount) {
     float tmin = INFINITY;
 #pragma unroll
@@ -737,7 +749,7 @@ __global__ __launch_bounds__(T) void select_kernel(SelectArgs a) {
       for (int e = 0; e < E; ++e) {
         const float d = mx - l[e];
         const u64 m = mass_of<kCount>(d);
-        if (m) atomicAdd(&sh.hist[level1_bin(d, bs)], m);
+        if (m) atomicAdd(&sh.hist[level1_bin(d, bs, kBins)], m);
       }
       __syncthreads();
       DP_MARK(8);
@@ -866,7 +878,7 @@ __global__ __launch_bounds__(T) void select_kernel(SelectArgs a) {
     a.out.n_exact_tokens[head] = n_tok;
     if (plan) {
       if (inline_attn) {
-        sh.l_start[n_ex + n_ap] = R;
+        sh.at.l_start[n_ex + n_ap] = R;
         a.plan.head_rows[head] = -1;  // attended here: nothing left for the decode kernel
       } else {
         emit.row_start[n_ex + n_ap] = R;
@@ -902,11 +914,11 @@ __global__ __launch_bounds__(T) void select_kernel(SelectArgs a) {
     constexpr int kGroups = T / 16;
     const int per = kAttendBatch * ((R + kGroups * kAttendBatch - 1) / (kGroups * kAttendBatch));
     const int ra = grp * per, rb = min(R, ra + per);
-    attend_rows(st, qv, a.scale_log2, src, sh.l_start, sh.l_src, n_ex + n_ap, 0, n_ex, ra, rb, kAttendBatch, lane16);
+    attend_rows(st, qv, a.scale_log2, src, sh.at.l_start, sh.at.l_src, n_ex + n_ap, 0, n_ex, ra, rb, kAttendBatch, lane16);
     DP_MARK(6);
     float M, L, o;
     const int groups_used = (R + per - 1) / per;
-    block_merge<(T / 64)>(st, sh.m_m, sh.m_l, sh.m_acc, (groups_used + 3) / 4, M, L, o);
+    block_merge<(T / 64)>(st, sh.at.m_m, sh.at.m_l, sh.at.m_acc, (groups_used + 3) / 4, M, L, o);
     if (tid < kHeadDim) {
       store_out(a.attn_out, a.out_is_bf16, head, tid, o / L);
       if (a.lse && tid == 0) a.lse[head] = (M + log2f(L)) * kLn2;
@@ -1037,9 +1049,14 @@ hipError_t launch_select(const CacheView &c, const float *logits, const SelectRu
   if (grid.x == 0) return hipSuccess;
   const int k = c.max_clusters_per_seg;
   // A 1024-thread workgroup fills a CU's wave slots by itself (its registers allow one per CU).  With more heads
-  // than CUs the heads would run in rounds, so they get 512-thread workgroups instead: two per CU at once.
-  constexpr int kHalf = kSelThreads / 2;
-  if (grid.x > 256 && k <= 8 * kHalf) {  // (16 logits per thread would need too many registers for two per CU)
+  // than CUs the heads would run in rounds, so they get smaller workgroups: two of 512 threads or four of 256 per
+  // CU at once (up to 8 logits per thread: 16 would need too many registers for that).
+  constexpr int kHalf = kSelThreads / 2, kQuarter = kSelThreads / 4;
+  if (grid.x > 512 && k <= 8 * kQuarter) {
+    if (k <= 2 * kQuarter) launch_select_e<2, kQuarter>(a, bc, grid, s, start, stop);
+    else if (k <= 4 * kQuarter) launch_select_e<4, kQuarter>(a, bc, grid, s, start, stop);
+    else launch_select_e<8, kQuarter>(a, bc, grid, s, start, stop);
+  } else if (grid.x > 256 && k <= 8 * kHalf) {
     if (k <= 2 * kHalf) launch_select_e<2, kHalf>(a, bc, grid, s, start, stop);
     else if (k <= 4 * kHalf) launch_select_e<4, kHalf>(a, bc, grid, s, start, stop);
     else launch_select_e<8, kHalf>(a, bc, grid, s, start, stop);

@@ -112,10 +112,21 @@ def case_many_heads():
     return pin_sink_and_window(c, first=1, last=2), 0.95, 0.9
 
 
+def case_very_many_heads():
+    # 640 heads: four 256-thread selection workgroups per CU; up to 1700 clusters per segment (8 logits per
+    # thread), flat and peaked heads, one head group with 300 - 600 rows (beyond that kernel's inline limit)
+    from workloads import pin_sink_and_window
+    ctx = [13600, 700, 5000, 64, 3000, 9999, 13000, 2048, 4096, 333] * 2
+    c = make_cache(batch=20, n_kv_heads=8, n_q_heads=32, context=ctx, mean_cluster=8, size_hi=32,
+                   q_scale=lambda rng, b, h: [0.3, 3.0, 0.8, 1.5][h % 4], seed=24)
+    return pin_sink_and_window(c, first=1, last=2), 0.95, 0.9
+
+
 CASES = {f.__name__[5:]: f for f in (case_cfg0, case_flat_ragged, case_mixed_sharpness, case_gqa8_pareto, case_gqa1,
                                      case_gqa3_and_12, case_gqa12, case_many_clusters, case_single_cluster,
                                      case_giant_cluster, case_empty_clusters_and_segment, case_pinned_peaked,
-                                     case_pinned_flat_ragged, case_pinned_many_clusters, case_many_heads)}
+                                     case_pinned_flat_ragged, case_pinned_many_clusters, case_many_heads,
+                                     case_very_many_heads)}
 
 
 @pytest.fixture(scope="module", params=sorted(CASES))
