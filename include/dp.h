@@ -249,6 +249,24 @@ dp_status dp_build_cluster_cache(const dp_prefill *in, void *k_cache, void *v_ca
                                  int32_t *cluster_sizes, void *k_centroids, void *v_centroids, float *v_sums,
                                  int32_t *token_row, void *workspace, size_t workspace_bytes, void *stream);
 
+/* Assignment step of the k-means clustering of the keys (Sec. 4.1): every token
+ * of segment seg goes to the nearest of the segment's centroids,
+ *   assignment[row] = argmax_c ( x . c - |c|^2 / 2 )   (= argmin_c |x - c|^2),
+ * the lower index on a tie; -1 if the segment has no centroid.  bf16 operands,
+ * fp32 accumulation on the matrix cores (two centroids whose scores differ by
+ * less than fp32 rounding of a 128-term sum may swap against exact arithmetic).
+ * Uses in->k_tokens, seg_row_base, seg_rows, seg_cluster_ptr and the three
+ * bounds; in->v_tokens and in->assignment are not read.
+ *   centroids   bf16 [total_clusters, head_dim]  (device)
+ *   assignment  int32 [total_rows]               (device, written)
+ *   best_score  fp32 [total_rows], nullable: the winning x . c - |c|^2 / 2
+ * With dp_build_cluster_cache (which recomputes the centroids as the cluster
+ * means) this is one Lloyd iteration; initial centroids and the iteration count
+ * are the caller's.  workspace: dp_kmeans_workspace_bytes, 256-byte aligned. */
+size_t dp_kmeans_workspace_bytes(const dp_prefill *in);
+dp_status dp_kmeans_assign(const dp_prefill *in, const void *centroids, int32_t *assignment, float *best_score,
+                           void *workspace, size_t workspace_bytes, void *stream);
+
 /* Where dp_decode_attention keeps its intermediate results inside the
  * workspace (byte offsets; host-only, for inspection by tests and tools):
  * logits as in dp_score_centroids, sel_ids as in dp_topp_select. */

@@ -85,6 +85,8 @@ def _load():
         L.dpo_budget_step.argtypes = [CP, I, I, P, P, P, P, P, C.c_int64, I]
         L.dpo_build_cluster_cache.restype = None
         L.dpo_build_cluster_cache.argtypes = [I, I] + [P] * 14
+        L.dpo_kmeans_assign.restype = None
+        L.dpo_kmeans_assign.argtypes = [I, I] + [P] * 8
         L.dpo_dense_step.restype = I
         L.dpo_dense_step.argtypes = [CP, P, P, I]
         _lib = L
@@ -312,3 +314,20 @@ def build_cluster_cache(tokens) -> dict:
         out[k] = out[k][:n_cl]
     out["token_row"] = out["token_row"][:n_rows]
     return out
+
+
+def kmeans_assign(tokens, centroids: np.ndarray):
+    """Nearest centroid of every token of a workloads.TokenOrderInput (Sec. 4.1, the assignment step of k-means).
+    centroids: uint16 bf16 bits [total_clusters, d].  -> (assignment int32, best score, runner-up score)"""
+    lib = _load()
+    t = tokens
+    n_rows = int(t.k_tokens.shape[0])
+    k = np.ascontiguousarray(t.k_tokens, np.uint16)
+    c = np.ascontiguousarray(centroids, np.uint16)
+    base, rows = np.ascontiguousarray(t.seg_row_base, np.int64), np.ascontiguousarray(t.seg_rows, np.int32)
+    ptr = np.ascontiguousarray(t.seg_cluster_ptr, np.int32)
+    asg = np.full(max(n_rows, 1), -7, np.int32)
+    best, second = np.zeros(max(n_rows, 1)), np.zeros(max(n_rows, 1))
+    lib.dpo_kmeans_assign(len(rows), int(t.head_dim), _ptr(k), _ptr(c), _ptr(base), _ptr(rows), _ptr(ptr), _ptr(asg),
+                          _ptr(best), _ptr(second))
+    return asg[:n_rows], best[:n_rows], second[:n_rows]

@@ -448,3 +448,37 @@ void dpo_build_cluster_cache(int32_t n_seg, int32_t d, const uint16_t *k_tokens,
     }
   }
 }
+
+/* ---- k-means assignment step (Sec. 4.1): nearest centroid of every key ---- */
+void dpo_kmeans_assign(int32_t n_seg, int32_t d, const uint16_t *k_tokens, const uint16_t *centroids,
+                       const int64_t *seg_row_base, const int32_t *seg_rows, const int32_t *seg_cluster_ptr,
+                       int32_t *assignment, double *best_score, double *runner_up) {
+  for (int32_t seg = 0; seg < n_seg; ++seg) {
+    const int64_t r0 = seg_row_base[seg];
+    const int32_t n = seg_rows[seg], c0 = seg_cluster_ptr[seg], kc = seg_cluster_ptr[seg + 1] - c0;
+    for (int32_t t = 0; t < n; ++t) {
+      /* |x - c|^2 = |x|^2 - 2 (x.c - |c|^2 / 2): the nearest centroid maximises x.c - |c|^2 / 2 */
+      double best = -INFINITY, second = -INFINITY;
+      int32_t arg = -1;
+      for (int32_t c = 0; c < kc; ++c) {
+        double dot = 0.0, nrm = 0.0;
+        for (int32_t j = 0; j < d; ++j) {
+          const double cj = bf16_to_double(centroids[(int64_t)(c0 + c) * d + j]);
+          dot += bf16_to_double(k_tokens[(r0 + t) * d + j]) * cj;
+          nrm += cj * cj;
+        }
+        const double s = dot - 0.5 * nrm;
+        if (s > best) { /* strict: the lower index keeps a tie */
+          second = best;
+          best = s;
+          arg = c;
+        } else if (s > second) {
+          second = s;
+        }
+      }
+      assignment[r0 + t] = arg;
+      if (best_score) best_score[r0 + t] = best;
+      if (runner_up) runner_up[r0 + t] = second;
+    }
+  }
+}

@@ -132,6 +132,15 @@ void dpo_build_cluster_cache(int32_t n_seg, int32_t d, const uint16_t *k_tokens,
                              int32_t *cluster_offsets, int32_t *cluster_sizes, uint16_t *k_centroids,
                              uint16_t *v_centroids, double *v_sums, int32_t *token_row);
 
+/* Assignment step of the k-means clustering of the keys (Sec. 4.1): every token
+ * goes to the nearest centroid of its segment (Euclidean distance), the lower
+ * index on a tie; written as argmax of x.c - |c|^2 / 2, which differs from
+ * -|x - c|^2 / 2 by a constant per token.  best_score / runner_up (nullable):
+ * the largest and the second largest of those scores (-inf if there is none). */
+void dpo_kmeans_assign(int32_t n_seg, int32_t d, const uint16_t *k_tokens, const uint16_t *centroids,
+                       const int64_t *seg_row_base, const int32_t *seg_rows, const int32_t *seg_cluster_ptr,
+                       int32_t *assignment, double *best_score, double *runner_up);
+
 #ifdef __cplusplus
 }
 #endif

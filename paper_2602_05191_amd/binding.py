@@ -25,7 +25,8 @@ _LIB_PATH = os.path.join(_PKG, "libdp_hip.so")
 EXPORTS = ["dp_workspace_bytes", "dp_logits_count", "dp_get_workspace_layout", "dp_score_centroids",
            "dp_score_centroids_timed",
            "dp_topp_select", "dp_topp_select_sorted", "dp_topk_select", "dp_sparse_decode", "dp_sparse_decode_gathered", "dp_decode_attention",
-           "dp_decode_attention_timed", "dp_budget_decode_attention", "dp_dense_decode", "dp_build_workspace_bytes", "dp_build_cluster_cache",
+           "dp_decode_attention_timed", "dp_budget_decode_attention", "dp_dense_decode", "dp_build_workspace_bytes", "dp_build_cluster_cache", "dp_kmeans_workspace_bytes",
+           "dp_kmeans_assign",
            "dp_status_string"]
 
 
@@ -108,6 +109,10 @@ def load_library():
     L.dp_build_workspace_bytes.argtypes = [C.POINTER(_Prefill)]
     L.dp_build_cluster_cache.restype = I
     L.dp_build_cluster_cache.argtypes = [C.POINTER(_Prefill), V, V, V, V, V, V, V, V, V, C.c_size_t, V]
+    L.dp_kmeans_workspace_bytes.restype = C.c_size_t
+    L.dp_kmeans_workspace_bytes.argtypes = [C.POINTER(_Prefill)]
+    L.dp_kmeans_assign.restype = I
+    L.dp_kmeans_assign.argtypes = [C.POINTER(_Prefill), V, V, V, V, C.c_size_t, V]
     L.dp_status_string.restype = C.c_char_p
     L.dp_status_string.argtypes = [I]
     _lib = L
@@ -369,3 +374,19 @@ def dp_sparse_decode_gathered(problem: Problem, sel_ids: torch.Tensor, n_exact: 
                                                     _ptr(workspace), workspace.numel() * workspace.element_size(),
                                                     _stream(stream)),
            "dp_sparse_decode_gathered")
+
+
+def dp_kmeans_workspace_bytes(prefill: Prefill) -> int:
+    return int(load_library().dp_kmeans_workspace_bytes(prefill.ref))
+
+
+def dp_kmeans_assign(prefill: Prefill, centroids: torch.Tensor, assignment: torch.Tensor, workspace: torch.Tensor,
+                     best_score: Optional[torch.Tensor] = None, stream=None) -> None:
+    assert centroids.is_contiguous() and centroids.element_size() == 2
+    assert centroids.numel() >= prefill.total_clusters * prefill.c.head_dim
+    assert assignment.dtype == torch.int32 and assignment.is_contiguous() and assignment.numel() >= prefill.total_rows
+    assert best_score is None or (best_score.dtype == torch.float32 and best_score.numel() >= prefill.total_rows)
+    _check(load_library().dp_kmeans_assign(prefill.ref, _ptr(centroids), _ptr(assignment), _ptr(best_score),
+                                           _ptr(workspace), workspace.numel() * workspace.element_size(),
+                                           _stream(stream)),
+           "dp_kmeans_assign")

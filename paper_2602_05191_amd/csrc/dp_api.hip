@@ -415,6 +415,38 @@ dp_status dp_build_cluster_cache(const dp_prefill *in, void *k_cache, void *v_ca
   return dp::launch_build(p, workspace, static_cast<hipStream_t>(stream)) == hipSuccess ? DP_OK : DP_ERR_HIP;
 }
 
+size_t dp_kmeans_workspace_bytes(const dp_prefill *in) {
+  if (!prefill_ok(in)) return 0;
+  return align_up(sizeof(float) * (size_t)in->total_clusters, 256);
+}
+
+dp_status dp_kmeans_assign(const dp_prefill *in, const void *centroids, int32_t *assignment, float *best_score,
+                           void *workspace, size_t workspace_bytes, void *stream) {
+  if (!prefill_ok(in)) return DP_ERR_INVALID_ARG;
+  if (in->head_dim != dp::kHeadDim) return DP_ERR_UNSUPPORTED;
+  if (in->n_seg == 0 || in->max_rows_per_seg == 0) return DP_OK;
+  if (!in->seg_row_base || !in->seg_rows || !in->seg_cluster_ptr || !in->k_tokens || !assignment)
+    return DP_ERR_INVALID_ARG;
+  if (in->total_clusters > 0 && !centroids) return DP_ERR_INVALID_ARG;
+  const size_t need = dp_kmeans_workspace_bytes(in);
+  if (workspace_bytes < need) return DP_ERR_WORKSPACE_TOO_SMALL;
+  if (need > 0 && (!workspace || reinterpret_cast<uintptr_t>(workspace) % 256)) return DP_ERR_INVALID_ARG;
+  dp::KmeansProblem p;
+  p.n_seg = in->n_seg;
+  p.k_tokens = in->k_tokens;
+  p.centroids = centroids;
+  p.seg_row_base = in->seg_row_base;
+  p.seg_rows = in->seg_rows;
+  p.seg_cluster_ptr = in->seg_cluster_ptr;
+  p.max_rows = in->max_rows_per_seg;
+  p.total_clusters = in->total_clusters;
+  p.assignment = assignment;
+  p.best_score = best_score;
+  return dp::launch_kmeans_assign(p, static_cast<float *>(workspace), static_cast<hipStream_t>(stream)) == hipSuccess
+             ? DP_OK
+             : DP_ERR_HIP;
+}
+
 const char *dp_status_string(dp_status status) {
   switch (status) {
     case DP_OK: return "DP_OK";

@@ -115,6 +115,18 @@ struct BuildProblem {
 void build_workspace_layout(int n_seg, int max_rows, int max_kc, size_t *hist_bytes, size_t *rank_bytes, int *n_blocks);
 hipError_t launch_build(const BuildProblem &p, void *workspace, hipStream_t s);
 
+// k-means assignment step: nearest centroid of every token (dp_kmeans.hip)
+struct KmeansProblem {
+  int32_t n_seg;
+  const void *k_tokens, *centroids;
+  const int64_t *seg_row_base;
+  const int32_t *seg_rows, *seg_cluster_ptr;
+  int32_t max_rows, total_clusters;
+  int32_t *assignment;
+  float *best_score;  // nullable
+};
+hipError_t launch_kmeans_assign(const KmeansProblem &p, float *half_norm, hipStream_t s);
+
 // largest max_clusters_per_seg the selection kernel supports
 constexpr int kSelectMaxClusters = 65536;
 

@@ -667,3 +667,62 @@ def test_decode_on_the_rebuilt_cache_equals_decode_on_the_original():
     a, b = oracle.Oracle(c).decode_step(0.95, 0.7), oracle.Oracle(rebuilt).decode_step(0.95, 0.7)
     assert (a.k1 == b.k1).all() and (a.k2 == b.k2).all() and (a.order == b.order).all()
     np.testing.assert_allclose(a.out, b.out, rtol=1e-11, atol=1e-13)
+
+
+# --------------------------------------------------------------------------
+# k-means assignment step (Sec. 4.1)
+# --------------------------------------------------------------------------
+def test_kmeans_assign_is_scipys_nearest_centroid():
+    from scipy.cluster.vq import vq
+    from scipy.spatial.distance import cdist
+    from workloads import token_order_input
+    c = make_cache(batch=2, n_kv_heads=1, n_q_heads=1, context=[400, 150], mean_cluster=10, size_hi=40, q_scale=1.0,
+                   seed=51)
+    t = token_order_input(c, seed=2)
+    rng = np.random.default_rng(4)
+    cent = c.k_centroids.copy()
+    cent[::3] = t.k_tokens[rng.integers(0, 400, size=len(cent[::3]))]          # some centroids are plain tokens
+    asg, best, second = oracle.kmeans_assign(t, cent)
+    X, C = bf16_bits_to_f32(t.k_tokens).astype(np.float64), bf16_bits_to_f32(cent).astype(np.float64)
+    for seg in range(2):
+        r0, n = int(t.seg_row_base[seg]), int(t.seg_rows[seg])
+        a, e = int(t.seg_cluster_ptr[seg]), int(t.seg_cluster_ptr[seg + 1])
+        code, dist = vq(X[r0:r0 + n], C[a:e])                                     # scipy's nearest code-book entry
+        d2 = cdist(X[r0:r0 + n], C[a:e], "sqeuclidean")
+        clear = (np.sort(d2, axis=1)[:, 1] - np.sort(d2, axis=1)[:, 0]) > 1e-9    # no near-tie
+        assert clear.mean() > 0.95
+        assert np.array_equal(asg[r0:r0 + n][clear], code[clear])
+        # the score is the distance up to the token's own norm
+        np.testing.assert_allclose((X[r0:r0 + n] ** 2).sum(1) - 2 * best[r0:r0 + n], dist ** 2, rtol=1e-9, atol=1e-9)
+        np.testing.assert_allclose((X[r0:r0 + n] ** 2).sum(1) - 2 * second[r0:r0 + n], np.sort(d2, axis=1)[:, 1],
+                                   rtol=1e-9, atol=1e-9)
+
+
+def test_kmeans_assign_ties_go_to_the_lower_index_and_lloyd_does_not_increase_the_objective():
+    from workloads import TokenOrderInput, token_order_input
+    d = 128
+    X = np.zeros((6, d), np.float32)
+    X[:, 0] = [0, 1, 2, 3, 4, 5]
+    C = np.zeros((3, d), np.float32)
+    C[:, 0] = [1, 3, 3]                                                           # centroid 2 duplicates centroid 1
+    t = TokenOrderInput(n_seg=1, head_dim=d, k_tokens=f32_to_bf16_bits(X), v_tokens=f32_to_bf16_bits(X),
+                        assignment=np.zeros(6, np.int32), seg_row_base=np.zeros(1, np.int64),
+                        seg_rows=np.array([6], np.int32), seg_cluster_ptr=np.array([0, 3], np.int32))
+    asg, best, second = oracle.kmeans_assign(t, f32_to_bf16_bits(C))
+    assert asg.tolist() == [0, 0, 0, 1, 1, 1]            # token 2 is equidistant from 1 and 3: lower index; never centroid 2
+    # one Lloyd iteration (assign, then means) never increases the sum of squared distances in exact arithmetic;
+    # with means rounded to bf16 it may move by the rounding, hence the small slack
+    c = make_cache(batch=1, n_kv_heads=1, n_q_heads=1, context=1500, mean_cluster=12, size_hi=40, q_scale=1.0, seed=52)
+    t = token_order_input(c, seed=3)
+    cent = t.k_tokens[np.random.default_rng(5).choice(1500, size=int(c.seg_cluster_ptr[1]), replace=False)].copy()
+    Xf = bf16_bits_to_f32(t.k_tokens).astype(np.float64)
+    prev = None
+    for it in range(4):
+        asg, best, _ = oracle.kmeans_assign(t, cent)
+        obj = float(((Xf ** 2).sum(1) - 2 * best).sum())
+        assert prev is None or obj <= prev * (1 + 1e-4), (it, obj, prev)
+        prev = obj
+        t.assignment = asg
+        m = oracle.build_cluster_cache(t)
+        keep = m["cluster_sizes"] > 0                      # an empty cluster keeps its old centroid
+        cent = np.where(keep[:, None], m["k_centroids"], cent)
