@@ -316,7 +316,14 @@ def main():
     b_kc, b_vc = torch.empty_like(base.k_centroids), torch.empty_like(base.v_centroids)
     build_us = wall_time(lambda i: dp.dp_build_cluster_cache(pf, b_k, b_v, b_off, b_sz, b_kc, b_vc, bws), 20)
     build_bytes = int(tok.k_tokens.shape[0]) * (3 * 512 + 4)   # K+V rows read, written, read again for the means; ids
-    del tok, pf, bws, b_k, b_v, b_off, b_sz, b_kc, b_vc
+    # the assignment step of the clustering itself (one Lloyd iteration = this + the build): a dense
+    # tokens x centroids x 128 contraction on the matrix cores
+    kws = torch.empty(max(dp.dp_kmeans_workspace_bytes(pf), 256), dtype=torch.uint8, device=dev)
+    k_asg = torch.empty(int(tok.k_tokens.shape[0]), dtype=torch.int32, device=dev)
+    kmeans_us = wall_time(lambda i: dp.dp_kmeans_assign(pf, base.k_centroids, k_asg, kws), 5)
+    kmeans_flops = 2.0 * cache.head_dim * float(
+        (tok.seg_rows.astype(np.int64) * np.diff(tok.seg_cluster_ptr).astype(np.int64)).sum())
+    del tok, pf, bws, kws, k_asg, b_k, b_v, b_off, b_sz, b_kc, b_vc
 
     # the kernel that moves the bytes: centroid scoring reads every key centroid and size once and
     # writes G logits per cluster
@@ -411,6 +418,9 @@ def main():
         "with_sink_and_window_pinned_us": round(pinned_us, 3),
         "prefill_build": {"entry_point": "dp_build_cluster_cache", "us": round(build_us, 1),
                           "bytes": build_bytes, "GBs": round(build_bytes / (build_us * 1e-6) / 1e9, 1)},
+        "kmeans_assign": {"entry_point": "dp_kmeans_assign", "us": round(kmeans_us, 1), "flops": kmeans_flops,
+                          "TFLOPs": round(kmeans_flops / (kmeans_us * 1e-6) / 1e12, 1),
+                          "frac_of_bf16_mfma_peak": round(kmeans_flops / (kmeans_us * 1e-6) / 2.5e15, 4)},
         "gen_seconds": round(t_gen, 1),
     }
 

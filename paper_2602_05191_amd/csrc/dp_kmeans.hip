@@ -10,14 +10,17 @@
 // stored, fp32 accumulation.  MFMA-bound; the operands come from cache (a
 // segment's centroids are 2 MB).
 //
-// A wave owns 64 tokens (4 MFMA row tiles, the A operand, held in registers for
-// the whole kernel) and walks the segment's centroids 16 at a time (the B
-// operand, loaded from global memory in operand layout, next tile in flight).
-// Operand layout of the instruction: lane l holds row l % 16 and the 8
+// A wave owns 16 x TM tokens (TM MFMA row tiles, the A operand, held in registers
+// for the whole kernel).  The workgroup walks the segment's centroids 64 at a time:
+// the block is fetched once from global memory by all 256 threads, kept in LDS
+// (double buffered, rows padded to 272 B so that the 16 rows an operand read
+// touches fall into different banks) and read from there by the four waves as
+// the B operand, so the next block's global latency hides behind 64 x TM MFMAs
+// per wave.  Operand layout of the instruction: lane l holds row l % 16 and the 8
 // consecutive k of block l / 16; the result tile holds, in lane l, column
 // l % 16 and rows 4 (l / 16) .. + 3.  The accumulator starts at -|c|^2 / 2 of
 // the lane's centroid column, so a result element IS the score.  Every lane
-// keeps the running best (score, centroid) of its 16 (token, column class)
+// keeps the running best (score, centroid) of its 4 x TM (token, column class)
 // pairs: no cross-lane work inside the loop; the 16 column classes of a token
 // are merged once at the end (DPP row reduction, lower index wins a tie).
 #include "dp_device.hpp"
@@ -30,9 +33,20 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int kKmThreads = 256;
-constexpr int kKmTM = 4;                               // 16-token row tiles per wave
+#ifndef DP_KM_TM
+#define DP_KM_TM 4
+#endif
+#ifndef DP_KM_UNROLL
+#define DP_KM_UNROLL 1
+#endif
+constexpr int kKmTM = DP_KM_TM;                        // 16-token row tiles per wave
 constexpr int kKmTokensPerWave = 16 * kKmTM;
 constexpr int kKmTokensPerBlock = kKmTokensPerWave * (kKmThreads / 64);
+#ifndef DP_KM_CB
+#define DP_KM_CB 64
+#endif
+constexpr int kKmCB = DP_KM_CB;                        // centroids per LDS block (a multiple of 64: 256 threads fetch 64 rows per pass)
+constexpr int kKmRowPad = kRowBytes + 16;              // LDS row stride: 68 words, 4 r mod 64 banks for row r
 
 struct KmArgs {
   const void *k_tokens, *centroids;
@@ -63,11 +77,14 @@ __device__ __forceinline__ uint4 operand_slice(const void *base, int64_t row, in
 }
 
 __global__ __launch_bounds__(kKmThreads) void km_assign_kernel(KmArgs a) {
+  __shared__ __attribute__((aligned(16))) char s_c[2][kKmCB * kKmRowPad];
+  __shared__ float s_hn[2][kKmCB];
   const int seg = blockIdx.y;
   const int n = min(a.seg_rows[seg], a.max_rows);
-  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-  const int t0 = blockIdx.x * kKmTokensPerBlock + wave * kKmTokensPerWave;  // first token of this wave
-  if (t0 >= n) return;
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const int blk0 = blockIdx.x * kKmTokensPerBlock;
+  if (blk0 >= n) return;  // uniform in the workgroup
+  const int t0 = blk0 + wave * kKmTokensPerWave;  // first token of this wave (a wave past the end only helps to load)
   const int c0 = a.seg_cluster_ptr[seg], kc = a.seg_cluster_ptr[seg + 1] - c0;
   const int64_t r0 = a.seg_row_base[seg];
   const int r = lane & 15, kq = lane >> 4;
@@ -91,43 +108,76 @@ __global__ __launch_bounds__(kKmThreads) void km_assign_kernel(KmArgs a) {
       bidx[tm][i] = 0x7fffffff;
     }
 
-  auto load_tile = [&](int tile, uint4 (&B)[4], float &hn) {
-    const int c = tile * 16 + r;  // this lane's centroid column
-    if (c < kc) {
+  // global -> registers -> LDS: per pass of 64 rows, thread tid fetches 64 B (quarter tid & 3) of row tid >> 2
+  constexpr int kPasses = kKmCB / 64;
+  const int lrow = tid >> 2, lq = tid & 3;
+  uint4 stage[kPasses][4];
+  float stage_hn[kPasses];
+  auto fetch_block = [&](int blk) {
 #pragma unroll
-      for (int j = 0; j < 4; ++j) B[j] = operand_slice(a.centroids, c0 + c, j, kq);
-      hn = a.half_norm[c0 + c];
-    } else {  // past the segment's centroids: a column that can never win
+    for (int ps = 0; ps < kPasses; ++ps) {
+      const int c = blk * kKmCB + ps * 64 + lrow;
+      if (c < kc) {
+        const char *src = static_cast<const char *>(a.centroids) + (int64_t)(c0 + c) * kRowBytes + lq * 64;
 #pragma unroll
-      for (int j = 0; j < 4; ++j) B[j] = make_uint4(0, 0, 0, 0);
-      hn = INFINITY;
+        for (int u = 0; u < 4; ++u) stage[ps][u] = *reinterpret_cast<const uint4 *>(src + 16 * u);
+        stage_hn[ps] = a.half_norm[c0 + c];
+      } else {  // past the segment's centroids: columns that can never win
+#pragma unroll
+        for (int u = 0; u < 4; ++u) stage[ps][u] = make_uint4(0, 0, 0, 0);
+        stage_hn[ps] = INFINITY;
+      }
+    }
+  };
+  auto store_block = [&](int buf) {
+#pragma unroll
+    for (int ps = 0; ps < kPasses; ++ps) {
+      char *dst = s_c[buf] + (ps * 64 + lrow) * kKmRowPad + lq * 64;
+#pragma unroll
+      for (int u = 0; u < 4; ++u) *reinterpret_cast<uint4 *>(dst + 16 * u) = stage[ps][u];
+      if (lq == 0) s_hn[buf][ps * 64 + lrow] = stage_hn[ps];
     }
   };
 
-  const int n_tiles = (kc + 15) / 16;
-  uint4 B[4], Bn[4];
-  float hn, hnn;
-  if (n_tiles > 0) load_tile(0, B, hn);
-  for (int tile = 0; tile < n_tiles; ++tile) {
-    if (tile + 1 < n_tiles) load_tile(tile + 1, Bn, hnn);
-    const int c = tile * 16 + r;
+  const int n_blocks = (kc + kKmCB - 1) / kKmCB;
+  if (n_blocks > 0) {
+    fetch_block(0);
+    store_block(0);
+  }
+  __syncthreads();
+  for (int blk = 0; blk < n_blocks; ++blk) {
+    const int buf = blk & 1;
+    if (blk + 1 < n_blocks) fetch_block(blk + 1);  // in flight during this block's MFMAs
+#pragma unroll DP_KM_UNROLL
+    for (int tt = 0; tt < kKmCB / 16; ++tt) {
+      const char *row = s_c[buf] + (tt * 16 + r) * kKmRowPad + kq * 16;
+      uint4 B[4];
 #pragma unroll
-    for (int tm = 0; tm < kKmTM; ++tm) {
-      f32x4 acc = {-hn, -hn, -hn, -hn};
+      for (int j = 0; j < 4; ++j) B[j] = *reinterpret_cast<const uint4 *>(row + j * 64);
+      const float hn = s_hn[buf][tt * 16 + r];
+      const int c = blk * kKmCB + tt * 16 + r;  // this lane's centroid column
+      // TM independent accumulation chains, advanced together: no MFMA waits for its predecessor
+      f32x4 acc[kKmTM];
+#pragma unroll
+      for (int tm = 0; tm < kKmTM; ++tm) acc[tm] = f32x4{-hn, -hn, -hn, -hn};
 #pragma unroll
       for (int j = 0; j < 4; ++j)
-        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, A[tm][j]), __builtin_bit_cast(bf16x8, B[j]),
-                                                      acc, 0, 0, 0);
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {  // centroids come in ascending order: a strict comparison keeps the lowest index
-        const bool better = acc[i] > best[tm][i];
-        best[tm][i] = better ? acc[i] : best[tm][i];
-        bidx[tm][i] = better ? c : bidx[tm][i];
-      }
+        for (int tm = 0; tm < kKmTM; ++tm)
+          acc[tm] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, A[tm][j]),
+                                                            __builtin_bit_cast(bf16x8, B[j]), acc[tm], 0, 0, 0);
+#pragma unroll
+      for (int tm = 0; tm < kKmTM; ++tm)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {  // centroids come in ascending order: a strict comparison keeps the lowest index
+          const bool better = acc[tm][i] > best[tm][i];
+          best[tm][i] = better ? acc[tm][i] : best[tm][i];
+          bidx[tm][i] = better ? c : bidx[tm][i];
+        }
     }
-#pragma unroll
-    for (int j = 0; j < 4; ++j) B[j] = Bn[j];
-    hn = hnn;
+    // the other buffer was last read in the previous iteration, which ended with a barrier
+    if (blk + 1 < n_blocks) store_block(buf ^ 1);
+    __syncthreads();
   }
 
   // merge the 16 column classes of each token: max score, lower index on a tie (DPP row exchange)
