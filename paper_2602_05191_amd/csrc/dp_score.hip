@@ -4,9 +4,15 @@
 //
 // HBM-bound streaming kernel: the key-centroid matrix is read exactly once
 // (256 B per cluster) and each row is scored against all G query heads of the
-// group from registers.  A 16-lane DPP row owns one centroid row (16 B per
-// lane, global_load_dwordx4); each lane's 8 products are accumulated by the
-// packed bf16 dot instruction and the 16 partial dots are summed with DPP adds.
+// group at once.  The scores of 16 clusters against up to 16 query heads are one
+// [16 x 128] x [128 x 16] contraction, done by four v_mfma_f32_16x16x32_bf16
+// (64 matrix-core cycles per 16 clusters, whatever G is; the same dots on the
+// vector ALU take 2.25 instructions per cluster and head: packed bf16 dots plus
+// a 16-lane reduction).  The operands go from global memory straight into the
+// MFMA register layout: lane l of a wave loads, for cluster row l % 16, the
+// 16-byte chunks l / 16 + 4 j (j = 0..3) of the row, so every load instruction
+// reads 64 contiguous bytes of each of 16 rows and the four together read the
+// rows whole.  Query heads beyond the group are zero columns.
 // Algorithmic traffic per cluster: 256 B centroid + 4 B size read, 4*G B written.
 #include <hip/hip_ext.h>
 
@@ -16,26 +22,31 @@
 namespace dp {
 namespace {
 
-constexpr int kScoreThreads = 256;                   // 16 DPP rows
-#ifndef DP_SCORE_RB
-#define DP_SCORE_RB 4
-#endif
-constexpr int kScoreRowsPerGroup = DP_SCORE_RB;      // centroid rows in flight per 16-lane row
-constexpr int kScoreTile = (kScoreThreads / 16) * kScoreRowsPerGroup;  // clusters per workgroup
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+constexpr int kScoreThreads = 256;                   // 4 waves
+constexpr int kScoreHeads = 16;                      // query heads per pass: the columns of one MFMA tile
+constexpr int kScoreTile = (kScoreThreads / 64) * 16;  // clusters per workgroup and tile step: a 16-row MFMA tile per wave
+constexpr int kScoreMinWgs = 512;  // a launch keeps at least this many workgroups when it takes several tiles per wave
 
 struct ScoreArgs {
   const void *q, *k_centroids;
   const int32_t *seg_cluster_ptr, *cluster_sizes;
   float *logits;
   int32_t n_kv_heads, n_q_heads, group;
-  int32_t head0;       // this launch scores heads [head0, head0 + GH) of each group
+  int32_t head0;       // this launch scores heads [head0, head0 + 16) of each group
   int32_t uniform_kc;  // > 0: every segment has exactly this many clusters
   float sm_scale;
   int32_t *zero_words;  // nullable: n_zero words cleared by the first workgroup (counters of the step's later kernels)
   int32_t n_zero;
 };
 
-template <int GH>
+// RT = 16-row tiles per wave.  Every wave loads the group's queries once and all its centroid tiles up front: a
+// larger RT means fewer query loads per centroid byte and more bytes in flight per wave, at the price of fewer
+// workgroups (measured: 17.4 -> 15.2 us with RT = 4 on 32 segments of 8192 clusters, G = 8; 6.0 -> 5.7 us with
+// RT = 2 on 8 segments of 8192 clusters, G = 4).
+template <int RT>
 __global__ __launch_bounds__(kScoreThreads) void score_kernel(ScoreArgs a) {
   const int seg = blockIdx.y;
   if (a.zero_words && blockIdx.x == 0 && blockIdx.y == 0 && (int)threadIdx.x < a.n_zero) a.zero_words[threadIdx.x] = 0;
@@ -47,70 +58,79 @@ __global__ __launch_bounds__(kScoreThreads) void score_kernel(ScoreArgs a) {
     c0 = a.seg_cluster_ptr[seg];
     kc = a.seg_cluster_ptr[seg + 1] - c0;
   }
-  const int tile0 = blockIdx.x * kScoreTile;
-  if (tile0 >= kc) return;
-
-  const int lane16 = threadIdx.x & 15;
-  const int grp = threadIdx.x >> 4;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int r = lane & 15, kq = lane >> 4;
+  // the workgroup's kScoreTile * RT consecutive clusters; tile t of wave w is rows (4 t + w) * 16 .. + 15 of them
+  const int base = blockIdx.x * (kScoreTile * RT) + wave * 16;
+  if (base >= kc) return;  // no barrier below: a wave may leave alone
   const int b = seg / a.n_kv_heads, g = seg % a.n_kv_heads;
 
-  // issue the centroid loads first: this group owns rows tile0 + grp*RB .. +RB-1
-  const int i0 = tile0 + grp * kScoreRowsPerGroup;
-  uint4 raw[kScoreRowsPerGroup];
-  int size[kScoreRowsPerGroup];
+  // issue the centroid loads first.  A operand: row r of the tile, chunks kq + 4 j
+  uint4 A[RT][4];
 #pragma unroll
-  for (int k = 0; k < kScoreRowsPerGroup; ++k)
-    raw[k] = (i0 + k < kc) ? load_row_slice(a.k_centroids, (int64_t)(c0 + i0 + k), lane16) : make_uint4(0, 0, 0, 0);
-  // sizes: one dword per row, the same address for the 16 lanes of the group (a broadcast load; wider
-  // or masked loads of the four sizes measured slower)
+  for (int t = 0; t < RT; ++t) {
+    const int row = base + t * kScoreTile + r;
+    const bool live = row < kc;
+    const char *src = static_cast<const char *>(a.k_centroids) + (int64_t)(c0 + row) * kRowBytes + kq * 16;
 #pragma unroll
-  for (int k = 0; k < kScoreRowsPerGroup; ++k) size[k] = (i0 + k < kc) ? a.cluster_sizes[c0 + i0 + k] : 0;
-
-  // the group's query slices stay packed bf16
-  uint4 qv[GH];
-#pragma unroll
-  for (int j = 0; j < GH; ++j)
-    qv[j] = load_row_slice(a.q, (int64_t)b * a.n_q_heads + g * a.group + a.head0 + j, lane16);
-
-  // lane j of the group ends up with head j's logits of the group's RB consecutive clusters
-  float mine[kScoreRowsPerGroup];
-#pragma unroll
-  for (int k = 0; k < kScoreRowsPerGroup; ++k) {
-    mine[k] = 0.f;
-#pragma unroll
-    for (int j = 0; j < GH; ++j) {
-      const float d = row16_sum(dot8_bf16(qv[j], raw[k]));
-      if (lane16 == j) mine[k] = d;
-    }
+    for (int j = 0; j < 4; ++j) A[t][j] = live ? *reinterpret_cast<const uint4 *>(src + j * 64) : make_uint4(0, 0, 0, 0);
   }
-  if (lane16 < GH && i0 < kc) {
-    float *out = a.logits + (int64_t)a.group * c0 + (int64_t)(a.head0 + lane16) * kc + i0;
-    float v[kScoreRowsPerGroup];
+  // the lane's results are head r of the pass, clusters i0 .. i0 + 3 of each tile; their sizes: one dword each,
+  // the same address for the lanes of a group (a broadcast load; wider or masked loads measured slower)
+  const bool head_live = a.head0 + r < a.group;
+  int size[RT][4];
 #pragma unroll
-    for (int k = 0; k < kScoreRowsPerGroup; ++k) {
-      // ln s from the hardware log2 (1 ulp), exact for s = 1
-      v[k] = (size[k] > 0) ? fmaf(mine[k], a.sm_scale, __builtin_amdgcn_logf((float)size[k]) * 0.6931471805599453f)
-                           : -INFINITY;
-    }
-    if (kScoreRowsPerGroup == 4 && i0 + 3 < kc && (reinterpret_cast<uintptr_t>(out) & 15) == 0) {
-      *reinterpret_cast<float4 *>(out) = make_float4(v[0], v[1 % kScoreRowsPerGroup], v[2 % kScoreRowsPerGroup],
-                                                     v[3 % kScoreRowsPerGroup]);
-    } else {
+  for (int t = 0; t < RT; ++t) {
+    const int i0 = base + t * kScoreTile + 4 * kq;
 #pragma unroll
-      for (int k = 0; k < kScoreRowsPerGroup; ++k)
-        if (i0 + k < kc) out[k] = v[k];
+    for (int k = 0; k < 4; ++k) size[t][k] = (i0 + k < kc) ? a.cluster_sizes[c0 + i0 + k] : 0;
+  }
+  // B operand: query head r of the pass (a zero column beyond the group), the same chunks
+  uint4 Q[4];
+  {
+    const char *row = static_cast<const char *>(a.q) +
+                      ((int64_t)b * a.n_q_heads + g * a.group + (head_live ? a.head0 + r : 0)) * kRowBytes + kq * 16;
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+      Q[j] = head_live ? *reinterpret_cast<const uint4 *>(row + j * 64) : make_uint4(0, 0, 0, 0);
+  }
+#pragma unroll
+  for (int t = 0; t < RT; ++t) {
+    f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+      acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, A[t][j]),
+                                                    __builtin_bit_cast(bf16x8, Q[j]), acc, 0, 0, 0);
+    const int i0 = base + t * kScoreTile + 4 * kq;
+    if (head_live && i0 < kc) {
+      float *out = a.logits + (int64_t)a.group * c0 + (int64_t)(a.head0 + r) * kc + i0;
+      float v[4];
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {
+        // ln s from the hardware log2 (1 ulp), exact for s = 1
+        v[k] = (size[t][k] > 0)
+                   ? fmaf(acc[k], a.sm_scale, __builtin_amdgcn_logf((float)size[t][k]) * 0.6931471805599453f)
+                   : -INFINITY;
+      }
+      if (i0 + 3 < kc && (reinterpret_cast<uintptr_t>(out) & 15) == 0) {
+        *reinterpret_cast<float4 *>(out) = make_float4(v[0], v[1], v[2], v[3]);
+      } else {
+#pragma unroll
+        for (int k = 0; k < 4; ++k)
+          if (i0 + k < kc) out[k] = v[k];
+      }
     }
   }
 }
 
 }  // namespace
 
-template <int GH>
+template <int RT>
 void launch_one(const ScoreArgs &a, dim3 grid, hipStream_t s, hipEvent_t start, hipEvent_t stop) {
   if (start || stop)
-    hipExtLaunchKernelGGL(score_kernel<GH>, grid, dim3(kScoreThreads), 0, s, start, stop, 0, a);
+    hipExtLaunchKernelGGL(score_kernel<RT>, grid, dim3(kScoreThreads), 0, s, start, stop, 0, a);
   else
-    hipLaunchKernelGGL(score_kernel<GH>, grid, dim3(kScoreThreads), 0, s, a);
+    hipLaunchKernelGGL(score_kernel<RT>, grid, dim3(kScoreThreads), 0, s, a);
 }
 
 hipError_t launch_score(const CacheView &c, float *logits, hipStream_t s, hipEvent_t start, hipEvent_t stop,
@@ -128,24 +148,22 @@ hipError_t launch_score(const CacheView &c, float *logits, hipStream_t s, hipEve
   a.uniform_kc = c.uniform_kc;
   a.zero_words = n_zero <= kScoreThreads ? zero_words : nullptr;
   a.n_zero = n_zero;
-  const dim3 grid((c.max_clusters_per_seg + kScoreTile - 1) / kScoreTile, c.batch * c.n_kv_heads);
-  if (grid.x == 0 || grid.y == 0) return hipSuccess;
-  // heads of a group are scored 8/4/2/1 at a time (one pass when G is 1, 2, 4 or 8)
-  int h0 = 0;
-  while (h0 < c.group) {
-    const int left = c.group - h0;
-    const int gh = left >= 8 ? 8 : left >= 4 ? 4 : left >= 2 ? 2 : 1;
+  if (c.max_clusters_per_seg == 0 || c.batch * c.n_kv_heads == 0) return hipSuccess;
+  // tiles per wave: as many (1, 2 or 4) as still leave the launch kScoreMinWgs workgroups
+  const int64_t wgs1 = (int64_t)((c.max_clusters_per_seg + kScoreTile - 1) / kScoreTile) * c.batch * c.n_kv_heads;
+  const int rt = wgs1 >= 4 * kScoreMinWgs ? 4 : wgs1 >= 2 * kScoreMinWgs ? 2 : 1;
+  const dim3 grid((c.max_clusters_per_seg + kScoreTile * rt - 1) / (kScoreTile * rt), c.batch * c.n_kv_heads);
+  // the heads of a group are scored 16 at a time (one pass for G <= 16)
+  for (int h0 = 0; h0 < c.group; h0 += kScoreHeads) {
     a.head0 = h0;
     if (h0 > 0) a.zero_words = nullptr;  // cleared once, by the first pass
     // with several passes the events bracket the first pass's begin and the last pass's end
-    hipEvent_t ev0 = (h0 == 0) ? start : nullptr, ev1 = (h0 + gh >= c.group) ? stop : nullptr;
-    switch (gh) {
-      case 8: launch_one<8>(a, grid, s, ev0, ev1); break;
+    hipEvent_t ev0 = (h0 == 0) ? start : nullptr, ev1 = (h0 + kScoreHeads >= c.group) ? stop : nullptr;
+    switch (rt) {
       case 4: launch_one<4>(a, grid, s, ev0, ev1); break;
       case 2: launch_one<2>(a, grid, s, ev0, ev1); break;
       default: launch_one<1>(a, grid, s, ev0, ev1); break;
     }
-    h0 += gh;
   }
   return hipGetLastError();
 }
