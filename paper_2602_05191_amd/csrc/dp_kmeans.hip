@@ -13,10 +13,14 @@
 // A wave owns 16 x TM tokens (TM MFMA row tiles, the A operand, held in registers
 // for the whole kernel).  The workgroup walks the segment's centroids 64 at a time:
 // the block is fetched once from global memory by all 256 threads, kept in LDS
-// (double buffered, rows padded to 272 B so that the 16 rows an operand read
-// touches fall into different banks) and read from there by the four waves as
-// the B operand, so the next block's global latency hides behind 64 x TM MFMAs
-// per wave.  Operand layout of the instruction: lane l holds row l % 16 and the 8
+// (three blocks in rotation, rows padded to 272 B so that the 16 rows an operand
+// read touches fall into different banks) and read from there by the four waves
+// as the B operand: the operand read of the next tile is issued before the
+// current tile's MFMAs (also across block borders: the next block is already in
+// LDS), and the block after that travels global -> registers -> LDS behind them.
+// The register budget is held at 168 (three waves per SIMD): with two waves the
+// same loop is 20 % slower.
+// Operand layout of the instruction: lane l holds row l % 16 and the 8
 // consecutive k of block l / 16; the result tile holds, in lane l, column
 // l % 16 and rows 4 (l / 16) .. + 3.  The accumulator starts at -|c|^2 / 2 of
 // the lane's centroid column, so a result element IS the score.  Every lane
@@ -36,9 +40,6 @@ constexpr int kKmThreads = 256;
 #ifndef DP_KM_TM
 #define DP_KM_TM 4
 #endif
-#ifndef DP_KM_UNROLL
-#define DP_KM_UNROLL 1
-#endif
 constexpr int kKmTM = DP_KM_TM;                        // 16-token row tiles per wave
 constexpr int kKmTokensPerWave = 16 * kKmTM;
 constexpr int kKmTokensPerBlock = kKmTokensPerWave * (kKmThreads / 64);
@@ -46,6 +47,7 @@ constexpr int kKmTokensPerBlock = kKmTokensPerWave * (kKmThreads / 64);
 #define DP_KM_CB 64
 #endif
 constexpr int kKmCB = DP_KM_CB;                        // centroids per LDS block (a multiple of 64: 256 threads fetch 64 rows per pass)
+constexpr int kKmBufs = 3;                              // LDS blocks in rotation: computed on, next (already stored), being filled
 constexpr int kKmRowPad = kRowBytes + 16;              // LDS row stride: 68 words, 4 r mod 64 banks for row r
 
 struct KmArgs {
@@ -76,9 +78,9 @@ __device__ __forceinline__ uint4 operand_slice(const void *base, int64_t row, in
   return *reinterpret_cast<const uint4 *>(static_cast<const char *>(base) + row * kRowBytes + j * 64 + kq * 16);
 }
 
-__global__ __launch_bounds__(kKmThreads) void km_assign_kernel(KmArgs a) {
-  __shared__ __attribute__((aligned(16))) char s_c[2][kKmCB * kKmRowPad];
-  __shared__ float s_hn[2][kKmCB];
+__global__ __launch_bounds__(kKmThreads) __attribute__((amdgpu_waves_per_eu(3, 3))) void km_assign_kernel(KmArgs a) {
+  __shared__ __attribute__((aligned(16))) char s_c[kKmBufs][kKmCB * kKmRowPad];
+  __shared__ float s_hn[kKmBufs][kKmCB];
   const int seg = blockIdx.y;
   const int n = min(a.seg_rows[seg], a.max_rows);
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
@@ -139,33 +141,54 @@ __global__ __launch_bounds__(kKmThreads) void km_assign_kernel(KmArgs a) {
     }
   };
 
+  // B operand of tile tt of LDS block buf, and the lane's -|c|^2/2 start value
+  struct Tile {
+    uint4 B[4];
+    float hn;
+  };
+  auto read_tile = [&](int buf, int tt) {
+    Tile t;
+    const char *row = s_c[buf] + (tt * 16 + r) * kKmRowPad + kq * 16;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) t.B[j] = *reinterpret_cast<const uint4 *>(row + j * 64);
+    t.hn = s_hn[buf][tt * 16 + r];
+    return t;
+  };
+
+  // Three LDS blocks in rotation: block blk is computed on while block blk + 1 (stored one iteration earlier) is
+  // already readable, so the operand read of the NEXT tile is always issued before the current tile's MFMAs,
+  // across block borders too, and block blk + 2 travels global -> registers -> LDS behind them.
   const int n_blocks = (kc + kKmCB - 1) / kKmCB;
   if (n_blocks > 0) {
     fetch_block(0);
     store_block(0);
   }
+  if (n_blocks > 1) {
+    fetch_block(1);
+    store_block(1);
+  }
   __syncthreads();
+  Tile next = read_tile(0, 0);  // harmless when there is no block: never used
+  int buf = 0;
   for (int blk = 0; blk < n_blocks; ++blk) {
-    const int buf = blk & 1;
-    if (blk + 1 < n_blocks) fetch_block(blk + 1);  // in flight during this block's MFMAs
-#pragma unroll DP_KM_UNROLL
+    const int buf1 = buf == kKmBufs - 1 ? 0 : buf + 1, buf2 = buf1 == kKmBufs - 1 ? 0 : buf1 + 1;
+    if (blk + 2 < n_blocks) fetch_block(blk + 2);  // in flight during this block's MFMAs
+#pragma unroll 1
     for (int tt = 0; tt < kKmCB / 16; ++tt) {
-      const char *row = s_c[buf] + (tt * 16 + r) * kKmRowPad + kq * 16;
-      uint4 B[4];
-#pragma unroll
-      for (int j = 0; j < 4; ++j) B[j] = *reinterpret_cast<const uint4 *>(row + j * 64);
-      const float hn = s_hn[buf][tt * 16 + r];
+      const Tile cur = next;
+      const bool last = tt == kKmCB / 16 - 1;
+      next = read_tile(last ? buf1 : buf, last ? 0 : tt + 1);  // past the last block: a stale block, never used
       const int c = blk * kKmCB + tt * 16 + r;  // this lane's centroid column
       // TM independent accumulation chains, advanced together: no MFMA waits for its predecessor
       f32x4 acc[kKmTM];
 #pragma unroll
-      for (int tm = 0; tm < kKmTM; ++tm) acc[tm] = f32x4{-hn, -hn, -hn, -hn};
+      for (int tm = 0; tm < kKmTM; ++tm) acc[tm] = f32x4{-cur.hn, -cur.hn, -cur.hn, -cur.hn};
 #pragma unroll
       for (int j = 0; j < 4; ++j)
 #pragma unroll
         for (int tm = 0; tm < kKmTM; ++tm)
           acc[tm] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, A[tm][j]),
-                                                            __builtin_bit_cast(bf16x8, B[j]), acc[tm], 0, 0, 0);
+                                                            __builtin_bit_cast(bf16x8, cur.B[j]), acc[tm], 0, 0, 0);
 #pragma unroll
       for (int tm = 0; tm < kKmTM; ++tm)
 #pragma unroll
@@ -175,9 +198,10 @@ __global__ __launch_bounds__(kKmThreads) void km_assign_kernel(KmArgs a) {
           bidx[tm][i] = better ? c : bidx[tm][i];
         }
     }
-    // the other buffer was last read in the previous iteration, which ended with a barrier
-    if (blk + 1 < n_blocks) store_block(buf ^ 1);
+    // buf2 held block blk - 1, last read before the barrier that ended the previous iteration
+    if (blk + 2 < n_blocks) store_block(buf2);
     __syncthreads();
+    buf = buf1;
   }
 
   // merge the 16 column classes of each token: max score, lower index on a tie (DPP row exchange)

@@ -65,7 +65,18 @@ __global__ __launch_bounds__(kScoreThreads) void score_kernel(ScoreArgs a) {
   if (base >= kc) return;  // no barrier below: a wave may leave alone
   const int b = seg / a.n_kv_heads, g = seg % a.n_kv_heads;
 
-  // issue the centroid loads first.  A operand: row r of the tile, chunks kq + 4 j
+  const bool head_live = a.head0 + r < a.group;
+  // B operand first (its few cache lines are hot, and loads return in issue order: behind the centroid stream the
+  // queries cost 0.25 us more): query head r of the pass (a zero column beyond the group), chunks kq + 4 j
+  uint4 Q[4];
+  {
+    const char *row = static_cast<const char *>(a.q) +
+                      ((int64_t)b * a.n_q_heads + g * a.group + (head_live ? a.head0 + r : 0)) * kRowBytes + kq * 16;
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+      Q[j] = head_live ? *reinterpret_cast<const uint4 *>(row + j * 64) : make_uint4(0, 0, 0, 0);
+  }
+  // A operand: row r of the tile, the same chunks
   uint4 A[RT][4];
 #pragma unroll
   for (int t = 0; t < RT; ++t) {
@@ -77,22 +88,12 @@ __global__ __launch_bounds__(kScoreThreads) void score_kernel(ScoreArgs a) {
   }
   // the lane's results are head r of the pass, clusters i0 .. i0 + 3 of each tile; their sizes: one dword each,
   // the same address for the lanes of a group (a broadcast load; wider or masked loads measured slower)
-  const bool head_live = a.head0 + r < a.group;
   int size[RT][4];
 #pragma unroll
   for (int t = 0; t < RT; ++t) {
     const int i0 = base + t * kScoreTile + 4 * kq;
 #pragma unroll
     for (int k = 0; k < 4; ++k) size[t][k] = (i0 + k < kc) ? a.cluster_sizes[c0 + i0 + k] : 0;
-  }
-  // B operand: query head r of the pass (a zero column beyond the group), the same chunks
-  uint4 Q[4];
-  {
-    const char *row = static_cast<const char *>(a.q) +
-                      ((int64_t)b * a.n_q_heads + g * a.group + (head_live ? a.head0 + r : 0)) * kRowBytes + kq * 16;
-#pragma unroll
-    for (int j = 0; j < 4; ++j)
-      Q[j] = head_live ? *reinterpret_cast<const uint4 *>(row + j * 64) : make_uint4(0, 0, 0, 0);
   }
 #pragma unroll
   for (int t = 0; t < RT; ++t) {
