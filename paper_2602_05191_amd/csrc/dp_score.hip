@@ -2,18 +2,26 @@
 //   logit[h][i] = sm_scale * (q_h . C_i) + ln s_i
 // for every cluster i of a KV segment and every query head h of its GQA group.
 //
-// HBM-bound streaming kernel: the key-centroid matrix is read exactly once
+// HBM-bound streaming kernels: the key-centroid matrix is read exactly once
 // (256 B per cluster) and each row is scored against all G query heads of the
-// group at once.  The scores of 16 clusters against up to 16 query heads are one
-// [16 x 128] x [128 x 16] contraction, done by four v_mfma_f32_16x16x32_bf16
-// (64 matrix-core cycles per 16 clusters, whatever G is; the same dots on the
-// vector ALU take 2.25 instructions per cluster and head: packed bf16 dots plus
-// a 16-lane reduction).  The operands go from global memory straight into the
-// MFMA register layout: lane l of a wave loads, for cluster row l % 16, the
-// 16-byte chunks l / 16 + 4 j (j = 0..3) of the row, so every load instruction
-// reads 64 contiguous bytes of each of 16 rows and the four together read the
-// rows whole.  Query heads beyond the group are zero columns.
-// Algorithmic traffic per cluster: 256 B centroid + 4 B size read, 4*G B written.
+// group at once.  Algorithmic traffic per cluster: 256 B centroid + 4 B size
+// read, 4*G B written.  Two formulations, chosen by G:
+//   G <= 4  vector ALU: packed bf16 dots (v_dot2c_f32_bf16) and a 16-lane DPP
+//           reduction per row and head, 2.25 instructions per cluster and head,
+//           behind whole-row loads (every load instruction reads 4 rows of 256 B)
+//   G >  4  matrix core: the scores of 16 clusters against up to 16 heads are one
+//           [16 x 128] x [128 x 16] contraction, four v_mfma_f32_16x16x32_bf16
+//           (64 matrix-core cycles per 16 clusters, whatever G is).  The operands
+//           go from global memory straight into the MFMA register layout: lane l
+//           loads, for cluster row l % 16, the 16-byte chunks l / 16 + 4 j of the
+//           row, so a load instruction reads 64 contiguous bytes of 16 rows and
+//           the four together read the rows whole.  Heads beyond the group are
+//           zero columns.
+// Measured (one MI355X, cold centroids): G = 8, 32 x 8192 clusters: 17.0 us on the
+// vector ALU, 15.0 us on the matrix core; G = 4: 8 x 8192 clusters 5.8 vs 5.4 us,
+// 128 x 1280 clusters 10.0 vs 10.7 us, 128 ragged segments of 512..2048 clusters
+// 12.3 vs 14.5 us (the 64-byte load pattern streams slower over many short
+// segments), so G = 4 stays on the vector ALU.
 #include <hip/hip_ext.h>
 
 #include "dp_device.hpp"
@@ -28,6 +36,7 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 constexpr int kScoreThreads = 256;                   // 4 waves
 constexpr int kScoreHeads = 16;                      // query heads per pass: the columns of one MFMA tile
 constexpr int kScoreTile = (kScoreThreads / 64) * 16;  // clusters per workgroup and tile step: a 16-row MFMA tile per wave
+constexpr int kScoreValuMaxGroup = 4;  // groups up to this size are scored on the vector ALU, larger ones on the matrix core
 constexpr int kScoreMinWgs = 512;  // a launch keeps at least this many workgroups when it takes several tiles per wave
 
 struct ScoreArgs {
@@ -41,6 +50,80 @@ struct ScoreArgs {
   int32_t *zero_words;  // nullable: n_zero words cleared by the first workgroup (counters of the step's later kernels)
   int32_t n_zero;
 };
+
+// The same scores on the vector ALU, for small groups: a 16-lane DPP row owns kValuRows consecutive centroid rows
+// (16 B per lane: every load instruction reads 4 whole rows), each lane's 8 products are accumulated by the packed
+// bf16 dot instruction and the 16 partial dots are summed with DPP adds.  2.25 vector instructions per cluster and
+// head: up to G = 4 they hide behind the loads and the wholly contiguous load pattern streams faster.
+constexpr int kValuRows = 4;  // centroid rows in flight per 16-lane row; 16 rows x 4 = the 64 clusters of a workgroup
+template <int GH>
+__global__ __launch_bounds__(kScoreThreads) void score_valu_kernel(ScoreArgs a) {
+  const int seg = blockIdx.y;
+  if (a.zero_words && blockIdx.x == 0 && blockIdx.y == 0 && (int)threadIdx.x < a.n_zero) a.zero_words[threadIdx.x] = 0;
+  int c0, kc;
+  if (a.uniform_kc > 0) {  // no CSR lookup in front of the centroid loads
+    c0 = seg * a.uniform_kc;
+    kc = a.uniform_kc;
+  } else {
+    c0 = a.seg_cluster_ptr[seg];
+    kc = a.seg_cluster_ptr[seg + 1] - c0;
+  }
+  const int tile0 = blockIdx.x * kScoreTile;  // 64 clusters per workgroup here too
+  if (tile0 >= kc) return;
+
+  const int lane16 = threadIdx.x & 15;
+  const int grp = threadIdx.x >> 4;
+  const int b = seg / a.n_kv_heads, g = seg % a.n_kv_heads;
+
+  // issue the centroid loads first: this group owns rows tile0 + grp*RB .. +RB-1
+  const int i0 = tile0 + grp * kValuRows;
+  uint4 raw[kValuRows];
+  int size[kValuRows];
+#pragma unroll
+  for (int k = 0; k < kValuRows; ++k)
+    raw[k] = (i0 + k < kc) ? load_row_slice(a.k_centroids, (int64_t)(c0 + i0 + k), lane16) : make_uint4(0, 0, 0, 0);
+  // sizes: one dword per row, the same address for the 16 lanes of the group (a broadcast load; wider
+  // or masked loads of the four sizes measured slower)
+#pragma unroll
+  for (int k = 0; k < kValuRows; ++k) size[k] = (i0 + k < kc) ? a.cluster_sizes[c0 + i0 + k] : 0;
+
+  // the group's query slices stay packed bf16
+  uint4 qv[GH];
+#pragma unroll
+  for (int j = 0; j < GH; ++j)
+    qv[j] = load_row_slice(a.q, (int64_t)b * a.n_q_heads + g * a.group + a.head0 + j, lane16);
+
+  // lane j of the group ends up with head j's logits of the group's RB consecutive clusters
+  float mine[kValuRows];
+#pragma unroll
+  for (int k = 0; k < kValuRows; ++k) {
+    mine[k] = 0.f;
+#pragma unroll
+    for (int j = 0; j < GH; ++j) {
+      const float d = row16_sum(dot8_bf16(qv[j], raw[k]));
+      if (lane16 == j) mine[k] = d;
+    }
+  }
+  if (lane16 < GH && i0 < kc) {
+    float *out = a.logits + (int64_t)a.group * c0 + (int64_t)(a.head0 + lane16) * kc + i0;
+    float v[kValuRows];
+#pragma unroll
+    for (int k = 0; k < kValuRows; ++k) {
+      // ln s from the hardware log2 (1 ulp), exact for s = 1
+      v[k] = (size[k] > 0) ? fmaf(mine[k], a.sm_scale, __builtin_amdgcn_logf((float)size[k]) * 0.6931471805599453f)
+                           : -INFINITY;
+    }
+    if (kValuRows == 4 && i0 + 3 < kc && (reinterpret_cast<uintptr_t>(out) & 15) == 0) {
+      *reinterpret_cast<float4 *>(out) = make_float4(v[0], v[1 % kValuRows], v[2 % kValuRows],
+                                                     v[3 % kValuRows]);
+    } else {
+#pragma unroll
+      for (int k = 0; k < kValuRows; ++k)
+        if (i0 + k < kc) out[k] = v[k];
+    }
+  }
+}
+
 
 // RT = 16-row tiles per wave.  Every wave loads the group's queries once and all its centroid tiles up front: a
 // larger RT means fewer query loads per centroid byte and more bytes in flight per wave, at the price of fewer
@@ -126,6 +209,14 @@ __global__ __launch_bounds__(kScoreThreads) void score_kernel(ScoreArgs a) {
 
 }  // namespace
 
+template <int GH>
+void launch_valu(const ScoreArgs &a, dim3 grid, hipStream_t s, hipEvent_t start, hipEvent_t stop) {
+  if (start || stop)
+    hipExtLaunchKernelGGL(score_valu_kernel<GH>, grid, dim3(kScoreThreads), 0, s, start, stop, 0, a);
+  else
+    hipLaunchKernelGGL(score_valu_kernel<GH>, grid, dim3(kScoreThreads), 0, s, a);
+}
+
 template <int RT>
 void launch_one(const ScoreArgs &a, dim3 grid, hipStream_t s, hipEvent_t start, hipEvent_t stop) {
   if (start || stop)
@@ -150,6 +241,24 @@ hipError_t launch_score(const CacheView &c, float *logits, hipStream_t s, hipEve
   a.zero_words = n_zero <= kScoreThreads ? zero_words : nullptr;
   a.n_zero = n_zero;
   if (c.max_clusters_per_seg == 0 || c.batch * c.n_kv_heads == 0) return hipSuccess;
+  if (c.group <= kScoreValuMaxGroup) {
+    // one pass: 4, 2 or 1 heads at a time
+    const dim3 vgrid((c.max_clusters_per_seg + kScoreTile - 1) / kScoreTile, c.batch * c.n_kv_heads);
+    int h0 = 0;
+    while (h0 < c.group) {
+      const int left = c.group - h0, gh = left >= 4 ? 4 : left >= 2 ? 2 : 1;
+      a.head0 = h0;
+      if (h0 > 0) a.zero_words = nullptr;  // cleared once, by the first pass
+      hipEvent_t ev0 = (h0 == 0) ? start : nullptr, ev1 = (h0 + gh >= c.group) ? stop : nullptr;
+      switch (gh) {
+        case 4: launch_valu<4>(a, vgrid, s, ev0, ev1); break;
+        case 2: launch_valu<2>(a, vgrid, s, ev0, ev1); break;
+        default: launch_valu<1>(a, vgrid, s, ev0, ev1); break;
+      }
+      h0 += gh;
+    }
+    return hipGetLastError();
+  }
   // tiles per wave: as many (1, 2 or 4) as still leave the launch kScoreMinWgs workgroups
   const int64_t wgs1 = (int64_t)((c.max_clusters_per_seg + kScoreTile - 1) / kScoreTile) * c.batch * c.n_kv_heads;
   const int rt = wgs1 >= 4 * kScoreMinWgs ? 4 : wgs1 >= 2 * kScoreMinWgs ? 2 : 1;

@@ -122,7 +122,21 @@ def case_very_many_heads():
     return pin_sink_and_window(c, first=1, last=2), 0.95, 0.9
 
 
-CASES = {f.__name__[5:]: f for f in (case_cfg0, case_flat_ragged, case_mixed_sharpness, case_gqa8_pareto, case_gqa1,
+def case_gqa16_and_6_ragged():
+    # the largest supported group (16 heads share a segment: every column of the scoring kernel's matrix tile is a
+    # head), ragged segments whose cluster counts are not multiples of the 16-row tile, flat and peaked heads
+    c = make_cache(batch=3, n_kv_heads=2, n_q_heads=32, context=[2100, 37, 1333], mean_cluster=7, size_hi=32,
+                   q_scale=lambda rng, b, h: [0.3, 2.0, 0.7, 4.0][h % 4], seed=25)
+    return c, 0.95, 0.9
+
+
+def case_gqa6():
+    c = make_cache(batch=2, n_kv_heads=3, n_q_heads=18, context=[999, 3001], mean_cluster=9, size_hi=40,
+                   q_scale=lambda rng, b, h: [0.4, 3.0][h % 2], seed=26)
+    return c, 0.9, 0.8
+
+
+CASES = {f.__name__[5:]: f for f in (case_gqa16_and_6_ragged, case_gqa6, case_cfg0, case_flat_ragged, case_mixed_sharpness, case_gqa8_pareto, case_gqa1,
                                      case_gqa3_and_12, case_gqa12, case_many_clusters, case_single_cluster,
                                      case_giant_cluster, case_empty_clusters_and_segment, case_pinned_peaked,
                                      case_pinned_flat_ragged, case_pinned_many_clusters, case_many_heads,
