@@ -308,6 +308,29 @@ def main():
         ab["gather_buffer_rows_per_head"] = cap
         del kb, vb
 
+    # ---- A/B: selection per GQA group (every head of a group attends over the union of the group's per-head
+    # sets, so a row is read once per group; NOT the same result: each head attends a superset of its own sets).
+    # Whole step, wall clock, same rotating replicas; the rows each variant attends are reported next to it. ----
+    n_seg = cache.batch * cache.n_kv_heads
+    u_ids = torch.empty((n_seg, max(mk, 1)), dtype=torch.int32, device=dev)
+    u_ne = torch.empty(n_seg, dtype=torch.int32, device=dev)
+    u_nr = torch.empty(n_seg, dtype=torch.int32, device=dev)
+    union_us = wall_time(lambda i: dp.dp_group_union_decode_attention(probs[i % L], p1, p2, out, lse, u_ids, u_ne, u_nr, ws),
+                         n_base)
+    dp.dp_group_union_decode_attention(pr0, p1, p2, out, lse, u_ids, u_ne, u_nr, ws)
+    torch.cuda.synchronize()
+    u_ids_h, u_ne_h, u_nr_h = u_ids.cpu().numpy(), u_ne.cpu().numpy(), u_nr.cpu().numpy()
+    union_rows = 0
+    for seg in range(n_seg):
+        c0 = int(cache.seg_cluster_ptr[seg])
+        union_rows += int(cache.cluster_sizes[c0 + u_ids_h[seg, :u_ne_h[seg]]].sum()) + int(u_nr_h[seg] - u_ne_h[seg])
+    ab["group_union"] = {"entry_point": "dp_group_union_decode_attention", "step_us": round(union_us, 3),
+                         "rows_read_once_per_group": union_rows,
+                         "rows_attended_per_head_times_heads": union_rows * cache.group,
+                         "note": "every head attends the union of its group's sets: a superset of its own"}
+    dp.dp_decode_attention(pr0, p1, p2, out, lse, ws, None, None, None)
+    torch.cuda.synchronize()
+
     # ---- the prefill-side build of this workload's cache (Sec. 4.1, Eq. 2): token-order K / V + cluster ids ->
     # cluster-contiguous rows, sizes, offsets, centroids.  One call per layer, not part of the decode step. ----
     from workloads import token_order_input

@@ -133,6 +133,28 @@ dp_status dp_sparse_decode(const dp_problem *problem, const int32_t *sel_ids, co
                            const int32_t *n_retained, const int32_t *n_exact_tokens, void *out, dp_dtype out_dtype,
                            float *lse, void *workspace, size_t workspace_bytes, void *stream);
 
+/* A/B variant: selection per GQA group.  The paper states the method for a
+ * single query; its model has groups of 4 query heads per KV head (Sec. 5.1) and
+ * the text does not say whether the two top-p sets are taken per query head or
+ * per group.  The library's path takes them per head.  This entry point takes
+ * them per head (exactly as dp_topp_select) and then lets EVERY head of a group
+ * attend (Eq. 8, Eq. 9) over the union of the group's sets:
+ *   exact(group)  = union over the heads h of C_exact(h)
+ *   approx(group) = (union over h of C_p1(h)) minus exact(group)
+ * so that a K / V row is read once per group.  Each head attends a superset of
+ * its own selection, so the output differs from dp_decode_attention's (it lies
+ * between it and dense attention).  Outputs besides out / lse (lse nullable):
+ *   union_ids    int32 [batch*n_kv_heads, max_clusters_per_seg]  per segment:
+ *                exact ids ascending, then approximated ids ascending (segment-local)
+ *   n_exact_u    int32 [batch*n_kv_heads]
+ *   n_retained_u int32 [batch*n_kv_heads]   exact + approximated
+ * all device, caller-owned.  Workspace as dp_decode_attention.  DP_ERR_UNSUPPORTED
+ * for more than 65536 clusters per segment. */
+dp_status dp_group_union_decode_attention(const dp_problem *problem, float p1, float p2, void *out,
+                                          dp_dtype out_dtype, float *lse, int32_t *union_ids, int32_t *n_exact_u,
+                                          int32_t *n_retained_u, void *workspace, size_t workspace_bytes,
+                                          void *stream);
+
 /* A/B variant of dp_sparse_decode in the structure the paper describes for its
  * own kernels (Sec. 4.4): the K / V rows of every head's exact clusters are first
  * copied into a contiguous per-head buffer (k_buf, v_buf: bf16

@@ -251,6 +251,35 @@ class Oracle:
                           k1=k1.reshape(self.batch, self.n_q_heads), k2=k2.reshape(self.batch, self.n_q_heads),
                           order=order, threads=int(used))
 
+    # ---- selection per GQA group (a reading the paper leaves open: it states the method for one query,
+    # its model shares a KV head among 4 query heads, Sec. 5.1) ----------------------------------
+    def group_union_sets(self, b: int, g: int, p1: float, p2: float, flags: int = 0):
+        """Union of the per-head sets of KV head g of sequence b: (exact ids, approximated ids), ascending.
+        exact = union of the heads' exact sets; approximated = union of their retained sets minus that."""
+        G = self.n_q_heads // self.n_kv_heads
+        exact, retained = set(), set()
+        for h in range(g * G, (g + 1) * G):
+            sel = self.select(self.centroid_logits(b, h), p1, p2, flags, pinned=self.pinned_clusters(b, h))
+            exact.update(int(i) for i in sel.exact)
+            retained.update(int(i) for i in sel.retained)
+        return np.array(sorted(exact), dtype=np.int32), np.array(sorted(retained - exact), dtype=np.int32)
+
+    def group_union_step(self, p1: float, p2: float, flags: int = 0):
+        """Every head attends (Eq. 8, Eq. 9) over the union sets of its group.
+        -> out [batch, n_q_heads, d], lse [batch, n_q_heads], {(b, g): (exact ids, approximated ids)}"""
+        G = self.n_q_heads // self.n_kv_heads
+        out = np.zeros((self.batch, self.n_q_heads, self.d), dtype=np.float64)
+        lse = np.full((self.batch, self.n_q_heads), -np.inf, dtype=np.float64)
+        sets = {}
+        for b in range(self.batch):
+            for g in range(self.n_kv_heads):
+                ex, ap = self.group_union_sets(b, g, p1, p2, flags)
+                sets[(b, g)] = (ex, ap)
+                for h in range(g * G, (g + 1) * G):
+                    if ex.size + ap.size:
+                        out[b, h], lse[b, h] = self.mixed_attention(b, h, ex, ap)
+        return out, lse, sets
+
     def dense_step(self, n_threads: int = 1):
         nh = self.batch * self.n_q_heads
         out = np.empty((self.batch, self.n_q_heads, self.d), dtype=np.float64)

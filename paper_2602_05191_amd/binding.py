@@ -25,6 +25,7 @@ _LIB_PATH = os.path.join(_PKG, "libdp_hip.so")
 EXPORTS = ["dp_workspace_bytes", "dp_logits_count", "dp_get_workspace_layout", "dp_score_centroids",
            "dp_score_centroids_timed",
            "dp_topp_select", "dp_topp_select_sorted", "dp_topk_select", "dp_sparse_decode", "dp_sparse_decode_gathered", "dp_decode_attention",
+           "dp_group_union_decode_attention",
            "dp_decode_attention_timed", "dp_budget_decode_attention", "dp_dense_decode", "dp_build_workspace_bytes", "dp_build_cluster_cache", "dp_kmeans_workspace_bytes",
            "dp_kmeans_assign",
            "dp_status_string"]
@@ -99,6 +100,8 @@ def load_library():
     L.dp_topp_select_sorted.argtypes = [PP, V, F, F, V, V, V, V, V]
     L.dp_sparse_decode_gathered.restype = I
     L.dp_sparse_decode_gathered.argtypes = [PP, V, V, V, V, I, V, V, V, I, V, C.c_size_t, V]
+    L.dp_group_union_decode_attention.restype = I
+    L.dp_group_union_decode_attention.argtypes = [PP, F, F, V, I, V, V, V, V, V, C.c_size_t, V]
     L.dp_topk_select.restype = I
     L.dp_topk_select.argtypes = [PP, V, I, I, V, V, V, V, V]
     L.dp_budget_decode_attention.restype = I
@@ -374,6 +377,24 @@ def dp_sparse_decode_gathered(problem: Problem, sel_ids: torch.Tensor, n_exact: 
                                                     _ptr(workspace), workspace.numel() * workspace.element_size(),
                                                     _stream(stream)),
            "dp_sparse_decode_gathered")
+
+
+def dp_group_union_decode_attention(problem: Problem, p1: float, p2: float, out: torch.Tensor,
+                                    lse: Optional[torch.Tensor], union_ids: torch.Tensor, n_exact_u: torch.Tensor,
+                                    n_retained_u: torch.Tensor, workspace: torch.Tensor, stream=None) -> None:
+    """A/B variant: every head of a GQA group attends over the union of the group's per-head sets."""
+    dt = {torch.float32: DP_F32, torch.bfloat16: DP_BF16}[out.dtype]
+    n_seg = problem.dc.batch * problem.dc.n_kv_heads
+    assert out.is_contiguous() and out.numel() == problem.nh * problem.dc.head_dim
+    assert union_ids.dtype == torch.int32 and union_ids.numel() >= n_seg * problem.dc.max_clusters_per_seg
+    for t in (n_exact_u, n_retained_u):
+        assert t.dtype == torch.int32 and t.numel() >= n_seg
+    _check(load_library().dp_group_union_decode_attention(problem.ref, p1, p2, _ptr(out), dt, _ptr(lse),
+                                                          _ptr(union_ids), _ptr(n_exact_u), _ptr(n_retained_u),
+                                                          _ptr(workspace),
+                                                          workspace.numel() * workspace.element_size(),
+                                                          _stream(stream)),
+           "dp_group_union_decode_attention")
 
 
 def dp_kmeans_workspace_bytes(prefill: Prefill) -> int:

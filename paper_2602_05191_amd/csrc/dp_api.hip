@@ -320,6 +320,44 @@ dp_status dp_sparse_decode_gathered(const dp_problem *problem, const int32_t *se
   return DP_OK;
 }
 
+dp_status dp_group_union_decode_attention(const dp_problem *problem, float p1, float p2, void *out,
+                                          dp_dtype out_dtype, float *lse, int32_t *union_ids, int32_t *n_exact_u,
+                                          int32_t *n_retained_u, void *workspace, size_t workspace_bytes,
+                                          void *stream) {
+  dp_status st = check_common(problem);
+  if (st != DP_OK) return st;
+  if (!p_in_domain(p1, p2)) return DP_ERR_INVALID_ARG;
+  if (out_dtype != DP_BF16 && out_dtype != DP_F32) return DP_ERR_UNSUPPORTED;
+  if (problem->max_clusters_per_seg > dp::kGroupUnionMaxClusters) return DP_ERR_UNSUPPORTED;
+  if (!out || !workspace || !n_exact_u || !n_retained_u) return DP_ERR_INVALID_ARG;
+  if (problem->max_clusters_per_seg > 0 && !union_ids) return DP_ERR_INVALID_ARG;
+  if (workspace_bytes < dp_workspace_bytes(problem)) return DP_ERR_WORKSPACE_TOO_SMALL;
+  if (reinterpret_cast<uintptr_t>(workspace) % 256) return DP_ERR_INVALID_ARG;
+  const dp::CacheView c = view_of(problem);
+  const Workspace w = carve(problem, workspace);
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  // per-head sets as in dp_topp_select, into the workspace
+  if (dp::launch_score(c, w.logits, s) != hipSuccess) return DP_ERR_HIP;
+  const dp::SelectOut per_head{w.sel_ids, w.n_exact, w.n_retained, w.n_exact_tokens};
+  const dp::Plan none{nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, 0};
+  const dp::AttnOut nowhere{nullptr, nullptr, 0};
+  if (dp::launch_select(c, w.logits, top_p_rule(problem, p1, p2), per_head, none, nowhere, s) != hipSuccess)
+    return DP_ERR_HIP;
+  if (dp::launch_group_union(c, w.sel_ids, w.n_exact, w.n_retained, union_ids, n_exact_u, n_retained_u, s) != hipSuccess)
+    return DP_ERR_HIP;
+  // the stage-3 plan of the union lists: the planner sees one "head" per segment
+  dp::CacheView per_seg = c;
+  per_seg.n_q_heads = c.n_kv_heads;
+  per_seg.group = 1;
+  if (dp::launch_plan(per_seg, union_ids, n_exact_u, n_retained_u, nullptr, w.plan, nowhere, s) != hipSuccess)
+    return DP_ERR_HIP;
+  const dp::AttnOut attn{out, lse, out_dtype == DP_BF16};
+  const int splits = w.splits < 64 ? w.splits : 64;
+  if (dp::launch_group_decode(c, n_exact_u, n_retained_u, w.plan, w.partials, splits, attn, s) != hipSuccess)
+    return DP_ERR_HIP;
+  return DP_OK;
+}
+
 dp_status dp_decode_attention(const dp_problem *problem, float p1, float p2, void *out, dp_dtype out_dtype,
                               float *lse, int32_t *n_exact, int32_t *n_retained, int32_t *n_exact_tokens,
                               void *workspace, size_t workspace_bytes, void *stream) {

@@ -95,6 +95,17 @@ hipError_t launch_select_sorted(const CacheView &c, const float *logits, const S
 hipError_t launch_gather_rows(const CacheView &c, const int32_t *n_exact, const Plan &plan, void *k_buf, void *v_buf,
                               int rows_cap, hipStream_t s);
 
+// A/B variant: selection per GQA group (dp_union.hip).  launch_group_union turns the heads' lists into one
+// list per segment (exact ids ascending, then approximated ids ascending); launch_group_decode attends every head of
+// a group over its segment's list (seg_plan: a Plan built with segments in the place of heads; partials: room for
+// nh * splits * (kHeadDim + 2) floats).
+constexpr int kGroupUnionMaxClusters = 65536;
+hipError_t launch_group_union(const CacheView &c, const int32_t *sel_ids, const int32_t *n_exact,
+                              const int32_t *n_retained, int32_t *union_ids, int32_t *n_exact_u,
+                              int32_t *n_retained_u, hipStream_t s);
+hipError_t launch_group_decode(const CacheView &c, const int32_t *n_exact_u, const int32_t *n_retained_u,
+                               const Plan &seg_plan, float *partials, int splits, const AttnOut &attn, hipStream_t s);
+
 // Dense attention over rows [seg_row_base[seg], + seg_rows[seg]) of every segment for all its query heads.
 // partials: room for nh * max_splits * (kHeadDim + 2) floats.
 hipError_t launch_dense(const CacheView &c, const int32_t *seg_rows, float *partials, int max_splits,

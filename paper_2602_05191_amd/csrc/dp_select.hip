@@ -987,7 +987,7 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(PlanArgs a) {
     if (a.n_exact_tokens) a.n_exact_tokens[head] = n_tok;
     if (R == 0 && a.lse) a.lse[head] = -INFINITY;
   }
-  if (R == 0 && tid < kHeadDim) store_out(a.attn_out, a.out_is_bf16, head, tid, 0.f);
+  if (R == 0 && a.attn_out && tid < kHeadDim) store_out(a.attn_out, a.out_is_bf16, head, tid, 0.f);
 }
 
 template <int E, int T>

@@ -101,3 +101,45 @@ def test_full_size_cfg2_with_sink_and_window_pinned():
     np.testing.assert_allclose(g.out, r.out, atol=H.OUT_MAX_ABS)
     assert min(len(e) for e in g.exact) >= 5
     print(f"[cfg2 pinned] max-abs {worst:.2e} rel-L2 {rel:.2e}")
+
+
+def test_full_size_cfg4_group_union_variant():
+    """The group-union A/B variant at cfg 4 (groups of 8, flat and peaked heads): the union lists equal the
+    union of the per-head sets of the one-call path on the same inputs (the same kernels: bit-exact), and a
+    sample of heads (one per segment, alternating flat and peaked) equals the oracle's Eq. 8 / Eq. 9 over
+    the union sets."""
+    import torch
+    import paper_2602_05191_amd as dp
+    cache = make_config(4)
+    orc = oracle.Oracle(cache)
+    per_head = H.gpu_decode_attention(cache, cache.p1, cache.p2)
+    n_seg, G = cache.batch * cache.n_kv_heads, cache.group
+    nh, mk = cache.batch * cache.n_q_heads, cache.max_clusters_per_seg
+    dc = dp.DeviceCache.from_host(cache)
+    pr = dp.Problem(dc)
+    ws = torch.zeros(dp.dp_workspace_bytes(pr), dtype=torch.uint8, device="cuda:0")
+    out = torch.full((cache.batch, cache.n_q_heads, 128), float("nan"), dtype=torch.float32, device="cuda:0")
+    lse = torch.full((nh,), float("nan"), dtype=torch.float32, device="cuda:0")
+    uid = torch.full((n_seg, mk), -7, dtype=torch.int32, device="cuda:0")
+    neu = torch.full((n_seg,), -7, dtype=torch.int32, device="cuda:0")
+    nru = neu.clone()
+    dp.dp_group_union_decode_attention(pr, cache.p1, cache.p2, out, lse, uid, neu, nru, ws)
+    torch.cuda.synchronize()
+    uid, neu, nru = uid.cpu().numpy(), neu.cpu().numpy(), nru.cpu().numpy()
+    out, lse = out.cpu().numpy(), lse.cpu().numpy().reshape(cache.batch, cache.n_q_heads)
+    assert np.isfinite(out).all()
+    worst = 0.0
+    for seg in range(n_seg):
+        b, g = divmod(seg, cache.n_kv_heads)
+        heads = [b * cache.n_q_heads + g * G + j for j in range(G)]
+        ex_want = set().union(*[set(per_head.exact[i].tolist()) for i in heads])
+        rt_want = set().union(*[set(per_head.exact[i].tolist()) | set(per_head.approx[i].tolist()) for i in heads])
+        ex_got, ap_got = uid[seg, :neu[seg]], uid[seg, neu[seg]:nru[seg]]
+        assert ex_got.tolist() == sorted(ex_want) and ap_got.tolist() == sorted(rt_want - ex_want), seg
+        h = g * G + seg % G
+        want, want_lse = orc.mixed_attention(b, h, ex_got, ap_got)
+        err = float(np.abs(out[b, h] - want).max())
+        worst = max(worst, err)
+        assert err <= 2e-4 and abs(lse[b, h] - want_lse) <= 1e-3, (seg, h, err)
+    print(f"[cfg4 group union] {n_seg} segments, union exact clusters mean {neu.mean():.0f}, retained mean "
+          f"{nru.mean():.0f}; sampled heads max-abs {worst:.2e}", flush=True)

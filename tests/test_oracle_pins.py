@@ -726,3 +726,51 @@ def test_kmeans_assign_ties_go_to_the_lower_index_and_lloyd_does_not_increase_th
         m = oracle.build_cluster_cache(t)
         keep = m["cluster_sizes"] > 0                      # an empty cluster keeps its old centroid
         cent = np.where(keep[:, None], m["k_centroids"], cent)
+
+
+# --------------------------------------------------------------------------
+# selection per GQA group (the union of the heads' sets; the paper states the method for one query)
+# --------------------------------------------------------------------------
+def test_group_union_with_one_head_per_group_is_the_per_head_step():
+    c = make_cache(batch=2, n_kv_heads=3, n_q_heads=3, context=[300, 170], mean_cluster=8, size_hi=32, q_scale=0.5, seed=31)
+    o = oracle.Oracle(c)
+    out, lse, sets = o.group_union_step(0.9, 0.6)
+    ref = o.decode_step(0.9, 0.6)
+    assert np.array_equal(out, ref.out) and np.array_equal(lse, ref.lse)
+    for (b, g), (ex, ap) in sets.items():
+        assert ex.size == ref.k2[b, g] and ex.size + ap.size == ref.k1[b, g]
+
+
+def test_group_union_sets_are_supersets_and_full_selection_is_dense():
+    c = make_cache(batch=1, n_kv_heads=2, n_q_heads=8, context=600, mean_cluster=8, size_hi=32,
+                   q_scale=lambda rng, b, h: [0.3, 3.0][h % 2], seed=32)
+    o = oracle.Oracle(c)
+    G = 4
+    out, lse, sets = o.group_union_step(0.9, 0.7)
+    for g in range(2):
+        ex_u, ap_u = sets[(0, g)]
+        assert not set(ex_u) & set(ap_u)
+        exact_of, retained_of = [], []
+        for h in range(g * G, (g + 1) * G):
+            sel = o.select(o.centroid_logits(0, h), 0.9, 0.7)
+            assert set(sel.exact) <= set(ex_u) and set(sel.retained) <= set(ex_u) | set(ap_u)
+            exact_of.append(set(sel.exact)), retained_of.append(set(sel.retained))
+            # every head's own retained mass is still covered: the union keeps at least p1 of its distribution
+            a_hat = o.cluster_distribution(o.centroid_logits(0, h))
+            assert a_hat[np.r_[ex_u, ap_u]].sum() >= 0.9 - 1e-12
+        assert set(ex_u) == set().union(*exact_of) and set(ex_u) | set(ap_u) == set().union(*retained_of)
+        # a cluster that one head approximates and another takes exactly is exact for the group
+        assert all(i in ex_u for s_ex in exact_of for i in s_ex)
+    # p1 = p2 = 1: every non-empty cluster exact for every head: dense attention (Eq. 1)
+    out1, lse1, _ = o.group_union_step(1.0, 1.0)
+    dense, dense_lse, _ = o.dense_step()
+    assert np.allclose(out1, dense, rtol=0, atol=1e-12) and np.allclose(lse1, dense_lse, rtol=0, atol=1e-12)
+
+
+def test_group_union_of_identical_queries_is_the_per_head_result():
+    c = make_cache(batch=1, n_kv_heads=1, n_q_heads=4, context=400, mean_cluster=8, size_hi=32, q_scale=0.6, seed=33)
+    c.q[0, 1:] = c.q[0, 0]
+    o = oracle.Oracle(c)
+    out, lse, sets = o.group_union_step(0.85, 0.5)
+    ref = o.decode_step(0.85, 0.5)
+    assert np.array_equal(out, ref.out) and np.array_equal(lse, ref.lse)
