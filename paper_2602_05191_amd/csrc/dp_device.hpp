@@ -109,14 +109,31 @@ __device__ __forceinline__ unsigned long long dpp_mov_u64(unsigned long long v) 
   return ((unsigned long long)hi << 32) | lo;
 }
 
+// After the 4 DPP steps every lane of a 16-lane row holds its row's result; the four rows are then combined
+// through readlane (lanes 0, 16, 32, 48 -> scalar registers), which is much shorter than two cross-row
+// shuffles through the LDS crossbar.  The combination order (r0 . r1) . (r2 . r3) is what the shuffles
+// gave every lane, so float results keep their bits.
+__device__ __forceinline__ uint32_t lane_u32(uint32_t v, int lane) { return (uint32_t)__builtin_amdgcn_readlane((int)v, lane); }
+__device__ __forceinline__ unsigned long long lane_u64(unsigned long long v, int lane) {
+  return ((unsigned long long)lane_u32((uint32_t)(v >> 32), lane) << 32) | lane_u32((uint32_t)v, lane);
+}
+__device__ __forceinline__ float lane_f32(float v, int lane) { return __uint_as_float(lane_u32(__float_as_uint(v), lane)); }
+
 __device__ __forceinline__ unsigned long long wave_sum(unsigned long long v) {
   v += dpp_mov_u64<0xB1>(v);
   v += dpp_mov_u64<0x4E>(v);
   v += dpp_mov_u64<0x141>(v);
   v += dpp_mov_u64<0x140>(v);
-  v += __shfl_xor(v, 16, 64);
-  v += __shfl_xor(v, 32, 64);
-  return v;
+  return (lane_u64(v, 0) + lane_u64(v, 16)) + (lane_u64(v, 32) + lane_u64(v, 48));
+}
+
+__device__ __forceinline__ unsigned long long wave_max(unsigned long long v) {
+  auto mx = [](unsigned long long a, unsigned long long b) { return a > b ? a : b; };
+  v = mx(v, dpp_mov_u64<0xB1>(v));
+  v = mx(v, dpp_mov_u64<0x4E>(v));
+  v = mx(v, dpp_mov_u64<0x141>(v));
+  v = mx(v, dpp_mov_u64<0x140>(v));
+  return mx(mx(lane_u64(v, 0), lane_u64(v, 16)), mx(lane_u64(v, 32), lane_u64(v, 48)));
 }
 
 __device__ __forceinline__ int wave_sum(int v) {
@@ -124,16 +141,12 @@ __device__ __forceinline__ int wave_sum(int v) {
   v += (int)dpp_mov_u32<0x4E>((uint32_t)v);
   v += (int)dpp_mov_u32<0x141>((uint32_t)v);
   v += (int)dpp_mov_u32<0x140>((uint32_t)v);
-  v += __shfl_xor(v, 16, 64);
-  v += __shfl_xor(v, 32, 64);
-  return v;
+  return (int)((lane_u32((uint32_t)v, 0) + lane_u32((uint32_t)v, 16)) + (lane_u32((uint32_t)v, 32) + lane_u32((uint32_t)v, 48)));
 }
 
 __device__ __forceinline__ float wave_sum(float v) {
   v = row16_sum(v);
-  v += __shfl_xor(v, 16, 64);
-  v += __shfl_xor(v, 32, 64);
-  return v;
+  return (lane_f32(v, 0) + lane_f32(v, 16)) + (lane_f32(v, 32) + lane_f32(v, 48));
 }
 
 __device__ __forceinline__ float wave_max(float v) {
@@ -141,9 +154,28 @@ __device__ __forceinline__ float wave_max(float v) {
   v = fmaxf(v, dpp_mov<0x4E>(v));
   v = fmaxf(v, dpp_mov<0x141>(v));
   v = fmaxf(v, dpp_mov<0x140>(v));
-  v = fmaxf(v, __shfl_xor(v, 16, 64));
-  v = fmaxf(v, __shfl_xor(v, 32, 64));
-  return v;
+  return fmaxf(fmaxf(lane_f32(v, 0), lane_f32(v, 16)), fmaxf(lane_f32(v, 32), lane_f32(v, 48)));
+}
+
+// Inclusive wave scans of integers: a shift-and-add scan inside each 16-lane row with DPP row shifts (a lane
+// without a source reads 0), then the totals of the rows before (lanes 15, 31, 47, through readlane) are added.
+__device__ __forceinline__ int wave_incl_scan(int v) {
+  v += (int)dpp_mov_u32<0x111>((uint32_t)v);  // row_shr:1
+  v += (int)dpp_mov_u32<0x112>((uint32_t)v);  // row_shr:2
+  v += (int)dpp_mov_u32<0x114>((uint32_t)v);  // row_shr:4
+  v += (int)dpp_mov_u32<0x118>((uint32_t)v);  // row_shr:8
+  const int t0 = (int)lane_u32((uint32_t)v, 15), t1 = (int)lane_u32((uint32_t)v, 31), t2 = (int)lane_u32((uint32_t)v, 47);
+  const int row = lane_id() >> 4;
+  return v + (row == 0 ? 0 : row == 1 ? t0 : row == 2 ? t0 + t1 : t0 + t1 + t2);
+}
+__device__ __forceinline__ unsigned long long wave_incl_scan(unsigned long long v) {
+  v += dpp_mov_u64<0x111>(v);
+  v += dpp_mov_u64<0x112>(v);
+  v += dpp_mov_u64<0x114>(v);
+  v += dpp_mov_u64<0x118>(v);
+  const unsigned long long t0 = lane_u64(v, 15), t1 = lane_u64(v, 31), t2 = lane_u64(v, 47);
+  const int row = lane_id() >> 4;
+  return v + (row == 0 ? 0ull : row == 1 ? t0 : row == 2 ? t0 + t1 : t0 + t1 + t2);
 }
 
 // Exclusive scan over the block (blockDim.x = 64*NW threads, thread order).

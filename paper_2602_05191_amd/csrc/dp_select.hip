@@ -262,11 +262,7 @@ __device__ __forceinline__ Refined refine_or_cut_ties(const float *lg, int kc, f
       mm = mass_of<kCount>(mx - le);
     }
   }
-#pragma unroll
-  for (int d = 32; d >= 1; d >>= 1) {
-    const u64 o = __shfl_xor(mm, d, 64);
-    mm = o > mm ? o : mm;
-  }
+  mm = wave_max(mm);
   if (lane_id() == 0) sh.scr64[wave_id()] = mm;
   __syncthreads();
   u64 m_tie = 0;
@@ -694,11 +690,7 @@ __global__ __launch_bounds__(T) void select_kernel(SelectArgs a) {
       {
         const bool ret = pin_i || (act && ahead < tau1);
         u64 m1 = (ret && !pin_i) ? ahead + m_i : 0;  // mass of the retained prefix = the largest inclusive prefix
-#pragma unroll
-        for (int d = 32; d >= 1; d >>= 1) {
-          const u64 o = __shfl_xor(m1, d, 64);
-          m1 = o > m1 ? o : m1;
-        }
+        m1 = wave_max(m1);
         u64 tau2 = 0;
         const int kind = second_tau<kCount>(a, W, m1, tau2);
         const bool exa = pin_i || (kind == 1 ? ret : (kind == 2 && act && ahead < tau2));
