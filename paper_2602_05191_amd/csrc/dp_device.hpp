@@ -178,21 +178,60 @@ __device__ __forceinline__ unsigned long long wave_incl_scan(unsigned long long 
   return v + (row == 0 ? 0ull : row == 1 ? t0 : row == 2 ? t0 + t1 : t0 + t1 + t2);
 }
 
+// ---- combining the per-wave partials of a block reduction ----
+// Lane t of every 16-lane row reads partial t % 16 (one LDS instruction per wave) and the row reduces the 16
+// values with DPP steps: every lane ends with the block's result.  Reading all NW partials in every thread costs
+// NW LDS instructions per wave, and the one LDS unit of a CU serialises them over the 16 waves of a big workgroup.
+__device__ __forceinline__ int row16_sum(int v) {
+  v += (int)dpp_mov_u32<0xB1>((uint32_t)v);
+  v += (int)dpp_mov_u32<0x4E>((uint32_t)v);
+  v += (int)dpp_mov_u32<0x141>((uint32_t)v);
+  v += (int)dpp_mov_u32<0x140>((uint32_t)v);
+  return v;
+}
+__device__ __forceinline__ unsigned long long row16_sum(unsigned long long v) {
+  v += dpp_mov_u64<0xB1>(v);
+  v += dpp_mov_u64<0x4E>(v);
+  v += dpp_mov_u64<0x141>(v);
+  v += dpp_mov_u64<0x140>(v);
+  return v;
+}
+__device__ __forceinline__ float row16_max(float v) {
+  v = fmaxf(v, dpp_mov<0xB1>(v));
+  v = fmaxf(v, dpp_mov<0x4E>(v));
+  v = fmaxf(v, dpp_mov<0x141>(v));
+  v = fmaxf(v, dpp_mov<0x140>(v));
+  return v;
+}
+__device__ __forceinline__ unsigned long long row16_max(unsigned long long v) {
+  auto mx = [](unsigned long long a, unsigned long long b) { return a > b ? a : b; };
+  v = mx(v, dpp_mov_u64<0xB1>(v));
+  v = mx(v, dpp_mov_u64<0x4E>(v));
+  v = mx(v, dpp_mov_u64<0x141>(v));
+  v = mx(v, dpp_mov_u64<0x140>(v));
+  return v;
+}
+// sum of partials[0 .. NW), NW <= 16, in every lane (call after the barrier that publishes them)
+template <typename T, int NW>
+__device__ __forceinline__ T partials_sum(const T *partials) {
+  static_assert(NW <= 16, "one 16-lane row holds the partials");
+  const int t = threadIdx.x & 15;
+  return row16_sum(t < NW ? partials[t] : T(0));
+}
+
 // Exclusive scan over the block (blockDim.x = 64*NW threads, thread order).
 // `total` receives the block sum.  scratch: NW + 1 elements of LDS.  Contains
 // two barriers; scratch may be reused after the call returns.
 template <typename T, int NW>
 __device__ __forceinline__ T block_excl_scan(T v, T *scratch, T &total) {
+  static_assert(NW <= 16, "one 16-lane row holds the partials");
   T incl = wave_incl_scan(v);
   if (lane_id() == 63) scratch[wave_id()] = incl;
   __syncthreads();
-  T base = 0, tot = 0;
-#pragma unroll
-  for (int w = 0; w < NW; ++w) {
-    T s = scratch[w];
-    if (w < wave_id()) base += s;
-    tot += s;
-  }
+  const int t = threadIdx.x & 15;
+  const T s = t < NW ? scratch[t] : T(0);
+  const T tot = row16_sum(s);
+  const T base = row16_sum(t < wave_id() ? s : T(0));
   __syncthreads();
   total = tot;
   return base + incl - v;
@@ -203,21 +242,19 @@ __device__ __forceinline__ T block_sum(T v, T *scratch) {
   v = wave_sum(v);
   if (lane_id() == 0) scratch[wave_id()] = v;
   __syncthreads();
-  T tot = 0;
-#pragma unroll
-  for (int w = 0; w < NW; ++w) tot += scratch[w];
+  const T tot = partials_sum<T, NW>(scratch);
   __syncthreads();
   return tot;
 }
 
 template <int NW>
 __device__ __forceinline__ float block_max(float v, float *scratch) {
+  static_assert(NW <= 16, "one 16-lane row holds the partials");
   v = wave_max(v);
   if (lane_id() == 0) scratch[wave_id()] = v;
   __syncthreads();
-  float m = scratch[0];
-#pragma unroll
-  for (int w = 1; w < NW; ++w) m = fmaxf(m, scratch[w]);
+  const int t = threadIdx.x & 15;
+  const float m = row16_max(t < NW ? scratch[t] : -INFINITY);
   __syncthreads();
   return m;
 }

@@ -266,8 +266,10 @@ __device__ __forceinline__ Refined refine_or_cut_ties(const float *lg, int kc, f
   if (lane_id() == 0) sh.scr64[wave_id()] = mm;
   __syncthreads();
   u64 m_tie = 0;
-#pragma unroll
-  for (int w = 0; w < (T / 64); ++w) m_tie = sh.scr64[w] > m_tie ? sh.scr64[w] : m_tie;
+  {
+    const int t = threadIdx.x & 15;
+    m_tie = row16_max(t < (T / 64) ? sh.scr64[t] : 0ull);
+  }
   __syncthreads();
   const u64 need = (tau - before + m_tie - 1) / m_tie;  // ties taken, 1 <= need <= cnt
   int tot;
@@ -635,15 +637,9 @@ __global__ __launch_bounds__(T) void select_kernel(SelectArgs a) {
       sh.scri[wave_id()] = ctop;
     }
     __syncthreads();
-    W = 0;
-    Wtop = 0;
-    ntop = 0;
-#pragma unroll
-    for (int w = 0; w < (T / 64); ++w) {
-      W += sh.scr64[w];
-      Wtop += sh.scr64b[w];
-      ntop += sh.scri[w];
-    }
+    W = partials_sum<u64, (T / 64)>(sh.scr64);
+    Wtop = partials_sum<u64, (T / 64)>(sh.scr64b);
+    ntop = partials_sum<int, (T / 64)>(sh.scri);
   }
   DP_MARK(2);
 
@@ -804,41 +800,24 @@ __global__ __launch_bounds__(T) void select_kernel(SelectArgs a) {
     const int ce = __popcll(exa_mask), ca = __popcll(ret_mask);
     int pe, pa, pt;
     {
-      // one scan for the three counters
-      int ie = ce, ia = ca, it = te;
-      const int lane = lane_id(), w = wave_id();
-#pragma unroll
-      for (int d = 1; d < 64; d <<= 1) {
-        const int oe = __shfl_up(ie, d, 64), oa = __shfl_up(ia, d, 64), ot = __shfl_up(it, d, 64);
-        if (lane >= d) {
-          ie += oe;
-          ia += oa;
-          it += ot;
-        }
-      }
-      if (lane == 63) {
+      // one barrier for the three counters: wave scans, wave totals through LDS, combined by 16-lane rows
+      const int w = wave_id();
+      const int ie = wave_incl_scan(ce), ia = wave_incl_scan(ca), it = wave_incl_scan(te);
+      if (lane_id() == 63) {
         sh.scri[w] = ie;
         sh.scri[(T / 64) + w] = ia;
         sh.scri[2 * (T / 64) + w] = it;
       }
       __syncthreads();
-      int be = 0, ba = 0, bt = 0;
-      n_ex = n_ap = n_tok = 0;
-#pragma unroll
-      for (int v = 0; v < (T / 64); ++v) {
-        const int se = sh.scri[v], sa = sh.scri[(T / 64) + v], st = sh.scri[2 * (T / 64) + v];
-        if (v < w) {
-          be += se;
-          ba += sa;
-          bt += st;
-        }
-        n_ex += se;
-        n_ap += sa;
-        n_tok += st;
-      }
-      pe = be + ie - ce;
-      pa = ba + ia - ca;
-      pt = bt + it - te;
+      const int t16 = tid & 15;
+      const bool has = t16 < (T / 64), mine = t16 < w;
+      const int se = has ? sh.scri[t16] : 0, sa = has ? sh.scri[(T / 64) + t16] : 0, st = has ? sh.scri[2 * (T / 64) + t16] : 0;
+      n_ex = row16_sum(se);
+      n_ap = row16_sum(sa);
+      n_tok = row16_sum(st);
+      pe = row16_sum(mine ? se : 0) + ie - ce;
+      pa = row16_sum(mine ? sa : 0) + ia - ca;
+      pt = row16_sum(mine ? st : 0) + it - te;
     }
     DP_MARK(12);
     emit.to_lds = can_inline && n_tok + n_ap <= kInlineRows;
