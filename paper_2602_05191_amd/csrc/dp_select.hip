@@ -376,9 +376,12 @@ __device__ __forceinline__ void find_prefix(const float (&l)[E], const float *lg
       const int ii = sh.cand_idx[tid];
       const u64 mi = sh.cand_m[tid];
       u64 ahead = before;
-      for (int j = 0; j < cnt; ++j) {
+#pragma unroll 4
+      for (int j = 0; j < cnt; ++j) {  // unconditional (broadcast) reads, four members in flight
         const uint32_t kj = sh.cand_key[j];
-        if (kj > ki || (kj == ki && sh.cand_idx[j] < ii)) ahead += sh.cand_m[j];
+        const int ij = sh.cand_idx[j];
+        const u64 mj = sh.cand_m[j];
+        ahead += (kj > ki || (kj == ki && ij < ii)) ? mj : 0;
       }
       if (ahead < tau && tau <= ahead + mi) {  // true for exactly one member
         sh.res_key = ki;
