@@ -736,3 +736,34 @@ def test_group_union_variant_matches_oracle(case):
             assert np.linalg.norm(out[b, h] - want) <= 5e-3 * max(np.linalg.norm(want), 1e-30) + 1e-6
             assert abs(lse[b, h] - want_lse) <= 1e-3
     print(f"[{name}] group-union variant: worst max-abs error {worst:.2e}")
+
+
+@pytest.mark.parametrize("seed", range(16))
+def test_random_shapes_match_oracle(seed):
+    """Seeded random shapes through the one-call path: GQA groups of 1 to 16, one to three sequences of unequal
+    length, cluster sizes from singletons to hundreds of tokens, flat / peaked / mixed heads, p1 and p2 at their
+    limits, both readings of the second threshold, pinned and emptied clusters now and then."""
+    from workloads import pin_sink_and_window
+    rng = np.random.default_rng(4000 + seed)
+    G = int(rng.choice([1, 2, 3, 4, 5, 6, 8, 12, 16]))
+    nkv, batch = int(rng.integers(1, 4)), int(rng.integers(1, 4))
+    ctx = [int(rng.integers(40, 7000)) for _ in range(batch)]
+    mc = int(rng.choice([3, 4, 8, 16, 32]))
+    flat = rng.random() < 0.5
+    qs = (lambda r, b, h: [0.3, 2.5, 0.7, 4.0][h % 4]) if rng.random() < 0.5 else (0.35 if flat else 3.0)
+    p1 = float(rng.choice([0.8, 0.9, 0.95, 0.99, 1.0]))
+    p2 = float(rng.choice([0.0, 0.5, 0.7, 0.9, 1.0]))
+    c = make_cache(batch=batch, n_kv_heads=nkv, n_q_heads=nkv * G, context=ctx, mean_cluster=mc,
+                   size_hi=int(rng.choice([2, 4, 8])) * mc, q_scale=qs, seed=5000 + seed)
+    if rng.random() < 0.3:
+        pin_sink_and_window(c, first=1, last=int(rng.integers(1, 4)))
+    if rng.random() < 0.2:
+        c.cluster_sizes[rng.integers(0, len(c.cluster_sizes), size=3)] = 0
+    flags = int(rng.random() < 0.3)
+    orc = oracle.Oracle(c)
+    g = H.gpu_decode_attention(c, p1, p2, flags=flags)
+    tolerated = H.check_sets(c, orc, g, p1, p2, flags)
+    worst, _ = H.check_outputs(c, orc, g, tight=2e-4)
+    print(f"[random {seed}] G {G}, {nkv} KV heads, contexts {ctx}, mean cluster {mc}, p {p1}/{p2}, flags {flags}: "
+          f"tolerated {tolerated}, max-abs {worst:.1e}")
+    assert tolerated <= max(1, (batch * nkv * G) // 20)
