@@ -494,21 +494,15 @@ __global__ __launch_bounds__(T) void select_kernel(SelectArgs a) {
   DP_MARK(0);
   // ---- load, max ---------------------------------------------------------
   float l[E];
-  if (E >= 4 && (reinterpret_cast<uintptr_t>(lg) & 15) == 0) {
+  if (E >= 4 && (reinterpret_cast<uintptr_t>(lg) & 15) == 0 && base + E <= kc) {
+    // the thread's whole run lies inside the segment: all its 16-byte loads go out back to back
 #pragma unroll
-    for (int e = 0; e < E; e += 4) {  // E >= 4 here; 16-byte loads
-      const int i = base + e;
-      if (i + 3 < kc) {
-        const float4 v = *reinterpret_cast<const float4 *>(lg + i);
-        l[e] = v.x;
-        l[e + 1 < E ? e + 1 : e] = v.y;
-        l[e + 2 < E ? e + 2 : e] = v.z;
-        l[e + 3 < E ? e + 3 : e] = v.w;
-      } else {
-#pragma unroll
-        for (int u = 0; u < 4; ++u)
-          if (e + u < E) l[e + u] = (i + u < kc) ? lg[i + u] : -INFINITY;
-      }
+    for (int e = 0; e < E; e += 4) {
+      const float4 v = *reinterpret_cast<const float4 *>(lg + base + e);
+      l[e] = v.x;
+      l[e + 1 < E ? e + 1 : e] = v.y;
+      l[e + 2 < E ? e + 2 : e] = v.z;
+      l[e + 3 < E ? e + 3 : e] = v.w;
     }
   } else {
 #pragma unroll
