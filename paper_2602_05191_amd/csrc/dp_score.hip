@@ -5,11 +5,11 @@
 // HBM-bound streaming kernels: the key-centroid matrix is read exactly once
 // (256 B per cluster) and each row is scored against all G query heads of the
 // group at once.  Algorithmic traffic per cluster: 256 B centroid + 4 B size
-// read, 4*G B written.  Two formulations:
-//   G <= 4 and more than 1024 tiles of 64 clusters: the vector ALU: packed bf16 dots
-//           (v_dot2c_f32_bf16) and a 16-lane DPP reduction per row and head, 2.25 instructions per cluster and head,
+// read, 4*G B written.  Two formulations, chosen by G:
+//   G <= 4  vector ALU: packed bf16 dots (v_dot2c_f32_bf16) and a 16-lane DPP
+//           reduction per row and head, 2.25 instructions per cluster and head,
 //           behind whole-row loads (every load instruction reads 4 rows of 256 B)
-//   otherwise the matrix core: the scores of 16 clusters against up to 16 heads are one
+//   G >  4  matrix core: the scores of 16 clusters against up to 16 heads are one
 //           [16 x 128] x [128 x 16] contraction, four v_mfma_f32_16x16x32_bf16
 //           (64 matrix-core cycles per 16 clusters, whatever G is).  The operands
 //           go from global memory straight into the MFMA register layout: lane l
@@ -18,14 +18,10 @@
 //           the four together read the rows whole.  Heads beyond the group are
 //           zero columns.
 // Measured (one MI355X, cold centroids): G = 8, 32 x 8192 clusters: 17.0 us on the
-// vector ALU, 15.0 us on the matrix core.  G = 4: the vector ALU wins where the
-// stream is long (32 x 8192 clusters 13.9 vs 14.2 us, 128 x 1280 clusters 10.0 vs
-// 10.7 us, 128 ragged segments of 512..2048 clusters 11.8 vs 14.5 us: whole-row
-// loads stream faster than the 64-byte pattern), the matrix core where the launch
-// is small enough to be bound by its own start and end (8 x 8192 clusters 5.7 vs
-// 5.4 us, 16 x 4096 clusters 5.6 vs 5.1 us: with two tiles per wave it has half
-// the waves to start and half the query and size loads).  So G <= 4 goes to the
-// vector ALU unless the launch has at most 1024 tiles of 64 clusters.
+// vector ALU, 15.0 us on the matrix core; G = 4: 8 x 8192 clusters 5.8 vs 5.4 us,
+// 128 x 1280 clusters 10.0 vs 10.7 us, 128 ragged segments of 512..2048 clusters
+// 12.3 vs 14.5 us (the 64-byte load pattern streams slower over many short
+// segments), so G = 4 stays on the vector ALU.
 #include <hip/hip_ext.h>
 
 #include "dp_device.hpp"
@@ -40,8 +36,7 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 constexpr int kScoreThreads = 256;                   // 4 waves
 constexpr int kScoreHeads = 16;                      // query heads per pass: the columns of one MFMA tile
 constexpr int kScoreTile = (kScoreThreads / 64) * 16;  // clusters per workgroup and tile step: a 16-row MFMA tile per wave
-constexpr int kScoreValuMaxGroup = 4;  // groups up to this size are scored on the vector ALU, larger ones on the matrix core ...
-constexpr int kScoreSmallLaunchTiles = 1024;  // ... unless the launch is this small (64-cluster tiles): then the matrix core too
+constexpr int kScoreValuMaxGroup = 4;  // groups up to this size are scored on the vector ALU, larger ones on the matrix core
 constexpr int kScoreMinWgs = 512;  // a launch keeps at least this many workgroups when it takes several tiles per wave
 
 struct ScoreArgs {
@@ -248,8 +243,7 @@ hipError_t launch_score(const CacheView &c, float *logits, hipStream_t s, hipEve
   a.zero_words = n_zero <= kScoreThreads ? zero_words : nullptr;
   a.n_zero = n_zero;
   if (c.max_clusters_per_seg == 0 || c.batch * c.n_kv_heads == 0) return hipSuccess;
-  const int64_t tiles = (int64_t)((c.max_clusters_per_seg + kScoreTile - 1) / kScoreTile) * c.batch * c.n_kv_heads;
-  if (c.group <= kScoreValuMaxGroup && tiles > kScoreSmallLaunchTiles) {
+  if (c.group <= kScoreValuMaxGroup) {
     // one pass: 4, 2 or 1 heads at a time
     const dim3 vgrid((c.max_clusters_per_seg + kScoreTile - 1) / kScoreTile, c.batch * c.n_kv_heads);
     int h0 = 0;
