@@ -59,12 +59,10 @@ dp::CacheView view_of(const dp_problem *p) {
 
 // stage-3 splits per head: aim at several thousand workgroups in total, many more than the 256 CUs can
 // hold at once, so that the last round of workgroups is short against the whole
-#ifndef DP_SPLIT_TARGET
-#define DP_SPLIT_TARGET 16384
-#endif
+constexpr long kSplitTarget = 16384;
 int choose_splits(const dp_problem *p) {
   const long nh = (long)p->batch * p->n_q_heads;
-  long s = (DP_SPLIT_TARGET + nh - 1) / nh;
+  long s = (kSplitTarget + nh - 1) / nh;
   const long by_rows = ((long)p->max_rows_per_seg + p->max_clusters_per_seg + dp::kChunkRows - 1) / dp::kChunkRows;
   if (s > by_rows) s = by_rows;
   if (s > dp::kMaxSplits) s = dp::kMaxSplits;

@@ -15,10 +15,7 @@
 
 namespace dp {
 
-#ifndef DP_ATTEND_BATCH
-#define DP_ATTEND_BATCH 4
-#endif
-constexpr int kAttendBatch = DP_ATTEND_BATCH;  // cache rows in flight per group
+constexpr int kAttendBatch = 4;  // cache rows in flight per group
 
 struct RowState {
   float m, l, acc[8];

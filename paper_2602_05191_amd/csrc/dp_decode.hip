@@ -40,16 +40,8 @@ constexpr int kDecWaves = kDecThreads / 64;
 constexpr int kDecGroups = kDecThreads / 16;   // 16 DPP rows per workgroup
 constexpr int kDecBlockRows = 512;             // rows resolved per LDS staging round
 constexpr int kPartialStride = kHeadDim + 2;   // m, l, acc[128]
-#ifndef DP_MIN_ITEM_CHUNKS
-#define DP_MIN_ITEM_CHUNKS 4
-#endif
-constexpr int kMinItemChunks = DP_MIN_ITEM_CHUNKS;  // items of a heavy launch have at least this many 64-row chunks
+constexpr int kMinItemChunks = 4;  // items of a heavy launch have at least this many 64-row chunks
 
-#ifdef DP_PHASE_CLOCKS  // development aid, never built into the library
-#define DD_MARK(i) do { if (a.dbg && threadIdx.x == 0 && blockIdx.x < 2048) a.dbg[blockIdx.x * 16 + (i)] = wall_clock64(); } while (0)
-#else
-#define DD_MARK(i) do { } while (0)
-#endif
 
 struct DecodeArgs {
   const void *q, *k_cache, *v_cache, *k_centroids, *v_centroids;
@@ -68,9 +60,6 @@ struct DecodeArgs {
   const void *k_gather, *v_gather;
   int32_t rows_cap;
   float scale_log2;        // sm_scale * log2(e)
-#ifdef DP_PHASE_CLOCKS
-  unsigned long long *dbg;
-#endif
 };
 
 // rows per item of a head with R rows (multiple of kChunkRows); g: least chunks per item of this launch
@@ -83,7 +72,6 @@ template <bool kGathered>
 __device__ __forceinline__ void decode_item(const DecodeArgs &a, int head, int split, int R, int g, int *s_start, int *s_src,
                                             float *s_m, float *s_l, float (*s_acc)[kHeadDim], int *s_last, int tid,
                                             int lane16, int grp) {
-  DD_MARK(1);
   const int c = rows_per_item(R, a.splits, g);
   const int row_a = split * c;
   const int row_b = min(R, row_a + c);
@@ -120,8 +108,6 @@ __device__ __forceinline__ void decode_item(const DecodeArgs &a, int head, int s
   row_state_init(st);
 
   int ent0 = a.plan.chunk_entry[(int64_t)head * a.plan.chunk_stride + row_a / kChunkRows];
-
-  DD_MARK(2);
   for (int r0 = row_a; r0 < row_b; r0 += kDecBlockRows) {
     const int r1 = min(row_b, r0 + kDecBlockRows);
     // stage the list entries that cover rows [r0, r1): every entry has >= 1 row
@@ -132,7 +118,6 @@ __device__ __forceinline__ void decode_item(const DecodeArgs &a, int head, int s
       s_src[k] = (k < n_ent) ? ent_src[ent0 + k] : 0;
     }
     __syncthreads();
-    DD_MARK(3);
     // the 16 DPP-row groups take consecutive 4-row pieces: one step of the workgroup reads 64 consecutive rows
     if (use_gather)
       attend_rows<true>(st, qv, a.scale_log2, src, s_start, s_src, n_ent, ent0, n_ex, r0 + grp * kAttendBatch, r1,
@@ -150,11 +135,8 @@ __device__ __forceinline__ void decode_item(const DecodeArgs &a, int head, int s
       ent0 += lo;
     }
   }
-
-  DD_MARK(4);
   float M, L, o;
   block_merge<kDecWaves>(st, s_m, s_l, s_acc, kDecWaves, M, L, o);
-  DD_MARK(5);
 
   if (n_active == 1) {  // the only split of this head: finish here
     if (tid < kHeadDim) {
@@ -184,7 +166,6 @@ __device__ __forceinline__ void decode_item(const DecodeArgs &a, int head, int s
     (*s_last) = (ticket == n_active - 1);
   }
   __syncthreads();
-  DD_MARK(6);
   if (!(*s_last)) return;
   if (tid < kHeadDim) {
     // running log-sum-exp merge; the coherent loads of 8 partials are issued together
@@ -225,8 +206,6 @@ __global__ __launch_bounds__(kDecThreads) void decode_kernel(DecodeArgs a) {
   __shared__ int s_scan[kDecWaves + 1];
   __shared__ int s_rows[kMaxQueueHeads];
   const int tid = threadIdx.x, lane16 = tid & 15, grp = tid >> 4;
-
-  DD_MARK(0);
   if (a.pending && *a.pending == 0) return;  // every head was finished by the selection kernel
   // ---- the queue: items per head from head_rows[], exclusive prefix in LDS ----
   constexpr int kPer = kMaxQueueHeads / kDecThreads;  // consecutive heads per thread
@@ -281,16 +260,11 @@ __global__ __launch_bounds__(kDecThreads) void decode_kernel(DecodeArgs a) {
     __syncthreads();  // also: LDS is reused by the next item
     item = s_item;
     __syncthreads();
-    DD_MARK(7);
   }
 }
 
 }  // namespace
 
-#ifdef DP_PHASE_CLOCKS
-unsigned long long *g_decode_clock_buffer = nullptr;
-extern "C" void dp_debug_set_decode_clock_buffer(void *p) { g_decode_clock_buffer = (unsigned long long *)p; }
-#endif
 
 hipError_t launch_decode(const CacheView &c, const int32_t *n_exact, const int32_t *n_retained, const Plan &plan,
                          float *partials, int splits, const AttnOut &attn, hipStream_t s, hipEvent_t start,
@@ -322,9 +296,6 @@ hipError_t launch_decode(const CacheView &c, const int32_t *n_exact, const int32
   a.k_gather = k_gather;
   a.v_gather = v_gather;
   a.rows_cap = rows_cap;
-#ifdef DP_PHASE_CLOCKS
-  a.dbg = g_decode_clock_buffer;
-#endif
   // one launch per slab of kMaxQueueHeads heads, each with its own item counter
   for (int h0 = 0, slab = 0; h0 < nh; h0 += kMaxQueueHeads, ++slab) {
     a.head0 = h0;

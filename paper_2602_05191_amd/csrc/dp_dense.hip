@@ -21,10 +21,7 @@ namespace {
 constexpr int kDenseThreads = 256;
 constexpr int kDenseWaves = kDenseThreads / 64;
 constexpr int kDenseGroups = kDenseThreads / 16;
-#ifndef DP_DENSE_BATCH
-#define DP_DENSE_BATCH 4
-#endif
-constexpr int kDenseBatch = DP_DENSE_BATCH;  // cache rows in flight per DPP row
+constexpr int kDenseBatch = 4;  // cache rows in flight per DPP row
 constexpr int kPartialStride = kHeadDim + 2;
 
 struct DenseArgs {

@@ -13,10 +13,7 @@ constexpr int kChunkRows = 64;
 // stage 3 pulls (head, split) items from a device-side queue: heads served per launch, workgroups per launch
 constexpr int kMaxQueueHeads = 1024;
 constexpr int kMaxSplits = 256;  // most partial slots per head
-#ifndef DP_DECODE_GRID
-#define DP_DECODE_GRID 1280
-#endif
-constexpr int kDecodeGrid = DP_DECODE_GRID;
+constexpr int kDecodeGrid = 1280;
 
 struct CacheView {
   int32_t batch, n_kv_heads, n_q_heads, group;  // group = n_q_heads / n_kv_heads

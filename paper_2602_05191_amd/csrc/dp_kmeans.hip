@@ -37,16 +37,10 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int kKmThreads = 256;
-#ifndef DP_KM_TM
-#define DP_KM_TM 4
-#endif
-constexpr int kKmTM = DP_KM_TM;                        // 16-token row tiles per wave
+constexpr int kKmTM = 4;                     // 16-token row tiles per wave
 constexpr int kKmTokensPerWave = 16 * kKmTM;
 constexpr int kKmTokensPerBlock = kKmTokensPerWave * (kKmThreads / 64);
-#ifndef DP_KM_CB
-#define DP_KM_CB 64
-#endif
-constexpr int kKmCB = DP_KM_CB;                        // centroids per LDS block (a multiple of 64: 256 threads fetch 64 rows per pass)
+constexpr int kKmCB = 64;                     // centroids per LDS block (a multiple of 64: 256 threads fetch 64 rows per pass)
 constexpr int kKmBufs = 3;                              // LDS blocks in rotation: computed on, next (already stored), being filled
 constexpr int kKmRowPad = kRowBytes + 16;              // LDS row stride: 68 words, 4 r mod 64 banks for row r
 

@@ -49,15 +49,7 @@ constexpr int kMaxCand = 512;            // largest bin population that is ranke
 constexpr float kTopCut = 6.0f;          // "top set": clusters whose logit is within this of the max
 constexpr int kTopMax = 64;              // largest top set handled by the one-wave fast path
 
-#ifdef DP_PHASE_CLOCKS  // development aid: per-phase timestamps of thread 0, never built into the library
-#define DP_MARK(i) do { if (a.dbg && threadIdx.x == 0) a.dbg[blockIdx.x * 16 + (i)] = wall_clock64(); } while (0)
-#else
-#define DP_MARK(i) do { } while (0)
-#endif
 
-#ifdef DP_PHASE_CLOCKS
-__device__ unsigned long long *g_dbg_ptr = nullptr;
-#endif
 
 struct SelectArgs {
   const float *logits;
@@ -77,9 +69,6 @@ struct SelectArgs {
   float *lse;
   int32_t out_is_bf16;
   float scale_log2;
-#ifdef DP_PHASE_CLOCKS
-  unsigned long long *dbg;
-#endif
 };
 
 // level-1 bin of a cluster at distance d below the max logit; bs = bins per unit of d
@@ -165,7 +154,8 @@ __device__ __forceinline__ void reduce_members(int cnt, uint32_t lo, uint32_t hi
 // be ranked, or are a run of equal keys which is cut in index order.  On return either
 // cnt <= kMaxCand (members = keys in [klo, khi], not yet gathered) or done and the result is in sh.res_*.
 // The logits are read again from memory in rolled loops, so that this path adds nothing to the register
-// pressure of the common one (it costs a few global round trips per pass instead).
+// pressure of the common one (it costs a few global round trips per pass instead).  `masked`: bit e set = this
+// thread's element e carries a cluster flag and is outside the distribution, whatever its stored logit.
 struct Refined {
   u64 before;
   uint32_t klo, khi;
@@ -174,11 +164,11 @@ struct Refined {
 };
 template <int E, bool kCount, int T>
 __device__ __forceinline__ Refined refine_or_cut_ties(const float *lg, int kc, float mx, float bs, int base, int bin1,
-                                                      u64 tau, u64 before, Shared<T> *shp) {
+                                                      u64 tau, u64 before, u64 masked, Shared<T> *shp) {
   Shared<T> &sh = *shp;
   constexpr int kBins = bins_of(T);
   const int tid = threadIdx.x;
-  auto logit = [&](int e) { return (base + e < kc) ? lg[base + e] + 0.0f : -INFINITY; };
+  auto logit = [&](int e) { return (base + e < kc && !((masked >> e) & 1)) ? lg[base + e] + 0.0f : -INFINITY; };
   uint32_t klo, khi;
   int cnt;
   {
@@ -299,7 +289,7 @@ __device__ __forceinline__ Refined refine_or_cut_ties(const float *lg, int kc, f
 // cached_*: the bin whose members are currently gathered in sh.cand_* (reused when the
 // second threshold falls into the same bin).  Block-uniform control flow.
 template <int E, bool kCount, int T>
-__device__ __forceinline__ void find_prefix(const float (&l)[E], const float *lg, int kc, float mx, float bs, int base, u64 tau, u64 ex,
+__device__ __forceinline__ void find_prefix(const float (&l)[E], const float *lg, int kc, float mx, float bs, int base, u64 masked, u64 tau, u64 ex,
                                             const u64 (&hb)[bins_of(T) / T], int slot, Shared<T> &sh, int &cached_bin, int &cached_cnt,
                                             u64 &cached_before, uint32_t &key_o, int &idx_o, u64 &mass_o) {
   const int tid = threadIdx.x;
@@ -339,15 +329,12 @@ __device__ __forceinline__ void find_prefix(const float (&l)[E], const float *lg
     }
     __syncthreads();
     cnt = sh.ncand[slot];
-#ifdef DP_PHASE_CLOCKS
-    if (threadIdx.x == 0 && g_dbg_ptr) g_dbg_ptr[blockIdx.x * 16 + 13 + slot] = cnt;
-#endif
     cached_bin = bin1;
     cached_cnt = cnt;
     cached_before = before;
     if (cnt > kMaxCand) {
       cached_bin = -1;  // the candidate arrays will not hold this bin
-      const Refined rf = refine_or_cut_ties<E, kCount, T>(lg, kc, mx, bs, base, bin1, tau, before, &sh);
+      const Refined rf = refine_or_cut_ties<E, kCount, T>(lg, kc, mx, bs, base, bin1, tau, before, masked, &sh);
       const uint32_t klo = rf.klo, khi = rf.khi;
       before = rf.before;
       cnt = rf.cnt;
@@ -486,12 +473,6 @@ __global__ __launch_bounds__(T) void select_kernel(SelectArgs a) {
   emit.plan = plan;
 
   if (plan && tid == 0 && head % kMaxQueueHeads == 0) a.plan.queue_next[head / kMaxQueueHeads] = 0;
-
-#ifdef DP_PHASE_CLOCKS
-  if (threadIdx.x == 0) g_dbg_ptr = a.dbg;
-  __syncthreads();
-#endif
-  DP_MARK(0);
   // ---- load, max ---------------------------------------------------------
   float l[E];
   if (E >= 4 && (reinterpret_cast<uintptr_t>(lg) & 15) == 0 && base + E <= kc) {
@@ -536,7 +517,7 @@ __global__ __launch_bounds__(T) void select_kernel(SelectArgs a) {
   }
   // Pinned clusters (the caller's sink / window tokens): their logits leave the distribution here and
   // they join the exact list further down.  bit e of pinmask: element e is a pinned, non-empty cluster.
-  u64 pinmask = 0;
+  u64 pinmask = 0, flagged = 0;  // flagged: every element that carries the flag, empty clusters included
   const bool has_flags = a.cluster_flags != nullptr;
   if (has_flags) {
     const uint8_t *fp = a.cluster_flags + c0 + base;
@@ -556,6 +537,7 @@ __global__ __launch_bounds__(T) void select_kernel(SelectArgs a) {
       for (int e = 0; e < E; ++e)
         if (base + e < kc && (fp[e] & 1u)) pinmask |= 1ull << e;
     }
+    flagged = pinmask;
 #pragma unroll
     for (int e = 0; e < E; ++e)
       if ((pinmask >> e) & 1) {
@@ -574,8 +556,6 @@ __global__ __launch_bounds__(T) void select_kernel(SelectArgs a) {
     tmax = fmaxf(tmax, l[e]);
   }
   const float mx_raw = block_max<(T / 64)>(tmax, sh.scrf);  // its barriers also publish the zeroed LDS
-
-  DP_MARK(1);
   // no candidate cluster, or a budget of 0: the distribution selects nothing
   const bool nothing = mx_raw == -INFINITY || (kCount && a.k_retained <= 0);
   const float mx = mx_raw == -INFINITY ? 0.f : mx_raw;
@@ -638,7 +618,6 @@ __global__ __launch_bounds__(T) void select_kernel(SelectArgs a) {
     Wtop = partials_sum<u64, (T / 64)>(sh.scr64b);
     ntop = partials_sum<int, (T / 64)>(sh.scri);
   }
-  DP_MARK(2);
 
   int n_ex, n_ap, n_tok;
   const bool all = !nothing && retain_all<kCount>(a, W);  // every non-empty candidate is retained
@@ -721,7 +700,6 @@ __global__ __launch_bounds__(T) void select_kernel(SelectArgs a) {
     n_ap = sh.f_nap;
     n_tok = sh.f_ntok;
   }
-  DP_MARK(3);
 
   if (!fast) {
     // the prefix ends: the last retained and the last exact cluster of the order as (key, index); the
@@ -737,7 +715,6 @@ __global__ __launch_bounds__(T) void select_kernel(SelectArgs a) {
         if (m) atomicAdd(&sh.hist[level1_bin(d, bs, kBins)], m);
       }
       __syncthreads();
-      DP_MARK(8);
       constexpr int B = kBins / T;  // consecutive bins per thread
       u64 hb[B], hsum = 0;
 #pragma unroll
@@ -747,7 +724,6 @@ __global__ __launch_bounds__(T) void select_kernel(SelectArgs a) {
       }
       u64 Wh;  // equals W: the same masses, summed in another order
       const u64 ex = block_excl_scan<u64, (T / 64)>(hsum, sh.scr64, Wh);
-      DP_MARK(9);
 
       u64 mass1;
       int cached_bin = -1, cached_cnt = 0;
@@ -757,10 +733,9 @@ __global__ __launch_bounds__(T) void select_kernel(SelectArgs a) {
         idx1 = INT_MAX;
         mass1 = W;
       } else {
-        find_prefix<E, kCount, T>(l, lg, kc, mx, bs, base, first_tau<kCount>(a, W), ex, hb, 0, sh, cached_bin, cached_cnt,
+        find_prefix<E, kCount, T>(l, lg, kc, mx, bs, base, flagged, first_tau<kCount>(a, W), ex, hb, 0, sh, cached_bin, cached_cnt,
                                cached_before, key1, idx1, mass1);
       }
-      DP_MARK(10);
       u64 tau2 = 0;
       const int kind = second_tau<kCount>(a, W, mass1, tau2);
       if (kind == 1) {
@@ -772,12 +747,11 @@ __global__ __launch_bounds__(T) void select_kernel(SelectArgs a) {
       } else {
         u64 mass2;
         __syncthreads();  // sh.bin / sh.res_* of the first search have been read by every thread
-        find_prefix<E, kCount, T>(l, lg, kc, mx, bs, base, tau2, ex, hb, 1, sh, cached_bin, cached_cnt, cached_before, key2, idx2,
+        find_prefix<E, kCount, T>(l, lg, kc, mx, bs, base, flagged, tau2, ex, hb, 1, sh, cached_bin, cached_cnt, cached_before, key2, idx2,
                                mass2);
       }
 
     }
-    DP_MARK(11);
     // ---- compaction in ascending cluster index ------------------------------
     // Only clusters in play (non-zero weight) can be selected, unless all non-empty ones are.
     u64 exa_mask = 0, ret_mask = 0;  // bit e: element e of this thread is exact / approximated
@@ -816,7 +790,6 @@ __global__ __launch_bounds__(T) void select_kernel(SelectArgs a) {
       pa = row16_sum(mine ? sa : 0) + ia - ca;
       pt = row16_sum(mine ? st : 0) + it - te;
     }
-    DP_MARK(12);
     emit.to_lds = can_inline && n_tok + n_ap <= kInlineRows;
     emit.n_ex = n_ex;
     emit.n_tok = n_tok;
@@ -836,7 +809,6 @@ __global__ __launch_bounds__(T) void select_kernel(SelectArgs a) {
       }
     }
   }
-  DP_MARK(4);
 
   const int R = n_tok + n_ap;
   const bool inline_attn = can_inline && R <= kInlineRows;
@@ -865,7 +837,6 @@ __global__ __launch_bounds__(T) void select_kernel(SelectArgs a) {
 
   // ---- inline attention for a head with few rows ---------------------------
   __syncthreads();
-  DP_MARK(5);
   {
     const int lane16 = tid & 15, grp = tid >> 4;
     const uint4 qv = load_row_slice(a.q, (int64_t)head, lane16);
@@ -883,7 +854,6 @@ __global__ __launch_bounds__(T) void select_kernel(SelectArgs a) {
     const int per = kAttendBatch * ((R + kGroups * kAttendBatch - 1) / (kGroups * kAttendBatch));
     const int ra = grp * per, rb = min(R, ra + per);
     attend_rows(st, qv, a.scale_log2, src, sh.at.l_start, sh.at.l_src, n_ex + n_ap, 0, n_ex, ra, rb, kAttendBatch, lane16);
-    DP_MARK(6);
     float M, L, o;
     const int groups_used = (R + per - 1) / per;
     block_merge<(T / 64)>(st, sh.at.m_m, sh.at.m_l, sh.at.m_acc, (groups_used + 3) / 4, M, L, o);
@@ -891,7 +861,6 @@ __global__ __launch_bounds__(T) void select_kernel(SelectArgs a) {
       store_out(a.attn_out, a.out_is_bf16, head, tid, o / L);
       if (a.lse && tid == 0) a.lse[head] = (M + log2f(L)) * kLn2;
     }
-    DP_MARK(7);
   }
 }
 
@@ -974,10 +943,6 @@ void launch_select_e(const SelectArgs &a, bool by_count, dim3 grid, hipStream_t 
 
 }  // namespace
 
-#ifdef DP_PHASE_CLOCKS
-unsigned long long *g_phase_clock_buffer = nullptr;
-extern "C" void dp_debug_set_phase_clock_buffer(void *p) { g_phase_clock_buffer = (unsigned long long *)p; }
-#endif
 
 hipError_t launch_select(const CacheView &c, const float *logits, const SelectRule &rule, const SelectOut &out,
                          const Plan &plan, const AttnOut &attn, hipStream_t s, hipEvent_t start, hipEvent_t stop) {
@@ -1010,9 +975,6 @@ hipError_t launch_select(const CacheView &c, const float *logits, const SelectRu
   a.lse = attn.lse;
   a.out_is_bf16 = attn.out_is_bf16;
   a.scale_log2 = c.sm_scale * kLog2e;
-#ifdef DP_PHASE_CLOCKS
-  a.dbg = g_phase_clock_buffer;
-#endif
   const dim3 grid(c.batch * c.n_q_heads);
   if (grid.x == 0) return hipSuccess;
   const int k = c.max_clusters_per_seg;

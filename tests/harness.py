@@ -105,8 +105,9 @@ def gpu_sparse_decode(cache: ClusteredCache, exact: List[np.ndarray], approx: Li
 
 
 def gpu_decode_attention(cache: ClusteredCache, p1: float, p2: float, flags: int = 0, sm_scale: float = 0.0,
-                         want_logits: bool = False, dc=None, budget=None) -> GpuStep:
-    """budget = (k_retained, k_exact): dp_budget_decode_attention instead of dp_decode_attention."""
+                         want_logits: bool = False, dc=None, budget=None, out_bf16: bool = False) -> GpuStep:
+    """budget = (k_retained, k_exact): dp_budget_decode_attention instead of dp_decode_attention.
+    out_bf16: ask the library for a bf16 output (returned widened to float32)."""
     import torch
     import paper_2602_05191_amd as dp
     if dc is None:
@@ -115,7 +116,8 @@ def gpu_decode_attention(cache: ClusteredCache, p1: float, p2: float, flags: int
     nh, mk = cache.batch * cache.n_q_heads, max(cache.max_clusters_per_seg, 1)
     nbytes = dp.dp_workspace_bytes(pr)
     ws = torch.zeros(max(nbytes, 256), dtype=torch.uint8, device="cuda:0")
-    out = torch.full((cache.batch, cache.n_q_heads, cache.head_dim), float("nan"), dtype=torch.float32, device="cuda:0")
+    out = torch.full((cache.batch, cache.n_q_heads, cache.head_dim), float("nan"),
+                     dtype=torch.bfloat16 if out_bf16 else torch.float32, device="cuda:0")
     lse = torch.full((nh,), float("nan"), dtype=torch.float32, device="cuda:0")
     ne = torch.full((nh,), -7, dtype=torch.int32, device="cuda:0")
     nr, nt = ne.clone(), ne.clone()
@@ -137,7 +139,7 @@ def gpu_decode_attention(cache: ClusteredCache, p1: float, p2: float, flags: int
             for h in range(cache.n_q_heads):
                 s, kc = head_logit_slice(cache, b, h)
                 logits.append(flat[s:s + kc].copy())
-    return GpuStep(out=out.cpu().numpy(), lse=lse.cpu().numpy().reshape(cache.batch, cache.n_q_heads),
+    return GpuStep(out=out.float().cpu().numpy(), lse=lse.cpu().numpy().reshape(cache.batch, cache.n_q_heads),
                    exact=[sel[i, :ne[i]].copy() for i in range(nh)],
                    approx=[sel[i, ne[i]:nr[i]].copy() for i in range(nh)], n_exact_tokens=nt, logits=logits)
 
@@ -194,6 +196,38 @@ def prefix_set_ok(got: np.ndarray, want: np.ndarray, a_hat: np.ndarray, logit: n
     return bool(ok), False
 
 
+def judge_head_sets(where, got_exact, got_approx, cand_logit, pins, p1, p2, flags, orc):
+    """One head's retained / exact sets against the oracle's selection on `cand_logit` (fp64 logits of the
+    candidates: pinned and empty clusters at -inf).  Pinned clusters must all be exact; the rest is judged as a
+    selection among the candidates, the second stage conditionally on the GPU's own retained set.  Raises on a
+    difference beyond the near-threshold rule; returns True when both sets equal the oracle's."""
+    assert (np.diff(got_exact) > 0).all() and (np.diff(got_approx) > 0).all(), f"{where}: ids not ascending"
+    assert len(np.intersect1d(got_exact, got_approx)) == 0
+    assert np.isin(pins, got_exact).all() and not np.isin(pins, got_approx).any(), f"{where}: pinned"
+    s = orc.select(cand_logit, p1, p2, flags)
+    got_ex = np.setdiff1d(got_exact, pins).astype(np.int64)
+    got_ret = np.sort(np.concatenate([got_ex, got_approx])).astype(np.int64)
+    if s.order.size == 0:
+        assert got_ret.size == 0, f"{where}: selected {got_ret[:8]} although no cluster is a candidate"
+        return True
+    if p1 >= 1.0:
+        ok1 = same1 = np.array_equal(got_ret, s.retained)
+    else:
+        ok1, same1 = prefix_set_ok(got_ret, s.retained.astype(np.int64), s.a_hat, cand_logit, p1)
+    assert ok1, f"{where}: retained set differs beyond tolerance: gpu {got_ret[:16]} oracle {s.retained[:16]}"
+    m1 = s.a_hat[got_ret].sum()
+    if p2 >= 1.0:
+        ok2 = same2 = np.array_equal(got_ex, got_ret)
+    elif p2 <= 0.0:
+        ok2 = same2 = got_ex.size == 0
+    else:
+        tau2 = min(p2, m1) if (flags & 1) else p2 * m1
+        want = s.exact.astype(np.int64) if same1 else oracle_prefix(s, tau2)
+        ok2, same2 = prefix_set_ok(got_ex, want, s.a_hat, cand_logit, tau2)
+    assert ok2, f"{where}: exact set differs beyond tolerance: gpu {got_ex[:16]} oracle {s.exact[:16]}"
+    return bool(same1 and same2)
+
+
 def check_sets(cache: ClusteredCache, orc: "oracle.Oracle", g: GpuStep, p1: float, p2: float, flags: int = 0):
     """Compare the GPU's retained / exact sets with the oracle's for every head.  Returns the
     number of heads with a tolerated (near-threshold) difference; raises on a real mismatch."""
@@ -202,43 +236,11 @@ def check_sets(cache: ClusteredCache, orc: "oracle.Oracle", g: GpuStep, p1: floa
         for h in range(cache.n_q_heads):
             i = b * cache.n_q_heads + h
             pins = orc.pinned_clusters(b, h)
-            logit = orc.candidate_logits(b, h)
+            logit = orc.candidate_logits(b, h)   # pinned logits are -inf here: the candidates alone
             full = orc.select(logit, p1, p2, flags, pinned=pins)
-            assert (np.diff(g.exact[i]) > 0).all() and (np.diff(g.approx[i]) > 0).all(), f"head {i}: ids not ascending"
-            assert len(np.intersect1d(g.exact[i], g.approx[i])) == 0
-            # pinned clusters: all of them exact; the rest is judged as a selection among the candidates
-            assert np.isin(pins, g.exact[i]).all() and not np.isin(pins, g.approx[i]).any(), f"head {i}: pinned"
-            s = orc.select(logit, p1, p2, flags)   # pinned logits are -inf here: the candidates alone
-            assert np.array_equal(full.exact, np.sort(np.concatenate([pins, s.exact])))
-            got_ex = np.setdiff1d(g.exact[i], pins).astype(np.int64)
-            got_ret = np.sort(np.concatenate([got_ex, g.approx[i]])).astype(np.int64)
-            if s.order.size == 0:
-                assert got_ret.size == 0
-                seg = b * cache.n_kv_heads + h // cache.group
-                c0 = int(cache.seg_cluster_ptr[seg])
-                assert int(g.n_exact_tokens[i]) == int(cache.cluster_sizes[c0 + pins].sum())
-                continue
-            tau1 = p1 if p1 < 1.0 else s.a_hat.sum()
-            if p1 >= 1.0:
-                ok1, same1 = np.array_equal(got_ret, s.retained), np.array_equal(got_ret, s.retained)
-            else:
-                ok1, same1 = prefix_set_ok(got_ret, s.retained.astype(np.int64), s.a_hat, logit, tau1)
-            assert ok1, f"head ({b},{h}): retained set differs beyond tolerance: gpu {got_ret[:16]} oracle {s.retained[:16]}"
-            # second stage is judged conditionally on the GPU's own retained set
-            m1 = s.a_hat[got_ret].sum()
-            if p2 >= 1.0:
-                ok2 = same2 = np.array_equal(got_ex, got_ret)
-            elif p2 <= 0.0:
-                ok2 = same2 = got_ex.size == 0
-            else:
-                tau2 = min(p2, m1) if (flags & 1) else p2 * m1
-                if same1:
-                    ok2, same2 = prefix_set_ok(got_ex, s.exact.astype(np.int64), s.a_hat, logit, tau2)
-                else:
-                    want = oracle_prefix(s, tau2)
-                    ok2, same2 = prefix_set_ok(got_ex, want, s.a_hat, logit, tau2)
-            assert ok2, f"head ({b},{h}): exact set differs beyond tolerance: gpu {got_ex[:16]} oracle {s.exact[:16]}"
-            tolerated += int(not (same1 and same2))
+            assert np.array_equal(full.exact, np.sort(np.concatenate([pins, orc.select(logit, p1, p2, flags).exact])))
+            same = judge_head_sets(f"head ({b},{h})", g.exact[i], g.approx[i], logit, pins, p1, p2, flags, orc)
+            tolerated += int(not same)
             seg = b * cache.n_kv_heads + h // cache.group
             c0 = int(cache.seg_cluster_ptr[seg])
             assert int(g.n_exact_tokens[i]) == int(cache.cluster_sizes[c0 + np.asarray(g.exact[i], np.int64)].sum())

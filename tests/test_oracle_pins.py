@@ -102,6 +102,10 @@ def test_hand_case_selection_and_output(hand):
     assert o.select(logit, e["p1"], 0.6).k2 == e["p2_0.6_renormalised"]["k2"]
     sa = o.select(logit, e["p1"], 0.6, flags=oracle.P2_ABSOLUTE)
     assert sa.k2 == e["p2_0.6_absolute"]["k2"]
+    outa, lsea = o.mixed_attention(0, 0, sa.exact, sa.approx)                                # Eq. 8, Eq. 9 on those sets
+    np.testing.assert_allclose(outa, np.array(e["p2_0.6_absolute"]["out_num"]) / e["p2_0.6_absolute"]["out_den"],
+                               rtol=1e-14)
+    assert lsea == pytest.approx(math.log(e["p2_0.6_absolute"]["Z_tilde"]), rel=1e-14)
     # p2 = 0: everything retained is approximated
     s0 = o.select(logit, e["p1"], 0.0)
     assert s0.k2 == 0
