@@ -179,20 +179,12 @@ dp_status whole_step(const dp_problem *problem, const dp::SelectRule &rule, void
   const int n_slabs = (int)(((size_t)problem->batch * problem->n_q_heads + dp::kMaxQueueHeads - 1) / dp::kMaxQueueHeads);
   if (problem->max_clusters_per_seg > 0 && n_slabs <= 256) w.plan.pending = w.plan.queue_next + n_slabs;
   if (dp::launch_score(c, w.logits, s, ev[0], ev[1], w.plan.pending, n_slabs) != hipSuccess) return DP_ERR_HIP;
-  dp::SelectOut so{w.sel_ids, w.n_exact, w.n_retained, w.n_exact_tokens};
+  // the optional count outputs are written by the selection kernel next to the workspace's own
+  dp::SelectOut so{w.sel_ids, w.n_exact, w.n_retained, w.n_exact_tokens, n_exact, n_retained, n_exact_tokens};
   const dp::AttnOut attn{out, lse, out_dtype == DP_BF16};
   if (dp::launch_select(c, w.logits, rule, so, w.plan, attn, s, ev[2], ev[3]) != hipSuccess) return DP_ERR_HIP;
   if (dp::launch_decode(c, w.n_exact, w.n_retained, w.plan, w.partials, w.splits, attn, s, ev[4], ev[5]) !=
       hipSuccess)
-    return DP_ERR_HIP;
-  const size_t nh = (size_t)problem->batch * problem->n_q_heads;
-  // optional count outputs: device-to-device copies on the same stream
-  if (n_exact && hipMemcpyAsync(n_exact, w.n_exact, nh * 4, hipMemcpyDeviceToDevice, s) != hipSuccess)
-    return DP_ERR_HIP;
-  if (n_retained && hipMemcpyAsync(n_retained, w.n_retained, nh * 4, hipMemcpyDeviceToDevice, s) != hipSuccess)
-    return DP_ERR_HIP;
-  if (n_exact_tokens &&
-      hipMemcpyAsync(n_exact_tokens, w.n_exact_tokens, nh * 4, hipMemcpyDeviceToDevice, s) != hipSuccess)
     return DP_ERR_HIP;
   return DP_OK;
 }

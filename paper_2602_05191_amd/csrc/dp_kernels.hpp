@@ -53,6 +53,8 @@ struct AttnOut {
 struct SelectOut {
   int32_t *sel_ids;  // [nh, max_k]
   int32_t *n_exact, *n_retained, *n_exact_tokens;  // [nh]
+  // nullable: second copies of the three counts (the caller's optional outputs of the one-call entry points)
+  int32_t *n_exact_copy = nullptr, *n_retained_copy = nullptr, *n_exact_tokens_copy = nullptr;
 };
 
 // start / stop (nullable): HIP events that receive the kernel's own begin and end timestamps

@@ -441,6 +441,15 @@ __device__ __forceinline__ int second_tau(const SelectArgs &a, u64 W, u64 m1, u6
   return top_p_second_tau(a.p2, a.p2_absolute != 0, W, m1, tau2);
 }
 
+__device__ __forceinline__ void put_counts(const SelectOut &o, int head, int n_exact, int n_retained, int n_tokens) {
+  o.n_exact[head] = n_exact;
+  o.n_retained[head] = n_retained;
+  o.n_exact_tokens[head] = n_tokens;
+  if (o.n_exact_copy) o.n_exact_copy[head] = n_exact;
+  if (o.n_retained_copy) o.n_retained_copy[head] = n_retained;
+  if (o.n_exact_tokens_copy) o.n_exact_tokens_copy[head] = n_tokens;
+}
+
 template <int E, bool kCount, int T>
 __global__ __launch_bounds__(T) void select_kernel(SelectArgs a) {
   __shared__ Shared<T> sh;
@@ -561,9 +570,7 @@ __global__ __launch_bounds__(T) void select_kernel(SelectArgs a) {
   const float mx = mx_raw == -INFINITY ? 0.f : mx_raw;
   if (nothing && !has_flags) {  // and nothing can be pinned: zero output
     if (tid == 0) {
-      a.out.n_exact[head] = 0;
-      a.out.n_retained[head] = 0;
-      a.out.n_exact_tokens[head] = 0;
+      put_counts(a.out, head, 0, 0, 0);
       if (plan) {
         emit.row_start[0] = 0;
         a.plan.head_rows[head] = 0;
@@ -813,9 +820,7 @@ __global__ __launch_bounds__(T) void select_kernel(SelectArgs a) {
   const int R = n_tok + n_ap;
   const bool inline_attn = can_inline && R <= kInlineRows;
   if (tid == 0) {
-    a.out.n_exact[head] = n_ex;
-    a.out.n_retained[head] = n_ex + n_ap;
-    a.out.n_exact_tokens[head] = n_tok;
+    put_counts(a.out, head, n_ex, n_ex + n_ap, n_tok);
     if (plan) {
       if (inline_attn) {
         sh.at.l_start[n_ex + n_ap] = R;
