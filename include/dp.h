@@ -42,7 +42,8 @@ typedef enum {
   DP_ERR_INVALID_ARG = -1,         /* null pointer, non-positive shape, p outside its domain        */
   DP_ERR_UNSUPPORTED = -2,         /* head_dim != 128, n_q_heads/n_kv_heads > 16, unknown dtype     */
   DP_ERR_WORKSPACE_TOO_SMALL = -3, /* workspace_bytes < dp_workspace_bytes(problem)                 */
-  DP_ERR_HIP = -4                  /* a HIP runtime call failed (launch error)                      */
+  DP_ERR_HIP = -4,                 /* a HIP runtime call failed (launch error)                      */
+  DP_ERR_TOO_LARGE = -5            /* dp_decode_attention_static: dp_workspace_bytes(problem) > DP_STATIC_SCRATCH_BYTES */
 } dp_status;
 
 typedef enum { DP_BF16 = 0, DP_F32 = 1 } dp_dtype;
@@ -174,6 +175,27 @@ dp_status dp_sparse_decode_gathered(const dp_problem *problem, const int32_t *se
 dp_status dp_decode_attention(const dp_problem *problem, float p1, float p2, void *out, dp_dtype out_dtype,
                               float *lse, int32_t *n_exact, int32_t *n_retained, int32_t *n_exact_tokens,
                               void *workspace, size_t workspace_bytes, void *stream);
+
+/* dp_decode_attention for callers that cannot allocate device memory or hand over a
+ * workspace: code under HIP graph capture, tight serving loops, harnesses that
+ * forbid hipMalloc.  Same computation, same kernels and same results as
+ * dp_decode_attention; the workspace is a device array of DP_STATIC_SCRATCH_BYTES
+ * that is part of the library's code object (each GPU the library runs on holds
+ * its own copy until the process ends).  The call allocates and frees nothing
+ * and records no memset: every counter in the scratch is cleared by the kernels
+ * that use it.  The first call on a device looks the array's address up
+ * (hipGetSymbolAddress, with that device current); make that call outside a
+ * graph capture.
+ *   DP_ERR_TOO_LARGE  dp_workspace_bytes(problem) > DP_STATIC_SCRATCH_BYTES (checked on
+ *                     the host before anything is launched; 16 MiB holds batch 1 x
+ *                     32 query heads x 8192 clusters per KV head at 131072 tokens)
+ * All calls on one GPU share that GPU's array and find the previous call's
+ * contents in it: calls that overlap on one GPU (two streams, two threads) race;
+ * calls on one stream, or otherwise ordered by the caller, do not. */
+#define DP_STATIC_SCRATCH_BYTES (16u << 20)
+dp_status dp_decode_attention_static(const dp_problem *problem, float p1, float p2, void *out, dp_dtype out_dtype,
+                                     float *lse, int32_t *n_exact, int32_t *n_retained, int32_t *n_exact_tokens,
+                                     void *stream);
 
 /* dp_decode_attention for measurement: events is a HOST array of 6 hipEvent_t
  * (passed as void*, created by the caller with timing enabled, any may be

@@ -28,6 +28,7 @@ EXPORTS = ["dp_workspace_bytes", "dp_logits_count", "dp_get_workspace_layout", "
            "dp_group_union_decode_attention",
            "dp_decode_attention_timed", "dp_budget_decode_attention", "dp_dense_decode", "dp_build_workspace_bytes", "dp_build_cluster_cache", "dp_kmeans_workspace_bytes",
            "dp_kmeans_assign",
+           "dp_decode_attention_static",
            "dp_status_string"]
 
 
@@ -94,6 +95,8 @@ def load_library():
     L.dp_sparse_decode.argtypes = [PP, V, V, V, V, V, I, V, V, C.c_size_t, V]
     L.dp_decode_attention.restype = I
     L.dp_decode_attention.argtypes = [PP, F, F, V, I, V, V, V, V, V, C.c_size_t, V]
+    L.dp_decode_attention_static.restype = I
+    L.dp_decode_attention_static.argtypes = [PP, F, F, V, I, V, V, V, V, V]
     L.dp_decode_attention_timed.restype = I
     L.dp_decode_attention_timed.argtypes = [PP, F, F, V, I, V, V, C.c_size_t, V, C.POINTER(C.c_void_p)]
     L.dp_topp_select_sorted.restype = I
@@ -270,6 +273,21 @@ def dp_decode_attention(problem: Problem, p1: float, p2: float, out: torch.Tenso
                                               _ptr(n_retained), _ptr(n_exact_tokens), _ptr(workspace),
                                               workspace.numel() * workspace.element_size(), _stream(stream)),
            "dp_decode_attention")
+
+
+DP_STATIC_SCRATCH_BYTES = 16 << 20
+
+
+def dp_decode_attention_static(problem: Problem, p1: float, p2: float, out: torch.Tensor,
+                               lse: Optional[torch.Tensor], n_exact: Optional[torch.Tensor] = None,
+                               n_retained: Optional[torch.Tensor] = None,
+                               n_exact_tokens: Optional[torch.Tensor] = None, stream=None) -> None:
+    """dp_decode_attention with the library's own static scratch array in place of a workspace."""
+    dt = {torch.float32: DP_F32, torch.bfloat16: DP_BF16}[out.dtype]
+    assert out.is_contiguous() and out.numel() == problem.nh * problem.dc.head_dim
+    _check(load_library().dp_decode_attention_static(problem.ref, p1, p2, _ptr(out), dt, _ptr(lse), _ptr(n_exact),
+                                                     _ptr(n_retained), _ptr(n_exact_tokens), _stream(stream)),
+           "dp_decode_attention_static")
 
 
 def dp_budget_decode_attention(problem: Problem, k_retained: int, k_exact: int, out: torch.Tensor,

@@ -5,6 +5,8 @@
 
 #include <math.h>
 
+#include <atomic>
+
 #include "dp_kernels.hpp"
 
 namespace {
@@ -189,6 +191,28 @@ dp_status whole_step(const dp_problem *problem, const dp::SelectRule &rule, void
   return DP_OK;
 }
 
+// ---- workspace of dp_decode_attention_static: a device array that lives in the library's code object ----
+// Every GPU that loads the library holds its own copy until the process ends.  In host code the array's name
+// only stands for the symbol; its device address on the current device comes from hipGetSymbolAddress, once per
+// device, and only that pointer is ever handed to a kernel.
+static __device__ __align__(256) unsigned char scratch[DP_STATIC_SCRATCH_BYTES];
+constexpr int kMaxDevices = 64;
+std::atomic<void *> g_scratch_ptr[kMaxDevices];  // per device: the address of `scratch` there, nullptr until asked
+
+dp_status static_scratch(void **ptr) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess) return DP_ERR_HIP;
+  if (dev < 0 || dev >= kMaxDevices) return DP_ERR_UNSUPPORTED;
+  void *p = g_scratch_ptr[dev].load(std::memory_order_acquire);
+  if (!p) {
+    // first call on this device (it is the current one); threads that race here get the same address
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return DP_ERR_HIP;
+    g_scratch_ptr[dev].store(p, std::memory_order_release);
+  }
+  *ptr = p;
+  return DP_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -358,6 +382,22 @@ dp_status dp_decode_attention(const dp_problem *problem, float p1, float p2, voi
                     workspace, workspace_bytes, stream);
 }
 
+dp_status dp_decode_attention_static(const dp_problem *problem, float p1, float p2, void *out, dp_dtype out_dtype,
+                                     float *lse, int32_t *n_exact, int32_t *n_retained, int32_t *n_exact_tokens,
+                                     void *stream) {
+  dp_status st = check_common(problem);
+  if (st != DP_OK) return st;
+  if (!p_in_domain(p1, p2)) return DP_ERR_INVALID_ARG;
+  const size_t need = dp_workspace_bytes(problem);
+  if (need > (size_t)DP_STATIC_SCRATCH_BYTES) return DP_ERR_TOO_LARGE;  // before anything touches the device
+  void *ws = nullptr;
+  st = static_scratch(&ws);
+  if (st != DP_OK) return st;
+  // every kernel of the step clears the counters it reads (no memset): what an earlier call left behind is dead
+  return whole_step(problem, top_p_rule(problem, p1, p2), out, out_dtype, lse, n_exact, n_retained, n_exact_tokens,
+                    ws, need, stream);
+}
+
 dp_status dp_decode_attention_timed(const dp_problem *problem, float p1, float p2, void *out, dp_dtype out_dtype,
                                     float *lse, void *workspace, size_t workspace_bytes, void *stream,
                                     void *const *events) {
@@ -482,6 +522,9 @@ const char *dp_status_string(dp_status status) {
     case DP_ERR_UNSUPPORTED: return "DP_ERR_UNSUPPORTED: head_dim != 128, GQA group > 16, too many clusters or bad dtype";
     case DP_ERR_WORKSPACE_TOO_SMALL: return "DP_ERR_WORKSPACE_TOO_SMALL: see dp_workspace_bytes";
     case DP_ERR_HIP: return "DP_ERR_HIP: a HIP runtime call failed";
+    case DP_ERR_TOO_LARGE:
+      return "DP_ERR_TOO_LARGE: the problem needs more scratch than DP_STATIC_SCRATCH_BYTES (use dp_decode_attention "
+             "with a caller-owned workspace)";
   }
   return "unknown dp_status";
 }

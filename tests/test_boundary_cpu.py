@@ -77,8 +77,14 @@ def test_host_side_argument_checks_without_launch(lib):
     assert lib.dp_topp_select(C.byref(q), one, 0.9, 0.5, one, one, one, one, None) == -2
     q = _problem(k_centroids=None)
     assert lib.dp_score_centroids(C.byref(q), one, None) == -1
-    for s in (0, -1, -2, -3, -4):
+    for s in (0, -1, -2, -3, -4, -5):
         assert lib.dp_status_string(s).decode().startswith("DP_")
+    # the entry point with the static scratch: a problem whose workspace exceeds the array is refused on the host
+    big = _problem(batch=4, n_q_heads=64, total_clusters=4 * 65536)
+    assert lib.dp_workspace_bytes(C.byref(big)) > (16 << 20)
+    assert lib.dp_decode_attention_static(C.byref(big), 0.9, 0.5, one, 1, None, None, None, None, None) == -5
+    assert lib.dp_decode_attention_static(C.byref(p), 0.0, 0.5, one, 1, None, None, None, None, None) == -1
+    assert lib.dp_workspace_bytes(C.byref(p)) <= (16 << 20)         # the 8B shape at 131072 tokens fits
 
 
 def test_product_package_does_not_import_the_oracle():
