@@ -318,6 +318,8 @@ typedef struct {
   size_t logits, sel_ids, row_start, chunk_entry, counts, partials, total;
   int32_t splits;      /* partial results per head in stage 3          */
   int32_t chunk_rows;  /* granularity (rows) of the stage-3 work split */
+  size_t summaries;    /* float2 [heads, ceil(max_clusters_per_seg / 16)]: per head and run of 16 clusters the
+                          largest logit and the sum of exp(logit - that), left by the scoring stage */
 } dp_workspace_layout;
 dp_status dp_get_workspace_layout(const dp_problem *problem, dp_workspace_layout *layout /* host */);
 

@@ -59,7 +59,7 @@ class _Prefill(C.Structure):
 class _Layout(C.Structure):
     _fields_ = [("logits", C.c_size_t), ("sel_ids", C.c_size_t), ("row_start", C.c_size_t),
                 ("chunk_entry", C.c_size_t), ("counts", C.c_size_t), ("partials", C.c_size_t),
-                ("total", C.c_size_t), ("splits", C.c_int32), ("chunk_rows", C.c_int32)]
+                ("total", C.c_size_t), ("splits", C.c_int32), ("chunk_rows", C.c_int32), ("summaries", C.c_size_t)]
 
 
 _lib = None

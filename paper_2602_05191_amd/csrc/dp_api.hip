@@ -94,6 +94,8 @@ void layout_of(const dp_problem *p, dp_workspace_layout *L) {
   off = align_up(off + sizeof(int32_t) * (5 * nh + 2 * ((nh + dp::kMaxQueueHeads - 1) / dp::kMaxQueueHeads)), 256);
   L->partials = off;
   off = align_up(off + sizeof(float) * nh * (size_t)splits * (dp::kHeadDim + 2), 256);
+  L->summaries = off;  // (max, sum exp) per head and sub-tile of kSubTile clusters
+  off = align_up(off + sizeof(float2) * nh * ((mk + dp::kSubTile - 1) / dp::kSubTile), 256);
   L->total = off;
   L->splits = splits;
   L->chunk_rows = dp::kChunkRows;
@@ -105,6 +107,8 @@ struct Workspace {
   int32_t *sel_ids, *n_exact, *n_retained, *n_exact_tokens;
   dp::Plan plan;
   float *partials;
+  float2 *summaries;
+  int sub_stride;
   int splits;
 };
 
@@ -130,6 +134,8 @@ Workspace carve(const dp_problem *p, void *ws) {
   w.plan.queue_next = counts + 5 * nh;
   w.plan.pending = nullptr;  // the one-call path turns it on (its scoring kernel clears the counters)
   w.partials = reinterpret_cast<float *>(b + L.partials);
+  w.summaries = reinterpret_cast<float2 *>(b + L.summaries);
+  w.sub_stride = (int)((mk + dp::kSubTile - 1) / dp::kSubTile);
   w.splits = L.splits;
   return w;
 }
@@ -180,11 +186,15 @@ dp_status whole_step(const dp_problem *problem, const dp::SelectRule &rule, void
   hipStream_t s = static_cast<hipStream_t>(stream);
   const int n_slabs = (int)(((size_t)problem->batch * problem->n_q_heads + dp::kMaxQueueHeads - 1) / dp::kMaxQueueHeads);
   if (problem->max_clusters_per_seg > 0 && n_slabs <= 256) w.plan.pending = w.plan.queue_next + n_slabs;
-  if (dp::launch_score(c, w.logits, s, ev[0], ev[1], w.plan.pending, n_slabs) != hipSuccess) return DP_ERR_HIP;
+  // the summaries serve the top-p rule on heads without cluster flags
+  float2 *summ = (!rule.by_count && !problem->cluster_flags && rule.p1 < 1.0f) ? w.summaries : nullptr;
+  if (dp::launch_score(c, w.logits, s, ev[0], ev[1], w.plan.pending, n_slabs, summ, w.sub_stride) != hipSuccess)
+    return DP_ERR_HIP;
   // the optional count outputs are written by the selection kernel next to the workspace's own
   dp::SelectOut so{w.sel_ids, w.n_exact, w.n_retained, w.n_exact_tokens, n_exact, n_retained, n_exact_tokens};
   const dp::AttnOut attn{out, lse, out_dtype == DP_BF16};
-  if (dp::launch_select(c, w.logits, rule, so, w.plan, attn, s, ev[2], ev[3]) != hipSuccess) return DP_ERR_HIP;
+  if (dp::launch_select(c, w.logits, rule, so, w.plan, attn, s, ev[2], ev[3], summ, w.sub_stride) != hipSuccess)
+    return DP_ERR_HIP;
   if (dp::launch_decode(c, w.n_exact, w.n_retained, w.plan, w.partials, w.splits, attn, s, ev[4], ev[5]) !=
       hipSuccess)
     return DP_ERR_HIP;

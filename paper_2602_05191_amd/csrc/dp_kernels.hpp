@@ -59,8 +59,13 @@ struct SelectOut {
 
 // start / stop (nullable): HIP events that receive the kernel's own begin and end timestamps
 // zero_words (nullable): n_zero int32 that the kernel clears (the step's pending counters)
+// summaries (nullable): float2 [heads, sub_stride]: per head and sub-tile of kSubTile consecutive clusters of its
+// segment, (max logit, sum over the sub-tile of exp(logit - that max)); entries beyond the segment's last
+// sub-tile are not written
+constexpr int kSubTile = 16;
 hipError_t launch_score(const CacheView &c, float *logits, hipStream_t s, hipEvent_t start = nullptr,
-                        hipEvent_t stop = nullptr, int32_t *zero_words = nullptr, int n_zero = 0);
+                        hipEvent_t stop = nullptr, int32_t *zero_words = nullptr, int n_zero = 0,
+                        float2 *summaries = nullptr, int sub_stride = 0);
 
 // How stage 2 cuts the order (logit descending, index ascending):
 //   by_count == 0: the two top-p thresholds p1, p2 (p2_absolute: p2 is a mass of the whole distribution)
@@ -73,9 +78,10 @@ struct SelectRule {
 
 // plan.ent_src == nullptr => no plan is written
 // With a plan and attn.out != nullptr, heads with few rows are attended inside the selection kernel.
+// summaries (nullable): what launch_score left for these logits; lets peaked heads skip reading their logits
 hipError_t launch_select(const CacheView &c, const float *logits, const SelectRule &rule, const SelectOut &out,
                          const Plan &plan, const AttnOut &attn, hipStream_t s, hipEvent_t start = nullptr,
-                         hipEvent_t stop = nullptr);
+                         hipEvent_t stop = nullptr, const float2 *summaries = nullptr, int sub_stride = 0);
 
 // builds the plan from caller-given sets
 hipError_t launch_plan(const CacheView &c, const int32_t *sel_ids, const int32_t *n_exact,

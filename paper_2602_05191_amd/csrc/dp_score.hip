@@ -49,7 +49,28 @@ struct ScoreArgs {
   float sm_scale;
   int32_t *zero_words;  // nullable: n_zero words cleared by the first workgroup (counters of the step's later kernels)
   int32_t n_zero;
+  // nullable: per head and sub-tile of kSubTile consecutive clusters, (max logit, sum of exp(logit - max)); row
+  // stride sub_stride.  Lets the selection find the top of the distribution without reading every logit.
+  float2 *summaries;
+  int32_t sub_stride;
 };
+
+// Both kernels leave the logits of one head's sub-tile (16 consecutive clusters) in the four lanes l, l ^ 16,
+// l ^ 32, l ^ 48 of a wave, four consecutive clusters each (-inf where there is no cluster).  Every lane of the
+// wave must call this; `writer` is true in the one lane per head that stores the result.
+__device__ __forceinline__ void publish_summary(const float (&v)[4], bool writer, float2 *dst) {
+  float m = fmaxf(fmaxf(v[0], v[1]), fmaxf(v[2], v[3]));
+  m = fmaxf(m, __shfl_xor(m, 16, 64));
+  m = fmaxf(m, __shfl_xor(m, 32, 64));
+  float s = 0.f;
+  if (m > -INFINITY) {
+#pragma unroll
+    for (int k = 0; k < 4; ++k) s += __builtin_amdgcn_exp2f((v[k] - m) * 1.4426950408889634f);  // exp2(-inf) = 0
+  }
+  s += __shfl_xor(s, 16, 64);  // fixed order: (row0 + row1) + (row2 + row3) in every lane
+  s += __shfl_xor(s, 32, 64);
+  if (writer) *dst = make_float2(m, s);
+}
 
 // The same scores on the vector ALU, for small groups: a 16-lane DPP row owns kValuRows consecutive centroid rows
 // (16 B per lane: every load instruction reads 4 whole rows), each lane's 8 products are accumulated by the packed
@@ -106,15 +127,21 @@ __global__ __launch_bounds__(kScoreThreads) void score_valu_kernel(ScoreArgs a, 
       if (lane16 == j) mine[k] = d;
     }
   }
+  float v[kValuRows];
+#pragma unroll
+  for (int k = 0; k < kValuRows; ++k) {
+    // ln s from the hardware log2 (1 ulp), exact for s = 1; a cluster beyond the segment was given size 0
+    v[k] = (size[k] > 0) ? fmaf(mine[k], a.sm_scale, __builtin_amdgcn_logf((float)size[k]) * 0.6931471805599453f)
+                         : -INFINITY;
+  }
+  if (a.summaries) {  // a wave's four rows are the 16 consecutive clusters tile0 + 16 w .. + 15
+    const int sub0 = tile0 + (threadIdx.x >> 6) * 16;
+    const int64_t head = (int64_t)b * a.n_q_heads + g * a.group + a.head0 + lane16;
+    publish_summary(v, lane16 < GH && (threadIdx.x & 63) < 16 && sub0 < kc,
+                    a.summaries + (lane16 < GH ? head : 0) * a.sub_stride + (sub0 >> 4));
+  }
   if (lane16 < GH && i0 < kc) {
     float *out = a.logits + (int64_t)a.group * c0 + (int64_t)(a.head0 + lane16) * kc + i0;
-    float v[kValuRows];
-#pragma unroll
-    for (int k = 0; k < kValuRows; ++k) {
-      // ln s from the hardware log2 (1 ulp), exact for s = 1
-      v[k] = (size[k] > 0) ? fmaf(mine[k], a.sm_scale, __builtin_amdgcn_logf((float)size[k]) * 0.6931471805599453f)
-                           : -INFINITY;
-    }
     if (kValuRows == 4 && i0 + 3 < kc && (reinterpret_cast<uintptr_t>(out) & 15) == 0) {
       *reinterpret_cast<float4 *>(out) = make_float4(v[0], v[1 % kValuRows], v[2 % kValuRows],
                                                      v[3 % kValuRows]);
@@ -188,16 +215,22 @@ __global__ __launch_bounds__(kScoreThreads) void score_kernel(ScoreArgs a, const
       acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, A[t][j]),
                                                     __builtin_bit_cast(bf16x8, Q[j]), acc, 0, 0, 0);
     const int i0 = base + t * kScoreTile + 4 * kq;
+    float v[4];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      // ln s from the hardware log2 (1 ulp), exact for s = 1; a cluster beyond the segment was given size 0
+      v[k] = (size[t][k] > 0)
+                 ? fmaf(acc[k], a.sm_scale, __builtin_amdgcn_logf((float)size[t][k]) * 0.6931471805599453f)
+                 : -INFINITY;
+    }
+    if (a.summaries) {  // the tile is the 16 consecutive clusters base + 64 t .. + 15
+      const int sub0 = base + t * kScoreTile;
+      const int64_t head = (int64_t)b * a.n_q_heads + g * a.group + a.head0 + r;
+      publish_summary(v, head_live && kq == 0 && sub0 < kc,
+                      a.summaries + (head_live ? head : 0) * a.sub_stride + (sub0 >> 4));
+    }
     if (head_live && i0 < kc) {
       float *out = a.logits + (int64_t)a.group * c0 + (int64_t)(a.head0 + r) * kc + i0;
-      float v[4];
-#pragma unroll
-      for (int k = 0; k < 4; ++k) {
-        // ln s from the hardware log2 (1 ulp), exact for s = 1
-        v[k] = (size[t][k] > 0)
-                   ? fmaf(acc[k], a.sm_scale, __builtin_amdgcn_logf((float)size[t][k]) * 0.6931471805599453f)
-                   : -INFINITY;
-      }
       if (i0 + 3 < kc && (reinterpret_cast<uintptr_t>(out) & 15) == 0) {
         *reinterpret_cast<float4 *>(out) = make_float4(v[0], v[1], v[2], v[3]);
       } else {
@@ -228,7 +261,7 @@ void launch_one(const ScoreArgs &a, dim3 grid, hipStream_t s, hipEvent_t start, 
 }
 
 hipError_t launch_score(const CacheView &c, float *logits, hipStream_t s, hipEvent_t start, hipEvent_t stop,
-                        int32_t *zero_words, int n_zero) {
+                        int32_t *zero_words, int n_zero, float2 *summaries, int sub_stride) {
   ScoreArgs a;
   a.q = c.q;
   a.k_centroids = c.k_centroids;
@@ -242,6 +275,8 @@ hipError_t launch_score(const CacheView &c, float *logits, hipStream_t s, hipEve
   a.uniform_kc = c.uniform_kc;
   a.zero_words = n_zero <= kScoreThreads ? zero_words : nullptr;
   a.n_zero = n_zero;
+  a.summaries = summaries;
+  a.sub_stride = sub_stride;
   if (c.max_clusters_per_seg == 0 || c.batch * c.n_kv_heads == 0) return hipSuccess;
   if (c.group <= kScoreValuMaxGroup) {
     // one pass: 4, 2 or 1 heads at a time

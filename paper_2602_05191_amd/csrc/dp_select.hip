@@ -48,6 +48,10 @@ constexpr int inline_rows_of(int T) { return T; }
 constexpr int kMaxCand = 512;            // largest bin population that is ranked pairwise
 constexpr float kTopCut = 6.0f;          // "top set": clusters whose logit is within this of the max
 constexpr int kTopMax = 64;              // largest top set handled by the one-wave fast path
+// Selection from the scoring kernel's sub-tile summaries (one-call path): one wave reads them, up to this many per
+// lane (8192 clusters), and the top set may spread over at most this many sub-tiles (one thread per cluster of those)
+constexpr int kLiteSubPerLane = 8;
+constexpr int kLiteMaxTopSub = 16;
 
 
 
@@ -57,6 +61,8 @@ struct SelectArgs {
   const uint8_t *cluster_flags;  // nullable; bit 0: pinned cluster (out of the distribution, always exact)
   int32_t n_kv_heads, n_q_heads, group, max_k;
   int32_t uniform_kc;  // > 0: every segment has exactly this many clusters (no CSR lookup needed)
+  const float2 *summaries;  // nullable: the scoring kernel's (max, sum exp) per head and sub-tile, row stride sub_stride
+  int32_t sub_stride;
   float p1, p2;
   uint32_t p2_absolute;
   int32_t k_retained, k_exact;  // fixed-budget rule (the kernel's kCount variant): counts instead of p1, p2
@@ -106,6 +112,10 @@ struct Shared {
   int top_idx[kTopMax], top_sz[kTopMax], top_off[kTopMax];
   u64 top_m[kTopMax];
   int ntop, f_nex, f_nap, f_ntok;
+  // selection from the sub-tile summaries
+  int lite_sub[kLiteMaxTopSub], lite_nsub;
+  float lite_mx;
+  u64 lite_W;
   // The refinement histogram of the (rare) crowded-bin search and the lists / merge buffers of the inline
   // attention never live at the same time: the lists are written once the search is over.
   union {
@@ -441,6 +451,151 @@ __device__ __forceinline__ int second_tau(const SelectArgs &a, u64 W, u64 m1, u6
   return top_p_second_tau(a.p2, a.p2_absolute != 0, W, m1, tau2);
 }
 
+// One wave ranks the top set gathered in sh.top_* (ntop <= kTopMax entries in any order: key, index, mass, size,
+// offset; an entry of mass 0 is a pinned cluster) pairwise on (key descending, index ascending) and, if the set
+// holds the first threshold's weight, emits both lists in ascending cluster index and leaves the three counts in
+// sh.f_*.  Otherwise sh.f_nex = -1 and nothing is emitted.  W: total weight of the head.  Call from every thread
+// of wave 0; the caller's barrier publishes the result.
+template <bool kCount, int T>
+__device__ __forceinline__ void rank_top_set(const SelectArgs &a, Shared<T> &sh, Emit &emit, int ntop, u64 W,
+                                             bool can_inline) {
+  const int i = lane_id();
+  const bool act = i < ntop;
+  const uint32_t key_i = act ? sh.top_key[i] : 0u;
+  const int idx_i = act ? sh.top_idx[i] : INT_MAX;
+  const u64 m_i = act ? sh.top_m[i] : 0;
+  const int sz_i = act ? sh.top_sz[i] : 0;
+  const bool pin_i = act && m_i == 0;  // a candidate of the top set has weight > 0, a pinned cluster 0
+  const u64 tau1 = first_tau<kCount>(a, W);
+  if (wave_sum(m_i) < tau1) {  // integer sums: exact.  The retained set is not inside the top set.
+    if (i == 0) sh.f_nex = -1;
+    return;
+  }
+  // lane j holds entry j: the loops below fetch it with readlane (j is uniform), not from LDS
+  const uint32_t mlo_i = (uint32_t)m_i, mhi_i = (uint32_t)(m_i >> 32);
+  u64 ahead = 0;  // mass of the clusters that precede cluster i in the order
+  for (int j = 0; j < ntop; ++j) {
+    const uint32_t kj = __builtin_amdgcn_readlane(key_i, j);
+    const int ij = __builtin_amdgcn_readlane(idx_i, j);
+    const u64 mj = ((u64)(uint32_t)__builtin_amdgcn_readlane(mhi_i, j) << 32) |
+                   (uint32_t)__builtin_amdgcn_readlane(mlo_i, j);
+    if (kj > key_i || (kj == key_i && ij < idx_i)) ahead += mj;
+  }
+  const bool ret = pin_i || (act && ahead < tau1);
+  u64 m1 = (ret && !pin_i) ? ahead + m_i : 0;  // mass of the retained prefix = the largest inclusive prefix
+  m1 = wave_max(m1);
+  u64 tau2 = 0;
+  const int kind = second_tau<kCount>(a, W, m1, tau2);
+  const bool exa = pin_i || (kind == 1 ? ret : (kind == 2 && act && ahead < tau2));
+  const bool apx = ret && !exa;
+  const u64 exa_mask = __ballot(exa), apx_mask = __ballot(apx);
+  const int n_ex = __popcll(exa_mask), n_ap = __popcll(apx_mask);
+  const int n_tok = wave_sum(exa ? sz_i : 0);
+  // position of cluster i in its list = selected clusters with a smaller index
+  int pe = 0, pa = 0, pt = 0;
+  for (int j = 0; j < ntop; ++j) {
+    const bool before = __builtin_amdgcn_readlane(idx_i, j) < idx_i;
+    if ((exa_mask >> j) & 1) {
+      pe += before;
+      pt += before ? __builtin_amdgcn_readlane(sz_i, j) : 0;
+    } else if ((apx_mask >> j) & 1) {
+      pa += before;
+    }
+  }
+  emit.to_lds = can_inline && n_tok + n_ap <= inline_rows_of(T);
+  emit.n_ex = n_ex;
+  emit.n_tok = n_tok;
+  if (exa) emit.exact(pe, pt, sz_i, sh.top_off[i], idx_i);
+  if (apx) emit.approx(pa, idx_i);
+  if (i == 0) {
+    sh.f_nex = n_ex;
+    sh.f_nap = n_ap;
+    sh.f_ntok = n_tok;
+  }
+}
+
+// Top-p selection of a peaked head from the scoring kernel's sub-tile summaries, without reading the head's
+// logits: one wave reads (max, sum exp) of every sub-tile, which gives the max logit exactly and the total mass
+// W (the sub-tile sums rescaled to the max, added up in fp64 and converted to the 2^-40 fixed point of the other
+// paths: W is within a few 1e-7 of the integer sum of the clusters' own masses, so a threshold p * W moves by that
+// much).  Only sub-tiles whose max lies within kTopCut of the head's max can hold a member of the top set; their
+// logits, sizes and offsets are read (one thread per cluster) and the top set is ranked as on the fast path.
+// Returns false (block-uniform) when the head is not peaked enough for that: then nothing has been emitted.
+template <int T>
+__device__ __forceinline__ bool lite_select(const SelectArgs &a, Shared<T> &sh, Emit &emit, int c0, int kc,
+                                            const float *lg, bool plan, bool can_inline, int &n_ex, int &n_ap,
+                                            int &n_tok) {
+  static_assert(T >= kLiteMaxTopSub * kSubTile, "one thread per cluster of the top sub-tiles");
+  const int tid = threadIdx.x;
+  if (tid < 64) {
+    const int n_sub = (kc + kSubTile - 1) / kSubTile;
+    const float2 *sp = a.summaries + (int64_t)blockIdx.x * a.sub_stride;
+    float2 sv[kLiteSubPerLane];
+#pragma unroll
+    for (int i = 0; i < kLiteSubPerLane; ++i) {
+      const int u = tid + 64 * i;
+      sv[i] = u < n_sub ? sp[u] : make_float2(-INFINITY, 0.f);
+    }
+    float m = -INFINITY;
+#pragma unroll
+    for (int i = 0; i < kLiteSubPerLane; ++i) m = fmaxf(m, sv[i].x);
+    const float M = wave_max(m);
+    double acc = 0.0;
+#pragma unroll
+    for (int i = 0; i < kLiteSubPerLane; ++i)
+      if (sv[i].x > -INFINITY) acc += (double)sv[i].y * (double)__builtin_amdgcn_exp2f((sv[i].x - M) * kLog2e);
+    const u64 W = wave_sum((u64)(acc * 1099511627776.0));  // per lane <= 128 * 2^40: integer sums from here on
+    int n_ts = 0;
+#pragma unroll
+    for (int i = 0; i < kLiteSubPerLane; ++i) {
+      const bool top = sv[i].x > -INFINITY && M - sv[i].x < kTopCut;
+      const u64 mask = __ballot(top);
+      const int pos = n_ts + __popcll(mask & ((1ull << tid) - 1));
+      if (top && pos < kLiteMaxTopSub) sh.lite_sub[pos] = tid + 64 * i;
+      n_ts += __popcll(mask);
+    }
+    if (tid == 0) {
+      sh.lite_nsub = M > -INFINITY ? n_ts : -1;  // no candidate at all: left to the general path
+      sh.lite_mx = M;
+      sh.lite_W = W;
+      sh.ntop = 0;
+    }
+  }
+  __syncthreads();
+  const int n_ts = sh.lite_nsub;
+  if (n_ts < 0 || n_ts > kLiteMaxTopSub) return false;
+  const float mx = sh.lite_mx;
+  if (tid < n_ts * kSubTile) {
+    const int i = sh.lite_sub[tid >> 4] * kSubTile + (tid & 15);
+    if (i < kc) {
+      const float l = lg[i] + 0.0f;  // -0 becomes +0
+      const int sz = a.cluster_sizes[c0 + i];
+      const int off = plan ? a.cluster_offsets[c0 + i] : 0;
+      const float d = mx - l;
+      if (d < kTopCut) {
+        const int s = atomicAdd(&sh.ntop, 1);
+        if (s < kTopMax) {
+          sh.top_key[s] = ordered_key(l);
+          sh.top_idx[s] = i;
+          sh.top_m[s] = fx_mass(d);
+          sh.top_sz[s] = sz;
+          sh.top_off[s] = off;
+        }
+      }
+    }
+  }
+  __syncthreads();
+  const int ntop = sh.ntop;
+  if (ntop > kTopMax) return false;
+  if (wave_id() == 0) rank_top_set<false, T>(a, sh, emit, ntop, sh.lite_W, can_inline);
+  __syncthreads();
+  if (sh.f_nex < 0) return false;
+  n_ex = sh.f_nex;
+  n_ap = sh.f_nap;
+  n_tok = sh.f_ntok;
+  return true;
+}
+
 __device__ __forceinline__ void put_counts(const SelectOut &o, int head, int n_exact, int n_retained, int n_tokens) {
   o.n_exact[head] = n_exact;
   o.n_retained[head] = n_retained;
@@ -450,38 +605,17 @@ __device__ __forceinline__ void put_counts(const SelectOut &o, int head, int n_e
   if (o.n_exact_tokens_copy) o.n_exact_tokens_copy[head] = n_tokens;
 }
 
+// The selection proper for one head (one workgroup): fast path for a peaked head, general threshold search
+// otherwise; emits the lists (and the plan) and returns the three counts.  Returns false when the head had no
+// candidate at all and has been finished here (counts, zero output).
 template <int E, bool kCount, int T>
-__global__ __launch_bounds__(T) void select_kernel(SelectArgs a) {
-  __shared__ Shared<T> sh;
+__device__ __forceinline__ bool full_select(const SelectArgs &a, Shared<T> &sh, Emit &emit, int head, int c0, int kc,
+                                            const float *lg, bool plan, bool can_inline, int &n_ex, int &n_ap,
+                                            int &n_tok) {
   constexpr int kBins = bins_of(T);
   constexpr int kInlineRows = inline_rows_of(T);
-  const int head = blockIdx.x;
-  const int b = head / a.n_q_heads, h = head % a.n_q_heads;
-  const int seg = b * a.n_kv_heads + h / a.group;
-  int c0, kc;
-  if (a.uniform_kc > 0) {
-    c0 = seg * a.uniform_kc;
-    kc = a.uniform_kc;
-  } else {
-    c0 = a.seg_cluster_ptr[seg];
-    kc = a.seg_cluster_ptr[seg + 1] - c0;
-  }
-  const float *lg = a.logits + (int64_t)a.group * c0 + (int64_t)(h % a.group) * kc;
   const int tid = threadIdx.x;
   const int base = tid * E;
-
-  const bool plan = a.plan.ent_src != nullptr;
-  const bool can_inline = plan && a.attn_out != nullptr;
-  Emit emit;
-  emit.sel = a.out.sel_ids + (int64_t)head * a.max_k;
-  emit.ent_src = plan ? a.plan.ent_src + (int64_t)head * a.max_k : nullptr;
-  emit.row_start = plan ? a.plan.row_start + (int64_t)head * (a.max_k + 1) : nullptr;
-  emit.chunk_entry = plan ? a.plan.chunk_entry + (int64_t)head * a.plan.chunk_stride : nullptr;
-  emit.l_start = sh.at.l_start;
-  emit.l_src = sh.at.l_src;
-  emit.plan = plan;
-
-  if (plan && tid == 0 && head % kMaxQueueHeads == 0) a.plan.queue_next[head / kMaxQueueHeads] = 0;
   // ---- load, max ---------------------------------------------------------
   float l[E];
   if (E >= 4 && (reinterpret_cast<uintptr_t>(lg) & 15) == 0 && base + E <= kc) {
@@ -498,7 +632,6 @@ __global__ __launch_bounds__(T) void select_kernel(SelectArgs a) {
 #pragma unroll
     for (int e = 0; e < E; ++e) l[e] = (base + e < kc) ? lg[base + e] : -INFINITY;
   }
-  const int64_t seg_row0 = can_inline ? a.seg_row_base[seg] : 0;  // needed last; its latency hides here
   // With few logits per thread, sizes and offsets are fetched up front next to the logits, so that no
   // dependent load sits between the selection and the first K/V row.
   constexpr bool kPre = E <= 8;
@@ -579,7 +712,7 @@ __global__ __launch_bounds__(T) void select_kernel(SelectArgs a) {
       if (can_inline && a.lse) a.lse[head] = -INFINITY;
     }
     if (can_inline && tid < kHeadDim) store_out(a.attn_out, a.out_is_bf16, head, tid, 0.f);
-    return;
+    return false;
   }
 
   // level-1 bins: top-p spreads them over the kCut below the max that carries mass; a fixed budget
@@ -626,7 +759,6 @@ __global__ __launch_bounds__(T) void select_kernel(SelectArgs a) {
     ntop = partials_sum<int, (T / 64)>(sh.scri);
   }
 
-  int n_ex, n_ap, n_tok;
   const bool all = !nothing && retain_all<kCount>(a, W);  // every non-empty candidate is retained
   // fast path: the top set is small and already holds the first threshold's weight (integer sums: exact), so
   // the retained set lies inside it (the usual case for a peaked head)
@@ -647,61 +779,7 @@ __global__ __launch_bounds__(T) void select_kernel(SelectArgs a) {
       }
     }
     __syncthreads();
-    if (wave_id() == 0) {
-      const int i = lane_id();
-      const bool act = i < ntop;
-      const uint32_t key_i = act ? sh.top_key[i] : 0u;
-      const int idx_i = act ? sh.top_idx[i] : INT_MAX;
-      const u64 m_i = act ? sh.top_m[i] : 0;
-      const int sz_i = act ? sh.top_sz[i] : 0;
-      const bool pin_i = act && m_i == 0;  // a candidate of the top set has weight > 0, a pinned cluster 0
-      // lane j holds entry j: the loops below fetch it with readlane (j is uniform), not from LDS
-      const uint32_t mlo_i = (uint32_t)m_i, mhi_i = (uint32_t)(m_i >> 32);
-      u64 ahead = 0;  // mass of the clusters that precede cluster i in the order
-      for (int j = 0; j < ntop; ++j) {
-        const uint32_t kj = __builtin_amdgcn_readlane(key_i, j);
-        const int ij = __builtin_amdgcn_readlane(idx_i, j);
-        const u64 mj = ((u64)(uint32_t)__builtin_amdgcn_readlane(mhi_i, j) << 32) |
-                       (uint32_t)__builtin_amdgcn_readlane(mlo_i, j);
-        if (kj > key_i || (kj == key_i && ij < idx_i)) ahead += mj;
-      }
-      const u64 tau1 = first_tau<kCount>(a, W);
-      {
-        const bool ret = pin_i || (act && ahead < tau1);
-        u64 m1 = (ret && !pin_i) ? ahead + m_i : 0;  // mass of the retained prefix = the largest inclusive prefix
-        m1 = wave_max(m1);
-        u64 tau2 = 0;
-        const int kind = second_tau<kCount>(a, W, m1, tau2);
-        const bool exa = pin_i || (kind == 1 ? ret : (kind == 2 && act && ahead < tau2));
-        const bool apx = ret && !exa;
-        const u64 exa_mask = __ballot(exa), apx_mask = __ballot(apx);
-        n_ex = __popcll(exa_mask);
-        n_ap = __popcll(apx_mask);
-        n_tok = wave_sum(exa ? sz_i : 0);
-        // position of cluster i in its list = selected clusters with a smaller index
-        int pe = 0, pa = 0, pt = 0;
-        for (int j = 0; j < ntop; ++j) {
-          const bool before = __builtin_amdgcn_readlane(idx_i, j) < idx_i;
-          if ((exa_mask >> j) & 1) {
-            pe += before;
-            pt += before ? __builtin_amdgcn_readlane(sz_i, j) : 0;
-          } else if ((apx_mask >> j) & 1) {
-            pa += before;
-          }
-        }
-        const int R = n_tok + n_ap;
-        emit.to_lds = can_inline && R <= kInlineRows;
-        emit.n_ex = n_ex;
-        emit.n_tok = n_tok;
-        if (exa) emit.exact(pe, pt, sz_i, sh.top_off[i], idx_i);
-        if (apx) emit.approx(pa, idx_i);
-        if (i == 0) {
-          sh.f_nex = n_ex;
-          sh.f_nap = n_ap;
-          sh.f_ntok = n_tok;
-        }
-      }
-    }
+    if (wave_id() == 0) rank_top_set<kCount, T>(a, sh, emit, ntop, W, can_inline);  // holds the weight: always emits
     __syncthreads();
     n_ex = sh.f_nex;
     n_ap = sh.f_nap;
@@ -816,6 +894,48 @@ __global__ __launch_bounds__(T) void select_kernel(SelectArgs a) {
       }
     }
   }
+
+  return true;
+}
+
+template <int E, bool kCount, int T>
+__global__ __launch_bounds__(T) void select_kernel(SelectArgs a) {
+  __shared__ Shared<T> sh;
+  constexpr int kInlineRows = inline_rows_of(T);
+  const int head = blockIdx.x;
+  const int b = head / a.n_q_heads, h = head % a.n_q_heads;
+  const int seg = b * a.n_kv_heads + h / a.group;
+  int c0, kc;
+  if (a.uniform_kc > 0) {
+    c0 = seg * a.uniform_kc;
+    kc = a.uniform_kc;
+  } else {
+    c0 = a.seg_cluster_ptr[seg];
+    kc = a.seg_cluster_ptr[seg + 1] - c0;
+  }
+  const float *lg = a.logits + (int64_t)a.group * c0 + (int64_t)(h % a.group) * kc;
+  const int tid = threadIdx.x;
+
+  const bool plan = a.plan.ent_src != nullptr;
+  const bool can_inline = plan && a.attn_out != nullptr;
+  Emit emit;
+  emit.sel = a.out.sel_ids + (int64_t)head * a.max_k;
+  emit.ent_src = plan ? a.plan.ent_src + (int64_t)head * a.max_k : nullptr;
+  emit.row_start = plan ? a.plan.row_start + (int64_t)head * (a.max_k + 1) : nullptr;
+  emit.chunk_entry = plan ? a.plan.chunk_entry + (int64_t)head * a.plan.chunk_stride : nullptr;
+  emit.l_start = sh.at.l_start;
+  emit.l_src = sh.at.l_src;
+  emit.plan = plan;
+
+  if (plan && tid == 0 && head % kMaxQueueHeads == 0) a.plan.queue_next[head / kMaxQueueHeads] = 0;
+  const int64_t seg_row0 = can_inline ? a.seg_row_base[seg] : 0;  // needed last; its latency hides behind the selection
+
+  int n_ex = 0, n_ap = 0, n_tok = 0;
+  // a peaked head is selected from the scoring kernel's summaries; any other head by the search over all its logits
+  bool chosen = false;
+  if (!kCount && a.summaries && !a.cluster_flags && a.p1 < 1.0f && kc > 0 && kc <= kLiteSubPerLane * 64 * kSubTile)
+    chosen = lite_select<T>(a, sh, emit, c0, kc, lg, plan, can_inline, n_ex, n_ap, n_tok);
+  if (!chosen && !full_select<E, kCount, T>(a, sh, emit, head, c0, kc, lg, plan, can_inline, n_ex, n_ap, n_tok)) return;
 
   const int R = n_tok + n_ap;
   const bool inline_attn = can_inline && R <= kInlineRows;
@@ -950,9 +1070,12 @@ void launch_select_e(const SelectArgs &a, bool by_count, dim3 grid, hipStream_t 
 
 
 hipError_t launch_select(const CacheView &c, const float *logits, const SelectRule &rule, const SelectOut &out,
-                         const Plan &plan, const AttnOut &attn, hipStream_t s, hipEvent_t start, hipEvent_t stop) {
+                         const Plan &plan, const AttnOut &attn, hipStream_t s, hipEvent_t start, hipEvent_t stop,
+                         const float2 *summaries, int sub_stride) {
   SelectArgs a;
   a.logits = logits;
+  a.summaries = summaries;
+  a.sub_stride = sub_stride;
   a.seg_cluster_ptr = c.seg_cluster_ptr;
   a.cluster_sizes = c.cluster_sizes;
   a.cluster_offsets = c.cluster_offsets;

@@ -50,10 +50,11 @@ def test_workspace_size_and_layout(lib):
     lay = _Layout()
     assert lib.dp_get_workspace_layout(C.byref(p), C.byref(lay)) == 0
     assert lay.total == total > 0
-    offs = [lay.logits, lay.sel_ids, lay.row_start, lay.chunk_entry, lay.counts, lay.partials, lay.total]
+    offs = [lay.logits, lay.sel_ids, lay.row_start, lay.chunk_entry, lay.counts, lay.partials, lay.summaries, lay.total]
     assert offs == sorted(offs) and all(o % 256 == 0 for o in offs)
     assert lay.sel_ids - lay.logits >= 4 * 4 * 65536                  # G * total_clusters floats
-    assert lay.total - lay.partials >= 4 * 32 * lay.splits * 130      # (m, l, acc[128]) per head and split
+    assert lay.summaries - lay.partials >= 4 * 32 * lay.splits * 130  # (m, l, acc[128]) per head and split
+    assert lay.total - lay.summaries >= 8 * 32 * (8192 // 16)         # (max, sum exp) per head and 16 clusters
     assert lib.dp_logits_count(C.byref(p)) == 4 * 65536
     # invalid shapes have no workspace
     assert lib.dp_workspace_bytes(C.byref(_problem(n_q_heads=30))) == 0

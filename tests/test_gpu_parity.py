@@ -241,6 +241,38 @@ def test_decode_attention_matches_oracle(case, pp):
     print(f"[{name} p=({p1},{p2})] sets exact on {nh - tolerated}/{nh} heads, out max-abs {worst:.2e} rel-L2 {rel:.2e}")
 
 
+def test_scoring_summaries_describe_the_logits(case):
+    """What the scoring stage leaves for the selection next to the logits: per head and run of 16 clusters the
+    largest logit (exactly) and the sum of exp(logit - that) (fp32 rounding of 16 terms)."""
+    import torch
+    import paper_2602_05191_amd as dp
+    name, cache, p1, p2, orc = case
+    if cache.cluster_flags is not None or cache.max_clusters_per_seg == 0:
+        pytest.skip("the summaries are written for the top-p rule on caches without cluster flags")
+    dc = dp.DeviceCache.from_host(cache)
+    pr = dp.Problem(dc)
+    nh, mk = cache.batch * cache.n_q_heads, cache.max_clusters_per_seg
+    ws = torch.zeros(dp.dp_workspace_bytes(pr), dtype=torch.uint8, device="cuda:0")
+    out = torch.empty((cache.batch, cache.n_q_heads, 128), dtype=torch.float32, device="cuda:0")
+    dp.dp_decode_attention(pr, 0.95, 0.9, out, None, ws)
+    torch.cuda.synchronize()
+    lay = dp.dp_workspace_layout(pr)
+    wsh = ws.cpu().numpy()
+    stride = (mk + 15) // 16
+    summ = wsh[lay["summaries"]: lay["summaries"] + 8 * nh * stride].view(np.float32).reshape(nh, stride, 2)
+    flat = wsh[lay["logits"]: lay["logits"] + 4 * cache.group * int(cache.seg_cluster_ptr[-1])].view(np.float32)
+    for i in range(nh):
+        s0, kc = H.head_logit_slice(cache, *divmod(i, cache.n_q_heads))
+        lg = np.full(((kc + 15) // 16) * 16, -np.inf, np.float32)
+        lg[:kc] = flat[s0:s0 + kc]
+        lg = lg.reshape(-1, 16)
+        mx = lg.max(axis=1)
+        assert np.array_equal(summ[i, : len(mx), 0], mx), (name, i)
+        with np.errstate(invalid="ignore"):
+            se = np.where(np.isfinite(mx), np.exp(lg.astype(np.float64) - mx[:, None].astype(np.float64)).sum(axis=1), 0.0)
+        np.testing.assert_allclose(summ[i, : len(mx), 1], se, rtol=2e-6, atol=0)
+
+
 def test_decode_attention_is_bitwise_reproducible(case):
     name, cache, p1, p2, orc = case
     a = H.gpu_decode_attention(cache, p1, p2)
