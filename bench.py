@@ -38,6 +38,8 @@ def parse():
     ap.add_argument("--warmup", type=int, default=360)
     ap.add_argument("--config", type=int, default=2, help="workload index 0..4 (default: 8B shape, 128k context)")
     ap.add_argument("--replicas", type=int, default=0, help="layer replicas to rotate over (0 = auto)")
+    ap.add_argument("--separate-decode-launch", action="store_true",
+                    help="A/B: keep the split decode a launch of its own (DP_FLAG_SEPARATE_DECODE_LAUNCH)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=10.0, help="CPU time budget of the oracle baseline")
     return ap.parse_args()
@@ -112,7 +114,8 @@ def main():
     mk = cache.max_clusters_per_seg
 
     base = dp.DeviceCache.from_host(cache, dev)
-    pr0 = dp.Problem(base)
+    pflags = dp.DP_FLAG_SEPARATE_DECODE_LAUNCH if args.separate_decode_launch else 0
+    pr0 = dp.Problem(base, flags=pflags)
     ws_bytes = dp.dp_workspace_bytes(pr0)
     ws = torch.zeros(ws_bytes, dtype=torch.uint8, device=dev)
     out = torch.empty((cache.batch, cache.n_q_heads, cache.head_dim), dtype=torch.float32, device=dev)
@@ -134,7 +137,7 @@ def main():
     per_replica = sum(t.numel() * t.element_size() for t in base.__dict__.values() if isinstance(t, torch.Tensor))
     L = int(max(1, min(L, (free * 0.8) // max(per_replica, 1))))
     reps = [base] + [base.clone() for _ in range(L - 1)]
-    probs = [dp.Problem(r) for r in reps]
+    probs = [dp.Problem(r, flags=pflags) for r in reps]
     torch.cuda.synchronize()
 
     def step(i):

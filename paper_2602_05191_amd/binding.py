@@ -17,6 +17,7 @@ import torch
 
 DP_BF16, DP_F32 = 0, 1
 DP_FLAG_P2_ABSOLUTE = 1
+DP_FLAG_SEPARATE_DECODE_LAUNCH = 2
 DP_CLUSTER_PINNED = 1
 
 _PKG = os.path.dirname(os.path.abspath(__file__))

@@ -90,8 +90,10 @@ void layout_of(const dp_problem *p, dp_workspace_layout *L) {
   off = align_up(off + sizeof(int32_t) * nh * (mk + 1), 256);
   L->chunk_entry = off;
   off = align_up(off + sizeof(int32_t) * nh * chunk_stride, 256);
-  L->counts = off;  // n_exact, n_retained, n_exact_tokens, head_rows, done : 5 x [nh], then the queue and pending counters
-  off = align_up(off + sizeof(int32_t) * (5 * nh + 2 * ((nh + dp::kMaxQueueHeads - 1) / dp::kMaxQueueHeads)), 256);
+  // n_exact, n_retained, n_exact_tokens, head_rows, done : 5 x [nh]; then per slab of heads the queue and the pending
+  // counter, then the count of heads whose selection is complete
+  L->counts = off;
+  off = align_up(off + sizeof(int32_t) * (5 * nh + 2 * ((nh + dp::kMaxQueueHeads - 1) / dp::kMaxQueueHeads) + 1), 256);
   L->partials = off;
   off = align_up(off + sizeof(float) * nh * (size_t)splits * (dp::kHeadDim + 2), 256);
   L->summaries = off;  // (max, sum exp) per head and sub-tile of kSubTile clusters
@@ -106,6 +108,7 @@ struct Workspace {
   float *logits;
   int32_t *sel_ids, *n_exact, *n_retained, *n_exact_tokens;
   dp::Plan plan;
+  int32_t *planned;
   float *partials;
   float2 *summaries;
   int sub_stride;
@@ -133,6 +136,7 @@ Workspace carve(const dp_problem *p, void *ws) {
   w.plan.done = counts + 4 * nh;
   w.plan.queue_next = counts + 5 * nh;
   w.plan.pending = nullptr;  // the one-call path turns it on (its scoring kernel clears the counters)
+  w.planned = w.plan.queue_next + 2 * ((nh + dp::kMaxQueueHeads - 1) / dp::kMaxQueueHeads);
   w.partials = reinterpret_cast<float *>(b + L.partials);
   w.summaries = reinterpret_cast<float2 *>(b + L.summaries);
   w.sub_stride = (int)((mk + dp::kSubTile - 1) / dp::kSubTile);
@@ -170,7 +174,9 @@ dp_status select_only(const dp_problem *problem, const float *logits, const dp::
              : DP_ERR_HIP;
 }
 
-// score -> select (+ attention of light heads) -> split decode, on one stream
+// score -> select (+ attention of light heads) -> split decode, on one stream.  A step that serves few heads runs
+// the split decode inside the selection launch (two launches); flags bit DP_FLAG_SEPARATE_DECODE_LAUNCH keeps the
+// three launches.
 dp_status whole_step(const dp_problem *problem, const dp::SelectRule &rule, void *out, dp_dtype out_dtype, float *lse,
                      int32_t *n_exact, int32_t *n_retained, int32_t *n_exact_tokens, void *workspace,
                      size_t workspace_bytes, void *stream, void *const *events = nullptr) {
@@ -185,14 +191,27 @@ dp_status whole_step(const dp_problem *problem, const dp::SelectRule &rule, void
   Workspace w = carve(problem, workspace);
   hipStream_t s = static_cast<hipStream_t>(stream);
   const int n_slabs = (int)(((size_t)problem->batch * problem->n_q_heads + dp::kMaxQueueHeads - 1) / dp::kMaxQueueHeads);
-  if (problem->max_clusters_per_seg > 0 && n_slabs <= 256) w.plan.pending = w.plan.queue_next + n_slabs;
+  if (problem->max_clusters_per_seg > 0 && n_slabs <= 64) w.plan.pending = w.plan.queue_next + n_slabs;
+  const bool same_launch = w.plan.pending && (int64_t)problem->batch * problem->n_q_heads <= dp::kSameLaunchMaxHeads &&
+                           !(problem->flags & DP_FLAG_SEPARATE_DECODE_LAUNCH);
   // the summaries serve the top-p rule on heads without cluster flags
   float2 *summ = (!rule.by_count && !problem->cluster_flags && rule.p1 < 1.0f) ? w.summaries : nullptr;
-  if (dp::launch_score(c, w.logits, s, ev[0], ev[1], w.plan.pending, n_slabs, summ, w.sub_stride) != hipSuccess)
+  // the scoring kernel clears the step's counters: item counters, pending counters, planned (contiguous)
+  if (dp::launch_score(c, w.logits, s, ev[0], ev[1], w.plan.pending ? w.plan.queue_next : nullptr, 2 * n_slabs + 1, summ,
+                       w.sub_stride) != hipSuccess)
     return DP_ERR_HIP;
   // the optional count outputs are written by the selection kernel next to the workspace's own
   dp::SelectOut so{w.sel_ids, w.n_exact, w.n_retained, w.n_exact_tokens, n_exact, n_retained, n_exact_tokens};
   const dp::AttnOut attn{out, lse, out_dtype == DP_BF16};
+  if (same_launch) {
+    const dp::SameLaunchQueue q{w.partials, w.splits, w.planned};
+    if (dp::launch_select(c, w.logits, rule, so, w.plan, attn, s, ev[2], ev[3], summ, w.sub_stride, &q) != hipSuccess)
+      return DP_ERR_HIP;
+    // measurement: there is no decode launch; its two events mark the end of the step
+    if (ev[4] && hipEventRecord(ev[4], s) != hipSuccess) return DP_ERR_HIP;
+    if (ev[5] && hipEventRecord(ev[5], s) != hipSuccess) return DP_ERR_HIP;
+    return DP_OK;
+  }
   if (dp::launch_select(c, w.logits, rule, so, w.plan, attn, s, ev[2], ev[3], summ, w.sub_stride) != hipSuccess)
     return DP_ERR_HIP;
   if (dp::launch_decode(c, w.n_exact, w.n_retained, w.plan, w.partials, w.splits, attn, s, ev[4], ev[5]) !=

@@ -78,10 +78,21 @@ struct SelectRule {
 
 // plan.ent_src == nullptr => no plan is written
 // With a plan and attn.out != nullptr, heads with few rows are attended inside the selection kernel.
+// The stage-3 queue inside the selection launch (for launches that serve at most kSameLaunchMaxHeads heads):
+// the heads that the selection does not attend itself are split over the same launch's workgroups, so no decode
+// launch follows.  planned: one counter; it, plan.pending[0] and plan.queue_next[0] must be zero when the launch
+// starts (launch_score's zero_words).
+constexpr int kSameLaunchMaxHeads = 128;
+struct SameLaunchQueue {
+  float *partials;
+  int splits;
+  int32_t *planned;
+};
 // summaries (nullable): what launch_score left for these logits; lets peaked heads skip reading their logits
 hipError_t launch_select(const CacheView &c, const float *logits, const SelectRule &rule, const SelectOut &out,
                          const Plan &plan, const AttnOut &attn, hipStream_t s, hipEvent_t start = nullptr,
-                         hipEvent_t stop = nullptr, const float2 *summaries = nullptr, int sub_stride = 0);
+                         hipEvent_t stop = nullptr, const float2 *summaries = nullptr, int sub_stride = 0,
+                         const SameLaunchQueue *queue = nullptr);
 
 // builds the plan from caller-given sets
 hipError_t launch_plan(const CacheView &c, const int32_t *sel_ids, const int32_t *n_exact,

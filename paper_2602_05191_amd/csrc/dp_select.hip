@@ -30,9 +30,7 @@
 #include <hip/hip_ext.h>
 #include <limits.h>
 
-#include "dp_attend.hpp"
-#include "dp_device.hpp"
-#include "dp_kernels.hpp"
+#include "dp_decode_body.hpp"
 #include "dp_mass.hpp"
 
 namespace dp {
@@ -395,10 +393,20 @@ __device__ __forceinline__ void find_prefix(const float (&l)[E], const float *lg
 
 // Where the selected ids and the stage-3 plan of one head go: the caller-visible id list,
 // and either the LDS lists of the inline attention or the global plan arrays.
+// A store that workgroups of the SAME launch will read (coherent: it is performed at the memory side, not left in
+// this compute die's L2), or a plain one for a later launch.
+__device__ __forceinline__ void st_i32(int32_t *p, int32_t v, bool coherent) {
+  if (coherent)
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  else
+    *p = v;
+}
+
 struct Emit {
   int32_t *sel, *ent_src, *row_start, *chunk_entry;
   int *l_start, *l_src;
   bool plan, to_lds;
+  bool coherent;  // the global plan is read by the stage-3 queue of this same launch
   int n_ex, n_tok;
   __device__ __forceinline__ void exact(int pe, int pt, int sz, int off, int id) const {
     sel[pe] = id;
@@ -407,9 +415,9 @@ struct Emit {
       l_start[pe] = pt;
       l_src[pe] = off;
     } else {
-      ent_src[pe] = off;
-      row_start[pe] = pt;
-      for (int q = (pt + kChunkRows - 1) / kChunkRows; q * kChunkRows < pt + sz; ++q) chunk_entry[q] = pe;
+      st_i32(ent_src + pe, off, coherent);
+      st_i32(row_start + pe, pt, coherent);
+      for (int q = (pt + kChunkRows - 1) / kChunkRows; q * kChunkRows < pt + sz; ++q) st_i32(chunk_entry + q, pe, coherent);
     }
   }
   __device__ __forceinline__ void approx(int pa, int id) const {
@@ -420,9 +428,9 @@ struct Emit {
       l_start[j] = row;
       l_src[j] = id;
     } else {
-      ent_src[j] = id;
-      row_start[j] = row;
-      if (row % kChunkRows == 0) chunk_entry[row / kChunkRows] = j;
+      st_i32(ent_src + j, id, coherent);
+      st_i32(row_start + j, row, coherent);
+      if (row % kChunkRows == 0) st_i32(chunk_entry + row / kChunkRows, j, coherent);
     }
   }
 };
@@ -596,9 +604,10 @@ __device__ __forceinline__ bool lite_select(const SelectArgs &a, Shared<T> &sh, 
   return true;
 }
 
-__device__ __forceinline__ void put_counts(const SelectOut &o, int head, int n_exact, int n_retained, int n_tokens) {
-  o.n_exact[head] = n_exact;
-  o.n_retained[head] = n_retained;
+__device__ __forceinline__ void put_counts(const SelectOut &o, int head, int n_exact, int n_retained, int n_tokens,
+                                           bool coherent) {
+  st_i32(o.n_exact + head, n_exact, coherent);
+  st_i32(o.n_retained + head, n_retained, coherent);
   o.n_exact_tokens[head] = n_tokens;
   if (o.n_exact_copy) o.n_exact_copy[head] = n_exact;
   if (o.n_retained_copy) o.n_retained_copy[head] = n_retained;
@@ -703,11 +712,11 @@ __device__ __forceinline__ bool full_select(const SelectArgs &a, Shared<T> &sh, 
   const float mx = mx_raw == -INFINITY ? 0.f : mx_raw;
   if (nothing && !has_flags) {  // and nothing can be pinned: zero output
     if (tid == 0) {
-      put_counts(a.out, head, 0, 0, 0);
+      put_counts(a.out, head, 0, 0, 0, emit.coherent);
       if (plan) {
-        emit.row_start[0] = 0;
-        a.plan.head_rows[head] = 0;
-        a.plan.done[head] = 0;
+        st_i32(emit.row_start, 0, emit.coherent);
+        st_i32(a.plan.head_rows + head, 0, emit.coherent);
+        st_i32(a.plan.done + head, 0, emit.coherent);
       }
       if (can_inline && a.lse) a.lse[head] = -INFINITY;
     }
@@ -898,9 +907,23 @@ __device__ __forceinline__ bool full_select(const SelectArgs &a, Shared<T> &sh, 
   return true;
 }
 
-template <int E, bool kCount, int T>
-__global__ __launch_bounds__(T) void select_kernel(SelectArgs a) {
-  __shared__ Shared<T> sh;
+// Arrival of a head at the launch's `planned` counter (kGate): everything the stage-3 queue of this launch reads
+// of the head has been stored coherently and has completed (the caller sees to that) before the counter moves;
+// a head that needs the queue is counted in `pending` first.  Returns the arrival number.
+__device__ __forceinline__ int head_planned(int32_t *planned, int32_t *pending, bool needs_queue) {
+  if (needs_queue) {
+    __hip_atomic_fetch_add(pending, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __builtin_amdgcn_s_waitcnt(0);  // performed before the arrival below can be seen
+  }
+  return __hip_atomic_fetch_add(planned, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// Stage 2 for one head by one workgroup, and stage 3 too when the head has few rows.  kGate: the stage-3 queue for
+// the heavier heads runs inside this same launch (select_decode_kernel): the plan, the counts and head_rows are then
+// stored coherently, and the head reports to `planned` once they have completed; thread 0 gets the arrival number
+// (-1 otherwise).
+template <int E, bool kCount, int T, bool kGate>
+__device__ __forceinline__ int select_head(const SelectArgs &a, Shared<T> &sh, int32_t *planned) {
   constexpr int kInlineRows = inline_rows_of(T);
   const int head = blockIdx.x;
   const int b = head / a.n_q_heads, h = head % a.n_q_heads;
@@ -915,6 +938,7 @@ __global__ __launch_bounds__(T) void select_kernel(SelectArgs a) {
   }
   const float *lg = a.logits + (int64_t)a.group * c0 + (int64_t)(h % a.group) * kc;
   const int tid = threadIdx.x;
+  int arrival = -1;
 
   const bool plan = a.plan.ent_src != nullptr;
   const bool can_inline = plan && a.attn_out != nullptr;
@@ -926,8 +950,11 @@ __global__ __launch_bounds__(T) void select_kernel(SelectArgs a) {
   emit.l_start = sh.at.l_start;
   emit.l_src = sh.at.l_src;
   emit.plan = plan;
+  emit.coherent = kGate;
 
-  if (plan && tid == 0 && head % kMaxQueueHeads == 0) a.plan.queue_next[head / kMaxQueueHeads] = 0;
+  // the item counter of the head's slab: cleared here for a decode launch that follows; with the queue in this
+  // same launch the scoring kernel has cleared it (a plain store here could be written back over claims)
+  if (!kGate && plan && tid == 0 && head % kMaxQueueHeads == 0) a.plan.queue_next[head / kMaxQueueHeads] = 0;
   const int64_t seg_row0 = can_inline ? a.seg_row_base[seg] : 0;  // needed last; its latency hides behind the selection
 
   int n_ex = 0, n_ap = 0, n_tok = 0;
@@ -935,29 +962,47 @@ __global__ __launch_bounds__(T) void select_kernel(SelectArgs a) {
   bool chosen = false;
   if (!kCount && a.summaries && !a.cluster_flags && a.p1 < 1.0f && kc > 0 && kc <= kLiteSubPerLane * 64 * kSubTile)
     chosen = lite_select<T>(a, sh, emit, c0, kc, lg, plan, can_inline, n_ex, n_ap, n_tok);
-  if (!chosen && !full_select<E, kCount, T>(a, sh, emit, head, c0, kc, lg, plan, can_inline, n_ex, n_ap, n_tok)) return;
+  if (!chosen && !full_select<E, kCount, T>(a, sh, emit, head, c0, kc, lg, plan, can_inline, n_ex, n_ap, n_tok)) {
+    // no candidate: finished inside (zero output, zero counts)
+    if (kGate && tid == 0) {
+      __builtin_amdgcn_s_waitcnt(0);
+      arrival = head_planned(planned, a.plan.pending, false);
+    }
+    return arrival;
+  }
 
   const int R = n_tok + n_ap;
   const bool inline_attn = can_inline && R <= kInlineRows;
   if (tid == 0) {
-    put_counts(a.out, head, n_ex, n_ex + n_ap, n_tok);
+    put_counts(a.out, head, n_ex, n_ex + n_ap, n_tok, kGate);
     if (plan) {
       if (inline_attn) {
         sh.at.l_start[n_ex + n_ap] = R;
-        a.plan.head_rows[head] = -1;  // attended here: nothing left for the decode kernel
+        st_i32(a.plan.head_rows + head, -1, kGate);  // attended here: nothing left for the stage-3 queue
       } else {
-        emit.row_start[n_ex + n_ap] = R;
-        a.plan.head_rows[head] = R;
-        if (a.plan.pending && R > 0) atomicAdd(&a.plan.pending[head / kMaxQueueHeads], 1);
+        st_i32(emit.row_start + n_ex + n_ap, R, kGate);
+        st_i32(a.plan.head_rows + head, R, kGate);
+        if (!kGate && a.plan.pending && R > 0) atomicAdd(&a.plan.pending[head / kMaxQueueHeads], 1);
       }
-      a.plan.done[head] = 0;
+      st_i32(a.plan.done + head, 0, kGate);
     }
   }
-  if (!inline_attn) return;
+  if (!inline_attn) {
+    if (kGate) {  // the plan was written by every thread: all of it has completed before the head reports
+      __builtin_amdgcn_s_waitcnt(0);
+      __syncthreads();
+      if (tid == 0) arrival = head_planned(planned, a.plan.pending, R > 0);
+    }
+    return arrival;
+  }
   if (R == 0) {  // nothing to attend to: zero output
     if (tid < kHeadDim) store_out(a.attn_out, a.out_is_bf16, head, tid, 0.f);
     if (tid == 0 && a.lse) a.lse[head] = -INFINITY;
-    return;
+    if (kGate && tid == 0) {
+      __builtin_amdgcn_s_waitcnt(0);
+      arrival = head_planned(planned, a.plan.pending, false);
+    }
+    return arrival;
   }
 
   // ---- inline attention for a head with few rows ---------------------------
@@ -979,6 +1024,11 @@ __global__ __launch_bounds__(T) void select_kernel(SelectArgs a) {
     const int per = kAttendBatch * ((R + kGroups * kAttendBatch - 1) / (kGroups * kAttendBatch));
     const int ra = grp * per, rb = min(R, ra + per);
     attend_rows(st, qv, a.scale_log2, src, sh.at.l_start, sh.at.l_src, n_ex + n_ap, 0, n_ex, ra, rb, kAttendBatch, lane16);
+    if (kGate && tid == 0) {
+      // the head's few coherent stores went out before the K / V loads that have just come back: this wait is short
+      __builtin_amdgcn_s_waitcnt(0);
+      arrival = head_planned(planned, a.plan.pending, false);
+    }
     float M, L, o;
     const int groups_used = (R + per - 1) / per;
     block_merge<(T / 64)>(st, sh.at.m_m, sh.at.m_l, sh.at.m_acc, (groups_used + 3) / 4, M, L, o);
@@ -987,6 +1037,44 @@ __global__ __launch_bounds__(T) void select_kernel(SelectArgs a) {
       if (a.lse && tid == 0) a.lse[head] = (M + log2f(L)) * kLn2;
     }
   }
+  return arrival;
+}
+
+template <int E, bool kCount, int T>
+__global__ __launch_bounds__(T) void select_kernel(SelectArgs a) {
+  __shared__ Shared<T> sh;
+  select_head<E, kCount, T, false>(a, sh, nullptr);
+}
+
+// Stage 2 and stage 3 in one launch, for launches that serve few heads (a separate decode launch that finds nothing
+// to do would cost as much as the selection itself).  Workgroup b < n_heads selects head b (and attends it if it has
+// few rows); every workgroup, the ones beyond n_heads included, then serves the stage-3 queue of the heads that
+// were left over.  The queue may only start when every head has reported to `planned`.  Nobody waits without
+// bound: a workgroup polls the counter for a limited time and leaves if the count is not reached; the workgroup
+// whose own arrival completes the count never polls and serves the queue until it is empty, so all items are
+// attended whoever else has left.  The scoring kernel of the step clears planned, pending and the item counter.
+constexpr int kGatePolls = 4000;  // about a microsecond each
+template <int E, bool kCount, int T>
+__global__ __launch_bounds__(T) void select_decode_kernel(SelectArgs a, DecodeArgs d, int32_t *planned, int n_heads) {
+  __shared__ Shared<T> sh;
+  __shared__ DecodeShared<T> dsh;
+  __shared__ int s_go;
+  int arrival = -1;
+  if ((int)blockIdx.x < n_heads) arrival = select_head<E, kCount, T, true>(a, sh, planned);
+  if (threadIdx.x == 0) {
+    int go = arrival == n_heads - 1;
+#pragma unroll 1
+    for (int it = 0; !go && it < kGatePolls; ++it) {
+      go = __hip_atomic_load(planned, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) >= n_heads;
+      if (!go) __builtin_amdgcn_s_sleep(32);
+    }
+    // every arrival was preceded by the head's count in pending: the value is final now
+    if (go) go = __hip_atomic_load(d.pending, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) > 0;
+    s_go = go;
+  }
+  __syncthreads();
+  if (!s_go) return;
+  decode_queue<T, false, true>(d, dsh);
 }
 
 // ---- plan from caller-given sets (staged API) -----------------------------
@@ -1052,9 +1140,25 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(PlanArgs a) {
   if (R == 0 && a.attn_out && tid < kHeadDim) store_out(a.attn_out, a.out_is_bf16, head, tid, 0.f);
 }
 
+// with a queue: grid = the heads, or as many workgroups as the chip holds at once if that is more
 template <int E, int T>
-void launch_select_e(const SelectArgs &a, bool by_count, dim3 grid, hipStream_t s, hipEvent_t start, hipEvent_t stop) {
-  if (start || stop) {  // measurement: the runtime stamps the kernel's own begin and end
+void launch_select_e(const SelectArgs &a, bool by_count, dim3 grid, hipStream_t s, hipEvent_t start, hipEvent_t stop,
+                     const DecodeArgs *queue, int32_t *planned) {
+  if (queue) {
+    const int n_heads = (int)grid.x;
+    const unsigned resident = 256u * (1024 / T);  // 256 CUs, 1024 threads of this kernel each
+    const dim3 g(grid.x > resident ? grid.x : resident);
+    if (start || stop) {
+      if (by_count)
+        hipExtLaunchKernelGGL((select_decode_kernel<E, true, T>), g, dim3(T), 0, s, start, stop, 0, a, *queue, planned, n_heads);
+      else
+        hipExtLaunchKernelGGL((select_decode_kernel<E, false, T>), g, dim3(T), 0, s, start, stop, 0, a, *queue, planned, n_heads);
+    } else if (by_count) {
+      hipLaunchKernelGGL((select_decode_kernel<E, true, T>), g, dim3(T), 0, s, a, *queue, planned, n_heads);
+    } else {
+      hipLaunchKernelGGL((select_decode_kernel<E, false, T>), g, dim3(T), 0, s, a, *queue, planned, n_heads);
+    }
+  } else if (start || stop) {  // measurement: the runtime stamps the kernel's own begin and end
     if (by_count)
       hipExtLaunchKernelGGL((select_kernel<E, true, T>), grid, dim3(T), 0, s, start, stop, 0, a);
     else
@@ -1071,7 +1175,7 @@ void launch_select_e(const SelectArgs &a, bool by_count, dim3 grid, hipStream_t 
 
 hipError_t launch_select(const CacheView &c, const float *logits, const SelectRule &rule, const SelectOut &out,
                          const Plan &plan, const AttnOut &attn, hipStream_t s, hipEvent_t start, hipEvent_t stop,
-                         const float2 *summaries, int sub_stride) {
+                         const float2 *summaries, int sub_stride, const SameLaunchQueue *queue) {
   SelectArgs a;
   a.logits = logits;
   a.summaries = summaries;
@@ -1106,6 +1210,19 @@ hipError_t launch_select(const CacheView &c, const float *logits, const SelectRu
   const dim3 grid(c.batch * c.n_q_heads);
   if (grid.x == 0) return hipSuccess;
   const int k = c.max_clusters_per_seg;
+  DecodeArgs dq;
+  const DecodeArgs *q = nullptr;
+  int32_t *planned = nullptr;
+  if (queue) {
+    if (grid.x > (unsigned)kSameLaunchMaxHeads || !plan.ent_src || !plan.pending || !attn.out) return hipErrorInvalidValue;
+    dq = decode_args_of(c, out.n_exact, out.n_retained, plan, queue->partials, queue->splits, attn);
+    dq.head0 = 0;
+    dq.n_heads = (int)grid.x;
+    dq.queue_next = plan.queue_next;
+    dq.pending = plan.pending;
+    q = &dq;
+    planned = queue->planned;
+  }
   // Workgroup size.  The kernel is bound by instruction issue on its one CU (every phase runs once per wave), so a
   // head gets the fewest threads that still leave it at most 8 logits per thread: 512 threads up to 4096 clusters
   // per segment (32 heads x 2048 clusters: 7.7 us instead of 8.6 us for peaked heads, 13.6 us instead of 22.4 us for
@@ -1114,17 +1231,17 @@ hipError_t launch_select(const CacheView &c, const float *logits, const SelectRu
   // of running in rounds.
   constexpr int kHalf = kSelThreads / 2, kQuarter = kSelThreads / 4;
   if (grid.x > 512 && k <= 8 * kQuarter) {
-    if (k <= 2 * kQuarter) launch_select_e<2, kQuarter>(a, bc, grid, s, start, stop);
-    else if (k <= 4 * kQuarter) launch_select_e<4, kQuarter>(a, bc, grid, s, start, stop);
-    else launch_select_e<8, kQuarter>(a, bc, grid, s, start, stop);
+    if (k <= 2 * kQuarter) launch_select_e<2, kQuarter>(a, bc, grid, s, start, stop, q, planned);
+    else if (k <= 4 * kQuarter) launch_select_e<4, kQuarter>(a, bc, grid, s, start, stop, q, planned);
+    else launch_select_e<8, kQuarter>(a, bc, grid, s, start, stop, q, planned);
   } else if (k <= 8 * kHalf) {
-    if (k <= 2 * kHalf) launch_select_e<2, kHalf>(a, bc, grid, s, start, stop);
-    else if (k <= 4 * kHalf) launch_select_e<4, kHalf>(a, bc, grid, s, start, stop);
-    else launch_select_e<8, kHalf>(a, bc, grid, s, start, stop);
-  } else if (k <= 8 * kSelThreads) launch_select_e<8, kSelThreads>(a, bc, grid, s, start, stop);
-  else if (k <= 16 * kSelThreads) launch_select_e<16, kSelThreads>(a, bc, grid, s, start, stop);
-  else if (k <= 32 * kSelThreads) launch_select_e<32, kSelThreads>(a, bc, grid, s, start, stop);
-  else if (k <= 64 * kSelThreads) launch_select_e<64, kSelThreads>(a, bc, grid, s, start, stop);
+    if (k <= 2 * kHalf) launch_select_e<2, kHalf>(a, bc, grid, s, start, stop, q, planned);
+    else if (k <= 4 * kHalf) launch_select_e<4, kHalf>(a, bc, grid, s, start, stop, q, planned);
+    else launch_select_e<8, kHalf>(a, bc, grid, s, start, stop, q, planned);
+  } else if (k <= 8 * kSelThreads) launch_select_e<8, kSelThreads>(a, bc, grid, s, start, stop, q, planned);
+  else if (k <= 16 * kSelThreads) launch_select_e<16, kSelThreads>(a, bc, grid, s, start, stop, q, planned);
+  else if (k <= 32 * kSelThreads) launch_select_e<32, kSelThreads>(a, bc, grid, s, start, stop, q, planned);
+  else if (k <= 64 * kSelThreads) launch_select_e<64, kSelThreads>(a, bc, grid, s, start, stop, q, planned);
   else return hipErrorInvalidValue;
   return hipGetLastError();
 }

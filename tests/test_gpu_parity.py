@@ -273,6 +273,24 @@ def test_scoring_summaries_describe_the_logits(case):
         np.testing.assert_allclose(summ[i, : len(mx), 1], se, rtol=2e-6, atol=0)
 
 
+def test_split_decode_inside_the_selection_launch_and_as_a_launch_of_its_own(case):
+    """A step that serves at most 128 heads runs the split decode inside the selection launch; the flag
+    DP_FLAG_SEPARATE_DECODE_LAUNCH keeps the three launches.  Same sets; outputs equal up to the different
+    split of a head's rows into partial results."""
+    import paper_2602_05191_amd as dp
+    name, cache, p1, p2, orc = case
+    for q1, q2 in ((p1, p2), (1.0, 1.0)):
+        a = H.gpu_decode_attention(cache, q1, q2)
+        b = H.gpu_decode_attention(cache, q1, q2, flags=dp.DP_FLAG_SEPARATE_DECODE_LAUNCH)
+        for x, y in zip(a.exact + a.approx, b.exact + b.approx):
+            assert np.array_equal(x, y)
+        assert np.array_equal(a.n_exact_tokens, b.n_exact_tokens)
+        assert np.abs(a.out - b.out).max() <= 2e-5, (name, q1, q2)
+        fin = np.isfinite(a.lse)
+        assert np.array_equal(fin, np.isfinite(b.lse)) and np.abs(a.lse[fin] - b.lse[fin]).max(initial=0.0) <= 1e-4
+        H.check_outputs(cache, orc, b, tight=2e-4)
+
+
 def test_decode_attention_is_bitwise_reproducible(case):
     name, cache, p1, p2, orc = case
     a = H.gpu_decode_attention(cache, p1, p2)
