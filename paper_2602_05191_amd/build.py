@@ -15,7 +15,9 @@ SOURCES = ["dp_api.hip", "dp_score.hip", "dp_select.hip", "dp_decode.hip", "dp_d
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 # packed-fp32 instructions are switched off for every device function
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
-         "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wno-unused-command-line-argument"]
+         "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wno-unused-command-line-argument",
+         # leading scalar kernel parameters arrive in registers at wave launch (no argument load in front of the work)
+         "-mllvm", "-amdgpu-kernarg-preload-count=16"]
 NOISE = "is not a recognized feature for this target"
 
 

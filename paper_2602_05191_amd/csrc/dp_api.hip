@@ -90,8 +90,9 @@ void layout_of(const dp_problem *p, dp_workspace_layout *L) {
   off = align_up(off + sizeof(int32_t) * nh * (mk + 1), 256);
   L->chunk_entry = off;
   off = align_up(off + sizeof(int32_t) * nh * chunk_stride, 256);
-  // n_exact, n_retained, n_exact_tokens, head_rows, done : 5 x [nh]; then per slab of heads the queue and the pending
-  // counter, then the count of heads whose selection is complete
+  // n_exact, n_retained, n_exact_tokens, done, head_rows : 5 x [nh]; then per slab of heads the queue and the pending
+  // counter, then the count of heads whose selection is complete (head_rows .. that count: one run of words, so the
+  // scoring kernel can clear them together)
   L->counts = off;
   off = align_up(off + sizeof(int32_t) * (5 * nh + 2 * ((nh + dp::kMaxQueueHeads - 1) / dp::kMaxQueueHeads) + 1), 256);
   L->partials = off;
@@ -132,8 +133,8 @@ Workspace carve(const dp_problem *p, void *ws) {
   w.n_exact = counts;
   w.n_retained = counts + nh;
   w.n_exact_tokens = counts + 2 * nh;
-  w.plan.head_rows = counts + 3 * nh;
-  w.plan.done = counts + 4 * nh;
+  w.plan.done = counts + 3 * nh;
+  w.plan.head_rows = counts + 4 * nh;
   w.plan.queue_next = counts + 5 * nh;
   w.plan.pending = nullptr;  // the one-call path turns it on (its scoring kernel clears the counters)
   w.planned = w.plan.queue_next + 2 * ((nh + dp::kMaxQueueHeads - 1) / dp::kMaxQueueHeads);
@@ -192,14 +193,24 @@ dp_status whole_step(const dp_problem *problem, const dp::SelectRule &rule, void
   hipStream_t s = static_cast<hipStream_t>(stream);
   const int n_slabs = (int)(((size_t)problem->batch * problem->n_q_heads + dp::kMaxQueueHeads - 1) / dp::kMaxQueueHeads);
   if (problem->max_clusters_per_seg > 0 && n_slabs <= 64) w.plan.pending = w.plan.queue_next + n_slabs;
+  // Where the shared launch pays (measured, 32 heads): it saves the decode launch of a step whose heads are all
+  // peaked (8192 clusters per KV head: 17.6 instead of 18.5 us; 256 clusters: 11 instead of 15 us), and its queue is
+  // served by the selection kernel's large workgroups, which is as fast as the decode kernel's many small ones
+  // when the heads that need it are long (8192 clusters, flat heads: 111 against 115 us) but slower when they are
+  // many and of middling length (2048 clusters, flat heads: 56 against 44 us; a fixed budget on every head: 64
+  // against 53 us).  Hence: top-p rule only, and not for segments of 513 to 4096 clusters.
+  const int mk = problem->max_clusters_per_seg;
   const bool same_launch = w.plan.pending && (int64_t)problem->batch * problem->n_q_heads <= dp::kSameLaunchMaxHeads &&
+                           !rule.by_count && (mk <= 512 || mk > 4096) &&
                            !(problem->flags & DP_FLAG_SEPARATE_DECODE_LAUNCH);
   // the summaries serve the top-p rule on heads without cluster flags
   float2 *summ = (!rule.by_count && !problem->cluster_flags && rule.p1 < 1.0f) ? w.summaries : nullptr;
-  // the scoring kernel clears the step's counters: item counters, pending counters, planned (contiguous)
-  if (dp::launch_score(c, w.logits, s, ev[0], ev[1], w.plan.pending ? w.plan.queue_next : nullptr, 2 * n_slabs + 1, summ,
-                       w.sub_stride) != hipSuccess)
-    return DP_ERR_HIP;
+  // the scoring kernel clears the step's counters: item counters, pending counters, planned (contiguous), and
+  // in front of them head_rows when the queue runs inside the selection launch (only heads with rows write it then)
+  const int nh_i = problem->batch * problem->n_q_heads;
+  int32_t *zero = !w.plan.pending ? nullptr : same_launch ? w.plan.head_rows : w.plan.queue_next;
+  const int n_zero = 2 * n_slabs + 1 + (same_launch ? nh_i : 0);
+  if (dp::launch_score(c, w.logits, s, ev[0], ev[1], zero, n_zero, summ, w.sub_stride) != hipSuccess) return DP_ERR_HIP;
   // the optional count outputs are written by the selection kernel next to the workspace's own
   dp::SelectOut so{w.sel_ids, w.n_exact, w.n_retained, w.n_exact_tokens, n_exact, n_retained, n_exact_tokens};
   const dp::AttnOut attn{out, lse, out_dtype == DP_BF16};

@@ -153,7 +153,7 @@ __device__ __forceinline__ void block_merge(RowState &st, float *s_m, float *s_l
       for (int i = 0; i < 8; ++i) s_acc[w][lane * 8 + i] = st.acc[i];
     }
   }
-  __syncthreads();
+  lds_barrier();  // only LDS is exchanged here
   M = -INFINITY;
   L = 0.f;
   o = 0.f;

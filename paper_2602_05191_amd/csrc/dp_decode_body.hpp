@@ -271,10 +271,20 @@ __device__ __forceinline__ void decode_queue(const DecodeArgs &a, DecodeShared<T
     sh.rows[hh] = rows[u];
     if (rows[u] > 0) chunks += min(1 << 20, (rows[u] + kChunkRows - 1) / kChunkRows);  // capped: the sum stays in range
   }
-  // least chunks per item: about one item for every second workgroup of the grid, between 1 and kMinItemChunks
+  // least chunks per item, between 1 and kMinItemChunks.  A launch of many small workgroups aims at about one item
+  // for every second workgroup; the few large workgroups of a shared launch (kCoherent) at two items each, in whole
+  // steps of the workgroup (T / 4 rows).
   const int all_chunks = block_sum<int, kWaves>(chunks, sh.scan);
-  const int half_grid = max(1, (int)gridDim.x / 2);
-  const int g = min(kMinItemChunks, max(1, (all_chunks + half_grid - 1) / half_grid));
+  int g;
+  if (kCoherent) {
+    constexpr int kStepChunks = T / 256 > 0 ? T / 256 : 1;
+    const int want = max(1, 4 * (int)gridDim.x);
+    g = (all_chunks + want - 1) / want;
+    g = min(kMinItemChunks, max(kStepChunks, (g + kStepChunks - 1) / kStepChunks * kStepChunks));
+  } else {
+    const int half_grid = max(1, (int)gridDim.x / 2);
+    g = min(kMinItemChunks, max(1, (all_chunks + half_grid - 1) / half_grid));
+  }
   int cnt[kPer], mine = 0;
 #pragma unroll
   for (int u = 0; u < kPer; ++u) {
@@ -317,10 +327,14 @@ __device__ __forceinline__ void decode_queue(const DecodeArgs &a, DecodeShared<T
       if (sh.first[mid] <= item) lo = mid; else hi = mid;
     }
     const int head = a.head0 + lo, split = item - sh.first[lo];
+    // the next item is claimed before this one is attended: the counter's round trip hides behind the rows
+    const bool claims = kCoherent || total > (int)gridDim.x;  // otherwise every item had its workgroup
+    int next = total;
+    if (claims && tid == 0)
+      next = claim_base + __hip_atomic_fetch_add(a.queue_next, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     decode_item<T, kGathered, kCoherent>(a, head, split, sh.rows[lo], g, sh);
-    if (!kCoherent && total <= (int)gridDim.x) break;  // every item had its workgroup: nothing to claim
-    if (tid == 0)
-      sh.item = claim_base + __hip_atomic_fetch_add(a.queue_next, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (!claims) break;
+    if (tid == 0) sh.item = next;
     __syncthreads();  // also: LDS is reused by the next item
     item = sh.item;
     __syncthreads();

@@ -83,6 +83,14 @@ __device__ __forceinline__ uint32_t ordered_key(float f) {
 }
 constexpr uint32_t kKeyLowestFinite = 0x00800000u;  // every finite float has a key >= this; key(-inf) is below
 
+// A workgroup barrier that orders LDS accesses only: unlike __syncthreads() it does not wait for the wave's
+// outstanding global memory operations (a counter update in flight, loads issued ahead).
+__device__ __forceinline__ void lds_barrier() {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+  __builtin_amdgcn_s_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+}
+
 // ------------------------------------------------- wave / block scans ----
 __device__ __forceinline__ int lane_id() { return threadIdx.x & 63; }
 __device__ __forceinline__ int wave_id() { return threadIdx.x >> 6; }

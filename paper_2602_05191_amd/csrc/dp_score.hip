@@ -78,13 +78,15 @@ __device__ __forceinline__ void publish_summary(const float (&v)[4], bool writer
 // head: up to G = 4 they hide behind the loads and the wholly contiguous load pattern streams faster.
 constexpr int kValuRows = 4;  // centroid rows in flight per 16-lane row; 16 rows x 4 = the 64 clusters of a workgroup
 template <int GH>
-__global__ __launch_bounds__(kScoreThreads) void score_valu_kernel(ScoreArgs a, const int32_t *__restrict__ seg_ptr) {
+__global__ __launch_bounds__(kScoreThreads) void score_valu_kernel(
+    const void *k_centroids, const int32_t *cluster_sizes, const void *q,
+    const int32_t *__restrict__ seg_ptr, int uniform_kc, int n_kv_heads, int n_q_heads, int group, int head0, ScoreArgs a) {
   const int seg = blockIdx.y;
   if (a.zero_words && blockIdx.x == 0 && blockIdx.y == 0 && (int)threadIdx.x < a.n_zero) a.zero_words[threadIdx.x] = 0;
   int c0, kc;
-  if (a.uniform_kc > 0) {  // no CSR lookup in front of the centroid loads
-    c0 = seg * a.uniform_kc;
-    kc = a.uniform_kc;
+  if (uniform_kc > 0) {  // no CSR lookup in front of the centroid loads
+    c0 = seg * uniform_kc;
+    kc = uniform_kc;
   } else {
     // the table comes as a separate restrict parameter: the compiler then reads it with scalar loads (as a member
     // of the argument struct it was a vector load and a wait in front of the centroid loads: 0.8 us on ragged batches)
@@ -96,7 +98,7 @@ __global__ __launch_bounds__(kScoreThreads) void score_valu_kernel(ScoreArgs a, 
 
   const int lane16 = threadIdx.x & 15;
   const int grp = threadIdx.x >> 4;
-  const int b = seg / a.n_kv_heads, g = seg % a.n_kv_heads;
+  const int b = seg / n_kv_heads, g = seg % n_kv_heads;
 
   // issue the centroid loads first: this group owns rows tile0 + grp*RB .. +RB-1
   const int i0 = tile0 + grp * kValuRows;
@@ -104,17 +106,17 @@ __global__ __launch_bounds__(kScoreThreads) void score_valu_kernel(ScoreArgs a, 
   int size[kValuRows];
 #pragma unroll
   for (int k = 0; k < kValuRows; ++k)
-    raw[k] = (i0 + k < kc) ? load_row_slice(a.k_centroids, (int64_t)(c0 + i0 + k), lane16) : make_uint4(0, 0, 0, 0);
+    raw[k] = (i0 + k < kc) ? load_row_slice(k_centroids, (int64_t)(c0 + i0 + k), lane16) : make_uint4(0, 0, 0, 0);
   // sizes: one dword per row, the same address for the 16 lanes of the group (a broadcast load; wider
   // or masked loads of the four sizes measured slower)
 #pragma unroll
-  for (int k = 0; k < kValuRows; ++k) size[k] = (i0 + k < kc) ? a.cluster_sizes[c0 + i0 + k] : 0;
+  for (int k = 0; k < kValuRows; ++k) size[k] = (i0 + k < kc) ? cluster_sizes[c0 + i0 + k] : 0;
 
   // the group's query slices stay packed bf16
   uint4 qv[GH];
 #pragma unroll
   for (int j = 0; j < GH; ++j)
-    qv[j] = load_row_slice(a.q, (int64_t)b * a.n_q_heads + g * a.group + a.head0 + j, lane16);
+    qv[j] = load_row_slice(q, (int64_t)b * n_q_heads + g * group + head0 + j, lane16);
 
   // lane j of the group ends up with head j's logits of the group's RB consecutive clusters
   float mine[kValuRows];
@@ -136,12 +138,12 @@ __global__ __launch_bounds__(kScoreThreads) void score_valu_kernel(ScoreArgs a, 
   }
   if (a.summaries) {  // a wave's four rows are the 16 consecutive clusters tile0 + 16 w .. + 15
     const int sub0 = tile0 + (threadIdx.x >> 6) * 16;
-    const int64_t head = (int64_t)b * a.n_q_heads + g * a.group + a.head0 + lane16;
+    const int64_t head = (int64_t)b * n_q_heads + g * group + head0 + lane16;
     publish_summary(v, lane16 < GH && (threadIdx.x & 63) < 16 && sub0 < kc,
                     a.summaries + (lane16 < GH ? head : 0) * a.sub_stride + (sub0 >> 4));
   }
   if (lane16 < GH && i0 < kc) {
-    float *out = a.logits + (int64_t)a.group * c0 + (int64_t)(a.head0 + lane16) * kc + i0;
+    float *out = a.logits + (int64_t)group * c0 + (int64_t)(head0 + lane16) * kc + i0;
     if (kValuRows == 4 && i0 + 3 < kc && (reinterpret_cast<uintptr_t>(out) & 15) == 0) {
       *reinterpret_cast<float4 *>(out) = make_float4(v[0], v[1 % kValuRows], v[2 % kValuRows],
                                                      v[3 % kValuRows]);
@@ -154,18 +156,23 @@ __global__ __launch_bounds__(kScoreThreads) void score_valu_kernel(ScoreArgs a, 
 }
 
 
+// (The arguments that the first loads depend on are leading scalar kernel parameters: the compiler flag
+// -amdgpu-kernarg-preload-count puts those into registers when a wave is launched, so no argument load sits in front
+// of the centroid loads.)
 // RT = 16-row tiles per wave.  Every wave loads the group's queries once and all its centroid tiles up front: a
 // larger RT means fewer query loads per centroid byte and more bytes in flight per wave, at the price of fewer
 // workgroups (measured: 17.4 -> 15.2 us with RT = 4 on 32 segments of 8192 clusters, G = 8; 6.0 -> 5.7 us with
 // RT = 2 on 8 segments of 8192 clusters, G = 4).
 template <int RT>
-__global__ __launch_bounds__(kScoreThreads) void score_kernel(ScoreArgs a, const int32_t *__restrict__ seg_ptr) {
+__global__ __launch_bounds__(kScoreThreads) void score_kernel(
+    const void *k_centroids, const int32_t *cluster_sizes, const void *q,
+    const int32_t *__restrict__ seg_ptr, int uniform_kc, int n_kv_heads, int n_q_heads, int group, int head0, ScoreArgs a) {
   const int seg = blockIdx.y;
   if (a.zero_words && blockIdx.x == 0 && blockIdx.y == 0 && (int)threadIdx.x < a.n_zero) a.zero_words[threadIdx.x] = 0;
   int c0, kc;
-  if (a.uniform_kc > 0) {  // no CSR lookup in front of the centroid loads
-    c0 = seg * a.uniform_kc;
-    kc = a.uniform_kc;
+  if (uniform_kc > 0) {  // no CSR lookup in front of the centroid loads
+    c0 = seg * uniform_kc;
+    kc = uniform_kc;
   } else {
     c0 = seg_ptr[seg];  // a separate restrict parameter: a scalar load
     kc = seg_ptr[seg + 1] - c0;
@@ -175,15 +182,15 @@ __global__ __launch_bounds__(kScoreThreads) void score_kernel(ScoreArgs a, const
   // the workgroup's kScoreTile * RT consecutive clusters; tile t of wave w is rows (4 t + w) * 16 .. + 15 of them
   const int base = blockIdx.x * (kScoreTile * RT) + wave * 16;
   if (base >= kc) return;  // no barrier below: a wave may leave alone
-  const int b = seg / a.n_kv_heads, g = seg % a.n_kv_heads;
+  const int b = seg / n_kv_heads, g = seg % n_kv_heads;
 
-  const bool head_live = a.head0 + r < a.group;
+  const bool head_live = head0 + r < group;
   // B operand first (its few cache lines are hot, and loads return in issue order: behind the centroid stream the
   // queries cost 0.25 us more): query head r of the pass (a zero column beyond the group), chunks kq + 4 j
   uint4 Q[4];
   {
-    const char *row = static_cast<const char *>(a.q) +
-                      ((int64_t)b * a.n_q_heads + g * a.group + (head_live ? a.head0 + r : 0)) * kRowBytes + kq * 16;
+    const char *row = static_cast<const char *>(q) +
+                      ((int64_t)b * n_q_heads + g * group + (head_live ? head0 + r : 0)) * kRowBytes + kq * 16;
 #pragma unroll
     for (int j = 0; j < 4; ++j)
       Q[j] = head_live ? *reinterpret_cast<const uint4 *>(row + j * 64) : make_uint4(0, 0, 0, 0);
@@ -194,7 +201,7 @@ __global__ __launch_bounds__(kScoreThreads) void score_kernel(ScoreArgs a, const
   for (int t = 0; t < RT; ++t) {
     const int row = base + t * kScoreTile + r;
     const bool live = row < kc;
-    const char *src = static_cast<const char *>(a.k_centroids) + (int64_t)(c0 + row) * kRowBytes + kq * 16;
+    const char *src = static_cast<const char *>(k_centroids) + (int64_t)(c0 + row) * kRowBytes + kq * 16;
 #pragma unroll
     for (int j = 0; j < 4; ++j) A[t][j] = live ? *reinterpret_cast<const uint4 *>(src + j * 64) : make_uint4(0, 0, 0, 0);
   }
@@ -205,7 +212,7 @@ __global__ __launch_bounds__(kScoreThreads) void score_kernel(ScoreArgs a, const
   for (int t = 0; t < RT; ++t) {
     const int i0 = base + t * kScoreTile + 4 * kq;
 #pragma unroll
-    for (int k = 0; k < 4; ++k) size[t][k] = (i0 + k < kc) ? a.cluster_sizes[c0 + i0 + k] : 0;
+    for (int k = 0; k < 4; ++k) size[t][k] = (i0 + k < kc) ? cluster_sizes[c0 + i0 + k] : 0;
   }
 #pragma unroll
   for (int t = 0; t < RT; ++t) {
@@ -225,12 +232,12 @@ __global__ __launch_bounds__(kScoreThreads) void score_kernel(ScoreArgs a, const
     }
     if (a.summaries) {  // the tile is the 16 consecutive clusters base + 64 t .. + 15
       const int sub0 = base + t * kScoreTile;
-      const int64_t head = (int64_t)b * a.n_q_heads + g * a.group + a.head0 + r;
+      const int64_t head = (int64_t)b * n_q_heads + g * group + head0 + r;
       publish_summary(v, head_live && kq == 0 && sub0 < kc,
                       a.summaries + (head_live ? head : 0) * a.sub_stride + (sub0 >> 4));
     }
     if (head_live && i0 < kc) {
-      float *out = a.logits + (int64_t)a.group * c0 + (int64_t)(a.head0 + r) * kc + i0;
+      float *out = a.logits + (int64_t)group * c0 + (int64_t)(head0 + r) * kc + i0;
       if (i0 + 3 < kc && (reinterpret_cast<uintptr_t>(out) & 15) == 0) {
         *reinterpret_cast<float4 *>(out) = make_float4(v[0], v[1], v[2], v[3]);
       } else {
@@ -244,20 +251,22 @@ __global__ __launch_bounds__(kScoreThreads) void score_kernel(ScoreArgs a, const
 
 }  // namespace
 
+#define HOT_ARGS(a) (a).k_centroids, (a).cluster_sizes, (a).q, (a).seg_cluster_ptr, (a).uniform_kc, (a).n_kv_heads, (a).n_q_heads, (a).group, (a).head0
+
 template <int GH>
 void launch_valu(const ScoreArgs &a, dim3 grid, hipStream_t s, hipEvent_t start, hipEvent_t stop) {
   if (start || stop)
-    hipExtLaunchKernelGGL(score_valu_kernel<GH>, grid, dim3(kScoreThreads), 0, s, start, stop, 0, a, a.seg_cluster_ptr);
+    hipExtLaunchKernelGGL(score_valu_kernel<GH>, grid, dim3(kScoreThreads), 0, s, start, stop, 0, HOT_ARGS(a), a);
   else
-    hipLaunchKernelGGL(score_valu_kernel<GH>, grid, dim3(kScoreThreads), 0, s, a, a.seg_cluster_ptr);
+    hipLaunchKernelGGL(score_valu_kernel<GH>, grid, dim3(kScoreThreads), 0, s, HOT_ARGS(a), a);
 }
 
 template <int RT>
 void launch_one(const ScoreArgs &a, dim3 grid, hipStream_t s, hipEvent_t start, hipEvent_t stop) {
   if (start || stop)
-    hipExtLaunchKernelGGL(score_kernel<RT>, grid, dim3(kScoreThreads), 0, s, start, stop, 0, a, a.seg_cluster_ptr);
+    hipExtLaunchKernelGGL(score_kernel<RT>, grid, dim3(kScoreThreads), 0, s, start, stop, 0, HOT_ARGS(a), a);
   else
-    hipLaunchKernelGGL(score_kernel<RT>, grid, dim3(kScoreThreads), 0, s, a, a.seg_cluster_ptr);
+    hipLaunchKernelGGL(score_kernel<RT>, grid, dim3(kScoreThreads), 0, s, HOT_ARGS(a), a);
 }
 
 hipError_t launch_score(const CacheView &c, float *logits, hipStream_t s, hipEvent_t start, hipEvent_t stop,

@@ -47,9 +47,9 @@ constexpr int kMaxCand = 512;            // largest bin population that is ranke
 constexpr float kTopCut = 6.0f;          // "top set": clusters whose logit is within this of the max
 constexpr int kTopMax = 64;              // largest top set handled by the one-wave fast path
 // Selection from the scoring kernel's sub-tile summaries (one-call path): one wave reads them, up to this many per
-// lane (8192 clusters), and the top set may spread over at most this many sub-tiles (one thread per cluster of those)
+// lane (8192 clusters), and the top set may spread over at most this many sub-tiles (one lane per cluster of those)
 constexpr int kLiteSubPerLane = 8;
-constexpr int kLiteMaxTopSub = 16;
+constexpr int kLiteMaxTopSub = 4;
 
 
 
@@ -110,10 +110,7 @@ struct Shared {
   int top_idx[kTopMax], top_sz[kTopMax], top_off[kTopMax];
   u64 top_m[kTopMax];
   int ntop, f_nex, f_nap, f_ntok;
-  // selection from the sub-tile summaries
-  int lite_sub[kLiteMaxTopSub], lite_nsub;
-  float lite_mx;
-  u64 lite_W;
+  int lite_sub[kLiteMaxTopSub];  // selection from the sub-tile summaries: the sub-tiles that may hold the top set
   // The refinement histogram of the (rare) crowded-bin search and the lists / merge buffers of the inline
   // attention never live at the same time: the lists are written once the search is over.
   union {
@@ -459,30 +456,32 @@ __device__ __forceinline__ int second_tau(const SelectArgs &a, u64 W, u64 m1, u6
   return top_p_second_tau(a.p2, a.p2_absolute != 0, W, m1, tau2);
 }
 
-// One wave ranks the top set gathered in sh.top_* (ntop <= kTopMax entries in any order: key, index, mass, size,
-// offset; an entry of mass 0 is a pinned cluster) pairwise on (key descending, index ascending) and, if the set
-// holds the first threshold's weight, emits both lists in ascending cluster index and leaves the three counts in
-// sh.f_*.  Otherwise sh.f_nex = -1 and nothing is emitted.  W: total weight of the head.  Call from every thread
-// of wave 0; the caller's barrier publishes the result.
+// One wave ranks a top set held one entry per lane (act: this lane holds one; key, index, mass, size, offset; an
+// entry of mass 0 is a pinned cluster) pairwise on (key descending, index ascending) and, if the set holds the first
+// threshold's weight, emits both lists in ascending cluster index and leaves the three counts in sh.f_*.
+// Otherwise sh.f_nex = -1 and nothing is emitted.  W: total weight of the head.  Call from every lane of one wave;
+// the caller's barrier publishes the result.
 template <bool kCount, int T>
-__device__ __forceinline__ void rank_top_set(const SelectArgs &a, Shared<T> &sh, Emit &emit, int ntop, u64 W,
-                                             bool can_inline) {
-  const int i = lane_id();
-  const bool act = i < ntop;
-  const uint32_t key_i = act ? sh.top_key[i] : 0u;
-  const int idx_i = act ? sh.top_idx[i] : INT_MAX;
-  const u64 m_i = act ? sh.top_m[i] : 0;
-  const int sz_i = act ? sh.top_sz[i] : 0;
+__device__ __forceinline__ void rank_lanes(const SelectArgs &a, Shared<T> &sh, Emit &emit, bool act, uint32_t key_i,
+                                           int idx_i, u64 m_i, int sz_i, int off_i, u64 W, bool can_inline) {
+  const u64 members = __ballot(act);
+  if (!act) {
+    key_i = 0u;
+    idx_i = INT_MAX;
+    m_i = 0;
+    sz_i = 0;
+  }
   const bool pin_i = act && m_i == 0;  // a candidate of the top set has weight > 0, a pinned cluster 0
   const u64 tau1 = first_tau<kCount>(a, W);
   if (wave_sum(m_i) < tau1) {  // integer sums: exact.  The retained set is not inside the top set.
-    if (i == 0) sh.f_nex = -1;
+    if (lane_id() == 0) sh.f_nex = -1;
     return;
   }
   // lane j holds entry j: the loops below fetch it with readlane (j is uniform), not from LDS
   const uint32_t mlo_i = (uint32_t)m_i, mhi_i = (uint32_t)(m_i >> 32);
   u64 ahead = 0;  // mass of the clusters that precede cluster i in the order
-  for (int j = 0; j < ntop; ++j) {
+  for (u64 mm = members; mm; mm &= mm - 1) {
+    const int j = __builtin_ctzll(mm);
     const uint32_t kj = __builtin_amdgcn_readlane(key_i, j);
     const int ij = __builtin_amdgcn_readlane(idx_i, j);
     const u64 mj = ((u64)(uint32_t)__builtin_amdgcn_readlane(mhi_i, j) << 32) |
@@ -501,39 +500,50 @@ __device__ __forceinline__ void rank_top_set(const SelectArgs &a, Shared<T> &sh,
   const int n_tok = wave_sum(exa ? sz_i : 0);
   // position of cluster i in its list = selected clusters with a smaller index
   int pe = 0, pa = 0, pt = 0;
-  for (int j = 0; j < ntop; ++j) {
+  for (u64 mm = exa_mask | apx_mask; mm; mm &= mm - 1) {
+    const int j = __builtin_ctzll(mm);
     const bool before = __builtin_amdgcn_readlane(idx_i, j) < idx_i;
     if ((exa_mask >> j) & 1) {
       pe += before;
       pt += before ? __builtin_amdgcn_readlane(sz_i, j) : 0;
-    } else if ((apx_mask >> j) & 1) {
+    } else {
       pa += before;
     }
   }
   emit.to_lds = can_inline && n_tok + n_ap <= inline_rows_of(T);
   emit.n_ex = n_ex;
   emit.n_tok = n_tok;
-  if (exa) emit.exact(pe, pt, sz_i, sh.top_off[i], idx_i);
+  if (exa) emit.exact(pe, pt, sz_i, off_i, idx_i);
   if (apx) emit.approx(pa, idx_i);
-  if (i == 0) {
+  if (lane_id() == 0) {
     sh.f_nex = n_ex;
     sh.f_nap = n_ap;
     sh.f_ntok = n_tok;
   }
 }
 
+// the same for a top set gathered in sh.top_* (ntop <= kTopMax entries in any order)
+template <bool kCount, int T>
+__device__ __forceinline__ void rank_top_set(const SelectArgs &a, Shared<T> &sh, Emit &emit, int ntop, u64 W,
+                                             bool can_inline) {
+  const int i = lane_id();
+  const bool act = i < ntop;
+  rank_lanes<kCount, T>(a, sh, emit, act, act ? sh.top_key[i] : 0u, act ? sh.top_idx[i] : 0, act ? sh.top_m[i] : 0,
+                        act ? sh.top_sz[i] : 0, act ? sh.top_off[i] : 0, W, can_inline);
+}
+
 // Top-p selection of a peaked head from the scoring kernel's sub-tile summaries, without reading the head's
-// logits: one wave reads (max, sum exp) of every sub-tile, which gives the max logit exactly and the total mass
-// W (the sub-tile sums rescaled to the max, added up in fp64 and converted to the 2^-40 fixed point of the other
-// paths: W is within a few 1e-7 of the integer sum of the clusters' own masses, so a threshold p * W moves by that
-// much).  Only sub-tiles whose max lies within kTopCut of the head's max can hold a member of the top set; their
-// logits, sizes and offsets are read (one thread per cluster) and the top set is ranked as on the fast path.
-// Returns false (block-uniform) when the head is not peaked enough for that: then nothing has been emitted.
+// logits, by ONE wave and without a barrier: it reads (max, sum exp) of every sub-tile, which gives the max logit
+// exactly and the total mass W (the sub-tile sums rescaled to the max, added up per lane in fp32 and over the lanes
+// in the 2^-40 fixed point of the other paths: W is within a few 1e-7 of the integer sum of the clusters' own
+// masses, so a threshold p * W moves by that much).  Only sub-tiles whose max lies within kTopCut of the head's max
+// can hold a member of the top set; if there are at most four of them, the wave reads their 64 logits, sizes and
+// offsets (one cluster per lane) and ranks the top set in place.  Returns false (block-uniform) when the head is not
+// peaked enough for that: then nothing has been emitted.
 template <int T>
 __device__ __forceinline__ bool lite_select(const SelectArgs &a, Shared<T> &sh, Emit &emit, int c0, int kc,
                                             const float *lg, bool plan, bool can_inline, int &n_ex, int &n_ap,
                                             int &n_tok) {
-  static_assert(T >= kLiteMaxTopSub * kSubTile, "one thread per cluster of the top sub-tiles");
   const int tid = threadIdx.x;
   if (tid < 64) {
     const int n_sub = (kc + kSubTile - 1) / kSubTile;
@@ -548,55 +558,37 @@ __device__ __forceinline__ bool lite_select(const SelectArgs &a, Shared<T> &sh, 
 #pragma unroll
     for (int i = 0; i < kLiteSubPerLane; ++i) m = fmaxf(m, sv[i].x);
     const float M = wave_max(m);
-    double acc = 0.0;
-#pragma unroll
-    for (int i = 0; i < kLiteSubPerLane; ++i)
-      if (sv[i].x > -INFINITY) acc += (double)sv[i].y * (double)__builtin_amdgcn_exp2f((sv[i].x - M) * kLog2e);
-    const u64 W = wave_sum((u64)(acc * 1099511627776.0));  // per lane <= 128 * 2^40: integer sums from here on
-    int n_ts = 0;
+    float acc = 0.f;
+    int n_ts = 0, my_sub = -1;
 #pragma unroll
     for (int i = 0; i < kLiteSubPerLane; ++i) {
-      const bool top = sv[i].x > -INFINITY && M - sv[i].x < kTopCut;
+      const bool live = sv[i].x > -INFINITY;
+      if (live) acc = fmaf(sv[i].y, __builtin_amdgcn_exp2f((sv[i].x - M) * kLog2e), acc);
+      // the sub-tiles that may hold a cluster within kTopCut of the max: slot k of the list goes to lanes 16 k .. + 15
+      const bool top = live && M - sv[i].x < kTopCut;
       const u64 mask = __ballot(top);
       const int pos = n_ts + __popcll(mask & ((1ull << tid) - 1));
       if (top && pos < kLiteMaxTopSub) sh.lite_sub[pos] = tid + 64 * i;
       n_ts += __popcll(mask);
     }
-    if (tid == 0) {
-      sh.lite_nsub = M > -INFINITY ? n_ts : -1;  // no candidate at all: left to the general path
-      sh.lite_mx = M;
-      sh.lite_W = W;
-      sh.ntop = 0;
+    const u64 W = wave_sum((u64)((double)acc * 1099511627776.0));  // per lane <= 128 * 2^40: integer sums from here on
+    bool ok = M > -INFINITY && n_ts <= kLiteMaxTopSub;  // no candidate at all, or a flat head: the general path
+    if (ok) {
+      __builtin_amdgcn_wave_barrier();  // the list was written by lanes of this wave
+      my_sub = (tid >> 4) < n_ts ? sh.lite_sub[tid >> 4] : -1;
+      const int i = my_sub * kSubTile + (tid & 15);
+      const bool have = my_sub >= 0 && i < kc;
+      const float l = have ? lg[i] + 0.0f : -INFINITY;  // -0 becomes +0
+      const int sz = have ? a.cluster_sizes[c0 + i] : 0;
+      const int off = (have && plan) ? a.cluster_offsets[c0 + i] : 0;
+      const float d = M - l;
+      const bool member = have && d < kTopCut;
+      rank_lanes<false, T>(a, sh, emit, member, ordered_key(l), i, member ? fx_mass(d) : 0, sz, off, W, can_inline);
+    } else if (tid == 0) {
+      sh.f_nex = -1;
     }
   }
-  __syncthreads();
-  const int n_ts = sh.lite_nsub;
-  if (n_ts < 0 || n_ts > kLiteMaxTopSub) return false;
-  const float mx = sh.lite_mx;
-  if (tid < n_ts * kSubTile) {
-    const int i = sh.lite_sub[tid >> 4] * kSubTile + (tid & 15);
-    if (i < kc) {
-      const float l = lg[i] + 0.0f;  // -0 becomes +0
-      const int sz = a.cluster_sizes[c0 + i];
-      const int off = plan ? a.cluster_offsets[c0 + i] : 0;
-      const float d = mx - l;
-      if (d < kTopCut) {
-        const int s = atomicAdd(&sh.ntop, 1);
-        if (s < kTopMax) {
-          sh.top_key[s] = ordered_key(l);
-          sh.top_idx[s] = i;
-          sh.top_m[s] = fx_mass(d);
-          sh.top_sz[s] = sz;
-          sh.top_off[s] = off;
-        }
-      }
-    }
-  }
-  __syncthreads();
-  const int ntop = sh.ntop;
-  if (ntop > kTopMax) return false;
-  if (wave_id() == 0) rank_top_set<false, T>(a, sh, emit, ntop, sh.lite_W, can_inline);
-  __syncthreads();
+  lds_barrier();
   if (sh.f_nex < 0) return false;
   n_ex = sh.f_nex;
   n_ap = sh.f_nap;
@@ -908,20 +900,21 @@ __device__ __forceinline__ bool full_select(const SelectArgs &a, Shared<T> &sh, 
 }
 
 // Arrival of a head at the launch's `planned` counter (kGate): everything the stage-3 queue of this launch reads
-// of the head has been stored coherently and has completed (the caller sees to that) before the counter moves;
-// a head that needs the queue is counted in `pending` first.  Returns the arrival number.
-__device__ __forceinline__ int head_planned(int32_t *planned, int32_t *pending, bool needs_queue) {
-  if (needs_queue) {
-    __hip_atomic_fetch_add(pending, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    __builtin_amdgcn_s_waitcnt(0);  // performed before the arrival below can be seen
-  }
-  return __hip_atomic_fetch_add(planned, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+// of the head has been stored coherently and has completed (the caller sees to that) before the counter moves.
+// One word counts both: the low 16 bits the heads that have arrived, the high 16 bits those among them that
+// left rows to the queue.  Returns the word as it was before this head: the caller must not touch that value
+// before the head is done (a use is a wait for the counter's round trip).
+constexpr int kQueueBit = 0x10000;
+__device__ __forceinline__ int head_planned(int32_t *planned, bool needs_queue) {
+  return __hip_atomic_fetch_add(planned, 1 + (needs_queue ? kQueueBit : 0), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
 // Stage 2 for one head by one workgroup, and stage 3 too when the head has few rows.  kGate: the stage-3 queue for
 // the heavier heads runs inside this same launch (select_decode_kernel): the plan, the counts and head_rows are then
-// stored coherently, and the head reports to `planned` once they have completed; thread 0 gets the arrival number
-// (-1 otherwise).
+// stored coherently, and the head reports to `planned` once they have completed; the first thread of the LAST wave
+// (thread T - 64, which has nothing to load when the head has few rows, so the counter's round trip delays nobody)
+// gets the counter word as it was before this head, with bit 31 set if the head left rows to the queue (-1 in the
+// other threads).
 template <int E, bool kCount, int T, bool kGate>
 __device__ __forceinline__ int select_head(const SelectArgs &a, Shared<T> &sh, int32_t *planned) {
   constexpr int kInlineRows = inline_rows_of(T);
@@ -964,9 +957,10 @@ __device__ __forceinline__ int select_head(const SelectArgs &a, Shared<T> &sh, i
     chosen = lite_select<T>(a, sh, emit, c0, kc, lg, plan, can_inline, n_ex, n_ap, n_tok);
   if (!chosen && !full_select<E, kCount, T>(a, sh, emit, head, c0, kc, lg, plan, can_inline, n_ex, n_ap, n_tok)) {
     // no candidate: finished inside (zero output, zero counts)
-    if (kGate && tid == 0) {
+    if (kGate) {
       __builtin_amdgcn_s_waitcnt(0);
-      arrival = head_planned(planned, a.plan.pending, false);
+      __syncthreads();  // thread 0's stores have completed
+      if (tid == T - 64) arrival = head_planned(planned, false);
     }
     return arrival;
   }
@@ -974,39 +968,40 @@ __device__ __forceinline__ int select_head(const SelectArgs &a, Shared<T> &sh, i
   const int R = n_tok + n_ap;
   const bool inline_attn = can_inline && R <= kInlineRows;
   if (tid == 0) {
-    put_counts(a.out, head, n_ex, n_ex + n_ap, n_tok, kGate);
+    // a head that is attended here leaves nothing for the queue to read: its stores stay plain
+    put_counts(a.out, head, n_ex, n_ex + n_ap, n_tok, kGate && !inline_attn);
     if (plan) {
       if (inline_attn) {
         sh.at.l_start[n_ex + n_ap] = R;
-        st_i32(a.plan.head_rows + head, -1, kGate);  // attended here: nothing left for the stage-3 queue
+        // attended here: nothing left for the stage-3 queue (kGate: head_rows was cleared by the scoring kernel)
+        if (!kGate) a.plan.head_rows[head] = -1;
       } else {
         st_i32(emit.row_start + n_ex + n_ap, R, kGate);
         st_i32(a.plan.head_rows + head, R, kGate);
         if (!kGate && a.plan.pending && R > 0) atomicAdd(&a.plan.pending[head / kMaxQueueHeads], 1);
       }
-      st_i32(a.plan.done + head, 0, kGate);
+      if (!kGate || !inline_attn) st_i32(a.plan.done + head, 0, kGate);
     }
   }
+  // a head that is attended here has nothing to publish: it reports at once, and the workgroups that wait for the
+  // count leave while it attends
+  if (kGate && inline_attn && tid == T - 64) arrival = head_planned(planned, false);
   if (!inline_attn) {
     if (kGate) {  // the plan was written by every thread: all of it has completed before the head reports
       __builtin_amdgcn_s_waitcnt(0);
       __syncthreads();
-      if (tid == 0) arrival = head_planned(planned, a.plan.pending, R > 0);
+      if (tid == T - 64) arrival = head_planned(planned, R > 0) | (R > 0 ? (int)0x80000000 : 0);
     }
     return arrival;
   }
   if (R == 0) {  // nothing to attend to: zero output
     if (tid < kHeadDim) store_out(a.attn_out, a.out_is_bf16, head, tid, 0.f);
     if (tid == 0 && a.lse) a.lse[head] = -INFINITY;
-    if (kGate && tid == 0) {
-      __builtin_amdgcn_s_waitcnt(0);
-      arrival = head_planned(planned, a.plan.pending, false);
-    }
     return arrival;
   }
 
   // ---- inline attention for a head with few rows ---------------------------
-  __syncthreads();
+  lds_barrier();  // the lists are in LDS; the head's report to the counter (kGate) may still be in flight
   {
     const int lane16 = tid & 15, grp = tid >> 4;
     const uint4 qv = load_row_slice(a.q, (int64_t)head, lane16);
@@ -1024,11 +1019,6 @@ __device__ __forceinline__ int select_head(const SelectArgs &a, Shared<T> &sh, i
     const int per = kAttendBatch * ((R + kGroups * kAttendBatch - 1) / (kGroups * kAttendBatch));
     const int ra = grp * per, rb = min(R, ra + per);
     attend_rows(st, qv, a.scale_log2, src, sh.at.l_start, sh.at.l_src, n_ex + n_ap, 0, n_ex, ra, rb, kAttendBatch, lane16);
-    if (kGate && tid == 0) {
-      // the head's few coherent stores went out before the K / V loads that have just come back: this wait is short
-      __builtin_amdgcn_s_waitcnt(0);
-      arrival = head_planned(planned, a.plan.pending, false);
-    }
     float M, L, o;
     const int groups_used = (R + per - 1) / per;
     block_merge<(T / 64)>(st, sh.at.m_m, sh.at.m_l, sh.at.m_acc, (groups_used + 3) / 4, M, L, o);
@@ -1050,30 +1040,68 @@ __global__ __launch_bounds__(T) void select_kernel(SelectArgs a) {
 // to do would cost as much as the selection itself).  Workgroup b < n_heads selects head b (and attends it if it has
 // few rows); every workgroup, the ones beyond n_heads included, then serves the stage-3 queue of the heads that
 // were left over.  The queue may only start when every head has reported to `planned`.  Nobody waits without
-// bound: a workgroup polls the counter for a limited time and leaves if the count is not reached; the workgroup
-// whose own arrival completes the count never polls and serves the queue until it is empty, so all items are
-// attended whoever else has left.  The scoring kernel of the step clears planned, pending and the item counter.
-constexpr int kGatePolls = 4000;  // about a microsecond each
+// bound: a selecting workgroup leaves when its head is done unless its own arrival completed the count, in which
+// case it serves the queue until it is empty (so all items are attended whoever else has left); the workgroups
+// beyond n_heads poll the counter for a limited time and leave if the count is not reached.  The scoring kernel of
+// the step clears planned and the item counter.
+constexpr int kGatePolls = 20000;  // a microsecond or two each
+struct QueueArgs {  // what the stage-3 queue needs beyond the selection's own arguments
+  float *partials;
+  int32_t *planned;
+  int32_t splits, n_heads;
+};
 template <int E, bool kCount, int T>
-__global__ __launch_bounds__(T) void select_decode_kernel(SelectArgs a, DecodeArgs d, int32_t *planned, int n_heads) {
+__global__ __launch_bounds__(T) void select_decode_kernel(SelectArgs a, QueueArgs qa) {
   __shared__ Shared<T> sh;
   __shared__ DecodeShared<T> dsh;
   __shared__ int s_go;
-  int arrival = -1;
-  if ((int)blockIdx.x < n_heads) arrival = select_head<E, kCount, T, true>(a, sh, planned);
-  if (threadIdx.x == 0) {
-    int go = arrival == n_heads - 1;
+  int32_t *const planned = qa.planned;
+  const int n_heads = qa.n_heads;
+  if ((int)blockIdx.x < n_heads) {
+    const int word = select_head<E, kCount, T, true>(a, sh, planned);
+    // the last head in serves the queue if any head (itself included) left rows to it
+    if (threadIdx.x == T - 64) s_go = (word & 0xffff) == n_heads - 1 && (word & 0xffff0000) != 0;
+  } else if (threadIdx.x == 0) {
+    int word = 0;
 #pragma unroll 1
-    for (int it = 0; !go && it < kGatePolls; ++it) {
-      go = __hip_atomic_load(planned, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) >= n_heads;
-      if (!go) __builtin_amdgcn_s_sleep(32);
+    for (int it = 0; it < kGatePolls; ++it) {
+      word = __hip_atomic_load(planned, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      if ((word & 0xffff) >= n_heads) break;
+      __builtin_amdgcn_s_sleep(64);
     }
-    // every arrival was preceded by the head's count in pending: the value is final now
-    if (go) go = __hip_atomic_load(d.pending, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) > 0;
-    s_go = go;
+    s_go = (word & 0xffff) >= n_heads && (word >> 16) > 0;
   }
   __syncthreads();
   if (!s_go) return;
+  // the queue's view of the same arguments
+  DecodeArgs d;
+  d.q = a.q;
+  d.k_cache = a.k_cache;
+  d.v_cache = a.v_cache;
+  d.k_centroids = a.k_centroids;
+  d.v_centroids = a.v_centroids;
+  d.seg_row_base = a.seg_row_base;
+  d.seg_cluster_ptr = a.seg_cluster_ptr;
+  d.cluster_sizes = a.cluster_sizes;
+  d.n_exact = a.out.n_exact;
+  d.n_retained = a.out.n_retained;
+  d.plan = a.plan;
+  d.partials = qa.partials;
+  d.out = a.attn_out;
+  d.lse = a.lse;
+  d.n_kv_heads = a.n_kv_heads;
+  d.n_q_heads = a.n_q_heads;
+  d.group = a.group;
+  d.max_k = a.max_k;
+  d.splits = qa.splits;
+  d.out_is_bf16 = a.out_is_bf16;
+  d.head0 = 0;
+  d.n_heads = n_heads;
+  d.queue_next = a.plan.queue_next;
+  d.pending = nullptr;
+  d.k_gather = d.v_gather = nullptr;
+  d.rows_cap = 0;
+  d.scale_log2 = a.scale_log2;
   decode_queue<T, false, true>(d, dsh);
 }
 
@@ -1140,23 +1168,24 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(PlanArgs a) {
   if (R == 0 && a.attn_out && tid < kHeadDim) store_out(a.attn_out, a.out_is_bf16, head, tid, 0.f);
 }
 
-// with a queue: grid = the heads, or as many workgroups as the chip holds at once if that is more
+// with a queue: more workgroups than heads
 template <int E, int T>
 void launch_select_e(const SelectArgs &a, bool by_count, dim3 grid, hipStream_t s, hipEvent_t start, hipEvent_t stop,
-                     const DecodeArgs *queue, int32_t *planned) {
+                     const QueueArgs *queue) {
   if (queue) {
-    const int n_heads = (int)grid.x;
-    const unsigned resident = 256u * (1024 / T);  // 256 CUs, 1024 threads of this kernel each
-    const dim3 g(grid.x > resident ? grid.x : resident);
+    // as many workgroups as 256 CUs hold at once (1024 threads of this kernel each): a workgroup that had to wait
+    // for a place would only find the count complete and leave, at the launch's expense
+    const unsigned resident = 256u * (1024 / T);
+    const dim3 g(grid.x + 32 > resident ? grid.x + 32 : resident);
     if (start || stop) {
       if (by_count)
-        hipExtLaunchKernelGGL((select_decode_kernel<E, true, T>), g, dim3(T), 0, s, start, stop, 0, a, *queue, planned, n_heads);
+        hipExtLaunchKernelGGL((select_decode_kernel<E, true, T>), g, dim3(T), 0, s, start, stop, 0, a, *queue);
       else
-        hipExtLaunchKernelGGL((select_decode_kernel<E, false, T>), g, dim3(T), 0, s, start, stop, 0, a, *queue, planned, n_heads);
+        hipExtLaunchKernelGGL((select_decode_kernel<E, false, T>), g, dim3(T), 0, s, start, stop, 0, a, *queue);
     } else if (by_count) {
-      hipLaunchKernelGGL((select_decode_kernel<E, true, T>), g, dim3(T), 0, s, a, *queue, planned, n_heads);
+      hipLaunchKernelGGL((select_decode_kernel<E, true, T>), g, dim3(T), 0, s, a, *queue);
     } else {
-      hipLaunchKernelGGL((select_decode_kernel<E, false, T>), g, dim3(T), 0, s, a, *queue, planned, n_heads);
+      hipLaunchKernelGGL((select_decode_kernel<E, false, T>), g, dim3(T), 0, s, a, *queue);
     }
   } else if (start || stop) {  // measurement: the runtime stamps the kernel's own begin and end
     if (by_count)
@@ -1210,18 +1239,12 @@ hipError_t launch_select(const CacheView &c, const float *logits, const SelectRu
   const dim3 grid(c.batch * c.n_q_heads);
   if (grid.x == 0) return hipSuccess;
   const int k = c.max_clusters_per_seg;
-  DecodeArgs dq;
-  const DecodeArgs *q = nullptr;
-  int32_t *planned = nullptr;
+  QueueArgs qa;
+  const QueueArgs *q = nullptr;
   if (queue) {
-    if (grid.x > (unsigned)kSameLaunchMaxHeads || !plan.ent_src || !plan.pending || !attn.out) return hipErrorInvalidValue;
-    dq = decode_args_of(c, out.n_exact, out.n_retained, plan, queue->partials, queue->splits, attn);
-    dq.head0 = 0;
-    dq.n_heads = (int)grid.x;
-    dq.queue_next = plan.queue_next;
-    dq.pending = plan.pending;
-    q = &dq;
-    planned = queue->planned;
+    if (grid.x > (unsigned)kSameLaunchMaxHeads || !plan.ent_src || !attn.out) return hipErrorInvalidValue;
+    qa = QueueArgs{queue->partials, queue->planned, queue->splits, (int32_t)grid.x};
+    q = &qa;
   }
   // Workgroup size.  The kernel is bound by instruction issue on its one CU (every phase runs once per wave), so a
   // head gets the fewest threads that still leave it at most 8 logits per thread: 512 threads up to 4096 clusters
@@ -1231,17 +1254,17 @@ hipError_t launch_select(const CacheView &c, const float *logits, const SelectRu
   // of running in rounds.
   constexpr int kHalf = kSelThreads / 2, kQuarter = kSelThreads / 4;
   if (grid.x > 512 && k <= 8 * kQuarter) {
-    if (k <= 2 * kQuarter) launch_select_e<2, kQuarter>(a, bc, grid, s, start, stop, q, planned);
-    else if (k <= 4 * kQuarter) launch_select_e<4, kQuarter>(a, bc, grid, s, start, stop, q, planned);
-    else launch_select_e<8, kQuarter>(a, bc, grid, s, start, stop, q, planned);
+    if (k <= 2 * kQuarter) launch_select_e<2, kQuarter>(a, bc, grid, s, start, stop, q);
+    else if (k <= 4 * kQuarter) launch_select_e<4, kQuarter>(a, bc, grid, s, start, stop, q);
+    else launch_select_e<8, kQuarter>(a, bc, grid, s, start, stop, q);
   } else if (k <= 8 * kHalf) {
-    if (k <= 2 * kHalf) launch_select_e<2, kHalf>(a, bc, grid, s, start, stop, q, planned);
-    else if (k <= 4 * kHalf) launch_select_e<4, kHalf>(a, bc, grid, s, start, stop, q, planned);
-    else launch_select_e<8, kHalf>(a, bc, grid, s, start, stop, q, planned);
-  } else if (k <= 8 * kSelThreads) launch_select_e<8, kSelThreads>(a, bc, grid, s, start, stop, q, planned);
-  else if (k <= 16 * kSelThreads) launch_select_e<16, kSelThreads>(a, bc, grid, s, start, stop, q, planned);
-  else if (k <= 32 * kSelThreads) launch_select_e<32, kSelThreads>(a, bc, grid, s, start, stop, q, planned);
-  else if (k <= 64 * kSelThreads) launch_select_e<64, kSelThreads>(a, bc, grid, s, start, stop, q, planned);
+    if (k <= 2 * kHalf) launch_select_e<2, kHalf>(a, bc, grid, s, start, stop, q);
+    else if (k <= 4 * kHalf) launch_select_e<4, kHalf>(a, bc, grid, s, start, stop, q);
+    else launch_select_e<8, kHalf>(a, bc, grid, s, start, stop, q);
+  } else if (k <= 8 * kSelThreads) launch_select_e<8, kSelThreads>(a, bc, grid, s, start, stop, q);
+  else if (k <= 16 * kSelThreads) launch_select_e<16, kSelThreads>(a, bc, grid, s, start, stop, q);
+  else if (k <= 32 * kSelThreads) launch_select_e<32, kSelThreads>(a, bc, grid, s, start, stop, q);
+  else if (k <= 64 * kSelThreads) launch_select_e<64, kSelThreads>(a, bc, grid, s, start, stop, q);
   else return hipErrorInvalidValue;
   return hipGetLastError();
 }
