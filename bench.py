@@ -163,6 +163,33 @@ def main():
         regions.append(((w1 - w0) * 1e6 / args.steps, ev0.elapsed_time(ev1) * 1e3 / args.steps))
     wall_us, event_us = sorted(regions)[1]
 
+    # spread of the step time: one rotation over the L replicas at a time between two events on the launch stream
+    # (an event costs a bubble, so these rotations are not the reported value); p10 / median / p90 of rotation / L
+    n_rot = max(10, min(200, args.steps // max(L, 1)))
+    rot_ev = [torch.cuda.Event(enable_timing=True) for _ in range(n_rot + 1)]
+    torch.cuda.synchronize()
+    rot_ev[0].record()
+    for r in range(n_rot):
+        for i in range(L):
+            step(i)
+        rot_ev[r + 1].record()
+    torch.cuda.synchronize()
+    rot_us = sorted(rot_ev[r].elapsed_time(rot_ev[r + 1]) * 1e3 / L for r in range(n_rot))
+    pct = lambda q: rot_us[min(n_rot - 1, int(q * n_rot))]
+
+    # the paper's own operating point (p1, p2) = (0.95, 0.7) of its ablation (Sec. 5.4), same inputs
+    torch.cuda.synchronize()
+    o0 = time.perf_counter()
+    for i in range(min(args.steps, 720)):
+        dp.dp_decode_attention(probs[i % L], 0.95, 0.7, out, lse, ws, None, None, None)
+    torch.cuda.synchronize()
+    op_us = (time.perf_counter() - o0) * 1e6 / min(args.steps, 720)
+    dp.dp_decode_attention(pr0, 0.95, 0.7, out, lse, ws, ne, nr, nt)
+    torch.cuda.synchronize()
+    op_counts = (float(nr.float().mean()), float(ne.float().mean()), float(nt.float().mean()))
+    dp.dp_decode_attention(pr0, p1, p2, out, lse, ws, ne, nr, nt)
+    torch.cuda.synchronize()
+
     # same-layer repeat (everything cache-resident), labelled as such
     torch.cuda.synchronize()
     c0 = time.perf_counter()
@@ -196,6 +223,25 @@ def main():
 
     score_gap_us, _ = time_stage(lambda i: dp.dp_score_centroids(probs[i % L], logits))
 
+    # What this machine streams: the loads-only probe (dp_stream_read_probe) over the same key-centroid matrices,
+    # back to back over the replicas like the scoring launches (the floor for one launch of that size), and over
+    # the whole K cache of the replicas (the streaming-read bandwidth of the box)
+    scan_bytes = base.k_centroids.numel() * base.k_centroids.element_size()
+    read_floor_gap_us, _ = time_stage(lambda i: dp.dp_stream_read_probe(reps[i % L].k_centroids))
+    big = [r.k_cache for r in reps]
+    big_bytes = big[0].numel() * big[0].element_size()
+    for i in range(min(L, 4)):
+        dp.dp_stream_read_probe(big[i])
+    torch.cuda.synchronize()
+    b0, b1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    n_big = max(4, min(64, int(8e9 // max(big_bytes, 1))))
+    b0.record()
+    for i in range(n_big):
+        dp.dp_stream_read_probe(big[i % L])
+    b1.record()
+    torch.cuda.synchronize()
+    stream_gbs = big_bytes * n_big / (b0.elapsed_time(b1) * 1e-3) / 1e9
+
     # The scoring kernel's own duration: every launch carries a pair of HIP events that the runtime stamps
     # with the kernel's begin and end (dp_score_centroids_timed), launched back-to-back on the same stream.
     import ctypes
@@ -219,6 +265,23 @@ def main():
         hip.hipEventDestroy(e0)
         hip.hipEventDestroy(e1)
     score_us, score_med = statistics.mean(durs), statistics.median(durs)
+    # the same for the loads-only probe over the same matrices: the kernel's own duration
+    pairs = []
+    for _ in range(n_stage):
+        e0, e1 = ctypes.c_void_p(), ctypes.c_void_p()
+        assert hip.hipEventCreate(ctypes.byref(e0)) == 0 and hip.hipEventCreate(ctypes.byref(e1)) == 0
+        pairs.append((e0, e1))
+    for i, (e0, e1) in enumerate(pairs):
+        dp.dp_stream_read_probe(reps[i % L].k_centroids, None, None, e0, e1)
+    torch.cuda.synchronize()
+    durs = []
+    for e0, e1 in pairs:
+        ms = ctypes.c_float()
+        assert hip.hipEventElapsedTime(ctypes.byref(ms), e0, e1) == 0
+        durs.append(ms.value * 1e3)
+        hip.hipEventDestroy(e0)
+        hip.hipEventDestroy(e1)
+    read_floor_us = statistics.mean(durs)
 
     # The three kernels inside the one-call path: dp_decode_attention_timed stamps each kernel's begin and end.
     n_in = min(n_stage, 360)
@@ -249,6 +312,11 @@ def main():
         in_step["gap_select_decode"].append(elapsed(ev[3], ev[4]))
         for e in ev:
             hip.hipEventDestroy(e)
+    n_launches = dp.dp_decode_attention_launches(pr0)
+    shared_launch = n_launches == 2      # the split decode runs inside the selection launch: no third kernel
+    if shared_launch:
+        for k in ("decode", "gap_select_decode"):
+            in_step[k] = [0.0] * len(in_step[k])
     in_step_avg = {k: statistics.mean(v) for k, v in in_step.items()}
     in_step_med = {k: statistics.median(v) for k, v in in_step.items()}
     select_us, select_med = time_stage(lambda i: dp.dp_topp_select(probs[i % L], logits, p1, p2, sel_d, ne, nr, nt))
@@ -334,6 +402,19 @@ def main():
     dp.dp_decode_attention(pr0, p1, p2, out, lse, ws, None, None, None)
     torch.cuda.synchronize()
 
+    # ---- A/B: the split decode inside the selection launch (two launches per step) against a decode launch of
+    # its own (three): the same step with DP_FLAG_SEPARATE_DECODE_LAUNCH set / cleared, wall clock, same replicas ----
+    probs_sep = [dp.Problem(r, flags=dp.DP_FLAG_SEPARATE_DECODE_LAUNCH) for r in reps]
+    probs_def = [dp.Problem(r) for r in reps]
+    n_ab = max(10, min(args.steps, 720))
+    ab["decode_launch"] = {
+        "default_policy_launches": dp.dp_decode_attention_launches(probs_def[0]),
+        "default_policy_us": round(wall_time(lambda i: dp.dp_decode_attention(probs_def[i % L], p1, p2, out, lse, ws), n_ab), 3),
+        "separate_decode_launch_us": round(wall_time(lambda i: dp.dp_decode_attention(probs_sep[i % L], p1, p2, out, lse, ws), n_ab), 3),
+    }
+    dp.dp_decode_attention(pr0, p1, p2, out, lse, ws, None, None, None)
+    torch.cuda.synchronize()
+
     # ---- the prefill-side build of this workload's cache (Sec. 4.1, Eq. 2): token-order K / V + cluster ids ->
     # cluster-contiguous rows, sizes, offsets, centroids.  One call per layer, not part of the decode step. ----
     from workloads import token_order_input
@@ -362,11 +443,19 @@ def main():
     total_k = int(cache.seg_cluster_ptr[-1])
     score_bytes = total_k * (2 * cache.head_dim + 4 + 4 * cache.group)
     score_gbs = score_bytes / (score_us * 1e-6) / 1e9
+    # what the selection launch must read of a step whose heads it attends itself: the summaries of every head
+    # (8 bytes per 16 clusters), the logits / sizes / offsets of the few sub-tiles that hold the top set (not
+    # counted), K and V rows of the selected tokens and centroids; written: the output
+    select_bytes = nh * ((mk + 15) // 16) * 8 + alg["rows_sum"] * 4 * cache.head_dim + nh * cache.head_dim * 6
 
     # the dominant kernel = the one that moves most of the step's algorithmic bytes: the centroid scan for
     # peaked heads, the row gather of the decode kernel when heads are flat
     decode_bytes = alg["rows_union"] * 4 * cache.head_dim
-    if decode_bytes > score_bytes:
+    if decode_bytes > score_bytes and shared_launch:
+        roof = dict(kernel="select_decode_kernel (selection and split decode in one launch)", name="select_decode_kernel",
+                    bytes=decode_bytes, avg=in_step_avg["select"], med=in_step_med["select"],
+                    how="kernel-stamped HIP events inside dp_decode_attention")
+    elif decode_bytes > score_bytes:
         roof = dict(kernel="decode_kernel (steps a5-a6 of dp_decode_attention)", name="decode_kernel",
                     bytes=decode_bytes, avg=in_step_avg["decode"], med=in_step_med["decode"],
                     how="kernel-stamped HIP events inside dp_decode_attention")
@@ -374,6 +463,12 @@ def main():
         roof = dict(kernel="score_kernel (dp_score_centroids)", name="score_kernel", bytes=score_bytes,
                     avg=score_us, med=score_med, how="kernel-stamped HIP events, back-to-back launches")
     roof_gbs = roof["bytes"] / (roof["avg"] * 1e-6) / 1e9
+    # the kernel that takes the longest inside the step (not necessarily the one that moves the bytes)
+    by_time = {"score": ("score kernel", score_bytes), "select": (
+        "select_decode_kernel" if shared_launch else "select_kernel",
+        decode_bytes + select_bytes if shared_launch else select_bytes), "decode": ("decode_kernel", decode_bytes)}
+    longest = max(("score", "select", "decode"), key=lambda k: in_step_med[k])
+    longest_gbs = by_time[longest][1] / (in_step_avg[longest] * 1e-6) / 1e9
 
     value = wall_us
     step_gbs = alg["total"] / (value * 1e-6) / 1e9
@@ -404,14 +499,41 @@ def main():
             "event_us": round(event_us, 3),
             "timed_regions_wall_us": [round(r[0], 3) for r in regions],
             "reported_region": "median of three regions of `steps` steps each",
+            "region_overhead_note": "a region is bracketed by two synchronisations: its first launch starts from an "
+                                    "idle queue and its last kernel drains alone, a few microseconds that are shared "
+                                    "by all `steps` steps, so a short region (--steps 20) reads some us per step higher "
+                                    "than a long one; event_us (HIP events inside the same region) excludes the host side",
+            "p10_us": round(pct(0.10), 3), "p50_us": round(pct(0.50), 3), "p90_us": round(pct(0.90), 3),
+            "percentiles_over": f"{n_rot} rotations of {L} steps, each between two HIP events",
+            "kernel_launches_per_step": n_launches,
             "cache_resident_us": round(resident_us, 3),
             "algorithmic_bytes": alg["total"],
             "algorithmic_bytes_per_head_sum": alg["total_per_head_sum"],
             "achieved_GBs": round(step_gbs, 1),
             "frac_of_hbm_peak": round(step_gbs / HBM_PEAK_GBS, 4),
+            "stream_read_GBs": round(stream_gbs, 1),
+            "frac_of_stream_read": round(step_gbs / stream_gbs, 4),
+            "stream_read_measured_with": f"dp_stream_read_probe over the {big_bytes >> 20} MiB K cache of the replicas, "
+                                         f"{n_big} launches between two HIP events",
+            "read_floor_of_one_scan_us": round(read_floor_us, 3),
+            "read_floor_back_to_back_interval_us": round(read_floor_gap_us, 3),
+            "read_floor_note": f"the same probe over the {scan_bytes >> 20} MiB key-centroid matrix of each replica, back to "
+                               "back: what one launch that only reads the scan's bytes takes on this machine",
             "retained_clusters_mean": float(nr_h.mean()),
             "exact_clusters_mean": float(ne_h.mean()),
             "exact_tokens_mean": float(nt_h.mean()),
+            "per_head": {
+                "retained_clusters": {"min": int(nr_h.min()), "median": float(np.median(nr_h)), "max": int(nr_h.max())},
+                "exact_clusters": {"min": int(ne_h.min()), "median": float(np.median(ne_h)), "max": int(ne_h.max())},
+                "exact_tokens": {"min": int(nt_h.min()), "median": float(np.median(nt_h)), "max": int(nt_h.max())},
+                "rows_attended": {"min": int((nt_h + nr_h - ne_h).min()), "median": float(np.median(nt_h + nr_h - ne_h)),
+                                  "max": int((nt_h + nr_h - ne_h).max())},
+            },
+        },
+        "operating_point_0.95_0.7": {
+            "step_us": round(op_us, 3), "retained_clusters_mean": op_counts[0], "exact_clusters_mean": op_counts[1],
+            "exact_tokens_mean": op_counts[2],
+            "note": "the (p1, p2) of the paper's ablation (Sec. 5.4) on the same inputs, wall clock over the rotating replicas",
         },
         "stages_us": {
             "dp_score_centroids": round(score_us, 3), "dp_topp_select": round(select_us, 3),
@@ -421,7 +543,8 @@ def main():
         "kernels_in_step_us": {
             "avg": {k: round(v, 3) for k, v in in_step_avg.items()},
             "median": {k: round(v, 3) for k, v in in_step_med.items()},
-            "how": "dp_decode_attention_timed: HIP events stamped with each kernel's own begin and end",
+            "how": "dp_decode_attention_timed: HIP events stamped with each kernel's own begin and end"
+                   + ("; the split decode runs inside the selection launch (no decode kernel)" if shared_launch else ""),
         },
         "roofline": {
             "kernel": roof["kernel"],
@@ -436,7 +559,17 @@ def main():
             "median_launch_us": round(roof["med"], 3),
             "measured_with": roof["how"],
             "score_kernel": {"bytes_per_launch": score_bytes, "avg_launch_us": round(score_us, 3),
-                             "GBs": round(score_gbs, 1), "back_to_back_interval_us": round(score_gap_us, 3)},
+                             "GBs": round(score_gbs, 1), "back_to_back_interval_us": round(score_gap_us, 3),
+                             "read_floor_us": round(read_floor_us, 3),
+                             "read_floor_over_score": round(read_floor_us / score_us, 3)},
+            "longest_kernel": {
+                "kernel": by_time[longest][0], "median_us_in_step": round(in_step_med[longest], 3),
+                "bytes_per_launch": by_time[longest][1], "GBs": round(longest_gbs, 1),
+                "frac": round(longest_gbs / HBM_PEAK_GBS, 4),
+                "note": "bound by the latency of its dependent memory round trips (summaries -> top sub-tiles -> K/V "
+                        "rows -> output), not by bytes, when the heads are peaked" if longest == "select" and
+                        decode_bytes <= score_bytes else "",
+            },
         },
         "baselines_same_box": {
             "dense_us": round(dense_us, 3),
@@ -468,6 +601,18 @@ def main():
             a = time.perf_counter()
             r = orc.decode_step(p1, p2, n_threads=threads, want_order=False)
             times.append(time.perf_counter() - a)
+        # the same step on one thread, and the oracle's dense attention (Eq. 1) over every token, a few runs each
+        single, dense_t = [], []
+        t_end = time.time() + args.cpu_seconds / 2
+        while (len(single) < 2 or time.time() < t_end) and len(single) < 20:
+            a = time.perf_counter()
+            orc.decode_step(p1, p2, n_threads=1, want_order=False)
+            single.append(time.perf_counter() - a)
+        t_end = time.time() + args.cpu_seconds / 2
+        while (len(dense_t) < 2 or time.time() < t_end) and len(dense_t) < 20:
+            a = time.perf_counter()
+            orc.dense_step(n_threads=threads)
+            dense_t.append(time.perf_counter() - a)
         result["cpu_baseline"] = {
             "value": round(statistics.median(times) * 1e6, 1),
             "unit": "us",
@@ -475,6 +620,11 @@ def main():
             "kind": "oracle",
             "sample": f"the whole {CONFIGS[args.config]} step (all {nh} heads), fp64 C oracle, OpenMP over heads, "
                       f"median of {len(times)} repetitions",
+            "single_thread_us": round(statistics.median(single) * 1e6, 1),
+            "single_thread_runs": len(single),
+            "dense_us": round(statistics.median(dense_t) * 1e6, 1),
+            "dense_note": f"the oracle's dense attention (Eq. 1) over every token, {threads} threads, "
+                          f"median of {len(dense_t)} runs",
         }
         err = float(np.abs(out.cpu().numpy() - r.out).max())
         result["step"]["max_abs_err_vs_oracle"] = err

@@ -181,6 +181,12 @@ dp_status dp_decode_attention(const dp_problem *problem, float p1, float p2, voi
                               float *lse, int32_t *n_exact, int32_t *n_retained, int32_t *n_exact_tokens,
                               void *workspace, size_t workspace_bytes, void *stream);
 
+/* Host-only.  Kernel launches that one dp_decode_attention call enqueues for this problem: scoring, selection (with
+ * the attention of heads of few rows), and the split decode either inside the selection launch or as launches of
+ * its own, one per 1024 heads (see DP_FLAG_SEPARATE_DECODE_LAUNCH).  0 for an invalid problem or one without
+ * clusters. */
+int32_t dp_decode_attention_launches(const dp_problem *problem);
+
 /* dp_decode_attention for callers that cannot allocate device memory or hand over a
  * workspace: code under HIP graph capture, tight serving loops, harnesses that
  * forbid hipMalloc.  Same computation, same kernels and same results as
@@ -327,6 +333,15 @@ typedef struct {
                           largest logit and the sum of exp(logit - that), left by the scoring stage */
 } dp_workspace_layout;
 dp_status dp_get_workspace_layout(const dp_problem *problem, dp_workspace_layout *layout /* host */);
+
+/* Measurement aid (not part of the method): one launch that reads `bytes` bytes of `buffer` (device, 16-byte
+ * aligned, bytes a multiple of 16) once, with the access shape of the scoring stage (256 threads per workgroup, four
+ * 16-byte loads in flight per thread, 16 KiB of consecutive bytes per workgroup), and writes nothing (sink: a device
+ * word that keeps the loads alive, may be NULL).  Its duration is the floor for any single launch that must read
+ * that many bytes on this machine.  start_event / stop_event (hipEvent_t as void*, either may be NULL) receive the
+ * kernel's own begin and end timestamps, as in dp_score_centroids_timed. */
+dp_status dp_stream_read_probe(const void *buffer, size_t bytes, uint32_t *sink, void *stream, void *start_event,
+                               void *stop_event);
 
 const char *dp_status_string(dp_status status);
 

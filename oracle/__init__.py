@@ -50,11 +50,21 @@ class _Cache(C.Structure):
 _lib = None
 
 
+def build_sanitized(out_path: str) -> str:
+    """The same source with AddressSanitizer and UndefinedBehaviorSanitizer (-O1), for the CPU test that runs the
+    pins through it (host code only; the GPU never sees this build)."""
+    subprocess.check_call(["gcc", "-O1", "-g", "-std=c11", "-fPIC", "-shared", "-fopenmp", "-fno-omit-frame-pointer",
+                           "-fsanitize=address,undefined", "-fno-sanitize-recover=undefined", "-Wall", "-Wextra",
+                           "-o", out_path, _SRC, "-lm"])
+    return out_path
+
+
 def _load():
     global _lib
     if _lib is None:
-        build()
-        L = C.CDLL(_LIB)
+        # DP_ORACLE_LIB: a build of dp_oracle.c to load instead (the sanitized one of tests/test_oracle_sanitized.py)
+        path = os.environ.get("DP_ORACLE_LIB") or build()
+        L = C.CDLL(path)
         P, I, D, U = C.c_void_p, C.c_int32, C.c_double, C.c_uint32
         CP = C.POINTER(_Cache)
         L.dpo_num_clusters.restype = I

@@ -29,7 +29,7 @@ EXPORTS = ["dp_workspace_bytes", "dp_logits_count", "dp_get_workspace_layout", "
            "dp_group_union_decode_attention",
            "dp_decode_attention_timed", "dp_budget_decode_attention", "dp_dense_decode", "dp_build_workspace_bytes", "dp_build_cluster_cache", "dp_kmeans_workspace_bytes",
            "dp_kmeans_assign",
-           "dp_decode_attention_static",
+           "dp_decode_attention_static", "dp_stream_read_probe", "dp_decode_attention_launches",
            "dp_status_string"]
 
 
@@ -120,6 +120,10 @@ def load_library():
     L.dp_kmeans_workspace_bytes.argtypes = [C.POINTER(_Prefill)]
     L.dp_kmeans_assign.restype = I
     L.dp_kmeans_assign.argtypes = [C.POINTER(_Prefill), V, V, V, V, C.c_size_t, V]
+    L.dp_decode_attention_launches.restype = C.c_int32
+    L.dp_decode_attention_launches.argtypes = [PP]
+    L.dp_stream_read_probe.restype = I
+    L.dp_stream_read_probe.argtypes = [V, C.c_size_t, V, V, V, V]
     L.dp_status_string.restype = C.c_char_p
     L.dp_status_string.argtypes = [I]
     _lib = L
@@ -414,6 +418,19 @@ def dp_group_union_decode_attention(problem: Problem, p1: float, p2: float, out:
                                                           workspace.numel() * workspace.element_size(),
                                                           _stream(stream)),
            "dp_group_union_decode_attention")
+
+
+def dp_decode_attention_launches(problem: Problem) -> int:
+    return int(load_library().dp_decode_attention_launches(problem.ref))
+
+
+def dp_stream_read_probe(buffer: torch.Tensor, sink: Optional[torch.Tensor] = None, stream=None, start_event=None,
+                         stop_event=None) -> None:
+    """Measurement aid: one launch that reads the whole tensor once and writes nothing.  start_event / stop_event:
+    raw hipEvent_t handles that receive the kernel's own timestamps."""
+    assert buffer.is_contiguous()
+    _check(load_library().dp_stream_read_probe(_ptr(buffer), buffer.numel() * buffer.element_size(), _ptr(sink),
+                                               _stream(stream), start_event, stop_event), "dp_stream_read_probe")
 
 
 def dp_kmeans_workspace_bytes(prefill: Prefill) -> int:

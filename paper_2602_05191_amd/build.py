@@ -11,7 +11,7 @@ INCLUDE = os.path.join(os.path.dirname(PKG), "include")
 LIB = os.path.join(PKG, "libdp_hip.so")
 OBJ_DIR = os.path.join(PKG, "_build")
 SOURCES = ["dp_api.hip", "dp_score.hip", "dp_select.hip", "dp_decode.hip", "dp_dense.hip", "dp_build.hip",
-           "dp_variants.hip", "dp_kmeans.hip", "dp_union.hip"]
+           "dp_variants.hip", "dp_kmeans.hip", "dp_union.hip", "dp_probe.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 # packed-fp32 instructions are switched off for every device function
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",

@@ -175,6 +175,19 @@ dp_status select_only(const dp_problem *problem, const float *logits, const dp::
              : DP_ERR_HIP;
 }
 
+// Whether a step runs the split decode inside the selection launch.
+// Where the shared launch pays (measured, 32 heads): it saves the decode launch of a step whose heads are all
+// peaked (8192 clusters per KV head: 15.4 instead of 16.5 us; 256 clusters: 11.6 instead of 13 us), and its queue is
+// served by the selection kernel's large workgroups, which is as fast as the decode kernel's many small ones
+// when the heads that need it are long (8192 clusters, flat heads: 111 against 115 us) but slower when they are
+// many and of middling length (2048 clusters, flat heads: 56 against 44 us; a fixed budget on every head: 64
+// against 53 us).  Hence: top-p rule only, and not for segments of 513 to 4096 clusters.
+bool shares_launch(const dp_problem *problem, bool by_count) {
+  const int mk = problem->max_clusters_per_seg;
+  return mk > 0 && (int64_t)problem->batch * problem->n_q_heads <= dp::kSameLaunchMaxHeads && !by_count &&
+         (mk <= 512 || mk > 4096) && !(problem->flags & DP_FLAG_SEPARATE_DECODE_LAUNCH);
+}
+
 // score -> select (+ attention of light heads) -> split decode, on one stream.  A step that serves few heads runs
 // the split decode inside the selection launch (two launches); flags bit DP_FLAG_SEPARATE_DECODE_LAUNCH keeps the
 // three launches.
@@ -193,16 +206,7 @@ dp_status whole_step(const dp_problem *problem, const dp::SelectRule &rule, void
   hipStream_t s = static_cast<hipStream_t>(stream);
   const int n_slabs = (int)(((size_t)problem->batch * problem->n_q_heads + dp::kMaxQueueHeads - 1) / dp::kMaxQueueHeads);
   if (problem->max_clusters_per_seg > 0 && n_slabs <= 64) w.plan.pending = w.plan.queue_next + n_slabs;
-  // Where the shared launch pays (measured, 32 heads): it saves the decode launch of a step whose heads are all
-  // peaked (8192 clusters per KV head: 17.6 instead of 18.5 us; 256 clusters: 11 instead of 15 us), and its queue is
-  // served by the selection kernel's large workgroups, which is as fast as the decode kernel's many small ones
-  // when the heads that need it are long (8192 clusters, flat heads: 111 against 115 us) but slower when they are
-  // many and of middling length (2048 clusters, flat heads: 56 against 44 us; a fixed budget on every head: 64
-  // against 53 us).  Hence: top-p rule only, and not for segments of 513 to 4096 clusters.
-  const int mk = problem->max_clusters_per_seg;
-  const bool same_launch = w.plan.pending && (int64_t)problem->batch * problem->n_q_heads <= dp::kSameLaunchMaxHeads &&
-                           !rule.by_count && (mk <= 512 || mk > 4096) &&
-                           !(problem->flags & DP_FLAG_SEPARATE_DECODE_LAUNCH);
+  const bool same_launch = w.plan.pending && shares_launch(problem, rule.by_count != 0);
   // the summaries serve the top-p rule on heads without cluster flags
   float2 *summ = (!rule.by_count && !problem->cluster_flags && rule.p1 < 1.0f) ? w.summaries : nullptr;
   // the scoring kernel clears the step's counters: item counters, pending counters, planned (contiguous), and
@@ -420,6 +424,15 @@ dp_status dp_decode_attention(const dp_problem *problem, float p1, float p2, voi
   if (!p_in_domain(p1, p2)) return DP_ERR_INVALID_ARG;
   return whole_step(problem, top_p_rule(problem, p1, p2), out, out_dtype, lse, n_exact, n_retained, n_exact_tokens,
                     workspace, workspace_bytes, stream);
+}
+
+int32_t dp_decode_attention_launches(const dp_problem *problem) {
+  if (check_common(problem) != DP_OK) return 0;
+  if (problem->max_clusters_per_seg == 0) return 0;
+  const int64_t nh = (int64_t)problem->batch * problem->n_q_heads;
+  const int score = problem->n_q_heads / problem->n_kv_heads == 3 ? 2 : 1;  // a group of 3 is scored as 2 + 1 heads
+  if (shares_launch(problem, false)) return score + 1;
+  return score + 1 + (int32_t)((nh + dp::kMaxQueueHeads - 1) / dp::kMaxQueueHeads);
 }
 
 dp_status dp_decode_attention_static(const dp_problem *problem, float p1, float p2, void *out, dp_dtype out_dtype,

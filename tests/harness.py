@@ -55,6 +55,29 @@ def gpu_logits(cache: ClusteredCache, sm_scale: float = 0.0):
     return out, lg
 
 
+CANARY = 0xA5
+
+
+class Guarded:
+    """A device buffer with 256 bytes of canary on either side: `t` is the tensor handed to the library, check()
+    asserts that nothing was written outside it."""
+
+    def __init__(self, shape, dtype, fill):
+        import torch
+        n = int(np.prod(shape)) * torch.empty((), dtype=dtype).element_size()
+        self.pad = 256
+        self.n = n
+        self.raw = torch.full((self.pad + (n + 255) // 256 * 256 + self.pad,), CANARY, dtype=torch.uint8, device="cuda:0")
+        self.t = self.raw[self.pad: self.pad + n].view(dtype).reshape(shape)
+        self.t.fill_(fill)
+
+    def check(self, what):
+        lo = self.raw[: self.pad].cpu().numpy()
+        hi = self.raw[self.pad + self.n:].cpu().numpy()
+        assert (lo == CANARY).all(), f"{what}: bytes in front of the buffer were overwritten"
+        assert (hi == CANARY).all(), f"{what}: bytes behind the buffer were overwritten"
+
+
 def gpu_select(cache: ClusteredCache, flat_logits: np.ndarray, p1: float, p2: float, flags: int = 0, budget=None):
     """budget = (k_retained, k_exact): dp_topk_select instead of dp_topp_select (p1, p2 unused);
     budget = "sorted": the sort-based A/B variant dp_topp_select_sorted."""
@@ -64,9 +87,10 @@ def gpu_select(cache: ClusteredCache, flat_logits: np.ndarray, p1: float, p2: fl
     pr = dp.Problem(dc, flags=flags)
     nh, mk = cache.batch * cache.n_q_heads, max(cache.max_clusters_per_seg, 1)
     lg = torch.from_numpy(np.ascontiguousarray(flat_logits, dtype=np.float32)).cuda()
-    sel = torch.full((nh, mk), -7, dtype=torch.int32, device="cuda:0")
-    ne = torch.full((nh,), -7, dtype=torch.int32, device="cuda:0")
-    nr, nt = ne.clone(), ne.clone()
+    g_sel = Guarded((nh, mk), torch.int32, -7)
+    g_cnt = [Guarded((nh,), torch.int32, -7) for _ in range(3)]
+    sel = g_sel.t
+    ne, nr, nt = (g.t for g in g_cnt)
     if budget == "sorted":
         dp.dp_topp_select_sorted(pr, lg, p1, p2, sel, ne, nr, nt)
     elif budget is None:
@@ -74,6 +98,9 @@ def gpu_select(cache: ClusteredCache, flat_logits: np.ndarray, p1: float, p2: fl
     else:
         dp.dp_topk_select(pr, lg, int(budget[0]), int(budget[1]), sel, ne, nr, nt)
     torch.cuda.synchronize()
+    g_sel.check("sel_ids")
+    for g in g_cnt:
+        g.check("counts")
     sel, ne, nr, nt = sel.cpu().numpy(), ne.cpu().numpy(), nr.cpu().numpy(), nt.cpu().numpy()
     exact = [sel[i, :ne[i]].copy() for i in range(nh)]
     approx = [sel[i, ne[i]:nr[i]].copy() for i in range(nh)]
@@ -94,13 +121,16 @@ def gpu_sparse_decode(cache: ClusteredCache, exact: List[np.ndarray], approx: Li
         ne[i], nr[i] = len(exact[i]), len(exact[i]) + len(approx[i])
         sel[i, :ne[i]] = exact[i]
         sel[i, ne[i]:nr[i]] = approx[i]
-    ws = torch.empty(max(dp.dp_workspace_bytes(pr), 256), dtype=torch.uint8, device="cuda:0")
-    out = torch.full((cache.batch, cache.n_q_heads, cache.head_dim), float("nan"),
-                     dtype=torch.bfloat16 if out_bf16 else torch.float32, device="cuda:0")
-    lse = torch.full((nh,), float("nan"), dtype=torch.float32, device="cuda:0")
+    g_ws = Guarded((max(dp.dp_workspace_bytes(pr), 256),), torch.uint8, 0)
+    g_out = Guarded((cache.batch, cache.n_q_heads, cache.head_dim), torch.bfloat16 if out_bf16 else torch.float32,
+                    float("nan"))
+    g_lse = Guarded((nh,), torch.float32, float("nan"))
+    ws, out, lse = g_ws.t, g_out.t, g_lse.t
     dp.dp_sparse_decode(pr, torch.from_numpy(sel).cuda(), torch.from_numpy(ne).cuda(), torch.from_numpy(nr).cuda(),
                         out, lse, ws)
     torch.cuda.synchronize()
+    for g, what in ((g_ws, "workspace"), (g_out, "out"), (g_lse, "lse")):
+        g.check(what)
     return out.float().cpu().numpy(), lse.cpu().numpy().reshape(cache.batch, cache.n_q_heads)
 
 
@@ -115,17 +145,22 @@ def gpu_decode_attention(cache: ClusteredCache, p1: float, p2: float, flags: int
     pr = dp.Problem(dc, sm_scale=sm_scale, flags=flags)
     nh, mk = cache.batch * cache.n_q_heads, max(cache.max_clusters_per_seg, 1)
     nbytes = dp.dp_workspace_bytes(pr)
-    ws = torch.zeros(max(nbytes, 256), dtype=torch.uint8, device="cuda:0")
-    out = torch.full((cache.batch, cache.n_q_heads, cache.head_dim), float("nan"),
-                     dtype=torch.bfloat16 if out_bf16 else torch.float32, device="cuda:0")
-    lse = torch.full((nh,), float("nan"), dtype=torch.float32, device="cuda:0")
-    ne = torch.full((nh,), -7, dtype=torch.int32, device="cuda:0")
-    nr, nt = ne.clone(), ne.clone()
+    # every buffer the call writes sits between canaries: the workspace (exactly the size the library asks for),
+    # the output, the normalisers and the three count vectors
+    g_ws = Guarded((max(nbytes, 256),), torch.uint8, 0)
+    g_out = Guarded((cache.batch, cache.n_q_heads, cache.head_dim), torch.bfloat16 if out_bf16 else torch.float32,
+                    float("nan"))
+    g_lse = Guarded((nh,), torch.float32, float("nan"))
+    g_cnt = [Guarded((nh,), torch.int32, -7) for _ in range(3)]
+    ws, out, lse = g_ws.t, g_out.t, g_lse.t
+    ne, nr, nt = (g.t for g in g_cnt)
     if budget is None:
         dp.dp_decode_attention(pr, p1, p2, out, lse, ws, ne, nr, nt)
     else:
         dp.dp_budget_decode_attention(pr, int(budget[0]), int(budget[1]), out, lse, ws, ne, nr, nt)
     torch.cuda.synchronize()
+    for g, what in [(g_ws, "workspace"), (g_out, "out"), (g_lse, "lse")] + [(g, "counts") for g in g_cnt]:
+        g.check(what)
     lay = dp.dp_workspace_layout(pr)
     wsh = ws.cpu().numpy()
     sel = wsh[lay["sel_ids"]: lay["sel_ids"] + 4 * nh * mk].view(np.int32).reshape(nh, mk)
