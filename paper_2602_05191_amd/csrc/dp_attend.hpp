@@ -124,13 +124,13 @@ __device__ __forceinline__ void attend_rows(RowState &st, const uint4 &qv, float
 __device__ __forceinline__ void wave_merge(RowState &st) {
 #pragma unroll
   for (int d = 16; d <= 32; d <<= 1) {
-    const float om = __shfl_xor(st.m, d, 64);
+    const float om = d == 16 ? xor16(st.m) : xor32(st.m);
     const float M = fmaxf(st.m, om);
     const float wa = (st.m == -INFINITY) ? 0.f : exp2f(st.m - M);
     const float wb = (om == -INFINITY) ? 0.f : exp2f(om - M);
-    st.l = st.l * wa + __shfl_xor(st.l, d, 64) * wb;
+    st.l = st.l * wa + (d == 16 ? xor16(st.l) : xor32(st.l)) * wb;
 #pragma unroll
-    for (int i = 0; i < 8; ++i) st.acc[i] = st.acc[i] * wa + __shfl_xor(st.acc[i], d, 64) * wb;
+    for (int i = 0; i < 8; ++i) st.acc[i] = st.acc[i] * wa + (d == 16 ? xor16(st.acc[i]) : xor32(st.acc[i])) * wb;
     st.m = M;
   }
 }

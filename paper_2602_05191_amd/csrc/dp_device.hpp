@@ -32,6 +32,21 @@ __device__ __forceinline__ float row16_sum(float v) {
   return v;
 }
 
+// Value of the lane 16 (32) positions away, i.e. the same column of the neighbouring DPP row (of the other half of
+// the wave), through the gfx950 row / half swap instructions: two vector-ALU operations instead of a trip through
+// the LDS crossbar.  v_permlane16_swap exchanges the odd rows of its first operand with the even rows of its second,
+// v_permlane32_swap the upper half of the first with the lower half of the second.
+__device__ __forceinline__ uint32_t xor16_u32(uint32_t v) {
+  const auto r = __builtin_amdgcn_permlane16_swap(v, v, false, false);
+  return (threadIdx.x & 16) ? r[0] : r[1];
+}
+__device__ __forceinline__ uint32_t xor32_u32(uint32_t v) {
+  const auto r = __builtin_amdgcn_permlane32_swap(v, v, false, false);
+  return (threadIdx.x & 32) ? r[0] : r[1];
+}
+__device__ __forceinline__ float xor16(float v) { return __uint_as_float(xor16_u32(__float_as_uint(v))); }
+__device__ __forceinline__ float xor32(float v) { return __uint_as_float(xor32_u32(__float_as_uint(v))); }
+
 // ------------------------------------------------------------- bf16 ------
 __device__ __forceinline__ float bf16_lo(uint32_t u) { return __uint_as_float(u << 16); }
 __device__ __forceinline__ float bf16_hi(uint32_t u) { return __uint_as_float(u & 0xffff0000u); }

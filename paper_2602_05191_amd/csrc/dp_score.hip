@@ -60,15 +60,15 @@ struct ScoreArgs {
 // wave must call this; `writer` is true in the one lane per head that stores the result.
 __device__ __forceinline__ void publish_summary(const float (&v)[4], bool writer, float2 *dst) {
   float m = fmaxf(fmaxf(v[0], v[1]), fmaxf(v[2], v[3]));
-  m = fmaxf(m, __shfl_xor(m, 16, 64));
-  m = fmaxf(m, __shfl_xor(m, 32, 64));
+  m = fmaxf(m, xor16(m));
+  m = fmaxf(m, xor32(m));
   float s = 0.f;
   if (m > -INFINITY) {
 #pragma unroll
     for (int k = 0; k < 4; ++k) s += __builtin_amdgcn_exp2f((v[k] - m) * 1.4426950408889634f);  // exp2(-inf) = 0
   }
-  s += __shfl_xor(s, 16, 64);  // fixed order: (row0 + row1) + (row2 + row3) in every lane
-  s += __shfl_xor(s, 32, 64);
+  s += xor16(s);  // fixed order: (row0 + row1) + (row2 + row3) in every lane
+  s += xor32(s);
   if (writer) *dst = make_float2(m, s);
 }
 
