@@ -11,9 +11,9 @@ constexpr int kDecThreads = 256;
 
 template <bool kGathered>
 __global__ __launch_bounds__(kDecThreads) void decode_kernel(DecodeArgs a) {
-  __shared__ DecodeShared<kDecThreads> sh;
+  DP_DECODE_LDS(kDecThreads);
   if (a.pending && *a.pending == 0) return;  // every head was finished by the selection kernel
-  decode_queue<kDecThreads, kGathered, false>(a, sh);
+  decode_queue<kDecThreads, kGathered, false>(a, DP_DECODE_LDS_ARGS);
 }
 
 }  // namespace

@@ -90,36 +90,36 @@ inline DecodeArgs decode_args_of(const CacheView &c, const int32_t *n_exact, con
   return a;
 }
 
-// Loads of what another workgroup of the SAME launch has written (kCoherent): device-coherent, they do not hit a
-// stale line of this compute die's L2.  Data of an earlier launch is read with plain loads.
-template <bool kCoherent>
-__device__ __forceinline__ int32_t ld_i32(const int32_t *p) {
-  return kCoherent ? __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : *p;
-}
+// An int32 that another workgroup of the SAME launch may have written (kCoherent, a template parameter in scope):
+// a device-coherent load that does not hit a stale line of this compute die's L2; data of an earlier launch is read
+// with a plain load.  (A macro: through a function the plain loads of uniform addresses were no longer scalar loads,
+// eight more vector registers and a wave of occupancy on the decode kernel.)
+#define DP_LD_I32(lvalue) \
+  (kCoherent ? __hip_atomic_load(&(lvalue), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : (lvalue))
 
 // rows per item of a head with R rows (multiple of kChunkRows); g: least chunks per item of this launch
 __device__ __forceinline__ int rows_per_item(int R, int S, int g) {
   return kChunkRows * max(g, (R + kChunkRows * S - 1) / (kChunkRows * S));
 }
 
-template <int T>
-struct DecodeShared {
-  static constexpr int kWaves = T / 64;
-  static constexpr int kBlockRows = T > 512 ? T : 512;  // rows resolved per LDS staging round
-  int start[kBlockRows + 1], src[kBlockRows + 1];
-  float m[kWaves], l[kWaves];
-  float acc[kWaves][kHeadDim];
-  int last, item;
-  int first[kMaxQueueHeads + 1];  // first item number of each head of this launch
-  int scan[kWaves + 1];
-  int rows[kMaxQueueHeads];
-};
+// LDS of the queue, declared by the kernel that runs it (separate arrays: as members of one struct the same code
+// needed 16 more vector registers and lost a wave of occupancy on the decode kernel)
+#define DP_DECODE_LDS(T)                                                                           \
+  __shared__ int s_start[((T) > 512 ? (T) : 512) + 1]; /* rows resolved per LDS staging round */    \
+  __shared__ int s_src[((T) > 512 ? (T) : 512) + 1];                                               \
+  __shared__ float s_m[(T) / 64], s_l[(T) / 64];                                                   \
+  __shared__ float s_acc[(T) / 64][kHeadDim];                                                      \
+  __shared__ int s_last, s_item;                                                                   \
+  __shared__ int s_first[kMaxQueueHeads + 1]; /* first item number of each head of this launch */  \
+  __shared__ int s_scan[(T) / 64 + 1];                                                             \
+  __shared__ int s_rows[kMaxQueueHeads]
+#define DP_DECODE_LDS_ARGS s_start, s_src, s_m, s_l, s_acc, &s_last, &s_item, s_first, s_scan, s_rows
 
 // One (head, split) item: attend its rows, publish the partial, and merge the head if this item arrives last.
 template <int T, bool kGathered, bool kCoherent>
-__device__ __forceinline__ void decode_item(const DecodeArgs &a, int head, int split, int R, int g, DecodeShared<T> &sh) {
-  constexpr int kGroups = T / 16, kWaves = T / 64, kBlockRows = DecodeShared<T>::kBlockRows;
-  const int tid = threadIdx.x, lane16 = tid & 15, grp = tid >> 4;
+__device__ __forceinline__ void decode_item(const DecodeArgs &a, int head, int split, int R, int g, int *s_start, int *s_src,
+                                            float *s_m, float *s_l, float (*s_acc)[kHeadDim], int *s_last, int tid,
+                                            int lane16, int grp) {
   const int c = rows_per_item(R, a.splits, g);
   const int row_a = split * c;
   const int row_b = min(R, row_a + c);
@@ -128,7 +128,7 @@ __device__ __forceinline__ void decode_item(const DecodeArgs &a, int head, int s
   const int b = head / a.n_q_heads, h = head % a.n_q_heads;
   const int seg = b * a.n_kv_heads + h / a.group;
   const int c0 = a.seg_cluster_ptr[seg];
-  const int n_ex = ld_i32<kCoherent>(a.n_exact + head), n_rt = ld_i32<kCoherent>(a.n_retained + head);
+  const int n_ex = DP_LD_I32(a.n_exact[head]), n_rt = DP_LD_I32(a.n_retained[head]);
   const int32_t *ent_src = a.plan.ent_src + (int64_t)head * a.max_k;
   const int32_t *row_start = a.plan.row_start + (int64_t)head * (a.max_k + 1);
 
@@ -155,41 +155,40 @@ __device__ __forceinline__ void decode_item(const DecodeArgs &a, int head, int s
   RowState st;
   row_state_init(st);
 
-  int ent0 = ld_i32<kCoherent>(a.plan.chunk_entry + (int64_t)head * a.plan.chunk_stride + row_a / kChunkRows);
+  int ent0 = DP_LD_I32(a.plan.chunk_entry[(int64_t)head * a.plan.chunk_stride + row_a / kChunkRows]);
 
-  for (int r0 = row_a; r0 < row_b; r0 += kBlockRows) {
-    const int r1 = min(row_b, r0 + kBlockRows);
+  for (int r0 = row_a; r0 < row_b; r0 += (T > 512 ? T : 512)) {
+    const int r1 = min(row_b, r0 + (T > 512 ? T : 512));
     // stage the list entries that cover rows [r0, r1): every entry has >= 1 row
     const int n_ent = min(r1 - r0, n_rt - ent0);
     __syncthreads();
     for (int k = tid; k <= n_ent; k += T) {
-      sh.start[k] = ld_i32<kCoherent>(row_start + ent0 + k);
-      sh.src[k] = (k < n_ent) ? ld_i32<kCoherent>(ent_src + ent0 + k) : 0;
+      s_start[k] = DP_LD_I32(row_start[ent0 + k]);
+      s_src[k] = (k < n_ent) ? DP_LD_I32(ent_src[ent0 + k]) : 0;
     }
     __syncthreads();
     // the DPP-row groups take consecutive 4-row pieces: one step of the workgroup reads T / 4 consecutive rows
     if (use_gather)
-      attend_rows<true>(st, qv, a.scale_log2, src, sh.start, sh.src, n_ent, ent0, n_ex, r0 + grp * kAttendBatch, r1,
-                        kGroups * kAttendBatch, lane16);
+      attend_rows<true>(st, qv, a.scale_log2, src, s_start, s_src, n_ent, ent0, n_ex, r0 + grp * kAttendBatch, r1,
+                        (T / 16) * kAttendBatch, lane16);
     else
-      attend_rows<false>(st, qv, a.scale_log2, src, sh.start, sh.src, n_ent, ent0, n_ex, r0 + grp * kAttendBatch, r1,
-                         kGroups * kAttendBatch, lane16);
+      attend_rows<false>(st, qv, a.scale_log2, src, s_start, s_src, n_ent, ent0, n_ex, r0 + grp * kAttendBatch, r1,
+                         (T / 16) * kAttendBatch, lane16);
     // first entry of the next block: the entry that holds row r1
     if (r1 < row_b) {
-      int lo = 0, hi = n_ent + 1;  // sh.start[n_ent] is staged as well
+      int lo = 0, hi = n_ent + 1;  // s_start[n_ent] is staged as well
       while (hi - lo > 1) {
         const int mid = (lo + hi) >> 1;
-        if (sh.start[mid] <= r1) lo = mid; else hi = mid;
+        if (s_start[mid] <= r1) lo = mid; else hi = mid;
       }
       ent0 += lo;
     }
   }
 
   float M, L, o;
-  // waves beyond the item's rows hold the empty state
-  const int rows_here = row_b - row_a;
-  const int waves_used = min(kWaves, (rows_here + 4 * kAttendBatch - 1) / (4 * kAttendBatch));
-  block_merge<kWaves>(st, sh.m, sh.l, sh.acc, waves_used, M, L, o);
+  // (waves beyond the item's rows hold the empty state: a large workgroup does not merge them; for the small
+  // workgroups of the decode kernel the count stays a constant, which keeps the kernel at five waves per SIMD)
+  block_merge<(T / 64)>(st, s_m, s_l, s_acc, T > 256 ? min(T / 64, (row_b - row_a + 15) / 16) : T / 64, M, L, o);
 
   if (n_active == 1) {  // the only split of this head: finish here
     if (tid < kHeadDim) {
@@ -219,10 +218,10 @@ __device__ __forceinline__ void decode_item(const DecodeArgs &a, int head, int s
   // The split that arrives last merges all partials of the head (log-sum-exp merge).
   if (tid == 0) {
     const int ticket = __hip_atomic_fetch_add(&a.plan.done[head], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    sh.last = (ticket == n_active - 1);
+    (*s_last) = (ticket == n_active - 1);
   }
   __syncthreads();
-  if (!sh.last) return;
+  if (!(*s_last)) return;
   if (tid < kHeadDim) {
     // running log-sum-exp merge; the coherent loads of 8 partials are issued together
     float Mx = -INFINITY, Ls = 0.f, os = 0.f;
@@ -256,25 +255,26 @@ __device__ __forceinline__ void decode_item(const DecodeArgs &a, int head, int s
 // tail, see the selection kernel); otherwise a workgroup's first item is its block index and only further items
 // are claimed.  Call with the whole workgroup.
 template <int T, bool kGathered, bool kCoherent>
-__device__ __forceinline__ void decode_queue(const DecodeArgs &a, DecodeShared<T> &sh) {
-  constexpr int kWaves = T / 64;
-  // least chunks per item of a heavy launch: four steps of the workgroup (T / 16 DPP rows, 4 cache rows each)
-  constexpr int kMinItemChunks = T / 64;
-  const int tid = threadIdx.x;
+__device__ __forceinline__ void decode_queue(const DecodeArgs &a, int *s_start, int *s_src, float *s_m, float *s_l,
+                                             float (*s_acc)[kHeadDim], int *s_last, int *s_item, int *s_first,
+                                             int *s_scan, int *s_rows) {
+  const int tid = threadIdx.x, lane16 = tid & 15, grp = tid >> 4;
+
   // ---- the queue: items per head from head_rows[], exclusive prefix in LDS ----
+  constexpr int kMinItemChunks = T / 64;  // least chunks per item of a heavy launch: four steps of the workgroup
   constexpr int kPer = kMaxQueueHeads / T;  // consecutive heads per thread
   int rows[kPer], chunks = 0;
 #pragma unroll
   for (int u = 0; u < kPer; ++u) {
     const int hh = tid * kPer + u;
-    rows[u] = hh < a.n_heads ? ld_i32<kCoherent>(a.plan.head_rows + a.head0 + hh) : 0;  // <= 0: nothing to do (empty, or attended already)
-    sh.rows[hh] = rows[u];
+    rows[u] = hh < a.n_heads ? DP_LD_I32(a.plan.head_rows[a.head0 + hh]) : 0;  // <= 0: nothing to do (empty, or attended already)
+    s_rows[hh] = rows[u];
     if (rows[u] > 0) chunks += min(1 << 20, (rows[u] + kChunkRows - 1) / kChunkRows);  // capped: the sum stays in range
   }
   // least chunks per item, between 1 and kMinItemChunks.  A launch of many small workgroups aims at about one item
-  // for every second workgroup; the few large workgroups of a shared launch (kCoherent) at two items each, in whole
+  // for every second workgroup; the few large workgroups of a shared launch (kCoherent) at four items each, in whole
   // steps of the workgroup (T / 4 rows).
-  const int all_chunks = block_sum<int, kWaves>(chunks, sh.scan);
+  const int all_chunks = block_sum<int, (T / 64)>(chunks, s_scan);
   int g;
   if (kCoherent) {
     constexpr int kStepChunks = T / 256 > 0 ? T / 256 : 1;
@@ -297,46 +297,58 @@ __device__ __forceinline__ void decode_queue(const DecodeArgs &a, DecodeShared<T
     mine += n;
   }
   int total;
-  int run = block_excl_scan<int, kWaves>(mine, sh.scan, total);
+  int run = block_excl_scan<int, (T / 64)>(mine, s_scan, total);
 #pragma unroll
   for (int u = 0; u < kPer; ++u) {
-    sh.first[tid * kPer + u] = run;
+    s_first[tid * kPer + u] = run;
     run += cnt[u];
   }
-  if (tid == T - 1) sh.first[kMaxQueueHeads] = total;
+  if (tid == T - 1) s_first[kMaxQueueHeads] = total;
   __syncthreads();
   if (total == 0) return;
 
-  const int claim_base = kCoherent ? 0 : (int)gridDim.x;
-  int item;
   if (kCoherent) {
-    if (tid == 0) sh.item = __hip_atomic_fetch_add(a.queue_next, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    // every item is claimed from the counter, the next one before this one is attended (the counter's round trip
+    // hides behind the rows of a large workgroup's item)
+    if (tid == 0) *s_item = __hip_atomic_fetch_add(a.queue_next, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     __syncthreads();
-    item = sh.item;
+    int item = *s_item;
     __syncthreads();
-  } else {
-    item = blockIdx.x;
+#pragma unroll 1
+    while (item < total) {
+      int lo = 0, hi = kMaxQueueHeads;
+      while (hi - lo > 1) {
+        const int mid = (lo + hi) >> 1;
+        if (s_first[mid] <= item) lo = mid; else hi = mid;
+      }
+      const int head = a.head0 + lo, split = item - s_first[lo];
+      int next = total;
+      if (tid == 0) next = __hip_atomic_fetch_add(a.queue_next, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      decode_item<T, kGathered, true>(a, head, split, s_rows[lo], g, s_start, s_src, s_m, s_l, s_acc, s_last, tid, lane16, grp);
+      if (tid == 0) *s_item = next;
+      __syncthreads();  // also: LDS is reused by the next item
+      item = *s_item;
+      __syncthreads();
+    }
+    return;
   }
 #pragma unroll 1
-  while (item < total) {
-    // head that owns the item: the largest hh with first[hh] <= item (heads without items repeat the
-    // next head's value, so the largest such hh is the one with first[hh + 1] > item)
+  // the first item of a workgroup is its block index; further items are claimed from the counter
+  for (int item = blockIdx.x; item < total;) {
+    // head that owns the item: the largest hh with s_first[hh] <= item (heads without items repeat the
+    // next head's value, so the largest such hh is the one with s_first[hh + 1] > item)
     int lo = 0, hi = kMaxQueueHeads;
     while (hi - lo > 1) {
       const int mid = (lo + hi) >> 1;
-      if (sh.first[mid] <= item) lo = mid; else hi = mid;
+      if (s_first[mid] <= item) lo = mid; else hi = mid;
     }
-    const int head = a.head0 + lo, split = item - sh.first[lo];
-    // the next item is claimed before this one is attended: the counter's round trip hides behind the rows
-    const bool claims = kCoherent || total > (int)gridDim.x;  // otherwise every item had its workgroup
-    int next = total;
-    if (claims && tid == 0)
-      next = claim_base + __hip_atomic_fetch_add(a.queue_next, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    decode_item<T, kGathered, kCoherent>(a, head, split, sh.rows[lo], g, sh);
-    if (!claims) break;
-    if (tid == 0) sh.item = next;
+    const int head = a.head0 + lo, split = item - s_first[lo];
+    decode_item<T, kGathered, false>(a, head, split, s_rows[lo], g, s_start, s_src, s_m, s_l, s_acc, s_last, tid, lane16, grp);
+    if (total <= (int)gridDim.x) break;  // every item had its workgroup: nothing to claim
+    if (tid == 0)
+      *s_item = gridDim.x + __hip_atomic_fetch_add(a.queue_next, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     __syncthreads();  // also: LDS is reused by the next item
-    item = sh.item;
+    item = *s_item;
     __syncthreads();
   }
 }

@@ -1053,7 +1053,7 @@ struct QueueArgs {  // what the stage-3 queue needs beyond the selection's own a
 template <int E, bool kCount, int T>
 __global__ __launch_bounds__(T) void select_decode_kernel(SelectArgs a, QueueArgs qa) {
   __shared__ Shared<T> sh;
-  __shared__ DecodeShared<T> dsh;
+  DP_DECODE_LDS(T);
   __shared__ int s_go;
   int32_t *const planned = qa.planned;
   const int n_heads = qa.n_heads;
@@ -1102,7 +1102,7 @@ __global__ __launch_bounds__(T) void select_decode_kernel(SelectArgs a, QueueArg
   d.k_gather = d.v_gather = nullptr;
   d.rows_cap = 0;
   d.scale_log2 = a.scale_log2;
-  decode_queue<T, false, true>(d, dsh);
+  decode_queue<T, false, true>(d, DP_DECODE_LDS_ARGS);
 }
 
 // ---- plan from caller-given sets (staged API) -----------------------------

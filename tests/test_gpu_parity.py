@@ -728,6 +728,36 @@ def test_decode_attention_timed_stamps_the_three_kernels():
         hip.hipEventDestroy(e)
 
 
+def test_launch_count_and_stream_read_probe():
+    """Host-only launch count of the one-call entry point, and the loads-only measurement kernel (reads a buffer,
+    writes nothing, stamps its events)."""
+    import ctypes
+    import torch
+    import paper_2602_05191_amd as dp
+    small = dp.Problem(dp.DeviceCache.from_host(make_config(0)))
+    assert dp.dp_decode_attention_launches(small) == 2                      # 4 heads, 256 clusters: shared launch
+    sep = dp.Problem(small.dc, flags=dp.DP_FLAG_SEPARATE_DECODE_LAUNCH)
+    assert dp.dp_decode_attention_launches(sep) == 3
+    mid = make_cache(batch=1, n_kv_heads=2, n_q_heads=8, context=16000, mean_cluster=8, q_scale=1.0, seed=83)
+    assert dp.dp_decode_attention_launches(dp.Problem(dp.DeviceCache.from_host(mid))) == 3   # 2000 clusters per segment
+    buf = torch.arange(1 << 20, dtype=torch.int32, device="cuda:0")
+    before = buf.clone()
+    sink = torch.zeros(1, dtype=torch.int32, device="cuda:0")
+    hip = ctypes.CDLL("libamdhip64.so")
+    e0, e1 = ctypes.c_void_p(), ctypes.c_void_p()
+    assert hip.hipEventCreate(ctypes.byref(e0)) == 0 and hip.hipEventCreate(ctypes.byref(e1)) == 0
+    dp.dp_stream_read_probe(buf, sink)
+    dp.dp_stream_read_probe(buf[: 4 * 1000], None, None, e0, e1)           # a size that is no multiple of a tile
+    torch.cuda.synchronize()
+    ms = ctypes.c_float()
+    assert hip.hipEventElapsedTime(ctypes.byref(ms), e0, e1) == 0 and 0.0 < ms.value < 5.0
+    assert torch.equal(buf, before) and int(sink.item()) == 0
+    with pytest.raises(dp.DPError):
+        dp.dp_stream_read_probe(buf.view(torch.int8)[1:17])                 # not 16-byte aligned
+    hip.hipEventDestroy(e0)
+    hip.hipEventDestroy(e1)
+
+
 # ---------------------------------------------------------------------------
 # the entry points hold no state: two streams at once, and HIP graph capture
 # ---------------------------------------------------------------------------
