@@ -281,7 +281,7 @@ typedef struct {
 } dp_prefill;
 
 /* Host-only.  Device workspace dp_build_cluster_cache needs (per segment and
- * 1024-token block one int32 per cluster, plus 2 bytes per token); 0 for an
+ * 1024-token block one int32 per cluster, plus 6 bytes per token); 0 for an
  * invalid description. */
 size_t dp_build_workspace_bytes(const dp_prefill *in);
 
@@ -299,7 +299,8 @@ size_t dp_build_workspace_bytes(const dp_prefill *in);
  * to even); an empty cluster gets zero rows.  A token whose id is outside
  * [0, clusters of its segment) is left out of the cache.  Bitwise reproducible.
  * The outputs must not alias the inputs.  workspace: dp_build_workspace_bytes,
- * 256-byte aligned. */
+ * 256-byte aligned.  DP_ERR_UNSUPPORTED: head_dim != 128 or more than 65536
+ * clusters in a segment (in->max_clusters_per_seg). */
 dp_status dp_build_cluster_cache(const dp_prefill *in, void *k_cache, void *v_cache, int32_t *cluster_offsets,
                                  int32_t *cluster_sizes, void *k_centroids, void *v_centroids, float *v_sums,
                                  int32_t *token_row, void *workspace, size_t workspace_bytes, void *stream);

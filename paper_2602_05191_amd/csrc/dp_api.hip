@@ -495,10 +495,10 @@ static bool prefill_ok(const dp_prefill *in) {
 
 size_t dp_build_workspace_bytes(const dp_prefill *in) {
   if (!prefill_ok(in)) return 0;
-  size_t hist, rank;
+  size_t hist, rank, row_token;
   int nb;
-  dp::build_workspace_layout(in->n_seg, in->max_rows_per_seg, in->max_clusters_per_seg, &hist, &rank, &nb);
-  return hist + rank;
+  dp::build_workspace_layout(in->n_seg, in->max_rows_per_seg, in->max_clusters_per_seg, &hist, &rank, &row_token, &nb);
+  return hist + rank + row_token;
 }
 
 dp_status dp_build_cluster_cache(const dp_prefill *in, void *k_cache, void *v_cache, int32_t *cluster_offsets,
@@ -506,6 +506,8 @@ dp_status dp_build_cluster_cache(const dp_prefill *in, void *k_cache, void *v_ca
                                  int32_t *token_row, void *workspace, size_t workspace_bytes, void *stream) {
   if (!prefill_ok(in)) return DP_ERR_INVALID_ARG;
   if (in->head_dim != dp::kHeadDim) return DP_ERR_UNSUPPORTED;
+  // the per-block cluster counts of the sort live in LDS; the bound is the one the decode step has as well
+  if (in->max_clusters_per_seg > dp::kSelectMaxClusters) return DP_ERR_UNSUPPORTED;
   if (in->n_seg == 0) return DP_OK;
   if (!in->seg_row_base || !in->seg_rows || !in->seg_cluster_ptr) return DP_ERR_INVALID_ARG;
   if (in->max_rows_per_seg > 0 && (!in->k_tokens || !in->v_tokens || !in->assignment || !k_cache || !v_cache))

@@ -3,21 +3,26 @@
 // the cluster-contiguous K / V rows, per-cluster sizes and offsets, the key
 // centroids C_i (mean key) and the value aggregates V^Sigma_i and V-bar_i.
 //
-// A stable counting sort by cluster id, then a segmented mean.  HBM-bound: the
-// K / V rows are read once and written once by the scatter and read once more
-// (mostly from cache) by the mean.  Everything is deterministic: counts are
-// integers, a token's place inside its cluster is its token order, and the
-// means are fp64 sums taken in row order and rounded once to bf16.
+// A stable counting sort by cluster id with the segmented mean taken while the
+// rows move.  HBM-bound: every K / V row is read once (a 256 B run at its token's
+// place) and written once (clusters are written as contiguous runs); nothing
+// is read back.  Everything is deterministic: counts are integers, a token's
+// place inside its cluster is its token order, and the means are fp64 sums
+// taken in row order and rounded once to bf16.
 //
-//   rank     per 1024-token block: a token's rank among the EARLIER tokens of
-//            its block with the same id (pairwise compare against ids staged in
-//            LDS) and, by integer atomic max, the block's count per cluster
+//   rank     per 1024-token block: the block's count of every cluster (integer
+//            atomics on a table in LDS, written out as one row) and a token's
+//            rank among the EARLIER tokens of its block with the same id: 0 when
+//            the token is alone with its id in the block (the common case), else
+//            by pairwise compare among the tokens that are not
 //   scan     per cluster: exclusive prefix of those counts over the blocks
 //            (in place) and the cluster's size
 //   offsets  per segment: exclusive prefix of the sizes
-//   scatter  row of a token = offset of its cluster + count of its cluster in
-//            earlier blocks + rank; a 16-lane DPP row moves one 256 B row
-//   means    one 16-lane row per cluster walks the cluster's rows in order
+//   place    row of a token = offset of its cluster + count of its cluster in
+//            earlier blocks + rank; written per token (token_row) and, inverted,
+//            per row (the token that fills it)
+//   gather   one 16-lane row per cluster walks the cluster's rows in order:
+//            fetches each row's token, stores it in place and adds it to the sums
 #include "dp_device.hpp"
 #include "dp_kernels.hpp"
 
@@ -36,38 +41,40 @@ struct BuildArgs {
   float *v_sums;                                         // nullable
   int32_t *hist;                                         // [n_seg, n_blocks, max_kc]
   uint16_t *rank;                                        // [n_seg, n_blocks * kBuildBlock]
+  int32_t *row_token;                                    // [n_seg, max_rows]: segment-relative token of each cache row
   int32_t n_blocks, max_kc, max_rows;
 };
 
-__global__ void build_zero_kernel(int32_t *p, size_t n) {
-  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) p[i] = 0;
-}
-
 __global__ __launch_bounds__(kBuildBlock) void build_rank_kernel(BuildArgs a) {
-  __shared__ int s_id[kBuildBlock];
+  extern __shared__ uint32_t s_count[];  // two 16-bit counts per word: clusters 2 w and 2 w + 1 (a count is <= 1024)
+  __shared__ int s_id[kBuildBlock];      // ids of the tokens that share their cluster inside the block, in token order
+  __shared__ int s_scr[kBuildBlock / 64 + 1];
   const int seg = blockIdx.y, blk = blockIdx.x, tid = threadIdx.x;
   const int n = min(a.seg_rows[seg], a.max_rows);
   if (blk * kBuildBlock >= n) return;
   const int c0 = a.seg_cluster_ptr[seg], kc = min(a.seg_cluster_ptr[seg + 1] - c0, a.max_kc);
   const int t = blk * kBuildBlock + tid;
+  for (int w = tid; 2 * w < kc; w += kBuildBlock) s_count[w] = 0;
   int c = -1;
   if (t < n) {
     c = a.assignment[a.seg_row_base[seg] + t];
     if ((unsigned)c >= (unsigned)kc) c = -1;  // a token without a valid cluster is left out
   }
-  s_id[tid] = c;
+  __syncthreads();
+  if (c >= 0) atomicAdd(&s_count[c >> 1], 1u << (16 * (c & 1)));  // integer counts: any order gives the same table
+  __syncthreads();
+  int32_t *row = a.hist + ((size_t)seg * a.n_blocks + blk) * a.max_kc;
+  for (int i = tid; i < kc; i += kBuildBlock) row[i] = (int32_t)((s_count[i >> 1] >> (16 * (i & 1))) & 0xffffu);
+  const bool shared_id = c >= 0 && ((s_count[c >> 1] >> (16 * (c & 1))) & 0xffffu) > 1u;
+  int m;
+  const int pos = block_excl_scan<int, kBuildBlock / 64>(shared_id ? 1 : 0, s_scr, m);
+  if (shared_id) s_id[pos] = c;
   __syncthreads();
   if (c < 0) return;
-  // earlier tokens of the block with the same id; the bound is uniform in the wave
   int earlier = 0;
-  const int bound = (tid | 63) + 1;
-  for (int j = 0; j < bound; j += 4) {
-    const int4 v = *reinterpret_cast<const int4 *>(&s_id[j]);
-    earlier += (v.x == c && j < tid) + (v.y == c && j + 1 < tid) + (v.z == c && j + 2 < tid) + (v.w == c && j + 3 < tid);
-  }
+  if (shared_id)  // the list is in token order: the earlier tokens are its first pos entries
+    for (int j = 0; j < pos; ++j) earlier += s_id[j] == c;
   a.rank[((size_t)seg * a.n_blocks + blk) * kBuildBlock + tid] = (uint16_t)earlier;
-  // the block's count of cluster c = the largest rank + 1 (an integer maximum: order-independent)
-  atomicMax(&a.hist[((size_t)seg * a.n_blocks + blk) * a.max_kc + c], earlier + 1);
 }
 
 __global__ __launch_bounds__(256) void build_scan_kernel(BuildArgs a) {
@@ -111,47 +118,22 @@ __global__ __launch_bounds__(1024) void build_offsets_kernel(BuildArgs a) {
   }
 }
 
-__global__ __launch_bounds__(kBuildBlock) void build_scatter_kernel(BuildArgs a) {
-  __shared__ int s_dest[kBuildBlock];
-  const int seg = blockIdx.y, blk = blockIdx.x, tid = threadIdx.x;
+__global__ __launch_bounds__(256) void build_place_kernel(BuildArgs a) {
+  const int seg = blockIdx.y;
   const int n = min(a.seg_rows[seg], a.max_rows);
-  if (blk * kBuildBlock >= n) return;
+  const int t = blockIdx.x * 256 + threadIdx.x;
+  if (t >= n) return;
   const int c0 = a.seg_cluster_ptr[seg], kc = min(a.seg_cluster_ptr[seg + 1] - c0, a.max_kc);
   const int64_t r0 = a.seg_row_base[seg];
-  const int t = blk * kBuildBlock + tid;
+  const int blk = t / kBuildBlock;
+  const int c = a.assignment[r0 + t];
   int dest = -1;
-  if (t < n) {
-    const int c = a.assignment[r0 + t];
-    if ((unsigned)c < (unsigned)kc)
-      dest = a.cluster_offsets[c0 + c] + a.hist[((size_t)seg * a.n_blocks + blk) * a.max_kc + c] +
-             a.rank[((size_t)seg * a.n_blocks + blk) * kBuildBlock + tid];
-    if (a.token_row) a.token_row[r0 + t] = dest;
+  if ((unsigned)c < (unsigned)kc) {
+    dest = a.cluster_offsets[c0 + c] + a.hist[((size_t)seg * a.n_blocks + blk) * a.max_kc + c] +
+           a.rank[(size_t)seg * a.n_blocks * kBuildBlock + t];
+    a.row_token[(size_t)seg * a.max_rows + dest] = t;
   }
-  s_dest[tid] = dest;
-  __syncthreads();
-  // every 16-lane row moves one 256 B K row and one V row per step, 4 steps in flight
-  const int lane16 = tid & 15, grp = tid >> 4;
-  constexpr int kGroups = kBuildBlock / 16;
-  for (int i0 = grp; i0 < kBuildBlock; i0 += 4 * kGroups) {
-    uint4 kr[4], vr[4];
-    int d[4];
-#pragma unroll
-    for (int u = 0; u < 4; ++u) {
-      const int i = i0 + u * kGroups;
-      d[u] = s_dest[i];
-      if (d[u] >= 0) {
-        kr[u] = load_row_slice(a.k_tokens, r0 + blk * kBuildBlock + i, lane16);
-        vr[u] = load_row_slice(a.v_tokens, r0 + blk * kBuildBlock + i, lane16);
-      }
-    }
-#pragma unroll
-    for (int u = 0; u < 4; ++u) {
-      if (d[u] >= 0) {
-        *reinterpret_cast<uint4 *>(static_cast<char *>(a.k_cache) + (r0 + d[u]) * kRowBytes + lane16 * 16) = kr[u];
-        *reinterpret_cast<uint4 *>(static_cast<char *>(a.v_cache) + (r0 + d[u]) * kRowBytes + lane16 * 16) = vr[u];
-      }
-    }
-  }
+  if (a.token_row) a.token_row[r0 + t] = dest;
 }
 
 // double -> bf16 bits with ONE rounding to 8 significant bits, ties to even.  Values whose magnitude
@@ -168,39 +150,52 @@ __device__ __forceinline__ uint32_t f64_to_bf16_rne(double x) {
   return bits;
 }
 
-__global__ __launch_bounds__(256) void build_means_kernel(BuildArgs a) {
+__global__ __launch_bounds__(256) void build_gather_kernel(BuildArgs a) {
   const int seg = blockIdx.y;
   const int c0 = a.seg_cluster_ptr[seg], kc = a.seg_cluster_ptr[seg + 1] - c0;
   const int lane16 = threadIdx.x & 15, grp = threadIdx.x >> 4;
   const int ci = blockIdx.x * 16 + grp;
   if (ci >= kc) return;
   const int s = a.cluster_sizes[c0 + ci];
-  const int64_t row0 = a.seg_row_base[seg] + a.cluster_offsets[c0 + ci];
+  const int off = a.cluster_offsets[c0 + ci];
+  const int64_t r0 = a.seg_row_base[seg], row0 = r0 + off;
+  const int32_t *tok = a.row_token + (size_t)seg * a.max_rows + off;
   double ks[8], vs[8];
 #pragma unroll
   for (int i = 0; i < 8; ++i) ks[i] = vs[i] = 0.0;
   constexpr int kB = 4;  // rows in flight per 16-lane row
-  for (int r = 0; r < s; r += kB) {
-    uint4 kr[kB], vr[kB];
+  for (int rb = 0; rb < s; rb += 16) {
+    // the tokens of the next 16 rows of the cluster, one per lane of the 16-lane row
+    const int mine = rb + lane16 < s ? tok[rb + lane16] : 0;
+    const int nb = min(16, s - rb);
+    for (int r = 0; r < nb; r += kB) {
+      uint4 kr[kB], vr[kB];
 #pragma unroll
-    for (int u = 0; u < kB; ++u) {
-      if (r + u < s) {
-        kr[u] = load_row_slice(a.k_cache, row0 + r + u, lane16);
-        vr[u] = load_row_slice(a.v_cache, row0 + r + u, lane16);
-      } else {
-        kr[u] = make_uint4(0, 0, 0, 0);
-        vr[u] = make_uint4(0, 0, 0, 0);
+      for (int u = 0; u < kB; ++u) {
+        const int t = __shfl(mine, r + u, 16);
+        if (r + u < nb) {
+          kr[u] = load_row_slice(a.k_tokens, r0 + t, lane16);
+          vr[u] = load_row_slice(a.v_tokens, r0 + t, lane16);
+        } else {
+          kr[u] = make_uint4(0, 0, 0, 0);
+          vr[u] = make_uint4(0, 0, 0, 0);
+        }
       }
-    }
 #pragma unroll
-    for (int u = 0; u < kB; ++u) {  // rows beyond the cluster add +0.0: the sums are unchanged
-      float kf[8], vf[8];
-      unpack8(kr[u], kf);
-      unpack8(vr[u], vf);
+      for (int u = 0; u < kB; ++u) {  // rows beyond the cluster add +0.0: the sums are unchanged
+        if (r + u < nb) {
+          const int64_t row = row0 + rb + r + u;
+          *reinterpret_cast<uint4 *>(static_cast<char *>(a.k_cache) + row * kRowBytes + lane16 * 16) = kr[u];
+          *reinterpret_cast<uint4 *>(static_cast<char *>(a.v_cache) + row * kRowBytes + lane16 * 16) = vr[u];
+        }
+        float kf[8], vf[8];
+        unpack8(kr[u], kf);
+        unpack8(vr[u], vf);
 #pragma unroll
-      for (int i = 0; i < 8; ++i) {
-        ks[i] += (double)kf[i];
-        vs[i] += (double)vf[i];
+        for (int i = 0; i < 8; ++i) {
+          ks[i] += (double)kf[i];
+          vs[i] += (double)vf[i];
+        }
       }
     }
   }
@@ -210,10 +205,10 @@ __global__ __launch_bounds__(256) void build_means_kernel(BuildArgs a) {
     kb[i] = s > 0 ? f64_to_bf16_rne(ks[i] / (double)s) : 0u;
     vb[i] = s > 0 ? f64_to_bf16_rne(vs[i] / (double)s) : 0u;
   }
-  const size_t off = (size_t)(c0 + ci) * kRowBytes + lane16 * 16;
-  *reinterpret_cast<uint4 *>(static_cast<char *>(a.k_centroids) + off) =
+  const size_t o16 = (size_t)(c0 + ci) * kRowBytes + lane16 * 16;
+  *reinterpret_cast<uint4 *>(static_cast<char *>(a.k_centroids) + o16) =
       make_uint4(kb[0] | (kb[1] << 16), kb[2] | (kb[3] << 16), kb[4] | (kb[5] << 16), kb[6] | (kb[7] << 16));
-  *reinterpret_cast<uint4 *>(static_cast<char *>(a.v_centroids) + off) =
+  *reinterpret_cast<uint4 *>(static_cast<char *>(a.v_centroids) + o16) =
       make_uint4(vb[0] | (vb[1] << 16), vb[2] | (vb[3] << 16), vb[4] | (vb[5] << 16), vb[6] | (vb[7] << 16));
   if (a.v_sums) {
     float *o = a.v_sums + (size_t)(c0 + ci) * kHeadDim + lane16 * 8;
@@ -224,18 +219,20 @@ __global__ __launch_bounds__(256) void build_means_kernel(BuildArgs a) {
 
 }  // namespace
 
-void build_workspace_layout(int n_seg, int max_rows, int max_kc, size_t *hist_bytes, size_t *rank_bytes, int *n_blocks) {
+void build_workspace_layout(int n_seg, int max_rows, int max_kc, size_t *hist_bytes, size_t *rank_bytes,
+                            size_t *row_token_bytes, int *n_blocks) {
   const int nb = (max_rows + kBuildBlock - 1) / kBuildBlock;
   *n_blocks = nb;
   *hist_bytes = ((size_t)n_seg * nb * max_kc * sizeof(int32_t) + 255) / 256 * 256;
   *rank_bytes = ((size_t)n_seg * nb * kBuildBlock * sizeof(uint16_t) + 255) / 256 * 256;
+  *row_token_bytes = ((size_t)n_seg * max_rows * sizeof(int32_t) + 255) / 256 * 256;
 }
 
 hipError_t launch_build(const BuildProblem &p, void *workspace, hipStream_t s) {
   if (p.n_seg == 0) return hipSuccess;
-  size_t hist_bytes, rank_bytes;
+  size_t hist_bytes, rank_bytes, row_token_bytes;
   int n_blocks;
-  build_workspace_layout(p.n_seg, p.max_rows, p.max_kc, &hist_bytes, &rank_bytes, &n_blocks);
+  build_workspace_layout(p.n_seg, p.max_rows, p.max_kc, &hist_bytes, &rank_bytes, &row_token_bytes, &n_blocks);
   BuildArgs a;
   a.k_tokens = p.k_tokens;
   a.v_tokens = p.v_tokens;
@@ -253,22 +250,26 @@ hipError_t launch_build(const BuildProblem &p, void *workspace, hipStream_t s) {
   a.v_sums = p.v_sums;
   a.hist = static_cast<int32_t *>(workspace);
   a.rank = reinterpret_cast<uint16_t *>(static_cast<char *>(workspace) + hist_bytes);
+  a.row_token = reinterpret_cast<int32_t *>(static_cast<char *>(workspace) + hist_bytes + rank_bytes);
   a.n_blocks = n_blocks;
   a.max_kc = p.max_kc;
   a.max_rows = p.max_rows;
-  const size_t hist_n = (size_t)p.n_seg * n_blocks * p.max_kc;
-  if (hist_n > 0) {
-    const size_t want = (hist_n + 255) / 256;
-    hipLaunchKernelGGL(build_zero_kernel, dim3((unsigned)(want < 4096 ? want : 4096)), dim3(256), 0, s, a.hist, hist_n);
+  if (n_blocks > 0 && p.max_kc > 0) {
+    // the count table of a block lives in LDS: 2 bytes per cluster of the longest segment (128 KB at the 65536 limit)
+    const size_t lds = ((size_t)p.max_kc + 1) / 2 * sizeof(uint32_t);
+    if (lds > 32768) {
+      const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(build_rank_kernel),
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+      if (e != hipSuccess) return e;
+    }
+    hipLaunchKernelGGL(build_rank_kernel, dim3(n_blocks, p.n_seg), dim3(kBuildBlock), lds, s, a);
   }
-  if (n_blocks > 0 && p.max_kc > 0)
-    hipLaunchKernelGGL(build_rank_kernel, dim3(n_blocks, p.n_seg), dim3(kBuildBlock), 0, s, a);
   if (p.max_kc > 0)
     hipLaunchKernelGGL(build_scan_kernel, dim3((p.max_kc + 255) / 256, p.n_seg), dim3(256), 0, s, a);
   hipLaunchKernelGGL(build_offsets_kernel, dim3(p.n_seg), dim3(1024), 0, s, a);
   if (n_blocks > 0 && p.max_kc > 0)
-    hipLaunchKernelGGL(build_scatter_kernel, dim3(n_blocks, p.n_seg), dim3(kBuildBlock), 0, s, a);
-  if (p.max_kc > 0) hipLaunchKernelGGL(build_means_kernel, dim3((p.max_kc + 15) / 16, p.n_seg), dim3(256), 0, s, a);
+    hipLaunchKernelGGL(build_place_kernel, dim3((p.max_rows + 255) / 256, p.n_seg), dim3(256), 0, s, a);
+  if (p.max_kc > 0) hipLaunchKernelGGL(build_gather_kernel, dim3((p.max_kc + 15) / 16, p.n_seg), dim3(256), 0, s, a);
   return hipGetLastError();
 }
 

@@ -139,7 +139,8 @@ struct BuildProblem {
   int32_t *cluster_offsets, *cluster_sizes, *token_row;  // token_row nullable
   float *v_sums;                                         // nullable
 };
-void build_workspace_layout(int n_seg, int max_rows, int max_kc, size_t *hist_bytes, size_t *rank_bytes, int *n_blocks);
+void build_workspace_layout(int n_seg, int max_rows, int max_kc, size_t *hist_bytes, size_t *rank_bytes,
+                            size_t *row_token_bytes, int *n_blocks);
 hipError_t launch_build(const BuildProblem &p, void *workspace, hipStream_t s);
 
 // k-means assignment step: nearest centroid of every token (dp_kmeans.hip)

@@ -99,6 +99,7 @@ struct Shared {
   uint32_t cand_key[kMaxCand];
   int cand_idx[kMaxCand];
   u64 cand_m[kMaxCand];
+  u64 cand_ahead[kMaxCand];  // weight that precedes a candidate inside its bin, summed by slices of the block
   int ncand[2];
   int bin;
   u64 before;
@@ -111,6 +112,7 @@ struct Shared {
   u64 top_m[kTopMax];
   int ntop, f_nex, f_nap, f_ntok;
   int lite_sub[kLiteMaxTopSub];  // selection from the sub-tile summaries: the sub-tiles that may hold the top set
+  float lite_max;                // the head's max logit as the summaries give it (exact), for the general path
   // The refinement histogram of the (rare) crowded-bin search and the lists / merge buffers of the inline
   // attention never live at the same time: the lists are written once the search is over.
   union {
@@ -315,7 +317,8 @@ __device__ __forceinline__ void find_prefix(const float (&l)[E], const float *lg
   u64 before = sh.before;
   int cnt;
   bool done = false;
-  if (bin1 == cached_bin) {
+  const bool reused = bin1 == cached_bin;
+  if (reused) {
     cnt = cached_cnt;
     before = cached_before;
   } else {
@@ -329,6 +332,7 @@ __device__ __forceinline__ void find_prefix(const float (&l)[E], const float *lg
           sh.cand_key[s] = ordered_key(l[e]);
           sh.cand_idx[s] = base + e;
           sh.cand_m[s] = mass_of<kCount>(d);
+          sh.cand_ahead[s] = 0;
         }
       }
     }
@@ -355,6 +359,7 @@ __device__ __forceinline__ void find_prefix(const float (&l)[E], const float *lg
             sh.cand_key[s] = k;
             sh.cand_idx[s] = base + e;
             sh.cand_m[s] = mass_of<kCount>(mx - l[e]);
+            sh.cand_ahead[s] = 0;
           }
         }
         __syncthreads();
@@ -362,22 +367,34 @@ __device__ __forceinline__ void find_prefix(const float (&l)[E], const float *lg
     }
   }
   if (!done) {
-    // rank the members exactly on (key descending, index ascending)
-    if (tid < cnt) {
-      const uint32_t ki = sh.cand_key[tid];
-      const int ii = sh.cand_idx[tid];
-      const u64 mi = sh.cand_m[tid];
-      u64 ahead = before;
+    // Rank the members exactly on (key descending, index ascending).  The block is cut into slices of P threads
+    // (P = the power of two that holds the members): thread i of slice s adds up the weight of the members of the
+    // s-th part of the list that precede member i, and the slices' integer sums meet in sh.cand_ahead (any order
+    // gives the same bits).  A bin that is still gathered from the first threshold keeps its sums.
+    const int P = cnt <= 64 ? 64 : cnt <= 128 ? 128 : cnt <= 256 ? 256 : kMaxCand;
+    const int n_slices = T > P ? T / P : 1, slice = T > P ? tid / P : 0;
+    if (!reused) {
+      const int ja = slice * cnt / n_slices, jb = (slice + 1) * cnt / n_slices;
+      for (int i = tid & (P - 1); i < cnt; i += T) {
+        const uint32_t ki = sh.cand_key[i];
+        const int ii = sh.cand_idx[i];
+        u64 part = 0;
 #pragma unroll 4
-      for (int j = 0; j < cnt; ++j) {  // unconditional (broadcast) reads, four members in flight
-        const uint32_t kj = sh.cand_key[j];
-        const int ij = sh.cand_idx[j];
-        const u64 mj = sh.cand_m[j];
-        ahead += (kj > ki || (kj == ki && ij < ii)) ? mj : 0;
+        for (int j = ja; j < jb; ++j) {  // j is uniform in a wave: broadcast reads, four members in flight
+          const uint32_t kj = sh.cand_key[j];
+          const int ij = sh.cand_idx[j];
+          const u64 mj = sh.cand_m[j];
+          part += (kj > ki || (kj == ki && ij < ii)) ? mj : 0;
+        }
+        if (part) atomicAdd(&sh.cand_ahead[i], part);
       }
+      __syncthreads();
+    }
+    for (int i = tid; i < cnt; i += T) {
+      const u64 ahead = before + sh.cand_ahead[i], mi = sh.cand_m[i];
       if (ahead < tau && tau <= ahead + mi) {  // true for exactly one member
-        sh.res_key = ki;
-        sh.res_idx = ii;
+        sh.res_key = sh.cand_key[i];
+        sh.res_idx = sh.cand_idx[i];
         sh.res_mass = ahead + mi;
       }
     }
@@ -567,13 +584,13 @@ __device__ __forceinline__ bool lite_select(const SelectArgs &a, Shared<T> &sh, 
       // the sub-tiles that may hold a cluster within kTopCut of the max: slot k of the list goes to lanes 16 k .. + 15
       const bool top = live && M - sv[i].x < kTopCut;
       const u64 mask = __ballot(top);
-      const int pos = n_ts + __popcll(mask & ((1ull << tid) - 1));
+      const int pos = n_ts + (int)__builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0u));
       if (top && pos < kLiteMaxTopSub) sh.lite_sub[pos] = tid + 64 * i;
       n_ts += __popcll(mask);
     }
-    const u64 W = wave_sum((u64)((double)acc * 1099511627776.0));  // per lane <= 128 * 2^40: integer sums from here on
     bool ok = M > -INFINITY && n_ts <= kLiteMaxTopSub;  // no candidate at all, or a flat head: the general path
     if (ok) {
+      const u64 W = wave_sum((u64)((double)acc * 1099511627776.0));  // per lane <= 128 * 2^40: integer sums from here on
       __builtin_amdgcn_wave_barrier();  // the list was written by lanes of this wave
       my_sub = (tid >> 4) < n_ts ? sh.lite_sub[tid >> 4] : -1;
       const int i = my_sub * kSubTile + (tid & 15);
@@ -587,6 +604,7 @@ __device__ __forceinline__ bool lite_select(const SelectArgs &a, Shared<T> &sh, 
     } else if (tid == 0) {
       sh.f_nex = -1;
     }
+    if (tid == 0) sh.lite_max = M;
   }
   lds_barrier();
   if (sh.f_nex < 0) return false;
@@ -606,19 +624,24 @@ __device__ __forceinline__ void put_counts(const SelectOut &o, int head, int n_e
   if (o.n_exact_tokens_copy) o.n_exact_tokens_copy[head] = n_tokens;
 }
 
-// The selection proper for one head (one workgroup): fast path for a peaked head, general threshold search
-// otherwise; emits the lists (and the plan) and returns the three counts.  Returns false when the head had no
-// candidate at all and has been finished here (counts, zero output).
-template <int E, bool kCount, int T>
-__device__ __forceinline__ bool full_select(const SelectArgs &a, Shared<T> &sh, Emit &emit, int head, int c0, int kc,
-                                            const float *lg, bool plan, bool can_inline, int &n_ex, int &n_ap,
-                                            int &n_tok) {
-  constexpr int kBins = bins_of(T);
-  constexpr int kInlineRows = inline_rows_of(T);
-  const int tid = threadIdx.x;
-  const int base = tid * E;
-  // ---- load, max ---------------------------------------------------------
+// A thread's E consecutive logits of the head and, with few logits per thread (kPre), the sizes and offsets of the
+// same clusters next to them, so that no dependent load sits between the selection and the first K/V row.
+template <int E>
+struct HeadInputs {
+  static constexpr bool kPre = E <= 8;
+  static constexpr int EP = kPre ? E : 1;
   float l[E];
+  int psz[EP], poff[EP];
+};
+template <int E>
+__device__ __forceinline__ void load_head_inputs(const SelectArgs &a, int c0, int kc, const float *lg, bool plan,
+                                                 HeadInputs<E> &in) {
+  constexpr bool kPre = HeadInputs<E>::kPre;
+  constexpr int EP = HeadInputs<E>::EP;
+  const int base = threadIdx.x * E;
+  float(&l)[E] = in.l;
+  int(&psz)[EP] = in.psz;
+  int(&poff)[EP] = in.poff;
   if (E >= 4 && (reinterpret_cast<uintptr_t>(lg) & 15) == 0 && base + E <= kc) {
     // the thread's whole run lies inside the segment: all its 16-byte loads go out back to back
 #pragma unroll
@@ -633,11 +656,6 @@ __device__ __forceinline__ bool full_select(const SelectArgs &a, Shared<T> &sh, 
 #pragma unroll
     for (int e = 0; e < E; ++e) l[e] = (base + e < kc) ? lg[base + e] : -INFINITY;
   }
-  // With few logits per thread, sizes and offsets are fetched up front next to the logits, so that no
-  // dependent load sits between the selection and the first K/V row.
-  constexpr bool kPre = E <= 8;
-  constexpr int EP = kPre ? E : 1;
-  int psz[EP], poff[EP];
   if (kPre) {
     const int32_t *sp = a.cluster_sizes + c0 + base, *op = a.cluster_offsets + c0 + base;
     if (E >= 4 && ((reinterpret_cast<uintptr_t>(sp) | reinterpret_cast<uintptr_t>(op)) & 15) == 0 && base + E <= kc) {
@@ -658,6 +676,27 @@ __device__ __forceinline__ bool full_select(const SelectArgs &a, Shared<T> &sh, 
       }
     }
   }
+}
+
+// The selection proper for one head (one workgroup) on the thread's loaded inputs: fast path for a peaked head,
+// general threshold search otherwise; emits the lists (and the plan) and returns the three counts.  Returns false
+// when the head had no candidate at all and has been finished here (counts, zero output).  known_max: the head's max
+// logit if the caller has it already (NaN if not).  inline_limit: the most rows of this head that are worth
+// attending in this workgroup (a head that took the general path has used up its time: 64 rows, which four waves
+// attend in one round of loads; a longer list goes to the split decode).
+template <int E, bool kCount, int T>
+__device__ __forceinline__ bool full_select(const SelectArgs &a, Shared<T> &sh, Emit &emit, int head, int c0, int kc,
+                                            const float *lg, bool plan, bool can_inline, HeadInputs<E> &in,
+                                            float known_max, int &n_ex, int &n_ap, int &n_tok, int &inline_limit) {
+  constexpr int kBins = bins_of(T);
+  constexpr bool kPre = HeadInputs<E>::kPre;
+  constexpr int kGeneralInlineRows = 64;
+  const int tid = threadIdx.x;
+  const int base = tid * E;
+  float(&l)[E] = in.l;
+  int(&psz)[HeadInputs<E>::EP] = in.psz;
+  int(&poff)[HeadInputs<E>::EP] = in.poff;
+  inline_limit = inline_rows_of(T);
   // Pinned clusters (the caller's sink / window tokens): their logits leave the distribution here and
   // they join the exact list further down.  bit e of pinmask: element e is a pinned, non-empty cluster.
   u64 pinmask = 0, flagged = 0;  // flagged: every element that carries the flag, empty clusters included
@@ -689,7 +728,11 @@ __device__ __forceinline__ bool full_select(const SelectArgs &a, Shared<T> &sh, 
         l[e] = -INFINITY;
       }
   }
-  for (int i = tid; i < kBins; i += T) sh.hist[i] = 0;
+  // With the max known, the level-1 histogram has been cleared (and published) by the caller and is filled while the
+  // weights are summed (one evaluation of the masses instead of two).
+  const bool hist_early = !kCount && known_max == known_max;
+  if (!hist_early)
+    for (int i = tid; i < kBins; i += T) sh.hist[i] = 0;
   if (tid < 2) sh.ncand[tid] = 0;
   if (tid == 2) sh.ntop = 0;
   float tmax = -INFINITY;
@@ -698,7 +741,8 @@ __device__ __forceinline__ bool full_select(const SelectArgs &a, Shared<T> &sh, 
     l[e] += 0.0f;  // -0 becomes +0
     tmax = fmaxf(tmax, l[e]);
   }
-  const float mx_raw = block_max<(T / 64)>(tmax, sh.scrf);  // its barriers also publish the zeroed LDS
+  // (the barriers of the block max, or else the one of the weight sums below, also publish the zeroed LDS)
+  const float mx_raw = known_max == known_max ? known_max + 0.0f : block_max<(T / 64)>(tmax, sh.scrf);
   // no candidate cluster, or a budget of 0: the distribution selects nothing
   const bool nothing = mx_raw == -INFINITY || (kCount && a.k_retained <= 0);
   const float mx = mx_raw == -INFINITY ? 0.f : mx_raw;
@@ -740,6 +784,7 @@ __device__ __forceinline__ bool full_select(const SelectArgs &a, Shared<T> &sh, 
         ++ctop;
         wtop += m;
       }
+      if (hist_early && m) atomicAdd(&sh.hist[level1_bin(d, bs, kBins)], m);
     }
   }
   ctop += __popcll(pinmask);  // pinned clusters ride along in the top set
@@ -794,13 +839,15 @@ __device__ __forceinline__ bool full_select(const SelectArgs &a, Shared<T> &sh, 
     int idx1 = -1, idx2 = -1;
     if (!nothing) {
       // ---- general path: level-1 mass histogram, scan, threshold search ---------
+      if (!hist_early) {
 #pragma unroll
-      for (int e = 0; e < E; ++e) {
-        const float d = mx - l[e];
-        const u64 m = mass_of<kCount>(d);
-        if (m) atomicAdd(&sh.hist[level1_bin(d, bs, kBins)], m);
+        for (int e = 0; e < E; ++e) {
+          const float d = mx - l[e];
+          const u64 m = mass_of<kCount>(d);
+          if (m) atomicAdd(&sh.hist[level1_bin(d, bs, kBins)], m);
+        }
+        __syncthreads();
       }
-      __syncthreads();
       constexpr int B = kBins / T;  // consecutive bins per thread
       u64 hb[B], hsum = 0;
 #pragma unroll
@@ -876,7 +923,8 @@ __device__ __forceinline__ bool full_select(const SelectArgs &a, Shared<T> &sh, 
       pa = row16_sum(mine ? sa : 0) + ia - ca;
       pt = row16_sum(mine ? st : 0) + it - te;
     }
-    emit.to_lds = can_inline && n_tok + n_ap <= kInlineRows;
+    inline_limit = kGeneralInlineRows;
+    emit.to_lds = can_inline && n_tok + n_ap <= kGeneralInlineRows;
     emit.n_ex = n_ex;
     emit.n_tok = n_tok;
     if (ce + ca > 0) {
@@ -950,12 +998,26 @@ __device__ __forceinline__ int select_head(const SelectArgs &a, Shared<T> &sh, i
   if (!kGate && plan && tid == 0 && head % kMaxQueueHeads == 0) a.plan.queue_next[head / kMaxQueueHeads] = 0;
   const int64_t seg_row0 = can_inline ? a.seg_row_base[seg] : 0;  // needed last; its latency hides behind the selection
 
-  int n_ex = 0, n_ap = 0, n_tok = 0;
-  // a peaked head is selected from the scoring kernel's summaries; any other head by the search over all its logits
+  int n_ex = 0, n_ap = 0, n_tok = 0, inline_limit = kInlineRows;
+  // A peaked head is selected from the scoring kernel's summaries by the first wave; any other head by the search
+  // over all its logits.  (Fetching the logits in the other waves while the first one tries was measured: their
+  // loads queue in front of the first wave's own on the same CU and cost a peaked head 1.8 us.)
+  const bool try_lite = !kCount && a.summaries && !a.cluster_flags && a.p1 < 1.0f && kc > 0 &&
+                        kc <= kLiteSubPerLane * 64 * kSubTile;
   bool chosen = false;
-  if (!kCount && a.summaries && !a.cluster_flags && a.p1 < 1.0f && kc > 0 && kc <= kLiteSubPerLane * 64 * kSubTile)
+  float known_max = __builtin_nanf("");
+  if (try_lite) {
     chosen = lite_select<T>(a, sh, emit, c0, kc, lg, plan, can_inline, n_ex, n_ap, n_tok);
-  if (!chosen && !full_select<E, kCount, T>(a, sh, emit, head, c0, kc, lg, plan, can_inline, n_ex, n_ap, n_tok)) {
+    if (!chosen) {  // the general path knows the max: it fills its histogram while it sums the weights
+      known_max = sh.lite_max;
+      for (int i = tid; i < bins_of(T); i += T) sh.hist[i] = 0;
+      __syncthreads();
+    }
+  }
+  HeadInputs<E> in;
+  if (!chosen) load_head_inputs<E>(a, c0, kc, lg, plan, in);
+  if (!chosen && !full_select<E, kCount, T>(a, sh, emit, head, c0, kc, lg, plan, can_inline, in, known_max, n_ex, n_ap,
+                                            n_tok, inline_limit)) {
     // no candidate: finished inside (zero output, zero counts)
     if (kGate) {
       __builtin_amdgcn_s_waitcnt(0);
@@ -966,7 +1028,7 @@ __device__ __forceinline__ int select_head(const SelectArgs &a, Shared<T> &sh, i
   }
 
   const int R = n_tok + n_ap;
-  const bool inline_attn = can_inline && R <= kInlineRows;
+  const bool inline_attn = can_inline && R <= inline_limit;
   if (tid == 0) {
     // a head that is attended here leaves nothing for the queue to read: its stores stay plain
     put_counts(a.out, head, n_ex, n_ex + n_ap, n_tok, kGate && !inline_attn);

@@ -74,6 +74,9 @@ CASES = {
                                      size_dist="ones", size_lo=1, size_hi=1, q_scale=1.0, seed=64),
     "many_clusters": lambda: make_cache(batch=1, n_kv_heads=1, n_q_heads=1, context=27000, mean_cluster=3, size_hi=8,
                                         q_scale=1.0, seed=65),
+    # more than 16384 clusters in a segment: the per-block count table needs more LDS than a kernel gets by default
+    "singletons_20k": lambda: make_cache(batch=1, n_kv_heads=1, n_q_heads=1, context=20000, n_clusters=20000,
+                                         size_dist="ones", size_lo=1, size_hi=1, q_scale=1.0, seed=66),
     "cfg1_quarter": lambda: make_config(1, shrink=4),
 }
 
