@@ -428,7 +428,7 @@ def main():
     b_off, b_sz = torch.empty_like(base.cluster_offsets), torch.empty_like(base.cluster_sizes)
     b_kc, b_vc = torch.empty_like(base.k_centroids), torch.empty_like(base.v_centroids)
     build_us = wall_time(lambda i: dp.dp_build_cluster_cache(pf, b_k, b_v, b_off, b_sz, b_kc, b_vc, bws), 20)
-    build_bytes = int(tok.k_tokens.shape[0]) * (3 * 512 + 4)   # K+V rows read, written, read again for the means; ids
+    build_bytes = int(tok.k_tokens.shape[0]) * (2 * 512 + 4)   # K+V rows read once and written once (the means are taken on the way); ids
     # the assignment step of the clustering itself (one Lloyd iteration = this + the build): a dense
     # tokens x centroids x 128 contraction on the matrix cores
     kws = torch.empty(max(dp.dp_kmeans_workspace_bytes(pf), 256), dtype=torch.uint8, device=dev)
@@ -436,7 +436,12 @@ def main():
     kmeans_us = wall_time(lambda i: dp.dp_kmeans_assign(pf, base.k_centroids, k_asg, kws), 5)
     kmeans_flops = 2.0 * cache.head_dim * float(
         (tok.seg_rows.astype(np.int64) * np.diff(tok.seg_cluster_ptr).astype(np.int64)).sum())
-    del tok, pf, bws, kws, k_asg, b_k, b_v, b_off, b_sz, b_kc, b_vc
+    # the clustering as a procedure: Lloyd rounds on the device from a strided start (assignment + means of the keys)
+    fws = torch.empty(max(dp.dp_kmeans_fit_workspace_bytes(pf), 256), dtype=torch.uint8, device=dev)
+    f_cent = torch.empty_like(base.k_centroids)
+    fit_rounds = 2
+    fit_us = wall_time(lambda i: dp.dp_kmeans_fit(pf, f_cent, fit_rounds, dp.DP_KMEANS_INIT_STRIDED, k_asg, fws), 3)
+    del tok, pf, bws, kws, fws, f_cent, k_asg, b_k, b_v, b_off, b_sz, b_kc, b_vc
 
     # the kernel that moves the bytes: centroid scoring reads every key centroid and size once and
     # writes G logits per cluster
@@ -588,6 +593,8 @@ def main():
         "kmeans_assign": {"entry_point": "dp_kmeans_assign", "us": round(kmeans_us, 1), "flops": kmeans_flops,
                           "TFLOPs": round(kmeans_flops / (kmeans_us * 1e-6) / 1e12, 1),
                           "frac_of_bf16_mfma_peak": round(kmeans_flops / (kmeans_us * 1e-6) / 2.5e15, 4)},
+        "kmeans_fit": {"entry_point": "dp_kmeans_fit", "rounds": fit_rounds, "init": "strided",
+                       "us_per_round": round(fit_us / fit_rounds, 1)},
         "gen_seconds": round(t_gen, 1),
     }
 

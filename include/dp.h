@@ -323,6 +323,35 @@ size_t dp_kmeans_workspace_bytes(const dp_prefill *in);
 dp_status dp_kmeans_assign(const dp_prefill *in, const void *centroids, int32_t *assignment, float *best_score,
                            void *workspace, size_t workspace_bytes, void *stream);
 
+/* k-means over the key vectors of every segment as a procedure (Sec. 4.1 names
+ * k-means and fixes neither the initial centroids, nor the number of iterations,
+ * nor the fate of a cluster that loses its tokens; the choices below are this
+ * library's).  Lloyd's iteration, n_iters rounds on the device, no host
+ * synchronisation:
+ *   assignment  dp_kmeans_assign's rule on the current centroids;
+ *   update      centroid = mean key of the cluster's tokens (fp64 sums in token
+ *               order, rounded once to bf16, as dp_build_cluster_cache does); a
+ *               cluster without tokens keeps its centroid.
+ * init: DP_KMEANS_INIT_GIVEN     centroids holds the initial centroids;
+ *       DP_KMEANS_INIT_STRIDED   centroid c of a segment with n tokens and kc
+ *                                clusters starts as the key of token
+ *                                floor(c * n / kc) (a zero row if n == 0).
+ *   centroids   bf16 [total_clusters, head_dim] (device, read and written): on
+ *               return, the centroids after the last update
+ *   assignment  int32 [total_rows] (device, written; may be null if n_iters == 0):
+ *               the last round's assignment, made with the centroids BEFORE that
+ *               round's update.  dp_build_cluster_cache on it gives a cache whose
+ *               key centroids equal `centroids` for every non-empty cluster.
+ *   best_score  fp32 [total_rows], nullable: as dp_kmeans_assign, last round
+ * in->v_tokens and in->assignment are not read.  n_iters == 0 only initialises.
+ * workspace: dp_kmeans_fit_workspace_bytes, 256-byte aligned.  Errors as the two
+ * steps'; DP_ERR_INVALID_ARG also for n_iters < 0 or an unknown init. */
+#define DP_KMEANS_INIT_GIVEN 0u
+#define DP_KMEANS_INIT_STRIDED 1u
+size_t dp_kmeans_fit_workspace_bytes(const dp_prefill *in);
+dp_status dp_kmeans_fit(const dp_prefill *in, void *centroids, int32_t n_iters, uint32_t init, int32_t *assignment,
+                        float *best_score, void *workspace, size_t workspace_bytes, void *stream);
+
 /* Where dp_decode_attention keeps its intermediate results inside the
  * workspace (byte offsets; host-only, for inspection by tests and tools):
  * logits as in dp_score_centroids, sel_ids as in dp_topp_select. */

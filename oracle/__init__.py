@@ -370,3 +370,37 @@ def kmeans_assign(tokens, centroids: np.ndarray):
     lib.dpo_kmeans_assign(len(rows), int(t.head_dim), _ptr(k), _ptr(c), _ptr(base), _ptr(rows), _ptr(ptr), _ptr(asg),
                           _ptr(best), _ptr(second))
     return asg[:n_rows], best[:n_rows], second[:n_rows]
+
+
+KMEANS_INIT_GIVEN, KMEANS_INIT_STRIDED = 0, 1
+
+
+def kmeans_fit(tokens, centroids, n_iters: int, init: int = KMEANS_INIT_GIVEN):
+    """k-means over the keys of every segment as a procedure (Sec. 4.1 names k-means; initial centroids, iteration
+    count and the fate of an emptied cluster are this build's reading): Lloyd's iteration, n_iters rounds of
+    kmeans_assign on the current centroids followed by centroid = mean key of the cluster (build_cluster_cache's
+    means: fp64 sums in token order, one rounding to bf16); a cluster without tokens keeps its centroid.
+    init STRIDED: centroid c of a segment with n tokens and kc clusters starts as the key of token floor(c n / kc)
+    (a zero row if n == 0); GIVEN: `centroids` (uint16 bf16 bits [total_clusters, d]).
+    -> (centroids after the last update, assignment of the last round or None if n_iters == 0)"""
+    import copy
+    t = copy.copy(tokens)
+    n_cl, d = int(t.seg_cluster_ptr[-1]), int(t.head_dim)
+    if init == KMEANS_INIT_STRIDED:
+        cent = np.zeros((n_cl, d), np.uint16)
+        for seg in range(t.n_seg):
+            a, e = int(t.seg_cluster_ptr[seg]), int(t.seg_cluster_ptr[seg + 1])
+            n, r0 = int(t.seg_rows[seg]), int(t.seg_row_base[seg])
+            for c in range(e - a):
+                if n > 0:
+                    cent[a + c] = t.k_tokens[r0 + (c * n) // (e - a)]
+    else:
+        cent = np.array(centroids, dtype=np.uint16, copy=True)
+    asg = None
+    for _ in range(n_iters):
+        asg, _best, _second = kmeans_assign(t, cent)
+        t.assignment = asg
+        means = build_cluster_cache(t)
+        keep = means["cluster_sizes"] > 0
+        cent = np.where(keep[:, None], means["k_centroids"], cent)
+    return cent, asg

@@ -28,7 +28,7 @@ EXPORTS = ["dp_workspace_bytes", "dp_logits_count", "dp_get_workspace_layout", "
            "dp_topp_select", "dp_topp_select_sorted", "dp_topk_select", "dp_sparse_decode", "dp_sparse_decode_gathered", "dp_decode_attention",
            "dp_group_union_decode_attention",
            "dp_decode_attention_timed", "dp_budget_decode_attention", "dp_dense_decode", "dp_build_workspace_bytes", "dp_build_cluster_cache", "dp_kmeans_workspace_bytes",
-           "dp_kmeans_assign",
+           "dp_kmeans_assign", "dp_kmeans_fit_workspace_bytes", "dp_kmeans_fit",
            "dp_decode_attention_static", "dp_stream_read_probe", "dp_decode_attention_launches",
            "dp_status_string"]
 
@@ -120,6 +120,10 @@ def load_library():
     L.dp_kmeans_workspace_bytes.argtypes = [C.POINTER(_Prefill)]
     L.dp_kmeans_assign.restype = I
     L.dp_kmeans_assign.argtypes = [C.POINTER(_Prefill), V, V, V, V, C.c_size_t, V]
+    L.dp_kmeans_fit_workspace_bytes.restype = C.c_size_t
+    L.dp_kmeans_fit_workspace_bytes.argtypes = [C.POINTER(_Prefill)]
+    L.dp_kmeans_fit.restype = I
+    L.dp_kmeans_fit.argtypes = [C.POINTER(_Prefill), V, C.c_int32, C.c_uint32, V, V, V, C.c_size_t, V]
     L.dp_decode_attention_launches.restype = C.c_int32
     L.dp_decode_attention_launches.argtypes = [PP]
     L.dp_stream_read_probe.restype = I
@@ -447,3 +451,24 @@ def dp_kmeans_assign(prefill: Prefill, centroids: torch.Tensor, assignment: torc
                                            _ptr(workspace), workspace.numel() * workspace.element_size(),
                                            _stream(stream)),
            "dp_kmeans_assign")
+
+
+DP_KMEANS_INIT_GIVEN = 0
+DP_KMEANS_INIT_STRIDED = 1
+
+
+def dp_kmeans_fit_workspace_bytes(prefill: Prefill) -> int:
+    return int(load_library().dp_kmeans_fit_workspace_bytes(prefill.ref))
+
+
+def dp_kmeans_fit(prefill: Prefill, centroids: torch.Tensor, n_iters: int, init: int, assignment: Optional[torch.Tensor],
+                  workspace: torch.Tensor, best_score: Optional[torch.Tensor] = None, stream=None) -> None:
+    assert centroids.is_contiguous() and centroids.element_size() == 2
+    assert centroids.numel() >= prefill.total_clusters * prefill.c.head_dim
+    assert assignment is None or (assignment.dtype == torch.int32 and assignment.is_contiguous() and
+                                  assignment.numel() >= prefill.total_rows)
+    assert best_score is None or (best_score.dtype == torch.float32 and best_score.numel() >= prefill.total_rows)
+    _check(load_library().dp_kmeans_fit(prefill.ref, _ptr(centroids), int(n_iters), int(init), _ptr(assignment),
+                                        _ptr(best_score), _ptr(workspace),
+                                        workspace.numel() * workspace.element_size(), _stream(stream)),
+           "dp_kmeans_fit")

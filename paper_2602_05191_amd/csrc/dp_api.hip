@@ -570,6 +570,68 @@ dp_status dp_kmeans_assign(const dp_prefill *in, const void *centroids, int32_t 
              : DP_ERR_HIP;
 }
 
+size_t dp_kmeans_fit_workspace_bytes(const dp_prefill *in) {
+  if (!prefill_ok(in)) return 0;
+  const size_t step = dp_kmeans_workspace_bytes(in) > dp_build_workspace_bytes(in) ? dp_kmeans_workspace_bytes(in)
+                                                                                    : dp_build_workspace_bytes(in);
+  return step + 2 * align_up(sizeof(int32_t) * (size_t)in->total_clusters, 256);
+}
+
+// Lloyd's iteration on one stream: assignment (matrix cores), then the means of the keys per cluster through the
+// kernels of the cache build with nothing moved (stable counting sort of the tokens, fp64 sums in token order).
+dp_status dp_kmeans_fit(const dp_prefill *in, void *centroids, int32_t n_iters, uint32_t init, int32_t *assignment,
+                        float *best_score, void *workspace, size_t workspace_bytes, void *stream) {
+  if (!prefill_ok(in) || n_iters < 0 || (init != DP_KMEANS_INIT_GIVEN && init != DP_KMEANS_INIT_STRIDED))
+    return DP_ERR_INVALID_ARG;
+  if (in->head_dim != dp::kHeadDim || in->max_clusters_per_seg > dp::kSelectMaxClusters) return DP_ERR_UNSUPPORTED;
+  if (in->n_seg == 0) return DP_OK;
+  if (!in->seg_row_base || !in->seg_rows || !in->seg_cluster_ptr) return DP_ERR_INVALID_ARG;
+  if (in->max_rows_per_seg > 0 && (!in->k_tokens || (n_iters > 0 && !assignment))) return DP_ERR_INVALID_ARG;
+  if (in->total_clusters > 0 && !centroids) return DP_ERR_INVALID_ARG;
+  const size_t need = dp_kmeans_fit_workspace_bytes(in);
+  if (workspace_bytes < need) return DP_ERR_WORKSPACE_TOO_SMALL;
+  if (need > 0 && (!workspace || reinterpret_cast<uintptr_t>(workspace) % 256)) return DP_ERR_INVALID_ARG;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  const size_t counts = align_up(sizeof(int32_t) * (size_t)in->total_clusters, 256);
+  char *ws = static_cast<char *>(workspace);
+  int32_t *sizes = reinterpret_cast<int32_t *>(ws + need - 2 * counts);
+  int32_t *offsets = reinterpret_cast<int32_t *>(ws + need - counts);
+
+  dp::KmeansProblem k;
+  k.n_seg = in->n_seg;
+  k.k_tokens = in->k_tokens;
+  k.centroids = centroids;
+  k.seg_row_base = in->seg_row_base;
+  k.seg_rows = in->seg_rows;
+  k.seg_cluster_ptr = in->seg_cluster_ptr;
+  k.max_rows = in->max_rows_per_seg;
+  k.total_clusters = in->total_clusters;
+  k.assignment = assignment;
+  k.best_score = best_score;
+  if (init == DP_KMEANS_INIT_STRIDED &&
+      dp::launch_kmeans_init_strided(k, centroids, in->max_clusters_per_seg, s) != hipSuccess)
+    return DP_ERR_HIP;
+
+  dp::BuildProblem b{};
+  b.n_seg = in->n_seg;
+  b.k_tokens = in->k_tokens;
+  b.assignment = assignment;
+  b.seg_row_base = in->seg_row_base;
+  b.seg_rows = in->seg_rows;
+  b.seg_cluster_ptr = in->seg_cluster_ptr;
+  b.max_kc = in->max_clusters_per_seg;
+  b.max_rows = in->max_rows_per_seg;
+  b.k_centroids = centroids;  // cache pointers null: keys only, nothing moved
+  b.cluster_offsets = offsets;
+  b.cluster_sizes = sizes;
+  if (in->max_rows_per_seg == 0) return DP_OK;  // no tokens anywhere: nothing to assign, every centroid stays
+  for (int it = 0; it < n_iters; ++it) {
+    if (dp::launch_kmeans_assign(k, reinterpret_cast<float *>(ws), s) != hipSuccess) return DP_ERR_HIP;
+    if (dp::launch_build(b, ws, s) != hipSuccess) return DP_ERR_HIP;
+  }
+  return DP_OK;
+}
+
 const char *dp_status_string(dp_status status) {
   switch (status) {
     case DP_OK: return "DP_OK";

@@ -23,6 +23,8 @@
 //            per row (the token that fills it)
 //   gather   one 16-lane row per cluster walks the cluster's rows in order:
 //            fetches each row's token, stores it in place and adds it to the sums
+// The update step of k-means (mean key of every cluster, nothing moved) is the same
+// sequence with the cache pointers left null.
 #include "dp_device.hpp"
 #include "dp_kernels.hpp"
 
@@ -150,6 +152,10 @@ __device__ __forceinline__ uint32_t f64_to_bf16_rne(double x) {
   return bits;
 }
 
+// kMove = false: keys only (the update step of k-means): nothing is moved, no value is read, a cluster without
+// tokens keeps the centroid it has, and four times as many key rows are in flight (a cluster's rows are summed in
+// order by one 16-lane row, so a very large cluster is a chain of dependent rounds of loads).
+template <bool kMove>
 __global__ __launch_bounds__(256) void build_gather_kernel(BuildArgs a) {
   const int seg = blockIdx.y;
   const int c0 = a.seg_cluster_ptr[seg], kc = a.seg_cluster_ptr[seg + 1] - c0;
@@ -160,10 +166,12 @@ __global__ __launch_bounds__(256) void build_gather_kernel(BuildArgs a) {
   const int off = a.cluster_offsets[c0 + ci];
   const int64_t r0 = a.seg_row_base[seg], row0 = r0 + off;
   const int32_t *tok = a.row_token + (size_t)seg * a.max_rows + off;
+  constexpr bool move = kMove;
+  if (!move && s == 0) return;
   double ks[8], vs[8];
 #pragma unroll
   for (int i = 0; i < 8; ++i) ks[i] = vs[i] = 0.0;
-  constexpr int kB = 4;  // rows in flight per 16-lane row
+  constexpr int kB = kMove ? 4 : 16;  // rows in flight per 16-lane row
   for (int rb = 0; rb < s; rb += 16) {
     // the tokens of the next 16 rows of the cluster, one per lane of the 16-lane row
     const int mine = rb + lane16 < s ? tok[rb + lane16] : 0;
@@ -173,17 +181,16 @@ __global__ __launch_bounds__(256) void build_gather_kernel(BuildArgs a) {
 #pragma unroll
       for (int u = 0; u < kB; ++u) {
         const int t = __shfl(mine, r + u, 16);
+        kr[u] = make_uint4(0, 0, 0, 0);
+        vr[u] = make_uint4(0, 0, 0, 0);
         if (r + u < nb) {
           kr[u] = load_row_slice(a.k_tokens, r0 + t, lane16);
-          vr[u] = load_row_slice(a.v_tokens, r0 + t, lane16);
-        } else {
-          kr[u] = make_uint4(0, 0, 0, 0);
-          vr[u] = make_uint4(0, 0, 0, 0);
+          if (move) vr[u] = load_row_slice(a.v_tokens, r0 + t, lane16);
         }
       }
 #pragma unroll
       for (int u = 0; u < kB; ++u) {  // rows beyond the cluster add +0.0: the sums are unchanged
-        if (r + u < nb) {
+        if (move && r + u < nb) {
           const int64_t row = row0 + rb + r + u;
           *reinterpret_cast<uint4 *>(static_cast<char *>(a.k_cache) + row * kRowBytes + lane16 * 16) = kr[u];
           *reinterpret_cast<uint4 *>(static_cast<char *>(a.v_cache) + row * kRowBytes + lane16 * 16) = vr[u];
@@ -208,6 +215,7 @@ __global__ __launch_bounds__(256) void build_gather_kernel(BuildArgs a) {
   const size_t o16 = (size_t)(c0 + ci) * kRowBytes + lane16 * 16;
   *reinterpret_cast<uint4 *>(static_cast<char *>(a.k_centroids) + o16) =
       make_uint4(kb[0] | (kb[1] << 16), kb[2] | (kb[3] << 16), kb[4] | (kb[5] << 16), kb[6] | (kb[7] << 16));
+  if (!move) return;
   *reinterpret_cast<uint4 *>(static_cast<char *>(a.v_centroids) + o16) =
       make_uint4(vb[0] | (vb[1] << 16), vb[2] | (vb[3] << 16), vb[4] | (vb[5] << 16), vb[6] | (vb[7] << 16));
   if (a.v_sums) {
@@ -269,7 +277,11 @@ hipError_t launch_build(const BuildProblem &p, void *workspace, hipStream_t s) {
   hipLaunchKernelGGL(build_offsets_kernel, dim3(p.n_seg), dim3(1024), 0, s, a);
   if (n_blocks > 0 && p.max_kc > 0)
     hipLaunchKernelGGL(build_place_kernel, dim3((p.max_rows + 255) / 256, p.n_seg), dim3(256), 0, s, a);
-  if (p.max_kc > 0) hipLaunchKernelGGL(build_gather_kernel, dim3((p.max_kc + 15) / 16, p.n_seg), dim3(256), 0, s, a);
+  if (p.max_kc > 0) {
+    const dim3 grid((p.max_kc + 15) / 16, p.n_seg);
+    if (p.k_cache) hipLaunchKernelGGL(build_gather_kernel<true>, grid, dim3(256), 0, s, a);
+    else hipLaunchKernelGGL(build_gather_kernel<false>, grid, dim3(256), 0, s, a);
+  }
   return hipGetLastError();
 }
 

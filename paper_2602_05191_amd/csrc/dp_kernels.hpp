@@ -154,6 +154,8 @@ struct KmeansProblem {
   float *best_score;  // nullable
 };
 hipError_t launch_kmeans_assign(const KmeansProblem &p, float *half_norm, hipStream_t s);
+// centroids[c] of a segment with n tokens and kc clusters = the key of token floor(c * n / kc) (zero if n == 0)
+hipError_t launch_kmeans_init_strided(const KmeansProblem &p, void *centroids, int max_kc, hipStream_t s);
 
 // largest max_clusters_per_seg the selection kernel supports
 constexpr int kSelectMaxClusters = 65536;

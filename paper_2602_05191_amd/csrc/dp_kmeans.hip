@@ -222,7 +222,31 @@ __global__ __launch_bounds__(kKmThreads) __attribute__((amdgpu_waves_per_eu(3, 3
     }
 }
 
+// One 16-lane row copies one key row: centroid c of the segment starts as the key of token floor(c * n / kc).
+__global__ __launch_bounds__(256) void km_init_strided_kernel(KmArgs a, void *centroids) {
+  const int seg = blockIdx.y;
+  const int c0 = a.seg_cluster_ptr[seg], kc = a.seg_cluster_ptr[seg + 1] - c0;
+  const int lane16 = threadIdx.x & 15, c = blockIdx.x * 16 + (threadIdx.x >> 4);
+  if (c >= kc) return;
+  const int n = min(a.seg_rows[seg], a.max_rows);
+  uint4 row = make_uint4(0, 0, 0, 0);
+  if (n > 0) row = load_row_slice(a.k_tokens, a.seg_row_base[seg] + (int64_t)c * n / kc, lane16);
+  *reinterpret_cast<uint4 *>(static_cast<char *>(centroids) + (size_t)(c0 + c) * kRowBytes + lane16 * 16) = row;
+}
+
 }  // namespace
+
+hipError_t launch_kmeans_init_strided(const KmeansProblem &p, void *centroids, int max_kc, hipStream_t s) {
+  if (p.n_seg == 0 || max_kc == 0) return hipSuccess;
+  KmArgs a{};
+  a.k_tokens = p.k_tokens;
+  a.seg_row_base = p.seg_row_base;
+  a.seg_rows = p.seg_rows;
+  a.seg_cluster_ptr = p.seg_cluster_ptr;
+  a.max_rows = p.max_rows;
+  hipLaunchKernelGGL(km_init_strided_kernel, dim3((max_kc + 15) / 16, p.n_seg), dim3(256), 0, s, a, centroids);
+  return hipGetLastError();
+}
 
 hipError_t launch_kmeans_assign(const KmeansProblem &p, float *half_norm, hipStream_t s) {
   if (p.n_seg == 0 || p.max_rows == 0) return hipSuccess;

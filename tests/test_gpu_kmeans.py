@@ -138,3 +138,107 @@ def test_lloyd_iterations_on_the_gpu_do_not_increase_the_objective():
         dp.dp_build_cluster_cache(pf, kb, vb, off, sz, kc_, vc_, ws)
         cent = torch.where((sz > 0)[:, None], kc_, cent)     # an empty cluster keeps its old centroid
     assert obj < 0.9 * x2
+
+
+# --------------------------------------------------------------------------
+# k-means as a procedure (dp_kmeans_fit): Lloyd's rounds on the device
+# --------------------------------------------------------------------------
+def gpu_fit(t, centroids, n_iters, init):
+    import torch
+    import paper_2602_05191_amd as dp
+    dev = "cuda:0"
+    up = lambda a, dt: torch.from_numpy(np.ascontiguousarray(a).view(dt)).to(dev)
+    n_rows, n_cl = int(t.k_tokens.shape[0]), int(t.seg_cluster_ptr[-1])
+    pf = dp.Prefill(up(t.k_tokens, np.int16), up(t.v_tokens, np.int16), up(t.assignment, np.int32),
+                    up(t.seg_row_base, np.int64), up(t.seg_rows, np.int32), up(t.seg_cluster_ptr, np.int32),
+                    n_cl, int(np.diff(t.seg_cluster_ptr).max()), int(t.seg_rows.max()))
+    ws = torch.full((max(dp.dp_kmeans_fit_workspace_bytes(pf), 256),), 0x5A, dtype=torch.uint8, device=dev)
+    cent = up(centroids, np.int16) if centroids is not None else \
+        torch.full((max(n_cl, 1), t.head_dim), 0x7FC0, dtype=torch.int16, device=dev)
+    asg = torch.full((max(n_rows, 1),), -7, dtype=torch.int32, device=dev)
+    score = torch.full((max(n_rows, 1),), float("nan"), dtype=torch.float32, device=dev)
+    dp.dp_kmeans_fit(pf, cent, n_iters, init, asg, ws, best_score=score)
+    torch.cuda.synchronize()
+    return (cent.cpu().numpy().view(np.uint16)[:n_cl], asg.cpu().numpy()[:n_rows], score.cpu().numpy()[:n_rows])
+
+
+def grouped_keys(seed, rows, clusters, groups=9):
+    """Keys in well-separated groups, ragged segments (the last one has more clusters than tokens)."""
+    from workloads import TokenOrderInput, f32_to_bf16_bits
+    rng = np.random.default_rng(seed)
+    d = 128
+    ks = []
+    for n in rows:
+        centres = rng.normal(size=(groups, d)) * 4.0
+        ks.append(centres[rng.integers(0, groups, size=n)] + 0.3 * rng.normal(size=(n, d)))
+    k = f32_to_bf16_bits(np.concatenate(ks).astype(np.float32))
+    rows = np.asarray(rows, np.int32)
+    return TokenOrderInput(n_seg=len(rows), head_dim=d, k_tokens=k, v_tokens=k.copy(),
+                           assignment=np.zeros(int(rows.sum()), np.int32),
+                           seg_row_base=np.concatenate([[0], np.cumsum(rows)[:-1]]).astype(np.int64), seg_rows=rows,
+                           seg_cluster_ptr=np.concatenate([[0], np.cumsum(clusters)]).astype(np.int32))
+
+
+@pytest.mark.parametrize("n_iters", [0, 1, 4])
+def test_kmeans_fit_matches_oracle_on_separated_groups(n_iters):
+    """Points far from every boundary: the fp32 decisions of the GPU are the oracle's fp64 ones in every round, so
+    centroids (bits) and assignment must be equal.  Strided start; clusters that never get a token keep it."""
+    import paper_2602_05191_amd as dp
+    t = grouped_keys(81, rows=[2100, 1300, 5], clusters=[12, 40, 9])
+    ref_c, ref_a = oracle.kmeans_fit(t, None, n_iters, oracle.KMEANS_INIT_STRIDED)
+    got_c, got_a, _ = gpu_fit(t, None, n_iters, dp.DP_KMEANS_INIT_STRIDED)
+    assert np.array_equal(got_c, ref_c)
+    if n_iters:
+        assert np.array_equal(got_a, ref_a)
+        assert (np.bincount(ref_a[-5:], minlength=9) == 0).any()      # the case does hold empty clusters
+    else:
+        assert (got_a == -7).all()                                     # nothing assigned, nothing written
+
+
+def test_kmeans_fit_round_by_round_on_clustered_keys():
+    """General keys (near-ties exist): round r is checked on its own.  From the GPU's centroids after r - 1 rounds,
+    the GPU's assignment of round r must be the oracle's wherever the margin is clear (and near-best elsewhere), and
+    the GPU's centroids after round r must be the oracle's means of THAT assignment bit for bit, an emptied cluster
+    keeping its centroid."""
+    import copy
+    import paper_2602_05191_amd as dp
+    c = make_cache(batch=2, n_kv_heads=1, n_q_heads=1, context=[5000, 3333], mean_cluster=16, q_scale=1.0, seed=83)
+    t = token_order_input(c, seed=11)
+    start = sampled_centroids(t, 12)
+    start[3] = start[2]                                                # a duplicate: cluster 3 wins no token in round 1
+    before = start
+    for r in (1, 2, 3):
+        cent, asg, score = gpu_fit(t, start, r, dp.DP_KMEANS_INIT_GIVEN)
+        check_assign(t, before, asg, score)
+        tt = copy.copy(t)
+        tt.assignment = asg
+        means = oracle.build_cluster_cache(tt)
+        filled = means["cluster_sizes"] > 0
+        assert r > 1 or not filled[3]
+        assert np.array_equal(cent[filled], means["k_centroids"][filled])
+        assert np.array_equal(cent[~filled], before[~filled])
+        before = cent
+
+
+def test_kmeans_fit_boundary_rejects_bad_arguments():
+    import torch
+    import paper_2602_05191_amd as dp
+    t = grouped_keys(85, rows=[300], clusters=[4])
+    dev = "cuda:0"
+    up = lambda a, dt: torch.from_numpy(np.ascontiguousarray(a).view(dt)).to(dev)
+    pf = dp.Prefill(up(t.k_tokens, np.int16), up(t.v_tokens, np.int16), up(t.assignment, np.int32),
+                    up(t.seg_row_base, np.int64), up(t.seg_rows, np.int32), up(t.seg_cluster_ptr, np.int32), 4, 4, 300)
+    need = dp.dp_kmeans_fit_workspace_bytes(pf)
+    assert need >= dp.dp_kmeans_workspace_bytes(pf) and need >= dp.dp_build_workspace_bytes(pf)
+    ws = torch.empty(need, dtype=torch.uint8, device=dev)
+    cent = torch.zeros((4, 128), dtype=torch.int16, device=dev)
+    asg = torch.zeros(300, dtype=torch.int32, device=dev)
+    for args, status in (((cent, -1, dp.DP_KMEANS_INIT_GIVEN, asg, ws), -1), ((cent, 1, 7, asg, ws), -1),
+                         ((cent, 1, dp.DP_KMEANS_INIT_GIVEN, asg, ws[:need - 256]), -3),
+                         ((cent, 1, dp.DP_KMEANS_INIT_GIVEN, None, ws), -1)):
+        with pytest.raises(dp.DPError) as e:
+            dp.dp_kmeans_fit(pf, *args)
+        assert e.value.status == status
+    dp.dp_kmeans_fit(pf, cent, 0, dp.DP_KMEANS_INIT_STRIDED, None, ws)    # only the start: no assignment needed
+    torch.cuda.synchronize()
+    assert np.array_equal(cent.cpu().numpy().view(np.uint16), t.k_tokens[[0, 75, 150, 225]])

@@ -732,6 +732,62 @@ def test_kmeans_assign_ties_go_to_the_lower_index_and_lloyd_does_not_increase_th
         cent = np.where(keep[:, None], m["k_centroids"], cent)
 
 
+def test_kmeans_fit_is_lloyds_iteration_as_a_library_runs_it():
+    """Round r of the procedure against one iteration of scikit-learn's Lloyd started from the procedure's own
+    centroids after r - 1 rounds (bf16 values, exact in fp64, so both sides assign on the same numbers): the
+    library's new centres are the procedure's centroids up to the one rounding to bf16 (a wrongly assigned point
+    would move a mean by more), and its assignment of the round is the procedure's."""
+    from sklearn.cluster import KMeans
+    from workloads import TokenOrderInput
+    rng = np.random.default_rng(77)
+    d, k, n = 128, 7, 900
+    centres = rng.normal(size=(k, d)) * 4.0
+    label = rng.integers(0, k, size=n)
+    X = bf16_bits_to_f32(f32_to_bf16_bits((centres[label] + 0.3 * rng.normal(size=(n, d))).astype(np.float32)))
+    t = TokenOrderInput(n_seg=1, head_dim=d, k_tokens=f32_to_bf16_bits(X), v_tokens=f32_to_bf16_bits(X),
+                        assignment=np.zeros(n, np.int32), seg_row_base=np.zeros(1, np.int64),
+                        seg_rows=np.array([n], np.int32), seg_cluster_ptr=np.array([0, k], np.int32))
+    # a poor start on purpose (k arbitrary points: some groups are hit twice, some not at all): several rounds move
+    start = f32_to_bf16_bits(X[rng.choice(n, size=k, replace=False)])
+    prev, moved = start, 0
+    for rounds in range(1, 7):
+        cent, asg = oracle.kmeans_fit(t, start, rounds)
+        km = KMeans(n_clusters=k, init=bf16_bits_to_f32(prev).astype(np.float64), n_init=1, max_iter=1, tol=0.0,
+                    algorithm="lloyd")
+        km.fit(X.astype(np.float64))
+        # within half a bf16 step of the library's fp64 centres (bf16 inputs and small counts put many means exactly on
+        # a rounding tie, where the library's last fp64 bit decides otherwise than the exact mean; the exact rounding
+        # of the means is pinned with rational arithmetic in the build tests)
+        ours = bf16_bits_to_f32(cent).astype(np.float64)
+        assert (np.abs(ours - km.cluster_centers_) <= 2.0 ** -8 * np.abs(km.cluster_centers_) * (1 + 1e-9) + 1e-30).all()
+        # the round's assignment = nearest of the previous centroids (the library's own predict on them)
+        km.cluster_centers_ = bf16_bits_to_f32(prev).astype(np.float64)
+        assert np.array_equal(asg, km.predict(X.astype(np.float64))), rounds
+        moved += int(not np.array_equal(cent, prev))
+        prev = cent
+    assert moved >= 3            # the start was poor enough for the iteration to do something
+
+
+def test_kmeans_fit_strided_start_empty_clusters_and_zero_rounds():
+    from workloads import TokenOrderInput
+    d = 128
+    X = np.zeros((8, d), np.float32)
+    X[:, 0] = [0, 0, 1, 1, 10, 10, 11, 11]
+    t = TokenOrderInput(n_seg=2, head_dim=d, k_tokens=f32_to_bf16_bits(np.r_[X, X[:3]]),
+                        v_tokens=f32_to_bf16_bits(np.r_[X, X[:3]]), assignment=np.zeros(11, np.int32),
+                        seg_row_base=np.array([0, 8], np.int64), seg_rows=np.array([8, 3], np.int32),
+                        seg_cluster_ptr=np.array([0, 4, 9], np.int32))
+    cent, asg = oracle.kmeans_fit(t, None, 0, oracle.KMEANS_INIT_STRIDED)
+    assert asg is None
+    # segment 0: tokens 0, 2, 4, 6; segment 1 (3 tokens, 5 clusters): tokens 0, 0, 1, 1, 2
+    assert bf16_bits_to_f32(cent)[:, 0].tolist() == [0, 1, 10, 11, 0, 0, 0, 0, 1]
+    cent, asg = oracle.kmeans_fit(t, None, 2, oracle.KMEANS_INIT_STRIDED)
+    assert asg[:8].tolist() == [0, 0, 1, 1, 2, 2, 3, 3]
+    # duplicated start centroids: ties go to the lower index, the twin stays empty and keeps its centroid
+    assert asg[8:].tolist() == [0, 0, 4]
+    assert bf16_bits_to_f32(cent)[:, 0].tolist() == [0, 1, 10, 11, 0, 0, 0, 0, 1]
+
+
 # --------------------------------------------------------------------------
 # selection per GQA group (the union of the heads' sets; the paper states the method for one query)
 # --------------------------------------------------------------------------
