@@ -103,6 +103,26 @@ def case_pinned_many_clusters():
     return c, 0.95, 0.9
 
 
+def case_pinned_on_top():
+    # Peaked heads on segments of 256 clusters with pinned clusters where they matter.  Segment 0: the cluster that
+    # holds the most attention of head 0 is pinned (the max of the distribution moves to another cluster), and so are
+    # its neighbour and two clusters far away; segment 1: sixteen pinned clusters, one of them emptied; segment 2:
+    # twenty; segment 3: none.
+    c = make_cache(batch=1, n_kv_heads=4, n_q_heads=8, context=4096, n_clusters=256, mean_cluster=16, size_hi=64,
+                   q_scale=lambda rng, b, h: [3.0, 4.0][h % 2], seed=27)
+    lg = oracle.Oracle(c).centroid_logits(0, 0)
+    top = int(np.argmax(lg))
+    flags = np.zeros(int(c.seg_cluster_ptr[-1]), np.uint8)
+    flags[[top, top ^ 1, 7, 250]] = 1
+    rng = np.random.default_rng(6)
+    s1 = 256 + rng.choice(256, size=16, replace=False)
+    flags[s1] = 1
+    c.cluster_sizes[int(s1[3])] = 0
+    flags[512 + rng.choice(256, size=20, replace=False)] = 1
+    c.cluster_flags = flags
+    return c, 0.95, 0.9
+
+
 def case_many_heads():
     # more heads (320) than CUs: the selection kernel runs two 512-thread workgroups per CU; flat and peaked
     # heads, ragged batch, 3300 / 1500 / 600 clusters per segment, sink and window pinned
@@ -139,7 +159,7 @@ def case_gqa6():
 CASES = {f.__name__[5:]: f for f in (case_gqa16_and_6_ragged, case_gqa6, case_cfg0, case_flat_ragged, case_mixed_sharpness, case_gqa8_pareto, case_gqa1,
                                      case_gqa3_and_12, case_gqa12, case_many_clusters, case_single_cluster,
                                      case_giant_cluster, case_empty_clusters_and_segment, case_pinned_peaked,
-                                     case_pinned_flat_ragged, case_pinned_many_clusters, case_many_heads,
+                                     case_pinned_flat_ragged, case_pinned_many_clusters, case_pinned_on_top, case_many_heads,
                                      case_very_many_heads)}
 
 
