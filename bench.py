@@ -165,8 +165,10 @@ def main():
 
     # spread of the step time: one rotation over the L replicas at a time between two events on the launch stream
     # (an event costs a bubble, so these rotations are not the reported value); p10 / median / p90 of rotation / L
-    n_rot = max(10, min(200, args.steps // max(L, 1)))
+    n_rot = max(50, min(200, args.steps // max(L, 1)))  # at least 50 timed rotations after 5 untimed ones
     rot_ev = [torch.cuda.Event(enable_timing=True) for _ in range(n_rot + 1)]
+    for i in range(5 * L):
+        step(i)
     torch.cuda.synchronize()
     rot_ev[0].record()
     for r in range(n_rot):
