@@ -490,39 +490,47 @@ __device__ __forceinline__ void rank_lanes(const SelectArgs &a, Shared<T> &sh, E
   }
   const bool pin_i = act && m_i == 0;  // a candidate of the top set has weight > 0, a pinned cluster 0
   const u64 tau1 = first_tau<kCount>(a, W);
-  if (wave_sum(m_i) < tau1) {  // integer sums: exact.  The retained set is not inside the top set.
-    if (lane_id() == 0) sh.f_nex = -1;
-    return;
-  }
-  // lane j holds entry j: the loops below fetch it with readlane (j is uniform), not from LDS
+  // lane j holds entry j: the loops below fetch it with readlane (j is uniform), not from LDS.  A top set has a
+  // handful of members, so the sums over it are taken in these loops on uniform values (scalar arithmetic) instead
+  // of by 64-lane reductions, each of which is a chain of a few dozen dependent vector instructions.
   const uint32_t mlo_i = (uint32_t)m_i, mhi_i = (uint32_t)(m_i >> 32);
+  auto mass_of_lane = [&](int j) {
+    return ((u64)(uint32_t)__builtin_amdgcn_readlane(mhi_i, j) << 32) | (uint32_t)__builtin_amdgcn_readlane(mlo_i, j);
+  };
   u64 ahead = 0;  // mass of the clusters that precede cluster i in the order
+  u64 in_set = 0;  // weight of the whole top set
   for (u64 mm = members; mm; mm &= mm - 1) {
     const int j = __builtin_ctzll(mm);
     const uint32_t kj = __builtin_amdgcn_readlane(key_i, j);
     const int ij = __builtin_amdgcn_readlane(idx_i, j);
-    const u64 mj = ((u64)(uint32_t)__builtin_amdgcn_readlane(mhi_i, j) << 32) |
-                   (uint32_t)__builtin_amdgcn_readlane(mlo_i, j);
+    const u64 mj = mass_of_lane(j);
+    in_set += mj;
     if (kj > key_i || (kj == key_i && ij < idx_i)) ahead += mj;
   }
+  if (in_set < tau1) {  // integer sums: exact.  The retained set is not inside the top set.
+    if (lane_id() == 0) sh.f_nex = -1;
+    return;
+  }
   const bool ret = pin_i || (act && ahead < tau1);
-  u64 m1 = (ret && !pin_i) ? ahead + m_i : 0;  // mass of the retained prefix = the largest inclusive prefix
-  m1 = wave_max(m1);
+  u64 m1 = 0;  // mass of the retained prefix
+  for (u64 mm = __ballot(ret && !pin_i); mm; mm &= mm - 1) m1 += mass_of_lane(__builtin_ctzll(mm));
   u64 tau2 = 0;
   const int kind = second_tau<kCount>(a, W, m1, tau2);
   const bool exa = pin_i || (kind == 1 ? ret : (kind == 2 && act && ahead < tau2));
   const bool apx = ret && !exa;
   const u64 exa_mask = __ballot(exa), apx_mask = __ballot(apx);
   const int n_ex = __popcll(exa_mask), n_ap = __popcll(apx_mask);
-  const int n_tok = wave_sum(exa ? sz_i : 0);
+  int n_tok = 0;
   // position of cluster i in its list = selected clusters with a smaller index
   int pe = 0, pa = 0, pt = 0;
   for (u64 mm = exa_mask | apx_mask; mm; mm &= mm - 1) {
     const int j = __builtin_ctzll(mm);
     const bool before = __builtin_amdgcn_readlane(idx_i, j) < idx_i;
     if ((exa_mask >> j) & 1) {
+      const int sz_j = __builtin_amdgcn_readlane(sz_i, j);
+      n_tok += sz_j;
       pe += before;
-      pt += before ? __builtin_amdgcn_readlane(sz_i, j) : 0;
+      pt += before ? sz_j : 0;
     } else {
       pa += before;
     }
