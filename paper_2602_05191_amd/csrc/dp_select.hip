@@ -111,7 +111,6 @@ struct Shared {
   int top_idx[kTopMax], top_sz[kTopMax], top_off[kTopMax];
   u64 top_m[kTopMax];
   int ntop, f_nex, f_nap, f_ntok;
-  int lite_sub[kLiteMaxTopSub];  // selection from the sub-tile summaries: the sub-tiles that may hold the top set
   float lite_max;                // the head's max logit as the summaries give it (exact), for the general path
   // The refinement histogram of the (rare) crowded-bin search and the lists / merge buffers of the inline
   // attention never live at the same time: the lists are written once the search is over.
@@ -559,10 +558,10 @@ __device__ __forceinline__ void rank_top_set(const SelectArgs &a, Shared<T> &sh,
 
 // Top-p selection of a peaked head from the scoring kernel's sub-tile summaries, without reading the head's
 // logits, by ONE wave and without a barrier: it reads (max, sum exp) of every sub-tile, which gives the max logit
-// exactly and the total mass W (the sub-tile sums rescaled to the max, added up per lane in fp32 and over the lanes
-// in the 2^-40 fixed point of the other paths: W is within a few 1e-7 of the integer sum of the clusters' own
-// masses, so a threshold p * W moves by that much).  Only sub-tiles whose max lies within kTopCut of the head's max
-// can hold a member of the top set; if there are at most four of them, the wave reads their 64 logits, sizes and
+// exactly and the total mass W (the sub-tile sums rescaled to the max and added up in fp32, per lane and then over
+// the lanes, and brought into the 2^-40 fixed point of the other paths: W is within a few 1e-7 of the integer sum of
+// the clusters' own masses, so a threshold p * W moves by that much).  Only sub-tiles whose max lies within kTopCut
+// of the head's max can hold a member of the top set; if there are at most four of them, the wave reads their 64 logits, sizes and
 // offsets (one cluster per lane) and ranks the top set in place.  Returns false (block-uniform) when the head is not
 // peaked enough for that: then nothing has been emitted.
 template <int T>
@@ -583,29 +582,41 @@ __device__ __forceinline__ bool lite_select(const SelectArgs &a, Shared<T> &sh, 
 #pragma unroll
     for (int i = 0; i < kLiteSubPerLane; ++i) m = fmaxf(m, sv[i].x);
     const float M = wave_max(m);
-    float acc = 0.f;
-    int n_ts = 0, my_sub = -1;
+    // The sub-tiles that may hold a cluster within kTopCut of the max: a bit per own sub-tile in every lane, then the
+    // few lanes that hold one are walked on uniform values (no LDS, no barrier); slot k of the list (any order) goes
+    // to lanes 16 k .. + 15.
+    uint32_t top_bits = 0;
 #pragma unroll
-    for (int i = 0; i < kLiteSubPerLane; ++i) {
-      const bool live = sv[i].x > -INFINITY;
-      if (live) acc = fmaf(sv[i].y, __builtin_amdgcn_exp2f((sv[i].x - M) * kLog2e), acc);
-      // the sub-tiles that may hold a cluster within kTopCut of the max: slot k of the list goes to lanes 16 k .. + 15
-      const bool top = live && M - sv[i].x < kTopCut;
-      const u64 mask = __ballot(top);
-      const int pos = n_ts + (int)__builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0u));
-      if (top && pos < kLiteMaxTopSub) sh.lite_sub[pos] = tid + 64 * i;
-      n_ts += __popcll(mask);
+    for (int i = 0; i < kLiteSubPerLane; ++i)
+      if (sv[i].x > -INFINITY && M - sv[i].x < kTopCut) top_bits |= 1u << i;
+    static_assert(kLiteMaxTopSub == 4, "the list below is four uniform values");
+    int n_ts = 0, s0 = -1, s1 = -1, s2 = -1, s3 = -1;
+    for (u64 lanes = __ballot(top_bits != 0); lanes && n_ts <= kLiteMaxTopSub; lanes &= lanes - 1) {
+      const int j = __builtin_ctzll(lanes);
+      for (uint32_t b = (uint32_t)__builtin_amdgcn_readlane((int)top_bits, j); b; b &= b - 1) {
+        s3 = s2;
+        s2 = s1;
+        s1 = s0;
+        s0 = j + 64 * __builtin_ctz(b);
+        ++n_ts;
+      }
     }
     bool ok = M > -INFINITY && n_ts <= kLiteMaxTopSub;  // no candidate at all, or a flat head: the general path
     if (ok) {
-      const u64 W = wave_sum((u64)((double)acc * 1099511627776.0));  // per lane <= 128 * 2^40: integer sums from here on
-      __builtin_amdgcn_wave_barrier();  // the list was written by lanes of this wave
-      my_sub = (tid >> 4) < n_ts ? sh.lite_sub[tid >> 4] : -1;
+      const int slot = tid >> 4;
+      const int my_sub = slot == 0 ? s0 : slot == 1 ? s1 : slot == 2 ? s2 : s3;  // -1: no such sub-tile
       const int i = my_sub * kSubTile + (tid & 15);
       const bool have = my_sub >= 0 && i < kc;
+      // the second round of loads goes out before the total mass is summed
       const float l = have ? lg[i] + 0.0f : -INFINITY;  // -0 becomes +0
       const int sz = have ? a.cluster_sizes[c0 + i] : 0;
       const int off = (have && plan) ? a.cluster_offsets[c0 + i] : 0;
+      float acc = 0.f;
+#pragma unroll
+      for (int u = 0; u < kLiteSubPerLane; ++u)
+        if (sv[u].x > -INFINITY) acc = fmaf(sv[u].y, __builtin_amdgcn_exp2f((sv[u].x - M) * kLog2e), acc);
+      // fp32 over the lanes (a tree of depth 6), then the 2^-40 fixed point of the other paths
+      const u64 W = (u64)((double)wave_sum(acc) * 1099511627776.0);
       const float d = M - l;
       const bool member = have && d < kTopCut;
       rank_lanes<false, T>(a, sh, emit, member, ordered_key(l), i, member ? fx_mass(d) : 0, sz, off, W, can_inline);
