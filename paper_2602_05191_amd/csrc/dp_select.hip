@@ -543,6 +543,7 @@ __device__ __forceinline__ void rank_lanes(const SelectArgs &a, Shared<T> &sh, E
     sh.f_nex = n_ex;
     sh.f_nap = n_ap;
     sh.f_ntok = n_tok;
+    if (emit.to_lds) emit.l_start[n_ex + n_ap] = n_tok + n_ap;  // the end of the row prefix: the lists are complete
   }
 }
 
@@ -1053,7 +1054,7 @@ __device__ __forceinline__ int select_head(const SelectArgs &a, Shared<T> &sh, i
     put_counts(a.out, head, n_ex, n_ex + n_ap, n_tok, kGate && !inline_attn);
     if (plan) {
       if (inline_attn) {
-        sh.at.l_start[n_ex + n_ap] = R;
+        if (!chosen) sh.at.l_start[n_ex + n_ap] = R;  // (the one-wave paths have written it with the lists)
         // attended here: nothing left for the stage-3 queue (kGate: head_rows was cleared by the scoring kernel)
         if (!kGate) a.plan.head_rows[head] = -1;
       } else {
@@ -1082,7 +1083,9 @@ __device__ __forceinline__ int select_head(const SelectArgs &a, Shared<T> &sh, i
   }
 
   // ---- inline attention for a head with few rows ---------------------------
-  lds_barrier();  // the lists are in LDS; the head's report to the counter (kGate) may still be in flight
+  // the lists are in LDS (a head selected from the summaries: since the barrier that ended that selection); the
+  // head's report to the counter (kGate) may still be in flight
+  if (!chosen) lds_barrier();
   {
     const int lane16 = tid & 15, grp = tid >> 4;
     const uint4 qv = load_row_slice(a.q, (int64_t)head, lane16);
