@@ -421,30 +421,34 @@ struct Emit {
   bool plan, to_lds;
   bool coherent;  // the global plan is read by the stage-3 queue of this same launch
   int n_ex, n_tok;
+  // (The store to the id list comes last: the offset of a cluster may still be on its way from memory when the
+  // entry is written, and a wait for it that follows a store also waits for that store to complete.)
   __device__ __forceinline__ void exact(int pe, int pt, int sz, int off, int id) const {
-    sel[pe] = id;
-    if (!plan) return;
-    if (to_lds) {
-      l_start[pe] = pt;
-      l_src[pe] = off;
-    } else {
-      st_i32(ent_src + pe, off, coherent);
-      st_i32(row_start + pe, pt, coherent);
-      for (int q = (pt + kChunkRows - 1) / kChunkRows; q * kChunkRows < pt + sz; ++q) st_i32(chunk_entry + q, pe, coherent);
+    if (plan) {
+      if (to_lds) {
+        l_start[pe] = pt;
+        l_src[pe] = off;
+      } else {
+        st_i32(ent_src + pe, off, coherent);
+        st_i32(row_start + pe, pt, coherent);
+        for (int q = (pt + kChunkRows - 1) / kChunkRows; q * kChunkRows < pt + sz; ++q) st_i32(chunk_entry + q, pe, coherent);
+      }
     }
+    sel[pe] = id;
   }
   __device__ __forceinline__ void approx(int pa, int id) const {
     const int j = n_ex + pa, row = n_tok + pa;
-    sel[j] = id;
-    if (!plan) return;
-    if (to_lds) {
-      l_start[j] = row;
-      l_src[j] = id;
-    } else {
-      st_i32(ent_src + j, id, coherent);
-      st_i32(row_start + j, row, coherent);
-      if (row % kChunkRows == 0) st_i32(chunk_entry + row / kChunkRows, j, coherent);
+    if (plan) {
+      if (to_lds) {
+        l_start[j] = row;
+        l_src[j] = id;
+      } else {
+        st_i32(ent_src + j, id, coherent);
+        st_i32(row_start + j, row, coherent);
+        if (row % kChunkRows == 0) st_i32(chunk_entry + row / kChunkRows, j, coherent);
+      }
     }
+    sel[j] = id;
   }
 };
 
@@ -557,6 +561,12 @@ __device__ __forceinline__ void rank_top_set(const SelectArgs &a, Shared<T> &sh,
                         act ? sh.top_sz[i] : 0, act ? sh.top_off[i] : 0, W, can_inline);
 }
 
+// Marks a loaded value as used here.  The compiler waits for a load at the first use of its result; when that use
+// sits in a branch behind stores, the wait (the counter of outstanding memory operations is shared and in order) also
+// waits for those stores to complete, a full round trip on the critical path, and at the joins of skipped branches it
+// has to assume the load is still outstanding.  A use right where the value has certainly arrived costs nothing.
+__device__ __forceinline__ void arrived(int v) { asm volatile("" ::"v"(v)); }
+
 // Top-p selection of a peaked head from the scoring kernel's sub-tile summaries, without reading the head's
 // logits, by ONE wave and without a barrier: it reads (max, sum exp) of every sub-tile, which gives the max logit
 // exactly and the total mass W (the sub-tile sums rescaled to the max and added up in fp32, per lane and then over
@@ -608,16 +618,24 @@ __device__ __forceinline__ bool lite_select(const SelectArgs &a, Shared<T> &sh, 
       const int my_sub = slot == 0 ? s0 : slot == 1 ? s1 : slot == 2 ? s2 : s3;  // -1: no such sub-tile
       const int i = my_sub * kSubTile + (tid & 15);
       const bool have = my_sub >= 0 && i < kc;
-      // the second round of loads goes out before the total mass is summed
-      const float l = have ? lg[i] + 0.0f : -INFINITY;  // -0 becomes +0
-      const int sz = have ? a.cluster_sizes[c0 + i] : 0;
-      const int off = (have && plan) ? a.cluster_offsets[c0 + i] : 0;
+      // the second round of loads: all three issued together (nothing uses a value inside the branch, so no wait
+      // separates them), and before the total mass is summed
+      float l = -INFINITY;
+      int sz = 0, off = 0;
+      if (have) {
+        l = lg[i];
+        sz = a.cluster_sizes[c0 + i];
+        off = plan ? a.cluster_offsets[c0 + i] : 0;
+      }
       float acc = 0.f;
 #pragma unroll
       for (int u = 0; u < kLiteSubPerLane; ++u)
         if (sv[u].x > -INFINITY) acc = fmaf(sv[u].y, __builtin_amdgcn_exp2f((sv[u].x - M) * kLog2e), acc);
       // fp32 over the lanes (a tree of depth 6), then the 2^-40 fixed point of the other paths
       const u64 W = (u64)((double)wave_sum(acc) * 1099511627776.0);
+      l += 0.0f;  // -0 becomes +0
+      arrived(sz);
+      arrived(off);
       const float d = M - l;
       const bool member = have && d < kTopCut;
       rank_lanes<false, T>(a, sh, emit, member, ordered_key(l), i, member ? fx_mass(d) : 0, sz, off, W, can_inline);
@@ -823,6 +841,13 @@ __device__ __forceinline__ bool full_select(const SelectArgs &a, Shared<T> &sh, 
     W = partials_sum<u64, (T / 64)>(sh.scr64);
     Wtop = partials_sum<u64, (T / 64)>(sh.scr64b);
     ntop = partials_sum<int, (T / 64)>(sh.scri);
+  }
+  if (kPre) {  // loaded next to the logits, long here: no wait for them between the stores of the emission
+#pragma unroll
+    for (int e = 0; e < HeadInputs<E>::EP; ++e) {
+      arrived(psz[e]);
+      arrived(poff[e]);
+    }
   }
 
   const bool all = !nothing && retain_all<kCount>(a, W);  // every non-empty candidate is retained
