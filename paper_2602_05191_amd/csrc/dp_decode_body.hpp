@@ -163,8 +163,15 @@ __device__ __forceinline__ void decode_item(const DecodeArgs &a, int head, int s
     const int n_ent = min(r1 - r0, n_rt - ent0);
     __syncthreads();
     for (int k = tid; k <= n_ent; k += T) {
-      s_start[k] = DP_LD_I32(row_start[ent0 + k]);
-      s_src[k] = (k < n_ent) ? DP_LD_I32(ent_src[ent0 + k]) : 0;
+      if (!kCoherent) {  // both loads go out together (n_ent >= 1: an item has a row)
+        const int start = row_start[ent0 + k];
+        const int source = ent_src[ent0 + min(k, n_ent - 1)];
+        s_start[k] = start;
+        s_src[k] = (k < n_ent) ? source : 0;
+      } else {
+        s_start[k] = DP_LD_I32(row_start[ent0 + k]);
+        s_src[k] = (k < n_ent) ? DP_LD_I32(ent_src[ent0 + k]) : 0;
+      }
     }
     __syncthreads();
     // the DPP-row groups take consecutive 4-row pieces: one step of the workgroup reads T / 4 consecutive rows
@@ -267,7 +274,16 @@ __device__ __forceinline__ void decode_queue(const DecodeArgs &a, int *s_start, 
 #pragma unroll
   for (int u = 0; u < kPer; ++u) {
     const int hh = tid * kPer + u;
-    rows[u] = hh < a.n_heads ? DP_LD_I32(a.plan.head_rows[a.head0 + hh]) : 0;  // <= 0: nothing to do (empty, or attended already)
+    // (an unconditional load at a clamped index, the value chosen afterwards: loads inside a condition are waited
+    // for one by one, four dependent round trips at the start of every workgroup)
+    // (Only in the decode launch of its own: inside the selection's launch the same rewrite changed nothing for the
+    // queue and cost the selection of a peaked head 0.2 us through the code around it.)
+    if (!kCoherent) {
+      const int got = a.plan.head_rows[a.head0 + min(hh, a.n_heads - 1)];
+      rows[u] = hh < a.n_heads ? got : 0;  // <= 0: nothing to do (empty, or attended already)
+    } else {
+      rows[u] = hh < a.n_heads ? DP_LD_I32(a.plan.head_rows[a.head0 + hh]) : 0;
+    }
     s_rows[hh] = rows[u];
     if (rows[u] > 0) chunks += min(1 << 20, (rows[u] + kChunkRows - 1) / kChunkRows);  // capped: the sum stays in range
   }

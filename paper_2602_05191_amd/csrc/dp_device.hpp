@@ -106,6 +106,14 @@ __device__ __forceinline__ void lds_barrier() {
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
 }
 
+// Marks a kernel argument (a uniform value) as used here: the compiler otherwise fetches an argument that is first
+// needed at the end of a kernel (an output pointer, a stride) from the argument segment right there, one more
+// dependent round trip behind the last loads.
+template <class V>
+__device__ __forceinline__ void fetch_early(V v) {
+  asm volatile("" ::"s"(v));
+}
+
 // ------------------------------------------------- wave / block scans ----
 __device__ __forceinline__ int lane_id() { return threadIdx.x & 63; }
 __device__ __forceinline__ int wave_id() { return threadIdx.x >> 6; }

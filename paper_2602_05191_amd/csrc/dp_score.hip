@@ -118,6 +118,12 @@ __global__ __launch_bounds__(kScoreThreads) void score_valu_kernel(
   for (int j = 0; j < GH; ++j)
     qv[j] = load_row_slice(q, (int64_t)b * n_q_heads + g * group + head0 + j, lane16);
 
+  // what the end of the kernel needs from the argument segment is fetched while the loads are in flight
+  fetch_early(a.logits);
+  fetch_early(a.summaries);
+  fetch_early(a.sub_stride);
+  fetch_early(a.sm_scale);
+
   // lane j of the group ends up with head j's logits of the group's RB consecutive clusters
   float mine[kValuRows];
 #pragma unroll
@@ -214,6 +220,10 @@ __global__ __launch_bounds__(kScoreThreads) void score_kernel(
 #pragma unroll
     for (int k = 0; k < 4; ++k) size[t][k] = (i0 + k < kc) ? cluster_sizes[c0 + i0 + k] : 0;
   }
+  fetch_early(a.logits);  // the end of the kernel's arguments, fetched while the loads are in flight
+  fetch_early(a.summaries);
+  fetch_early(a.sub_stride);
+  fetch_early(a.sm_scale);
 #pragma unroll
   for (int t = 0; t < RT; ++t) {
     f32x4 acc = {0.f, 0.f, 0.f, 0.f};

@@ -691,8 +691,17 @@ __device__ __forceinline__ void load_head_inputs(const SelectArgs &a, int c0, in
       l[e + 3 < E ? e + 3 : e] = v.w;
     }
   } else {
+    // the ragged or unaligned case: unconditional loads at clamped indices, the values chosen afterwards (loads
+    // inside a condition are waited for one by one: E dependent round trips)
 #pragma unroll
-    for (int e = 0; e < E; ++e) l[e] = (base + e < kc) ? lg[base + e] : -INFINITY;
+    for (int e = 0; e < E; ++e) l[e] = -INFINITY;
+    if (kc > 0) {
+      float got[E];
+#pragma unroll
+      for (int e = 0; e < E; ++e) got[e] = lg[min(base + e, kc - 1)];
+#pragma unroll
+      for (int e = 0; e < E; ++e) l[e] = (base + e < kc) ? got[e] : -INFINITY;
+    }
   }
   if (kPre) {
     const int32_t *sp = a.cluster_sizes + c0 + base, *op = a.cluster_offsets + c0 + base;
@@ -708,9 +717,20 @@ __device__ __forceinline__ void load_head_inputs(const SelectArgs &a, int c0, in
       }
     } else {
 #pragma unroll
-      for (int e = 0; e < EP; ++e) {
-        psz[e] = (base + e < kc) ? sp[e] : 0;
-        poff[e] = (plan && base + e < kc) ? op[e] : 0;
+      for (int e = 0; e < EP; ++e) psz[e] = poff[e] = 0;
+      if (kc > 0) {
+        const int32_t *s0 = a.cluster_sizes + c0, *o0 = a.cluster_offsets + c0;
+        int gs[EP], go[EP];
+#pragma unroll
+        for (int e = 0; e < EP; ++e) {
+          gs[e] = s0[min(base + e, kc - 1)];
+          go[e] = plan ? o0[min(base + e, kc - 1)] : 0;
+        }
+#pragma unroll
+        for (int e = 0; e < EP; ++e) {
+          psz[e] = (base + e < kc) ? gs[e] : 0;
+          poff[e] = (base + e < kc) ? go[e] : 0;
+        }
       }
     }
   }
