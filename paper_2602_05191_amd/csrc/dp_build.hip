@@ -25,7 +25,7 @@
 //            chunks: fetches each row's token, stores it in place, and sums the
 //            chunk's rows column by column from a copy in LDS
 // The update step of k-means (mean key of every cluster, nothing moved) is the same
-// sequence with the cache pointers left null and a keys-only kernel in place of the move.
+// sequence with the cache pointers left null: the last kernel then fetches keys only and stores no row.
 #include "dp_device.hpp"
 #include "dp_kernels.hpp"
 
@@ -153,52 +153,16 @@ __device__ __forceinline__ uint32_t f64_to_bf16_rne(double x) {
   return bits;
 }
 
-// Keys only (the update step of k-means): nothing is moved, no value is read, a cluster without tokens keeps the
-// centroid it has.  One 16-lane row per cluster walks the cluster's rows in order, 16 key rows in flight (a very
-// large cluster is a chain of dependent rounds of loads).
-__global__ __launch_bounds__(256) void build_key_means_kernel(BuildArgs a) {
-  const int seg = blockIdx.y;
-  const int c0 = a.seg_cluster_ptr[seg], kc = a.seg_cluster_ptr[seg + 1] - c0;
-  const int64_t r0 = a.seg_row_base[seg];
-  const int lane16 = threadIdx.x & 15, grp = threadIdx.x >> 4;
-  const int ci = blockIdx.x * 16 + grp;
-  if (ci >= kc) return;
-  const int s = a.cluster_sizes[c0 + ci];
-  const int off = a.cluster_offsets[c0 + ci];
-  if (s == 0) return;
-  const int32_t *tok = a.row_token + (size_t)seg * a.max_rows + off;
-  double ks[8];
-#pragma unroll
-  for (int i = 0; i < 8; ++i) ks[i] = 0.0;
-  for (int rb = 0; rb < s; rb += 16) {
-    // the tokens of the next 16 rows of the cluster, one per lane of the 16-lane row (the last one again beyond it)
-    const int mine = tok[min(rb + lane16, s - 1)];
-    const int nb = min(16, s - rb);
-    uint4 kr[16];
-#pragma unroll
-    for (int u = 0; u < 16; ++u) kr[u] = load_row_slice(a.k_tokens, r0 + __shfl(mine, u, 16), lane16);
-#pragma unroll
-    for (int u = 0; u < 16; ++u) {  // rows beyond the cluster add +0.0: the sums are unchanged
-      float kf[8];
-      unpack8(u < nb ? kr[u] : make_uint4(0, 0, 0, 0), kf);
-#pragma unroll
-      for (int i = 0; i < 8; ++i) ks[i] += (double)kf[i];
-    }
-  }
-  uint32_t kb[8];
-#pragma unroll
-  for (int i = 0; i < 8; ++i) kb[i] = f64_to_bf16_rne(ks[i] / (double)s);
-  *reinterpret_cast<uint4 *>(static_cast<char *>(a.k_centroids) + (size_t)(c0 + ci) * kRowBytes + lane16 * 16) =
-      make_uint4(kb[0] | (kb[1] << 16), kb[2] | (kb[3] << 16), kb[4] | (kb[5] << 16), kb[6] | (kb[7] << 16));
-}
-
 // The move.  A workgroup owns 16 consecutive clusters, whose rows are one contiguous run of the cache.  The run is
 // taken in chunks of 64 rows: the sixteen 16-lane rows of the workgroup fetch four rows each (whatever the sizes
 // of the clusters, every lane has the same number of loads in flight), store them in place and leave a copy in LDS;
 // then thread d sums column d (key dimensions, then value dimensions) of the chunk's rows in row order, in fp64, and
 // writes a cluster's means when its last row has gone by.  A sum carries over from chunk to chunk.
+// kMove = false: keys only (the update step of k-means): nothing is stored in place, no value is read, and a cluster
+// without tokens keeps the centroid it has.
 constexpr int kMoveRows = 64;
 
+template <bool kMove>
 __global__ __launch_bounds__(256) void build_move_kernel(BuildArgs a) {
   __shared__ __align__(16) uint16_t s_rows[kMoveRows][2 * kHeadDim];  // key | value of every row of the chunk
   const int seg = blockIdx.y, tid = threadIdx.x;
@@ -218,6 +182,7 @@ __global__ __launch_bounds__(256) void build_move_kernel(BuildArgs a) {
   // lanes u, u + 4, ... of a 16-lane row: the token of the row's u-th share of the chunk (row 16 u + grp)
   auto token_of = [&](int base) { return tok[min(base + 16 * (lane16 & 3) + grp, n_run - 1)]; };
   auto flush = [&](int c, int s, double sum) {
+    if (!kMove && (s == 0 || tid >= kHeadDim)) return;
     const uint32_t bits = s > 0 ? f64_to_bf16_rne(sum / (double)s) : 0u;
     const size_t o = (size_t)(c0 + cf + c) * kHeadDim;
     if (tid < kHeadDim) {
@@ -240,19 +205,19 @@ __global__ __launch_bounds__(256) void build_move_kernel(BuildArgs a) {
     for (int u = 0; u < 4; ++u) {  // shares beyond the run fetch its last row again and are not stored
       const int t = __shfl(mine, u, 16);
       kr[u] = load_row_slice(a.k_tokens, r0 + t, lane16);
-      vr[u] = load_row_slice(a.v_tokens, r0 + t, lane16);
+      if (kMove) vr[u] = load_row_slice(a.v_tokens, r0 + t, lane16);
     }
     mine = token_of(base + kMoveRows);  // the next chunk's tokens arrive while this chunk is summed
     lds_barrier();                      // the previous chunk has been summed
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
       *reinterpret_cast<uint4 *>(&s_rows[16 * u + grp][lane16 * 8]) = kr[u];
-      *reinterpret_cast<uint4 *>(&s_rows[16 * u + grp][kHeadDim + lane16 * 8]) = vr[u];
+      if (kMove) *reinterpret_cast<uint4 *>(&s_rows[16 * u + grp][kHeadDim + lane16 * 8]) = vr[u];
     }
 #pragma unroll
     for (int u = 0; u < 4; ++u) {  // after the copies: a wait placed behind a store would wait for the store
       const int j = 16 * u + grp;
-      if (j < nb) {
+      if (kMove && j < nb) {
         const int64_t row = r0 + run0 + base + j;
         *reinterpret_cast<uint4 *>(static_cast<char *>(a.k_cache) + row * kRowBytes + lane16 * 16) = kr[u];
         *reinterpret_cast<uint4 *>(static_cast<char *>(a.v_cache) + row * kRowBytes + lane16 * 16) = vr[u];
@@ -262,6 +227,7 @@ __global__ __launch_bounds__(256) void build_move_kernel(BuildArgs a) {
     int j = 0;
     while (cur < ncl) {
       const int hi = min(cur_end - base, nb);
+      if (!kMove && tid >= kHeadDim) j = hi;  // keys only: the upper half of the workgroup has no column
       for (; j + 8 <= hi; j += 8) {
         uint16_t x[8];
 #pragma unroll
@@ -338,8 +304,8 @@ hipError_t launch_build(const BuildProblem &p, void *workspace, hipStream_t s) {
     hipLaunchKernelGGL(build_place_kernel, dim3((p.max_rows + 255) / 256, p.n_seg), dim3(256), 0, s, a);
   if (p.max_kc > 0) {
     const dim3 grid((p.max_kc + 15) / 16, p.n_seg);
-    if (p.k_cache) hipLaunchKernelGGL(build_move_kernel, grid, dim3(256), 0, s, a);
-    else hipLaunchKernelGGL(build_key_means_kernel, grid, dim3(256), 0, s, a);
+    if (p.k_cache) hipLaunchKernelGGL(build_move_kernel<true>, grid, dim3(256), 0, s, a);
+    else hipLaunchKernelGGL(build_move_kernel<false>, grid, dim3(256), 0, s, a);
   }
   return hipGetLastError();
 }
