@@ -575,10 +575,10 @@ __device__ __forceinline__ void arrived(int v) { asm volatile("" ::"v"(v)); }
 // of the head's max can hold a member of the top set; if there are at most four of them, the wave reads their 64 logits, sizes and
 // offsets (one cluster per lane) and ranks the top set in place.  Returns false (block-uniform) when the head is not
 // peaked enough for that: then nothing has been emitted.
-template <int T>
+template <int T, bool kWarm>
 __device__ __forceinline__ bool lite_select(const SelectArgs &a, Shared<T> &sh, Emit &emit, int c0, int kc,
-                                            const float *lg, bool plan, bool can_inline, int &n_ex, int &n_ap,
-                                            int &n_tok) {
+                                            const float *lg, bool plan, bool can_inline, int64_t seg_row0,
+                                            int (&warm)[4], int &n_ex, int &n_ap, int &n_tok) {
   const int tid = threadIdx.x;
   if (tid < 64) {
     const int n_sub = (kc + kSubTile - 1) / kSubTile;
@@ -636,6 +636,23 @@ __device__ __forceinline__ bool lite_select(const SelectArgs &a, Shared<T> &sh, 
       l += 0.0f;  // -0 becomes +0
       arrived(sz);
       arrived(off);
+      if (kWarm && can_inline) {
+        // The cluster with the largest logit is exact whatever the thresholds are: its rows start their way from HBM
+        // now, one touch per 64 bytes, and have arrived in the L2 when the lists are written and the rows are
+        // attended (the values are never used; the caller marks them as arrived once the rows have been read).
+        const u64 top = __ballot(have && l == M);
+        const int j = top ? __builtin_ctzll(top) : 0;
+        const int n4 = 4 * min(__builtin_amdgcn_readlane(top ? sz : 0, j), 32);
+        const int64_t byte0 = (seg_row0 + __builtin_amdgcn_readlane(off, j)) * kRowBytes;
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+          const int piece = min(tid + 64 * u, n4 - 1);
+          if (n4 > 0) {
+            warm[2 * u] = *reinterpret_cast<const int *>(static_cast<const char *>(a.k_cache) + byte0 + 64 * piece);
+            warm[2 * u + 1] = *reinterpret_cast<const int *>(static_cast<const char *>(a.v_cache) + byte0 + 64 * piece);
+          }
+        }
+      }
       const float d = M - l;
       const bool member = have && d < kTopCut;
       rank_lanes<false, T>(a, sh, emit, member, ordered_key(l), i, member ? fx_mass(d) : 0, sz, off, W, can_inline);
@@ -1070,9 +1087,11 @@ __device__ __forceinline__ int select_head(const SelectArgs &a, Shared<T> &sh, i
   const bool try_lite = !kCount && a.summaries && !a.cluster_flags && a.p1 < 1.0f && kc > 0 &&
                         kc <= kLiteSubPerLane * 64 * kSubTile;
   bool chosen = false;
+  int warm[4] = {0, 0, 0, 0};  // rows fetched ahead by the summary path (never used)
   float known_max = __builtin_nanf("");
   if (try_lite) {
-    chosen = lite_select<T>(a, sh, emit, c0, kc, lg, plan, can_inline, n_ex, n_ap, n_tok);
+    // (the kernels for more than 8192 clusters per segment have no registers to spare for the rows fetched ahead)
+    chosen = lite_select<T, (E <= 8)>(a, sh, emit, c0, kc, lg, plan, can_inline, seg_row0, warm, n_ex, n_ap, n_tok);
     if (!chosen) {  // the general path knows the max: it fills its histogram while it sums the weights
       known_max = sh.lite_max;
       for (int i = tid; i < bins_of(T); i += T) sh.hist[i] = 0;
@@ -1148,6 +1167,8 @@ __device__ __forceinline__ int select_head(const SelectArgs &a, Shared<T> &sh, i
     const int per = kAttendBatch * ((R + kGroups * kAttendBatch - 1) / (kGroups * kAttendBatch));
     const int ra = grp * per, rb = min(R, ra + per);
     attend_rows(st, qv, a.scale_log2, src, sh.at.l_start, sh.at.l_src, n_ex + n_ap, 0, n_ex, ra, rb, kAttendBatch, lane16);
+#pragma unroll
+    for (int u = 0; u < 4; ++u) arrived(warm[u]);  // loads complete in order: these have, with the rows read above
     float M, L, o;
     const int groups_used = (R + per - 1) / per;
     block_merge<(T / 64)>(st, sh.at.m_m, sh.at.m_l, sh.at.m_acc, (groups_used + 3) / 4, M, L, o);
