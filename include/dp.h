@@ -54,9 +54,10 @@ typedef enum { DP_BF16 = 0, DP_F32 = 1 } dp_dtype;
  * threshold is min(p2, M1): p2 measured on the whole distribution. */
 #define DP_FLAG_P2_ABSOLUTE 1u
 /* dp_decode_attention runs the split decode of stage 3 inside the selection launch (two kernel launches per step)
- * when a step serves at most 128 heads and a KV segment has at most 512 or more than 4096 clusters.  With this
- * flag it always uses a separate decode launch (three launches), as it does for all other steps.  Same sets; the outputs may differ in the last bits (the rows of a
- * head are split into partial results differently).  For A/B timing. */
+ * when a step serves at most 128 heads.  With this flag it always uses a separate decode launch (three launches),
+ * as it does for all other steps: faster by about a tenth when every head of the step is flat (a caller who knows
+ * may say so), slower when most heads are peaked.  Same sets; the outputs may differ in the last bits (the rows of
+ * a head are split into partial results differently). */
 #define DP_FLAG_SEPARATE_DECODE_LAUNCH 2u
 
 typedef struct {

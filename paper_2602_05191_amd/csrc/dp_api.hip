@@ -176,16 +176,20 @@ dp_status select_only(const dp_problem *problem, const float *logits, const dp::
 }
 
 // Whether a step runs the split decode inside the selection launch.
-// Where the shared launch pays (measured, 32 heads): it saves the decode launch of a step whose heads are all
-// peaked (8192 clusters per KV head: 15.4 instead of 16.5 us; 256 clusters: 11.6 instead of 13 us), and its queue is
-// served by the selection kernel's large workgroups, which is as fast as the decode kernel's many small ones
-// when the heads that need it are long (8192 clusters, flat heads: 111 against 115 us) but slower when they are
-// many and of middling length (2048 clusters, flat heads: 56 against 44 us; a fixed budget on every head: 64
-// against 53 us).  Hence: top-p rule only, and not for segments of 513 to 4096 clusters.
+// Where the shared launch pays (measured, 32 heads, us per step against three launches): it saves the decode launch
+// of a step whose heads are all attended inline (8192 clusters per KV head: 13.3 against 14.7; 2048 clusters: 12.0
+// against 14.9), and it starts the queue without a launch in between when only some heads are flat (one flat head
+// in eight: 30.3 against 31.8 at 2048 clusters, 50.5 against 55.9 at 8192).  A step of flat heads only is served
+// more slowly by the selection kernel's few large workgroups than by the decode kernel's many small ones (2048
+// clusters: 46 against 43; 8192: 93 against 84): the flag below is for a caller who knows.  With more heads than
+// kSameLaunchMaxHeads the selecting workgroups come in rounds and the shared launch loses (512 peaked heads: 29.6
+// against 24.3).  Top-p rule only (a fixed budget leaves rows on every head).
 bool shares_launch(const dp_problem *problem, bool by_count) {
   const int mk = problem->max_clusters_per_seg;
-  return mk > 0 && (int64_t)problem->batch * problem->n_q_heads <= dp::kSameLaunchMaxHeads && !by_count &&
-         (mk <= 512 || mk > 4096) && !(problem->flags & DP_FLAG_SEPARATE_DECODE_LAUNCH);
+  const int64_t nh = (int64_t)problem->batch * problem->n_q_heads;
+  // (the scoring kernel clears 256 words per segment for the step: the shared launch needs one per head and three more)
+  return mk > 0 && nh <= dp::kSameLaunchMaxHeads && nh + 3 <= 256 * (int64_t)problem->batch * problem->n_kv_heads &&
+         !by_count && !(problem->flags & DP_FLAG_SEPARATE_DECODE_LAUNCH);
 }
 
 // score -> select (+ attention of light heads) -> split decode, on one stream.  A step that serves few heads runs
@@ -206,12 +210,12 @@ dp_status whole_step(const dp_problem *problem, const dp::SelectRule &rule, void
   hipStream_t s = static_cast<hipStream_t>(stream);
   const int n_slabs = (int)(((size_t)problem->batch * problem->n_q_heads + dp::kMaxQueueHeads - 1) / dp::kMaxQueueHeads);
   if (problem->max_clusters_per_seg > 0 && n_slabs <= 64) w.plan.pending = w.plan.queue_next + n_slabs;
+  const int nh_i = problem->batch * problem->n_q_heads;
   const bool same_launch = w.plan.pending && shares_launch(problem, rule.by_count != 0);
   // the summaries serve the top-p rule on heads without cluster flags
   float2 *summ = (!rule.by_count && !problem->cluster_flags && rule.p1 < 1.0f) ? w.summaries : nullptr;
   // the scoring kernel clears the step's counters: item counters, pending counters, planned (contiguous), and
   // in front of them head_rows when the queue runs inside the selection launch (only heads with rows write it then)
-  const int nh_i = problem->batch * problem->n_q_heads;
   int32_t *zero = !w.plan.pending ? nullptr : same_launch ? w.plan.head_rows : w.plan.queue_next;
   const int n_zero = 2 * n_slabs + 1 + (same_launch ? nh_i : 0);
   if (dp::launch_score(c, w.logits, s, ev[0], ev[1], zero, n_zero, summ, w.sub_stride) != hipSuccess) return DP_ERR_HIP;

@@ -38,12 +38,12 @@ struct RowSources {
   int64_t gather_row0;
 };
 
-// Attend rows ra, ra+1, .., ra+B-1, then ra+stride .. (B = kAttendBatch rows per step), below rb.  s_start[0 .. n_ent] and s_src[0 .. n_ent)
+// Attend rows ra, ra+1, .., ra+B-1, then ra+stride .. (B rows in flight per step), below rb.  s_start[0 .. n_ent] and s_src[0 .. n_ent)
 // are the staged row_start / ent_src of entries ent0 .. ent0+n_ent-1, which
 // cover [ra, rb) (s_start[0] <= ra).  Every lane of the group runs the same
 // entry walk (uniform inside the group), so nothing is exchanged between lanes
 // except the DPP sum of the dot product.
-template <bool kGathered = false>
+template <bool kGathered = false, int B = kAttendBatch>
 __device__ __forceinline__ void attend_rows(RowState &st, const uint4 &qv, float scale_log2, const RowSources &src,
                                             const int *s_start, const int *s_src, int n_ent, int ent0, int n_ex,
                                             int ra, int rb, int stride, int lane16) {
@@ -59,16 +59,13 @@ __device__ __forceinline__ void attend_rows(RowState &st, const uint4 &qv, float
   }
   int next_start = s_start[k + 1];
   for (int r = ra; r < rb; r += stride) {
-    uint4 kraw[kAttendBatch], vraw[kAttendBatch];
-    int ssz[kAttendBatch];
-    bool valid[kAttendBatch], approx[kAttendBatch];
+    uint4 kraw[B], vraw[B];
+    int ssz[B];  // the row's additive weight is log2 of this: 1 for a token, the cluster's size for a pseudo-token, 0 (-inf) for no row
 #pragma unroll
-    for (int u = 0; u < kAttendBatch; ++u) {
+    for (int u = 0; u < B; ++u) {
       const int row = r + u;
-      valid[u] = row < rb;
-      approx[u] = false;
-      ssz[u] = 1;
-      if (valid[u]) {
+      ssz[u] = 0;
+      if (row < rb) {
         while (row >= next_start) {  // walk forward to the entry that holds this row
           ++k;
           next_start = s_start[k + 1];
@@ -76,6 +73,7 @@ __device__ __forceinline__ void attend_rows(RowState &st, const uint4 &qv, float
         const int s = s_src[k];
         if (ent0 + k < n_ex) {
           const int64_t g = src.seg_row0 + s + (row - s_start[k]);
+          ssz[u] = 1;
           if (kGathered) {
             kraw[u] = load_row_slice(src.k_gather, src.gather_row0 + row, lane16);
             vraw[u] = load_row_slice(src.v_gather, src.gather_row0 + row, lane16);
@@ -84,7 +82,6 @@ __device__ __forceinline__ void attend_rows(RowState &st, const uint4 &qv, float
             vraw[u] = load_row_slice(src.v_cache, g, lane16);
           }
         } else {
-          approx[u] = true;
           ssz[u] = src.seg_sizes[s];
           kraw[u] = load_row_slice(src.k_centroids, src.c0 + s, lane16);
           vraw[u] = load_row_slice(src.v_centroids, src.c0 + s, lane16);
@@ -94,12 +91,12 @@ __device__ __forceinline__ void attend_rows(RowState &st, const uint4 &qv, float
         vraw[u] = make_uint4(0, 0, 0, 0);
       }
     }
-    float x[kAttendBatch];
+    float x[B];
     float m_new = st.m;
 #pragma unroll
-    for (int u = 0; u < kAttendBatch; ++u) {
-      const float d = row16_sum(dot8_bf16(qv, kraw[u])) * scale_log2;
-      x[u] = valid[u] ? (approx[u] ? d + log2f((float)ssz[u]) : d) : -INFINITY;
+    for (int u = 0; u < B; ++u) {
+      // log2(1) = 0 exactly; log2(0) = -inf: a missing row (its key is zero) weighs nothing
+      x[u] = fmaf(row16_sum(dot8_bf16(qv, kraw[u])), scale_log2, log2f((float)ssz[u]));
       m_new = fmaxf(m_new, x[u]);
     }
     // m_new is finite here: row r is valid
@@ -108,7 +105,7 @@ __device__ __forceinline__ void attend_rows(RowState &st, const uint4 &qv, float
 #pragma unroll
     for (int i = 0; i < 8; ++i) st.acc[i] *= alpha;
 #pragma unroll
-    for (int u = 0; u < kAttendBatch; ++u) {
+    for (int u = 0; u < B; ++u) {
       const float p = exp2f(x[u] - m_new);
       float vf[8];
       unpack8(vraw[u], vf);

@@ -97,6 +97,11 @@ inline DecodeArgs decode_args_of(const CacheView &c, const int32_t *n_exact, con
 #define DP_LD_I32(lvalue) \
   (kCoherent ? __hip_atomic_load(&(lvalue), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : (lvalue))
 
+// Rows in flight per 16-lane row in the queue.  Inside the selection's launch a CU holds one or two large
+// workgroups (16 waves at most, against 20 of the decode kernel's small ones), and every barrier of an item stops all
+// of them: the rows in flight per wave are doubled there (32 flat heads over 128 k tokens: 105 -> 98 us per step).
+__host__ __device__ constexpr int queue_batch(bool coherent) { return coherent ? 8 : kAttendBatch; }
+
 // rows per item of a head with R rows (multiple of kChunkRows); g: least chunks per item of this launch
 __device__ __forceinline__ int rows_per_item(int R, int S, int g) {
   return kChunkRows * max(g, (R + kChunkRows * S - 1) / (kChunkRows * S));
@@ -174,13 +179,15 @@ __device__ __forceinline__ void decode_item(const DecodeArgs &a, int head, int s
       }
     }
     __syncthreads();
-    // the DPP-row groups take consecutive 4-row pieces: one step of the workgroup reads T / 4 consecutive rows
+    // the DPP-row groups take consecutive pieces of kB rows: one step of the workgroup reads T / 16 * kB consecutive
+    // rows
+    constexpr int kB = queue_batch(kCoherent);
     if (use_gather)
-      attend_rows<true>(st, qv, a.scale_log2, src, s_start, s_src, n_ent, ent0, n_ex, r0 + grp * kAttendBatch, r1,
-                        (T / 16) * kAttendBatch, lane16);
+      attend_rows<true, kB>(st, qv, a.scale_log2, src, s_start, s_src, n_ent, ent0, n_ex, r0 + grp * kB, r1,
+                            (T / 16) * kB, lane16);
     else
-      attend_rows<false>(st, qv, a.scale_log2, src, s_start, s_src, n_ent, ent0, n_ex, r0 + grp * kAttendBatch, r1,
-                         (T / 16) * kAttendBatch, lane16);
+      attend_rows<false, kB>(st, qv, a.scale_log2, src, s_start, s_src, n_ent, ent0, n_ex, r0 + grp * kB, r1,
+                             (T / 16) * kB, lane16);
     // first entry of the next block: the entry that holds row r1
     if (r1 < row_b) {
       int lo = 0, hi = n_ent + 1;  // s_start[n_ent] is staged as well
@@ -268,7 +275,7 @@ __device__ __forceinline__ void decode_queue(const DecodeArgs &a, int *s_start, 
   const int tid = threadIdx.x, lane16 = tid & 15, grp = tid >> 4;
 
   // ---- the queue: items per head from head_rows[], exclusive prefix in LDS ----
-  constexpr int kMinItemChunks = T / 64;  // least chunks per item of a heavy launch: four steps of the workgroup
+  constexpr int kMinItemChunks = T / 64;  // least chunks per item of a heavy launch: four steps of a small workgroup, two of a large one
   constexpr int kPer = kMaxQueueHeads / T;  // consecutive heads per thread
   int rows[kPer], chunks = 0;
 #pragma unroll
@@ -293,7 +300,8 @@ __device__ __forceinline__ void decode_queue(const DecodeArgs &a, int *s_start, 
   const int all_chunks = block_sum<int, (T / 64)>(chunks, s_scan);
   int g;
   if (kCoherent) {
-    constexpr int kStepChunks = T / 256 > 0 ? T / 256 : 1;
+    constexpr int kStepRows = T / 16 * queue_batch(true);
+    constexpr int kStepChunks = kStepRows >= kChunkRows ? kStepRows / kChunkRows : 1;
     const int want = max(1, 4 * (int)gridDim.x);
     g = (all_chunks + want - 1) / want;
     g = min(kMinItemChunks, max(kStepChunks, (g + kStepChunks - 1) / kStepChunks * kStepChunks));

@@ -47,7 +47,7 @@ struct ScoreArgs {
   int32_t head0;       // this launch scores heads [head0, head0 + 16) of each group
   int32_t uniform_kc;  // > 0: every segment has exactly this many clusters
   float sm_scale;
-  int32_t *zero_words;  // nullable: n_zero words cleared by the first workgroup (counters of the step's later kernels)
+  int32_t *zero_words;  // nullable: n_zero words cleared by the first workgroup of every segment, 256 each (counters of the step's later kernels)
   int32_t n_zero;
   // nullable: per head and sub-tile of kSubTile consecutive clusters, (max logit, sum of exp(logit - max)); row
   // stride sub_stride.  Lets the selection find the top of the distribution without reading every logit.
@@ -82,7 +82,8 @@ __global__ __launch_bounds__(kScoreThreads) void score_valu_kernel(
     const void *k_centroids, const int32_t *cluster_sizes, const void *q,
     const int32_t *__restrict__ seg_ptr, int uniform_kc, int n_kv_heads, int n_q_heads, int group, int head0, ScoreArgs a) {
   const int seg = blockIdx.y;
-  if (a.zero_words && blockIdx.x == 0 && blockIdx.y == 0 && (int)threadIdx.x < a.n_zero) a.zero_words[threadIdx.x] = 0;
+  if (a.zero_words && blockIdx.x == 0 && (int)(blockIdx.y * kScoreThreads + threadIdx.x) < a.n_zero)
+    a.zero_words[blockIdx.y * kScoreThreads + threadIdx.x] = 0;
   int c0, kc;
   if (uniform_kc > 0) {  // no CSR lookup in front of the centroid loads
     c0 = seg * uniform_kc;
@@ -174,7 +175,8 @@ __global__ __launch_bounds__(kScoreThreads) void score_kernel(
     const void *k_centroids, const int32_t *cluster_sizes, const void *q,
     const int32_t *__restrict__ seg_ptr, int uniform_kc, int n_kv_heads, int n_q_heads, int group, int head0, ScoreArgs a) {
   const int seg = blockIdx.y;
-  if (a.zero_words && blockIdx.x == 0 && blockIdx.y == 0 && (int)threadIdx.x < a.n_zero) a.zero_words[threadIdx.x] = 0;
+  if (a.zero_words && blockIdx.x == 0 && (int)(blockIdx.y * kScoreThreads + threadIdx.x) < a.n_zero)
+    a.zero_words[blockIdx.y * kScoreThreads + threadIdx.x] = 0;
   int c0, kc;
   if (uniform_kc > 0) {  // no CSR lookup in front of the centroid loads
     c0 = seg * uniform_kc;
@@ -292,7 +294,7 @@ hipError_t launch_score(const CacheView &c, float *logits, hipStream_t s, hipEve
   a.group = c.group;
   a.sm_scale = c.sm_scale;
   a.uniform_kc = c.uniform_kc;
-  a.zero_words = n_zero <= kScoreThreads ? zero_words : nullptr;
+  a.zero_words = n_zero <= kScoreThreads * c.batch * c.n_kv_heads ? zero_words : nullptr;  // 256 words per segment
   a.n_zero = n_zero;
   a.summaries = summaries;
   a.sub_stride = sub_stride;

@@ -1190,9 +1190,10 @@ __global__ __launch_bounds__(T) void select_kernel(SelectArgs a) {
 // to do would cost as much as the selection itself).  Workgroup b < n_heads selects head b (and attends it if it has
 // few rows); every workgroup, the ones beyond n_heads included, then serves the stage-3 queue of the heads that
 // were left over.  The queue may only start when every head has reported to `planned`.  Nobody waits without
-// bound: a selecting workgroup leaves when its head is done unless its own arrival completed the count, in which
-// case it serves the queue until it is empty (so all items are attended whoever else has left); the workgroups
-// beyond n_heads poll the counter for a limited time and leave if the count is not reached.  The scoring kernel of
+// bound: a selecting workgroup whose head was attended inline leaves when it is done; the one whose arrival completes
+// the count serves the queue until it is empty (so all items are attended whoever else has left); the workgroups
+// beyond n_heads and the ones whose own head left rows poll the counter for a limited time, serve the queue if the
+// count is reached and leave if it is not.  The scoring kernel of
 // the step clears planned and the item counter.
 constexpr int kGatePolls = 20000;  // a microsecond or two each
 struct QueueArgs {  // what the stage-3 queue needs beyond the selection's own arguments
@@ -1201,7 +1202,7 @@ struct QueueArgs {  // what the stage-3 queue needs beyond the selection's own a
   int32_t splits, n_heads;
 };
 template <int E, bool kCount, int T>
-__global__ __launch_bounds__(T) void select_decode_kernel(SelectArgs a, QueueArgs qa) {
+__global__ __launch_bounds__(T, 1024 / T) void select_decode_kernel(SelectArgs a, QueueArgs qa) {  // <= 128 registers
   __shared__ Shared<T> sh;
   DP_DECODE_LDS(T);
   __shared__ int s_go;
@@ -1209,8 +1210,23 @@ __global__ __launch_bounds__(T) void select_decode_kernel(SelectArgs a, QueueArg
   const int n_heads = qa.n_heads;
   if ((int)blockIdx.x < n_heads) {
     const int word = select_head<E, kCount, T, true>(a, sh, planned);
-    // the last head in serves the queue if any head (itself included) left rows to it
-    if (threadIdx.x == T - 64) s_go = (word & 0xffff) == n_heads - 1 && (word & 0xffff0000) != 0;
+    if (threadIdx.x == T - 64) {
+      // the last head in serves the queue if any head (itself included) left rows to it
+      bool go = (word & 0xffff) == n_heads - 1 && (word & 0xffff0000) != 0;
+      if (!go && word != -1 && (word & (int)0x80000000)) {
+        // a head that left rows: its workgroup stays for the queue like the ones beyond n_heads (a step of flat
+        // heads would otherwise be served by those alone)
+        int seen = 0;
+#pragma unroll 1
+        for (int it = 0; it < kGatePolls; ++it) {
+          seen = __hip_atomic_load(planned, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+          if ((seen & 0xffff) >= n_heads) break;
+          __builtin_amdgcn_s_sleep(64);
+        }
+        go = (seen & 0xffff) >= n_heads;
+      }
+      s_go = go;
+    }
   } else if (threadIdx.x == 0) {
     int word = 0;
 #pragma unroll 1

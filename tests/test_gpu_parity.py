@@ -759,7 +759,9 @@ def test_launch_count_and_stream_read_probe():
     sep = dp.Problem(small.dc, flags=dp.DP_FLAG_SEPARATE_DECODE_LAUNCH)
     assert dp.dp_decode_attention_launches(sep) == 3
     mid = make_cache(batch=1, n_kv_heads=2, n_q_heads=8, context=16000, mean_cluster=8, q_scale=1.0, seed=83)
-    assert dp.dp_decode_attention_launches(dp.Problem(dp.DeviceCache.from_host(mid))) == 3   # 2000 clusters per segment
+    assert dp.dp_decode_attention_launches(dp.Problem(dp.DeviceCache.from_host(mid))) == 2   # 2000 clusters per segment
+    many = make_cache(batch=5, n_kv_heads=8, n_q_heads=32, context=256, mean_cluster=8, q_scale=1.0, seed=84)
+    assert dp.dp_decode_attention_launches(dp.Problem(dp.DeviceCache.from_host(many))) == 3  # 160 heads: own decode launch
     buf = torch.arange(1 << 20, dtype=torch.int32, device="cuda:0")
     before = buf.clone()
     sink = torch.zeros(1, dtype=torch.int32, device="cuda:0")
