@@ -1202,7 +1202,7 @@ struct QueueArgs {  // what the stage-3 queue needs beyond the selection's own a
   int32_t splits, n_heads;
 };
 template <int E, bool kCount, int T>
-__global__ __launch_bounds__(T, 1024 / T) void select_decode_kernel(SelectArgs a, QueueArgs qa) {  // <= 128 registers
+__global__ __launch_bounds__(T) void select_decode_kernel(SelectArgs a, QueueArgs qa) {
   __shared__ Shared<T> sh;
   DP_DECODE_LDS(T);
   __shared__ int s_go;
