@@ -10,9 +10,11 @@ namespace {
 constexpr int kDecThreads = 256;
 
 template <bool kGathered>
-__global__ __launch_bounds__(kDecThreads) void decode_kernel(DecodeArgs a) {
+__global__ __launch_bounds__(kDecThreads) void decode_kernel(const int32_t *pending, DecodeArgs a) {
   DP_DECODE_LDS(kDecThreads);
-  if (a.pending && *a.pending == 0) return;  // every head was finished by the selection kernel
+  // (a leading scalar parameter: it is in a register when the wave starts, so a launch that finds nothing to do
+  // issues this load first and fetches no other argument)
+  if (pending && *pending == 0) return;  // every head was finished by the selection kernel
   decode_queue<kDecThreads, kGathered, false>(a, DP_DECODE_LDS_ARGS);
 }
 
@@ -38,11 +40,11 @@ hipError_t launch_decode(const CacheView &c, const int32_t *n_exact, const int32
     // measurement: the events bracket the first slab's begin and the last slab's end
     hipEvent_t ev0 = (h0 == 0) ? start : nullptr, ev1 = (h0 + kMaxQueueHeads >= nh) ? stop : nullptr;
     if (k_gather)
-      hipLaunchKernelGGL(decode_kernel<true>, dim3(grid), dim3(kDecThreads), 0, s, a);
+      hipLaunchKernelGGL(decode_kernel<true>, dim3(grid), dim3(kDecThreads), 0, s, a.pending, a);
     else if (ev0 || ev1)
-      hipExtLaunchKernelGGL(decode_kernel<false>, dim3(grid), dim3(kDecThreads), 0, s, ev0, ev1, 0, a);
+      hipExtLaunchKernelGGL(decode_kernel<false>, dim3(grid), dim3(kDecThreads), 0, s, ev0, ev1, 0, a.pending, a);
     else
-      hipLaunchKernelGGL(decode_kernel<false>, dim3(grid), dim3(kDecThreads), 0, s, a);
+      hipLaunchKernelGGL(decode_kernel<false>, dim3(grid), dim3(kDecThreads), 0, s, a.pending, a);
   }
   return hipGetLastError();
 }
