@@ -17,8 +17,10 @@
  *     itself is a host struct read during the call only.
  *   - Calls enqueue work on `stream` (a hipStream_t passed as void*; NULL = the
  *     default stream) and return without synchronising.  Nothing is allocated
- *     or freed; the library keeps no state between calls.  Inputs are never
- *     written.  Two calls that share a workspace must be ordered by the caller.
+ *     or freed; the library keeps no state between calls that changes a result
+ *     (it remembers per process how many workgroups of a kernel the device
+ *     holds, asked from the runtime once, and dp_decode_attention_static owns a
+ *     scratch array).  Inputs are never written.  Two calls that share a workspace must be ordered by the caller.
  *   - Errors that can be detected on the host (null pointers, bad shapes, p out
  *     of range, workspace too small, unsupported head_dim) are returned before
  *     anything is launched.  Device data (offsets, sizes, ids) is NOT validated:
