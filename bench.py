@@ -37,6 +37,9 @@ def parse():
     ap.add_argument("--steps", type=int, default=3600)
     ap.add_argument("--warmup", type=int, default=360)
     ap.add_argument("--config", type=int, default=2, help="workload index 0..4 (default: 8B shape, 128k context)")
+    ap.add_argument("--heads", choices=["flat", "mixed"], default=None,
+                    help="workloads 1 and 2 with other query scales: every head flat, or one in eight (the cases "
+                         "behind the launch policy; see ab_paper_kernel_structure_us.decode_launch in the line)")
     ap.add_argument("--replicas", type=int, default=0, help="layer replicas to rotate over (0 = auto)")
     ap.add_argument("--separate-decode-launch", action="store_true",
                     help="A/B: keep the split decode a launch of its own (DP_FLAG_SEPARATE_DECODE_LAUNCH)")
@@ -107,7 +110,8 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     dev = "cuda:0"
     t0 = time.time()
-    cache = make_config(args.config)
+    cache = make_config(args.config, heads=args.heads)
+    wname = CONFIGS[args.config] + (f" with {args.heads} heads" if args.heads else "")
     t_gen = time.time() - t0
     p1, p2 = cache.p1, cache.p2
     nh = cache.batch * cache.n_q_heads
@@ -493,7 +497,7 @@ def main():
         "dtype": "bf16",
         "data": "synthetic",
         "config": {
-            "workload": f"{CONFIGS[args.config]}: batch {cache.batch}, {cache.n_kv_heads} KV heads, "
+            "workload": f"{wname}: batch {cache.batch}, {cache.n_kv_heads} KV heads, "
                         f"{cache.n_q_heads} query heads, head_dim {cache.head_dim}, context "
                         f"{cache.meta['context'] if cache.batch > 1 else cache.meta['context'][0]}, "
                         f"{mk} clusters per KV head, bf16 K/V with fp32 accumulation, p1 {p1}, p2 {p2}",
@@ -627,7 +631,7 @@ def main():
             "unit": "us",
             "cores": int(r.threads),
             "kind": "oracle",
-            "sample": f"the whole {CONFIGS[args.config]} step (all {nh} heads), fp64 C oracle, OpenMP over heads, "
+            "sample": f"the whole {wname} step (all {nh} heads), fp64 C oracle, OpenMP over heads, "
                       f"median of {len(times)} repetitions",
             "single_thread_us": round(statistics.median(single) * 1e6, 1),
             "single_thread_runs": len(single),

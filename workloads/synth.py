@@ -285,11 +285,21 @@ def make_cache(*, batch: int, n_kv_heads: int, n_q_heads: int, context: Sequence
 CONFIGS: List[str] = ["cfg0_tiny", "cfg1_8b_32k", "cfg2_8b_128k", "cfg3_batch16", "cfg4_gqa8_128k"]
 
 
-def make_config(idx: int, *, seed: Optional[int] = None, shrink: int = 1) -> ClusteredCache:
+def make_config(idx: int, *, seed: Optional[int] = None, shrink: int = 1,
+                heads: Optional[str] = None) -> ClusteredCache:
     """Workload ``idx`` (0..4). ``shrink`` divides every context length (kept a
-    multiple of the mean cluster size) to get a same-shaped but smaller case."""
+    multiple of the mean cluster size) to get a same-shaped but smaller case.
+    ``heads`` (workloads 1 and 2 only) replaces the query scales: "flat" makes every
+    head flat (scale 0.4: hundreds of clusters retained), "mixed" one head in eight."""
     if seed is None:
         seed = idx  # cfg0 uses seed 0
+    if heads is not None:
+        if idx not in (1, 2) or heads not in ("flat", "mixed"):
+            raise ValueError("heads: 'flat' or 'mixed', for workloads 1 and 2")
+        scale = 0.4 if heads == "flat" else (lambda rng, b, h: 0.4 if h % 8 == 0 else 3.0)
+        return make_cache(batch=1, n_kv_heads=8, n_q_heads=32, context=(32768 if idx == 1 else 131072) // shrink,
+                          mean_cluster=16, size_lo=1, size_hi=64, q_scale=scale, p1=0.95, p2=0.9, seed=seed,
+                          tag=10 + idx, name=f"{CONFIGS[idx]}_{heads}_heads")
     if idx == 0:
         return make_cache(batch=1, n_kv_heads=1, n_q_heads=4, context=4096 // shrink, mean_cluster=16,
                           size_lo=1, size_hi=64, q_scale=3.0, p1=0.95, p2=0.9, seed=seed, tag=0,
