@@ -11,6 +11,11 @@ usage:
         --counter-args "<counter-run args>" --trace <trace_dir>/bench_results.db --fetch <fetch_dir>/f_results.db \
         --write <write_dir>/w_results.db [--kernel <name prefix> --alg-bytes <bytes per launch>] > profiles/<name>.txt
 
+Optionally a fourth run with SQ counters (at most 8 in one run), reported for the kernel named by --kernel:
+
+    rocprofv3 --pmc <SQ counters>     -d <sq_dir>    -o s     -- python3 bench.py <counter-run args>
+    ... --sq <sq_dir>/s_results.db --sq-counters "<SQ counters>"
+
 Durations are aggregated per kernel name; HBM traffic is the median per dispatch of the two counters, scaled by
 what the same counters read for the largest device-to-device copy of the run (a K cache replica of known size).
 """
@@ -54,6 +59,8 @@ def main():
     ap.add_argument("--kernel", default=None, help="name prefix of the kernel to report the roofline figures for")
     ap.add_argument("--alg-bytes", type=float, default=None, help="algorithmic bytes per launch of that kernel")
     ap.add_argument("--in-step", default="score,select", help="prefixes of the kernels of one dp_decode_attention step, in order")
+    ap.add_argument("--sq", default=None, help="result database of a run with SQ counters (one --pmc run)")
+    ap.add_argument("--sq-counters", default="", help="the counters of that run, as given to --pmc")
     a = ap.parse_args()
     cargs = a.counter_args or a.bench_args
     out = []
@@ -132,6 +139,36 @@ def main():
                 P(f"algorithmic_bytes_per_launch = {a.alg_bytes:.0f}   (traffic / algorithmic = {tb / a.alg_bytes:.3f})")
                 P(f"achieved = algorithmic bytes / duration ({ref:.2f} us) = {a.alg_bytes / ref / 1e3:.0f} GB/s = "
                   f"{a.alg_bytes / ref / 1e3 / 8000:.3f} of the 8000 GB/s HBM peak")
+    if a.sq and a.kernel:
+        cur = sqlite3.connect(a.sq).cursor()
+        per = defaultdict(lambda: defaultdict(list))
+        for name, counter, val, grid in cur.execute(
+                "select kernel_name,counter_name,value,grid_size from counters_collection"):
+            if short(name).startswith(a.kernel):
+                per[grid][counter].append(val)
+        if per:
+            grid = max(per, key=lambda g: sum(len(v) for v in per[g].values()))
+            c = {k: statistics.median(v) for k, v in per[grid].items()}
+            P("")
+            P(f"== SQ counters of {a.kernel} (one counter run; median per launch, summed over the device) ==")
+            P(f"command: rocprofv3 --pmc {a.sq_counters} -d {os.path.dirname(a.sq)} -o s -- python3 bench.py {cargs}")
+            for k in sorted(c):
+                P(f"{k:32s} n={len(per[grid][k]):5d} median {c[k]:16.0f}")
+            wc = c.get("SQ_WAVE_CYCLES")
+            if wc:
+                parts = []
+                for k, label in (("SQ_WAIT_INST_ANY", "waiting on an instruction's dependency"),
+                                 ("SQ_WAIT_INST_LDS", "waiting on LDS"), ("SQ_ACTIVE_INST_VALU", "issuing vector ALU"),
+                                 ("SQ_ACTIVE_INST_LDS", "issuing LDS"), ("SQ_ACTIVE_INST_SCA", "issuing scalar")):
+                    if k in c:
+                        parts.append(f"{100 * c[k] / wc:.0f} % {label}")
+                if parts:
+                    P("share of the cycles that waves were resident (waves that wait at a barrier or sleep count too): "
+                      + ", ".join(parts))
+            insts = [(k, c[k]) for k in ("SQ_INSTS_VALU", "SQ_INSTS_SALU", "SQ_INSTS_LDS", "SQ_INSTS_VMEM_RD",
+                                         "SQ_INSTS_VMEM_WR", "SQ_INSTS_SMEM") if k in c]
+            if insts:
+                P("instructions per launch: " + ", ".join(f"{k[9:]} {v:.0f}" for k, v in insts))
     print("\n".join(out))
 
 
