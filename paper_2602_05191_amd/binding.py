@@ -284,6 +284,31 @@ def dp_decode_attention(problem: Problem, p1: float, p2: float, out: torch.Tenso
            "dp_decode_attention")
 
 
+class BoundDecodeStep:
+    """dp_decode_attention with its arguments marshalled once: calling the object enqueues one step (a serving loop
+    calls the same step many times; converting the same pointers again on every call costs the host several
+    microseconds, as much as a third of a small step).  The tensors are kept alive by the object and must not be
+    resized; ``stream`` (default: the stream current at construction) is fixed too."""
+
+    def __init__(self, problem: Problem, p1: float, p2: float, out: torch.Tensor, lse: Optional[torch.Tensor],
+                 workspace: torch.Tensor, n_exact: Optional[torch.Tensor] = None,
+                 n_retained: Optional[torch.Tensor] = None, n_exact_tokens: Optional[torch.Tensor] = None,
+                 stream=None):
+        dt = {torch.float32: DP_F32, torch.bfloat16: DP_BF16}[out.dtype]
+        assert out.is_contiguous() and out.numel() == problem.nh * problem.dc.head_dim
+        self._keep = (problem, out, lse, workspace, n_exact, n_retained, n_exact_tokens)
+        self._fn = load_library().dp_decode_attention
+        V = C.c_void_p
+        self._args = (problem.ref, C.c_float(p1), C.c_float(p2), V(_ptr(out)), C.c_int(dt), V(_ptr(lse)),
+                      V(_ptr(n_exact)), V(_ptr(n_retained)), V(_ptr(n_exact_tokens)), V(_ptr(workspace)),
+                      C.c_size_t(workspace.numel() * workspace.element_size()), V(_stream(stream)))
+
+    def __call__(self) -> None:
+        status = self._fn(*self._args)
+        if status != 0:
+            raise DPError(status, "dp_decode_attention")
+
+
 DP_STATIC_SCRATCH_BYTES = 16 << 20
 
 

@@ -311,6 +311,30 @@ def test_split_decode_inside_the_selection_launch_and_as_a_launch_of_its_own(cas
         H.check_outputs(cache, orc, b, tight=2e-4)
 
 
+def test_bound_step_is_the_same_call():
+    """BoundDecodeStep marshals the arguments of dp_decode_attention once: same bits as the direct call, on every call."""
+    import torch
+    import paper_2602_05191_amd as dp
+    cache = make_config(0)
+    dc = dp.DeviceCache.from_host(cache)
+    pr = dp.Problem(dc)
+    ws = torch.zeros(dp.dp_workspace_bytes(pr), dtype=torch.uint8, device="cuda:0")
+    nh = cache.batch * cache.n_q_heads
+    a = torch.full((cache.batch, cache.n_q_heads, cache.head_dim), float("nan"), dtype=torch.float32, device="cuda:0")
+    b = torch.full_like(a, float("nan"))
+    la = torch.empty(nh, dtype=torch.float32, device="cuda:0")
+    lb, ne = torch.empty_like(la), torch.empty(nh, dtype=torch.int32, device="cuda:0")
+    dp.dp_decode_attention(pr, cache.p1, cache.p2, a, la, ws)
+    torch.cuda.synchronize()
+    step = dp.BoundDecodeStep(pr, cache.p1, cache.p2, b, lb, ws, ne)
+    for _ in range(3):
+        b.fill_(float("nan"))
+        step()
+        torch.cuda.synchronize()
+        assert torch.equal(a.view(torch.int32), b.view(torch.int32)) and torch.equal(la.view(torch.int32), lb.view(torch.int32))
+    assert int(ne.min().item()) >= 1
+
+
 def test_decode_attention_is_bitwise_reproducible(case):
     name, cache, p1, p2, orc = case
     a = H.gpu_decode_attention(cache, p1, p2)
